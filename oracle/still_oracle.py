@@ -1,0 +1,430 @@
+"""Float64 CPU oracle for STILL's intra-layer hybrid attention forward (arXiv 2602.02180).
+
+TEST INFRASTRUCTURE ONLY.  Nothing on the product path may import this file; it is
+used by tests/, by __graft_entry__.smoke() and by bench.py's cpu_baseline leg.  It
+shares no code with the HIP kernels and imports nothing from them.
+
+Everything here works on ONE (batch, query-head) problem at a time: q, k, v are
+[N, d] float64 arrays (k, v already taken from the kv-head that the query head maps
+to), tokens are 0-indexed in code (the paper counts from 1; token t here is the
+paper's token t+1, chunk c here is the paper's chunk c+1).
+
+The same operator is written three ways, each from a different passage of the paper:
+
+  * still_definition  - Sec. 3.3 recurrent form (cache-routing and output equations)
+                        unrolled per output row into explicit index sets, O(N^2);
+  * still_recurrent   - the same equations stepped token by token with the salient
+                        cache h, and the state (s, z), routing one chunk at the
+                        first token of a new chunk (delayed selection);
+  * still_chunkwise   - Algorithm 1 (chunk-wise parallel form), chunk tensors,
+                        cumulative sum of per-chunk states delayed by two chunks.
+
+They must agree to rounding; tests/ pins them further against textbook softmax
+attention (all tokens kept), plain linear attention (quadratic vs state form),
+closed forms of the score, norm preservation of the feature map and brute-force
+selection.
+
+Readings of the paper used here (each is listed with its reason in the design notes):
+  - one scalar `scale` multiplies every q.k logit (score window and softmax branch);
+  - the window of token t holds the W keys t-W+1..t clipped at the sequence start;
+  - masked positions are excluded from softmax/exp sums (not multiplied by zero);
+  - a one-token window gives a_nodiag = 0, so Score = ln((1+eps)/eps);
+  - only full chunks are ranked; ties go to the lower index; indices kept ascending;
+  - the state sums only the un-selected tokens; the gate multiplies N_LA only;
+  - f(x) = x W + b (one linear layer), phi = [softmax(u), softmax(-u)].
+
+parity unpinned: the whole operator on random inputs at general lambda has no value
+printed in the paper; beyond the special cases above its correctness rests on the
+agreement of the three independent forms and on the readings listed.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+F64 = np.float64
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.1: Self-Saliency Score (window set, the two window softmaxes, the score)
+# ----------------------------------------------------------------------------
+
+def _softmax(x: np.ndarray) -> np.ndarray:
+    e = np.exp(x - np.max(x))
+    return e / np.sum(e)
+
+
+def self_saliency_scores(q: np.ndarray, k: np.ndarray, W: int, scale: float, eps: float) -> np.ndarray:
+    """Score_t for every token: sum over the window of a_diag * ln((a_diag+eps)/(a_nodiag+eps)).
+
+    Window of token t = keys max(0, t-W+1) .. t.  a_diag is the softmax over the whole
+    window; a_nodiag the softmax over the window without t itself and 0 at t.
+    """
+    q = np.asarray(q, F64)
+    k = np.asarray(k, F64)
+    N = q.shape[0]
+    score = np.empty(N, F64)
+    for t in range(N):
+        lo = max(0, t - W + 1)
+        logit = scale * (k[lo:t + 1] @ q[t])
+        a_diag = _softmax(logit)
+        a_nodiag = np.zeros_like(a_diag)
+        if t > lo:
+            a_nodiag[:-1] = _softmax(logit[:-1])
+        score[t] = np.sum(a_diag * np.log((a_diag + eps) / (a_nodiag + eps)))
+    return score
+
+
+def alg1_scores(q: np.ndarray, k: np.ndarray, C: int, scale: float, eps: float) -> np.ndarray:
+    """Scores as Algorithm 1 builds them (its window is exactly one chunk long, W = C).
+
+    Per chunk: s_in = q k^T within the chunk, s_prev = q against the previous chunk's
+    keys; the diag softmax runs over [s_in where key<=query, s_prev where key>query],
+    the nodiag one over [s_in where key<query, s_prev where key>query].  The first
+    chunk has no previous keys.  N must be a multiple of C here.
+    """
+    q = np.asarray(q, F64)
+    k = np.asarray(k, F64)
+    N, d = q.shape
+    assert N % C == 0
+    T = N // C
+    qc = q.reshape(T, C, d)
+    kc = k.reshape(T, C, d)
+    row = np.arange(C)[:, None]
+    col = np.arange(C)[None, :]
+    m_down, m_up, m_diag = row >= col, row < col, row > col
+    out = np.empty((T, C), F64)
+    for c in range(T):
+        s_in = scale * (qc[c] @ kc[c].T)
+        if c > 0:
+            s_prev = scale * (qc[c] @ kc[c - 1].T)
+            prev_ok = m_up
+        else:
+            s_prev = np.zeros((C, C), F64)
+            prev_ok = np.zeros((C, C), bool)
+        logits = np.concatenate([s_in, s_prev], axis=1)
+        keep_diag = np.concatenate([m_down, prev_ok], axis=1)
+        keep_nodiag = np.concatenate([m_diag, prev_ok], axis=1)
+
+        def masked_softmax(keep):
+            neg = np.where(keep, logits, -np.inf)
+            mx = np.max(neg, axis=1, keepdims=True)
+            mx = np.where(np.isfinite(mx), mx, 0.0)
+            e = np.where(keep, np.exp(neg - mx), 0.0)
+            den = np.sum(e, axis=1, keepdims=True)
+            return np.where(den > 0, e / np.where(den > 0, den, 1.0), 0.0)
+
+        a_diag = masked_softmax(keep_diag)
+        a_nodiag = masked_softmax(keep_nodiag)
+        term = np.where(keep_diag, a_diag * np.log((a_diag + eps) / (a_nodiag + eps)), 0.0)
+        out[c] = term.sum(axis=1)
+    return out.reshape(N)
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.3: delayed selection (Top-lambda per completed chunk)
+# ----------------------------------------------------------------------------
+
+def select_top_lambda(score: np.ndarray, C: int, lam: int) -> np.ndarray:
+    """Indices (global, ascending) of the lam highest scores of every FULL chunk.
+
+    Ties go to the lower index.  Returns int64 [N // C, lam].
+    """
+    N = score.shape[0]
+    ncf = N // C
+    sel = np.empty((ncf, lam), np.int64)
+    for c in range(ncf):
+        s = score[c * C:(c + 1) * C]
+        order = sorted(range(C), key=lambda i: (-s[i], i))
+        sel[c] = np.sort(np.asarray(order[:lam], np.int64)) + c * C
+    return sel
+
+
+def selection_gaps(score: np.ndarray, C: int, lam: int) -> np.ndarray:
+    """Per full chunk: (lam-th highest score) - ((lam+1)-th highest); +inf if lam in {0, C}."""
+    ncf = score.shape[0] // C
+    gaps = np.full(ncf, np.inf)
+    if 0 < lam < C:
+        for c in range(ncf):
+            s = np.sort(score[c * C:(c + 1) * C])[::-1]
+            gaps[c] = s[lam - 1] - s[lam]
+    return gaps
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.2: Norm-Preserved Feature Map
+# ----------------------------------------------------------------------------
+
+def np_map(x: np.ndarray, Wm: np.ndarray, b: Optional[np.ndarray] = None) -> np.ndarray:
+    """phi_NP(x) for rows of x: u = f(x) / ||f(x)|| * ||x||, phi = softmax(u) (+) softmax(-u).
+
+    f(x) = x Wm + b.  A zero f(x) gives u = 0 (uniform phi).
+    """
+    x = np.atleast_2d(np.asarray(x, F64))
+    f = x @ np.asarray(Wm, F64)
+    if b is not None:
+        f = f + np.asarray(b, F64)
+    nx = np.sqrt(np.sum(x * x, axis=1, keepdims=True))
+    nf = np.sqrt(np.sum(f * f, axis=1, keepdims=True))
+    u = np.where(nf > 0, f / np.where(nf > 0, nf, 1.0) * nx, 0.0)
+    ep = np.exp(u - u.max(axis=1, keepdims=True))
+    en = np.exp(-u - (-u).max(axis=1, keepdims=True))
+    return np.concatenate([ep / ep.sum(axis=1, keepdims=True),
+                           en / en.sum(axis=1, keepdims=True)], axis=1)
+
+
+def np_map_u(x: np.ndarray, Wm: np.ndarray, b: Optional[np.ndarray] = None) -> np.ndarray:
+    """The rescaled pre-activation u of the feature map (exposed for the norm test)."""
+    x = np.atleast_2d(np.asarray(x, F64))
+    f = x @ np.asarray(Wm, F64)
+    if b is not None:
+        f = f + np.asarray(b, F64)
+    nx = np.sqrt(np.sum(x * x, axis=1, keepdims=True))
+    nf = np.sqrt(np.sum(f * f, axis=1, keepdims=True))
+    return np.where(nf > 0, f / np.where(nf > 0, nf, 1.0) * nx, 0.0)
+
+
+# ----------------------------------------------------------------------------
+# shared result container
+# ----------------------------------------------------------------------------
+
+def _prep(q, k, v, g, Wq, Wk, bq, bk):
+    q = np.asarray(q, F64)
+    k = np.asarray(k, F64)
+    v = np.asarray(v, F64)
+    g = None if g is None else np.asarray(g, F64)
+    return q, k, v, g
+
+
+def _result(N, d, rows):
+    return {
+        "rows": rows,
+        "out": np.zeros((N, d), F64),
+        "M": np.zeros(N, F64),       # max softmax-branch logit of the row
+        "N_SA": np.zeros((N, d), F64),  # sum exp(l - M) v   over the salient cache
+        "D_SA": np.zeros(N, F64),       # sum exp(l - M)
+        "N_LA": np.zeros((N, d), F64),  # gate * phi_q(q) s   (not shifted)
+        "D_LA": np.zeros(N, F64),       # phi_q(q) z          (not shifted)
+    }
+
+
+def _merge(res, t):
+    """y = (N_SA + N_LA) / (D_SA + D_LA) with the common factor exp(-M) applied to both."""
+    f = np.exp(-res["M"][t])
+    res["out"][t] = (res["N_SA"][t] + f * res["N_LA"][t]) / (res["D_SA"][t] + f * res["D_LA"][t])
+
+
+def _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score):
+    if score is None:
+        score = self_saliency_scores(q, k, W, scale, eps)
+    if sel is None:
+        sel = select_top_lambda(score, C, lam)
+    sel = np.asarray(sel, np.int64)
+    sel = sel.reshape(q.shape[0] // C, sel.size // max(1, q.shape[0] // C))
+    return score, sel
+
+
+# ----------------------------------------------------------------------------
+# Form 1: per-row index sets (the recurrent equations unrolled), O(N^2)
+# ----------------------------------------------------------------------------
+
+def still_definition(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
+                     sel=None, score=None, rows: Optional[Tuple[int, int]] = None) -> Dict:
+    """Row t in chunk c sees, through exp: the local span (previous chunk and own chunk up to t)
+    plus the selected tokens of chunks <= c-2; through phi_q.phi_k: every other token of
+    chunks <= c-2.  One division merges them."""
+    q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk)
+    N, d = q.shape
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score)
+    phi_q = np_map(q, Wq, bq)
+    phi_k = np_map(k, Wk, bk)
+    rows = (0, N) if rows is None else rows
+    res = _result(N, v.shape[1], rows)
+    res["score"], res["sel"] = score, sel
+    for t in range(*rows):
+        c = t // C
+        local = list(range(max(0, (c - 1) * C), t + 1))
+        ret, lin = [], []
+        for cc in range(0, c - 1):
+            chosen = set(int(i) for i in sel[cc])
+            for i in range(cc * C, (cc + 1) * C):
+                (ret if i in chosen else lin).append(i)
+        sa = np.asarray(ret + local, np.int64)
+        logit = scale * (k[sa] @ q[t])
+        M = logit.max()
+        e = np.exp(logit - M)
+        res["M"][t] = M
+        res["N_SA"][t] = e @ v[sa]
+        res["D_SA"][t] = e.sum()
+        if lin:
+            li = np.asarray(lin, np.int64)
+            wgt = phi_k[li] @ phi_q[t]
+            n_la = wgt @ v[li]
+            res["N_LA"][t] = n_la * (g[t] if g is not None else 1.0)
+            res["D_LA"][t] = wgt.sum()
+        _merge(res, t)
+    return res
+
+
+# ----------------------------------------------------------------------------
+# Form 2: token-by-token recurrence with the salient cache and the (s, z) state
+# ----------------------------------------------------------------------------
+
+def still_recurrent(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
+                    sel=None, score=None, rows: Optional[Tuple[int, int]] = None,
+                    return_state: bool = False) -> Dict:
+    """Step t (1-indexed as in the paper) is written t = (a+1)C + b with 1 <= b <= C.
+    When b == 1 and a >= 1 the chunk a (tokens (a-1)C+1 .. aC) is routed: its top-lambda
+    keys/values join the retained part of the cache, the others are added to (s, z).
+    The cache also always holds the local span aC < i <= t."""
+    q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk)
+    N, d = q.shape
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score)
+    dprime = 2 * np.asarray(Wq).shape[1]
+    s = np.zeros((dprime, v.shape[1]), F64)
+    z = np.zeros(dprime, F64)
+    retained: list = []           # token indices (0-indexed) in routing order
+    rows = (0, N) if rows is None else rows
+    res = _result(N, v.shape[1], rows)
+    res["score"], res["sel"] = score, sel
+    for t1 in range(1, N + 1):
+        a = (t1 - 1) // C - 1
+        b = t1 - (a + 1) * C
+        if a >= 1 and b == 1:
+            chunk0 = a - 1                      # 0-indexed chunk being routed
+            chosen = [int(i) for i in sel[chunk0]]
+            retained.extend(chosen)
+            cs = set(chosen)
+            rest = np.asarray([i for i in range(chunk0 * C, (chunk0 + 1) * C) if i not in cs], np.int64)
+            if rest.size:
+                pk = np_map(k[rest], Wk, bk)
+                s = s + pk.T @ v[rest]
+                z = z + pk.sum(axis=0)
+        t = t1 - 1
+        if not (rows[0] <= t < rows[1]):
+            continue
+        local = np.arange(max(0, a * C), t1, dtype=np.int64)     # paper: a*C < i <= t, 1-indexed
+        h = np.concatenate([np.asarray(retained, np.int64), local])
+        logit = scale * (k[h] @ q[t])
+        M = logit.max()
+        e = np.exp(logit - M)
+        pq = np_map(q[t], Wq, bq)[0]
+        res["M"][t] = M
+        res["N_SA"][t] = e @ v[h]
+        res["D_SA"][t] = e.sum()
+        res["N_LA"][t] = (pq @ s) * (g[t] if g is not None else 1.0)
+        res["D_LA"][t] = pq @ z
+        _merge(res, t)
+    if return_state:
+        res["state"] = {"s": s, "z": z, "retained": np.asarray(retained, np.int64)}
+    return res
+
+
+# ----------------------------------------------------------------------------
+# Form 3: Algorithm 1, chunk-wise parallel
+# ----------------------------------------------------------------------------
+
+def still_chunkwise(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
+                    sel=None, score=None, rows: Optional[Tuple[int, int]] = None) -> Dict:
+    """Chunk tensors; per-chunk states phi_k(k_LA)^T v_LA cumulated over chunks and delayed by
+    two; chunk c attends with exp to the flattened selected keys of chunks <= c-2, to the whole
+    previous chunk and causally to itself; a single division merges both branches."""
+    q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk)
+    N, d = q.shape
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score)
+    T = -(-N // C)
+    ncf = N // C
+    lam_eff = sel.shape[1]
+    dprime = 2 * np.asarray(Wq).shape[1]
+    rows = (0, N) if rows is None else rows
+    res = _result(N, v.shape[1], rows)
+    res["score"], res["sel"] = score, sel
+
+    # selected / unselected split per full chunk
+    k_sa = k[sel.reshape(-1)].reshape(ncf, lam_eff, d)
+    v_sa = v[sel.reshape(-1)].reshape(ncf, lam_eff, v.shape[1])
+    ds = np.zeros((T, dprime, v.shape[1]), F64)
+    dz = np.zeros((T, dprime), F64)
+    for c in range(ncf):
+        keep = np.ones(C, bool)
+        keep[sel[c] - c * C] = False
+        idx = np.nonzero(keep)[0] + c * C
+        if idx.size:
+            pk = np_map(k[idx], Wk, bk)
+            ds[c] = pk.T @ v[idx]
+            dz[c] = pk.sum(axis=0)
+    s_cum = np.cumsum(ds, axis=0)
+    z_cum = np.cumsum(dz, axis=0)
+    k_sa_flat = k_sa.reshape(ncf * lam_eff, d)
+    v_sa_flat = v_sa.reshape(ncf * lam_eff, v.shape[1])
+
+    c_lo, c_hi = rows[0] // C, -(-rows[1] // C)
+    for c in range(c_lo, c_hi):
+        t0, t1 = c * C, min(N, (c + 1) * C)
+        qc = q[t0:t1]
+        n_vis = max(0, c - 1) * lam_eff                  # selected keys of chunks 0..c-2
+        blocks_k = [k_sa_flat[:n_vis]]
+        blocks_v = [v_sa_flat[:n_vis]]
+        masks = [np.ones((t1 - t0, n_vis), bool)]
+        if c >= 1:
+            blocks_k.append(k[t0 - C:t0])
+            blocks_v.append(v[t0 - C:t0])
+            masks.append(np.ones((t1 - t0, C), bool))
+        blocks_k.append(k[t0:t1])
+        blocks_v.append(v[t0:t1])
+        r = np.arange(t1 - t0)
+        masks.append(r[:, None] >= r[None, :])
+        kk = np.concatenate(blocks_k, axis=0)
+        vv = np.concatenate(blocks_v, axis=0)
+        keep = np.concatenate(masks, axis=1)
+        logit = np.where(keep, scale * (qc @ kk.T), -np.inf)
+        M = logit.max(axis=1)
+        o = np.where(keep, np.exp(logit - M[:, None]), 0.0)
+        pq = np_map(qc, Wq, bq)
+        if c >= 2:
+            s_shift, z_shift = s_cum[c - 2], z_cum[c - 2]
+        else:
+            s_shift, z_shift = np.zeros((dprime, v.shape[1]), F64), np.zeros(dprime, F64)
+        n_la = pq @ s_shift
+        if g is not None:
+            n_la = n_la * g[t0:t1]
+        d_la = pq @ z_shift
+        f = np.exp(-M)
+        n_sa = o @ vv
+        d_sa = o.sum(axis=1)
+        y = (n_sa + f[:, None] * n_la) / (d_sa + f * d_la)[:, None]
+        res["M"][t0:t1] = M
+        res["N_SA"][t0:t1] = n_sa
+        res["D_SA"][t0:t1] = d_sa
+        res["N_LA"][t0:t1] = n_la
+        res["D_LA"][t0:t1] = d_la
+        res["out"][t0:t1] = y
+    res["s_cum"], res["z_cum"] = s_cum, z_cum
+    return res
+
+
+# ----------------------------------------------------------------------------
+# batch / head driver
+# ----------------------------------------------------------------------------
+
+def still_forward_units(inputs: Dict[str, np.ndarray], kv_map: np.ndarray, units, C, W, lam, scale, eps,
+                        form: str = "chunkwise", sel: Optional[np.ndarray] = None,
+                        rows: Optional[Tuple[int, int]] = None) -> Dict[Tuple[int, int], Dict]:
+    """Run one form on the listed (b, hq) units of a batched problem.
+
+    inputs: q [B,N,Hq,d], k,v [B,N,Hkv,d], Wq,Wk [Hq,d,d_f], optional g [B,N,Hq,d],
+    optional bq,bk [Hq,d_f].  sel (optional) [B,Hq,N//C,lam] overrides the selection.
+    """
+    fn = {"chunkwise": still_chunkwise, "recurrent": still_recurrent, "definition": still_definition}[form]
+    out = {}
+    for (b, h) in units:
+        kh = int(kv_map[h])
+        g = inputs["g"][b, :, h] if inputs.get("g") is not None else None
+        bq = inputs["bq"][h] if inputs.get("bq") is not None else None
+        bk = inputs["bk"][h] if inputs.get("bk") is not None else None
+        s_in = None if sel is None else sel[b, h]
+        out[(b, h)] = fn(inputs["q"][b, :, h], inputs["k"][b, :, kh], inputs["v"][b, :, kh], g,
+                         inputs["Wq"][h], inputs["Wk"][h], C, W, lam, scale, eps, bq=bq, bk=bk,
+                         sel=s_in, rows=rows)
+    return out

@@ -1,0 +1,348 @@
+"""Pins of the float64 oracle against what the paper and the mathematics fix.
+
+None of these tests touches the HIP path.  Each pin is chosen so that one class of
+mistake in oracle/still_oracle.py (a dropped term, a wrong sign, an off-by-one chunk
+delay, a transposed operand, a wrong tie-break) fails it:
+
+  * all tokens kept  -> textbook causal softmax attention (appendix softmax-attention eq.)
+  * nothing kept     -> plain normalised linear attention over the routed prefix, in its
+                        quadratic and its running-state form (appendix linear-attention eqs.)
+  * one-hot values   -> every past token is seen exactly once, by exactly one branch, with the
+                        two-chunk delay of Sec. 3.3 / Algorithm 1
+  * the recurrent equations and Algorithm 1 are two separate statements of the operator in the
+    paper; a third form enumerates the index sets row by row - all three must agree
+  * score: closed value for a one-token window, closed value for a uniform window, closed form
+    through the self-weight p as eps -> 0, and Algorithm 1's mask construction (W = C)
+  * NP-Map: ||u|| = ||x||, halves sum to 1, identity MLP gives softmax(x) (+) softmax(-x)
+  * selection: brute force over all subsets on tiny chunks, lowest-index tie-break
+  * causality: appending tokens never changes earlier rows (prefill/decode consistency)
+
+The paper prints no worked numeric example of the operator, so there are no golden values
+from it; tests/golden/ says so.
+"""
+import itertools
+
+import numpy as np
+import pytest
+from scipy.special import softmax as sp_softmax
+
+from oracle import still_oracle as O
+
+EPS = 1e-6
+
+
+def rand_problem(seed, N, d, df=None, scale_in=1.0):
+    rng = np.random.default_rng(seed)
+    df = df or d
+    q = rng.standard_normal((N, d)) * scale_in
+    k = rng.standard_normal((N, d)) * scale_in
+    v = rng.standard_normal((N, d))
+    g = 1.0 / (1.0 + np.exp(-rng.standard_normal((N, d))))
+    Wq = rng.standard_normal((d, df)) / np.sqrt(d)
+    Wk = rng.standard_normal((d, df)) / np.sqrt(d)
+    return q, k, v, g, Wq, Wk
+
+
+def causal_softmax_attention(q, k, v, scale):
+    """Textbook: y_t = sum_{i<=t} softmax_i(scale q_t.k_i) v_i, through scipy's softmax."""
+    N = q.shape[0]
+    logits = scale * (q @ k.T)
+    logits[np.triu_indices(N, 1)] = -np.inf
+    return sp_softmax(logits, axis=1) @ v
+
+
+FORMS = [O.still_definition, O.still_recurrent, O.still_chunkwise]
+
+
+# --------------------------------------------------------------------------- all kept
+@pytest.mark.parametrize("form", FORMS)
+@pytest.mark.parametrize("N,C", [(48, 8), (50, 8), (37, 16), (16, 16), (5, 8)])
+def test_all_tokens_kept_is_causal_softmax_attention(form, N, C):
+    q, k, v, g, Wq, Wk = rand_problem(1, N, 8)
+    scale = 1 / np.sqrt(8)
+    r = form(q, k, v, g, Wq, Wk, C=C, W=C, lam=C, scale=scale, eps=EPS)
+    ref = causal_softmax_attention(q, k, v, scale)
+    np.testing.assert_allclose(r["out"], ref, rtol=1e-11, atol=1e-12)
+    assert np.all(r["D_LA"] == 0) and np.all(r["N_LA"] == 0)
+
+
+def test_all_kept_is_chunk_size_invariant_and_stable_for_large_logits():
+    q, k, v, g, Wq, Wk = rand_problem(2, 64, 8, scale_in=12.0)   # logits of several hundred
+    outs = [O.still_chunkwise(q, k, v, None, Wq, Wk, C=C, W=4, lam=C, scale=1.0, eps=EPS)["out"]
+            for C in (4, 8, 32)]
+    ref = causal_softmax_attention(q, k, v, 1.0)
+    for o in outs:
+        assert np.all(np.isfinite(o))
+        np.testing.assert_allclose(o, ref, rtol=1e-10, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- none kept
+@pytest.mark.parametrize("form", FORMS)
+def test_nothing_kept_linear_branch_is_plain_linear_attention(form):
+    """lam = 0: the state seen by a row of chunk c is the sum over ALL tokens of chunks <= c-2,
+    so N_LA / D_LA must equal normalised linear attention over that prefix, evaluated here in
+    the quadratic form sum_i (phi(q_t).phi(k_i)) v_i with phi recomputed from its definition."""
+    N, C, d = 40, 8, 6
+    q, k, v, g, Wq, Wk = rand_problem(3, N, d, df=5)
+    r = form(q, k, v, None, Wq, Wk, C=C, W=8, lam=0, scale=0.4, eps=EPS)
+
+    def phi(x, Wm):
+        f = x @ Wm
+        u = f / np.linalg.norm(f, axis=1, keepdims=True) * np.linalg.norm(x, axis=1, keepdims=True)
+        return np.concatenate([sp_softmax(u, axis=1), sp_softmax(-u, axis=1)], axis=1)
+
+    pq, pk = phi(q, Wq), phi(k, Wk)
+    A = pq @ pk.T                                    # quadratic form weights
+    for t in range(N):
+        n_prefix = max(0, (t // C - 1)) * C          # tokens of chunks <= c-2
+        w = A[t, :n_prefix]
+        np.testing.assert_allclose(r["D_LA"][t], w.sum(), rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(r["N_LA"][t], w @ v[:n_prefix], rtol=1e-11, atol=1e-14)
+        # the softmax branch then covers exactly the local span
+        lo = max(0, (t // C - 1) * C)
+        e = np.exp(0.4 * (k[lo:t + 1] @ q[t]) - r["M"][t])
+        np.testing.assert_allclose(r["D_SA"][t], e.sum(), rtol=1e-12)
+
+
+def test_state_recurrence_matches_running_sum():
+    """The (s, z) left after the last token equals the token-by-token recurrence
+    s += phi(k)^T v, z += phi(k)^T over the routed, un-selected tokens."""
+    N, C, d, lam = 48, 8, 6, 3
+    q, k, v, g, Wq, Wk = rand_problem(4, N, d)
+    r = O.still_recurrent(q, k, v, None, Wq, Wk, C=C, W=8, lam=lam, scale=0.4, eps=EPS, return_state=True)
+    n_routed_chunks = (N - 1) // C - 1               # chunks <= c(last) - 2
+    chosen = set(r["sel"][:n_routed_chunks].reshape(-1).tolist())
+    s = np.zeros((2 * d, d))
+    z = np.zeros(2 * d)
+    for i in range(n_routed_chunks * C):
+        if i in chosen:
+            continue
+        p = O.np_map(k[i], Wk)[0]
+        s += np.outer(p, v[i])
+        z += p
+    np.testing.assert_allclose(r["state"]["s"], s, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(r["state"]["z"], z, rtol=1e-12, atol=1e-14)
+    assert sorted(r["state"]["retained"].tolist()) == sorted(chosen)
+
+
+# --------------------------------------------------------------------------- each token exactly once
+@pytest.mark.parametrize("form", FORMS)
+@pytest.mark.parametrize("N,C,lam", [(24, 4, 1), (23, 4, 2), (20, 5, 0), (18, 6, 6)])
+def test_every_past_token_contributes_once_with_two_chunk_delay(form, N, C, lam):
+    """With v = identity (d = N) the numerators list each key's weight separately.  Row t
+    (chunk c) must give: exp-weights exactly on the local span [(c-1)C, t] and on the selected
+    tokens of chunks <= c-2; phi-weights exactly on the other tokens of chunks <= c-2; nothing
+    on the future; never both."""
+    rng = np.random.default_rng(5)
+    dq = 4
+    q = rng.standard_normal((N, dq))
+    k = rng.standard_normal((N, dq))
+    v = np.eye(N)
+    Wq = rng.standard_normal((dq, 3))
+    Wk = rng.standard_normal((dq, 3))
+    # v has d = N columns while q,k have dq: the operator never mixes those dimensions
+    r = form(q, k, v, None, Wq, Wk, C=C, W=3, lam=lam, scale=0.5, eps=EPS)
+    sel = r["sel"]
+    for t in range(N):
+        c = t // C
+        sa = r["N_SA"][t] > 0
+        la = r["N_LA"][t] > 0
+        assert not np.any(sa & la)
+        assert np.all((sa | la)[: t + 1]) and not np.any((sa | la)[t + 1:])
+        expect_sa = np.zeros(N, bool)
+        expect_sa[max(0, (c - 1) * C): t + 1] = True
+        for cc in range(0, c - 1):
+            expect_sa[sel[cc]] = True
+        assert np.array_equal(sa, expect_sa)
+        # weights themselves
+        e = np.exp(0.5 * (k @ q[t]) - r["M"][t])
+        np.testing.assert_allclose(r["N_SA"][t][sa], e[sa], rtol=1e-12)
+
+
+# --------------------------------------------------------------------------- three forms agree
+@pytest.mark.parametrize("N,C,W,lam,df", [(64, 8, 8, 2, 8), (61, 8, 12, 3, 4), (40, 16, 5, 4, 8),
+                                          (33, 4, 9, 1, 6), (7, 8, 8, 2, 8)])
+def test_recurrent_chunkwise_and_definition_forms_agree(N, C, W, lam, df):
+    q, k, v, g, Wq, Wk = rand_problem(6, N, 8, df=df)
+    rng = np.random.default_rng(7)
+    bq, bk = rng.standard_normal(df) * 0.1, rng.standard_normal(df) * 0.1
+    rs = [f(q, k, v, g, Wq, Wk, C=C, W=W, lam=lam, scale=0.35, eps=EPS, bq=bq, bk=bk) for f in FORMS]
+    for key in ("out", "M", "N_SA", "D_SA", "N_LA", "D_LA"):
+        np.testing.assert_allclose(rs[0][key], rs[1][key], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(rs[0][key], rs[2][key], rtol=1e-11, atol=1e-13)
+    assert all(np.all(r["D_SA"] > 0) for r in rs)
+
+
+def test_row_range_mode_matches_full_run():
+    q, k, v, g, Wq, Wk = rand_problem(8, 80, 8)
+    full = O.still_chunkwise(q, k, v, g, Wq, Wk, C=8, W=8, lam=2, scale=0.35, eps=EPS)
+    part = O.still_chunkwise(q, k, v, g, Wq, Wk, C=8, W=8, lam=2, scale=0.35, eps=EPS, rows=(40, 56))
+    np.testing.assert_array_equal(full["out"][40:56], part["out"][40:56])
+    rec = O.still_recurrent(q, k, v, g, Wq, Wk, C=8, W=8, lam=2, scale=0.35, eps=EPS, rows=(43, 50))
+    np.testing.assert_allclose(full["out"][43:50], rec["out"][43:50], rtol=1e-11)
+
+
+# --------------------------------------------------------------------------- gate
+def test_gate_multiplies_linear_numerator_only():
+    q, k, v, g, Wq, Wk = rand_problem(9, 48, 8)
+    kw = dict(C=8, W=8, lam=2, scale=0.35, eps=EPS)
+    r0 = O.still_chunkwise(q, k, v, None, Wq, Wk, **kw)
+    r1 = O.still_chunkwise(q, k, v, g, Wq, Wk, **kw)
+    np.testing.assert_allclose(r1["N_LA"], r0["N_LA"] * g, rtol=1e-13)
+    np.testing.assert_array_equal(r1["D_LA"], r0["D_LA"])
+    f = np.exp(-r0["M"])[:, None]
+    y = (r0["N_SA"] + f * g * r0["N_LA"]) / (r0["D_SA"][:, None] + f * r0["D_LA"][:, None])
+    np.testing.assert_allclose(r1["out"], y, rtol=1e-12)
+    # a gate of zeros removes the linear numerator but keeps its share of the normaliser
+    rz = O.still_recurrent(q, k, v, np.zeros_like(g), Wq, Wk, **kw)
+    np.testing.assert_allclose(rz["out"], r0["N_SA"] / (r0["D_SA"][:, None] + f * r0["D_LA"][:, None]),
+                               rtol=1e-10, atol=1e-14)
+
+
+# --------------------------------------------------------------------------- score
+def test_score_of_one_token_window_is_closed_value():
+    q, k, *_ = rand_problem(10, 12, 8)
+    s = O.self_saliency_scores(q, k, W=5, scale=0.3, eps=EPS)
+    assert s[0] == pytest.approx(np.log((1 + EPS) / EPS), rel=1e-14)
+    s1 = O.self_saliency_scores(q, k, W=1, scale=0.3, eps=EPS)      # every window has one token
+    np.testing.assert_allclose(s1, np.log((1 + EPS) / EPS), rtol=1e-14)
+    assert np.all(s <= np.log((1 + EPS) / EPS) * (1 + 1e-12))       # the largest value it can take
+
+
+def test_score_of_uniform_window_is_closed_value():
+    rng = np.random.default_rng(11)
+    k = rng.standard_normal((20, 8))
+    q = np.zeros((20, 8))
+    Wn = 6
+    s = O.self_saliency_scores(q, k, W=Wn, scale=1.0, eps=EPS)
+    for t in range(1, 20):
+        n = min(t + 1, Wn)
+        expect = ((n - 1) / n) * np.log((1 / n + EPS) / (1 / (n - 1) + EPS)) + (1 / n) * np.log((1 / n + EPS) / EPS)
+        assert s[t] == pytest.approx(expect, rel=1e-12)
+
+
+def test_score_closed_form_through_self_weight():
+    """With p the softmax weight the token gives itself, a_nodiag_j = a_diag_j / (1 - p), hence for
+    eps -> 0:  Score -> p ln((p + eps)/eps) + (1 - p) ln(1 - p)."""
+    q, k, *_ = rand_problem(12, 64, 8)
+    eps = 1e-13
+    Wn = 9
+    s = O.self_saliency_scores(q, k, W=Wn, scale=0.5, eps=eps)
+    for t in range(1, 64):
+        lo = max(0, t - Wn + 1)
+        p = sp_softmax(0.5 * (k[lo:t + 1] @ q[t]))[-1]
+        expect = p * np.log((p + eps) / eps) + (1 - p) * np.log1p(-p)
+        assert s[t] == pytest.approx(expect, rel=1e-8, abs=1e-9)
+
+
+def test_score_matches_algorithm1_mask_construction_when_window_is_one_chunk():
+    q, k, *_ = rand_problem(13, 96, 8)
+    for C in (8, 16, 32):
+        a = O.self_saliency_scores(q, k, W=C, scale=0.4, eps=EPS)
+        b = O.alg1_scores(q, k, C=C, scale=0.4, eps=EPS)
+        np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-13)
+
+
+def test_score_ignores_keys_outside_window_and_future():
+    q, k, *_ = rand_problem(14, 40, 8)
+    s = O.self_saliency_scores(q, k, W=6, scale=0.4, eps=EPS)
+    k2 = k.copy()
+    k2[:10] += 5.0          # outside the window of token 20
+    k2[21:] -= 3.0          # future of token 20
+    s2 = O.self_saliency_scores(q, k2, W=6, scale=0.4, eps=EPS)
+    assert s2[20] == s[20]
+    assert s2[12] != s[12]
+
+
+# --------------------------------------------------------------------------- NP-Map
+def test_np_map_preserves_norm_and_is_two_distributions():
+    rng = np.random.default_rng(15)
+    x = rng.standard_normal((50, 16)) * np.exp(rng.standard_normal((50, 1)))
+    Wm = rng.standard_normal((16, 12)) * 3.0      # an MLP that would rescale norms a lot
+    b = rng.standard_normal(12)
+    u = O.np_map_u(x, Wm, b)
+    np.testing.assert_allclose(np.linalg.norm(u, axis=1), np.linalg.norm(x, axis=1), rtol=1e-14)
+    phi = O.np_map(x, Wm, b)
+    assert phi.shape == (50, 24) and np.all(phi > 0)
+    np.testing.assert_allclose(phi[:, :12].sum(1), 1.0, rtol=1e-14)
+    np.testing.assert_allclose(phi[:, 12:].sum(1), 1.0, rtol=1e-14)
+    # direction is that of f(x)
+    f = x @ Wm + b
+    cos = np.sum(u * f, axis=1) / (np.linalg.norm(u, axis=1) * np.linalg.norm(f, axis=1))
+    np.testing.assert_allclose(cos, 1.0, rtol=1e-13)
+
+
+def test_np_map_with_identity_mlp_is_hedgehog_softmax_pair():
+    rng = np.random.default_rng(16)
+    x = rng.standard_normal((9, 7))
+    phi = O.np_map(x, np.eye(7))
+    np.testing.assert_allclose(phi[:, :7], sp_softmax(x, axis=1), rtol=1e-13)
+    np.testing.assert_allclose(phi[:, 7:], sp_softmax(-x, axis=1), rtol=1e-13)
+    # scaling the MLP changes nothing: only its direction is used
+    np.testing.assert_allclose(O.np_map(x, 7.5 * np.eye(7)), phi, rtol=1e-13)
+    # zero MLP output -> uniform
+    np.testing.assert_allclose(O.np_map(x, np.zeros((7, 4))), 0.25)
+
+
+# --------------------------------------------------------------------------- selection
+def test_selection_brute_force_and_tie_break():
+    rng = np.random.default_rng(17)
+    C = 9
+    for trial in range(30):
+        score = rng.standard_normal(3 * C + 4)          # ragged tail is never ranked
+        if trial % 2:
+            score = np.round(score * 2) / 2             # plant many exact ties
+        for lam in (0, 1, 3, 8, 9):
+            sel = O.select_top_lambda(score, C, lam)
+            assert sel.shape == (3, lam)
+            for c in range(3):
+                s = score[c * C:(c + 1) * C]
+                best = None
+                for comb in itertools.combinations(range(C), lam):    # lexicographic order
+                    tot = sum(s[i] for i in comb)
+                    if best is None or tot > best[0] + 1e-15:
+                        best = (tot, comb)
+                # first maximiser in lexicographic order == ties broken toward low indices
+                assert tuple(sel[c] - c * C) == best[1]
+                assert np.all(np.diff(sel[c]) > 0)
+
+
+def test_uniform_scores_select_lowest_indices():
+    rng = np.random.default_rng(18)
+    N, C, lam, Wn = 64, 8, 3, 8
+    k = rng.standard_normal((N, 4))
+    v = rng.standard_normal((N, 4))
+    q = np.zeros((N, 4))
+    r = O.still_chunkwise(q, k, v, None, np.eye(4), np.eye(4), C=C, W=Wn, lam=lam, scale=1.0, eps=EPS)
+    for c in range(1, N // C):                  # chunks whose windows are all full: exact ties
+        assert r["sel"][c].tolist() == [c * C, c * C + 1, c * C + 2]
+    # first chunk: shorter windows score higher (token 0 highest), still the first three
+    assert r["sel"][0].tolist() == [0, 1, 2]
+    gaps = O.selection_gaps(r["score"], C, lam)
+    assert gaps[1] == 0.0 and gaps[0] > 0
+
+
+# --------------------------------------------------------------------------- causality
+@pytest.mark.parametrize("form", [O.still_recurrent, O.still_chunkwise])
+def test_appending_tokens_never_changes_earlier_rows(form):
+    q, k, v, g, Wq, Wk = rand_problem(19, 70, 8)
+    kw = dict(C=8, W=10, lam=2, scale=0.35, eps=EPS)
+    full = form(q, k, v, g, Wq, Wk, **kw)
+    for n in (1, 8, 9, 37, 64):
+        part = form(q[:n], k[:n], v[:n], g[:n], Wq, Wk, **kw)
+        np.testing.assert_allclose(part["out"], full["out"][:n], rtol=1e-12, atol=1e-14)
+        np.testing.assert_array_equal(part["score"], full["score"][:n])
+
+
+# --------------------------------------------------------------------------- batched driver
+def test_unit_driver_uses_gqa_map():
+    rng = np.random.default_rng(20)
+    B, N, Hq, Hkv, d = 2, 24, 4, 2, 8
+    inp = {"q": rng.standard_normal((B, N, Hq, d)), "k": rng.standard_normal((B, N, Hkv, d)),
+           "v": rng.standard_normal((B, N, Hkv, d)), "Wq": rng.standard_normal((Hq, d, d)),
+           "Wk": rng.standard_normal((Hq, d, d))}
+    kv_map = np.array([0, 0, 1, 1])
+    res = O.still_forward_units(inp, kv_map, [(1, 2)], C=4, W=4, lam=1, scale=0.3, eps=EPS)
+    direct = O.still_chunkwise(inp["q"][1, :, 2], inp["k"][1, :, 1], inp["v"][1, :, 1], None,
+                               inp["Wq"][2], inp["Wk"][2], C=4, W=4, lam=1, scale=0.3, eps=EPS)
+    np.testing.assert_array_equal(res[(1, 2)]["out"], direct["out"])
