@@ -1,0 +1,162 @@
+/*
+ * libstill - forward hot path of STILL's intra-layer hybrid attention on AMD MI355X (gfx950).
+ *
+ * One Transformer layer's attention operator from "STILL" (arXiv 2602.02180), forward only:
+ *   - Self-Saliency Score over a causal sliding window            (Sec. 3.1, score equation)
+ *   - delayed, chunk-granular Top-lambda routing                   (Sec. 3.3, delayed-selection eq.)
+ *   - softmax attention over the salient cache (local span + retained tokens)
+ *   - NP-Map linear attention over every other routed token        (Sec. 3.2; cache-routing eq.)
+ *   - one shared normaliser  y = (N_SA + N_LA) / (D_SA + D_LA)     (Sec. 3.3, output eqs.)
+ * in its chunk-wise parallel form (Algorithm 1) for prefill and its recurrent form for decode.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every tensor, workspace and state pointer is DEVICE memory owned by the caller,
+ *     16-byte aligned, unless marked HOST.  The library allocates and frees nothing on the device,
+ *     never synchronises the stream, and keeps no global mutable state except a per-thread error text.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Tokens and chunks are 0-indexed here (the paper counts from 1).
+ *   - Every function returning still_status_t validates its arguments on the host before any launch;
+ *     on failure nothing has been enqueued and still_last_error() describes the reason.
+ */
+#ifndef STILL_H
+#define STILL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define STILL_API __attribute__((visibility("default")))
+
+typedef enum {
+  STILL_OK = 0,
+  STILL_ERR_INVALID_ARG = 1,         /* null/misaligned pointer, inconsistent sizes              */
+  STILL_ERR_UNSUPPORTED = 2,         /* legal problem outside the shapes the kernels are built for */
+  STILL_ERR_WORKSPACE_TOO_SMALL = 3,
+  STILL_ERR_HIP = 4,                 /* a launch was rejected by the runtime                     */
+  STILL_ERR_STATE = 5                /* decode state full or not initialised for these params    */
+} still_status_t;
+
+typedef enum { STILL_F32 = 0, STILL_BF16 = 1 } still_dtype_t;
+
+/*
+ * Problem description (Algorithm 1's inputs: q, k, v, gate g, feature maps phi_q / phi_k, chunk size C,
+ * number lambda, small constant eps; plus what the paper leaves implicit: batch, GQA head map, the
+ * score window W of the window-set equation, and the logit scale).
+ *
+ * Supported by the kernels: d in {64,128}; d_f == d; C in {64,128}; 1 <= W <= 128; 0 <= lambda <= C;
+ * Hq <= 128; Hq % Hkv == 0 when kv_head_of_q is NULL.  N >= 1 need not be a multiple of C: the trailing
+ * partial chunk is never ranked.  Anything else returns STILL_ERR_UNSUPPORTED.
+ *
+ * Strides are in ELEMENTS for (batch, token, head); the head dimension is contiguous.  Every stride
+ * must be a multiple of 16 bytes.
+ */
+typedef struct still_params {
+  int32_t B, N, Hq, Hkv, d, d_f; /* d_f: width of the NP-Map layer f(x) = x W + b; phi has 2*d_f features */
+  int32_t C, W, lambda;          /* chunk size, score window (keys, token itself included), kept per chunk */
+  float scale;                   /* multiplies every q.k logit, score window and softmax branch alike      */
+  float eps;                     /* eps of the score equation                                              */
+  int32_t dtype;                 /* still_dtype_t of q, k, v, g, out, Wq, Wk, bq, bk                        */
+  int64_t q_sb, q_st, q_sh;      /* q   [B, N, Hq,  d]                                                     */
+  int64_t k_sb, k_st, k_sh;      /* k   [B, N, Hkv, d]                                                     */
+  int64_t v_sb, v_st, v_sh;      /* v   [B, N, Hkv, d]                                                     */
+  int64_t o_sb, o_st, o_sh;      /* out [B, N, Hq,  d]                                                     */
+  int64_t g_sb, g_st, g_sh;      /* g   [B, N, Hq,  d] (ignored when g == NULL)                            */
+  const int32_t* kv_head_of_q;   /* HOST, Hq entries in [0,Hkv), or NULL => hq / (Hq / Hkv)                */
+} still_params_t;
+
+/* Byte offsets of the regions still_hybrid_attn_fwd lays out inside its workspace (for tests/tools). */
+typedef struct still_ws_layout {
+  size_t score;    /* float   [B, Hq, N]                         Self-Saliency Score of every token        */
+  size_t sel;      /* int32   [B, Hq, N/C, lambda]               selected tokens per full chunk, ascending */
+  size_t vt;       /* dtype   [B, Hkv, d, Npad]                  v transposed, zero padded                 */
+  size_t kret;     /* dtype   [B, Hq, cap, d]                    retained keys in routing order            */
+  size_t vrett;    /* dtype   [B, Hq, d, cap]                    retained values, transposed               */
+  size_t wqt;      /* dtype   [Hq, d_f, d]                       Wq transposed                             */
+  size_t wkt;      /* dtype   [Hq, d_f, d]                       Wk transposed                             */
+  size_t seg;      /* float   [B, Hq, nseg, 2*d_f*(d+1)]         per-segment linear-attention states       */
+  size_t n_la;     /* float   [B, Hq, N, d]                      gated linear-branch numerator N_LA        */
+  size_t d_la;     /* float   [B, Hq, N]                         linear-branch normaliser D_LA             */
+  size_t total;    /* bytes needed                                                                         */
+  int32_t n_pad;   /* Npad                                                                                 */
+  int32_t cap;     /* retained-row capacity (multiple of 64)                                               */
+  int32_t nseg;    /* segments of the chunk scan                                                           */
+  int32_t seg_chunks; /* chunks per segment                                                                */
+} still_ws_layout_t;
+
+/* Library/ABI version: major*10000 + minor*100 + patch. */
+STILL_API int32_t still_version(void);
+
+/* Text of the last failure on the calling thread (static storage, never NULL). */
+STILL_API const char* still_last_error(void);
+
+/* Bytes of device workspace still_hybrid_attn_fwd needs for `p`; 0 on invalid/unsupported params
+ * (still_last_error() says why). */
+STILL_API size_t still_fwd_workspace_bytes(const still_params_t* p);
+
+/* Fills *layout for `p`; same validation as above. */
+STILL_API still_status_t still_fwd_workspace_layout(const still_params_t* p, still_ws_layout_t* layout);
+
+/*
+ * Prefill: the chunk-wise parallel form (Algorithm 1) over all N tokens of B sequences.
+ *
+ *   q, k, v        device, dtype, strided as described in `p`
+ *   g              device, dtype, or NULL (gate of ones); multiplies the linear numerator only
+ *   Wq, Wk         device, dtype, [Hq, d, d_f] contiguous: per-query-head NP-Map layers for q and k
+ *   bq, bk         device, dtype, [Hq, d_f] contiguous, or NULL (no bias)
+ *   out            device, dtype, strided; rows written for every (b, t < N, hq)
+ *   score_out      device float [B, Hq, N] or NULL: Score of every token
+ *   sel_idx        device int32 [B, Hq, N/C, lambda] or NULL: global token indices of the tokens kept
+ *                  in each full chunk, ascending within a chunk
+ *   sel_idx_is_input  0: sel_idx (if given) is an OUTPUT.  1: sel_idx is an INPUT that replaces the
+ *                  Top-lambda step (indices must lie inside their chunk, strictly ascending); test hook
+ *   state_out      device, or NULL: a decode state (see still_state_bytes) initialised with
+ *                  still_state_init for the same params; on return it stands after token N-1
+ *   workspace      device scratch of at least still_fwd_workspace_bytes(p) bytes; contents undefined
+ *                  afterwards
+ *   stream         hipStream_t (as void*)
+ *
+ * Ties in the Top-lambda step go to the lower token index.  NaN inputs give undefined routing.
+ */
+STILL_API still_status_t still_hybrid_attn_fwd(const still_params_t* p,
+                                     const void* q, const void* k, const void* v, const void* g,
+                                     const void* Wq, const void* bq, const void* Wk, const void* bk,
+                                     void* out, float* score_out, int32_t* sel_idx,
+                                     int32_t sel_idx_is_input, void* state_out,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Decode state of B sequences (the salient cache h and the state (s, z) of the cache-routing
+ * equation, plus the local ring that delayed selection needs).  One opaque caller-owned buffer:
+ *   header | pos[B] | n_routed[B] | S[B,Hq,2*d_f,d] f32 | z[B,Hq,2*d_f] f32 |
+ *   Kret[B,Hq,cap,d] | VretT... | local K/V ring [B,Hkv,R,d] | score ring [B,Hq,R] f32
+ * with cap = lambda * ceil(max_tokens / C) rounded up to 64 and R >= 2*C + W.
+ * It can be copied or saved with plain memcpy.  `p->N` is ignored by the state functions.
+ */
+STILL_API size_t still_state_bytes(const still_params_t* p, int32_t max_tokens);
+
+/* Resets a state buffer to "no token seen".  Enqueues fill kernels on `stream`. */
+STILL_API still_status_t still_state_init(const still_params_t* p, void* state, int32_t max_tokens, void* stream);
+
+/*
+ * One decode step of the recurrent form for every sequence in the batch: appends (k_t, v_t), scores the
+ * new token over its window, routes the chunk that has just left the local span when the token opens a
+ * new chunk (Top-lambda -> retained cache, the rest -> (s, z)), and writes
+ * y_t = (N_SA + N_LA) / (D_SA + D_LA).
+ *
+ *   q_t [B, Hq, d], k_t, v_t [B, Hkv, d], g_t [B, Hq, d] or NULL, out_t [B, Hq, d]: device, dtype, contiguous.
+ * Returns STILL_ERR_STATE when a sequence would exceed max_tokens (checked against the host-side
+ * position the library mirrors in the state header; no device read-back).
+ */
+STILL_API still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* state,
+                                             const void* q_t, const void* k_t, const void* v_t,
+                                             const void* g_t,
+                                             const void* Wq, const void* bq, const void* Wk, const void* bk,
+                                             void* out_t, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STILL_H */

@@ -1,0 +1,176 @@
+"""ctypes binding of libstill's C ABI (include/still.h): same names, argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels.  torch is used for device
+memory and streams; tensors are passed as raw device pointers.  There is no CPU fallback:
+if the library has not been built the import of the native handle raises.
+"""
+from __future__ import annotations
+
+import ctypes as ct
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libstill.so")
+
+STILL_OK, STILL_ERR_INVALID_ARG, STILL_ERR_UNSUPPORTED, STILL_ERR_WORKSPACE_TOO_SMALL, STILL_ERR_HIP, \
+    STILL_ERR_STATE = range(6)
+STILL_F32, STILL_BF16 = 0, 1
+DTYPE_CODE = {"f32": STILL_F32, "bf16": STILL_BF16}
+
+
+class StillParams(ct.Structure):
+    _fields_ = [
+        ("B", ct.c_int32), ("N", ct.c_int32), ("Hq", ct.c_int32), ("Hkv", ct.c_int32), ("d", ct.c_int32),
+        ("d_f", ct.c_int32), ("C", ct.c_int32), ("W", ct.c_int32), ("lam", ct.c_int32),
+        ("scale", ct.c_float), ("eps", ct.c_float), ("dtype", ct.c_int32),
+        ("q_sb", ct.c_int64), ("q_st", ct.c_int64), ("q_sh", ct.c_int64),
+        ("k_sb", ct.c_int64), ("k_st", ct.c_int64), ("k_sh", ct.c_int64),
+        ("v_sb", ct.c_int64), ("v_st", ct.c_int64), ("v_sh", ct.c_int64),
+        ("o_sb", ct.c_int64), ("o_st", ct.c_int64), ("o_sh", ct.c_int64),
+        ("g_sb", ct.c_int64), ("g_st", ct.c_int64), ("g_sh", ct.c_int64),
+        ("kv_head_of_q", ct.POINTER(ct.c_int32)),
+    ]
+
+
+class StillWsLayout(ct.Structure):
+    _fields_ = [(n, ct.c_size_t) for n in
+                ("score", "sel", "vt", "kret", "vrett", "wqt", "wkt", "seg", "n_la", "d_la", "total")] + \
+               [(n, ct.c_int32) for n in ("n_pad", "cap", "nseg", "seg_chunks")]
+
+
+class StillError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libstill status {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ct.CDLL:
+    """The loaded library; raises if it was never built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2602_02180_amd.build`")
+        L = ct.CDLL(LIB_PATH)
+        vp, pp = ct.c_void_p, ct.POINTER(StillParams)
+        L.still_version.restype = ct.c_int32
+        L.still_last_error.restype = ct.c_char_p
+        L.still_fwd_workspace_bytes.restype = ct.c_size_t
+        L.still_fwd_workspace_bytes.argtypes = [pp]
+        L.still_fwd_workspace_layout.restype = ct.c_int
+        L.still_fwd_workspace_layout.argtypes = [pp, ct.POINTER(StillWsLayout)]
+        L.still_hybrid_attn_fwd.restype = ct.c_int
+        L.still_hybrid_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ct.c_int32, vp, vp,
+                                            ct.c_size_t, vp]
+        L.still_state_bytes.restype = ct.c_size_t
+        L.still_state_bytes.argtypes = [pp, ct.c_int32]
+        L.still_state_init.restype = ct.c_int
+        L.still_state_init.argtypes = [pp, vp, ct.c_int32, vp]
+        L.still_hybrid_attn_decode_step.restype = ct.c_int
+        L.still_hybrid_attn_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _check(code: int) -> None:
+    if code != STILL_OK:
+        raise StillError(code, still_last_error())
+
+
+def _strides(t):
+    if t is None:
+        return 0, 0, 0
+    assert t.dim() == 4 and t.stride(3) == 1, "tensors are [B, N, H, d] with a contiguous last dim"
+    return t.stride(0), t.stride(1), t.stride(2)
+
+
+def make_params(*, B, N, Hq, Hkv, d, C, W, lam, scale, eps, dtype, d_f=None, q=None, k=None, v=None, out=None,
+                g=None, kv_head_of_q=None) -> StillParams:
+    """Fill a still_params_t; strides are taken from the torch tensors ([B, N, H, d])."""
+    p = StillParams()
+    p.B, p.N, p.Hq, p.Hkv, p.d, p.d_f = B, N, Hq, Hkv, d, (d_f or d)
+    p.C, p.W, p.lam, p.scale, p.eps = C, W, lam, scale, eps
+    p.dtype = DTYPE_CODE[dtype] if isinstance(dtype, str) else dtype
+    p.q_sb, p.q_st, p.q_sh = _strides(q)
+    p.k_sb, p.k_st, p.k_sh = _strides(k)
+    p.v_sb, p.v_st, p.v_sh = _strides(v)
+    p.o_sb, p.o_st, p.o_sh = _strides(out)
+    p.g_sb, p.g_st, p.g_sh = _strides(g)
+    if kv_head_of_q is not None:
+        arr = (C_int32_array(len(kv_head_of_q)))(*[int(x) for x in kv_head_of_q])
+        p._keepalive = arr
+        p.kv_head_of_q = ct.cast(arr, ct.POINTER(ct.c_int32))
+    return p
+
+
+def C_int32_array(n):
+    return ct.c_int32 * n
+
+
+# ------------------------------------------------------------------ entry points (same names as still.h)
+
+def still_version() -> int:
+    return int(lib().still_version())
+
+
+def still_last_error() -> str:
+    return lib().still_last_error().decode()
+
+
+def still_fwd_workspace_bytes(p: StillParams) -> int:
+    n = int(lib().still_fwd_workspace_bytes(ct.byref(p)))
+    if n == 0:
+        raise StillError(-1, still_last_error())
+    return n
+
+
+def still_fwd_workspace_layout(p: StillParams) -> StillWsLayout:
+    L = StillWsLayout()
+    _check(lib().still_fwd_workspace_layout(ct.byref(p), ct.byref(L)))
+    return L
+
+
+def still_hybrid_attn_fwd(p: StillParams, q, k, v, g, Wq, bq, Wk, bk, out, score_out=None, sel_idx=None,
+                          sel_idx_is_input: bool = False, state_out=None, workspace=None, stream=None) -> None:
+    """Enqueue the prefill on `stream` (a torch.cuda.Stream; default: torch's current stream)."""
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(lib().still_hybrid_attn_fwd(
+        ct.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(out),
+        _ptr(score_out), _ptr(sel_idx), 1 if sel_idx_is_input else 0, _ptr(state_out), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), stream.cuda_stream))
+
+
+def still_state_bytes(p: StillParams, max_tokens: int) -> int:
+    n = int(lib().still_state_bytes(ct.byref(p), max_tokens))
+    if n == 0:
+        raise StillError(-1, still_last_error())
+    return n
+
+
+def still_state_init(p: StillParams, state, max_tokens: int, stream=None) -> None:
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(lib().still_state_init(ct.byref(p), _ptr(state), max_tokens, stream.cuda_stream))
+
+
+def still_hybrid_attn_decode_step(p: StillParams, state, q_t, k_t, v_t, g_t, Wq, bq, Wk, bk, out_t,
+                                  stream=None) -> None:
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(lib().still_hybrid_attn_decode_step(ct.byref(p), _ptr(state), _ptr(q_t), _ptr(k_t), _ptr(v_t),
+                                               _ptr(g_t), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(out_t),
+                                               stream.cuda_stream))

@@ -1,0 +1,267 @@
+// C ABI of libstill: argument validation, workspace layout and the launch sequence of the prefill path.
+// See include/still.h for the contract of every entry point.
+#include "../../include/still.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "still_kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+still_status_t fail(still_status_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline size_t esize(int dtype) { return dtype == STILL_BF16 ? 2 : 4; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+still_status_t validate_params(const still_params_t* p, bool need_n) {
+  if (p == nullptr) return fail(STILL_ERR_INVALID_ARG, "params is NULL");
+  if (p->dtype != STILL_F32 && p->dtype != STILL_BF16) return fail(STILL_ERR_INVALID_ARG, "dtype %d unknown", p->dtype);
+  if (p->B < 1 || p->Hq < 1 || p->Hkv < 1) return fail(STILL_ERR_INVALID_ARG, "B, Hq, Hkv must be >= 1");
+  if (need_n && p->N < 1) return fail(STILL_ERR_INVALID_ARG, "N must be >= 1 (got %d)", p->N);
+  if (p->lambda < 0 || p->lambda > p->C) return fail(STILL_ERR_INVALID_ARG, "lambda %d outside [0, C=%d]", p->lambda, p->C);
+  if (p->W < 1) return fail(STILL_ERR_INVALID_ARG, "W must be >= 1");
+  if (!(p->eps > 0.f)) return fail(STILL_ERR_INVALID_ARG, "eps must be > 0");
+  if (!(p->scale == p->scale)) return fail(STILL_ERR_INVALID_ARG, "scale is NaN");
+  if (p->Hq > still::kMaxHq) return fail(STILL_ERR_UNSUPPORTED, "Hq %d > %d", p->Hq, still::kMaxHq);
+  if (p->kv_head_of_q == nullptr) {
+    if (p->Hq % p->Hkv != 0) return fail(STILL_ERR_INVALID_ARG, "Hq %% Hkv != 0 and no kv_head_of_q map given");
+  } else {
+    for (int h = 0; h < p->Hq; ++h)
+      if (p->kv_head_of_q[h] < 0 || p->kv_head_of_q[h] >= p->Hkv)
+        return fail(STILL_ERR_INVALID_ARG, "kv_head_of_q[%d] = %d outside [0, Hkv)", h, p->kv_head_of_q[h]);
+  }
+  if (p->d != 64 && p->d != 128) return fail(STILL_ERR_UNSUPPORTED, "d = %d (supported: 64, 128)", p->d);
+  if (p->d_f != p->d) return fail(STILL_ERR_UNSUPPORTED, "d_f = %d (supported: d_f == d)", p->d_f);
+  if (p->C != 64 && p->C != 128) return fail(STILL_ERR_UNSUPPORTED, "C = %d (supported: 64, 128)", p->C);
+  if (p->W > 128) return fail(STILL_ERR_UNSUPPORTED, "W = %d (supported: 1..128)", p->W);
+  if (p->dtype == STILL_F32 && p->d == 128 && p->C == 128)
+    return fail(STILL_ERR_UNSUPPORTED, "fp32 with d = 128 and C = 128 exceeds the LDS budget of the linear branch");
+  if (need_n && (int64_t)p->N > (int64_t)1 << 24) return fail(STILL_ERR_UNSUPPORTED, "N = %d too large", p->N);
+  return STILL_OK;
+}
+
+still_status_t validate_strides(const still_params_t* p, bool with_g) {
+  const int64_t unit = 16 / (int64_t)esize(p->dtype);
+  const int64_t s[] = {p->q_sb, p->q_st, p->q_sh, p->k_sb, p->k_st, p->k_sh, p->v_sb, p->v_st, p->v_sh,
+                       p->o_sb, p->o_st, p->o_sh};
+  for (int64_t x : s)
+    if (x < 0 || x % unit != 0) return fail(STILL_ERR_INVALID_ARG, "stride %lld is negative or not a multiple of 16 bytes", (long long)x);
+  if (p->q_st < p->d || p->k_st < p->d || p->v_st < p->d || p->o_st < p->d)
+    return fail(STILL_ERR_INVALID_ARG, "token stride smaller than d");
+  if (with_g) {
+    const int64_t gs[] = {p->g_sb, p->g_st, p->g_sh};
+    for (int64_t x : gs)
+      if (x < 0 || x % unit != 0) return fail(STILL_ERR_INVALID_ARG, "gate stride %lld invalid", (long long)x);
+  }
+  return STILL_OK;
+}
+
+void fill_map(const still_params_t* p, still::HeadMap* m) {
+  for (int h = 0; h < still::kMaxHq; ++h) m->kv[h] = 0;
+  for (int h = 0; h < p->Hq; ++h) m->kv[h] = p->kv_head_of_q ? p->kv_head_of_q[h] : h / (p->Hq / p->Hkv);
+}
+
+void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
+  const size_t es = esize(p->dtype);
+  const int64_t B = p->B, N = p->N, Hq = p->Hq, Hkv = p->Hkv, d = p->d, df = p->d_f;
+  const int64_t nc = (N + p->C - 1) / p->C, ncf = N / p->C;
+  const int64_t npad = (N + 127) / 128 * 128;
+  const int64_t cap = (ncf * p->lambda + 63) / 64 * 64;
+  int64_t G = (nc * B * Hq + 511) / 512;
+  if (G < 2) G = 2;
+  if (G > nc) G = nc;
+  const int64_t nseg = (nc + G - 1) / G;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + (bytes ? bytes : 16), 256);
+    return o;
+  };
+  L->score = take((size_t)B * Hq * N * 4);
+  L->sel = take((size_t)B * Hq * ncf * p->lambda * 4);
+  L->vt = take((size_t)B * Hkv * d * npad * es);
+  L->kret = take((size_t)B * Hq * cap * d * es);
+  L->vrett = take((size_t)B * Hq * cap * d * es);
+  L->wqt = take((size_t)Hq * df * d * es);
+  L->wkt = take((size_t)Hq * df * d * es);
+  L->seg = take((size_t)B * Hq * nseg * (2 * df * (d + 1)) * 4);
+  L->n_la = take((size_t)B * Hq * N * d * 4);
+  L->d_la = take((size_t)B * Hq * N * 4);
+  L->total = off;
+  L->n_pad = (int32_t)npad;
+  L->cap = (int32_t)cap;
+  L->nseg = (int32_t)nseg;
+  L->seg_chunks = (int32_t)G;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t still_version(void) { return 100; }
+
+const char* still_last_error(void) { return g_err; }
+
+still_status_t still_fwd_workspace_layout(const still_params_t* p, still_ws_layout_t* layout) {
+  if (layout == nullptr) return fail(STILL_ERR_INVALID_ARG, "layout is NULL");
+  still_status_t st = validate_params(p, true);
+  if (st != STILL_OK) return st;
+  compute_layout(p, layout);
+  return STILL_OK;
+}
+
+size_t still_fwd_workspace_bytes(const still_params_t* p) {
+  still_ws_layout_t L;
+  if (still_fwd_workspace_layout(p, &L) != STILL_OK) return 0;
+  return L.total;
+}
+
+still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, const void* k, const void* v,
+                                     const void* g, const void* Wq, const void* bq, const void* Wk,
+                                     const void* bk, void* out, float* score_out, int32_t* sel_idx,
+                                     int32_t sel_idx_is_input, void* state_out, void* workspace,
+                                     size_t workspace_bytes, void* stream_v) {
+  still_status_t st = validate_params(p, true);
+  if (st != STILL_OK) return st;
+  st = validate_strides(p, g != nullptr);
+  if (st != STILL_OK) return st;
+  if (!q || !k || !v || !Wq || !Wk || !out || !workspace)
+    return fail(STILL_ERR_INVALID_ARG, "a required pointer (q, k, v, Wq, Wk, out, workspace) is NULL");
+  const void* ptrs[] = {q, k, v, g, Wq, bq, Wk, bk, out, score_out, sel_idx, workspace};
+  for (const void* x : ptrs)
+    if (x != nullptr && !aligned16(x)) return fail(STILL_ERR_INVALID_ARG, "pointer %p is not 16-byte aligned", x);
+  if (sel_idx_is_input && sel_idx == nullptr && p->lambda > 0 && p->N >= p->C)
+    return fail(STILL_ERR_INVALID_ARG, "sel_idx_is_input set but sel_idx is NULL");
+  if (state_out != nullptr) return fail(STILL_ERR_UNSUPPORTED, "state_out is not available in this build");
+  still_ws_layout_t L;
+  compute_layout(p, &L);
+  if (workspace_bytes < L.total)
+    return fail(STILL_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  const int B = p->B, N = p->N, d = p->d, C = p->C;
+  const int nc = (N + C - 1) / C, ncf = N / C;
+  still::HeadMap map;
+  fill_map(p, &map);
+  float* score = reinterpret_cast<float*>(ws + L.score);
+  int32_t* sel = (sel_idx != nullptr) ? sel_idx : reinterpret_cast<int32_t*>(ws + L.sel);
+  const bool have_sel = p->lambda > 0 && ncf > 0;
+  hipError_t e;
+
+  // layout preparation
+  still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, N, L.n_pad, p->Hkv, d};
+  if ((e = still::launch_transpose_v(tv, p->dtype, B, stream)) != hipSuccess)
+    return fail(STILL_ERR_HIP, "transpose_v: %s", hipGetErrorString(e));
+  still::TransposeWArgs twq{Wq, ws + L.wqt, p->Hq, d, p->d_f};
+  still::TransposeWArgs twk{Wk, ws + L.wkt, p->Hq, d, p->d_f};
+  if ((e = still::launch_transpose_w(twq, p->dtype, stream)) != hipSuccess ||
+      (e = still::launch_transpose_w(twk, p->dtype, stream)) != hipSuccess)
+    return fail(STILL_ERR_HIP, "transpose_w: %s", hipGetErrorString(e));
+
+  // Self-Saliency Score + Top-lambda
+  still::ScoreArgs sa{};
+  sa.q = q; sa.k = k;
+  sa.q_sb = p->q_sb; sa.q_st = p->q_st; sa.q_sh = p->q_sh;
+  sa.k_sb = p->k_sb; sa.k_st = p->k_st; sa.k_sh = p->k_sh;
+  sa.map = map;
+  sa.N = N; sa.C = C; sa.W = p->W; sa.lam = p->lambda; sa.Hq = p->Hq; sa.ncf = ncf;
+  sa.scale = p->scale; sa.eps = p->eps;
+  sa.score = score;
+  sa.sel = (have_sel && !sel_idx_is_input) ? sel : nullptr;
+  const bool need_scores = !sel_idx_is_input || score_out != nullptr;
+  if (need_scores) {
+    if ((e = still::launch_score(sa, p->dtype, d, B, nc, stream)) != hipSuccess)
+      return fail(STILL_ERR_HIP, "score_select: %s", hipGetErrorString(e));
+    if (score_out != nullptr) {
+      e = hipMemcpyAsync(score_out, score, (size_t)B * p->Hq * N * sizeof(float), hipMemcpyDeviceToDevice, stream);
+      if (e != hipSuccess) return fail(STILL_ERR_HIP, "score copy: %s", hipGetErrorString(e));
+    }
+  }
+
+  // retained K/V of every full chunk
+  still::GatherArgs ga{};
+  ga.k = k; ga.v = v;
+  ga.k_sb = p->k_sb; ga.k_st = p->k_st; ga.k_sh = p->k_sh;
+  ga.v_sb = p->v_sb; ga.v_st = p->v_st; ga.v_sh = p->v_sh;
+  ga.map = map;
+  ga.sel = sel;
+  ga.nsel = have_sel ? ncf * p->lambda : 0;
+  ga.cap = L.cap; ga.Hq = p->Hq; ga.d = d; ga.N = N;
+  ga.kret = ws + L.kret; ga.vrett = ws + L.vrett;
+  if ((e = still::launch_gather(ga, p->dtype, B, stream)) != hipSuccess)
+    return fail(STILL_ERR_HIP, "gather: %s", hipGetErrorString(e));
+
+  // NP-Map + chunk linear attention
+  still::LaArgs la{};
+  la.q = q; la.k = k;
+  la.q_sb = p->q_sb; la.q_st = p->q_st; la.q_sh = p->q_sh;
+  la.k_sb = p->k_sb; la.k_st = p->k_st; la.k_sh = p->k_sh;
+  la.g = g; la.g_sb = p->g_sb; la.g_st = p->g_st; la.g_sh = p->g_sh;
+  la.vt = ws + L.vt; la.wqt = ws + L.wqt; la.wkt = ws + L.wkt; la.bq = bq; la.bk = bk;
+  la.sel = sel;
+  la.map = map;
+  la.N = N; la.Np = L.n_pad; la.C = C; la.lam = have_sel ? p->lambda : 0; la.Hq = p->Hq; la.Hkv = p->Hkv;
+  la.nc = nc; la.ncf = ncf;
+  la.seg_chunks = L.seg_chunks; la.nseg = L.nseg;
+  la.seg = reinterpret_cast<float*>(ws + L.seg);
+  la.n_la = reinterpret_cast<float*>(ws + L.n_la);
+  la.d_la = reinterpret_cast<float*>(ws + L.d_la);
+  la.s_final = nullptr;
+  if ((e = still::launch_la_state(la, p->dtype, d, B, stream)) != hipSuccess)
+    return fail(STILL_ERR_HIP, "la_state: %s", hipGetErrorString(e));
+  if ((e = still::launch_la_prefix(la, d, B, stream)) != hipSuccess)
+    return fail(STILL_ERR_HIP, "la_prefix: %s", hipGetErrorString(e));
+  if ((e = still::launch_la_out(la, p->dtype, d, B, stream)) != hipSuccess)
+    return fail(STILL_ERR_HIP, "la_out: %s", hipGetErrorString(e));
+
+  // sparse softmax branch + merge
+  still::SaArgs sx{};
+  sx.q = q; sx.k = k;
+  sx.q_sb = p->q_sb; sx.q_st = p->q_st; sx.q_sh = p->q_sh;
+  sx.k_sb = p->k_sb; sx.k_st = p->k_st; sx.k_sh = p->k_sh;
+  sx.vt = ws + L.vt; sx.kret = ws + L.kret; sx.vrett = ws + L.vrett;
+  sx.n_la = la.n_la; sx.d_la = la.d_la;
+  sx.out = out; sx.o_sb = p->o_sb; sx.o_st = p->o_st; sx.o_sh = p->o_sh;
+  sx.map = map;
+  sx.N = N; sx.Np = L.n_pad; sx.C = C; sx.lam = have_sel ? p->lambda : 0; sx.Hq = p->Hq; sx.Hkv = p->Hkv;
+  sx.cap = L.cap; sx.ntiles = (N + 127) / 128;
+  sx.scale = p->scale;
+  if ((e = still::launch_sa(sx, p->dtype, d, B, stream)) != hipSuccess)
+    return fail(STILL_ERR_HIP, "sparse_attention: %s", hipGetErrorString(e));
+  g_err[0] = 0;
+  return STILL_OK;
+}
+
+size_t still_state_bytes(const still_params_t* p, int32_t max_tokens) {
+  (void)max_tokens;
+  if (validate_params(p, false) != STILL_OK) return 0;
+  fail(STILL_ERR_UNSUPPORTED, "decode state is not available in this build");
+  return 0;
+}
+
+still_status_t still_state_init(const still_params_t* p, void* state, int32_t max_tokens, void* stream) {
+  (void)p; (void)state; (void)max_tokens; (void)stream;
+  return fail(STILL_ERR_UNSUPPORTED, "decode state is not available in this build");
+}
+
+still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* state, const void* q_t, const void* k_t,
+                                             const void* v_t, const void* g_t, const void* Wq, const void* bq,
+                                             const void* Wk, const void* bk, void* out_t, void* stream) {
+  (void)p; (void)state; (void)q_t; (void)k_t; (void)v_t; (void)g_t; (void)Wq; (void)bq; (void)Wk; (void)bk;
+  (void)out_t; (void)stream;
+  return fail(STILL_ERR_UNSUPPORTED, "decode step is not available in this build");
+}
+
+}  // extern "C"

@@ -1,0 +1,107 @@
+// Shared device helpers for the STILL hybrid-attention kernels (gfx950 only).
+//
+// Matrix work is expressed through the 32x32 MFMA instructions of CDNA4:
+//   bf16 : v_mfma_f32_32x32x16_bf16  (each lane supplies 8 consecutive k values of one row)
+//   fp32 : v_mfma_f32_32x32x2_f32    (each lane supplies 1 k value of one row)
+// Operand convention used everywhere (lane = 32*g + r, g in {0,1}, r in 0..31):
+//   A (32 x KK): lane holds row r,    k = KPL*g .. KPL*g+KPL-1   of the current k-step
+//   B (KK x 32): lane holds column r, same k values
+//   C (32 x 32): lane holds column r; accumulator register i is row 8*(i/4) + 4*g + (i%4)
+// A result in C layout can feed the next contraction directly as an operand: its register
+// dimension (rows) becomes the contracted index, its lane dimension stays free.  To make the
+// registers of one lane group hold CONSECUTIVE k positions, the producer assigns logical row
+// `kappa(m)` to MFMA row m; then accumulator register i of group g is position pos_of_reg(i, g).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace still {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxHq = 128;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct HeadMap {
+  int32_t kv[kMaxHq];
+};
+
+template <typename T>
+struct Mma;
+
+template <>
+struct Mma<bf16> {
+  typedef bf16x8 frag;
+  static constexpr int KK = 16;  // k per instruction
+  static constexpr int KPL = 8;  // k per lane
+  static __device__ __forceinline__ floatx16 mma(frag a, frag b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+  // logical row carried by MFMA row m (swap bits 2 and 3)
+  static __device__ __forceinline__ int kappa(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1); }
+  static __device__ __forceinline__ int kappa_inv(int p) { return kappa(p); }
+  // logical position (0..31) held by accumulator register i of lane group g
+  static __device__ __forceinline__ int pos_of_reg(int i, int g) { return 16 * (i >> 3) + 8 * g + (i & 7); }
+  static __device__ __forceinline__ frag load(const bf16* p) { return *reinterpret_cast<const frag*>(p); }
+  // operand fragment of k-step s (positions 16s .. 16s+15 of a 32-position tile) from C-layout registers
+  static __device__ __forceinline__ frag from_acc(const floatx16& c, int s /*0..1*/) {
+    frag f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = static_cast<bf16>(c[8 * s + e]);
+    return f;
+  }
+  static constexpr int STEPS_PER_TILE = 2;  // k-steps covering one 32-position tile
+};
+
+template <>
+struct Mma<float> {
+  typedef float frag;
+  static constexpr int KK = 2;
+  static constexpr int KPL = 1;
+  static __device__ __forceinline__ floatx16 mma(frag a, frag b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+  }
+  // m = 8a + 4g + r  ->  8a + 2r + g
+  static __device__ __forceinline__ int kappa(int m) { return (m & ~7) | ((m & 3) << 1) | ((m >> 2) & 1); }
+  // p = 8a + 2r + g  ->  8a + 4g + r
+  static __device__ __forceinline__ int kappa_inv(int p) { return (p & ~7) | ((p & 1) << 2) | ((p >> 1) & 3); }
+  static __device__ __forceinline__ int pos_of_reg(int i, int g) { return 2 * i + g; }
+  static __device__ __forceinline__ frag load(const float* p) { return *p; }
+  static __device__ __forceinline__ frag from_acc(const floatx16& c, int s /*0..15*/) { return c[s]; }
+  static constexpr int STEPS_PER_TILE = 16;
+};
+
+// natural C-layout row of accumulator register i for lane group g
+__device__ __forceinline__ int c_row(int i, int g) { return 8 * (i >> 2) + 4 * g + (i & 3); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
+// exchange with the other lane group (lane ^ 32)
+__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+
+template <typename T>
+__device__ __forceinline__ float to_f32(T x) { return static_cast<float>(x); }
+
+template <typename T>
+__device__ __forceinline__ T from_f32(float x) { return static_cast<T>(x); }
+
+__device__ __forceinline__ floatx16 zero16() {
+  floatx16 z;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) z[i] = 0.f;
+  return z;
+}
+
+// 16-byte global/LDS copy unit
+struct __attribute__((aligned(16))) Vec16 {
+  uint32_t w[4];
+};
+
+}  // namespace still

@@ -1,0 +1,89 @@
+// Kernel argument blocks and host-side launchers shared by the translation units of libstill.
+// Nothing here is part of the public ABI (include/still.h is).
+#pragma once
+#include "still_common.h"
+
+namespace still {
+
+struct ScoreArgs {
+  const void* q;
+  const void* k;
+  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
+  HeadMap map;
+  int N, C, W, lam, Hq, ncf;
+  float scale, eps;
+  float* score;   // [B, Hq, N]
+  int32_t* sel;   // [B, Hq, ncf, lam] or nullptr (no selection)
+};
+
+struct TransposeVArgs {
+  const void* v;
+  int64_t v_sb, v_st, v_sh;
+  void* vt;       // [B, Hkv, d, Np]
+  int N, Np, Hkv, d;
+};
+
+struct TransposeWArgs {
+  const void* w;  // [Hq, d, df]
+  void* wt;       // [Hq, df, d]
+  int Hq, d, df;
+};
+
+struct GatherArgs {
+  const void* k;
+  const void* v;
+  int64_t k_sb, k_st, k_sh, v_sb, v_st, v_sh;
+  HeadMap map;
+  const int32_t* sel;  // [B, Hq, nsel]
+  int nsel, cap, Hq, d, N;
+  void* kret;          // [B, Hq, cap, d]
+  void* vrett;         // [B, Hq, d, cap]
+};
+
+struct LaArgs {
+  const void* q;
+  const void* k;
+  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
+  const void* g;       // nullable
+  int64_t g_sb, g_st, g_sh;
+  const void* vt;      // [B, Hkv, d, Np]
+  const void* wqt;     // [Hq, df, d]
+  const void* wkt;
+  const void* bq;      // nullable [Hq, df]
+  const void* bk;
+  const int32_t* sel;  // [B, Hq, ncf, lam]
+  HeadMap map;
+  int N, Np, C, lam, Hq, Hkv, nc, ncf;
+  int seg_chunks, nseg;
+  float* seg;          // [B, Hq, nseg, DP*(D+1)]: S (DP x D) then z (DP)
+  float* n_la;         // [B, Hq, N, d]
+  float* d_la;         // [B, Hq, N]
+  float* s_final;      // nullable [B, Hq, DP*(D+1)]: state after chunk (last chunk - 2)
+};
+
+struct SaArgs {
+  const void* q;
+  const void* k;
+  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
+  const void* vt;      // [B, Hkv, d, Np]
+  const void* kret;    // [B, Hq, cap, d]
+  const void* vrett;   // [B, Hq, d, cap]
+  const float* n_la;   // [B, Hq, N, d]
+  const float* d_la;   // [B, Hq, N]
+  void* out;
+  int64_t o_sb, o_st, o_sh;
+  HeadMap map;
+  int N, Np, C, lam, Hq, Hkv, cap, ntiles;
+  float scale;
+};
+
+hipError_t launch_score(const ScoreArgs& a, int dtype, int d, int B, int nc, hipStream_t stream);
+hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStream_t stream);
+hipError_t launch_transpose_w(const TransposeWArgs& a, int dtype, hipStream_t stream);
+hipError_t launch_gather(const GatherArgs& a, int dtype, int B, hipStream_t stream);
+hipError_t launch_la_state(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
+hipError_t launch_la_prefix(const LaArgs& a, int d, int B, hipStream_t stream);
+hipError_t launch_la_out(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
+hipError_t launch_sa(const SaArgs& a, int dtype, int d, int B, hipStream_t stream);
+
+}  // namespace still

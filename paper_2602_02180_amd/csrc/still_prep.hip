@@ -1,0 +1,123 @@
+// Layout preparation: pure data movement, no arithmetic of the method.
+//
+//   transpose_v : v [B,N,Hkv,d] -> vt [B,Hkv,d,Np] (tokens contiguous, zero padded to Np), so that
+//                 the value operand of every "contract over tokens" MFMA is k-contiguous.
+//   transpose_w : NP-Map weights [Hq,d,df] -> [Hq,df,d] (feature rows, d contiguous).
+//   gather      : Index(k, M^SA), Index(v, M^SA) of Algorithm 1: the keys of the selected tokens of
+//                 every full chunk, flattened in chunk order, as rows of kret [B,Hq,cap,d]; the values
+//                 transposed into vrett [B,Hq,d,cap].  Rows beyond the selected count are zero.
+#include "still_kernels.h"
+
+namespace still {
+
+template <typename E>
+__global__ __launch_bounds__(256) void transpose_v_kernel(TransposeVArgs a) {
+  __shared__ E tile[64][65];
+  const E* __restrict__ v = static_cast<const E*>(a.v);
+  E* __restrict__ vt = static_cast<E*>(a.vt);
+  const int tok0 = blockIdx.x * 64;
+  const int nd = a.d / 64;
+  const int h = blockIdx.y / nd, d0 = (blockIdx.y % nd) * 64;
+  const int b = blockIdx.z;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int tok = tok0 + i;
+    E val = 0;
+    if (tok < a.N) val = v[(int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)h * a.v_sh + d0 + tx];
+    tile[i][tx] = val;
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    vt[(((int64_t)b * a.Hkv + h) * a.d + d0 + i) * a.Np + tok0 + tx] = tile[tx][i];
+  }
+}
+
+template <typename E>
+__global__ __launch_bounds__(256) void transpose_w_kernel(TransposeWArgs a) {
+  const E* __restrict__ w = static_cast<const E*>(a.w);
+  E* __restrict__ wt = static_cast<E*>(a.wt);
+  const int h = blockIdx.x;
+  const int n = a.d * a.df;
+  for (int idx = threadIdx.x; idx < n; idx += blockDim.x) {
+    const int f = idx / a.d, x = idx % a.d;
+    wt[(int64_t)h * n + idx] = w[(int64_t)h * n + (int64_t)x * a.df + f];
+  }
+}
+
+template <typename E, int D>
+__global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
+  __shared__ E tile[64][D + 2];
+  __shared__ int s_tok[64];
+  const E* __restrict__ k = static_cast<const E*>(a.k);
+  const E* __restrict__ v = static_cast<const E*>(a.v);
+  E* __restrict__ kret = static_cast<E*>(a.kret);
+  E* __restrict__ vrett = static_cast<E*>(a.vrett);
+  const int r0 = blockIdx.x * 64, hq = blockIdx.y, b = blockIdx.z;
+  const int kvh = a.map.kv[hq];
+  if (threadIdx.x < 64) {
+    const int row = r0 + threadIdx.x;
+    int tok = -1;
+    if (row < a.nsel) {
+      tok = a.sel[((int64_t)b * a.Hq + hq) * a.nsel + row];
+      if (tok < 0 || tok >= a.N) tok = -1;  // caller-supplied indices are never trusted for addressing
+    }
+    s_tok[threadIdx.x] = tok;
+  }
+  __syncthreads();
+  const int lane32 = threadIdx.x & 31, grp = threadIdx.x >> 5;  // 8 groups of 32 threads
+  for (int i = grp; i < 64; i += 8) {
+    const int tok = s_tok[i];
+    const int row = r0 + i;
+    for (int x = lane32; x < D; x += 32) {
+      E kv = 0, vv = 0;
+      if (tok >= 0) {
+        kv = k[(int64_t)b * a.k_sb + (int64_t)tok * a.k_st + (int64_t)kvh * a.k_sh + x];
+        vv = v[(int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)kvh * a.v_sh + x];
+      }
+      kret[(((int64_t)b * a.Hq + hq) * a.cap + row) * D + x] = kv;
+      tile[i][x] = vv;
+    }
+  }
+  __syncthreads();
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int x = ty; x < D; x += 4) {
+    vrett[(((int64_t)b * a.Hq + hq) * D + x) * a.cap + r0 + tx] = tile[tx][x];
+  }
+}
+
+hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStream_t stream) {
+  dim3 grid(a.Np / 64, a.Hkv * (a.d / 64), B), block(256);
+  if (dtype == 1)
+    hipLaunchKernelGGL(transpose_v_kernel<uint16_t>, grid, block, 0, stream, a);
+  else
+    hipLaunchKernelGGL(transpose_v_kernel<uint32_t>, grid, block, 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_w(const TransposeWArgs& a, int dtype, hipStream_t stream) {
+  dim3 grid(a.Hq), block(256);
+  if (dtype == 1)
+    hipLaunchKernelGGL(transpose_w_kernel<uint16_t>, grid, block, 0, stream, a);
+  else
+    hipLaunchKernelGGL(transpose_w_kernel<uint32_t>, grid, block, 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather(const GatherArgs& a, int dtype, int B, hipStream_t stream) {
+  if (a.cap == 0) return hipSuccess;
+  dim3 grid(a.cap / 64, a.Hq, B), block(256);
+  if (dtype == 1) {
+    if (a.d == 64)
+      hipLaunchKernelGGL((gather_kernel<uint16_t, 64>), grid, block, 0, stream, a);
+    else
+      hipLaunchKernelGGL((gather_kernel<uint16_t, 128>), grid, block, 0, stream, a);
+  } else {
+    if (a.d == 64)
+      hipLaunchKernelGGL((gather_kernel<uint32_t, 64>), grid, block, 0, stream, a);
+    else
+      hipLaunchKernelGGL((gather_kernel<uint32_t, 128>), grid, block, 0, stream, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace still

@@ -1,0 +1,96 @@
+"""Helpers shared by the GPU parity tests: run the HIP path through the C ABI, run the oracle on
+the same dtype-rounded inputs, compare."""
+from __future__ import annotations
+
+import ctypes
+from typing import Dict, Iterable, Optional, Tuple
+
+import numpy as np
+
+from oracle import still_oracle as O
+from paper_2602_02180_amd import binding as S
+from paper_2602_02180_amd import synth
+
+
+def run_hip(w: synth.Workload, inp: Dict[str, np.ndarray], sel_in: Optional[np.ndarray] = None,
+            kv_map: Optional[np.ndarray] = None, want_terms: bool = True) -> Dict[str, np.ndarray]:
+    """One still_hybrid_attn_fwd call; returns out, score, sel and (from the workspace) N_LA, D_LA."""
+    import torch
+
+    dev = "cuda"
+    q = synth.to_torch(inp["q"], w.dtype, dev)
+    k = synth.to_torch(inp["k"], w.dtype, dev)
+    v = synth.to_torch(inp["v"], w.dtype, dev)
+    Wq = synth.to_torch(inp["Wq"], w.dtype, dev)
+    Wk = synth.to_torch(inp["Wk"], w.dtype, dev)
+    g = synth.to_torch(inp["g"], w.dtype, dev) if inp.get("g") is not None else None
+    bq = synth.to_torch(inp["bq"], w.dtype, dev) if inp.get("bq") is not None else None
+    bk = synth.to_torch(inp["bk"], w.dtype, dev) if inp.get("bk") is not None else None
+    B, N = q.shape[0], q.shape[1]
+    out = torch.full_like(q, float("nan"))
+    p = S.make_params(B=B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, g=g, kv_head_of_q=kv_map)
+    ncf = N // w.C
+    score = torch.full((B, w.Hq, N), float("nan"), dtype=torch.float32, device=dev)
+    sel = torch.full((B, w.Hq, max(ncf, 1), max(w.lam, 1)), -1, dtype=torch.int32, device=dev)
+    if sel_in is not None:
+        sel = torch.from_numpy(np.ascontiguousarray(sel_in, dtype=np.int32)).to(dev)
+    ws_bytes = S.still_fwd_workspace_bytes(p)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    S.still_hybrid_attn_fwd(p, q, k, v, g, Wq, bq, Wk, bk, out, score_out=score, sel_idx=sel,
+                            sel_idx_is_input=sel_in is not None, workspace=ws)
+    torch.cuda.synchronize()
+    res = {"out": synth.from_torch(out), "score": score.cpu().numpy(),
+           "sel": sel.cpu().numpy()[:, :, :ncf, :w.lam].astype(np.int64)}
+    if want_terms:
+        L = S.still_fwd_workspace_layout(p)
+        n_la = ws[L.n_la:L.n_la + B * w.Hq * N * w.d * 4].view(torch.float32).reshape(B, w.Hq, N, w.d)
+        d_la = ws[L.d_la:L.d_la + B * w.Hq * N * 4].view(torch.float32).reshape(B, w.Hq, N)
+        res["N_LA"] = n_la.cpu().numpy()
+        res["D_LA"] = d_la.cpu().numpy()
+        res["layout"] = L
+    return res
+
+
+def oracle_units(w: synth.Workload, inp, units: Iterable[Tuple[int, int]], sel: Optional[np.ndarray] = None,
+                 kv_map: Optional[np.ndarray] = None, rows=None, N: Optional[int] = None):
+    kv_map = synth.kv_head_map(w) if kv_map is None else kv_map
+    return O.still_forward_units(inp, kv_map, list(units), C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                                 form="chunkwise", sel=sel, rows=rows)
+
+
+def selection_report(score_ref: np.ndarray, sel_ref: np.ndarray, sel_hip: np.ndarray, C: int, lam: int,
+                     gap_tol: float = 1e-5):
+    """Chunks whose oracle gap (lam-th vs (lam+1)-th score) exceeds gap_tol must match exactly.
+    Returns (n_chunks, n_clear, n_clear_mismatch, n_tie_mismatch)."""
+    gaps = O.selection_gaps(score_ref, C, lam)
+    n = sel_ref.shape[0]
+    clear = gaps > gap_tol
+    mism = np.array([not np.array_equal(sel_ref[c], sel_hip[c]) for c in range(n)])
+    return n, int(clear.sum()), int((mism & clear).sum()), int((mism & ~clear).sum())
+
+
+def selection_is_valid(score_ref: np.ndarray, sel_hip: np.ndarray, C: int, tol: float) -> bool:
+    """Every kept token scores at least (every dropped token's score - tol); indices ascending, in chunk."""
+    for c in range(sel_hip.shape[0]):
+        idx = sel_hip[c]
+        if idx.size == 0:
+            continue
+        if np.any(np.diff(idx) <= 0) or idx[0] < c * C or idx[-1] >= (c + 1) * C:
+            return False
+        s = score_ref[c * C:(c + 1) * C]
+        keep = np.zeros(C, bool)
+        keep[idx - c * C] = True
+        if (~keep).any() and s[keep].min() < s[~keep].max() - tol:
+            return False
+    return True
+
+
+def rel_err(x: np.ndarray, ref: np.ndarray) -> float:
+    return float(np.max(np.abs(x - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def row_rel_err(x: np.ndarray, ref: np.ndarray) -> float:
+    num = np.linalg.norm(x - ref, axis=-1)
+    den = np.maximum(np.linalg.norm(ref, axis=-1), 1e-30)
+    return float(np.max(num / den))

@@ -1,0 +1,89 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol that
+include/still.h declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_02180_amd import binding as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "still.h")).read()
+    return sorted(set(re.findall(r"STILL_API\s+[\w\s\*]+?\b(still_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert {"still_hybrid_attn_fwd", "still_hybrid_attn_decode_step", "still_fwd_workspace_bytes",
+            "still_state_bytes", "still_state_init", "still_last_error", "still_version"} <= set(names)
+    lib = S.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert S.still_version() >= 100
+
+
+def params(**kw):
+    base = dict(B=1, N=1024, Hq=4, Hkv=2, d=64, C=64, W=64, lam=16, scale=0.125, eps=1e-6, dtype="bf16")
+    base.update(kw)
+    return S.make_params(**base)
+
+
+def test_workspace_layout_is_consistent():
+    p = params()
+    L = S.still_fwd_workspace_layout(p)
+    assert S.still_fwd_workspace_bytes(p) == L.total
+    offs = [L.score, L.sel, L.vt, L.kret, L.vrett, L.wqt, L.wkt, L.seg, L.n_la, L.d_la, L.total]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    assert L.n_pad % 128 == 0 and L.n_pad >= 1024
+    assert L.cap % 64 == 0 and L.cap >= (1024 // 64) * 16
+    assert L.nseg * L.seg_chunks >= 16
+    assert L.n_la - L.seg >= 1 * 4 * L.nseg * (2 * 64 * 65) * 4
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(d=96), S.STILL_ERR_UNSUPPORTED),
+    (dict(C=32), S.STILL_ERR_UNSUPPORTED),
+    (dict(W=129), S.STILL_ERR_UNSUPPORTED),
+    (dict(d_f=32), S.STILL_ERR_UNSUPPORTED),
+    (dict(dtype="f32", d=128, C=128), S.STILL_ERR_UNSUPPORTED),
+    (dict(lam=65), S.STILL_ERR_INVALID_ARG),
+    (dict(lam=-1), S.STILL_ERR_INVALID_ARG),
+    (dict(N=0), S.STILL_ERR_INVALID_ARG),
+    (dict(Hq=5), S.STILL_ERR_INVALID_ARG),
+    (dict(eps=0.0), S.STILL_ERR_INVALID_ARG),
+    (dict(kv_head_of_q=[0, 1, 2, 0]), S.STILL_ERR_INVALID_ARG),
+])
+def test_bad_params_are_rejected_on_the_host(kw, code):
+    p = params(**kw)
+    with pytest.raises(S.StillError) as e:
+        S.still_fwd_workspace_layout(p)
+    assert e.value.code == code
+    assert S.still_last_error() != ""
+
+
+def test_fwd_rejects_null_and_misaligned_pointers_without_launching():
+    p = params()
+    lib = S.lib()
+    null = ctypes.c_void_p(None)
+    rc = lib.still_hybrid_attn_fwd(ctypes.byref(p), null, null, null, null, null, null, null, null, null, null,
+                                   null, 0, null, null, 0, null)
+    assert rc == S.STILL_ERR_INVALID_ARG
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    p.q_st = p.k_st = p.v_st = p.o_st = 64
+    rc = lib.still_hybrid_attn_fwd(ctypes.byref(p), odd, fake, fake, null, fake, null, fake, null, fake, null,
+                                   null, 0, null, fake, 1 << 40, null)
+    assert rc == S.STILL_ERR_INVALID_ARG and "aligned" in S.still_last_error()
+    p.q_st = 63   # not a multiple of 16 bytes
+    rc = lib.still_hybrid_attn_fwd(ctypes.byref(p), fake, fake, fake, null, fake, null, fake, null, fake, null,
+                                   null, 0, null, fake, 1 << 40, null)
+    assert rc == S.STILL_ERR_INVALID_ARG
+    p = params()
+    p.q_st = p.k_st = p.v_st = p.o_st = 64
+    rc = lib.still_hybrid_attn_fwd(ctypes.byref(p), fake, fake, fake, null, fake, null, fake, null, fake, null,
+                                   null, 0, null, fake, 16, null)
+    assert rc == S.STILL_ERR_WORKSPACE_TOO_SMALL
