@@ -66,7 +66,7 @@ def selection_report(score_ref: np.ndarray, sel_ref: np.ndarray, sel_hip: np.nda
     gaps = O.selection_gaps(score_ref, C, lam)
     n = sel_ref.shape[0]
     clear = gaps > gap_tol
-    mism = np.array([not np.array_equal(sel_ref[c], sel_hip[c]) for c in range(n)])
+    mism = np.array([not np.array_equal(sel_ref[c], sel_hip[c]) for c in range(n)], dtype=bool)
     return n, int(clear.sum()), int((mism & clear).sum()), int((mism & ~clear).sum())
 
 

@@ -4,7 +4,10 @@ dtype-rounded inputs.
 Bars (from the benchmark spec):
   * selected-index sets bit-exact wherever the oracle's gap between the lambda-th and the
     (lambda+1)-th score exceeds 1e-5; the mismatch rate among near-ties is printed;
-  * outputs within 1e-4 relative on fp32 (max-normalised and per row), 2e-2 absolute on bf16.
+  * outputs within 1e-4 relative on fp32 (max-normalised and per row); on bf16 within 2e-2 absolute
+    plus one bf16 ulp (2^-8 relative) of the reference value: the synthetic values reach |y| ~ 20,
+    where merely storing the exact result in bf16 already moves it by up to 2^-9 * 20 = 0.04, so a
+    purely absolute 2e-2 cannot hold for any bf16 output; the plain max-abs error is printed too.
 Output parity is run twice: with the oracle's indices injected into the HIP path (isolates the
 gather / linear / softmax / merge kernels) and end to end, where the oracle is re-run with the
 HIP path's own indices after those were checked to be a valid Top-lambda set.
@@ -19,6 +22,7 @@ pytestmark = pytest.mark.gpu
 
 F32_REL = 1e-4
 BF16_ABS = 2e-2
+BF16_ULP = 2.0 ** -8
 
 
 def small(name, **kw):
@@ -32,7 +36,7 @@ def all_units(w):
 
 
 def check_outputs(w, hip, ref_units, units, what):
-    worst_rel = worst_row = worst_abs = 0.0
+    worst_rel = worst_row = worst_abs = worst_excess = 0.0
     for (b, h) in units:
         ref = ref_units[(b, h)]
         r0, r1 = ref["rows"]
@@ -42,11 +46,13 @@ def check_outputs(w, hip, ref_units, units, what):
         worst_rel = max(worst_rel, U.rel_err(x, y))
         worst_row = max(worst_row, U.row_rel_err(x, y))
         worst_abs = max(worst_abs, float(np.max(np.abs(x - y))))
-    print(f"[{w.name}:{what}] out: max-rel {worst_rel:.3e} row-rel {worst_row:.3e} max-abs {worst_abs:.3e}")
+        worst_excess = max(worst_excess, float(np.max(np.abs(x - y) / (BF16_ABS + BF16_ULP * np.abs(y)))))
+    print(f"[{w.name}:{what}] out: max-rel {worst_rel:.3e} row-rel {worst_row:.3e} max-abs {worst_abs:.3e} "
+          f"bf16-bar-fraction {worst_excess:.3f}")
     if w.dtype == "f32":
         assert worst_rel <= F32_REL and worst_row <= F32_REL, (worst_rel, worst_row)
     else:
-        assert worst_abs <= BF16_ABS, worst_abs
+        assert worst_excess <= 1.0, (worst_abs, worst_excess)
 
 
 def check_terms(w, hip, ref_units, units, what):
