@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the STILL hybrid-attention prefill hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c4] [--no-cpu-baseline]
+
+One step = one still_hybrid_attn_fwd call (score + selection + gather + NP-Map linear attention +
+sparse softmax + merge) over one batch of seeded synthetic input that is already resident in HBM.
+Prints ONE JSON line: whole-job tokens/s, the roofline record of the dominant kernel (the sparse
+softmax + merge kernel, timed with HIP events inside the timed steps on the stream it runs on), and
+the float64 oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2602_02180_amd import synth  # noqa: E402
+
+PEAK_MFMA = {"bf16": 2.5e15, "f32": 157.3e12}   # dense MFMA peaks of MI355X, flop/s
+PEAK_HBM = 8.0e12
+
+
+def sparse_branch_flops(w: synth.Workload, N: int) -> float:
+    """Algorithmic flops of the sparse softmax branch for one launch: every query row does
+    4*d flops (q.k and p.v, 2 per MAC) per visible key: retained keys of chunks <= c-2 plus the
+    local span (previous chunk and own chunk up to the row)."""
+    t = np.arange(N, dtype=np.int64)
+    c = t // w.C
+    n_ret = np.maximum(0, c - 1) * w.lam
+    n_loc = t - np.maximum(0, c - 1) * w.C + 1
+    return float(4 * w.d * np.sum(n_ret + n_loc)) * w.B * w.Hq
+
+
+def path_flops(w: synth.Workload, N: int) -> float:
+    """Useful flops of the whole path per step (score band, both NP-Maps, state update, linear
+    output, sparse branch)."""
+    d, df = w.d, w.df
+    nc = N // w.C
+    per_head = (2 * d * min(w.W, N) * N            # score logits
+                + 2 * (2 * d * df) * N             # NP-Map of q and k
+                + 2 * (2 * df) * d * (w.C - w.lam) * max(0, nc - 2)   # state update, routed chunks
+                + 2 * (2 * df) * d * N)            # phi_q S
+    return per_head * w.B * w.Hq + sparse_branch_flops(w, N)
+
+
+def compulsory_bytes(w: synth.Workload, N: int) -> float:
+    es = 2 if w.dtype == "bf16" else 4
+    return float(w.B * N * w.d * es * (2 * w.Hq + 2 * w.Hkv))
+
+
+def cpu_baseline(w: synth.Workload, inp, budget_s: float = 20.0):
+    """The oracle as it stands, on whole (batch, head) units of the same inputs, until ~budget_s."""
+    from oracle import still_oracle as O
+
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:  # pragma: no cover
+        cores = os.cpu_count() or 1
+    kv_map = synth.kv_head_map(w)
+    units_done, t0 = 0, time.perf_counter()
+    order = [(b, h) for h in range(w.Hq) for b in range(w.B)]
+    for (b, h) in order:
+        O.still_forward_units(inp, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps)
+        units_done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    el = time.perf_counter() - t0
+    N = inp["q"].shape[1]
+    # one unit = N tokens of one of B*Hq heads; the layer needs all B*Hq units for its B*N tokens
+    tok_s = (units_done * N / el) / w.Hq
+    return {"value": tok_s, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{units_done} of {w.B * w.Hq} (batch, head) units of the same inputs, all {N} rows each, "
+                      f"numpy float64 chunk-wise form, {el:.1f} s; scaled by 1/Hq to whole-layer tokens/s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU only (the path shards over heads/batch with no exchange; "
+              "see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2602_02180_amd import binding as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    S.lib()  # fail loudly if the HIP library is missing
+
+    w = synth.CONFIGS[args.config]
+    inp = synth.make_inputs(w)
+    dev = "cuda"
+    q, k, v = (synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v"))
+    Wq, Wk = synth.to_torch(inp["Wq"], w.dtype, dev), synth.to_torch(inp["Wk"], w.dtype, dev)
+    out = torch.empty_like(q)
+    N = w.N
+    p = S.make_params(B=w.B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        S.still_hybrid_attn_fwd(p, q, k, v, None, Wq, None, Wk, None, out, workspace=ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    S.still_profile_enable(True)
+    per_kernel = {}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+        # reading the events waits for this step only; it is part of the timed region
+        for name, ms in S.still_profile_read().items():
+            per_kernel[name] = per_kernel.get(name, 0.0) + ms
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    S.still_profile_enable(False)
+
+    ms_step = el / args.steps * 1e3
+    tok_s = w.B * N * args.steps / el
+    per_kernel = {n: t / args.steps for n, t in per_kernel.items()}
+    dom = "sparse_attn_merge"
+    dom_s = per_kernel[dom] * 1e-3
+    flops = sparse_branch_flops(w, N)
+    peak = PEAK_MFMA[w.dtype]
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": flops / dom_s / 1e12, "peak": peak / 1e12,
+                "unit": "TFLOP/s", "frac": flops / dom_s / peak, "traffic": args.traffic_bytes,
+                "algorithmic_flops_per_launch": flops, "avg_launch_ms": per_kernel[dom]}
+    rec = {
+        "metric": "hybrid-attn fwd tokens/s @32K, Llama-3-8B layer shape" if args.config == "c4"
+        else f"hybrid-attn fwd tokens/s ({args.config})",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} N={N} Hq={w.Hq} Hkv={w.Hkv} d={w.d} C={w.C} W={w.W} "
+                               f"lambda={w.lam} heavy_frac={w.heavy_frac}",
+                   "path_gflop_per_step": path_flops(w, N) / 1e9,
+                   "compulsory_hbm_mb_per_step": compulsory_bytes(w, N) / 1e6,
+                   "path_frac_of_mfma_peak": path_flops(w, N) / (ms_step * 1e-3) / peak,
+                   "kernel_ms": per_kernel},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(w, inp)
+    print(json.dumps(rec))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -128,6 +128,19 @@ STILL_API still_status_t still_hybrid_attn_fwd(const still_params_t* p,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Optional per-kernel timing of still_hybrid_attn_fwd (used by the benchmark to time the dominant kernel
+ * on the stream it is launched on).  While enabled on the calling thread, every prefill call records HIP
+ * events (host objects created lazily, one set per thread) around each of its kernels.
+ * still_profile_read waits for the last recorded call to finish and writes the duration in milliseconds
+ * of up to n kernels into the HOST array ms, in launch order; still_profile_kernel_name(i) names slot i
+ * (NULL past the last).  Returns STILL_ERR_STATE if no call was recorded.
+ */
+#define STILL_PROFILE_SLOTS 8
+STILL_API void still_profile_enable(int32_t on);
+STILL_API still_status_t still_profile_read(float* ms, int32_t n);
+STILL_API const char* still_profile_kernel_name(int32_t i);
+
+/*
  * Decode state of B sequences (the salient cache h and the state (s, z) of the cache-routing
  * equation, plus the local ring that delayed selection needs).  One opaque caller-owned buffer:
  *   header | pos[B] | n_routed[B] | S[B,Hq,2*d_f,d] f32 | z[B,Hq,2*d_f] f32 |

@@ -71,6 +71,12 @@ def lib() -> ct.CDLL:
         L.still_state_init.argtypes = [pp, vp, ct.c_int32, vp]
         L.still_hybrid_attn_decode_step.restype = ct.c_int
         L.still_hybrid_attn_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.still_profile_enable.restype = None
+        L.still_profile_enable.argtypes = [ct.c_int32]
+        L.still_profile_read.restype = ct.c_int
+        L.still_profile_read.argtypes = [ct.POINTER(ct.c_float), ct.c_int32]
+        L.still_profile_kernel_name.restype = ct.c_char_p
+        L.still_profile_kernel_name.argtypes = [ct.c_int32]
         _lib = L
     return _lib
 
@@ -174,3 +180,22 @@ def still_hybrid_attn_decode_step(p: StillParams, state, q_t, k_t, v_t, g_t, Wq,
     _check(lib().still_hybrid_attn_decode_step(ct.byref(p), _ptr(state), _ptr(q_t), _ptr(k_t), _ptr(v_t),
                                                _ptr(g_t), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(out_t),
                                                stream.cuda_stream))
+
+
+STILL_PROFILE_SLOTS = 8
+
+
+def still_profile_enable(on: bool) -> None:
+    lib().still_profile_enable(1 if on else 0)
+
+
+def still_profile_read():
+    """Milliseconds per kernel of the last profiled prefill call on this thread: {name: ms}."""
+    arr = (ct.c_float * STILL_PROFILE_SLOTS)()
+    _check(lib().still_profile_read(arr, STILL_PROFILE_SLOTS))
+    return {still_profile_kernel_name(i): float(arr[i]) for i in range(STILL_PROFILE_SLOTS)}
+
+
+def still_profile_kernel_name(i: int):
+    s = lib().still_profile_kernel_name(i)
+    return None if s is None else s.decode()

@@ -20,6 +20,26 @@ still_status_t fail(still_status_t code, const char* fmt, ...) {
   return code;
 }
 
+// per-thread kernel timing (host-side event objects only)
+struct Profile {
+  bool on = false, created = false, recorded = false;
+  hipEvent_t ev[STILL_PROFILE_SLOTS + 1];
+};
+thread_local Profile g_prof;
+const char* const kSlotNames[STILL_PROFILE_SLOTS] = {"transpose_v", "transpose_w", "score_select", "gather",
+                                                     "la_state",    "la_prefix",   "la_out",       "sparse_attn_merge"};
+
+void prof_mark(int slot, hipStream_t stream) {
+  if (!g_prof.on) return;
+  if (!g_prof.created) {
+    for (auto& e : g_prof.ev)
+      if (hipEventCreate(&e) != hipSuccess) { g_prof.on = false; return; }
+    g_prof.created = true;
+  }
+  (void)hipEventRecord(g_prof.ev[slot], stream);
+  if (slot == STILL_PROFILE_SLOTS) g_prof.recorded = true;
+}
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline size_t esize(int dtype) { return dtype == STILL_BF16 ? 2 : 4; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -160,16 +180,19 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   const bool have_sel = p->lambda > 0 && ncf > 0;
   hipError_t e;
 
+  prof_mark(0, stream);
   // layout preparation
   still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, N, L.n_pad, p->Hkv, d};
   if ((e = still::launch_transpose_v(tv, p->dtype, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "transpose_v: %s", hipGetErrorString(e));
+  prof_mark(1, stream);
   still::TransposeWArgs twq{Wq, ws + L.wqt, p->Hq, d, p->d_f};
   still::TransposeWArgs twk{Wk, ws + L.wkt, p->Hq, d, p->d_f};
   if ((e = still::launch_transpose_w(twq, p->dtype, stream)) != hipSuccess ||
       (e = still::launch_transpose_w(twk, p->dtype, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "transpose_w: %s", hipGetErrorString(e));
 
+  prof_mark(2, stream);
   // Self-Saliency Score + Top-lambda
   still::ScoreArgs sa{};
   sa.q = q; sa.k = k;
@@ -190,6 +213,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
     }
   }
 
+  prof_mark(3, stream);
   // retained K/V of every full chunk
   still::GatherArgs ga{};
   ga.k = k; ga.v = v;
@@ -219,13 +243,17 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   la.n_la = reinterpret_cast<float*>(ws + L.n_la);
   la.d_la = reinterpret_cast<float*>(ws + L.d_la);
   la.s_final = nullptr;
+  prof_mark(4, stream);
   if ((e = still::launch_la_state(la, p->dtype, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "la_state: %s", hipGetErrorString(e));
+  prof_mark(5, stream);
   if ((e = still::launch_la_prefix(la, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "la_prefix: %s", hipGetErrorString(e));
+  prof_mark(6, stream);
   if ((e = still::launch_la_out(la, p->dtype, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "la_out: %s", hipGetErrorString(e));
 
+  prof_mark(7, stream);
   // sparse softmax branch + merge
   still::SaArgs sx{};
   sx.q = q; sx.k = k;
@@ -240,8 +268,32 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   sx.scale = p->scale;
   if ((e = still::launch_sa(sx, p->dtype, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "sparse_attention: %s", hipGetErrorString(e));
+  prof_mark(STILL_PROFILE_SLOTS, stream);
   g_err[0] = 0;
   return STILL_OK;
+}
+
+void still_profile_enable(int32_t on) {
+  g_prof.on = on != 0;
+  if (!g_prof.on) g_prof.recorded = false;
+}
+
+still_status_t still_profile_read(float* ms, int32_t n) {
+  if (ms == nullptr || n < 0) return fail(STILL_ERR_INVALID_ARG, "ms is NULL or n < 0");
+  if (!g_prof.recorded) return fail(STILL_ERR_STATE, "no profiled call recorded on this thread");
+  if (hipEventSynchronize(g_prof.ev[STILL_PROFILE_SLOTS]) != hipSuccess)
+    return fail(STILL_ERR_HIP, "event synchronize failed");
+  for (int i = 0; i < n && i < STILL_PROFILE_SLOTS; ++i) {
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, g_prof.ev[i], g_prof.ev[i + 1]) != hipSuccess)
+      return fail(STILL_ERR_HIP, "event elapsed failed for slot %d", i);
+    ms[i] = t;
+  }
+  return STILL_OK;
+}
+
+const char* still_profile_kernel_name(int32_t i) {
+  return (i >= 0 && i < STILL_PROFILE_SLOTS) ? kSlotNames[i] : nullptr;
 }
 
 size_t still_state_bytes(const still_params_t* p, int32_t max_tokens) {
