@@ -56,7 +56,7 @@ typedef enum { STILL_F32 = 0, STILL_BF16 = 1 } still_dtype_t;
 typedef struct still_params {
   int32_t B, N, Hq, Hkv, d, d_f; /* d_f: width of the NP-Map layer f(x) = x W + b; phi has 2*d_f features */
   int32_t C, W, lambda;          /* chunk size, score window (keys, token itself included), kept per chunk */
-  float scale;                   /* multiplies every q.k logit, score window and softmax branch alike      */
+  float scale;                   /* > 0; multiplies every q.k logit, score window and softmax branch alike */
   float eps;                     /* eps of the score equation                                              */
   int32_t dtype;                 /* still_dtype_t of q, k, v, g, out, Wq, Wk, bq, bk                        */
   int64_t q_sb, q_st, q_sh;      /* q   [B, N, Hq,  d]                                                     */

@@ -52,7 +52,7 @@ still_status_t validate_params(const still_params_t* p, bool need_n) {
   if (p->lambda < 0 || p->lambda > p->C) return fail(STILL_ERR_INVALID_ARG, "lambda %d outside [0, C=%d]", p->lambda, p->C);
   if (p->W < 1) return fail(STILL_ERR_INVALID_ARG, "W must be >= 1");
   if (!(p->eps > 0.f)) return fail(STILL_ERR_INVALID_ARG, "eps must be > 0");
-  if (!(p->scale == p->scale)) return fail(STILL_ERR_INVALID_ARG, "scale is NaN");
+  if (!(p->scale > 0.f)) return fail(STILL_ERR_INVALID_ARG, "scale must be > 0");
   if (p->Hq > still::kMaxHq) return fail(STILL_ERR_UNSUPPORTED, "Hq %d > %d", p->Hq, still::kMaxHq);
   if (p->kv_head_of_q == nullptr) {
     if (p->Hq % p->Hkv != 0) return fail(STILL_ERR_INVALID_ARG, "Hq %% Hkv != 0 and no kv_head_of_q map given");
@@ -264,7 +264,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   sx.out = out; sx.o_sb = p->o_sb; sx.o_st = p->o_st; sx.o_sh = p->o_sh;
   sx.map = map;
   sx.N = N; sx.Np = L.n_pad; sx.C = C; sx.lam = have_sel ? p->lambda : 0; sx.Hq = p->Hq; sx.Hkv = p->Hkv;
-  sx.cap = L.cap; sx.ntiles = (N + 127) / 128;
+  sx.cap = L.cap; sx.ntiles = (N + 127) / 128; sx.B_ = B;
   sx.scale = p->scale;
   if ((e = still::launch_sa(sx, p->dtype, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "sparse_attention: %s", hipGetErrorString(e));

@@ -73,7 +73,7 @@ struct SaArgs {
   void* out;
   int64_t o_sb, o_st, o_sh;
   HeadMap map;
-  int N, Np, C, lam, Hq, Hkv, cap, ntiles;
+  int N, Np, C, lam, Hq, Hkv, cap, ntiles, B_;
   float scale;
 };
 

@@ -13,13 +13,17 @@
 // Everything is computed transposed so that one lane owns one query row:
 //   S^T (keys x queries)  = K_tile (A operand, from LDS)  x  Q^T (B operand, registers)
 //   O^T (d    x queries) += V^T_tile (A operand, from LDS) x  P^T (B operand = S^T accumulators, in place)
-// Row statistics are then plain per-lane reductions plus one exchange with lane^32.
-// K tiles (64 keys x d) and V^T tiles (d x 64 keys) are staged through LDS once per workgroup; the next
-// tile's global loads are issued before the current tile's MFMAs.  Retained keys come from the compacted
+// Row statistics are then per-lane reductions plus one exchange with lane^32 per tile.
+// K tiles (64 keys x d) and V^T tiles (d x 64 keys) are double-buffered in LDS: one barrier per tile, the
+// global loads of tile i+2 are in flight while tile i+1 is computed.  Retained keys come from the compacted
 // per-head buffers, local keys from k and from the token-contiguous transposed copy of v.
+// Workgroups of one (batch, head) are placed on one XCD (block ids are dealt round-robin to the 8 XCDs), so
+// the head's retained K/V (2 MB at 32K tokens) is served from that XCD's L2; long rows are scheduled first.
 #include "still_kernels.h"
 
 namespace still {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename T, int D>
 struct SaCfg {
@@ -29,28 +33,112 @@ struct SaCfg {
   static constexpr int KST = D + PAD;    // K tile row stride (elements)
   static constexpr int VST = BN + PAD;   // V^T tile row stride
   static constexpr int EPV = 16 / sizeof(T);                 // elements per 16-byte vector
-  static constexpr int KVEC = BN * D / EPV;                  // vectors in a K tile
-  static constexpr int KPT = KVEC / 256;                     // per thread
-  static constexpr int VVEC = D * BN / EPV;
-  static constexpr int VPT = VVEC / 256;
-  static constexpr size_t smem_bytes = sizeof(T) * (BN * KST + D * VST);
+  static constexpr int KPT = BN * D / EPV / 256;             // 16-byte vectors per thread, K tile
+  static constexpr int VPT = D * BN / EPV / 256;             // same, V^T tile
+  static constexpr int BUF_ELEMS = BN * KST + D * VST;
+  static constexpr size_t smem_bytes = 2 * sizeof(T) * BUF_ELEMS;
 };
 
-template <typename T, int D>
-__global__ __launch_bounds__(256) void sa_kernel(SaArgs a) {
+// MASK: 0 = every key of the tile is visible to every row of the wave, 1 = retained tile with a ragged end,
+//       2 = local tile (window start and causal limit)
+template <typename T, int D, int MASK>
+__device__ __forceinline__ void sa_tile(const T* __restrict__ Ks, const T* __restrict__ Vs,
+                                        const typename Mma<T>::frag (&qf)[D / Mma<T>::KK], floatx16 (&o)[D / 32],
+                                        float& m2, float& lpart, int kb, int ret_w, int lo_w, int t, float sc2,
+                                        int r, int g) {
   typedef Mma<T> M;
   typedef SaCfg<T, D> Cf;
   constexpr int KS = D / M::KK;
   constexpr int DT = D / 32;
   constexpr int SPT = M::STEPS_PER_TILE;
+
+  floatx16 st[2];
+  st[0] = zero16();
+  st[1] = zero16();
+  const T* krow = Ks + r * Cf::KST + g * M::KPL;
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    st[0] = M::mma(M::load(krow + s * M::KK), qf[s], st[0]);
+    st[1] = M::mma(M::load(krow + 32 * Cf::KST + s * M::KK), qf[s], st[1]);
+  }
+  if (MASK != 0) {
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = kb + 32 * mt + M::pos_of_reg(i, g);
+        const bool valid = MASK == 1 ? (key < ret_w) : (key >= lo_w && key <= t);
+        st[mt][i] = valid ? st[mt][i] : -INFINITY;
+      }
+  }
+  float tmax = st[0][0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, st[0][i]);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, st[1][i]);
+  tmax = fmaxf(tmax, xor32(tmax));
+  const float m_new = fmaxf(m2, tmax * sc2);
+  const float m_sub = (MASK != 0 && m_new == -INFINITY) ? 0.f : m_new;
+  if (__any(m_new > m2)) {  // wave-uniform: skip the rescale once the running maxima have settled
+    const float alpha = fast_exp2(m2 - m_sub);
+    lpart *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;
+  }
+  m2 = m_new;
+  float rs = 0.f;
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float pv = fast_exp2(fmaf(st[mt][i], sc2, -m_sub));
+      st[mt][i] = pv;
+      rs += pv;
+    }
+  lpart += rs;
+  // O^T += V^T P^T
+  const T* vrow = Vs + r * Cf::VST + g * M::KPL;
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int s = 0; s < SPT; ++s) {
+      const typename M::frag pf = M::from_acc(st[mt], s);
+      const int koff = 32 * mt + s * M::KK;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) o[dt] = M::mma(M::load(vrow + 32 * dt * Cf::VST + koff), pf, o[dt]);
+    }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256, 2) void sa_kernel(SaArgs a) {
+  typedef Mma<T> M;
+  typedef SaCfg<T, D> Cf;
+  constexpr int KS = D / M::KK;
+  constexpr int DT = D / 32;
   constexpr int BN = Cf::BN;
+  constexpr int VR = D / Cf::EPV;   // 16-byte vectors per K row
+  constexpr int VV = BN / Cf::EPV;  // 16-byte vectors per V^T row
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  T* Ks = reinterpret_cast<T*>(smem);
-  T* Vs = Ks + BN * Cf::KST;
+  T* lds = reinterpret_cast<T*>(smem);
 
-  const int tile = a.ntiles - 1 - (int)blockIdx.x;  // long rows first
-  const int hq = blockIdx.y, b = blockIdx.z;
+  // block id -> (unit = batch*Hq + head, row tile); units are dealt to XCDs, long tiles first
+  int unit, tile;
+  {
+    const int L = blockIdx.x;
+    const int units = a.Hq * a.B_;
+    if (units % 8 == 0) {
+      const int xcd = L & 7, j = L >> 3;
+      unit = (j / a.ntiles) * 8 + xcd;
+      tile = a.ntiles - 1 - (j % a.ntiles);
+    } else {
+      unit = L / a.ntiles;
+      tile = a.ntiles - 1 - (L % a.ntiles);
+    }
+  }
+  const int b = unit / a.Hq, hq = unit % a.Hq;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
   const int N = a.N, C = a.C, lam = a.lam;
@@ -68,14 +156,56 @@ __global__ __launch_bounds__(256) void sa_kernel(SaArgs a) {
   const int c_last = last_row / C;
   const int ret_max = (c_last >= 1 ? c_last - 1 : 0) * lam;
   const int loc_lo = (c_first >= 1 ? c_first - 1 : 0) * C;
-  const int loc_hi = last_row + 1;
   const int n_ret_tiles = (ret_max + BN - 1) / BN;
-  const int n_tiles = n_ret_tiles + (loc_hi - loc_lo + BN - 1) / BN;
+  const int n_tiles = n_ret_tiles + (last_row + 1 - loc_lo + BN - 1) / BN;
 
   const T* __restrict__ kloc = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)kvh * a.k_sh;
   const T* __restrict__ vtl = static_cast<const T*>(a.vt) + ((int64_t)b * a.Hkv + kvh) * (int64_t)D * a.Np;
   const T* __restrict__ kret = static_cast<const T*>(a.kret) + ((int64_t)b * a.Hq + hq) * (int64_t)a.cap * D;
   const T* __restrict__ vrett = static_cast<const T*>(a.vrett) + ((int64_t)b * a.Hq + hq) * (int64_t)D * a.cap;
+
+  // per-thread slots of the cooperative tile copy
+  const int kp = tid / VR, kvec = tid % VR;           // K: row kp (+ 256/VR per step), vector kvec
+  const int vx = tid / VV, vvec = tid % VV;           // V^T: row vx (+ 256/VV per step), vector vvec
+  constexpr int KROWS_PER_STEP = 256 / VR;
+  constexpr int VROWS_PER_STEP = 256 / VV;
+
+  u32x4 kreg[Cf::KPT], vreg[Cf::VPT];
+
+#define SA_GLOAD(TI)                                                                                       \
+  {                                                                                                        \
+    const int ti_ = (TI);                                                                                  \
+    const bool ret_ = ti_ < n_ret_tiles;                                                                   \
+    const int kb_ = ret_ ? ti_ * BN : loc_lo + (ti_ - n_ret_tiles) * BN;                                   \
+    _Pragma("unroll") for (int j = 0; j < Cf::KPT; ++j) {                                                  \
+      const int p_ = kp + j * KROWS_PER_STEP;                                                              \
+      int tok_ = kb_ + p_;                                                                                 \
+      tok_ = tok_ < N ? tok_ : N - 1;                                                                      \
+      const T* src_ = ret_ ? kret + (int64_t)(kb_ + p_) * D : kloc + (int64_t)tok_ * a.k_st;               \
+      kreg[j] = *reinterpret_cast<const u32x4*>(src_ + kvec * Cf::EPV);                                    \
+    }                                                                                                      \
+    const T* vsrc_ = ret_ ? vrett : vtl;                                                                   \
+    const int64_t vstride_ = ret_ ? a.cap : a.Np;                                                          \
+    _Pragma("unroll") for (int j = 0; j < Cf::VPT; ++j) {                                                  \
+      const int x_ = vx + j * VROWS_PER_STEP;                                                              \
+      vreg[j] = *reinterpret_cast<const u32x4*>(vsrc_ + (int64_t)x_ * vstride_ + kb_ + vvec * Cf::EPV);    \
+    }                                                                                                      \
+  }
+
+#define SA_LSTORE(BUF)                                                                                     \
+  {                                                                                                        \
+    T* Ks_ = lds + (BUF) * Cf::BUF_ELEMS;                                                                  \
+    T* Vs_ = Ks_ + BN * Cf::KST;                                                                           \
+    _Pragma("unroll") for (int j = 0; j < Cf::KPT; ++j) {                                                  \
+      const int p_ = kp + j * KROWS_PER_STEP;                                                              \
+      const int row_ = (p_ & ~31) + M::kappa_inv(p_ & 31);                                                 \
+      *reinterpret_cast<u32x4*>(Ks_ + row_ * Cf::KST + kvec * Cf::EPV) = kreg[j];                          \
+    }                                                                                                      \
+    _Pragma("unroll") for (int j = 0; j < Cf::VPT; ++j) {                                                  \
+      const int x_ = vx + j * VROWS_PER_STEP;                                                              \
+      *reinterpret_cast<u32x4*>(Vs_ + x_ * Cf::VST + vvec * Cf::EPV) = vreg[j];                            \
+    }                                                                                                      \
+  }
 
   // queries of this wave (B operand of S^T = K Q^T)
   typename M::frag qf[KS];
@@ -90,140 +220,42 @@ __global__ __launch_bounds__(256) void sa_kernel(SaArgs a) {
   floatx16 o[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) o[dt] = zero16();
-  float m2 = -INFINITY, l = 0.f;
+  float m2 = -INFINITY, lpart = 0.f;
   const float sc2 = a.scale * kLog2e;
 
-  Vec16 kreg[Cf::KPT], vreg[Cf::VPT];
+  SA_GLOAD(0);
+  SA_LSTORE(0);
+  __syncthreads();
+  if (n_tiles > 1) SA_GLOAD(1);
 
-  auto gload = [&](int ti) {
-    const bool ret = ti < n_ret_tiles;
-    const int kb = ret ? ti * BN : loc_lo + (ti - n_ret_tiles) * BN;
-    constexpr int VR = D / Cf::EPV;  // vectors per K row
-#pragma unroll
-    for (int j = 0; j < Cf::KPT; ++j) {
-      const int idx = tid + 256 * j;
-      const int p = idx / VR, vec = idx % VR;
-      const T* src;
-      if (ret) {
-        src = kret + (int64_t)(kb + p) * D;
-      } else {
-        int tok = kb + p;
-        tok = tok < N ? tok : N - 1;
-        src = kloc + (int64_t)tok * a.k_st;
-      }
-      kreg[j] = *reinterpret_cast<const Vec16*>(src + vec * Cf::EPV);
-    }
-    constexpr int VV = BN / Cf::EPV;  // vectors per V^T row
-    const T* vsrc = ret ? vrett : vtl;
-    const int64_t vstride = ret ? a.cap : a.Np;
-#pragma unroll
-    for (int j = 0; j < Cf::VPT; ++j) {
-      const int idx = tid + 256 * j;
-      const int x = idx / VV, vec = idx % VV;
-      vreg[j] = *reinterpret_cast<const Vec16*>(vsrc + (int64_t)x * vstride + kb + vec * Cf::EPV);
-    }
-  };
-
-  auto lstore = [&]() {
-    constexpr int VR = D / Cf::EPV;
-#pragma unroll
-    for (int j = 0; j < Cf::KPT; ++j) {
-      const int idx = tid + 256 * j;
-      const int p = idx / VR, vec = idx % VR;
-      const int row = (p & ~31) + M::kappa_inv(p & 31);
-      *reinterpret_cast<Vec16*>(Ks + row * Cf::KST + vec * Cf::EPV) = kreg[j];
-    }
-    constexpr int VV = BN / Cf::EPV;
-#pragma unroll
-    for (int j = 0; j < Cf::VPT; ++j) {
-      const int idx = tid + 256 * j;
-      const int x = idx / VV, vec = idx % VV;
-      *reinterpret_cast<Vec16*>(Vs + x * Cf::VST + vec * Cf::EPV) = vreg[j];
-    }
-  };
-
-  if (n_tiles > 0) gload(0);
   for (int ti = 0; ti < n_tiles; ++ti) {
-    __syncthreads();
-    lstore();
-    __syncthreads();
-    if (ti + 1 < n_tiles) gload(ti + 1);
-
     const bool ret = ti < n_ret_tiles;
     const int kb = ret ? ti * BN : loc_lo + (ti - n_ret_tiles) * BN;
-    bool relevant, need_mask;
-    if (ret) {
-      relevant = kb < ret_w;
-      need_mask = kb + BN > ret_w;
-    } else {
-      relevant = (kb + BN - 1 >= lo_w) && (kb <= q0 + 31);
-      need_mask = (kb < lo_w) || (kb + BN - 1 > q0);
-    }
-    if (!wave_active || !relevant) continue;
-
-    floatx16 st[2];
-    st[0] = zero16();
-    st[1] = zero16();
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        const typename M::frag af = M::load(Ks + (32 * mt + r) * Cf::KST + s * M::KK + g * M::KPL);
-        st[mt] = M::mma(af, qf[s], st[mt]);
+    const T* Ks = lds + (ti & 1) * Cf::BUF_ELEMS;
+    const T* Vs = Ks + BN * Cf::KST;
+    if (wave_active) {
+      if (ret) {
+        if (kb + BN <= ret_w)
+          sa_tile<T, D, 0>(Ks, Vs, qf, o, m2, lpart, kb, ret_w, lo_w, t, sc2, r, g);
+        else if (kb < ret_w)
+          sa_tile<T, D, 1>(Ks, Vs, qf, o, m2, lpart, kb, ret_w, lo_w, t, sc2, r, g);
+      } else if (kb + BN - 1 >= lo_w && kb <= q0 + 31) {
+        if (kb >= lo_w && kb + BN - 1 <= q0)
+          sa_tile<T, D, 0>(Ks, Vs, qf, o, m2, lpart, kb, ret_w, lo_w, t, sc2, r, g);
+        else
+          sa_tile<T, D, 2>(Ks, Vs, qf, o, m2, lpart, kb, ret_w, lo_w, t, sc2, r, g);
       }
     }
-    // logits in the log2 domain, masked
-    float tmax = -INFINITY;
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float x = st[mt][i] * sc2;
-        if (need_mask) {
-          const int key = kb + 32 * mt + M::pos_of_reg(i, g);
-          const bool valid = ret ? (key < ret_w) : (key >= lo_w && key <= t);
-          x = valid ? x : -INFINITY;
-        }
-        st[mt][i] = x;
-        tmax = fmaxf(tmax, x);
-      }
-    tmax = fmaxf(tmax, xor32(tmax));
-    const float m_new = fmaxf(m2, tmax);
-    const float m_sub = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = fast_exp2(m2 - m_sub);
-    float rs = 0.f;
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pv = fast_exp2(st[mt][i] - m_sub);
-        st[mt][i] = pv;
-        rs += pv;
-      }
-    rs += xor32(rs);
-    l = l * alpha + rs;
-    m2 = m_new;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;
-    // O^T += V^T P^T
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int s = 0; s < SPT; ++s) {
-        const typename M::frag pf = M::from_acc(st[mt], s);
-        const int koff = 32 * mt + s * M::KK + g * M::KPL;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const typename M::frag vf = M::load(Vs + (32 * dt + r) * Cf::VST + koff);
-          o[dt] = M::mma(vf, pf, o[dt]);
-        }
-      }
+    if (ti + 1 < n_tiles) SA_LSTORE((ti + 1) & 1);
+    __syncthreads();
+    if (ti + 2 < n_tiles) SA_GLOAD(ti + 2);
   }
+#undef SA_GLOAD
+#undef SA_LSTORE
 
   // ---- merge epilogue
   if (wave_active && t < N) {
+    const float l = lpart + xor32(lpart);
     float fs, fl;
     if (m2 >= 0.f) {
       fs = 1.f;
@@ -268,7 +300,7 @@ static hipError_t launch_sa_t(const SaArgs& a, int B, hipStream_t stream) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cf::smem_bytes);
   if (e != hipSuccess) return e;
-  dim3 grid(a.ntiles, a.Hq, B), block(256);
+  dim3 grid((unsigned)(a.ntiles * a.Hq * B)), block(256);
   hipLaunchKernelGGL(kern, grid, block, Cf::smem_bytes, stream, a);
   return hipGetLastError();
 }
