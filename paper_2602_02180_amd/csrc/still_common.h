@@ -99,6 +99,30 @@ __device__ __forceinline__ floatx16 zero16() {
   return z;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
+// load and store of the wave (vmcnt(0)), which would expose the latency of prefetches and of result
+// stores at each pipeline step; the kernels that use this barrier exchange data between waves through
+// LDS only, and never read global memory written by another wave of the same launch.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Block id -> (query head, work item) with the head varying fastest, so that workgroups running at the same
+// time read the SAME token range of q/k/v for different heads: in the [B, N, H, d] layout one token's rows of
+// all heads are contiguous, and a DRAM page fetched for one head is used by the others while it is open.
+// Block ids are dealt round-robin to the 8 XCDs; XCD x is given the heads [x*Hq/8, (x+1)*Hq/8), i.e. whole
+// GQA groups when Hq/Hkv divides Hq/8, so a kv-head's rows are shared through that XCD's L2.
+__device__ __forceinline__ void head_major_block(int L, int Hq, int& hq, int& item) {
+  if ((Hq & 7) == 0) {
+    const int hpx = Hq >> 3, xcd = L & 7, slot = L >> 3;
+    hq = xcd * hpx + slot % hpx;
+    item = slot / hpx;
+  } else {
+    hq = L % Hq;
+    item = L / Hq;
+  }
+}
+
 // 16-byte global/LDS copy unit
 struct __attribute__((aligned(16))) Vec16 {
   uint32_t w[4];

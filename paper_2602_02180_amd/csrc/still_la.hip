@@ -15,11 +15,18 @@
 // Segment s of the state pass covers chunks [s*G-1, (s+1)*G-1), so the exclusive prefix handed to the
 // output pass of segment s is exactly the state through chunk s*G-2.
 //
-// Register/LDS plan per workgroup (NW = d/32 waves): the fp32 state S (2*d_f x d) lives in MFMA accumulators,
-// wave w owning value columns [32w, 32w+32) for all features.  phi_k is staged in LDS as [feature][token]
-// (A operand of S += phi_k^T V), phi_q as [token][feature] (A operand of N = phi_q S); S itself is the B
-// operand of the output product straight from its accumulator registers (converted to the input dtype).
-// V comes from the token-contiguous transposed copy.  z is kept in LDS in fp32.
+// Workgroup plan: the waves are specialised.
+//   consumer waves (d/32): wave w keeps the fp32 state columns [32w, 32w+32) of S (2*d_f x d) in MFMA
+//     accumulators for the whole scan and does the two token-contracting products from LDS operands:
+//     S += phi_k^T V (phi_k staged as [feature][token], V from the token-contiguous transposed copy) and
+//     N = phi_q S (phi_q staged as [token][feature]; S is the B operand straight from its accumulator
+//     registers, converted to the input dtype).  z is kept in LDS in fp32; D_LA = phi_q z is a short
+//     dot product per row.
+//   producer waves (C/32): wave v computes the feature map of 32 tokens of the NEXT unit (x W on MFMA, the
+//     norm re-injection and the two softmaxes on the vector ALU, which is what bounds this kernel) and
+//     writes it into the other LDS slot.
+// Units alternate "queries of chunk c" / "keys of chunk c-1" so that the outputs of chunk c see the state
+// through chunk c-2; one barrier per unit hands a slot from producers to consumers.
 #include "still_kernels.h"
 
 namespace still {
@@ -29,21 +36,21 @@ struct LaPad {
   static constexpr int value = 16 / sizeof(T);
 };
 
-// Feature map of 32 tokens (one per lane column).  On return pp[ft][i] / pn[ft][i] hold phi's first/second
-// half at feature 32*ft + pos_of_reg(i, g) for the token of this lane.
+// Feature map of 32 tokens (one per lane column) from their preloaded rows xf (B operand fragments).
+// On return pp[ft][i] / pn[ft][i] hold phi's first / second half, multiplied by `keep`, at feature
+// 32*ft + pos_of_reg(i, g) for the token of this lane.  The W^T fragments of the next feature tile are
+// requested before the current tile's MFMAs so that only the first request's latency is exposed.
 template <typename T, int D, int DF>
-__device__ __forceinline__ void np_map_tile(const T* __restrict__ xp /* row + g*KPL */,
+__device__ __forceinline__ void np_map_tile(const typename Mma<T>::frag (&xf)[D / Mma<T>::KK],
                                             const T* __restrict__ wt_head /* [DF][D] */,
-                                            const T* __restrict__ bias /* [DF] or null */, int r, int g,
-                                            floatx16 (&pp)[DF / 32], floatx16 (&pn)[DF / 32]) {
+                                            const T* __restrict__ bias /* [DF] or null */, float keep, int r,
+                                            int g, floatx16 (&pp)[DF / 32], floatx16 (&pn)[DF / 32]) {
   typedef Mma<T> M;
   constexpr int KS = D / M::KK;
   constexpr int FT = DF / 32;
-  typename M::frag xf[KS];
   float nx2 = 0.f;
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
-    xf[s] = M::load(xp + s * M::KK);
     if constexpr (M::KPL == 1) {
       nx2 += xf[s] * xf[s];
     } else {
@@ -55,43 +62,48 @@ __device__ __forceinline__ void np_map_tile(const T* __restrict__ xp /* row + g*
     }
   }
   nx2 += xor32(nx2);
-  float nf2 = 0.f;
+  typename M::frag w[2][KS];
+  const T* wrow = wt_head + (int64_t)M::kappa(r) * D + g * M::KPL;
+#pragma unroll
+  for (int s = 0; s < KS; ++s) w[0][s] = M::load(wrow + s * M::KK);
+  float nf2 = 0.f, fmax = -INFINITY, fmin = INFINITY;
 #pragma unroll
   for (int ft = 0; ft < FT; ++ft) {
-    floatx16 acc = zero16();
-    const T* wrow = wt_head + (int64_t)(32 * ft + M::kappa(r)) * D + g * M::KPL;
+    if (ft + 1 < FT) {
 #pragma unroll
-    for (int s = 0; s < KS; ++s) acc = M::mma(M::load(wrow + s * M::KK), xf[s], acc);
+      for (int s = 0; s < KS; ++s) w[(ft + 1) & 1][s] = M::load(wrow + (int64_t)(32 * (ft + 1)) * D + s * M::KK);
+    }
+    floatx16 acc = zero16();
+#pragma unroll
+    for (int s = 0; s < KS; ++s) acc = M::mma(w[ft & 1][s], xf[s], acc);
     if (bias != nullptr) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[i] += to_f32(bias[32 * ft + M::pos_of_reg(i, g)]);
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) nf2 += acc[i] * acc[i];
+    for (int i = 0; i < 16; ++i) {
+      nf2 = fmaf(acc[i], acc[i], nf2);
+      fmax = fmaxf(fmax, acc[i]);
+      fmin = fminf(fmin, acc[i]);
+    }
     pp[ft] = acc;
   }
   nf2 += xor32(nf2);
+  fmax = fmaxf(fmax, xor32(fmax));
+  fmin = fminf(fmin, xor32(fmin));
+  // u = f * ratio with ratio = ||x|| / ||f|| >= 0, so max/min of u are ratio * max/min of f;
+  // exp(u - umax) = exp2(f * a1 - fmax * a1),  exp(umin - u) = exp2(fmin * a1 - f * a1)
   const float ratio = nf2 > 0.f ? sqrtf(nx2 / nf2) : 0.f;
-  float umax = -INFINITY, umin = INFINITY;
-#pragma unroll
-  for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float u = pp[ft][i] * ratio;
-      pp[ft][i] = u;
-      umax = fmaxf(umax, u);
-      umin = fminf(umin, u);
-    }
-  umax = fmaxf(umax, xor32(umax));
-  umin = fminf(umin, xor32(umin));
+  const float a1 = ratio * kLog2e;
+  const float bp = -fmax * a1, bn = fmin * a1;
   float sp = 0.f, sn = 0.f;
 #pragma unroll
   for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const float u = pp[ft][i];
-      const float ep = fast_exp2((u - umax) * kLog2e);
-      const float en = fast_exp2((umin - u) * kLog2e);
+      const float f = pp[ft][i];
+      const float ep = fast_exp2(fmaf(f, a1, bp));
+      const float en = fast_exp2(fmaf(f, -a1, bn));
       pp[ft][i] = ep;
       pn[ft][i] = en;
       sp += ep;
@@ -99,7 +111,7 @@ __device__ __forceinline__ void np_map_tile(const T* __restrict__ xp /* row + g*
     }
   sp += xor32(sp);
   sn += xor32(sn);
-  const float ip = 1.0f / sp, in = 1.0f / sn;
+  const float ip = keep / sp, in = keep / sn;
 #pragma unroll
   for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
@@ -141,31 +153,42 @@ struct LaSmem {
   static constexpr int QSTRIDE = DP + PAD;  // phiq row stride
   static constexpr size_t phik_bytes = sizeof(T) * DP * KSTRIDE;
   static constexpr size_t phiq_bytes = sizeof(T) * C * QSTRIDE;
+  static constexpr size_t slot_bytes(int mode) {
+    return (mode && phiq_bytes > phik_bytes) ? phiq_bytes : phik_bytes;
+  }
   static constexpr size_t z_bytes = sizeof(float) * DP;
-  static constexpr size_t keep_bytes = 128;
-  static constexpr size_t total(int mode) { return phik_bytes + (mode ? phiq_bytes : 0) + z_bytes + keep_bytes; }
+  static constexpr size_t total(int mode) { return 2 * slot_bytes(mode) + z_bytes; }
+};
+
+// One work unit of the scan: either the queries of chunk `chunk` (kind 0) or the keys of chunk `chunk`
+// that are folded into the state (kind 1).  `valid` false = an empty pipeline slot.
+struct LaUnit {
+  int kind, chunk;
+  bool valid;
 };
 
 template <typename T, int D, int DF, int C, int MODE>
-__global__ __launch_bounds__((D / 32) * 64) void la_kernel(LaArgs a) {
+__global__ __launch_bounds__((D / 32 + C / 32) * 64) void la_kernel(LaArgs a) {
   typedef Mma<T> M;
   typedef LaSmem<T, D, DF, C> L;
   constexpr int DP = 2 * DF;
-  constexpr int NW = D / 32;
+  constexpr int NM = D / 32;     // consumer (MFMA) waves: wave w owns value columns [32w, 32w+32)
+  constexpr int NV = C / 32;     // producer (feature-map) waves: wave NM+v owns tokens [32v, 32v+32) of a unit
   constexpr int FT = DF / 32;    // feature tiles per half
   constexpr int PT = DP / 32;    // feature tiles of the state
   constexpr int CT = C / 32;     // token tiles per chunk
   constexpr int SPT = M::STEPS_PER_TILE;
+  constexpr size_t SLOT = L::slot_bytes(MODE);
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  T* phik = reinterpret_cast<T*>(smem);
-  T* phiq = reinterpret_cast<T*>(smem + L::phik_bytes);
-  float* zsh = reinterpret_cast<float*>(smem + L::phik_bytes + (MODE ? L::phiq_bytes : 0));
-  unsigned char* keep = reinterpret_cast<unsigned char*>(zsh) + L::z_bytes;
+  float* zsh = reinterpret_cast<float*>(smem + 2 * SLOT);
 
-  const int seg = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+  int seg, hq;
+  head_major_block(blockIdx.x, a.Hq, hq, seg);
+  const int b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 31, g = lane >> 5;
+  const bool consumer = wave < NM;
   const int kvh = a.map.kv[hq];
   const int N = a.N;
   const int G = a.seg_chunks;
@@ -178,117 +201,177 @@ __global__ __launch_bounds__((D / 32) * 64) void la_kernel(LaArgs a) {
   const T* __restrict__ bq = a.bq ? static_cast<const T*>(a.bq) + (int64_t)hq * DF : nullptr;
   const T* __restrict__ bk = a.bk ? static_cast<const T*>(a.bk) + (int64_t)hq * DF : nullptr;
   float* __restrict__ segp = a.seg + (((int64_t)b * a.Hq + hq) * a.nseg + seg) * (int64_t)(DP * (D + 1));
-  const int col = 32 * wave + r;  // value column owned by this lane
+  const int col = 32 * wave + r;  // value column owned by this lane (consumer waves)
 
-  // ---- state in accumulators
+  // chunk range and pipeline slots of this workgroup
+  const int c_beg = seg * G;
+  const int c_end = MODE == 1 ? (c_beg + G < a.nc ? c_beg + G : a.nc) : c_beg + G;
+  // Unit list.  Output pass: Q(c_beg), then for every later chunk c of the segment K(c-2), Q(c): the
+  // outputs of chunk c see the state through chunk c-2.  State pass: K(c_beg-1) .. K(c_beg+G-2).
+  // A K unit whose chunk does not exist (before the sequence start, or not a full chunk) is produced as
+  // zeros, so the consumer code is straight-line.
+  const int n_units = MODE == 1 ? 2 * (c_end - c_beg) - 1 : G;
+  auto unit_at = [&](int u) {
+    LaUnit x;
+    if (MODE == 1) {
+      const int j = (u + 1) >> 1;
+      if ((u & 1) == 0) {
+        x.kind = 0; x.chunk = c_beg + j; x.valid = true;
+      } else {
+        x.kind = 1; x.chunk = c_beg + j - 2; x.valid = x.chunk >= 0;
+      }
+    } else {
+      x.kind = 1; x.chunk = c_beg + u - 1; x.valid = x.chunk >= 0 && x.chunk < a.ncf;
+    }
+    return x;
+  };
+
+  // ---- producer waves: feature map of 32 tokens of every unit, one unit ahead of the consumers.
+  // The token rows of the following unit are requested before the current unit's arithmetic.
+  // Producer and consumer waves run separate loops with the same number of barriers (the barrier counts
+  // waves, and a wave never diverges inside itself here), so the state registers are live only in the
+  // consumer path and the feature-map temporaries only in the producer path.
+  if (!consumer) {
+    constexpr int KS = D / M::KK;
+    const int tt = wave - NM;
+    auto row_ptr = [&](const LaUnit& x) -> const T* {
+      int tok = x.chunk * C + 32 * tt + r;
+      tok = tok < N ? tok : N - 1;
+      tok = tok < 0 ? 0 : tok;
+      return (x.kind == 0 ? qbase + (int64_t)tok * a.q_st : kbase + (int64_t)tok * a.k_st) + g * M::KPL;
+    };
+    typename M::frag xnext[KS];
+    {
+      const T* xp = row_ptr(unit_at(0));
+#pragma unroll
+      for (int s = 0; s < KS; ++s) xnext[s] = M::load(xp + s * M::KK);
+    }
+    for (int u = 0; u < n_units; ++u) {
+      const LaUnit x = unit_at(u);
+      typename M::frag xf[KS];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) xf[s] = xnext[s];
+      if (u + 1 < n_units) {
+        const T* xp = row_ptr(unit_at(u + 1));
+#pragma unroll
+        for (int s = 0; s < KS; ++s) xnext[s] = M::load(xp + s * M::KK);
+      }
+      unsigned char* slot = smem + (u & 1) * SLOT;
+      if (!x.valid) {
+        T* kcol = reinterpret_cast<T*>(slot) + 32 * tt + r;   // absent chunk: contributes nothing
+        for (int f = g; f < DP; f += 2) kcol[f * L::KSTRIDE] = from_f32<T>(0.f);
+      } else {
+        floatx16 pp[FT], pn[FT];
+        if (x.kind == 0) {
+          np_map_tile<T, D, DF>(xf, wqt, bq, 1.f, r, g, pp, pn);
+          T* qrow = reinterpret_cast<T*>(slot) + (32 * tt + r) * L::QSTRIDE;
+#pragma unroll
+          for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+            for (int s = 0; s < SPT; ++s) {
+              const int p0 = 32 * ft + s * M::KK + g * M::KPL;
+              *reinterpret_cast<typename M::frag*>(qrow + p0) = M::from_acc(pp[ft], s);
+              *reinterpret_cast<typename M::frag*>(qrow + DF + p0) = M::from_acc(pn[ft], s);
+            }
+        } else {
+          const int tl = 32 * tt + r;                 // token inside the (full) chunk
+          const int tok = x.chunk * C + tl;
+          float kf = 1.f;                             // 0 for tokens kept by the softmax branch
+          const int32_t* selc = a.sel + (((int64_t)b * a.Hq + hq) * a.ncf + x.chunk) * a.lam;
+          for (int j = 0; j < a.lam; ++j) kf = (selc[j] == tok) ? 0.f : kf;
+          np_map_tile<T, D, DF>(xf, wkt, bk, kf, r, g, pp, pn);
+          T* kcol = reinterpret_cast<T*>(slot) + tl;
+#pragma unroll
+          for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int f = 32 * ft + M::pos_of_reg(i, g);
+              kcol[f * L::KSTRIDE] = from_f32<T>(pp[ft][i]);
+              kcol[(DF + f) * L::KSTRIDE] = from_f32<T>(pn[ft][i]);
+            }
+        }
+      }
+      lds_barrier();
+    }
+    lds_barrier();
+    return;
+  }
+
+  // ---- consumer waves: S in accumulators, z in LDS
   floatx16 S[PT];
   if (MODE == 1) {
 #pragma unroll
     for (int ft = 0; ft < PT; ++ft)
 #pragma unroll
       for (int i = 0; i < 16; ++i) S[ft][i] = segp[(int64_t)(32 * ft + M::pos_of_reg(i, g)) * D + col];
-    for (int f = threadIdx.x; f < DP; f += NW * 64) zsh[f] = segp[DP * D + f];
+    for (int f = threadIdx.x; f < DP; f += NM * 64) zsh[f] = segp[DP * D + f];
   } else {
 #pragma unroll
     for (int ft = 0; ft < PT; ++ft) S[ft] = zero16();
-    for (int f = threadIdx.x; f < DP; f += NW * 64) zsh[f] = 0.f;
-  }
-  __syncthreads();
-
-  // chunk range of this workgroup
-  int c_beg, c_end;
-  if (MODE == 1) {
-    c_beg = seg * G;
-    c_end = c_beg + G < a.nc ? c_beg + G : a.nc;
-  } else {
-    c_beg = seg * G;       // iteration c absorbs chunk c-1, like the output pass does
-    c_end = c_beg + G;     // (so segment s sums chunks [sG-1, (s+1)G-1))
+    for (int f = threadIdx.x; f < DP; f += NM * 64) zsh[f] = 0.f;
   }
 
-  for (int c = c_beg; c < c_end; ++c) {
-    const int cu = c - 1;                                  // chunk absorbed into the state this iteration
-    // state pass: every full chunk of the segment; output pass: only while a later chunk of this
-    // segment still needs the state (the next segment starts from its own prefix)
-    const bool update = MODE == 0 ? (cu >= 0 && cu < a.ncf) : (cu >= 0 && c + 1 < c_end);
-    // keep flags of chunk cu: 1 = token goes to the linear state
-    if (update) {
-      for (int i = threadIdx.x; i < C; i += NW * 64) keep[i] = 1;
-      __syncthreads();
-      if (a.lam > 0) {
-        for (int j = threadIdx.x; j < a.lam; j += NW * 64) {
-          const int tok = a.sel[(((int64_t)b * a.Hq + hq) * a.ncf + cu) * a.lam + j] - cu * C;
-          if (tok >= 0 && tok < C) keep[tok] = 0;
-        }
-      }
-      __syncthreads();
-    }
+  typename M::frag vf[C / M::KK];   // V fragments of the next K unit (B operand, k = tokens)
+  auto load_v = [&](int u) {
+    const LaUnit x = unit_at(u);
+    const int ch = x.valid ? x.chunk : 0;   // an absent chunk meets zero features; any finite V will do
+    const T* vrow = vt + (int64_t)col * a.Np + (int64_t)ch * C + g * M::KPL;
+#pragma unroll
+    for (int s = 0; s < C / M::KK; ++s) vf[s] = M::load(vrow + s * M::KK);
+  };
 
-    // ---- phase A: feature maps
-    constexpr int NTASK = (MODE == 1 ? 2 : 1) * CT;
-    for (int task = wave; task < NTASK; task += NW) {
-      const bool is_q = MODE == 1 && task < CT;
-      const int tt = is_q ? task : task - (MODE == 1 ? CT : 0);
-      if (!is_q && !update) continue;
-      floatx16 pp[FT], pn[FT];
-      if (is_q) {
-        const int tok = c * C + 32 * tt + r;
-        const int tl = tok < N ? tok : N - 1;
-        np_map_tile<T, D, DF>(qbase + (int64_t)tl * a.q_st + g * M::KPL, wqt, bq, r, g, pp, pn);
-        float dla = 0.f;
-        T* qrow = phiq + (32 * tt + r) * L::QSTRIDE;
+  // S += phi_k^T V, z += sum phi_k for the unit in slot `u & 1`
+  auto consume_k = [&](int u) {
+    const T* phik = reinterpret_cast<const T*>(smem + (u & 1) * SLOT);
 #pragma unroll
-        for (int ft = 0; ft < FT; ++ft)
+    for (int s = 0; s < C / M::KK; ++s) {
 #pragma unroll
-          for (int s = 0; s < SPT; ++s) {
-            const int p0 = 32 * ft + s * M::KK + g * M::KPL;
-            const typename M::frag fp = M::from_acc(pp[ft], s);
-            const typename M::frag fn = M::from_acc(pn[ft], s);
-            *reinterpret_cast<typename M::frag*>(qrow + p0) = fp;
-            *reinterpret_cast<typename M::frag*>(qrow + DF + p0) = fn;
-            dla += frag_dot<T>(fp, zsh + p0) + frag_dot<T>(fn, zsh + DF + p0);
-          }
-        dla += xor32(dla);
-        if (g == 0 && tok < N) a.d_la[((int64_t)b * a.Hq + hq) * N + tok] = dla;
-      } else {
-        const int tok = cu * C + 32 * tt + r;  // full chunk: always < N
-        np_map_tile<T, D, DF>(kbase + (int64_t)tok * a.k_st + g * M::KPL, wkt, bk, r, g, pp, pn);
-        const float kf = keep[32 * tt + r] ? 1.f : 0.f;
-        T* kcol = phik + 32 * tt + r;
-#pragma unroll
-        for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int f = 32 * ft + M::pos_of_reg(i, g);
-            kcol[f * L::KSTRIDE] = from_f32<T>(pp[ft][i] * kf);
-            kcol[(DF + f) * L::KSTRIDE] = from_f32<T>(pn[ft][i] * kf);
-          }
+      for (int ft = 0; ft < PT; ++ft) {
+        const typename M::frag af = M::load(phik + (32 * ft + M::kappa(r)) * L::KSTRIDE + s * M::KK + g * M::KPL);
+        S[ft] = M::mma(af, vf[s], S[ft]);
       }
     }
-    __syncthreads();
-
-    // ---- phase B
-    if (MODE == 1) {
-      floatx16 o[CT];
+    // row sums of the same LDS rows, PT/NM feature tiles per consumer wave, outside the MFMA loop
+    constexpr int ZT = PT / NM;
+#pragma unroll 1
+    for (int j = 0; j < ZT; ++j) {
+      const int ft = wave * ZT + j;
+      const T* zrow = phik + (32 * ft + r) * L::KSTRIDE + g * M::KPL;
+      float zp = 0.f;
 #pragma unroll
-      for (int mt = 0; mt < CT; ++mt) o[mt] = zero16();
+      for (int s = 0; s < C / M::KK; ++s) zp += frag_sum<T>(M::load(zrow + s * M::KK));
+      zp += xor32(zp);
+      if (g == 0) zsh[32 * ft + r] += zp;
+    }
+  };
+
+  // N_LA = phi_q S and D_LA = phi_q z for the rows of the chunk in slot `u & 1`
+  auto consume_q = [&](int u) {
+    const LaUnit x = unit_at(u);
+    const T* phiq = reinterpret_cast<const T*>(smem + (u & 1) * SLOT);
+    float* nrow = a.n_la + ((int64_t)b * a.Hq + hq) * (int64_t)N * D;
+    // two token tiles at a time keeps the accumulators next to the state registers
+#pragma unroll 1
+    for (int mh = 0; mh < CT; mh += 2) {
+      floatx16 o[2];
+      o[0] = zero16();
+      o[1] = zero16();
 #pragma unroll
       for (int ft = 0; ft < PT; ++ft)
 #pragma unroll
         for (int s = 0; s < SPT; ++s) {
           const typename M::frag bf = M::from_acc(S[ft], s);
           const int p0 = 32 * ft + s * M::KK + g * M::KPL;
-#pragma unroll
-          for (int mt = 0; mt < CT; ++mt)
-            o[mt] = M::mma(M::load(phiq + (32 * mt + r) * L::QSTRIDE + p0), bf, o[mt]);
+          o[0] = M::mma(M::load(phiq + (32 * mh + r) * L::QSTRIDE + p0), bf, o[0]);
+          o[1] = M::mma(M::load(phiq + (32 * mh + 32 + r) * L::QSTRIDE + p0), bf, o[1]);
         }
-      float* nrow = a.n_la + ((int64_t)b * a.Hq + hq) * (int64_t)N * D;
 #pragma unroll
-      for (int mt = 0; mt < CT; ++mt)
+      for (int mm = 0; mm < 2; ++mm)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int tok = c * C + 32 * mt + c_row(i, g);
+          const int tok = x.chunk * C + 32 * (mh + mm) + c_row(i, g);
           if (tok < N) {
-            float val = o[mt][i];
+            float val = o[mm][i];
             if (a.g != nullptr)
               val *= to_f32(static_cast<const T*>(a.g)[(int64_t)b * a.g_sb + (int64_t)tok * a.g_st +
                                                        (int64_t)hq * a.g_sh + col]);
@@ -296,30 +379,41 @@ __global__ __launch_bounds__((D / 32) * 64) void la_kernel(LaArgs a) {
           }
         }
     }
-    if (update) {
-      float zp[PT];
-#pragma unroll
-      for (int ft = 0; ft < PT; ++ft) zp[ft] = 0.f;
-      const T* vrow = vt + (int64_t)col * a.Np + (int64_t)cu * C + g * M::KPL;
+    // D_LA: this wave's share of the chunk's rows; lane group g sums feature half g
+    constexpr int TPW = C / NM;
+    for (int j = r; j < TPW; j += 32) {
+      const int tl = wave * TPW + j;
+      const T* qrow = phiq + tl * L::QSTRIDE + g * DF;
+      const float* zz = zsh + g * DF;
+      float dla = 0.f;
 #pragma unroll 4
-      for (int s = 0; s < C / M::KK; ++s) {
-        const typename M::frag bf = M::load(vrow + s * M::KK);
-#pragma unroll
-        for (int ft = 0; ft < PT; ++ft) {
-          const typename M::frag af = M::load(phik + (32 * ft + M::kappa(r)) * L::KSTRIDE + s * M::KK + g * M::KPL);
-          S[ft] = M::mma(af, bf, S[ft]);
-          if (wave == 0) zp[ft] += frag_sum<T>(af);
-        }
-      }
-      if (wave == 0) {
-#pragma unroll
-        for (int ft = 0; ft < PT; ++ft) {
-          const float tot = zp[ft] + xor32(zp[ft]);
-          if (g == 0) zsh[32 * ft + M::kappa(r)] += tot;
-        }
-      }
+      for (int f0 = 0; f0 < DF; f0 += M::KPL) dla += frag_dot<T>(M::load(qrow + f0), zz + f0);
+      dla += xor32(dla);
+      const int tok = x.chunk * C + tl;
+      if (g == 0 && tok < N) a.d_la[((int64_t)b * a.Hq + hq) * N + tok] = dla;
     }
-    __syncthreads();
+  };
+
+  if (MODE == 1) {
+    if (n_units > 1) load_v(1);
+    lds_barrier();
+    consume_q(0);
+    lds_barrier();
+    for (int u = 1; u + 1 < n_units; u += 2) {
+      consume_k(u);
+      lds_barrier();
+      consume_q(u + 1);
+      if (u + 2 < n_units) load_v(u + 2);   // requested before the barrier: the wait hides the latency
+      lds_barrier();
+    }
+  } else {
+    load_v(0);
+    lds_barrier();
+    for (int u = 0; u < n_units; ++u) {
+      consume_k(u);
+      if (u + 1 < n_units) load_v(u + 1);
+      lds_barrier();
+    }
   }
 
   // ---- write the state
@@ -332,7 +426,7 @@ __global__ __launch_bounds__((D / 32) * 64) void la_kernel(LaArgs a) {
     for (int ft = 0; ft < PT; ++ft)
 #pragma unroll
       for (int i = 0; i < 16; ++i) dst[(int64_t)(32 * ft + M::pos_of_reg(i, g)) * D + col] = S[ft][i];
-    for (int f = threadIdx.x; f < DP; f += NW * 64) dst[DP * D + f] = zsh[f];
+    for (int f = threadIdx.x; f < DP; f += NM * 64) dst[DP * D + f] = zsh[f];
   }
 }
 
@@ -357,7 +451,7 @@ static hipError_t launch_la_t(const LaArgs& a, int B, int nblocks, hipStream_t s
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
-  dim3 grid(nblocks, a.Hq, B), block((D / 32) * 64);
+  dim3 grid(nblocks * a.Hq, 1, B), block((D / 32 + C / 32) * 64);
   hipLaunchKernelGGL(kern, grid, block, smem, stream, a);
   return hipGetLastError();
 }

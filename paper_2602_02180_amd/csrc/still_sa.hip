@@ -225,7 +225,7 @@ __global__ __launch_bounds__(256, 2) void sa_kernel(SaArgs a) {
 
   SA_GLOAD(0);
   SA_LSTORE(0);
-  __syncthreads();
+  lds_barrier();
   if (n_tiles > 1) SA_GLOAD(1);
 
   for (int ti = 0; ti < n_tiles; ++ti) {
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256, 2) void sa_kernel(SaArgs a) {
       }
     }
     if (ti + 1 < n_tiles) SA_LSTORE((ti + 1) & 1);
-    __syncthreads();
+    lds_barrier();
     if (ti + 2 < n_tiles) SA_GLOAD(ti + 2);
   }
 #undef SA_GLOAD

@@ -22,7 +22,9 @@ __global__ __launch_bounds__(256) void score_select_kernel(ScoreArgs a) {
   constexpr int KS = D / M::KK;
   const T* __restrict__ q = static_cast<const T*>(a.q);
   const T* __restrict__ k = static_cast<const T*>(a.k);
-  const int c = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+  int c, hq;
+  head_major_block(blockIdx.x, a.Hq, hq, c);
+  const int b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 31, g = lane >> 5;
   const int N = a.N, C = a.C, W = a.W;
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(256) void score_select_kernel(ScoreArgs a) {
 
 template <typename T, int D>
 static hipError_t launch_score_t(const ScoreArgs& a, int B, int nc, hipStream_t stream) {
-  dim3 grid(nc, a.Hq, B), block((a.C / 32) * 64);
+  dim3 grid(nc * a.Hq, 1, B), block((a.C / 32) * 64);
   if (a.W <= 65)
     hipLaunchKernelGGL((score_select_kernel<T, D, 3>), grid, block, 0, stream, a);
   else
