@@ -59,6 +59,8 @@ typedef struct still_params {
   float scale;                   /* > 0; multiplies every q.k logit, score window and softmax branch alike */
   float eps;                     /* eps of the score equation                                              */
   int32_t dtype;                 /* still_dtype_t of q, k, v, g, out, Wq, Wk, bq, bk                        */
+  int32_t max_tokens;            /* capacity (tokens per sequence) of a decode state; used only by the state
+                                    functions, the decode step and state_out; 0 where no state is involved  */
   int64_t q_sb, q_st, q_sh;      /* q   [B, N, Hq,  d]                                                     */
   int64_t k_sb, k_st, k_sh;      /* k   [B, N, Hkv, d]                                                     */
   int64_t v_sb, v_st, v_sh;      /* v   [B, N, Hkv, d]                                                     */
@@ -112,8 +114,9 @@ STILL_API still_status_t still_fwd_workspace_layout(const still_params_t* p, sti
  *                  in each full chunk, ascending within a chunk
  *   sel_idx_is_input  0: sel_idx (if given) is an OUTPUT.  1: sel_idx is an INPUT that replaces the
  *                  Top-lambda step (indices must lie inside their chunk, strictly ascending); test hook
- *   state_out      device, or NULL: a decode state (see still_state_bytes) initialised with
- *                  still_state_init for the same params; on return it stands after token N-1
+ *   state_out      device, or NULL: a decode state buffer (see still_state_bytes; p->max_tokens >= N);
+ *                  on return it holds the tokens 0..N-1, so the next decode step is t = N.  Its previous
+ *                  contents are overwritten (no still_state_init needed)
  *   workspace      device scratch of at least still_fwd_workspace_bytes(p) bytes; contents undefined
  *                  afterwards
  *   stream         hipStream_t (as void*)
@@ -141,33 +144,48 @@ STILL_API still_status_t still_profile_read(float* ms, int32_t n);
 STILL_API const char* still_profile_kernel_name(int32_t i);
 
 /*
- * Decode state of B sequences (the salient cache h and the state (s, z) of the cache-routing
- * equation, plus the local ring that delayed selection needs).  One opaque caller-owned buffer:
- *   header | pos[B] | n_routed[B] | S[B,Hq,2*d_f,d] f32 | z[B,Hq,2*d_f] f32 |
- *   Kret[B,Hq,cap,d] | VretT... | local K/V ring [B,Hkv,R,d] | score ring [B,Hq,R] f32
- * with cap = lambda * ceil(max_tokens / C) rounded up to 64 and R >= 2*C + W.
- * It can be copied or saved with plain memcpy.  `p->N` is ignored by the state functions.
+ * Decode state of B sequences that advance in lock step: the salient cache h and the state (s, z) of the
+ * cache-routing equation (Sec. 3.3), plus the ring of recent tokens that delayed selection needs.  One
+ * opaque caller-owned device buffer of still_state_bytes(p) bytes (p->max_tokens = capacity per sequence):
+ *   S    float [B, Hq, 2*d_f*(d+1)]   state through the last routed chunk: S (2*d_f x d) then z (2*d_f)
+ *   Kret dtype [B, Hq, cap, d]        retained keys in routing order, cap = lambda*ceil(max_tokens/C) (+pad)
+ *   Vret dtype [B, Hq, cap, d]        retained values
+ *   sel  int32 [B, Hq, ceil(max_tokens/C), lambda]   token indices kept per routed chunk (for inspection)
+ *   ring dtype [B, Hkv, R, d] x 2     keys and values of the last R = 4*C tokens, slot = token % R
+ *   sc   float [B, Hq, R]             Self-Saliency Score of the same tokens
+ *   part float [B, Hq, 32, d+2]       split partials of the attention pass
+ * The number of tokens seen is NOT stored: the caller passes the index t of the new token to every step.
+ * The buffer can be copied or saved with plain memcpy.  p->N is ignored by the state functions.
  */
-STILL_API size_t still_state_bytes(const still_params_t* p, int32_t max_tokens);
+STILL_API size_t still_state_bytes(const still_params_t* p);
 
-/* Resets a state buffer to "no token seen".  Enqueues fill kernels on `stream`. */
-STILL_API still_status_t still_state_init(const still_params_t* p, void* state, int32_t max_tokens, void* stream);
+/* Byte offsets of the regions above inside a state buffer (for tests/tools). */
+typedef struct still_state_layout {
+  size_t S, kret, vret, sel, kring, vring, score, part, total;
+  int32_t cap, R, n_chunks;
+} still_state_layout_t;
+STILL_API still_status_t still_state_layout(const still_params_t* p, still_state_layout_t* layout);
+
+/* Resets a state buffer to "no token seen" (zero fill on `stream`). */
+STILL_API still_status_t still_state_init(const still_params_t* p, void* state, void* stream);
 
 /*
- * One decode step of the recurrent form for every sequence in the batch: appends (k_t, v_t), scores the
- * new token over its window, routes the chunk that has just left the local span when the token opens a
- * new chunk (Top-lambda -> retained cache, the rest -> (s, z)), and writes
- * y_t = (N_SA + N_LA) / (D_SA + D_LA).
+ * One decode step of the recurrent form (Sec. 3.3) for the token with index t (0-based; the state must hold
+ * exactly the tokens 0..t-1) of every sequence in the batch:
+ *   - (k_t, v_t) are appended to the ring and the token's Self-Saliency Score over its window is stored;
+ *   - if t opens a new chunk c = t/C >= 2, chunk c-2 leaves the local span and is routed: its Top-lambda
+ *     keys/values join the retained cache, the others are added to (s, z) through the NP-Map;
+ *   - y_t = (N_SA + N_LA) / (D_SA + D_LA) over the retained cache, the local span and the state.
  *
  *   q_t [B, Hq, d], k_t, v_t [B, Hkv, d], g_t [B, Hq, d] or NULL, out_t [B, Hq, d]: device, dtype, contiguous.
- * Returns STILL_ERR_STATE when a sequence would exceed max_tokens (checked against the host-side
- * position the library mirrors in the state header; no device read-back).
+ *   Wq, Wk, bq, bk as for the prefill.
+ * Returns STILL_ERR_STATE when t < 0 or t >= p->max_tokens.
  */
-STILL_API still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* state,
-                                             const void* q_t, const void* k_t, const void* v_t,
-                                             const void* g_t,
-                                             const void* Wq, const void* bq, const void* Wk, const void* bk,
-                                             void* out_t, void* stream);
+STILL_API still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* state, int32_t t,
+                                                       const void* q_t, const void* k_t, const void* v_t,
+                                                       const void* g_t,
+                                                       const void* Wq, const void* bq, const void* Wk, const void* bk,
+                                                       void* out_t, void* stream);
 
 #ifdef __cplusplus
 }

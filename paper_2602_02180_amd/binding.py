@@ -24,7 +24,7 @@ class StillParams(ct.Structure):
     _fields_ = [
         ("B", ct.c_int32), ("N", ct.c_int32), ("Hq", ct.c_int32), ("Hkv", ct.c_int32), ("d", ct.c_int32),
         ("d_f", ct.c_int32), ("C", ct.c_int32), ("W", ct.c_int32), ("lam", ct.c_int32),
-        ("scale", ct.c_float), ("eps", ct.c_float), ("dtype", ct.c_int32),
+        ("scale", ct.c_float), ("eps", ct.c_float), ("dtype", ct.c_int32), ("max_tokens", ct.c_int32),
         ("q_sb", ct.c_int64), ("q_st", ct.c_int64), ("q_sh", ct.c_int64),
         ("k_sb", ct.c_int64), ("k_st", ct.c_int64), ("k_sh", ct.c_int64),
         ("v_sb", ct.c_int64), ("v_st", ct.c_int64), ("v_sh", ct.c_int64),
@@ -38,6 +38,12 @@ class StillWsLayout(ct.Structure):
     _fields_ = [(n, ct.c_size_t) for n in
                 ("score", "sel", "vt", "kret", "vrett", "wqt", "wkt", "seg", "n_la", "d_la", "total")] + \
                [(n, ct.c_int32) for n in ("n_pad", "cap", "nseg", "seg_chunks")]
+
+
+class StillStateLayout(ct.Structure):
+    _fields_ = [(n, ct.c_size_t) for n in
+                ("S", "kret", "vret", "sel", "kring", "vring", "score", "part", "total")] + \
+               [(n, ct.c_int32) for n in ("cap", "R", "n_chunks")]
 
 
 class StillError(RuntimeError):
@@ -67,11 +73,13 @@ def lib() -> ct.CDLL:
         L.still_hybrid_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ct.c_int32, vp, vp,
                                             ct.c_size_t, vp]
         L.still_state_bytes.restype = ct.c_size_t
-        L.still_state_bytes.argtypes = [pp, ct.c_int32]
+        L.still_state_bytes.argtypes = [pp]
+        L.still_state_layout.restype = ct.c_int
+        L.still_state_layout.argtypes = [pp, ct.POINTER(StillStateLayout)]
         L.still_state_init.restype = ct.c_int
-        L.still_state_init.argtypes = [pp, vp, ct.c_int32, vp]
+        L.still_state_init.argtypes = [pp, vp, vp]
         L.still_hybrid_attn_decode_step.restype = ct.c_int
-        L.still_hybrid_attn_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.still_hybrid_attn_decode_step.argtypes = [pp, vp, ct.c_int32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.still_profile_enable.restype = None
         L.still_profile_enable.argtypes = [ct.c_int32]
         L.still_profile_read.restype = ct.c_int
@@ -99,12 +107,13 @@ def _strides(t):
 
 
 def make_params(*, B, N, Hq, Hkv, d, C, W, lam, scale, eps, dtype, d_f=None, q=None, k=None, v=None, out=None,
-                g=None, kv_head_of_q=None) -> StillParams:
+                g=None, kv_head_of_q=None, max_tokens=0) -> StillParams:
     """Fill a still_params_t; strides are taken from the torch tensors ([B, N, H, d])."""
     p = StillParams()
     p.B, p.N, p.Hq, p.Hkv, p.d, p.d_f = B, N, Hq, Hkv, d, (d_f or d)
     p.C, p.W, p.lam, p.scale, p.eps = C, W, lam, scale, eps
     p.dtype = DTYPE_CODE[dtype] if isinstance(dtype, str) else dtype
+    p.max_tokens = max_tokens
     p.q_sb, p.q_st, p.q_sh = _strides(q)
     p.k_sb, p.k_st, p.k_sh = _strides(k)
     p.v_sb, p.v_st, p.v_sh = _strides(v)
@@ -157,28 +166,34 @@ def still_hybrid_attn_fwd(p: StillParams, q, k, v, g, Wq, bq, Wk, bk, out, score
         0 if workspace is None else workspace.numel() * workspace.element_size(), stream.cuda_stream))
 
 
-def still_state_bytes(p: StillParams, max_tokens: int) -> int:
-    n = int(lib().still_state_bytes(ct.byref(p), max_tokens))
+def still_state_bytes(p: StillParams) -> int:
+    n = int(lib().still_state_bytes(ct.byref(p)))
     if n == 0:
         raise StillError(-1, still_last_error())
     return n
 
 
-def still_state_init(p: StillParams, state, max_tokens: int, stream=None) -> None:
+def still_state_layout(p: StillParams) -> StillStateLayout:
+    L = StillStateLayout()
+    _check(lib().still_state_layout(ct.byref(p), ct.byref(L)))
+    return L
+
+
+def still_state_init(p: StillParams, state, stream=None) -> None:
     import torch
 
     if stream is None:
         stream = torch.cuda.current_stream()
-    _check(lib().still_state_init(ct.byref(p), _ptr(state), max_tokens, stream.cuda_stream))
+    _check(lib().still_state_init(ct.byref(p), _ptr(state), stream.cuda_stream))
 
 
-def still_hybrid_attn_decode_step(p: StillParams, state, q_t, k_t, v_t, g_t, Wq, bq, Wk, bk, out_t,
+def still_hybrid_attn_decode_step(p: StillParams, state, t: int, q_t, k_t, v_t, g_t, Wq, bq, Wk, bk, out_t,
                                   stream=None) -> None:
     import torch
 
     if stream is None:
         stream = torch.cuda.current_stream()
-    _check(lib().still_hybrid_attn_decode_step(ct.byref(p), _ptr(state), _ptr(q_t), _ptr(k_t), _ptr(v_t),
+    _check(lib().still_hybrid_attn_decode_step(ct.byref(p), _ptr(state), t, _ptr(q_t), _ptr(k_t), _ptr(v_t),
                                                _ptr(g_t), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(out_t),
                                                stream.cuda_stream))
 

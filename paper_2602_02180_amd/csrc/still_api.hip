@@ -125,6 +125,40 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   L->seg_chunks = (int32_t)G;
 }
 
+still_status_t validate_state_params(const still_params_t* p) {
+  still_status_t st = validate_params(p, false);
+  if (st != STILL_OK) return st;
+  if (p->max_tokens < 1) return fail(STILL_ERR_INVALID_ARG, "max_tokens must be >= 1 for a decode state");
+  if ((int64_t)p->max_tokens > (int64_t)1 << 24) return fail(STILL_ERR_UNSUPPORTED, "max_tokens too large");
+  return STILL_OK;
+}
+
+void compute_state_layout(const still_params_t* p, still_state_layout_t* L) {
+  const size_t es = esize(p->dtype);
+  const int64_t B = p->B, Hq = p->Hq, Hkv = p->Hkv, d = p->d, df = p->d_f;
+  const int64_t nch = ((int64_t)p->max_tokens + p->C - 1) / p->C;
+  const int64_t cap = (nch * p->lambda + 63) / 64 * 64 + 64;
+  const int64_t R = 4 * (int64_t)p->C;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + (bytes ? bytes : 16), 256);
+    return o;
+  };
+  L->S = take((size_t)B * Hq * (2 * df * (d + 1)) * 4);
+  L->kret = take((size_t)B * Hq * cap * d * es);
+  L->vret = take((size_t)B * Hq * cap * d * es);
+  L->sel = take((size_t)B * Hq * nch * p->lambda * 4);
+  L->kring = take((size_t)B * Hkv * R * d * es);
+  L->vring = take((size_t)B * Hkv * R * d * es);
+  L->score = take((size_t)B * Hq * R * 4);
+  L->part = take((size_t)B * Hq * 32 * (d + 2) * 4);
+  L->total = off;
+  L->cap = (int32_t)cap;
+  L->R = (int32_t)R;
+  L->n_chunks = (int32_t)nch;
+}
+
 }  // namespace
 
 extern "C" {
@@ -163,7 +197,11 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
     if (x != nullptr && !aligned16(x)) return fail(STILL_ERR_INVALID_ARG, "pointer %p is not 16-byte aligned", x);
   if (sel_idx_is_input && sel_idx == nullptr && p->lambda > 0 && p->N >= p->C)
     return fail(STILL_ERR_INVALID_ARG, "sel_idx_is_input set but sel_idx is NULL");
-  if (state_out != nullptr) return fail(STILL_ERR_UNSUPPORTED, "state_out is not available in this build");
+  if (state_out != nullptr) {
+    if (!aligned16(state_out)) return fail(STILL_ERR_INVALID_ARG, "state_out is not 16-byte aligned");
+    if (p->max_tokens < p->N) return fail(STILL_ERR_INVALID_ARG, "state_out needs max_tokens >= N");
+    if ((int64_t)p->max_tokens > (int64_t)1 << 24) return fail(STILL_ERR_UNSUPPORTED, "max_tokens too large");
+  }
   still_ws_layout_t L;
   compute_layout(p, &L);
   if (workspace_bytes < L.total)
@@ -242,7 +280,10 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   la.seg = reinterpret_cast<float*>(ws + L.seg);
   la.n_la = reinterpret_cast<float*>(ws + L.n_la);
   la.d_la = reinterpret_cast<float*>(ws + L.d_la);
-  la.s_final = nullptr;
+  still_state_layout_t SL{};
+  unsigned char* stp = static_cast<unsigned char*>(state_out);
+  if (state_out != nullptr) compute_state_layout(p, &SL);
+  la.s_final = state_out != nullptr ? reinterpret_cast<float*>(stp + SL.S) : nullptr;
   prof_mark(4, stream);
   if ((e = still::launch_la_state(la, p->dtype, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "la_state: %s", hipGetErrorString(e));
@@ -269,6 +310,25 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   if ((e = still::launch_sa(sx, p->dtype, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "sparse_attention: %s", hipGetErrorString(e));
   prof_mark(STILL_PROFILE_SLOTS, stream);
+
+  // decode state standing after token N-1: (S, z) through chunk c_last-2 came from the linear pass above
+  if (state_out != nullptr) {
+    still::StateFillArgs sf{};
+    sf.k = k; sf.v = v;
+    sf.k_sb = p->k_sb; sf.k_st = p->k_st; sf.k_sh = p->k_sh;
+    sf.v_sb = p->v_sb; sf.v_st = p->v_st; sf.v_sh = p->v_sh;
+    sf.score = score; sf.sel = sel; sf.map = map;
+    sf.kret = stp + SL.kret; sf.vret = stp + SL.vret;
+    sf.sel_state = reinterpret_cast<int32_t*>(stp + SL.sel);
+    sf.kring = stp + SL.kring; sf.vring = stp + SL.vring;
+    sf.score_ring = reinterpret_cast<float*>(stp + SL.score);
+    sf.N = N; sf.R = SL.R; sf.Hq = p->Hq; sf.Hkv = p->Hkv; sf.d = d; sf.lam = have_sel ? p->lambda : 0;
+    sf.cap = SL.cap; sf.ncf = ncf; sf.nchunks = SL.n_chunks;
+    const int n_routed = nc >= 2 ? nc - 2 : 0;
+    if (!need_scores) return fail(STILL_ERR_INVALID_ARG, "state_out needs the scores: do not combine it with sel_idx_is_input unless score_out is given");
+    if ((e = still::launch_state_fill(sf, p->dtype, B, n_routed, stream)) != hipSuccess)
+      return fail(STILL_ERR_HIP, "state_fill: %s", hipGetErrorString(e));
+  }
   g_err[0] = 0;
   return STILL_OK;
 }
@@ -296,24 +356,72 @@ const char* still_profile_kernel_name(int32_t i) {
   return (i >= 0 && i < STILL_PROFILE_SLOTS) ? kSlotNames[i] : nullptr;
 }
 
-size_t still_state_bytes(const still_params_t* p, int32_t max_tokens) {
-  (void)max_tokens;
-  if (validate_params(p, false) != STILL_OK) return 0;
-  fail(STILL_ERR_UNSUPPORTED, "decode state is not available in this build");
-  return 0;
+size_t still_state_bytes(const still_params_t* p) {
+  still_state_layout_t L;
+  if (still_state_layout(p, &L) != STILL_OK) return 0;
+  return L.total;
 }
 
-still_status_t still_state_init(const still_params_t* p, void* state, int32_t max_tokens, void* stream) {
-  (void)p; (void)state; (void)max_tokens; (void)stream;
-  return fail(STILL_ERR_UNSUPPORTED, "decode state is not available in this build");
+still_status_t still_state_layout(const still_params_t* p, still_state_layout_t* layout) {
+  if (layout == nullptr) return fail(STILL_ERR_INVALID_ARG, "layout is NULL");
+  still_status_t st = validate_state_params(p);
+  if (st != STILL_OK) return st;
+  compute_state_layout(p, layout);
+  return STILL_OK;
 }
 
-still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* state, const void* q_t, const void* k_t,
-                                             const void* v_t, const void* g_t, const void* Wq, const void* bq,
-                                             const void* Wk, const void* bk, void* out_t, void* stream) {
-  (void)p; (void)state; (void)q_t; (void)k_t; (void)v_t; (void)g_t; (void)Wq; (void)bq; (void)Wk; (void)bk;
-  (void)out_t; (void)stream;
-  return fail(STILL_ERR_UNSUPPORTED, "decode step is not available in this build");
+still_status_t still_state_init(const still_params_t* p, void* state, void* stream) {
+  still_status_t st = validate_state_params(p);
+  if (st != STILL_OK) return st;
+  if (state == nullptr || !aligned16(state)) return fail(STILL_ERR_INVALID_ARG, "state is NULL or misaligned");
+  still_state_layout_t L;
+  compute_state_layout(p, &L);
+  hipError_t e = still::launch_fill_zero(state, L.total, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(STILL_ERR_HIP, "state_init: %s", hipGetErrorString(e));
+  g_err[0] = 0;
+  return STILL_OK;
+}
+
+still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* state, int32_t t, const void* q_t,
+                                             const void* k_t, const void* v_t, const void* g_t, const void* Wq,
+                                             const void* bq, const void* Wk, const void* bk, void* out_t,
+                                             void* stream_v) {
+  still_status_t st = validate_state_params(p);
+  if (st != STILL_OK) return st;
+  if (!state || !q_t || !k_t || !v_t || !Wq || !Wk || !out_t)
+    return fail(STILL_ERR_INVALID_ARG, "a required pointer (state, q_t, k_t, v_t, Wq, Wk, out_t) is NULL");
+  const void* ptrs[] = {state, q_t, k_t, v_t, g_t, Wq, bq, Wk, bk, out_t};
+  for (const void* x : ptrs)
+    if (x != nullptr && !aligned16(x)) return fail(STILL_ERR_INVALID_ARG, "pointer %p is not 16-byte aligned", x);
+  if (t < 0 || t >= p->max_tokens)
+    return fail(STILL_ERR_STATE, "token index %d outside the state capacity [0, %d)", t, p->max_tokens);
+  still_state_layout_t L;
+  compute_state_layout(p, &L);
+  unsigned char* sp = static_cast<unsigned char*>(state);
+  still::DecArgs a{};
+  a.S = reinterpret_cast<float*>(sp + L.S);
+  a.kret = sp + L.kret; a.vret = sp + L.vret;
+  a.sel = reinterpret_cast<int32_t*>(sp + L.sel);
+  a.kring = sp + L.kring; a.vring = sp + L.vring;
+  a.score = reinterpret_cast<float*>(sp + L.score);
+  a.part = reinterpret_cast<float*>(sp + L.part);
+  a.q = q_t; a.k = k_t; a.v = v_t; a.g = g_t; a.wq = Wq; a.wk = Wk; a.bq = bq; a.bk = bk; a.out = out_t;
+  fill_map(p, &a.map);
+  a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.C = p->C; a.W = p->W; a.lam = p->lambda;
+  a.cap = L.cap; a.R = L.R; a.nchunks = L.n_chunks; a.t = t;
+  a.scale = p->scale; a.eps = p->eps;
+  const int c = t / p->C;
+  const int rows = (c >= 1 ? c - 1 : 0) * p->lambda + (t - (c >= 1 ? c - 1 : 0) * p->C + 1);
+  int nsplit = (1024 + p->B * p->Hq - 1) / (p->B * p->Hq);
+  if (nsplit > 32) nsplit = 32;
+  if (nsplit > (rows + 63) / 64) nsplit = (rows + 63) / 64;
+  if (nsplit < 1) nsplit = 1;
+  a.nsplit = nsplit;
+  const bool route = (t % p->C == 0) && c >= 2;
+  hipError_t e = still::launch_decode_step(a, p->dtype, p->d, route, static_cast<hipStream_t>(stream_v));
+  if (e != hipSuccess) return fail(STILL_ERR_HIP, "decode_step: %s", hipGetErrorString(e));
+  g_err[0] = 0;
+  return STILL_OK;
 }
 
 }  // extern "C"

@@ -1,0 +1,509 @@
+// Decode step of STILL's recurrent form (paper Sec. 3.3: delayed selection, cache-routing equation, output
+// equations) and the export of a decode state from the prefill.
+//
+// One step is bandwidth-bound: every (batch, query head) reads all its retained keys/values plus the local
+// span once.  Kernels of a step, all on the caller's stream:
+//   append   : (k_t, v_t) into the ring of recent tokens (slot = t mod R)
+//   score    : Self-Saliency Score of token t over its window (Sec. 3.1), one thread per window key
+//   route    : only when t opens chunk c >= 2: Top-lambda of chunk c-2 (ties to the lower index), selected
+//              rows appended to the retained cache, the others folded into (S, z) through the NP-Map
+//   attend   : split over the rows of the salient cache: per split an online-softmax partial (m, l, acc)
+//   finish   : NP-Map of q_t, N_LA = phi_q S, D_LA = phi_q z, merge of the split partials,
+//              y = (N_SA + g*N_LA) / (D_SA + D_LA) with both branches scaled by exp(-max(m, 0))
+// Everything is plain vector-ALU code with fp32 accumulation: there is no contraction here that could
+// feed a matrix core (one query row per head).
+#include "still_kernels.h"
+
+namespace still {
+
+template <typename T>
+struct Vec {
+  static constexpr int N = 16 / sizeof(T);
+  T v[16 / sizeof(T)];
+};
+
+template <typename T>
+__device__ __forceinline__ void load16(const T* p, float (&out)[16 / sizeof(T)]) {
+  const Vec<T> x = *reinterpret_cast<const Vec<T>*>(p);
+#pragma unroll
+  for (int e = 0; e < Vec<T>::N; ++e) out[e] = to_f32(x.v[e]);
+}
+
+template <typename T>
+__device__ __forceinline__ float round_to(float x) {
+  return to_f32(from_f32<T>(x));
+}
+
+// ---- block reductions over 256 (or fewer) threads; `sh` has room for 4 floats per wave
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// sums a and b, max of c, min of d over the block
+__device__ __forceinline__ void block_reduce4(float& a, float& b, float& c, float& d, float* sh, int nwaves) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  c = wave_max(c);
+  d = -wave_max(-d);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) {
+    sh[4 * wave + 0] = a;
+    sh[4 * wave + 1] = b;
+    sh[4 * wave + 2] = c;
+    sh[4 * wave + 3] = d;
+  }
+  __syncthreads();
+  a = sh[0]; b = sh[1]; c = sh[2]; d = sh[3];
+  for (int w = 1; w < nwaves; ++w) {
+    a += sh[4 * w];
+    b += sh[4 * w + 1];
+    c = fmaxf(c, sh[4 * w + 2]);
+    d = fminf(d, sh[4 * w + 3]);
+  }
+}
+
+// ---------------------------------------------------------------- append
+template <typename T>
+__global__ void decode_append_kernel(DecArgs a, int D) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int slot = a.t % a.R;
+  const T* k = static_cast<const T*>(a.k) + ((int64_t)b * a.Hkv + h) * D;
+  const T* v = static_cast<const T*>(a.v) + ((int64_t)b * a.Hkv + h) * D;
+  T* kr = static_cast<T*>(a.kring) + (((int64_t)b * a.Hkv + h) * a.R + slot) * D;
+  T* vr = static_cast<T*>(a.vring) + (((int64_t)b * a.Hkv + h) * a.R + slot) * D;
+  for (int x = threadIdx.x; x < D; x += blockDim.x) {
+    kr[x] = k[x];
+    vr[x] = v[x];
+  }
+}
+
+// ---------------------------------------------------------------- score of the new token
+template <typename T, int D>
+__global__ __launch_bounds__(128) void decode_score_kernel(DecArgs a) {
+  __shared__ float sh[16];
+  const int hq = blockIdx.x, b = blockIdx.y;
+  const int kvh = a.map.kv[hq];
+  const int j = threadIdx.x;              // window key t - j
+  const int pj = a.t - j;
+  const bool valid = j < a.W && pj >= 0;
+  const T* q = static_cast<const T*>(a.q) + ((int64_t)b * a.Hq + hq) * D;
+  const T* krow = j == 0 ? static_cast<const T*>(a.k) + ((int64_t)b * a.Hkv + kvh) * D
+                         : static_cast<const T*>(a.kring) +
+                               (((int64_t)b * a.Hkv + kvh) * a.R + ((valid ? pj : 0) % a.R)) * D;
+  float dot = 0.f;
+  constexpr int EPV = 16 / sizeof(T);
+  if (valid) {
+#pragma unroll 4
+    for (int x = 0; x < D; x += EPV) {
+      float qv[EPV], kv[EPV];
+      load16<T>(q + x, qv);
+      load16<T>(krow + x, kv);
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) dot = fmaf(qv[e], kv[e], dot);
+    }
+  }
+  const float x2 = valid ? dot * (a.scale * kLog2e) : -INFINITY;
+  float s0 = 0.f, s1 = 0.f, mx = x2, mn = 0.f;
+  block_reduce4(s0, s1, mx, mn, sh, 2);
+  const float e = valid ? fast_exp2(x2 - mx) : 0.f;
+  float d_all = e, d_no = j == 0 ? 0.f : e;
+  float c0 = 0.f, c1 = 0.f;
+  block_reduce4(d_all, d_no, c0, c1, sh, 2);
+  const float inv_all = 1.0f / d_all;
+  const float inv_no = d_no > 0.f ? 1.0f / d_no : 0.f;
+  const float ad = e * inv_all;
+  const float an = j == 0 ? 0.f : e * inv_no;
+  float term = valid ? ad * (fast_log2(ad + a.eps) - fast_log2(an + a.eps)) : 0.f;
+  float z0 = 0.f, z1 = 0.f, z2 = 0.f;
+  block_reduce4(term, z0, z1, z2, sh, 2);
+  if (threadIdx.x == 0) a.score[((int64_t)b * a.Hq + hq) * a.R + a.t % a.R] = term * kLn2;
+}
+
+// ---------------------------------------------------------------- routing of chunk cr = t/C - 2
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr) {
+  constexpr int DF = D, DP = 2 * D;
+  __shared__ float s_sc[128];
+  __shared__ unsigned char s_flag[128];
+  __shared__ int s_list[128];
+  __shared__ float xs[D], vs[D], phi[DP], sh[16];
+  const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int kvh = a.map.kv[hq];
+  const int C = a.C, lam = a.lam, R = a.R;
+  const int64_t unit = (int64_t)b * a.Hq + hq;
+  const T* kring = static_cast<const T*>(a.kring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)R * D;
+  const T* vring = static_cast<const T*>(a.vring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)R * D;
+
+  if (tid < C) s_sc[tid] = a.score[unit * R + (cr * C + tid) % R];
+  __syncthreads();
+  bool chosen = false;
+  if (tid < C) {
+    const float si = s_sc[tid];
+    int rank = 0;
+    for (int jx = 0; jx < C; ++jx) {
+      const float sj = s_sc[jx];
+      rank += (sj > si || (sj == si && jx < tid)) ? 1 : 0;
+    }
+    chosen = rank < lam;
+    s_flag[tid] = chosen ? 1 : 0;
+  }
+  __syncthreads();
+  if (chosen) {
+    int pos = 0;
+    for (int jx = 0; jx < tid; ++jx) pos += s_flag[jx];
+    if (pos < lam) {
+      a.sel[(unit * a.nchunks + cr) * lam + pos] = cr * C + tid;
+      s_list[pos] = tid;
+    }
+  }
+  __syncthreads();
+  // selected rows -> retained cache (rows cr*lam ..)
+  {
+    T* kret = static_cast<T*>(a.kret) + (unit * a.cap + (int64_t)cr * lam) * D;
+    T* vret = static_cast<T*>(a.vret) + (unit * a.cap + (int64_t)cr * lam) * D;
+    for (int idx = tid; idx < lam * D; idx += 256) {
+      const int row = idx / D, x = idx % D;
+      const int slot = (cr * C + s_list[row]) % R;
+      kret[(int64_t)row * D + x] = kring[(int64_t)slot * D + x];
+      vret[(int64_t)row * D + x] = vring[(int64_t)slot * D + x];
+    }
+  }
+  // the others -> (S, z): thread f owns row f of S; thread j < DF also owns column j of Wk
+  float wcol[D];
+  if (tid < DF) {
+    const T* wk = static_cast<const T*>(a.wk) + (int64_t)hq * D * DF + tid;
+#pragma unroll
+    for (int x = 0; x < D; ++x) wcol[x] = to_f32(wk[(int64_t)x * DF]);
+  }
+  const float bias = (a.bk != nullptr && tid < DF) ? to_f32(static_cast<const T*>(a.bk)[(int64_t)hq * DF + tid]) : 0.f;
+  float* Sg = a.S + unit * (int64_t)(DP * (D + 1));
+  float srow[D];
+  float zf = 0.f;
+  if (tid < DP) {
+#pragma unroll
+    for (int x = 0; x < D; ++x) srow[x] = Sg[(int64_t)tid * D + x];
+    zf = Sg[DP * D + tid];
+  }
+  for (int i = 0; i < C; ++i) {
+    if (s_flag[i]) continue;                     // block-uniform
+    const int slot = (cr * C + i) % R;
+    __syncthreads();
+    if (tid < D) {
+      xs[tid] = to_f32(kring[(int64_t)slot * D + tid]);
+      vs[tid] = to_f32(vring[(int64_t)slot * D + tid]);
+    }
+    __syncthreads();
+    float f = 0.f;
+    if (tid < DF) {
+#pragma unroll
+      for (int x = 0; x < D; ++x) f = fmaf(xs[x], wcol[x], f);
+      f += bias;
+    }
+    float nx2 = tid < D ? xs[tid] * xs[tid] : 0.f;
+    float nf2 = tid < DF ? f * f : 0.f;
+    float fmx = tid < DF ? f : -INFINITY, fmn = tid < DF ? f : INFINITY;
+    block_reduce4(nx2, nf2, fmx, fmn, sh, 4);
+    const float ratio = nf2 > 0.f ? sqrtf(nx2 / nf2) : 0.f;
+    const float a1 = ratio * kLog2e;
+    float ep = tid < DF ? fast_exp2(fmaf(f, a1, -fmx * a1)) : 0.f;
+    float en = tid < DF ? fast_exp2(fmaf(f, -a1, fmn * a1)) : 0.f;
+    float sp = ep, sn = en, u0 = 0.f, u1 = 0.f;
+    block_reduce4(sp, sn, u0, u1, sh, 4);
+    if (tid < DF) {
+      phi[tid] = round_to<T>(ep / sp);
+      phi[DF + tid] = round_to<T>(en / sn);
+    }
+    __syncthreads();
+    if (tid < DP) {
+      const float pf = phi[tid];
+      zf += pf;
+#pragma unroll
+      for (int x = 0; x < D; ++x) srow[x] = fmaf(pf, vs[x], srow[x]);
+    }
+  }
+  if (tid < DP) {
+#pragma unroll
+    for (int x = 0; x < D; ++x) Sg[(int64_t)tid * D + x] = srow[x];
+    Sg[DP * D + tid] = zf;
+  }
+}
+
+// ---------------------------------------------------------------- attention over the salient cache (split)
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_attend_kernel(DecArgs a) {
+  constexpr int EPV = 16 / sizeof(T);
+  constexpr int LPR = D / EPV;        // lanes per row
+  constexpr int RPW = 64 / LPR;       // rows per wave step
+  constexpr int NG = 4 * RPW;         // row groups per block
+  __shared__ float s_m[NG], s_l[NG], s_acc[NG][D];
+  const int split = blockIdx.x, hq = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int sub = lane % LPR, grp = lane / LPR;
+  const int kvh = a.map.kv[hq];
+  const int64_t unit = (int64_t)b * a.Hq + hq;
+  const int c = a.t / a.C;
+  const int n_ret = (c >= 1 ? c - 1 : 0) * a.lam;
+  const int lo = (c >= 1 ? c - 1 : 0) * a.C;
+  const int nr = n_ret + (a.t - lo + 1);
+  int per = (nr + a.nsplit - 1) / a.nsplit;
+  per = (per + NG - 1) / NG * NG;
+  const int r_beg = split * per;
+  const int r_end = r_beg + per < nr ? r_beg + per : nr;
+
+  const T* kret = static_cast<const T*>(a.kret) + unit * (int64_t)a.cap * D;
+  const T* vret = static_cast<const T*>(a.vret) + unit * (int64_t)a.cap * D;
+  const T* kring = static_cast<const T*>(a.kring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)a.R * D;
+  const T* vring = static_cast<const T*>(a.vring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)a.R * D;
+
+  float qv[EPV];
+  load16<T>(static_cast<const T*>(a.q) + unit * D + sub * EPV, qv);
+  const float sc2 = a.scale * kLog2e;
+  float m2 = -INFINITY, l = 0.f, acc[EPV];
+#pragma unroll
+  for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
+
+  for (int r0 = r_beg + wave * RPW; r0 < r_end; r0 += NG) {
+    const int row = r0 + grp;
+    const bool valid = row < r_end;
+    const T *kp, *vp;
+    if (row < n_ret || !valid) {
+      const int rr = valid ? row : 0;
+      kp = kret + (int64_t)rr * D;
+      vp = vret + (int64_t)rr * D;
+    } else {
+      const int slot = (lo + (row - n_ret)) % a.R;
+      kp = kring + (int64_t)slot * D;
+      vp = vring + (int64_t)slot * D;
+    }
+    float kv[EPV], vv[EPV];
+    load16<T>(kp + sub * EPV, kv);
+    load16<T>(vp + sub * EPV, vv);
+    float dot = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) dot = fmaf(qv[e], kv[e], dot);
+#pragma unroll
+    for (int o = LPR / 2; o >= 1; o >>= 1) dot += __shfl_xor(dot, o, 64);
+    const float x2 = valid ? dot * sc2 : -INFINITY;
+    const float m_new = fmaxf(m2, x2);
+    const float m_sub = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = fast_exp2(m2 - m_sub);
+    const float pv = fast_exp2(x2 - m_sub);
+    l = l * alpha + pv;
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) acc[e] = fmaf(pv, vv[e], acc[e] * alpha);
+    m2 = m_new;
+  }
+  const int gidx = wave * RPW + grp;
+  if (sub == 0) {
+    s_m[gidx] = m2;
+    s_l[gidx] = l;
+  }
+#pragma unroll
+  for (int e = 0; e < EPV; ++e) s_acc[gidx][sub * EPV + e] = acc[e];
+  __syncthreads();
+  float M = -INFINITY;
+  for (int gi = 0; gi < NG; ++gi) M = fmaxf(M, s_m[gi]);
+  float* part = a.part + (unit * 32 + split) * (int64_t)(D + 2);
+  if (tid < D) {
+    float av = 0.f;
+    for (int gi = 0; gi < NG; ++gi) {
+      const float w = s_m[gi] == -INFINITY ? 0.f : fast_exp2(s_m[gi] - M);
+      av = fmaf(w, s_acc[gi][tid], av);
+    }
+    part[2 + tid] = av;
+  }
+  if (tid == 0) {
+    float L = 0.f;
+    for (int gi = 0; gi < NG; ++gi) {
+      const float w = s_m[gi] == -INFINITY ? 0.f : fast_exp2(s_m[gi] - M);
+      L = fmaf(w, s_l[gi], L);
+    }
+    part[0] = M;
+    part[1] = L;
+  }
+}
+
+// ---------------------------------------------------------------- NP-Map of q_t, linear terms, merge
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_finish_kernel(DecArgs a) {
+  constexpr int DF = D, DP = 2 * D;
+  __shared__ float qs[D], phi[DP], sh[16], half[2][D];
+  const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int64_t unit = (int64_t)b * a.Hq + hq;
+  const T* q = static_cast<const T*>(a.q) + unit * D;
+  if (tid < D) qs[tid] = to_f32(q[tid]);
+  __syncthreads();
+  float f = 0.f;
+  if (tid < DF) {
+    const T* wq = static_cast<const T*>(a.wq) + (int64_t)hq * D * DF + tid;
+#pragma unroll 8
+    for (int x = 0; x < D; ++x) f = fmaf(qs[x], to_f32(wq[(int64_t)x * DF]), f);
+    if (a.bq != nullptr) f += to_f32(static_cast<const T*>(a.bq)[(int64_t)hq * DF + tid]);
+  }
+  float nx2 = tid < D ? qs[tid] * qs[tid] : 0.f;
+  float nf2 = tid < DF ? f * f : 0.f;
+  float fmx = tid < DF ? f : -INFINITY, fmn = tid < DF ? f : INFINITY;
+  block_reduce4(nx2, nf2, fmx, fmn, sh, 4);
+  const float ratio = nf2 > 0.f ? sqrtf(nx2 / nf2) : 0.f;
+  const float a1 = ratio * kLog2e;
+  float ep = tid < DF ? fast_exp2(fmaf(f, a1, -fmx * a1)) : 0.f;
+  float en = tid < DF ? fast_exp2(fmaf(f, -a1, fmn * a1)) : 0.f;
+  float sp = ep, sn = en, u0 = 0.f, u1 = 0.f;
+  block_reduce4(sp, sn, u0, u1, sh, 4);
+  if (tid < DF) {
+    phi[tid] = round_to<T>(ep / sp);
+    phi[DF + tid] = round_to<T>(en / sn);
+  }
+  __syncthreads();
+  // N_LA[x] = sum_f phi[f] S[f][x]: thread (h2, x) sums half of the features
+  const float* Sg = a.S + unit * (int64_t)(DP * (D + 1));
+  {
+    constexpr int PARTS = 256 / D;                 // 2 (d=128) or 4 (d=64)
+    const int x = tid % D, h2 = tid / D;
+    float n = 0.f;
+    for (int ff = h2; ff < DP; ff += PARTS) n = fmaf(phi[ff], Sg[(int64_t)ff * D + x], n);
+    if (h2 < 2) half[h2][x] = n;
+    __syncthreads();
+    if (PARTS == 4) {
+      if (h2 >= 2) half[h2 - 2][x] += n;          // distinct (h2-2, x) per thread
+      __syncthreads();
+    }
+  }
+  float dl = tid < DP ? phi[tid] * Sg[DP * D + tid] : 0.f;
+  float d1 = 0.f, d2 = 0.f, d3 = 0.f;
+  block_reduce4(dl, d1, d2, d3, sh, 4);
+  // merge the split partials
+  const float* part = a.part + unit * 32 * (int64_t)(D + 2);
+  float M = -INFINITY;
+  for (int s = 0; s < a.nsplit; ++s) M = fmaxf(M, part[(int64_t)s * (D + 2)]);
+  if (tid < D) {
+    float L = 0.f, acc = 0.f;
+    for (int s = 0; s < a.nsplit; ++s) {
+      const float ms = part[(int64_t)s * (D + 2)];
+      const float w = ms == -INFINITY ? 0.f : fast_exp2(ms - M);
+      L = fmaf(w, part[(int64_t)s * (D + 2) + 1], L);
+      acc = fmaf(w, part[(int64_t)s * (D + 2) + 2 + tid], acc);
+    }
+    float fs, fl;
+    if (M >= 0.f) {
+      fs = 1.f;
+      fl = fast_exp2(-M);
+    } else {
+      fs = fast_exp2(M);
+      fl = 1.f;
+    }
+    float nla = half[0][tid] + half[1][tid];
+    if (a.g != nullptr) nla *= to_f32(static_cast<const T*>(a.g)[unit * D + tid]);
+    const float y = (fs * acc + fl * nla) / (fs * L + fl * dl);
+    static_cast<T*>(a.out)[unit * D + tid] = from_f32<T>(y);
+  }
+}
+
+// ---------------------------------------------------------------- state export from the prefill
+// ring and score ring <- the last min(N, R) tokens; retained K/V rows and sel <- chunks 0 .. n_routed-1
+template <typename T>
+__global__ void state_fill_ring_kernel(StateFillArgs a) {
+  const int h = blockIdx.y, b = blockIdx.z;     // grid.y = max(Hq, Hkv)
+  const int first = a.N > a.R ? a.N - a.R : 0;
+  const int tok = first + blockIdx.x;
+  if (tok >= a.N) return;
+  const int slot = tok % a.R;
+  if (h < a.Hkv) {
+    const T* k = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)tok * a.k_st + (int64_t)h * a.k_sh;
+    const T* v = static_cast<const T*>(a.v) + (int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)h * a.v_sh;
+    T* kr = static_cast<T*>(a.kring) + (((int64_t)b * a.Hkv + h) * a.R + slot) * a.d;
+    T* vr = static_cast<T*>(a.vring) + (((int64_t)b * a.Hkv + h) * a.R + slot) * a.d;
+    for (int x = threadIdx.x; x < a.d; x += blockDim.x) {
+      kr[x] = k[x];
+      vr[x] = v[x];
+    }
+  }
+  if (h < a.Hq && threadIdx.x == 0)
+    a.score_ring[((int64_t)b * a.Hq + h) * a.R + slot] = a.score[((int64_t)b * a.Hq + h) * a.N + tok];
+}
+
+template <typename T>
+__global__ void state_fill_retained_kernel(StateFillArgs a) {
+  const int row = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;   // row < n_routed * lam
+  const int64_t unit = (int64_t)b * a.Hq + hq;
+  const int kvh = a.map.kv[hq];
+  const int cr = row / a.lam, pos = row % a.lam;
+  int tok = a.sel[(unit * a.ncf + cr) * a.lam + pos];
+  if (threadIdx.x == 0) a.sel_state[(unit * a.nchunks + cr) * a.lam + pos] = tok;
+  if (tok < 0 || tok >= a.N) tok = 0;
+  const T* k = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)tok * a.k_st + (int64_t)kvh * a.k_sh;
+  const T* v = static_cast<const T*>(a.v) + (int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)kvh * a.v_sh;
+  T* kr = static_cast<T*>(a.kret) + (unit * a.cap + row) * a.d;
+  T* vr = static_cast<T*>(a.vret) + (unit * a.cap + row) * a.d;
+  for (int x = threadIdx.x; x < a.d; x += blockDim.x) {
+    kr[x] = k[x];
+    vr[x] = v[x];
+  }
+}
+
+// ---------------------------------------------------------------- launchers
+#define STILL_DISPATCH(DTYPE, DD, CALL)                     \
+  if ((DTYPE) == 1) {                                       \
+    if ((DD) == 64) { CALL(bf16, 64) } else { CALL(bf16, 128) } \
+  } else {                                                  \
+    if ((DD) == 64) { CALL(float, 64) } else { CALL(float, 128) } \
+  }
+
+hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hipStream_t stream) {
+  if (dtype == 1)
+    hipLaunchKernelGGL(decode_append_kernel<bf16>, dim3(a.Hkv, a.B), dim3(128), 0, stream, a, d);
+  else
+    hipLaunchKernelGGL(decode_append_kernel<float>, dim3(a.Hkv, a.B), dim3(128), 0, stream, a, d);
+#define CALL_SCORE(TT, DD) hipLaunchKernelGGL((decode_score_kernel<TT, DD>), dim3(a.Hq, a.B), dim3(128), 0, stream, a);
+  STILL_DISPATCH(dtype, d, CALL_SCORE)
+  if (route) {
+    const int cr = a.t / a.C - 2;
+#define CALL_ROUTE(TT, DD) hipLaunchKernelGGL((decode_route_kernel<TT, DD>), dim3(a.Hq, a.B), dim3(256), 0, stream, a, cr);
+    STILL_DISPATCH(dtype, d, CALL_ROUTE)
+  }
+#define CALL_ATT(TT, DD) hipLaunchKernelGGL((decode_attend_kernel<TT, DD>), dim3(a.nsplit, a.Hq, a.B), dim3(256), 0, stream, a);
+  STILL_DISPATCH(dtype, d, CALL_ATT)
+#define CALL_FIN(TT, DD) hipLaunchKernelGGL((decode_finish_kernel<TT, DD>), dim3(a.Hq, a.B), dim3(256), 0, stream, a);
+  STILL_DISPATCH(dtype, d, CALL_FIN)
+  return hipGetLastError();
+}
+
+hipError_t launch_state_fill(const StateFillArgs& a, int dtype, int B, int n_routed, hipStream_t stream) {
+  const int ntok = a.N < a.R ? a.N : a.R;
+  const int hy = a.Hq > a.Hkv ? a.Hq : a.Hkv;
+  if (dtype == 1)
+    hipLaunchKernelGGL(state_fill_ring_kernel<bf16>, dim3(ntok, hy, B), dim3(64), 0, stream, a);
+  else
+    hipLaunchKernelGGL(state_fill_ring_kernel<float>, dim3(ntok, hy, B), dim3(64), 0, stream, a);
+  if (n_routed > 0 && a.lam > 0) {
+    if (dtype == 1)
+      hipLaunchKernelGGL(state_fill_retained_kernel<bf16>, dim3(n_routed * a.lam, a.Hq, B), dim3(64), 0, stream, a);
+    else
+      hipLaunchKernelGGL(state_fill_retained_kernel<float>, dim3(n_routed * a.lam, a.Hq, B), dim3(64), 0, stream, a);
+  }
+  return hipGetLastError();
+}
+
+__global__ void fill_zero_kernel(uint32_t* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+// a fill kernel rather than hipMemsetAsync, so that a caller may capture the call into a HIP graph
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream) {
+  const size_t n = bytes / 4;
+  if (n == 0) return hipSuccess;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, static_cast<uint32_t*>(p), n);
+  return hipGetLastError();
+}
+
+}  // namespace still

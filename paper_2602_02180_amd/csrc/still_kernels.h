@@ -77,6 +77,48 @@ struct SaArgs {
   float scale;
 };
 
+struct DecArgs {
+  float* S;            // [B, Hq, DP*(D+1)]
+  void* kret;          // [B, Hq, cap, d]
+  void* vret;
+  int32_t* sel;        // [B, Hq, nchunks, lam]
+  void* kring;         // [B, Hkv, R, d]
+  void* vring;
+  float* score;        // [B, Hq, R]
+  float* part;         // [B, Hq, 32, d+2]
+  const void* q;       // [B, Hq, d]
+  const void* k;       // [B, Hkv, d]
+  const void* v;
+  const void* g;       // nullable
+  const void* wq;      // [Hq, d, df]
+  const void* wk;
+  const void* bq;      // nullable
+  const void* bk;
+  void* out;           // [B, Hq, d]
+  HeadMap map;
+  int B, Hq, Hkv, C, W, lam, cap, R, nchunks, t, nsplit;
+  float scale, eps;
+};
+
+struct StateFillArgs {
+  const void* k;
+  const void* v;
+  int64_t k_sb, k_st, k_sh, v_sb, v_st, v_sh;
+  const float* score;      // [B, Hq, N]
+  const int32_t* sel;      // [B, Hq, ncf, lam]
+  HeadMap map;
+  void* kret;
+  void* vret;
+  int32_t* sel_state;
+  void* kring;
+  void* vring;
+  float* score_ring;
+  int N, R, Hq, Hkv, d, lam, cap, ncf, nchunks;
+};
+
+hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hipStream_t stream);
+hipError_t launch_state_fill(const StateFillArgs& a, int dtype, int B, int n_routed, hipStream_t stream);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
 hipError_t launch_score(const ScoreArgs& a, int dtype, int d, int B, int nc, hipStream_t stream);
 hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStream_t stream);
 hipError_t launch_transpose_w(const TransposeWArgs& a, int dtype, hipStream_t stream);

@@ -1,0 +1,142 @@
+"""GPU parity of the decode step (recurrent form) against the oracle.
+
+The oracle for decode is the prefill oracle on the concatenated sequence (causality: appending tokens
+never changes earlier rows, pinned in test_oracle_pins.py); the rows of the decoded tokens are compared.
+The indices the HIP path kept at each routing step are read back from the state and injected into the
+oracle after being checked against the oracle's own Top-lambda (exact wherever the score gap > 1e-5).
+"""
+import numpy as np
+import pytest
+
+from oracle import still_oracle as O
+from paper_2602_02180_amd import binding as S
+from paper_2602_02180_amd import synth
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False):
+    """Prefill tokens [0, n_prefill) with state_out (or start from an empty state), then decode up to n_total."""
+    import torch
+
+    dev = "cuda"
+    full = {k: synth.to_torch(inp[k], w.dtype, dev) for k in ("q", "k", "v", "Wq", "Wk")}
+    g_full = synth.to_torch(inp["g"], w.dtype, dev) if with_gate else None
+    B = w.B
+    out = torch.full((B, n_total, w.Hq, w.d), float("nan"), dtype=full["q"].dtype, device=dev)
+    base = dict(B=B, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype=w.dtype,
+                d_f=w.df, kv_head_of_q=kv_map, max_tokens=n_total)
+    ps = S.make_params(N=1, **base)
+    state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
+    S.still_state_init(ps, state)
+    if n_prefill > 0:
+        q0, k0, v0 = (full[n][:, :n_prefill].contiguous() for n in ("q", "k", "v"))
+        g0 = g_full[:, :n_prefill].contiguous() if with_gate else None
+        o0 = torch.empty_like(q0)
+        p0 = S.make_params(N=n_prefill, q=q0, k=k0, v=v0, out=o0, g=g0, **base)
+        ws = torch.empty(S.still_fwd_workspace_bytes(p0), dtype=torch.uint8, device=dev)
+        S.still_hybrid_attn_fwd(p0, q0, k0, v0, g0, full["Wq"], None, full["Wk"], None, o0, state_out=state,
+                                workspace=ws)
+        out[:, :n_prefill] = o0
+    for t in range(n_prefill, n_total):
+        qt = full["q"][:, t].contiguous()
+        kt = full["k"][:, t].contiguous()
+        vt = full["v"][:, t].contiguous()
+        gt = g_full[:, t].contiguous() if with_gate else None
+        ot = torch.empty_like(qt)
+        S.still_hybrid_attn_decode_step(ps, state, t, qt, kt, vt, gt, full["Wq"], None, full["Wk"], None, ot)
+        out[:, t] = ot
+    torch.cuda.synchronize()
+    L = S.still_state_layout(ps)
+    n_routed = max(0, (n_total - 1) // w.C - 1)
+    sel = state[L.sel:L.sel + B * w.Hq * L.n_chunks * max(w.lam, 1) * 4].view(torch.int32)
+    sel = sel.reshape(B, w.Hq, L.n_chunks, max(w.lam, 1)).cpu().numpy().astype(np.int64)[:, :, :n_routed, :w.lam]
+    return synth.from_torch(out), sel
+
+
+def check_decode(w, inp, n_prefill, n_total, with_gate=False):
+    got, sel_h = run_decode(w, inp, n_prefill, n_total, with_gate=with_gate)
+    kv_map = synth.kv_head_map(w)
+    sub = {k: (v[:, :n_total] if k in ("q", "k", "v", "g") else v) for k, v in inp.items() if k != "heavy"}
+    if not with_gate:
+        sub.pop("g", None)
+    worst = 0.0
+    for b in range(w.B):
+        for h in range(w.Hq):
+            own = O.still_forward_units(sub, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps)[(b, h)]
+            n_routed = sel_h.shape[2]
+            ncf = n_total // w.C
+            sel_full = own["sel"].copy()
+            # routed chunks: the HIP path's choice must be the oracle's wherever the gap is clear
+            gaps = O.selection_gaps(own["score"], w.C, w.lam)
+            for c in range(n_routed):
+                if gaps[c] > 1e-5:
+                    assert np.array_equal(sel_h[b, h, c], own["sel"][c]), (b, h, c)
+                sel_full[c] = sel_h[b, h, c]
+            ref = O.still_forward_units(sub, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                                        sel=sel_full[None, None].repeat(w.B, 0).repeat(w.Hq, 1))[(b, h)]
+            x = got[b, n_prefill:n_total, h].astype(np.float64)
+            y = ref["out"][n_prefill:n_total]
+            assert np.all(np.isfinite(x))
+            if w.dtype == "f32":
+                err = max(U.rel_err(x, y), U.row_rel_err(x, y))
+                assert err <= 1e-4, (b, h, err)
+            else:
+                err = float(np.max(np.abs(x - y) / (2e-2 + 2.0 ** -8 * np.abs(y))))
+                assert err <= 1.0, (b, h, err)
+            worst = max(worst, err)
+    print(f"[decode {w.name} prefill={n_prefill} total={n_total}] worst error measure {worst:.3e}")
+
+
+def wl(name, **kw):
+    base = dict(B=1, N=512, Hq=2, Hkv=1, d=64, C=64, W=64, lam=16, dtype="f32")
+    base.update(kw)
+    return synth.Workload(name, **base)
+
+
+@pytest.mark.parametrize("kw,n_total", [
+    (dict(dtype="f32", d=64, C=64, W=64), 300),
+    (dict(dtype="bf16", d=128, C=64, W=128, Hq=4, Hkv=2, B=2), 330),
+    (dict(dtype="f32", d=64, C=128, W=100, lam=5), 400),
+])
+def test_decode_from_empty_state(kw, n_total):
+    w = wl("dec0", **kw)
+    inp = synth.make_inputs(w, seed=21, n_tokens=n_total)
+    check_decode(w, inp, 0, n_total)
+
+
+@pytest.mark.parametrize("kw,n_prefill,n_total", [
+    (dict(dtype="f32", d=64, C=64, W=64), 200, 340),            # prefill ends inside a chunk
+    (dict(dtype="f32", d=64, C=64, W=64), 256, 400),            # prefill ends on a chunk boundary
+    (dict(dtype="bf16", d=128, C=128, W=128, Hq=4, Hkv=2), 700, 1000),
+    (dict(dtype="bf16", d=64, C=64, W=33, lam=0), 130, 300),
+    (dict(dtype="f32", d=64, C=64, W=64, lam=64), 130, 300),
+    (dict(dtype="f32", d=64, C=64, W=64), 50, 200),             # prefill shorter than a chunk
+])
+def test_decode_continues_prefill(kw, n_prefill, n_total):
+    w = wl("dec1", **kw)
+    inp = synth.make_inputs(w, seed=22, n_tokens=n_total)
+    check_decode(w, inp, n_prefill, n_total)
+
+
+def test_decode_with_gate():
+    w = wl("decg", dtype="f32", d=64, C=64, W=64, lam=8)
+    inp = synth.make_inputs(w, seed=23, n_tokens=280, with_gate=True)
+    check_decode(w, inp, 150, 280, with_gate=True)
+
+
+def test_decode_rejects_token_beyond_capacity():
+    import torch
+
+    w = wl("deccap")
+    ps = S.make_params(B=1, N=1, Hq=2, Hkv=1, d=64, C=64, W=64, lam=16, scale=0.125, eps=1e-6, dtype="f32",
+                       max_tokens=128)
+    state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device="cuda")
+    S.still_state_init(ps, state)
+    x = torch.zeros((1, 2, 64), device="cuda")
+    kx = torch.zeros((1, 1, 64), device="cuda")
+    Wm = torch.zeros((2, 64, 64), device="cuda")
+    with pytest.raises(S.StillError) as e:
+        S.still_hybrid_attn_decode_step(ps, state, 128, x, kx, kx, None, Wm, None, Wm, None, torch.empty_like(x))
+    assert e.value.code == S.STILL_ERR_STATE
