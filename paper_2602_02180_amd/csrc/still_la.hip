@@ -73,6 +73,7 @@ __device__ __forceinline__ void np_map_tile(const typename Mma<T>::frag (&xf)[D 
 #pragma unroll
       for (int s = 0; s < KS; ++s) w[(ft + 1) & 1][s] = M::load(wrow + (int64_t)(32 * (ft + 1)) * D + s * M::KK);
     }
+    __builtin_amdgcn_sched_barrier(0);  // keep the requests ahead of this tile's MFMAs
     floatx16 acc = zero16();
 #pragma unroll
     for (int s = 0; s < KS; ++s) acc = M::mma(w[ft & 1][s], xf[s], acc);
@@ -256,9 +257,11 @@ __global__ __launch_bounds__((D / 32 + C / 32) * 64) void la_kernel(LaArgs a) {
 #pragma unroll
         for (int s = 0; s < KS; ++s) xnext[s] = M::load(xp + s * M::KK);
       }
+      __builtin_amdgcn_sched_barrier(0);  // the prefetch is issued here, not sunk into the arithmetic below
       unsigned char* slot = smem + (u & 1) * SLOT;
       if (!x.valid) {
         T* kcol = reinterpret_cast<T*>(slot) + 32 * tt + r;   // absent chunk: contributes nothing
+#pragma unroll 1
         for (int f = g; f < DP; f += 2) kcol[f * L::KSTRIDE] = from_f32<T>(0.f);
       } else {
         floatx16 pp[FT], pn[FT];
