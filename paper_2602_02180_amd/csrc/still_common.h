@@ -56,6 +56,21 @@ struct Mma<bf16> {
     return f;
   }
   static constexpr int STEPS_PER_TILE = 2;  // k-steps covering one 32-position tile
+  // acc + sum of the fragment's elements, in fp32, on the ROUNDED bf16 values (v_dot2c_f32_bf16 with ones)
+  static __device__ __forceinline__ float sum_into(frag f, float acc) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 one;
+    one[0] = static_cast<__bf16>(1.0f);
+    one[1] = static_cast<__bf16>(1.0f);
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      bf16x2 pr;
+      pr[0] = f[e];
+      pr[1] = f[e + 1];
+      acc = __builtin_amdgcn_fdot2_f32_bf16(pr, one, acc, false);
+    }
+    return acc;
+  }
 };
 
 template <>
@@ -74,6 +89,7 @@ struct Mma<float> {
   static __device__ __forceinline__ frag load(const float* p) { return *p; }
   static __device__ __forceinline__ frag from_acc(const floatx16& c, int s /*0..15*/) { return c[s]; }
   static constexpr int STEPS_PER_TILE = 16;
+  static __device__ __forceinline__ float sum_into(frag f, float acc) { return acc + f; }
 };
 
 // natural C-layout row of accumulator register i for lane group g

@@ -5,7 +5,7 @@
 //   (ii) the whole previous chunk and its own chunk up to t (s_prev, s_in with the causal mask),
 // giving N_SA, D_SA; the epilogue adds the linear-attention terms and divides once:
 //   y = (N_SA + N_LA) / (D_SA + D_LA).
-// The softmax sums are kept relative to a running maximum m (online softmax); the linear terms are not
+// The softmax sums are kept relative to a per-row reference m (online softmax); the linear terms are not
 // exponentials, so both branches are brought to the common factor exp(-max(m, 0)) before the division
 // (any common positive factor cancels; this one can neither overflow nor lose the larger branch).
 //
@@ -13,54 +13,78 @@
 // Everything is computed transposed so that one lane owns one query row:
 //   S^T (keys x queries)  = K_tile (A operand, from LDS)  x  Q^T (B operand, registers)
 //   O^T (d    x queries) += V^T_tile (A operand, from LDS) x  P^T (B operand = S^T accumulators, in place)
-// Row statistics are then per-lane reductions plus one exchange with lane^32 per tile.
-// K tiles (64 keys x d) and V^T tiles (d x 64 keys) are double-buffered in LDS: one barrier per tile, the
-// global loads of tile i+2 are in flight while tile i+1 is computed.  Retained keys come from the compacted
-// per-head buffers, local keys from k and from the token-contiguous transposed copy of v.
+// Data movement: K tiles (64 keys x d) and V^T tiles (d x 64 keys) go from global memory straight into LDS
+// (global_load_lds, 16 bytes per lane, no staging registers).  Such a load writes lane L's bytes at
+// base + 16 L, so the tiles are unpadded and bank conflicts are avoided by an XOR swizzle of the 16-byte
+// column index, applied on the global-address side when loading and on the LDS-address side when reading.
+// Software pipeline inside every wave, per iteration i:
+//   request K(i+2), V(i+1)  |  S(i+1) = K(i+1) Q^T on the matrix core  |  softmax of S(i) on the vector ALU
+//   |  O += V(i) P(i)  |  wait for own requests, barrier
+// so the MFMAs of the next tile's logits run under the current tile's exponentials.
+// The reference m only moves when a row maximum exceeds it by more than 2^8 (the exponentials then stay
+// below 2^8, harmless in fp32/bf16), which removes almost all rescales of O.
 // Workgroups of one (batch, head) are placed on one XCD (block ids are dealt round-robin to the 8 XCDs), so
 // the head's retained K/V (2 MB at 32K tokens) is served from that XCD's L2; long rows are scheduled first.
 #include "still_kernels.h"
 
 namespace still {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 template <typename T, int D>
 struct SaCfg {
   typedef Mma<T> M;
   static constexpr int BM = 128, BN = 64, NW = 4;
-  static constexpr int PAD = 16 / sizeof(T);
-  static constexpr int KST = D + PAD;    // K tile row stride (elements)
-  static constexpr int VST = BN + PAD;   // V^T tile row stride
-  static constexpr int EPV = 16 / sizeof(T);                 // elements per 16-byte vector
-  static constexpr int KPT = BN * D / EPV / 256;             // 16-byte vectors per thread, K tile
-  static constexpr int VPT = D * BN / EPV / 256;             // same, V^T tile
-  static constexpr int BUF_ELEMS = BN * KST + D * VST;
-  static constexpr size_t smem_bytes = 2 * sizeof(T) * BUF_ELEMS;
+  static constexpr int EPV = 16 / sizeof(T);          // elements per 16-byte vector
+  static constexpr int KVR = D / EPV;                 // vectors per K row
+  static constexpr int VVR = BN / EPV;                // vectors per V^T row
+  static constexpr int K_ELEMS = BN * D;              // one K tile
+  static constexpr int V_ELEMS = D * BN;              // one V^T tile
+  static constexpr int K_INSTR = K_ELEMS / EPV / 64 / NW;   // direct-to-LDS requests per wave and tile
+  static constexpr int V_INSTR = V_ELEMS / EPV / 64 / NW;
+  static constexpr size_t smem_bytes = 2 * sizeof(T) * (K_ELEMS + V_ELEMS);
+  // swizzles: XOR applied to the 16-byte column index of a row
+  // (a 128-byte row holds 8 columns and two rows share a pass over the banks; longer rows hold >= 16)
+  static __device__ __forceinline__ int kswz(int row) { return KVR == 8 ? ((row >> 1) & 7) : (row & 15); }
+  static __device__ __forceinline__ int vswz(int row) { return VVR == 8 ? ((row >> 1) & 7) : (row & 15); }
+  // element offset inside a tile of element (row, e) with e the element index along the row
+  static __device__ __forceinline__ int koff(int row, int e) {
+    return row * D + ((((e / EPV) ^ kswz(row))) * EPV) + (e % EPV);
+  }
+  static __device__ __forceinline__ int voff(int row, int e) {
+    return row * BN + ((((e / EPV) ^ vswz(row))) * EPV) + (e % EPV);
+  }
 };
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// S^T tile (64 keys x 32 queries) = K tile x Q^T
+template <typename T, int D>
+__device__ __forceinline__ void sa_qk(const T* __restrict__ Ks, const typename Mma<T>::frag (&qf)[D / Mma<T>::KK],
+                                      floatx16 (&st)[2], int r, int g) {
+  typedef Mma<T> M;
+  typedef SaCfg<T, D> Cf;
+  constexpr int KS = D / M::KK;
+  st[0] = zero16();
+  st[1] = zero16();
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    const int e = s * M::KK + g * M::KPL;
+    st[0] = M::mma(M::load(Ks + Cf::koff(r, e)), qf[s], st[0]);
+    st[1] = M::mma(M::load(Ks + Cf::koff(32 + r, e)), qf[s], st[1]);
+  }
+}
 
 // MASK: 0 = every key of the tile is visible to every row of the wave, 1 = retained tile with a ragged end,
 //       2 = local tile (window start and causal limit)
 template <typename T, int D, int MASK>
-__device__ __forceinline__ void sa_tile(const T* __restrict__ Ks, const T* __restrict__ Vs,
-                                        const typename Mma<T>::frag (&qf)[D / Mma<T>::KK], floatx16 (&o)[D / 32],
-                                        float& m2, float& lpart, int kb, int ret_w, int lo_w, int t, float sc2,
-                                        int r, int g) {
+__device__ __forceinline__ void sa_softmax_pv(const T* __restrict__ Vs, floatx16 (&st)[2], floatx16 (&o)[D / 32],
+                                              float& m_ref, float& lpart, int kb, int ret_w, int lo_w, int t,
+                                              float sc2, int r, int g) {
   typedef Mma<T> M;
   typedef SaCfg<T, D> Cf;
-  constexpr int KS = D / M::KK;
   constexpr int DT = D / 32;
   constexpr int SPT = M::STEPS_PER_TILE;
+  constexpr float TAU = 8.f;
 
-  floatx16 st[2];
-  st[0] = zero16();
-  st[1] = zero16();
-  const T* krow = Ks + r * Cf::KST + g * M::KPL;
-#pragma unroll
-  for (int s = 0; s < KS; ++s) {
-    st[0] = M::mma(M::load(krow + s * M::KK), qf[s], st[0]);
-    st[1] = M::mma(M::load(krow + 32 * Cf::KST + s * M::KK), qf[s], st[1]);
-  }
   if (MASK != 0) {
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -77,52 +101,52 @@ __device__ __forceinline__ void sa_tile(const T* __restrict__ Ks, const T* __res
 #pragma unroll
   for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, st[1][i]);
   tmax = fmaxf(tmax, xor32(tmax));
-  const float m_new = fmaxf(m2, tmax * sc2);
-  const float m_sub = (MASK != 0 && m_new == -INFINITY) ? 0.f : m_new;
-  if (__any(m_new > m2)) {  // wave-uniform: skip the rescale once the running maxima have settled
-    const float alpha = fast_exp2(m2 - m_sub);
+  const float tm = tmax * sc2;
+  if (__any(tm > m_ref + TAU)) {  // wave-uniform; rare once the references have settled
+    const float m_new = fmaxf(m_ref, tm);
+    const float alpha = m_new == -INFINITY ? 1.f : fast_exp2(m_ref - m_new);
     lpart *= alpha;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;
+    m_ref = m_new;
   }
-  m2 = m_new;
-  float rs = 0.f;
+  const float m_sub = (MASK != 0 && m_ref == -INFINITY) ? 0.f : m_ref;
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float pv = fast_exp2(fmaf(st[mt][i], sc2, -m_sub));
-      st[mt][i] = pv;
-      rs += pv;
-    }
-  lpart += rs;
-  // O^T += V^T P^T
-  const T* vrow = Vs + r * Cf::VST + g * M::KPL;
+    for (int i = 0; i < 16; ++i) st[mt][i] = fast_exp2(fmaf(st[mt][i], sc2, -m_sub));
+  // O^T += V^T P^T.  The row sums are taken over the ROUNDED operand values (one dot-with-ones per pair on
+  // bf16), so that numerator and normaliser see the same weights: a row dominated by one key then returns
+  // that key's value exactly, whatever the reference m is.
+  float rs = 0.f;
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
     for (int s = 0; s < SPT; ++s) {
       const typename M::frag pf = M::from_acc(st[mt], s);
-      const int koff = 32 * mt + s * M::KK;
+      rs = M::sum_into(pf, rs);
+      const int e = 32 * mt + s * M::KK + g * M::KPL;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) o[dt] = M::mma(M::load(vrow + 32 * dt * Cf::VST + koff), pf, o[dt]);
+      for (int dt = 0; dt < DT; ++dt) o[dt] = M::mma(M::load(Vs + Cf::voff(32 * dt + r, e)), pf, o[dt]);
     }
+  lpart += rs;
 }
 
+// (a __device__ body behind a thin __global__ wrapper: the direct-to-LDS builtin exists on the device side
+// only, and the host pass must still be able to emit the kernel's launch stub)
 template <typename T, int D>
-__global__ __launch_bounds__(256, 2) void sa_kernel(SaArgs a) {
+__device__ __forceinline__ void sa_body(const SaArgs& a) {
   typedef Mma<T> M;
   typedef SaCfg<T, D> Cf;
   constexpr int KS = D / M::KK;
   constexpr int DT = D / 32;
   constexpr int BN = Cf::BN;
-  constexpr int VR = D / Cf::EPV;   // 16-byte vectors per K row
-  constexpr int VV = BN / Cf::EPV;  // 16-byte vectors per V^T row
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  T* lds = reinterpret_cast<T*>(smem);
+  T* Kl = reinterpret_cast<T*>(smem);                 // two K tiles
+  T* Vl = Kl + 2 * Cf::K_ELEMS;                       // two V^T tiles
 
   // block id -> (unit = batch*Hq + head, row tile); units are dealt to XCDs, long tiles first
   int unit, tile;
@@ -163,49 +187,69 @@ __global__ __launch_bounds__(256, 2) void sa_kernel(SaArgs a) {
   const T* __restrict__ vtl = static_cast<const T*>(a.vt) + ((int64_t)b * a.Hkv + kvh) * (int64_t)D * a.Np;
   const T* __restrict__ kret = static_cast<const T*>(a.kret) + ((int64_t)b * a.Hq + hq) * (int64_t)a.cap * D;
   const T* __restrict__ vrett = static_cast<const T*>(a.vrett) + ((int64_t)b * a.Hq + hq) * (int64_t)D * a.cap;
+  const int kst = (int)a.k_st;
 
-  // per-thread slots of the cooperative tile copy
-  const int kp = tid / VR, kvec = tid % VR;           // K: row kp (+ 256/VR per step), vector kvec
-  const int vx = tid / VV, vvec = tid % VV;           // V^T: row vx (+ 256/VV per step), vector vvec
-  constexpr int KROWS_PER_STEP = 256 / VR;
-  constexpr int VROWS_PER_STEP = 256 / VV;
-
-  u32x4 kreg[Cf::KPT], vreg[Cf::VPT];
-
-#define SA_GLOAD(TI)                                                                                       \
-  {                                                                                                        \
-    const int ti_ = (TI);                                                                                  \
-    const bool ret_ = ti_ < n_ret_tiles;                                                                   \
-    const int kb_ = ret_ ? ti_ * BN : loc_lo + (ti_ - n_ret_tiles) * BN;                                   \
-    _Pragma("unroll") for (int j = 0; j < Cf::KPT; ++j) {                                                  \
-      const int p_ = kp + j * KROWS_PER_STEP;                                                              \
-      int tok_ = kb_ + p_;                                                                                 \
-      tok_ = tok_ < N ? tok_ : N - 1;                                                                      \
-      const T* src_ = ret_ ? kret + (int64_t)(kb_ + p_) * D : kloc + (int64_t)tok_ * a.k_st;               \
-      kreg[j] = *reinterpret_cast<const u32x4*>(src_ + kvec * Cf::EPV);                                    \
-    }                                                                                                      \
-    const T* vsrc_ = ret_ ? vrett : vtl;                                                                   \
-    const int64_t vstride_ = ret_ ? a.cap : a.Np;                                                          \
-    _Pragma("unroll") for (int j = 0; j < Cf::VPT; ++j) {                                                  \
-      const int x_ = vx + j * VROWS_PER_STEP;                                                              \
-      vreg[j] = *reinterpret_cast<const u32x4*>(vsrc_ + (int64_t)x_ * vstride_ + kb_ + vvec * Cf::EPV);    \
-    }                                                                                                      \
+  // Per-lane constants of the direct-to-LDS requests.  Request j of this wave fills the 1 KB LDS segment
+  // number (wave + 4 j) of a tile; lane L lands at segment + 16 L, i.e. at LDS (row, slot); it therefore
+  // fetches the global 16-byte column  slot ^ swizzle(row)  of the key (K) or feature row (V^T) that LDS row holds.
+  int k_key[Cf::K_INSTR], k_col[Cf::K_INSTR], v_row[Cf::V_INSTR], v_col[Cf::V_INSTR];
+#pragma unroll
+  for (int j = 0; j < Cf::K_INSTR; ++j) {
+    const int v = (wave + 4 * j) * 64 + lane;          // 16-byte vector index inside the tile
+    const int lrow = v / Cf::KVR, slot = v % Cf::KVR;
+    k_key[j] = (lrow & ~31) + M::kappa(lrow & 31);     // LDS row lrow holds key kappa(lrow) of its 32-block
+    k_col[j] = (slot ^ Cf::kswz(lrow)) * Cf::EPV;
+  }
+#pragma unroll
+  for (int j = 0; j < Cf::V_INSTR; ++j) {
+    const int v = (wave + 4 * j) * 64 + lane;
+    const int lrow = v / Cf::VVR, slot = v % Cf::VVR;
+    v_row[j] = lrow;
+    v_col[j] = (slot ^ Cf::vswz(lrow)) * Cf::EPV;
   }
 
-#define SA_LSTORE(BUF)                                                                                     \
-  {                                                                                                        \
-    T* Ks_ = lds + (BUF) * Cf::BUF_ELEMS;                                                                  \
-    T* Vs_ = Ks_ + BN * Cf::KST;                                                                           \
-    _Pragma("unroll") for (int j = 0; j < Cf::KPT; ++j) {                                                  \
-      const int p_ = kp + j * KROWS_PER_STEP;                                                              \
-      const int row_ = (p_ & ~31) + M::kappa_inv(p_ & 31);                                                 \
-      *reinterpret_cast<u32x4*>(Ks_ + row_ * Cf::KST + kvec * Cf::EPV) = kreg[j];                          \
-    }                                                                                                      \
-    _Pragma("unroll") for (int j = 0; j < Cf::VPT; ++j) {                                                  \
-      const int x_ = vx + j * VROWS_PER_STEP;                                                              \
-      *reinterpret_cast<u32x4*>(Vs_ + x_ * Cf::VST + vvec * Cf::EPV) = vreg[j];                            \
-    }                                                                                                      \
-  }
+  auto tile_kb = [&](int ti) { return ti < n_ret_tiles ? ti * BN : loc_lo + (ti - n_ret_tiles) * BN; };
+
+  auto request_k = [&](int ti) {
+    const bool ret = ti < n_ret_tiles;
+    const int kb = tile_kb(ti);
+    T* dst = Kl + (ti & 1) * Cf::K_ELEMS;
+#pragma unroll
+    for (int j = 0; j < Cf::K_INSTR; ++j) {
+      const T* src;
+      if (ret) {
+        src = kret + ((kb + k_key[j]) * D + k_col[j]);
+      } else {
+        int tok = kb + k_key[j];
+        tok = tok < N ? tok : N - 1;
+        src = kloc + (tok * kst + k_col[j]);
+      }
+      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(dst + (wave + 4 * j) * 64 * Cf::EPV), 16, 0, 0);
+    }
+  };
+  auto request_v = [&](int ti) {
+    const bool ret = ti < n_ret_tiles;
+    const int kb = tile_kb(ti);
+    T* dst = Vl + (ti & 1) * Cf::V_ELEMS;
+    const T* vsrc = ret ? vrett : vtl;
+    const int vstride = ret ? a.cap : a.Np;
+#pragma unroll
+    for (int j = 0; j < Cf::V_INSTR; ++j) {
+      const T* src = vsrc + (v_row[j] * vstride + kb + v_col[j]);
+      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(dst + (wave + 4 * j) * 64 * Cf::EPV), 16, 0, 0);
+    }
+  };
+  // wave-uniform: does this wave use tile ti, and with which mask variant
+  auto tile_mode = [&](int ti) -> int {   // -1 = skip
+    if (!wave_active) return -1;
+    const int kb = tile_kb(ti);
+    if (ti < n_ret_tiles) {
+      if (kb + BN <= ret_w) return 0;
+      return kb < ret_w ? 1 : -1;
+    }
+    if (kb + BN - 1 < lo_w || kb > q0 + 31) return -1;
+    return (kb >= lo_w && kb + BN - 1 <= q0) ? 0 : 2;
+  };
 
   // queries of this wave (B operand of S^T = K Q^T)
   typename M::frag qf[KS];
@@ -220,42 +264,43 @@ __global__ __launch_bounds__(256, 2) void sa_kernel(SaArgs a) {
   floatx16 o[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) o[dt] = zero16();
-  float m2 = -INFINITY, lpart = 0.f;
+  float m_ref = -INFINITY, lpart = 0.f;
   const float sc2 = a.scale * kLog2e;
 
-  SA_GLOAD(0);
-  SA_LSTORE(0);
+  // ---- prologue: K(0), V(0), K(1) resident; S(0) computed
+  request_k(0);
+  request_v(0);
+  if (n_tiles > 1) request_k(1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   lds_barrier();
-  if (n_tiles > 1) SA_GLOAD(1);
+  floatx16 st_cur[2], st_next[2];
+  if (tile_mode(0) >= 0) sa_qk<T, D>(Kl, qf, st_cur, r, g);
+  lds_barrier();   // every wave has read K(0) before its slot is refilled with K(2)
 
   for (int ti = 0; ti < n_tiles; ++ti) {
-    const bool ret = ti < n_ret_tiles;
-    const int kb = ret ? ti * BN : loc_lo + (ti - n_ret_tiles) * BN;
-    const T* Ks = lds + (ti & 1) * Cf::BUF_ELEMS;
-    const T* Vs = Ks + BN * Cf::KST;
-    if (wave_active) {
-      if (ret) {
-        if (kb + BN <= ret_w)
-          sa_tile<T, D, 0>(Ks, Vs, qf, o, m2, lpart, kb, ret_w, lo_w, t, sc2, r, g);
-        else if (kb < ret_w)
-          sa_tile<T, D, 1>(Ks, Vs, qf, o, m2, lpart, kb, ret_w, lo_w, t, sc2, r, g);
-      } else if (kb + BN - 1 >= lo_w && kb <= q0 + 31) {
-        if (kb >= lo_w && kb + BN - 1 <= q0)
-          sa_tile<T, D, 0>(Ks, Vs, qf, o, m2, lpart, kb, ret_w, lo_w, t, sc2, r, g);
-        else
-          sa_tile<T, D, 2>(Ks, Vs, qf, o, m2, lpart, kb, ret_w, lo_w, t, sc2, r, g);
-      }
-    }
-    if (ti + 1 < n_tiles) SA_LSTORE((ti + 1) & 1);
+    if (ti + 2 < n_tiles) request_k(ti + 2);          // into the slot S(ti) was computed from
+    if (ti + 1 < n_tiles) request_v(ti + 1);          // into the slot the previous iteration's P V read
+    const int mode_next = ti + 1 < n_tiles ? tile_mode(ti + 1) : -1;
+    if (mode_next >= 0) sa_qk<T, D>(Kl + ((ti + 1) & 1) * Cf::K_ELEMS, qf, st_next, r, g);
+    const int mode = tile_mode(ti);
+    const T* Vs = Vl + (ti & 1) * Cf::V_ELEMS;
+    const int kb = tile_kb(ti);
+    if (mode == 0)
+      sa_softmax_pv<T, D, 0>(Vs, st_cur, o, m_ref, lpart, kb, ret_w, lo_w, t, sc2, r, g);
+    else if (mode == 1)
+      sa_softmax_pv<T, D, 1>(Vs, st_cur, o, m_ref, lpart, kb, ret_w, lo_w, t, sc2, r, g);
+    else if (mode == 2)
+      sa_softmax_pv<T, D, 2>(Vs, st_cur, o, m_ref, lpart, kb, ret_w, lo_w, t, sc2, r, g);
+    st_cur[0] = st_next[0];
+    st_cur[1] = st_next[1];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();
-    if (ti + 2 < n_tiles) SA_GLOAD(ti + 2);
   }
-#undef SA_GLOAD
-#undef SA_LSTORE
 
   // ---- merge epilogue
   if (wave_active && t < N) {
     const float l = lpart + xor32(lpart);
+    const float m2 = m_ref;
     float fs, fl;
     if (m2 >= 0.f) {
       fs = 1.f;
@@ -291,6 +336,11 @@ __global__ __launch_bounds__(256, 2) void sa_kernel(SaArgs a) {
         }
       }
   }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256, 2) void sa_kernel(SaArgs a) {
+  sa_body<T, D>(a);
 }
 
 template <typename T, int D>
