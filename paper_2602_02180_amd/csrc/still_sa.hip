@@ -191,52 +191,68 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
 
   // Per-lane constants of the direct-to-LDS requests.  Request j of this wave fills the 1 KB LDS segment
   // number (wave + 4 j) of a tile; lane L lands at segment + 16 L, i.e. at LDS (row, slot); it therefore
-  // fetches the global 16-byte column  slot ^ swizzle(row)  of the key (K) or feature row (V^T) that LDS row holds.
-  int k_key[Cf::K_INSTR], k_col[Cf::K_INSTR], v_row[Cf::V_INSTR], v_col[Cf::V_INSTR];
+  // fetches the global 16-byte column  slot ^ swizzle(row)  of the key (K) or feature row (V^T) that LDS row
+  // holds.  Every request is "tile base (wave-uniform) + constant per-lane element offset", so a tile costs
+  // no per-lane address arithmetic.
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  uint32_t k_off_ret[Cf::K_INSTR], k_off_loc[Cf::K_INSTR], v_off_ret[Cf::V_INSTR], v_off_loc[Cf::V_INSTR];
+  int k_key[Cf::K_INSTR], k_col[Cf::K_INSTR];
 #pragma unroll
   for (int j = 0; j < Cf::K_INSTR; ++j) {
     const int v = (wave + 4 * j) * 64 + lane;          // 16-byte vector index inside the tile
     const int lrow = v / Cf::KVR, slot = v % Cf::KVR;
     k_key[j] = (lrow & ~31) + M::kappa(lrow & 31);     // LDS row lrow holds key kappa(lrow) of its 32-block
     k_col[j] = (slot ^ Cf::kswz(lrow)) * Cf::EPV;
+    k_off_ret[j] = (uint32_t)(k_key[j] * D + k_col[j]);
+    k_off_loc[j] = (uint32_t)(k_key[j] * kst + k_col[j]);
   }
 #pragma unroll
   for (int j = 0; j < Cf::V_INSTR; ++j) {
     const int v = (wave + 4 * j) * 64 + lane;
     const int lrow = v / Cf::VVR, slot = v % Cf::VVR;
-    v_row[j] = lrow;
-    v_col[j] = (slot ^ Cf::vswz(lrow)) * Cf::EPV;
+    const int col = (slot ^ Cf::vswz(lrow)) * Cf::EPV;
+    v_off_ret[j] = (uint32_t)(lrow * a.cap + col);
+    v_off_loc[j] = (uint32_t)(lrow * a.Np + col);
   }
 
   auto tile_kb = [&](int ti) { return ti < n_ret_tiles ? ti * BN : loc_lo + (ti - n_ret_tiles) * BN; };
 
   auto request_k = [&](int ti) {
-    const bool ret = ti < n_ret_tiles;
     const int kb = tile_kb(ti);
-    T* dst = Kl + (ti & 1) * Cf::K_ELEMS;
+    T* dst = Kl + (ti & 1) * Cf::K_ELEMS + wave_s * 64 * Cf::EPV;
+    if (ti < n_ret_tiles) {
+      const T* base = kret + (int64_t)kb * D;
 #pragma unroll
-    for (int j = 0; j < Cf::K_INSTR; ++j) {
-      const T* src;
-      if (ret) {
-        src = kret + ((kb + k_key[j]) * D + k_col[j]);
-      } else {
+      for (int j = 0; j < Cf::K_INSTR; ++j)
+        __builtin_amdgcn_global_load_lds(base + k_off_ret[j], (lds_ptr_t)(dst + 4 * j * 64 * Cf::EPV), 16, 0, 0);
+    } else if (kb + BN <= N) {
+      const T* base = kloc + (int64_t)kb * kst;
+#pragma unroll
+      for (int j = 0; j < Cf::K_INSTR; ++j)
+        __builtin_amdgcn_global_load_lds(base + k_off_loc[j], (lds_ptr_t)(dst + 4 * j * 64 * Cf::EPV), 16, 0, 0);
+    } else {   // last tile of a ragged sequence: rows past the end re-read the last token (masked later)
+#pragma unroll
+      for (int j = 0; j < Cf::K_INSTR; ++j) {
         int tok = kb + k_key[j];
         tok = tok < N ? tok : N - 1;
-        src = kloc + (tok * kst + k_col[j]);
+        __builtin_amdgcn_global_load_lds(kloc + ((int64_t)tok * kst + k_col[j]),
+                                         (lds_ptr_t)(dst + 4 * j * 64 * Cf::EPV), 16, 0, 0);
       }
-      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(dst + (wave + 4 * j) * 64 * Cf::EPV), 16, 0, 0);
     }
   };
   auto request_v = [&](int ti) {
-    const bool ret = ti < n_ret_tiles;
     const int kb = tile_kb(ti);
-    T* dst = Vl + (ti & 1) * Cf::V_ELEMS;
-    const T* vsrc = ret ? vrett : vtl;
-    const int vstride = ret ? a.cap : a.Np;
+    T* dst = Vl + (ti & 1) * Cf::V_ELEMS + wave_s * 64 * Cf::EPV;
+    if (ti < n_ret_tiles) {
+      const T* base = vrett + kb;
 #pragma unroll
-    for (int j = 0; j < Cf::V_INSTR; ++j) {
-      const T* src = vsrc + (v_row[j] * vstride + kb + v_col[j]);
-      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(dst + (wave + 4 * j) * 64 * Cf::EPV), 16, 0, 0);
+      for (int j = 0; j < Cf::V_INSTR; ++j)
+        __builtin_amdgcn_global_load_lds(base + v_off_ret[j], (lds_ptr_t)(dst + 4 * j * 64 * Cf::EPV), 16, 0, 0);
+    } else {
+      const T* base = vtl + kb;
+#pragma unroll
+      for (int j = 0; j < Cf::V_INSTR; ++j)
+        __builtin_amdgcn_global_load_lds(base + v_off_loc[j], (lds_ptr_t)(dst + 4 * j * 64 * Cf::EPV), 16, 0, 0);
     }
   };
   // wave-uniform: does this wave use tile ti, and with which mask variant
@@ -273,13 +289,14 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   if (n_tiles > 1) request_k(1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   lds_barrier();
-  floatx16 st_cur[2], st_next[2];
-  if (tile_mode(0) >= 0) sa_qk<T, D>(Kl, qf, st_cur, r, g);
+  floatx16 st_a[2], st_b[2];
+  if (tile_mode(0) >= 0) sa_qk<T, D>(Kl, qf, st_a, r, g);
   lds_barrier();   // every wave has read K(0) before its slot is refilled with K(2)
 
-  for (int ti = 0; ti < n_tiles; ++ti) {
+  // one pipeline step: st_cur holds S(ti); S(ti+1) is started into st_next before the softmax of S(ti)
+  auto step = [&](int ti, floatx16 (&st_cur)[2], floatx16 (&st_next)[2]) {
     if (ti + 2 < n_tiles) request_k(ti + 2);          // into the slot S(ti) was computed from
-    if (ti + 1 < n_tiles) request_v(ti + 1);          // into the slot the previous iteration's P V read
+    if (ti + 1 < n_tiles) request_v(ti + 1);          // into the slot the previous step's P V read
     const int mode_next = ti + 1 < n_tiles ? tile_mode(ti + 1) : -1;
     if (mode_next >= 0) sa_qk<T, D>(Kl + ((ti + 1) & 1) * Cf::K_ELEMS, qf, st_next, r, g);
     const int mode = tile_mode(ti);
@@ -291,10 +308,12 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       sa_softmax_pv<T, D, 1>(Vs, st_cur, o, m_ref, lpart, kb, ret_w, lo_w, t, sc2, r, g);
     else if (mode == 2)
       sa_softmax_pv<T, D, 2>(Vs, st_cur, o, m_ref, lpart, kb, ret_w, lo_w, t, sc2, r, g);
-    st_cur[0] = st_next[0];
-    st_cur[1] = st_next[1];
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();
+  };
+  for (int ti = 0; ti < n_tiles; ti += 2) {           // two steps per trip: the S tiles swap roles, no copies
+    step(ti, st_a, st_b);
+    if (ti + 1 < n_tiles) step(ti + 1, st_b, st_a);
   }
 
   // ---- merge epilogue
