@@ -82,12 +82,116 @@ def cpu_baseline(w: synth.Workload, inp, budget_s: float = 20.0):
                       f"numpy float64 chunk-wise form, {el:.1f} s; scaled by 1/Hq to whole-layer tokens/s"}
 
 
+def decode_bench(args) -> int:
+    """Config 5: B sequences with a prefilled 32K context, then single-token steps.  The contexts are drawn
+    on the GPU (seeded torch generator, same distributions as synth.make_inputs) and prefilled in slices of
+    8 sequences through still_hybrid_attn_fwd with state_out; one timed step = one decode step for all B."""
+    import torch
+    from paper_2602_02180_amd import binding as S
+
+    w = synth.CONFIGS["c5"]
+    dev = "cuda"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    B, N, Hq, Hkv, d = w.B, w.N, w.Hq, w.Hkv, w.d
+    n_steps = args.steps if args.steps else w.decode_steps
+    max_tokens = N + n_steps + args.warmup + 8
+    bf = torch.bfloat16
+
+    def lognormal(*shape):
+        return torch.exp(0.5 * torch.randn(*shape, generator=gen, device=dev))
+
+    sq, sk, sv = lognormal(Hq, d), lognormal(Hkv, d), lognormal(Hkv, d)
+    Wq = (torch.randn(Hq, d, d, generator=gen, device=dev) / d ** 0.5).to(bf)
+    Wk = (torch.randn(Hq, d, d, generator=gen, device=dev) / d ** 0.5).to(bf)
+    base = dict(B=B, Hq=Hq, Hkv=Hkv, d=d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype="bf16",
+                max_tokens=max_tokens)
+    ps = S.make_params(N=1, **base)
+    L = S.still_state_layout(ps)
+    state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
+    S.still_state_init(ps, state)
+    # prefill in slices of SB sequences into per-slice states, then scatter into the batch state
+    SB = 8
+    pslice = S.make_params(N=1, **{**base, "B": SB})
+    Ls = S.still_state_layout(pslice)
+    st_slice = torch.empty(S.still_state_bytes(pslice), dtype=torch.uint8, device=dev)
+    regions = [("S", 4 * 2 * d * (d + 1) * Hq), ("kret", 2 * L.cap * d * Hq), ("vret", 2 * L.cap * d * Hq),
+               ("sel", 4 * L.n_chunks * w.lam * Hq), ("kring", 2 * L.R * d * Hkv), ("vring", 2 * L.R * d * Hkv),
+               ("score", 4 * L.R * Hq), ("part", 4 * 32 * (d + 2) * Hq)]
+    t_prefill = 0.0
+    for b0 in range(0, B, SB):
+        q = (torch.randn(SB, N, Hq, d, generator=gen, device=dev) * sq).to(bf)
+        k = torch.randn(SB, N, Hkv, d, generator=gen, device=dev) * sk
+        v = (torch.randn(SB, N, Hkv, d, generator=gen, device=dev) * sv).to(bf)
+        n_heavy = int(w.heavy_frac * N)
+        for i in range(SB):
+            idx = torch.randperm(N, generator=gen, device=dev)[:n_heavy]
+            k[i, idx] *= w.heavy_mult
+        k = k.to(bf)
+        o = torch.empty_like(q)
+        pf = S.make_params(N=N, q=q, k=k, v=v, out=o, **{**base, "B": SB})
+        ws = torch.empty(S.still_fwd_workspace_bytes(pf), dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        S.still_hybrid_attn_fwd(pf, q, k, v, None, Wq, None, Wk, None, o, state_out=st_slice, workspace=ws)
+        torch.cuda.synchronize()
+        t_prefill += time.perf_counter() - t0
+        for name, per_seq in regions:   # every region is [B, ...]: copy the slice's sequences into place
+            src0, dst0 = getattr(Ls, name), getattr(L, name)
+            state[dst0 + b0 * per_seq: dst0 + (b0 + SB) * per_seq] = st_slice[src0: src0 + SB * per_seq]
+        del q, k, v, o, ws
+    torch.cuda.empty_cache()
+
+    def draw_step():
+        q = (torch.randn(B, Hq, d, generator=gen, device=dev) * sq).to(bf)
+        k = (torch.randn(B, Hkv, d, generator=gen, device=dev) * sk).to(bf)
+        v = (torch.randn(B, Hkv, d, generator=gen, device=dev) * sv).to(bf)
+        return q, k, v
+
+    toks = [draw_step() for _ in range(args.warmup + n_steps)]
+    out = torch.empty(B, Hq, d, dtype=bf, device=dev)
+    t = N
+    for i in range(args.warmup):
+        S.still_hybrid_attn_decode_step(ps, state, t, *toks[i], None, Wq, None, Wk, None, out)
+        t += 1
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_steps)]
+    t0 = time.perf_counter()
+    for i in range(n_steps):
+        ev[i][0].record()
+        S.still_hybrid_attn_decode_step(ps, state, t, *toks[args.warmup + i], None, Wq, None, Wk, None, out)
+        ev[i][1].record()
+        t += 1
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    lat = np.array([a.elapsed_time(b) for a, b in ev])
+    routing = np.array([((N + args.warmup + i) % w.C) == 0 for i in range(n_steps)])
+    c = (N + args.warmup) // w.C
+    rows = (c - 1) * w.lam + (N + args.warmup - (c - 1) * w.C + 1)
+    bytes_step = B * Hq * (rows * 2 * d * 2 + (2 * d * (d + 1)) * 4)
+    ordinary = float(np.median(lat[~routing])) if (~routing).any() else float("nan")
+    rec = {
+        "metric": "hybrid-attn decode tokens/s @32K context, Llama-3-8B layer shape", "value": B * n_steps / el,
+        "unit": "tokens/s", "n_gpus": 1, "steps": n_steps, "warmup": args.warmup, "ms_per_step": el / n_steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"c5: B={B} context={N} Hq={Hq} Hkv={Hkv} d={d} C={w.C} W={w.W} lambda={w.lam}",
+                   "median_ordinary_step_ms": ordinary,
+                   "routing_step_ms": [float(x) for x in lat[routing]],
+                   "prefill_of_contexts_s": t_prefill, "state_gb": state.numel() / 1e9},
+        "roofline": {"bound": "hbm", "kernel": "decode step (attend + finish)", "achieved": bytes_step / (ordinary * 1e-3) / 1e9,
+                     "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": bytes_step / (ordinary * 1e-3) / PEAK_HBM,
+                     "traffic": args.traffic_bytes, "algorithmic_bytes_per_step": bytes_step},
+    }
+    print(json.dumps(rec))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 20 prefill calls, 128 decode steps)")
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc runs)")
@@ -105,6 +209,10 @@ def main() -> int:
         return 2
     S.lib()  # fail loudly if the HIP library is missing
 
+    if args.config == "c5":
+        return decode_bench(args)
+    if not args.steps:
+        args.steps = 20
     w = synth.CONFIGS[args.config]
     inp = synth.make_inputs(w)
     dev = "cuda"
