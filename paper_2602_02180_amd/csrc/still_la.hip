@@ -405,8 +405,11 @@ __global__ __launch_bounds__((D / 32 + C / 32) * 64) void la_kernel(LaArgs a) {
     for (int u = 1; u + 1 < n_units; u += 2) {
       consume_k(u);
       lds_barrier();
+      // V of the next K unit is requested BEFORE this unit's N_LA stores: the vector-memory counter retires
+      // in order, so a later wait for these loads does not have to wait for the stores as well
+      if (u + 2 < n_units) load_v(u + 2);
+      __builtin_amdgcn_sched_barrier(0);
       consume_q(u + 1);
-      if (u + 2 < n_units) load_v(u + 2);   // requested before the barrier: the wait hides the latency
       lds_barrier();
     }
   } else {
