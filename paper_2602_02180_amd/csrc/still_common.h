@@ -123,6 +123,16 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Lane index within the wave, recomputed by two instructions at the point of the call.  The asm is opaque to the
+// compiler, so the value (and every address derived from it) has a short live range: in kernels whose register
+// file is full of accumulators this keeps lane-dependent addresses from being computed once up front and then
+// spilled to scratch memory, whose reloads queue behind the outstanding global prefetches.
+__device__ __forceinline__ int fresh_lane_id() {
+  int l;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+  return l;
+}
+
 // Block id -> (query head, work item) with the head varying fastest, so that workgroups running at the same
 // time read the SAME token range of q/k/v for different heads: in the [B, N, H, d] layout one token's rows of
 // all heads are contiguous, and a DRAM page fetched for one head is used by the others while it is open.

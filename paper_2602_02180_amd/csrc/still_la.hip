@@ -28,6 +28,7 @@
 // Units alternate "queries of chunk c" / "keys of chunk c-1" so that the outputs of chunk c see the state
 // through chunk c-2; one barrier per unit hands a slot from producers to consumers.
 #include "still_kernels.h"
+#include <type_traits>
 
 namespace still {
 
@@ -36,113 +37,29 @@ struct LaPad {
   static constexpr int value = 16 / sizeof(T);
 };
 
-// Feature map of 32 tokens (one per lane column) from their preloaded rows xf (B operand fragments).
-// On return pp[ft][i] / pn[ft][i] hold phi's first / second half, multiplied by `keep`, at feature
-// 32*ft + pos_of_reg(i, g) for the token of this lane.  The W^T fragments of the next feature tile are
-// requested before the current tile's MFMAs so that only the first request's latency is exposed.
-template <typename T, int D, int DF>
-__device__ __forceinline__ void np_map_tile(const typename Mma<T>::frag (&xf)[D / Mma<T>::KK],
-                                            const T* __restrict__ wt_head /* [DF][D] */,
-                                            const T* __restrict__ bias /* [DF] or null */, float keep, int r,
-                                            int g, floatx16 (&pp)[DF / 32], floatx16 (&pn)[DF / 32]) {
-  typedef Mma<T> M;
-  constexpr int KS = D / M::KK;
-  constexpr int FT = DF / 32;
-  float nx2 = 0.f;
-#pragma unroll
-  for (int s = 0; s < KS; ++s) {
-    if constexpr (M::KPL == 1) {
-      nx2 += xf[s] * xf[s];
-    } else {
-#pragma unroll
-      for (int e = 0; e < M::KPL; ++e) {
-        const float xv = to_f32(xf[s][e]);
-        nx2 += xv * xv;
-      }
-    }
-  }
-  nx2 += xor32(nx2);
-  typename M::frag w[2][KS];
-  const T* wrow = wt_head + (int64_t)M::kappa(r) * D + g * M::KPL;
-#pragma unroll
-  for (int s = 0; s < KS; ++s) w[0][s] = M::load(wrow + s * M::KK);
-  float nf2 = 0.f, fmax = -INFINITY, fmin = INFINITY;
-#pragma unroll
-  for (int ft = 0; ft < FT; ++ft) {
-    if (ft + 1 < FT) {
-#pragma unroll
-      for (int s = 0; s < KS; ++s) w[(ft + 1) & 1][s] = M::load(wrow + (int64_t)(32 * (ft + 1)) * D + s * M::KK);
-    }
-    __builtin_amdgcn_sched_barrier(0);  // keep the requests ahead of this tile's MFMAs
-    floatx16 acc = zero16();
-#pragma unroll
-    for (int s = 0; s < KS; ++s) acc = M::mma(w[ft & 1][s], xf[s], acc);
-    if (bias != nullptr) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[i] += to_f32(bias[32 * ft + M::pos_of_reg(i, g)]);
-    }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      nf2 = fmaf(acc[i], acc[i], nf2);
-      fmax = fmaxf(fmax, acc[i]);
-      fmin = fminf(fmin, acc[i]);
-    }
-    pp[ft] = acc;
-  }
-  nf2 += xor32(nf2);
-  fmax = fmaxf(fmax, xor32(fmax));
-  fmin = fminf(fmin, xor32(fmin));
-  // u = f * ratio with ratio = ||x|| / ||f|| >= 0, so max/min of u are ratio * max/min of f;
-  // exp(u - umax) = exp2(f * a1 - fmax * a1),  exp(umin - u) = exp2(fmin * a1 - f * a1)
-  const float ratio = nf2 > 0.f ? sqrtf(nx2 / nf2) : 0.f;
-  const float a1 = ratio * kLog2e;
-  const float bp = -fmax * a1, bn = fmin * a1;
-  float sp = 0.f, sn = 0.f;
-#pragma unroll
-  for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float f = pp[ft][i];
-      const float ep = fast_exp2(fmaf(f, a1, bp));
-      const float en = fast_exp2(fmaf(f, -a1, bn));
-      pp[ft][i] = ep;
-      pn[ft][i] = en;
-      sp += ep;
-      sn += en;
-    }
-  sp += xor32(sp);
-  sn += xor32(sn);
-  const float ip = keep / sp, in = keep / sn;
-#pragma unroll
-  for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      pp[ft][i] *= ip;
-      pn[ft][i] *= in;
-    }
-}
-
+// sum over the fragment's k positions of  f[e] * w[e]
 template <typename T>
-__device__ __forceinline__ float frag_dot(typename Mma<T>::frag f, const float* __restrict__ z) {
+__device__ __forceinline__ float frag_dot(typename Mma<T>::frag f, const float* __restrict__ w) {
   if constexpr (Mma<T>::KPL == 1) {
-    return f * z[0];
+    return f * w[0];
   } else {
     float acc = 0.f;
 #pragma unroll
-    for (int e = 0; e < Mma<T>::KPL; ++e) acc += to_f32(f[e]) * z[e];
+    for (int e = 0; e < Mma<T>::KPL; ++e) acc += to_f32(f[e]) * w[e];
     return acc;
   }
 }
 
+// fragment with element e multiplied by w[e] (rounded back to the operand type)
 template <typename T>
-__device__ __forceinline__ float frag_sum(typename Mma<T>::frag f) {
+__device__ __forceinline__ typename Mma<T>::frag frag_scale(typename Mma<T>::frag f, const float* __restrict__ w) {
   if constexpr (Mma<T>::KPL == 1) {
-    return f;
+    return f * w[0];
   } else {
-    float acc = 0.f;
+    typename Mma<T>::frag o;
 #pragma unroll
-    for (int e = 0; e < Mma<T>::KPL; ++e) acc += to_f32(f[e]);
-    return acc;
+    for (int e = 0; e < Mma<T>::KPL; ++e) o[e] = from_f32<T>(to_f32(f[e]) * w[e]);
+    return o;
   }
 }
 
@@ -150,6 +67,7 @@ template <typename T, int D, int DF, int C>
 struct LaSmem {
   static constexpr int DP = 2 * DF;
   static constexpr int PAD = LaPad<T>::value;
+  static constexpr int NM = D / 32, NV = DF / 32, CT = C / 32;
   static constexpr int KSTRIDE = C + PAD;   // phik row stride (elements)
   static constexpr int QSTRIDE = DP + PAD;  // phiq row stride
   static constexpr size_t phik_bytes = sizeof(T) * DP * KSTRIDE;
@@ -157,37 +75,56 @@ struct LaSmem {
   static constexpr size_t slot_bytes(int mode) {
     return (mode && phiq_bytes > phik_bytes) ? phiq_bytes : phik_bytes;
   }
+  static constexpr size_t stat_bytes = sizeof(float) * 2 * NV * 32 * 4;   // [tile of the sub-unit][wave][token]{nf2,max,min,-}
+  static constexpr size_t sums_bytes = sizeof(float) * 2 * 2 * NV * C;    // [parity][half][wave][token]
+  static constexpr size_t inv_bytes = sizeof(float) * NM * 2 * C;         // [consumer wave][half][token]
   static constexpr size_t z_bytes = sizeof(float) * DP;
-  static constexpr size_t total(int mode) { return 2 * slot_bytes(mode) + z_bytes; }
+  static constexpr size_t keep_bytes = NV * C;                            // [producer wave][token] flags
+  static constexpr size_t total(int mode) {
+    return 2 * slot_bytes(mode) + stat_bytes + sums_bytes + inv_bytes + z_bytes + keep_bytes;
+  }
 };
 
 // One work unit of the scan: either the queries of chunk `chunk` (kind 0) or the keys of chunk `chunk`
-// that are folded into the state (kind 1).  `valid` false = an empty pipeline slot.
+// that are folded into the state (kind 1).  `valid` false = a chunk that does not exist or is not routed;
+// it is produced with every token masked, so it contributes nothing.
 struct LaUnit {
   int kind, chunk;
   bool valid;
 };
 
+template <int V>
+using IC = std::integral_constant<int, V>;
+
 template <typename T, int D, int DF, int C, int MODE>
-__global__ __launch_bounds__((D / 32 + C / 32) * 64) void la_kernel(LaArgs a) {
+__global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
   typedef Mma<T> M;
   typedef LaSmem<T, D, DF, C> L;
   constexpr int DP = 2 * DF;
-  constexpr int NM = D / 32;     // consumer (MFMA) waves: wave w owns value columns [32w, 32w+32)
-  constexpr int NV = C / 32;     // producer (feature-map) waves: wave NM+v owns tokens [32v, 32v+32) of a unit
+  constexpr int NM = D / 32;     // consumer (state) waves: wave w owns value columns [32w, 32w+32)
+  constexpr int NV = DF / 32;    // producer (feature-map) waves: wave NM+v owns features [32v, 32v+32) of f
   constexpr int FT = DF / 32;    // feature tiles per half
   constexpr int PT = DP / 32;    // feature tiles of the state
   constexpr int CT = C / 32;     // token tiles per chunk
+  constexpr int NSUB = CT / 2;   // sub-units (two token tiles) per unit
+  constexpr int NPART = 2 * NSUB;  // barrier-separated parts per unit = token tiles per chunk
   constexpr int SPT = M::STEPS_PER_TILE;
+  constexpr int KS = D / M::KK;  // k-steps over the head dimension
+  constexpr int VS = C / M::KK;  // k-steps over the tokens of a chunk
   constexpr size_t SLOT = L::slot_bytes(MODE);
+  static_assert(NPART == CT, "one token tile per part");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  float* zsh = reinterpret_cast<float*>(smem + 2 * SLOT);
+  float* stat = reinterpret_cast<float*>(smem + 2 * SLOT);
+  float* sums = reinterpret_cast<float*>(smem + 2 * SLOT + L::stat_bytes);
+  float* invs = reinterpret_cast<float*>(smem + 2 * SLOT + L::stat_bytes + L::sums_bytes);
+  float* zsh = reinterpret_cast<float*>(smem + 2 * SLOT + L::stat_bytes + L::sums_bytes + L::inv_bytes);
+  unsigned char* keep = smem + 2 * SLOT + L::stat_bytes + L::sums_bytes + L::inv_bytes + L::z_bytes;
 
   int seg, hq;
   head_major_block(blockIdx.x, a.Hq, hq, seg);
   const int b = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r = lane & 31, g = lane >> 5;
   const bool consumer = wave < NM;
   const int kvh = a.map.kv[hq];
@@ -209,8 +146,6 @@ __global__ __launch_bounds__((D / 32 + C / 32) * 64) void la_kernel(LaArgs a) {
   const int c_end = MODE == 1 ? (c_beg + G < a.nc ? c_beg + G : a.nc) : c_beg + G;
   // Unit list.  Output pass: Q(c_beg), then for every later chunk c of the segment K(c-2), Q(c): the
   // outputs of chunk c see the state through chunk c-2.  State pass: K(c_beg-1) .. K(c_beg+G-2).
-  // A K unit whose chunk does not exist (before the sequence start, or not a full chunk) is produced as
-  // zeros, so the consumer code is straight-line.
   const int n_units = MODE == 1 ? 2 * (c_end - c_beg) - 1 : G;
   auto unit_at = [&](int u) {
     LaUnit x;
@@ -227,76 +162,210 @@ __global__ __launch_bounds__((D / 32 + C / 32) * 64) void la_kernel(LaArgs a) {
     return x;
   };
 
-  // ---- producer waves: feature map of 32 tokens of every unit, one unit ahead of the consumers.
-  // The token rows of the following unit are requested before the current unit's arithmetic.
-  // Producer and consumer waves run separate loops with the same number of barriers (the barrier counts
-  // waves, and a wave never diverges inside itself here), so the state registers are live only in the
-  // consumer path and the feature-map temporaries only in the producer path.
+  // A unit is produced in NSUB sub-units of two token tiles, each taking two workgroup barriers: projection
+  // and partial statistics, barrier, exponentials into slot u&1, barrier.  Consumers run one unit behind and
+  // do one of the NPART parts of their unit between consecutive barriers.  Both roles execute
+  // NPART * (n_units + 1) barriers.
   if (!consumer) {
-    constexpr int KS = D / M::KK;
-    const int tt = wave - NM;
-    auto row_ptr = [&](const LaUnit& x) -> const T* {
+    // ---- producer wave v: features [32v, 32v+32) of f = x W for ALL tokens of the unit.  Its 32 rows of W^T
+    // stay in registers, so the projection weights are read once per unit instead of once per token tile.
+    // The statistics that span the whole feature dimension (||f||^2, max f, min f per token) are combined
+    // across the producer waves through LDS.  The exponentials are written UN-normalised, next to this
+    // wave's partial softmax sums; the consumers fold 1/sum into their own operands.
+    const int v = wave - NM;
+    auto row_ptr = [&](const LaUnit& x, int tt, int r, int g) -> const T* {
       int tok = x.chunk * C + 32 * tt + r;
       tok = tok < N ? tok : N - 1;
       tok = tok < 0 ? 0 : tok;
       return (x.kind == 0 ? qbase + (int64_t)tok * a.q_st : kbase + (int64_t)tok * a.k_st) + g * M::KPL;
     };
-    typename M::frag xnext[KS];
-    {
-      const T* xp = row_ptr(unit_at(0));
+    typename M::frag xb[2][KS];    // token rows of the sub-unit (B operand), refilled right after their use
+    typename M::frag w[KS];        // this wave's rows of W^T (A operand) for the current unit kind
+    int32_t selv[2];               // Top-lambda list of the next K unit, entries lane and lane + 64
+    unsigned char* keepb = keep + v * C;   // this wave's private table: 1 = token goes to the linear state
+    auto load_w = [&](int kind, int r, int g) {
+      const T* wrow = (kind == 0 ? wqt : wkt) + (int64_t)(32 * v + M::kappa(r)) * D + g * M::KPL;
 #pragma unroll
-      for (int s = 0; s < KS; ++s) xnext[s] = M::load(xp + s * M::KK);
-    }
-    for (int u = 0; u < n_units; ++u) {
+      for (int s = 0; s < KS; ++s) w[s] = M::load(wrow + s * M::KK);
+    };
+    auto load_x = [&](const LaUnit& x, int tt, int j, int r, int g) {
+      const T* xp = row_ptr(x, tt, r, g);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) xb[j][s] = M::load(xp + s * M::KK);
+    };
+    auto load_sel = [&](const LaUnit& x, int lane) {
+      const int32_t* selc = a.sel + (((int64_t)b * a.Hq + hq) * a.ncf + (x.valid ? x.chunk : 0)) * a.lam;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) selv[j] = (x.valid && lane + 64 * j < a.lam) ? selc[lane + 64 * j] : -1;
+    };
+
+    // One unit.  kind_c: 0 = queries, 1 = keys; next_c: kind of the following unit, -1 if there is none.
+    auto produce = [&](int u, auto kind_c, auto next_c) __attribute__((always_inline)) {
+      constexpr int kind = decltype(kind_c)::value;
+      constexpr int next = decltype(next_c)::value;
       const LaUnit x = unit_at(u);
-      typename M::frag xf[KS];
-#pragma unroll
-      for (int s = 0; s < KS; ++s) xf[s] = xnext[s];
-      if (u + 1 < n_units) {
-        const T* xp = row_ptr(unit_at(u + 1));
-#pragma unroll
-        for (int s = 0; s < KS; ++s) xnext[s] = M::load(xp + s * M::KK);
-      }
-      __builtin_amdgcn_sched_barrier(0);  // the prefetch is issued here, not sunk into the arithmetic below
+      const LaUnit xn = unit_at(next >= 0 ? u + 1 : u);
+      const T* bias = kind == 0 ? bq : bk;
       unsigned char* slot = smem + (u & 1) * SLOT;
-      if (!x.valid) {
-        T* kcol = reinterpret_cast<T*>(slot) + 32 * tt + r;   // absent chunk: contributes nothing
-#pragma unroll 1
-        for (int f = g; f < DP; f += 2) kcol[f * L::KSTRIDE] = from_f32<T>(0.f);
-      } else {
-        floatx16 pp[FT], pn[FT];
-        if (x.kind == 0) {
-          np_map_tile<T, D, DF>(xf, wqt, bq, 1.f, r, g, pp, pn);
-          T* qrow = reinterpret_cast<T*>(slot) + (32 * tt + r) * L::QSTRIDE;
+      float* sums_u = sums + (u & 1) * (2 * NV * C);
+      // Lane ids are re-derived per sub-unit: the many lane-dependent LDS and global addresses
+      // below are then recomputed where they are used (a few integer operations each) instead of being kept
+      // in registers across the whole scan, where they would not fit.
+      int lane = fresh_lane_id(), r = lane & 31, g = lane >> 5;
+      if (kind == 1) {
+        // keep table of this K unit from the list requested during the previous unit; the wave's own LDS
+        // accesses are processed in order, so the later reads need no barrier
+        for (int t = lane; t < C; t += 64) keepb[t] = x.valid ? 1 : 0;
 #pragma unroll
-          for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-            for (int s = 0; s < SPT; ++s) {
-              const int p0 = 32 * ft + s * M::KK + g * M::KPL;
-              *reinterpret_cast<typename M::frag*>(qrow + p0) = M::from_acc(pp[ft], s);
-              *reinterpret_cast<typename M::frag*>(qrow + DF + p0) = M::from_acc(pn[ft], s);
-            }
-        } else {
-          const int tl = 32 * tt + r;                 // token inside the (full) chunk
-          const int tok = x.chunk * C + tl;
-          float kf = 1.f;                             // 0 for tokens kept by the softmax branch
-          const int32_t* selc = a.sel + (((int64_t)b * a.Hq + hq) * a.ncf + x.chunk) * a.lam;
-          for (int j = 0; j < a.lam; ++j) kf = (selc[j] == tok) ? 0.f : kf;
-          np_map_tile<T, D, DF>(xf, wkt, bk, kf, r, g, pp, pn);
-          T* kcol = reinterpret_cast<T*>(slot) + tl;
-#pragma unroll
-          for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int f = 32 * ft + M::pos_of_reg(i, g);
-              kcol[f * L::KSTRIDE] = from_f32<T>(pp[ft][i]);
-              kcol[(DF + f) * L::KSTRIDE] = from_f32<T>(pn[ft][i]);
-            }
+        for (int j = 0; j < 2; ++j) {
+          const unsigned off = (unsigned)(selv[j] - x.chunk * C);
+          if (selv[j] >= 0 && off < (unsigned)C) keepb[off] = 0;
         }
       }
-      lds_barrier();
+#pragma unroll
+      for (int sub = 0; sub < NSUB; ++sub) {
+        if (sub > 0) {
+          lane = fresh_lane_id(); r = lane & 31; g = lane >> 5;
+        }
+        floatx16 f[2];
+        float nx2[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          floatx16 acc = zero16();
+#pragma unroll
+          for (int s = 0; s < KS; ++s) acc = M::mma(w[s], xb[j][s], acc);
+          float n2 = 0.f;
+#pragma unroll
+          for (int s = 0; s < KS; ++s) {
+            if constexpr (M::KPL == 1) {
+              n2 = fmaf(xb[j][s], xb[j][s], n2);
+            } else {
+#pragma unroll
+              for (int e = 0; e < M::KPL; ++e) {
+                const float xv = to_f32(xb[j][s][e]);
+                n2 = fmaf(xv, xv, n2);
+              }
+            }
+          }
+          n2 += xor32(n2);
+          nx2[j] = n2;
+          if (bias != nullptr) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] += to_f32(bias[32 * v + M::pos_of_reg(i, g)]);
+          }
+          float nf2 = 0.f, fmax = -INFINITY, fmin = INFINITY;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            nf2 = fmaf(acc[i], acc[i], nf2);
+            fmax = fmaxf(fmax, acc[i]);
+            fmin = fminf(fmin, acc[i]);
+          }
+          nf2 += xor32(nf2);
+          fmax = fmaxf(fmax, xor32(fmax));
+          fmin = fminf(fmin, xor32(fmin));
+          if (g == 0) {
+            floatx4 st;
+            st[0] = nf2; st[1] = fmax; st[2] = fmin; st[3] = 0.f;
+            *reinterpret_cast<floatx4*>(stat + ((j * NV + v) * 32 + r) * 4) = st;
+          }
+          f[j] = acc;
+        }
+        lds_barrier();
+        lane = fresh_lane_id(); r = lane & 31; g = lane >> 5;
+        if (sub == NSUB - 1) {
+          if (next >= 0 && next != kind) load_w(next, r, g);
+          if (next == 1) load_sel(xn, lane);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int tt = 2 * sub + j;
+          float nf2 = 0.f, fmax = -INFINITY, fmin = INFINITY;
+#pragma unroll
+          for (int vv = 0; vv < NV; ++vv) {
+            const floatx4 st = *reinterpret_cast<const floatx4*>(stat + ((j * NV + vv) * 32 + r) * 4);
+            nf2 += st[0];
+            fmax = fmaxf(fmax, st[1]);
+            fmin = fminf(fmin, st[2]);
+          }
+          // u = f * ratio with ratio = ||x|| / ||f|| >= 0, so max/min of u are ratio * max/min of f;
+          // exp(u - umax) = exp2(f * a1 - fmax * a1),  exp(umin - u) = exp2(fmin * a1 - f * a1)
+          const float ratio = nf2 > 0.f ? sqrtf(nx2[j] / nf2) : 0.f;
+          const float a1 = ratio * kLog2e;
+          const float bp = -fmax * a1, bn = fmin * a1;
+          const int tl = 32 * tt + r;
+          // tokens kept by the softmax branch (and every token of an absent chunk) are stored as zeros
+          const float kf = kind == 1 ? (keepb[tl] ? 1.f : 0.f) : 1.f;
+          floatx16 ep, en;
+          float sp = 0.f, sn = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            ep[i] = fast_exp2(fmaf(f[j][i], a1, bp));
+            en[i] = fast_exp2(fmaf(f[j][i], -a1, bn));
+            sp += ep[i];
+            sn += en[i];
+          }
+          sp += xor32(sp);
+          sn += xor32(sn);
+          sums_u[(g * NV + v) * C + tl] = g ? sn : sp;   // lane group g records the sum of half g
+          if (kind == 0) {
+            T* qrow = reinterpret_cast<T*>(slot) + tl * L::QSTRIDE;
+#pragma unroll
+            for (int s = 0; s < SPT; ++s) {
+              const int p0 = 32 * v + s * M::KK + g * M::KPL;
+              *reinterpret_cast<typename M::frag*>(qrow + p0) = M::from_acc(ep, s);
+              *reinterpret_cast<typename M::frag*>(qrow + DF + p0) = M::from_acc(en, s);
+            }
+          } else {
+            T* kcol = reinterpret_cast<T*>(slot) + tl;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int fi = 32 * v + M::pos_of_reg(i, g);
+              kcol[fi * L::KSTRIDE] = from_f32<T>(ep[i] * kf);
+              kcol[(DF + fi) * L::KSTRIDE] = from_f32<T>(en[i] * kf);
+            }
+          }
+          // The rows of this token tile are dead since the projection and its f values since the lines
+          // above: request the tile that will use the same registers, one sub-unit ahead of its use.
+          if (sub + 1 < NSUB) load_x(x, tt + 2, j, r, g);
+          else if (next >= 0) load_x(xn, j, j, r, g);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        lds_barrier();
+      }
+    };
+
+    constexpr IC<0> KQ{};
+    constexpr IC<1> KK1{};
+    constexpr IC<-1> KNONE{};
+    {
+      const LaUnit x0 = unit_at(0);
+      load_x(x0, 0, 0, r, g);
+      load_x(x0, 1, 1, r, g);
+      load_w(x0.kind, r, g);
+      if (x0.kind == 1) load_sel(x0, lane);
     }
-    lds_barrier();
+    if (MODE == 1) {
+      // Q(c_beg), then K, Q pairs
+      if (n_units == 1) {
+        produce(0, KQ, KNONE);
+      } else {
+        produce(0, KQ, KK1);
+#pragma unroll 1
+        for (int u = 1; u + 1 < n_units; u += 2) {
+          produce(u, KK1, KQ);
+          if (u + 2 < n_units) produce(u + 1, KQ, KK1);
+          else produce(u + 1, KQ, KNONE);
+        }
+      }
+    } else {
+#pragma unroll 1
+      for (int u = 0; u + 1 < n_units; ++u) produce(u, KK1, KK1);
+      produce(n_units - 1, KK1, KNONE);
+    }
+#pragma unroll
+    for (int i = 0; i < NPART; ++i) lds_barrier();
     return;
   }
 
@@ -307,118 +376,229 @@ __global__ __launch_bounds__((D / 32 + C / 32) * 64) void la_kernel(LaArgs a) {
     for (int ft = 0; ft < PT; ++ft)
 #pragma unroll
       for (int i = 0; i < 16; ++i) S[ft][i] = segp[(int64_t)(32 * ft + M::pos_of_reg(i, g)) * D + col];
-    for (int f = threadIdx.x; f < DP; f += NM * 64) zsh[f] = segp[DP * D + f];
+    for (int fi = threadIdx.x; fi < DP; fi += NM * 64) zsh[fi] = segp[DP * D + fi];
   } else {
 #pragma unroll
     for (int ft = 0; ft < PT; ++ft) S[ft] = zero16();
-    for (int f = threadIdx.x; f < DP; f += NM * 64) zsh[f] = 0.f;
+    for (int fi = threadIdx.x; fi < DP; fi += NM * 64) zsh[fi] = 0.f;
   }
+  float* invw = invs + wave * (2 * C);   // this wave's private table: 1/softmax-sum per [half][token]
 
-  typename M::frag vf[C / M::KK];   // V fragments of the next K unit (B operand, k = tokens)
-  auto load_v = [&](int u) {
+  typedef typename M::frag VFrag[VS];    // V fragments of a K unit (B operand, k = tokens)
+  auto load_v = [&](int u, VFrag& vf) __attribute__((always_inline)) {
     const LaUnit x = unit_at(u);
     const int ch = x.valid ? x.chunk : 0;   // an absent chunk meets zero features; any finite V will do
     const T* vrow = vt + (int64_t)col * a.Np + (int64_t)ch * C + g * M::KPL;
 #pragma unroll
-    for (int s = 0; s < C / M::KK; ++s) vf[s] = M::load(vrow + s * M::KK);
+    for (int s = 0; s < VS; ++s) vf[s] = M::load(vrow + s * M::KK);
   };
 
-  // S += phi_k^T V, z += sum phi_k for the unit in slot `u & 1`
-  auto consume_k = [&](int u) {
+  // reciprocal softmax sums of the unit in slot u&1, from the producers' partial sums
+  auto make_inv = [&](int u) __attribute__((always_inline)) {
+    // entry lane + 64*j of the table [half][token]; every address is one lane-dependent base plus a constant
+    const int lane = fresh_lane_id();
+    const float* src = sums + (u & 1) * (2 * NV * C) + lane;
+#pragma unroll
+    for (int j = 0; j < 2 * C / 64; ++j) {
+      const int h = (64 * j) / C, t0 = (64 * j) % C;
+      float sacc = 0.f;
+#pragma unroll
+      for (int vv = 0; vv < NV; ++vv) sacc += src[(h * NV + vv) * C + t0];
+      invw[lane + 64 * j] = fast_rcp(sacc);
+    }
+  };
+
+  // S += phi_k^T V, z += sum phi_k for the unit in slot u&1, over one part (32 tokens) of the chunk.  The
+  // softmax normalisers are per token, i.e. per contracted index: they are folded into the V operand, once
+  // for each half of the feature dimension.  The phi_k fragments are read from LDS ADEPTH products ahead of
+  // their use (the scheduling barriers pin that order), so a product never waits for its own read.
+  constexpr int ADEPTH = 8;
+  auto consume_k = [&](int u, const VFrag& vf, auto part_c) __attribute__((always_inline)) {
+    constexpr int part = decltype(part_c)::value;
+    const int lane = fresh_lane_id(), r = lane & 31, g = lane >> 5;   // addresses are rebuilt here, not kept across units
+    constexpr int HS = VS / NPART;       // k-steps in this part
+    constexpr int NSTEP = HS * PT;       // products in this part
     const T* phik = reinterpret_cast<const T*>(smem + (u & 1) * SLOT);
+    const T* abase = phik + M::kappa(r) * L::KSTRIDE + part * 32 + g * M::KPL;
+    auto a_at = [&](int idx) { return M::load(abase + (32 * (idx % PT)) * L::KSTRIDE + (idx / PT) * M::KK); };
+    const float* ivp = invw + part * 32 + g * M::KPL;
+    typename M::frag af[ADEPTH];
 #pragma unroll
-    for (int s = 0; s < C / M::KK; ++s) {
+    for (int i = 0; i < ADEPTH; ++i) af[i] = a_at(i);
+    float iv[2][M::KPL];   // reciprocal sums of the next k-step's tokens, read well before they are used
 #pragma unroll
-      for (int ft = 0; ft < PT; ++ft) {
-        const typename M::frag af = M::load(phik + (32 * ft + M::kappa(r)) * L::KSTRIDE + s * M::KK + g * M::KPL);
-        S[ft] = M::mma(af, vf[s], S[ft]);
+    for (int e = 0; e < M::KPL; ++e) {
+      iv[0][e] = ivp[e];
+      iv[1][e] = ivp[C + e];
+    }
+    typename M::frag vp = frag_scale<T>(vf[part * HS], iv[0]);
+    typename M::frag vn = frag_scale<T>(vf[part * HS], iv[1]);
+    typename M::frag vp_next = vp, vn_next = vn;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int idx = 0; idx < NSTEP; ++idx) {
+      const int sh = idx / PT, ft = idx % PT;
+      if (ft == 0 && sh > 0) {
+        vp = vp_next;
+        vn = vn_next;
       }
+      S[ft] = M::mma(af[idx % ADEPTH], ft < FT ? vp : vn, S[ft]);
+      if (idx + ADEPTH < NSTEP) af[idx % ADEPTH] = a_at(idx + ADEPTH);
+      if (ft == 0 && sh + 1 < HS) {
+#pragma unroll
+        for (int e = 0; e < M::KPL; ++e) {
+          iv[0][e] = ivp[(sh + 1) * M::KK + e];
+          iv[1][e] = ivp[C + (sh + 1) * M::KK + e];
+        }
+      }
+      if (ft == PT - 2 && sh + 1 < HS) vp_next = frag_scale<T>(vf[part * HS + sh + 1], iv[0]);
+      if (ft == PT - 1 && sh + 1 < HS) vn_next = frag_scale<T>(vf[part * HS + sh + 1], iv[1]);
+      __builtin_amdgcn_sched_barrier(0);
     }
     // row sums of the same LDS rows, PT/NM feature tiles per consumer wave, outside the MFMA loop
     constexpr int ZT = PT / NM;
-#pragma unroll 1
+#pragma unroll
     for (int j = 0; j < ZT; ++j) {
       const int ft = wave * ZT + j;
-      const T* zrow = phik + (32 * ft + r) * L::KSTRIDE + g * M::KPL;
+      const T* zrow = phik + (32 * ft + r) * L::KSTRIDE + part * 32 + g * M::KPL;
+      const float* izp = invw + (j * NM >= FT ? 0 : 0) + part * 32 + g * M::KPL;
       float zp = 0.f;
 #pragma unroll
-      for (int s = 0; s < C / M::KK; ++s) zp += frag_sum<T>(M::load(zrow + s * M::KK));
+      for (int sh = 0; sh < HS; ++sh)
+        zp += frag_dot<T>(M::load(zrow + sh * M::KK), izp + (ft >= FT ? C : 0) + sh * M::KK);
       zp += xor32(zp);
       if (g == 0) zsh[32 * ft + r] += zp;
     }
   };
 
-  // N_LA = phi_q S and D_LA = phi_q z for the rows of the chunk in slot `u & 1`
-  auto consume_q = [&](int u) {
+  // N_LA = phi_q S and D_LA = phi_q z for token tile `part` of the chunk in slot u&1.  Each half of the
+  // feature dimension gets its own accumulator; the per-token normalisers scale the two partial products
+  // when they are combined.
+  auto consume_q = [&](int u, auto part_c) __attribute__((always_inline)) {
+    constexpr int mt = decltype(part_c)::value;
+    const int lane = fresh_lane_id(), r = lane & 31, g = lane >> 5;   // addresses are rebuilt here, not kept across units
+    const int col = 32 * wave + r;
     const LaUnit x = unit_at(u);
     const T* phiq = reinterpret_cast<const T*>(smem + (u & 1) * SLOT);
     float* nrow = a.n_la + ((int64_t)b * a.Hq + hq) * (int64_t)N * D;
-    // two token tiles at a time keeps the accumulators next to the state registers
-#pragma unroll 1
-    for (int mh = 0; mh < CT; mh += 2) {
-      floatx16 o[2];
-      o[0] = zero16();
-      o[1] = zero16();
+    // The operand-type copies of S are made again for every token tile: kept across tiles (the state does
+    // not change between them) they would need as many registers as the state itself.
 #pragma unroll
-      for (int ft = 0; ft < PT; ++ft)
+    for (int ft = 0; ft < PT; ++ft) asm volatile("" : "+v"(S[ft]));
+    floatx16 op = zero16(), on = zero16();
+    const T* arow = phiq + (32 * mt + r) * L::QSTRIDE + g * M::KPL;
+    // product idx: feature k-step idx/2 of half idx%2 (first half accumulates into op, second into on)
+    constexpr int NQ = 2 * FT * SPT;
+    auto a_at = [&](int idx) { return M::load(arow + (idx & 1) * DF + (idx >> 1) * M::KK); };
+    auto b_at = [&](int idx) { return M::from_acc(S[(idx & 1) * FT + (idx >> 1) / SPT], (idx >> 1) % SPT); };
+    typename M::frag af[ADEPTH];
 #pragma unroll
-        for (int s = 0; s < SPT; ++s) {
-          const typename M::frag bf = M::from_acc(S[ft], s);
-          const int p0 = 32 * ft + s * M::KK + g * M::KPL;
-          o[0] = M::mma(M::load(phiq + (32 * mh + r) * L::QSTRIDE + p0), bf, o[0]);
-          o[1] = M::mma(M::load(phiq + (32 * mh + 32 + r) * L::QSTRIDE + p0), bf, o[1]);
-        }
+    for (int i = 0; i < ADEPTH; ++i) af[i] = a_at(i);
+    typename M::frag bcur = b_at(0);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int mm = 0; mm < 2; ++mm)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int tok = x.chunk * C + 32 * (mh + mm) + c_row(i, g);
-          if (tok < N) {
-            float val = o[mm][i];
-            if (a.g != nullptr)
-              val *= to_f32(static_cast<const T*>(a.g)[(int64_t)b * a.g_sb + (int64_t)tok * a.g_st +
-                                                       (int64_t)hq * a.g_sh + col]);
-            nrow[(int64_t)tok * D + col] = val;
-          }
-        }
+    for (int idx = 0; idx < NQ; ++idx) {
+      typename M::frag bnext = bcur;
+      if (idx + 1 < NQ) bnext = b_at(idx + 1);
+      if (idx & 1) on = M::mma(af[idx % ADEPTH], bcur, on);
+      else op = M::mma(af[idx % ADEPTH], bcur, op);
+      if (idx + ADEPTH < NQ) af[idx % ADEPTH] = a_at(idx + ADEPTH);
+      bcur = bnext;
+      __builtin_amdgcn_sched_barrier(0);
     }
-    // D_LA: this wave's share of the chunk's rows; lane group g sums feature half g
-    constexpr int TPW = C / NM;
-    for (int j = r; j < TPW; j += 32) {
-      const int tl = wave * TPW + j;
+    const bool tile_full = x.chunk * C + 32 * mt + 32 <= N;   // uniform: no per-row test in the common case
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      const int row0 = 32 * mt + 8 * i4 + 4 * g;
+      const floatx4 ip = *reinterpret_cast<const floatx4*>(invw + row0);
+      const floatx4 in = *reinterpret_cast<const floatx4*>(invw + C + row0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int tok = x.chunk * C + row0 + e;
+        if (tile_full || tok < N) {
+          float val = op[4 * i4 + e] * ip[e] + on[4 * i4 + e] * in[e];
+          if (a.g != nullptr)
+            val *= to_f32(static_cast<const T*>(a.g)[(int64_t)b * a.g_sb + (int64_t)tok * a.g_st +
+                                                     (int64_t)hq * a.g_sh + col]);
+          nrow[(int64_t)tok * D + col] = val;
+        }
+      }
+    }
+    // D_LA: this wave's share of the tile's rows; lane group g sums feature half g
+    constexpr int TPW = 32 / NM;
+    if (r < TPW) {
+      const int tl = 32 * mt + wave * TPW + r;
       const T* qrow = phiq + tl * L::QSTRIDE + g * DF;
       const float* zz = zsh + g * DF;
       float dla = 0.f;
 #pragma unroll 4
       for (int f0 = 0; f0 < DF; f0 += M::KPL) dla += frag_dot<T>(M::load(qrow + f0), zz + f0);
+      dla *= invw[g * C + tl];
       dla += xor32(dla);
       const int tok = x.chunk * C + tl;
       if (g == 0 && tok < N) a.d_la[((int64_t)b * a.Hq + hq) * N + tok] = dla;
     }
   };
 
-  if (MODE == 1) {
-    if (n_units > 1) load_v(1);
+  // all parts of one unit, a barrier after each
+  auto consume_q_unit = [&](int u) __attribute__((always_inline)) {
+    make_inv(u);
+    consume_q(u, IC<0>{});
     lds_barrier();
-    consume_q(0);
+    consume_q(u, IC<1>{});
     lds_barrier();
-    for (int u = 1; u + 1 < n_units; u += 2) {
-      consume_k(u);
+    if constexpr (NPART == 4) {
+      consume_q(u, IC<2>{});
       lds_barrier();
-      // V of the next K unit is requested BEFORE this unit's N_LA stores: the vector-memory counter retires
-      // in order, so a later wait for these loads does not have to wait for the stores as well
-      if (u + 2 < n_units) load_v(u + 2);
-      __builtin_amdgcn_sched_barrier(0);
-      consume_q(u + 1);
+      consume_q(u, IC<3>{});
       lds_barrier();
     }
-  } else {
-    load_v(0);
+  };
+  auto consume_k_unit = [&](int u, const VFrag& vf) __attribute__((always_inline)) {
+    make_inv(u);
+    consume_k(u, vf, IC<0>{});
     lds_barrier();
-    for (int u = 0; u < n_units; ++u) {
-      consume_k(u);
-      if (u + 1 < n_units) load_v(u + 1);
+    consume_k(u, vf, IC<1>{});
+    lds_barrier();
+    if constexpr (NPART == 4) {
+      consume_k(u, vf, IC<2>{});
       lds_barrier();
+      consume_k(u, vf, IC<3>{});
+      lds_barrier();
+    }
+  };
+
+  if (MODE == 1) {
+    VFrag vf;
+    if (n_units > 1) load_v(1, vf);
+#pragma unroll
+    for (int i = 0; i < NPART; ++i) lds_barrier();
+    consume_q_unit(0);
+#pragma unroll 1
+    for (int u = 1; u + 1 < n_units; u += 2) {
+      consume_k_unit(u, vf);
+      // V of the next K unit is requested BEFORE this unit's N_LA stores: the vector-memory counter retires
+      // in order, so a later wait for these loads does not have to wait for the stores as well
+      if (u + 2 < n_units) load_v(u + 2, vf);
+      __builtin_amdgcn_sched_barrier(0);
+      consume_q_unit(u + 1);
+    }
+  } else {
+    // two V buffers: the next unit's V is in flight while the current one is contracted
+    VFrag va, vb;
+    load_v(0, va);
+#pragma unroll
+    for (int i = 0; i < NPART; ++i) lds_barrier();
+#pragma unroll 1
+    for (int u = 0; u < n_units; u += 2) {
+      if (u + 1 < n_units) load_v(u + 1, vb);
+      __builtin_amdgcn_sched_barrier(0);
+      consume_k_unit(u, va);
+      if (u + 1 < n_units) {
+        if (u + 2 < n_units) load_v(u + 2, va);
+        __builtin_amdgcn_sched_barrier(0);
+        consume_k_unit(u + 1, vb);
+      }
     }
   }
 
@@ -432,7 +612,7 @@ __global__ __launch_bounds__((D / 32 + C / 32) * 64) void la_kernel(LaArgs a) {
     for (int ft = 0; ft < PT; ++ft)
 #pragma unroll
       for (int i = 0; i < 16; ++i) dst[(int64_t)(32 * ft + M::pos_of_reg(i, g)) * D + col] = S[ft][i];
-    for (int f = threadIdx.x; f < DP; f += NM * 64) dst[DP * D + f] = zsh[f];
+    for (int fi = threadIdx.x; fi < DP; fi += NM * 64) dst[DP * D + fi] = zsh[fi];
   }
 }
 
@@ -457,7 +637,7 @@ static hipError_t launch_la_t(const LaArgs& a, int B, int nblocks, hipStream_t s
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
-  dim3 grid(nblocks * a.Hq, 1, B), block((D / 32 + C / 32) * 64);
+  dim3 grid(nblocks * a.Hq, 1, B), block((D / 32 + D / 32) * 64);
   hipLaunchKernelGGL(kern, grid, block, smem, stream, a);
   return hipGetLastError();
 }
