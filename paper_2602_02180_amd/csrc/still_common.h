@@ -56,6 +56,18 @@ struct Mma<bf16> {
     return f;
   }
   static constexpr int STEPS_PER_TILE = 2;  // k-steps covering one 32-position tile
+  // acc + sum_e a[e] * b[e] in fp32 (v_dot2c_f32_bf16, two products per instruction)
+  static __device__ __forceinline__ float dot_into(frag a, frag b, float acc) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      bf16x2 pa, pb;
+      pa[0] = a[e]; pa[1] = a[e + 1];
+      pb[0] = b[e]; pb[1] = b[e + 1];
+      acc = __builtin_amdgcn_fdot2_f32_bf16(pa, pb, acc, false);
+    }
+    return acc;
+  }
   // acc + sum of the fragment's elements, in fp32, on the ROUNDED bf16 values (v_dot2c_f32_bf16 with ones)
   static __device__ __forceinline__ float sum_into(frag f, float acc) {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -90,6 +102,7 @@ struct Mma<float> {
   static __device__ __forceinline__ frag from_acc(const floatx16& c, int s /*0..15*/) { return c[s]; }
   static constexpr int STEPS_PER_TILE = 16;
   static __device__ __forceinline__ float sum_into(frag f, float acc) { return acc + f; }
+  static __device__ __forceinline__ float dot_into(frag a, frag b, float acc) { return fmaf(a, b, acc); }
 };
 
 // natural C-layout row of accumulator register i for lane group g

@@ -75,13 +75,15 @@ struct LaSmem {
   static constexpr size_t slot_bytes(int mode) {
     return (mode && phiq_bytes > phik_bytes) ? phiq_bytes : phik_bytes;
   }
-  static constexpr size_t stat_bytes = sizeof(float) * 2 * NV * 32 * 4;   // [tile of the sub-unit][wave][token]{nf2,max,min,-}
-  static constexpr size_t sums_bytes = sizeof(float) * 2 * 2 * NV * C;    // [parity][half][wave][token]
+  static constexpr int STAT_FLOATS = 2 * NV * 32 * 4;                     // one buffer: [tile][wave][token]{nf2,max,min,nx2}
+  static constexpr size_t stat_bytes = sizeof(float) * 2 * STAT_FLOATS;   // two buffers (sub-unit parity)
+  static constexpr size_t sums_bytes = sizeof(float) * 2 * 2 * NV * C;    // [unit parity][half][wave][token]
   static constexpr size_t inv_bytes = sizeof(float) * NM * 2 * C;         // [consumer wave][half][token]
   static constexpr size_t z_bytes = sizeof(float) * DP;
   static constexpr size_t keep_bytes = NV * C;                            // [producer wave][token] flags
+  static constexpr size_t warm_bytes = 256;                               // landing zone of cache-warming loads
   static constexpr size_t total(int mode) {
-    return 2 * slot_bytes(mode) + stat_bytes + sums_bytes + inv_bytes + z_bytes + keep_bytes;
+    return 2 * slot_bytes(mode) + stat_bytes + sums_bytes + inv_bytes + z_bytes + keep_bytes + warm_bytes;
   }
 };
 
@@ -96,8 +98,10 @@ struct LaUnit {
 template <int V>
 using IC = std::integral_constant<int, V>;
 
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
 template <typename T, int D, int DF, int C, int MODE>
-__global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
+__device__ __forceinline__ void la_body(const LaArgs& a) {
   typedef Mma<T> M;
   typedef LaSmem<T, D, DF, C> L;
   constexpr int DP = 2 * DF;
@@ -120,6 +124,7 @@ __global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
   float* invs = reinterpret_cast<float*>(smem + 2 * SLOT + L::stat_bytes + L::sums_bytes);
   float* zsh = reinterpret_cast<float*>(smem + 2 * SLOT + L::stat_bytes + L::sums_bytes + L::inv_bytes);
   unsigned char* keep = smem + 2 * SLOT + L::stat_bytes + L::sums_bytes + L::inv_bytes + L::z_bytes;
+  unsigned char* warm = keep + L::keep_bytes;
 
   int seg, hq;
   head_major_block(blockIdx.x, a.Hq, hq, seg);
@@ -162,16 +167,18 @@ __global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
     return x;
   };
 
-  // A unit is produced in NSUB sub-units of two token tiles, each taking two workgroup barriers: projection
-  // and partial statistics, barrier, exponentials into slot u&1, barrier.  Consumers run one unit behind and
-  // do one of the NPART parts of their unit between consecutive barriers.  Both roles execute
-  // NPART * (n_units + 1) barriers.
+  // A unit is produced in NSUB sub-units of two token tiles.  Sub-unit m takes two steps: the projection and
+  // the per-wave partial statistics in interval m, the exponentials (which need every wave's statistics) in
+  // interval m+1; one workgroup barrier ends each interval, so interval m holds the second step of sub-unit
+  // m-1 and the first step of sub-unit m, two independent instruction streams that hide each other's
+  // latencies.  The consumers handle sub-unit m in interval m+2.  Both roles execute n_units*NSUB + 2 barriers.
+  const int M_sub = n_units * NSUB;
   if (!consumer) {
-    // ---- producer wave v: features [32v, 32v+32) of f = x W for ALL tokens of the unit.  Its 32 rows of W^T
-    // stay in registers, so the projection weights are read once per unit instead of once per token tile.
-    // The statistics that span the whole feature dimension (||f||^2, max f, min f per token) are combined
-    // across the producer waves through LDS.  The exponentials are written UN-normalised, next to this
-    // wave's partial softmax sums; the consumers fold 1/sum into their own operands.
+    // ---- producer wave v: features [32v, 32v+32) of f = x W for ALL tokens.  Its 32 rows of W^T stay in
+    // registers, so the projection weights are read once per unit instead of once per token tile.  The
+    // statistics that span the whole feature dimension (||f||^2, max f, min f per token) are combined across
+    // the producer waves through LDS.  The exponentials are written UN-normalised, next to this wave's
+    // partial softmax sums; the consumers fold 1/sum into their own operands.
     const int v = wave - NM;
     auto row_ptr = [&](const LaUnit& x, int tt, int r, int g) -> const T* {
       int tok = x.chunk * C + 32 * tt + r;
@@ -179,76 +186,148 @@ __global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
       tok = tok < 0 ? 0 : tok;
       return (x.kind == 0 ? qbase + (int64_t)tok * a.q_st : kbase + (int64_t)tok * a.k_st) + g * M::KPL;
     };
-    typename M::frag xb[2][KS];    // token rows of the sub-unit (B operand), refilled right after their use
+    typename M::frag xb[2][KS];    // token rows of the next sub-unit (B operand), refilled right after their use
     typename M::frag w[KS];        // this wave's rows of W^T (A operand) for the current unit kind
+    floatx16 f[2];                 // f of the sub-unit between its two steps
     int32_t selv[2];               // Top-lambda list of the next K unit, entries lane and lane + 64
     unsigned char* keepb = keep + v * C;   // this wave's private table: 1 = token goes to the linear state
-    auto load_w = [&](int kind, int r, int g) {
+    auto load_w = [&](int kind, int r, int g) __attribute__((always_inline)) {
       const T* wrow = (kind == 0 ? wqt : wkt) + (int64_t)(32 * v + M::kappa(r)) * D + g * M::KPL;
 #pragma unroll
       for (int s = 0; s < KS; ++s) w[s] = M::load(wrow + s * M::KK);
     };
-    auto load_x = [&](const LaUnit& x, int tt, int j, int r, int g) {
+    auto load_x = [&](const LaUnit& x, int tt, int j, int r, int g) __attribute__((always_inline)) {
       const T* xp = row_ptr(x, tt, r, g);
 #pragma unroll
       for (int s = 0; s < KS; ++s) xb[j][s] = M::load(xp + s * M::KK);
     };
-    auto load_sel = [&](const LaUnit& x, int lane) {
+    auto load_sel = [&](const LaUnit& x, int lane) __attribute__((always_inline)) {
       const int32_t* selc = a.sel + (((int64_t)b * a.Hq + hq) * a.ncf + (x.valid ? x.chunk : 0)) * a.lam;
 #pragma unroll
       for (int j = 0; j < 2; ++j) selv[j] = (x.valid && lane + 64 * j < a.lam) ? selc[lane + 64 * j] : -1;
     };
+    {
+      const LaUnit x0 = unit_at(0);
+      load_x(x0, 0, 0, r, g);
+      load_x(x0, 1, 1, r, g);
+      load_w(x0.kind, r, g);
+      if (x0.kind == 1) load_sel(x0, lane);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) f[j] = zero16();
 
-    // One unit.  kind_c: 0 = queries, 1 = keys; next_c: kind of the following unit, -1 if there is none.
-    auto produce = [&](int u, auto kind_c, auto next_c) __attribute__((always_inline)) {
-      constexpr int kind = decltype(kind_c)::value;
-      constexpr int next = decltype(next_c)::value;
-      const LaUnit x = unit_at(u);
-      const LaUnit xn = unit_at(next >= 0 ? u + 1 : u);
-      const T* bias = kind == 0 ? bq : bk;
-      unsigned char* slot = smem + (u & 1) * SLOT;
-      float* sums_u = sums + (u & 1) * (2 * NV * C);
-      // Lane ids are re-derived per sub-unit: the many lane-dependent LDS and global addresses
-      // below are then recomputed where they are used (a few integer operations each) instead of being kept
-      // in registers across the whole scan, where they would not fit.
-      int lane = fresh_lane_id(), r = lane & 31, g = lane >> 5;
-      if (kind == 1) {
-        // keep table of this K unit from the list requested during the previous unit; the wave's own LDS
-        // accesses are processed in order, so the later reads need no barrier
-        for (int t = lane; t < C; t += 64) keepb[t] = x.valid ? 1 : 0;
+#pragma unroll 1
+    for (int m = 0; m <= M_sub; ++m) {
+      // Lane ids are re-derived per interval: the many lane-dependent LDS and global addresses below are
+      // then recomputed where they are used (a few integer operations each) instead of being kept in
+      // registers across the whole scan, where they would not fit.
+      const int lane = fresh_lane_id(), r = lane & 31, g = lane >> 5;
+      if (m >= 1) {
+        // ---- second step of sub-unit m-1: statistics of all waves -> exponentials -> slot
+        const int mp = m - 1, up = mp / NSUB, subp = mp % NSUB;
+        const LaUnit x = unit_at(up);
+        unsigned char* slot = smem + (up & 1) * SLOT;
+        float* sums_u = sums + (up & 1) * (2 * NV * C);
+        const float* statp = stat + (mp & 1) * L::STAT_FLOATS;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          const unsigned off = (unsigned)(selv[j] - x.chunk * C);
-          if (selv[j] >= 0 && off < (unsigned)C) keepb[off] = 0;
+          const int tl = 32 * (2 * subp + j) + r;
+          float nf2 = 0.f, fmax = -INFINITY, fmin = INFINITY, nx2 = 0.f;
+#pragma unroll
+          for (int vv = 0; vv < NV; ++vv) {
+            const floatx4 st = *reinterpret_cast<const floatx4*>(statp + ((j * NV + vv) * 32 + r) * 4);
+            nf2 += st[0];
+            fmax = fmaxf(fmax, st[1]);
+            fmin = fminf(fmin, st[2]);
+            nx2 += st[3];
+          }
+          nx2 *= NV >= 2 ? 2.f / NV : 1.f;   // NV/2 waves (all of them if NV = 1) recorded ||x||^2 of this tile
+          // u = f * ratio with ratio = ||x|| / ||f|| >= 0, so max/min of u are ratio * max/min of f;
+          // exp(u - umax) = exp2(f * a1 - fmax * a1),  exp(umin - u) = exp2(fmin * a1 - f * a1).
+          // Tokens kept by the softmax branch (and every token of an absent chunk) get -inf offsets, i.e.
+          // zero features; their (unused) sums are recorded as 1.
+          const float ratio = nf2 > 0.f ? __builtin_amdgcn_sqrtf(nx2 * fast_rcp(nf2)) : 0.f;
+          const float a1 = ratio * kLog2e;
+          const bool live = x.kind == 0 || keepb[tl] != 0;
+          const float bp = live ? -fmax * a1 : -INFINITY, bn = live ? fmin * a1 : -INFINITY;
+          floatx16 ep, en;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            ep[i] = fast_exp2(fmaf(f[j][i], a1, bp));
+            en[i] = fast_exp2(fmaf(f[j][i], -a1, bn));
+          }
+          typename M::frag pf[SPT], nf[SPT];
+          float sp = 0.f, sn = 0.f;   // sums of the ROUNDED weights: the stored features then sum to one
+#pragma unroll
+          for (int s = 0; s < SPT; ++s) {
+            pf[s] = M::from_acc(ep, s);
+            nf[s] = M::from_acc(en, s);
+            sp = M::sum_into(pf[s], sp);
+            sn = M::sum_into(nf[s], sn);
+          }
+          sp += xor32(sp);
+          sn += xor32(sn);
+          const float srec = g ? sn : sp;   // lane group g records the sum of half g
+          sums_u[(g * NV + v) * C + tl] = live ? srec : 1.f;
+          if (x.kind == 0) {
+            T* qrow = reinterpret_cast<T*>(slot) + tl * L::QSTRIDE + 32 * v + g * M::KPL;
+#pragma unroll
+            for (int s = 0; s < SPT; ++s) {
+              *reinterpret_cast<typename M::frag*>(qrow + s * M::KK) = pf[s];
+              *reinterpret_cast<typename M::frag*>(qrow + DF + s * M::KK) = nf[s];
+            }
+          } else {
+            T* kcol = reinterpret_cast<T*>(slot) + (32 * v + g * M::KPL) * L::KSTRIDE + tl;
+#pragma unroll
+            for (int s = 0; s < SPT; ++s) {
+              if constexpr (M::KPL == 1) {
+                kcol[(s * M::KK) * L::KSTRIDE] = pf[s];
+                kcol[(DF + s * M::KK) * L::KSTRIDE] = nf[s];
+              } else {
+#pragma unroll
+                for (int e = 0; e < M::KPL; ++e) {
+                  kcol[(s * M::KK + e) * L::KSTRIDE] = pf[s][e];
+                  kcol[(DF + s * M::KK + e) * L::KSTRIDE] = nf[s][e];
+                }
+              }
+            }
+          }
         }
       }
+      if (m < M_sub) {
+        // ---- first step of sub-unit m: projection, partial statistics
+        const int u = m / NSUB, sub = m % NSUB;
+        const LaUnit x = unit_at(u);
+        const bool more = m + 1 < M_sub;
+        const LaUnit xn = unit_at(more ? (m + 1) / NSUB : u);
+        const int subn = (m + 1) % NSUB;
+        const T* bias = x.kind == 0 ? bq : bk;
+        float* statc = stat + (m & 1) * L::STAT_FLOATS;
+        if (x.kind == 1 && sub == 0) {
+          // keep table of this K unit from the list requested an interval ago; the wave's own LDS accesses
+          // are processed in order, so the later reads need no barrier
+          for (int t = lane; t < C; t += 64) keepb[t] = x.valid ? 1 : 0;
 #pragma unroll
-      for (int sub = 0; sub < NSUB; ++sub) {
-        if (sub > 0) {
-          lane = fresh_lane_id(); r = lane & 31; g = lane >> 5;
+          for (int j = 0; j < 2; ++j) {
+            const unsigned off = (unsigned)(selv[j] - x.chunk * C);
+            if (selv[j] >= 0 && off < (unsigned)C) keepb[off] = 0;
+          }
         }
-        floatx16 f[2];
-        float nx2[2];
+        if (more && xn.kind == 1 && subn == 0) load_sel(xn, lane);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           floatx16 acc = zero16();
 #pragma unroll
           for (int s = 0; s < KS; ++s) acc = M::mma(w[s], xb[j][s], acc);
+          // ||x||^2 of a tile is needed once per token, not once per wave: the waves take turns
           float n2 = 0.f;
+          if (NV == 1 || (v & 1) == j) {
 #pragma unroll
-          for (int s = 0; s < KS; ++s) {
-            if constexpr (M::KPL == 1) {
-              n2 = fmaf(xb[j][s], xb[j][s], n2);
-            } else {
-#pragma unroll
-              for (int e = 0; e < M::KPL; ++e) {
-                const float xv = to_f32(xb[j][s][e]);
-                n2 = fmaf(xv, xv, n2);
-              }
-            }
+            for (int s = 0; s < KS; ++s) n2 = M::dot_into(xb[j][s], xb[j][s], n2);
+            n2 += xor32(n2);
           }
-          n2 += xor32(n2);
-          nx2[j] = n2;
+          // the rows are dead now: request the tile that will use the same registers
+          if (more) load_x(xn, 2 * subn + j, j, r, g);
           if (bias != nullptr) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] += to_f32(bias[32 * v + M::pos_of_reg(i, g)]);
@@ -265,107 +344,24 @@ __global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
           fmin = fminf(fmin, xor32(fmin));
           if (g == 0) {
             floatx4 st;
-            st[0] = nf2; st[1] = fmax; st[2] = fmin; st[3] = 0.f;
-            *reinterpret_cast<floatx4*>(stat + ((j * NV + v) * 32 + r) * 4) = st;
+            st[0] = nf2; st[1] = fmax; st[2] = fmin; st[3] = n2;
+            *reinterpret_cast<floatx4*>(statc + ((j * NV + v) * 32 + r) * 4) = st;
           }
           f[j] = acc;
         }
-        lds_barrier();
-        lane = fresh_lane_id(); r = lane & 31; g = lane >> 5;
-        if (sub == NSUB - 1) {
-          if (next >= 0 && next != kind) load_w(next, r, g);
-          if (next == 1) load_sel(xn, lane);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int tt = 2 * sub + j;
-          float nf2 = 0.f, fmax = -INFINITY, fmin = INFINITY;
-#pragma unroll
-          for (int vv = 0; vv < NV; ++vv) {
-            const floatx4 st = *reinterpret_cast<const floatx4*>(stat + ((j * NV + vv) * 32 + r) * 4);
-            nf2 += st[0];
-            fmax = fmaxf(fmax, st[1]);
-            fmin = fminf(fmin, st[2]);
-          }
-          // u = f * ratio with ratio = ||x|| / ||f|| >= 0, so max/min of u are ratio * max/min of f;
-          // exp(u - umax) = exp2(f * a1 - fmax * a1),  exp(umin - u) = exp2(fmin * a1 - f * a1)
-          const float ratio = nf2 > 0.f ? sqrtf(nx2[j] / nf2) : 0.f;
-          const float a1 = ratio * kLog2e;
-          const float bp = -fmax * a1, bn = fmin * a1;
-          const int tl = 32 * tt + r;
-          // tokens kept by the softmax branch (and every token of an absent chunk) are stored as zeros
-          const float kf = kind == 1 ? (keepb[tl] ? 1.f : 0.f) : 1.f;
-          floatx16 ep, en;
-          float sp = 0.f, sn = 0.f;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            ep[i] = fast_exp2(fmaf(f[j][i], a1, bp));
-            en[i] = fast_exp2(fmaf(f[j][i], -a1, bn));
-            sp += ep[i];
-            sn += en[i];
-          }
-          sp += xor32(sp);
-          sn += xor32(sn);
-          sums_u[(g * NV + v) * C + tl] = g ? sn : sp;   // lane group g records the sum of half g
-          if (kind == 0) {
-            T* qrow = reinterpret_cast<T*>(slot) + tl * L::QSTRIDE;
-#pragma unroll
-            for (int s = 0; s < SPT; ++s) {
-              const int p0 = 32 * v + s * M::KK + g * M::KPL;
-              *reinterpret_cast<typename M::frag*>(qrow + p0) = M::from_acc(ep, s);
-              *reinterpret_cast<typename M::frag*>(qrow + DF + p0) = M::from_acc(en, s);
-            }
-          } else {
-            T* kcol = reinterpret_cast<T*>(slot) + tl;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int fi = 32 * v + M::pos_of_reg(i, g);
-              kcol[fi * L::KSTRIDE] = from_f32<T>(ep[i] * kf);
-              kcol[(DF + fi) * L::KSTRIDE] = from_f32<T>(en[i] * kf);
-            }
-          }
-          // The rows of this token tile are dead since the projection and its f values since the lines
-          // above: request the tile that will use the same registers, one sub-unit ahead of its use.
-          if (sub + 1 < NSUB) load_x(x, tt + 2, j, r, g);
-          else if (next >= 0) load_x(xn, j, j, r, g);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        lds_barrier();
-      }
-    };
-
-    constexpr IC<0> KQ{};
-    constexpr IC<1> KK1{};
-    constexpr IC<-1> KNONE{};
-    {
-      const LaUnit x0 = unit_at(0);
-      load_x(x0, 0, 0, r, g);
-      load_x(x0, 1, 1, r, g);
-      load_w(x0.kind, r, g);
-      if (x0.kind == 1) load_sel(x0, lane);
-    }
-    if (MODE == 1) {
-      // Q(c_beg), then K, Q pairs
-      if (n_units == 1) {
-        produce(0, KQ, KNONE);
-      } else {
-        produce(0, KQ, KK1);
-#pragma unroll 1
-        for (int u = 1; u + 1 < n_units; u += 2) {
-          produce(u, KK1, KQ);
-          if (u + 2 < n_units) produce(u + 1, KQ, KK1);
-          else produce(u + 1, KQ, KNONE);
+        if (more && xn.kind != x.kind) load_w(xn.kind, r, g);
+        // Warm the cache for the sub-unit after the next one: a 4-byte load per 128-byte line of its rows,
+        // landing in a scratch corner of LDS (no registers are held while it is in flight).
+        if (m + 2 < M_sub && v < 2) {
+          const LaUnit xw = unit_at((m + 2) / NSUB);
+          const T* wp = row_ptr(xw, 2 * ((m + 2) % NSUB) + v, r, 0) + g * (128 / sizeof(T));
+          if (g * (128 / sizeof(T)) < D)
+            __builtin_amdgcn_global_load_lds(wp, (lds_ptr_t)warm, 4, 0, 0);
         }
       }
-    } else {
-#pragma unroll 1
-      for (int u = 0; u + 1 < n_units; ++u) produce(u, KK1, KK1);
-      produce(n_units - 1, KK1, KNONE);
+      lds_barrier();
     }
-#pragma unroll
-    for (int i = 0; i < NPART; ++i) lds_barrier();
+    lds_barrier();
     return;
   }
 
@@ -393,18 +389,17 @@ __global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
     for (int s = 0; s < VS; ++s) vf[s] = M::load(vrow + s * M::KK);
   };
 
-  // reciprocal softmax sums of the unit in slot u&1, from the producers' partial sums
-  auto make_inv = [&](int u) __attribute__((always_inline)) {
-    // entry lane + 64*j of the table [half][token]; every address is one lane-dependent base plus a constant
+  // reciprocal softmax sums of the 64 tokens of sub-unit `sub` of the unit in slot u&1, from the producers'
+  // partial sums: lane t handles token 64*sub + t, both halves
+  auto make_inv = [&](int u, int sub) __attribute__((always_inline)) {
     const int lane = fresh_lane_id();
-    const float* src = sums + (u & 1) * (2 * NV * C) + lane;
+    const float* src = sums + (u & 1) * (2 * NV * C) + 64 * sub + lane;
 #pragma unroll
-    for (int j = 0; j < 2 * C / 64; ++j) {
-      const int h = (64 * j) / C, t0 = (64 * j) % C;
+    for (int h = 0; h < 2; ++h) {
       float sacc = 0.f;
 #pragma unroll
-      for (int vv = 0; vv < NV; ++vv) sacc += src[(h * NV + vv) * C + t0];
-      invw[lane + 64 * j] = fast_rcp(sacc);
+      for (int vv = 0; vv < NV; ++vv) sacc += src[(h * NV + vv) * C];
+      invw[h * C + 64 * sub + lane] = fast_rcp(sacc);
     }
   };
 
@@ -506,73 +501,93 @@ __global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
       bcur = bnext;
       __builtin_amdgcn_sched_barrier(0);
     }
-    const bool tile_full = x.chunk * C + 32 * mt + 32 <= N;   // uniform: no per-row test in the common case
+    const int tok0 = x.chunk * C + 32 * mt;                   // first token of the tile
+    const bool tile_full = tok0 + 32 <= N;                    // uniform: no per-row test in the common case
+    float* ntile = nrow + (int64_t)tok0 * D + col;
+    if (tile_full && a.g == nullptr) {
 #pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      const int row0 = 32 * mt + 8 * i4 + 4 * g;
-      const floatx4 ip = *reinterpret_cast<const floatx4*>(invw + row0);
-      const floatx4 in = *reinterpret_cast<const floatx4*>(invw + C + row0);
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int row0 = 8 * i4 + 4 * g;
+        const floatx4 ip = *reinterpret_cast<const floatx4*>(invw + 32 * mt + row0);
+        const floatx4 in = *reinterpret_cast<const floatx4*>(invw + C + 32 * mt + row0);
+        float* np = ntile + row0 * D;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int tok = x.chunk * C + row0 + e;
-        if (tile_full || tok < N) {
-          float val = op[4 * i4 + e] * ip[e] + on[4 * i4 + e] * in[e];
-          if (a.g != nullptr)
-            val *= to_f32(static_cast<const T*>(a.g)[(int64_t)b * a.g_sb + (int64_t)tok * a.g_st +
-                                                     (int64_t)hq * a.g_sh + col]);
-          nrow[(int64_t)tok * D + col] = val;
+        for (int e = 0; e < 4; ++e) np[e * D] = op[4 * i4 + e] * ip[e] + on[4 * i4 + e] * in[e];
+      }
+    } else {
+#pragma unroll 1
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int row0 = 8 * i4 + 4 * g;
+        const floatx4 ip = *reinterpret_cast<const floatx4*>(invw + 32 * mt + row0);
+        const floatx4 in = *reinterpret_cast<const floatx4*>(invw + C + 32 * mt + row0);
+        floatx4 vo, vn4;
+        if (i4 == 0) { vo = {op[0], op[1], op[2], op[3]}; vn4 = {on[0], on[1], on[2], on[3]}; }
+        else if (i4 == 1) { vo = {op[4], op[5], op[6], op[7]}; vn4 = {on[4], on[5], on[6], on[7]}; }
+        else if (i4 == 2) { vo = {op[8], op[9], op[10], op[11]}; vn4 = {on[8], on[9], on[10], on[11]}; }
+        else { vo = {op[12], op[13], op[14], op[15]}; vn4 = {on[12], on[13], on[14], on[15]}; }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int tok = tok0 + row0 + e;
+          if (tok < N) {
+            float val = vo[e] * ip[e] + vn4[e] * in[e];
+            if (a.g != nullptr)
+              val *= to_f32(static_cast<const T*>(a.g)[(int64_t)b * a.g_sb + (int64_t)tok * a.g_st +
+                                                       (int64_t)hq * a.g_sh + col]);
+            ntile[(row0 + e) * D] = val;
+          }
         }
       }
     }
-    // D_LA: this wave's share of the tile's rows; lane group g sums feature half g
-    constexpr int TPW = 32 / NM;
-    if (r < TPW) {
-      const int tl = 32 * mt + wave * TPW + r;
-      const T* qrow = phiq + tl * L::QSTRIDE + g * DF;
-      const float* zz = zsh + g * DF;
+    // D_LA = phi_q z for this wave's share of the tile's rows.  LPT consecutive lanes split one row's 2*d_f
+    // features into slices of 32 (a slice lies in one half, so it has one normaliser); the partial dot
+    // products are added across those lanes.
+    constexpr int TPW = 32 / NM, LPT = 64 / TPW;
+    static_assert(DP / LPT == 32, "32 features per lane");
+    {
+      const int tl = 32 * mt + wave * TPW + lane / LPT;
+      const int sl = lane % LPT;
+      const T* qrow = phiq + tl * L::QSTRIDE + 32 * sl;
+      const float* zz = zsh + 32 * sl;
       float dla = 0.f;
-#pragma unroll 4
-      for (int f0 = 0; f0 < DF; f0 += M::KPL) dla += frag_dot<T>(M::load(qrow + f0), zz + f0);
-      dla *= invw[g * C + tl];
-      dla += xor32(dla);
+#pragma unroll
+      for (int f0 = 0; f0 < 32; f0 += M::KPL) dla += frag_dot<T>(M::load(qrow + f0), zz + f0);
+      dla *= invw[(sl >= LPT / 2 ? C : 0) + tl];
+#pragma unroll
+      for (int m = 1; m < LPT; m <<= 1) dla += __shfl_xor(dla, m, 64);
       const int tok = x.chunk * C + tl;
-      if (g == 0 && tok < N) a.d_la[((int64_t)b * a.Hq + hq) * N + tok] = dla;
+      if (sl == 0 && tok < N) a.d_la[((int64_t)b * a.Hq + hq) * N + tok] = dla;
     }
   };
 
-  // all parts of one unit, a barrier after each
+  // one sub-unit (two token tiles) per interval
+  auto consume_q_sub = [&](int u, auto sub_c) __attribute__((always_inline)) {
+    constexpr int sub = decltype(sub_c)::value;
+    make_inv(u, sub);
+    consume_q(u, IC<2 * sub>{});
+    consume_q(u, IC<2 * sub + 1>{});
+    lds_barrier();
+  };
+  auto consume_k_sub = [&](int u, const VFrag& vf, auto sub_c) __attribute__((always_inline)) {
+    constexpr int sub = decltype(sub_c)::value;
+    make_inv(u, sub);
+    consume_k(u, vf, IC<2 * sub>{});
+    consume_k(u, vf, IC<2 * sub + 1>{});
+    lds_barrier();
+  };
   auto consume_q_unit = [&](int u) __attribute__((always_inline)) {
-    make_inv(u);
-    consume_q(u, IC<0>{});
-    lds_barrier();
-    consume_q(u, IC<1>{});
-    lds_barrier();
-    if constexpr (NPART == 4) {
-      consume_q(u, IC<2>{});
-      lds_barrier();
-      consume_q(u, IC<3>{});
-      lds_barrier();
-    }
+    consume_q_sub(u, IC<0>{});
+    if constexpr (NSUB == 2) consume_q_sub(u, IC<1>{});
   };
   auto consume_k_unit = [&](int u, const VFrag& vf) __attribute__((always_inline)) {
-    make_inv(u);
-    consume_k(u, vf, IC<0>{});
-    lds_barrier();
-    consume_k(u, vf, IC<1>{});
-    lds_barrier();
-    if constexpr (NPART == 4) {
-      consume_k(u, vf, IC<2>{});
-      lds_barrier();
-      consume_k(u, vf, IC<3>{});
-      lds_barrier();
-    }
+    consume_k_sub(u, vf, IC<0>{});
+    if constexpr (NSUB == 2) consume_k_sub(u, vf, IC<1>{});
   };
 
   if (MODE == 1) {
     VFrag vf;
     if (n_units > 1) load_v(1, vf);
-#pragma unroll
-    for (int i = 0; i < NPART; ++i) lds_barrier();
+    lds_barrier();
+    lds_barrier();
     consume_q_unit(0);
 #pragma unroll 1
     for (int u = 1; u + 1 < n_units; u += 2) {
@@ -587,8 +602,8 @@ __global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
     // two V buffers: the next unit's V is in flight while the current one is contracted
     VFrag va, vb;
     load_v(0, va);
-#pragma unroll
-    for (int i = 0; i < NPART; ++i) lds_barrier();
+    lds_barrier();
+    lds_barrier();
 #pragma unroll 1
     for (int u = 0; u < n_units; u += 2) {
       if (u + 1 < n_units) load_v(u + 1, vb);
@@ -614,6 +629,13 @@ __global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
       for (int i = 0; i < 16; ++i) dst[(int64_t)(32 * ft + M::pos_of_reg(i, g)) * D + col] = S[ft][i];
     for (int fi = threadIdx.x; fi < DP; fi += NM * 64) dst[DP * D + fi] = zsh[fi];
   }
+}
+
+// The body lives in a device function: a kernel template that uses the load-to-LDS builtin directly does not
+// get its host-side launch stub.
+template <typename T, int D, int DF, int C, int MODE>
+__global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
+  la_body<T, D, DF, C, MODE>(a);
 }
 
 // exclusive prefix over segments, in place: seg[s] <- sum_{s' < s} seg[s'] (slot nseg-1 is only written)
