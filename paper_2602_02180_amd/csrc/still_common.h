@@ -162,6 +162,34 @@ __device__ __forceinline__ void head_major_block(int L, int Hq, int& hq, int& it
   }
 }
 
+// Global -> LDS copies without staging registers (global_load_lds): lane L's 16 (or 4) bytes land at
+// lds_base + 16 L (4 L).  They are issued as opaque assembly on purpose.  Issued through the compiler builtin,
+// an in-flight copy makes the compiler's wait-count bookkeeping treat every later LDS wait as "wait for
+// everything" (the instruction touches two address spaces), which drains the LDS read pipeline of the very
+// loops these copies are meant to run under.  The price: the compiler does not know about these copies, so the
+// caller must wait for them itself (s_waitcnt vmcnt(0), then a workgroup barrier) before the data is read.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)(uintptr_t)(lds_ptr_t)p;
+}
+
+__device__ __forceinline__ void async_copy16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gptr), "s"(lds_base)
+               : "memory", "m0");
+}
+
+__device__ __forceinline__ void async_copy4(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :
+               : "v"(gptr), "s"(lds_base)
+               : "memory", "m0");
+}
+
+__device__ __forceinline__ void wait_async_copies() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // 16-byte global/LDS copy unit
 struct __attribute__((aligned(16))) Vec16 {
   uint32_t w[4];

@@ -98,8 +98,6 @@ struct LaUnit {
 template <int V>
 using IC = std::integral_constant<int, V>;
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-
 template <typename T, int D, int DF, int C, int MODE>
 __device__ __forceinline__ void la_body(const LaArgs& a) {
   typedef Mma<T> M;
@@ -356,7 +354,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
           const LaUnit xw = unit_at((m + 2) / NSUB);
           const T* wp = row_ptr(xw, 2 * ((m + 2) % NSUB) + v, r, 0) + g * (128 / sizeof(T));
           if (g * (128 / sizeof(T)) < D)
-            __builtin_amdgcn_global_load_lds(wp, (lds_ptr_t)warm, 4, 0, 0);
+            async_copy4(wp, lds_address(warm));
         }
       }
       lds_barrier();

@@ -54,8 +54,6 @@ struct SaCfg {
   }
 };
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-
 // S^T tile (64 keys x 32 queries) = K tile x Q^T
 template <typename T, int D>
 __device__ __forceinline__ void sa_qk(const T* __restrict__ Ks, const typename Mma<T>::frag (&qf)[D / Mma<T>::KK],
@@ -65,11 +63,21 @@ __device__ __forceinline__ void sa_qk(const T* __restrict__ Ks, const typename M
   constexpr int KS = D / M::KK;
   st[0] = zero16();
   st[1] = zero16();
+  // The K fragments are read from LDS DEPTH products ahead of their use (the scheduling barriers pin that
+  // order), so a product does not wait for its own read.
+  constexpr int NP = 2 * KS;                 // product idx: key tile idx & 1, k-step idx >> 1
+  constexpr int DEPTH = NP < 6 ? NP : 6;
+  auto a_at = [&](int idx) { return M::load(Ks + Cf::koff(32 * (idx & 1) + r, (idx >> 1) * M::KK + g * M::KPL)); };
+  typename M::frag af[DEPTH];
 #pragma unroll
-  for (int s = 0; s < KS; ++s) {
-    const int e = s * M::KK + g * M::KPL;
-    st[0] = M::mma(M::load(Ks + Cf::koff(r, e)), qf[s], st[0]);
-    st[1] = M::mma(M::load(Ks + Cf::koff(32 + r, e)), qf[s], st[1]);
+  for (int i = 0; i < DEPTH; ++i) af[i] = a_at(i);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int idx = 0; idx < NP; ++idx) {
+    if (idx & 1) st[1] = M::mma(af[idx % DEPTH], qf[idx >> 1], st[1]);
+    else st[0] = M::mma(af[idx % DEPTH], qf[idx >> 1], st[0]);
+    if (idx + DEPTH < NP) af[idx % DEPTH] = a_at(idx + DEPTH);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -134,8 +142,7 @@ __device__ __forceinline__ void sa_softmax_pv(const T* __restrict__ Vs, floatx16
   lpart += rs;
 }
 
-// (a __device__ body behind a thin __global__ wrapper: the direct-to-LDS builtin exists on the device side
-// only, and the host pass must still be able to emit the kernel's launch stub)
+// (a __device__ body behind a thin __global__ wrapper keeps the kernel's host-side launch stub simple)
 template <typename T, int D>
 __device__ __forceinline__ void sa_body(const SaArgs& a) {
   typedef Mma<T> M;
@@ -224,19 +231,18 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       const T* base = kret + (int64_t)kb * D;
 #pragma unroll
       for (int j = 0; j < Cf::K_INSTR; ++j)
-        __builtin_amdgcn_global_load_lds(base + k_off_ret[j], (lds_ptr_t)(dst + 4 * j * 64 * Cf::EPV), 16, 0, 0);
+        async_copy16(base + k_off_ret[j], lds_address(dst + 4 * j * 64 * Cf::EPV));
     } else if (kb + BN <= N) {
       const T* base = kloc + (int64_t)kb * kst;
 #pragma unroll
       for (int j = 0; j < Cf::K_INSTR; ++j)
-        __builtin_amdgcn_global_load_lds(base + k_off_loc[j], (lds_ptr_t)(dst + 4 * j * 64 * Cf::EPV), 16, 0, 0);
+        async_copy16(base + k_off_loc[j], lds_address(dst + 4 * j * 64 * Cf::EPV));
     } else {   // last tile of a ragged sequence: rows past the end re-read the last token (masked later)
 #pragma unroll
       for (int j = 0; j < Cf::K_INSTR; ++j) {
         int tok = kb + k_key[j];
         tok = tok < N ? tok : N - 1;
-        __builtin_amdgcn_global_load_lds(kloc + ((int64_t)tok * kst + k_col[j]),
-                                         (lds_ptr_t)(dst + 4 * j * 64 * Cf::EPV), 16, 0, 0);
+        async_copy16(kloc + ((int64_t)tok * kst + k_col[j]), lds_address(dst + 4 * j * 64 * Cf::EPV));
       }
     }
   };
@@ -247,12 +253,12 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       const T* base = vrett + kb;
 #pragma unroll
       for (int j = 0; j < Cf::V_INSTR; ++j)
-        __builtin_amdgcn_global_load_lds(base + v_off_ret[j], (lds_ptr_t)(dst + 4 * j * 64 * Cf::EPV), 16, 0, 0);
+        async_copy16(base + v_off_ret[j], lds_address(dst + 4 * j * 64 * Cf::EPV));
     } else {
       const T* base = vtl + kb;
 #pragma unroll
       for (int j = 0; j < Cf::V_INSTR; ++j)
-        __builtin_amdgcn_global_load_lds(base + v_off_loc[j], (lds_ptr_t)(dst + 4 * j * 64 * Cf::EPV), 16, 0, 0);
+        async_copy16(base + v_off_loc[j], lds_address(dst + 4 * j * 64 * Cf::EPV));
     }
   };
   // wave-uniform: does this wave use tile ti, and with which mask variant
@@ -287,7 +293,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   request_k(0);
   request_v(0);
   if (n_tiles > 1) request_k(1);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  wait_async_copies();
   lds_barrier();
   floatx16 st_a[2], st_b[2];
   if (tile_mode(0) >= 0) sa_qk<T, D>(Kl, qf, st_a, r, g);
@@ -308,7 +314,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       sa_softmax_pv<T, D, 1>(Vs, st_cur, o, m_ref, lpart, kb, ret_w, lo_w, t, sc2, r, g);
     else if (mode == 2)
       sa_softmax_pv<T, D, 2>(Vs, st_cur, o, m_ref, lpart, kb, ret_w, lo_w, t, sc2, r, g);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_async_copies();
     lds_barrier();
   };
   for (int ti = 0; ti < n_tiles; ti += 2) {           // two steps per trip: the S tiles swap roles, no copies
