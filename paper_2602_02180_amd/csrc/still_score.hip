@@ -17,7 +17,7 @@
 namespace still {
 
 template <typename T, int D, int NT>
-__global__ __launch_bounds__(256) void score_select_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
   typedef Mma<T> M;
   constexpr int KS = D / M::KK;
   const T* __restrict__ q = static_cast<const T*>(a.q);
@@ -33,7 +33,8 @@ __global__ __launch_bounds__(256) void score_select_kernel(ScoreArgs a) {
   const int t = t0 + r;
 
   __shared__ float s_score[128];
-  __shared__ unsigned char s_flag[128];
+  __shared__ int s_rank[256];
+  __shared__ unsigned long long s_ball[4];
 
   // queries of this wave as B operand
   typename M::frag qf[KS];
@@ -57,53 +58,77 @@ __global__ __launch_bounds__(256) void score_select_kernel(ScoreArgs a) {
     for (int s = 0; s < KS; ++s) acc[j] = M::mma(M::load(kp + s * M::KK), qf[s], acc[j]);
   }
 
-  // window softmaxes for query t (this lane and lane^32 share the query)
+  // window softmaxes for query t (this lane and lane^32 share the query).
+  // A tile whose 32 keys are inside the window of all 32 queries of the wave needs no mask; only the oldest
+  // tile(s) (window start) and the newest one (causal limit, and the only one that can hold the diagonal key)
+  // do.  Which tiles those are is wave-uniform.
   const int lo = (t - W + 1) > 0 ? (t - W + 1) : 0;
+  const int lo_max = (t0 + 32 - W) > 0 ? (t0 + 32 - W) : 0;   // window start of the wave's last query
   const float sc2 = a.scale * kLog2e;
-  float m2 = -INFINITY;
+  bool full[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
     const int kb = t0 - 32 * (NT - 1 - j);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int key = kb + M::pos_of_reg(i, g);
-      const bool valid = key >= lo && key <= t;
-      const float x = valid ? acc[j][i] * sc2 : -INFINITY;
-      acc[j][i] = x;
-      m2 = fmaxf(m2, x);
-    }
+    full[j] = j < NT - 1 && kb >= lo_max && kb >= 0;
   }
-  m2 = fmaxf(m2, xor32(m2));
-  float d_all = 0.f, d_no = 0.f;
+  // pass 1: masked logits (raw, the positive scale commutes with the maximum) and their maximum
+  float mraw = -INFINITY;
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
     const int kb = t0 - 32 * (NT - 1 - j);
+    if (!full[j]) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = kb + M::pos_of_reg(i, g);
+        acc[j][i] = (key >= lo && key <= t) ? acc[j][i] : -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mraw = fmaxf(mraw, acc[j][i]);
+  }
+  mraw = fmaxf(mraw, xor32(mraw));
+  // pass 2: e = exp(scale * (x - max)); masked entries give exp2(-inf) = 0.  The sums without the diagonal
+  // differ from the full sums only in the newest tile.
+  const float moff = -mraw * sc2;
+  float d_old = 0.f, d_new = 0.f, d_new_no = 0.f;
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int key = kb + M::pos_of_reg(i, g);
-      const float e = fast_exp2(acc[j][i] - m2);  // masked entries: exp2(-inf) = 0
+      const float e = fast_exp2(fmaf(acc[j][i], sc2, moff));
       acc[j][i] = e;
-      d_all += e;
-      d_no += (key == t) ? 0.f : e;
+      if (j < NT - 1) {
+        d_old += e;
+      } else {
+        d_new += e;
+        d_new_no += (M::pos_of_reg(i, g) == r) ? 0.f : e;   // key t0 + pos is the query itself iff pos == r
+      }
     }
   }
+  float d_all = d_old + d_new, d_no = d_old + d_new_no;
   d_all += xor32(d_all);
   d_no += xor32(d_no);
   const float inv_all = 1.0f / d_all;
   const float inv_no = d_no > 0.f ? 1.0f / d_no : 0.f;
+  // pass 3: sum of a_diag * (log(a_diag + eps) - log(a_nodiag + eps)); a masked entry has a_diag = 0 and
+  // is skipped explicitly (with eps = 0 its term would be 0 * (inf - inf))
   float score = 0.f;
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
     const int kb = t0 - 32 * (NT - 1 - j);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int key = kb + M::pos_of_reg(i, g);
-      const bool valid = key >= lo && key <= t;
       const float e = acc[j][i];
       const float ad = e * inv_all;
-      const float an = (key == t) ? 0.f : e * inv_no;
+      float an = e * inv_no;
+      if (j == NT - 1) an = (M::pos_of_reg(i, g) == r) ? 0.f : an;
       const float term = ad * (fast_log2(ad + a.eps) - fast_log2(an + a.eps));
-      score += valid ? term : 0.f;
+      if (full[j]) {
+        score += term;
+      } else {
+        const int key = kb + M::pos_of_reg(i, g);
+        score += (key >= lo && key <= t) ? term : 0.f;
+      }
     }
   }
   score *= kLn2;
@@ -114,27 +139,32 @@ __global__ __launch_bounds__(256) void score_select_kernel(ScoreArgs a) {
     if (t < N) a.score[((int64_t)b * a.Hq + hq) * N + t] = score;
   }
 
-  // Top-lambda of a full chunk, ties to the lower index, written ascending.
+  // Top-lambda of a full chunk, ties to the lower index, written ascending.  Token i's rank = number of
+  // tokens that beat it; the count is split between threads i and i + C (half of the opponents each).  The
+  // output position of a chosen token = number of chosen tokens before it, from wave ballots.
   if (a.sel != nullptr && c < a.ncf) {
     __syncthreads();
-    const int i = threadIdx.x;
-    bool chosen = false;
-    if (i < C) {
-      const float si = s_score[i];
-      int rank = 0;
-      for (int j = 0; j < C; ++j) {
-        const float sj = s_score[j];
-        rank += (sj > si || (sj == si && j < i)) ? 1 : 0;
-      }
-      chosen = rank < a.lam;
-      s_flag[i] = chosen ? 1 : 0;
+    const int i = threadIdx.x % C, half = threadIdx.x / C;   // blockDim = 2 C
+    const float si = s_score[i];
+    int part = 0;
+    const int j0 = half * (C / 2);
+#pragma unroll 8
+    for (int j = j0; j < j0 + C / 2; ++j) {
+      const float sj = s_score[j];
+      part += (sj > si || (sj == si && j < i)) ? 1 : 0;
     }
+    s_rank[threadIdx.x] = part;
+    __syncthreads();
+    bool chosen = false;
+    if (threadIdx.x < C) chosen = s_rank[threadIdx.x] + s_rank[threadIdx.x + C] < a.lam;
+    const unsigned long long bal = __ballot(chosen);
+    if (lane == 0) s_ball[wave] = bal;
     __syncthreads();
     if (chosen) {
-      int pos = 0;
-      for (int j = 0; j < i; ++j) pos += s_flag[j];
+      int pos = __popcll(bal & ((1ull << lane) - 1ull));
+      for (int w = 0; w < wave; ++w) pos += __popcll(s_ball[w]);
       if (pos < a.lam)  // NaN scores can flag more than lam tokens; never write past the chunk's slots
-        a.sel[(((int64_t)b * a.Hq + hq) * a.ncf + c) * a.lam + pos] = c * C + i;
+        a.sel[(((int64_t)b * a.Hq + hq) * a.ncf + c) * a.lam + pos] = c * C + threadIdx.x;
     }
   }
 }
