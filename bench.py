@@ -195,6 +195,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run plain device-to-device copies of 1 GiB and exit: the known-size reference against "
+                         "which the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU only (the path shards over heads/batch with no exchange; "
@@ -208,6 +211,15 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     S.lib()  # fail loudly if the HIP library is missing
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "launches": 4}))
+        return 0
 
     if args.config == "c5":
         return decode_bench(args)
