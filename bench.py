@@ -28,6 +28,11 @@ PEAK_MFMA = {"bf16": 2.5e15, "f32": 157.3e12}   # dense MFMA peaks of MI355X, fl
 PEAK_HBM = 8.0e12
 
 
+# HBM bytes per launch of the dominant prefill kernel (sparse_attn_merge), measured with rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE and scaled by the plain-copy calibration; see profiles/sa_kernel_c4_hbm_traffic.md.  Other configs: null.
+MEASURED_TRAFFIC = {"c4": 1.966e9}
+
+
 def sparse_branch_flops(w: synth.Workload, N: int) -> float:
     """Algorithmic flops of the sparse softmax branch for one launch: every query row does
     4*d flops (q.k and p.v, 2 per MAC) per visible key: retained keys of chunks <= c-2 plus the
@@ -265,7 +270,8 @@ def main() -> int:
     flops = sparse_branch_flops(w, N)
     peak = PEAK_MFMA[w.dtype]
     roofline = {"bound": "mfma", "kernel": dom, "achieved": flops / dom_s / 1e12, "peak": peak / 1e12,
-                "unit": "TFLOP/s", "frac": flops / dom_s / peak, "traffic": args.traffic_bytes,
+                "unit": "TFLOP/s", "frac": flops / dom_s / peak,
+                "traffic": args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC.get(args.config),
                 "algorithmic_flops_per_launch": flops, "avg_launch_ms": per_kernel[dom]}
     rec = {
         "metric": "hybrid-attn fwd tokens/s @32K, Llama-3-8B layer shape" if args.config == "c4"
