@@ -15,18 +15,20 @@
 // Segment s of the state pass covers chunks [s*G-1, (s+1)*G-1), so the exclusive prefix handed to the
 // output pass of segment s is exactly the state through chunk s*G-2.
 //
-// Workgroup plan: the waves are specialised.
+// Workgroup plan: the waves are specialised, and wave w shares a SIMD with wave w + d/32.
 //   consumer waves (d/32): wave w keeps the fp32 state columns [32w, 32w+32) of S (2*d_f x d) in MFMA
 //     accumulators for the whole scan and does the two token-contracting products from LDS operands:
 //     S += phi_k^T V (phi_k staged as [feature][token], V from the token-contiguous transposed copy) and
 //     N = phi_q S (phi_q staged as [token][feature]; S is the B operand straight from its accumulator
 //     registers, converted to the input dtype).  z is kept in LDS in fp32; D_LA = phi_q z is a short
 //     dot product per row.
-//   producer waves (C/32): wave v computes the feature map of 32 tokens of the NEXT unit (x W on MFMA, the
-//     norm re-injection and the two softmaxes on the vector ALU, which is what bounds this kernel) and
-//     writes it into the other LDS slot.
+//   producer waves (d_f/32): wave v computes features [32v, 32v+32) of f = x W for ALL tokens of a sub-unit
+//     (its rows of W^T stay in registers), exchanges the per-token statistics that span the feature dimension
+//     with the other producers through LDS, and writes the two exponential halves UN-normalised into the LDS
+//     slot together with its partial softmax sums; the consumers fold the reciprocal sums into their operands.
 // Units alternate "queries of chunk c" / "keys of chunk c-1" so that the outputs of chunk c see the state
-// through chunk c-2; one barrier per unit hands a slot from producers to consumers.
+// through chunk c-2; a unit is cut into sub-units of 64 tokens, and one barrier per sub-unit interval hands data
+// from the projection step to the exponential step to the consumers.
 #include "still_kernels.h"
 #include <type_traits>
 
@@ -629,8 +631,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
   }
 }
 
-// The body lives in a device function: a kernel template that uses the load-to-LDS builtin directly does not
-// get its host-side launch stub.
+// (the body lives in a __device__ function behind a thin __global__ wrapper)
 template <typename T, int D, int DF, int C, int MODE>
 __global__ __launch_bounds__((D / 32 + DF / 32) * 64) void la_kernel(LaArgs a) {
   la_body<T, D, DF, C, MODE>(a);
