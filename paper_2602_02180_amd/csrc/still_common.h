@@ -14,6 +14,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
+#include <utility>
 
 namespace still {
 
@@ -189,6 +191,18 @@ __device__ __forceinline__ void async_copy4(const void* gptr, uint32_t lds_base)
 }
 
 __device__ __forceinline__ void wait_async_copies() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N-1>{}) in order: a loop whose index is a
+// compile-time constant in every iteration by construction (register arrays indexed with it never depend on
+// the loop unroller's thresholds).
+template <int... Is, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
 
 // 16-byte global/LDS copy unit
 struct __attribute__((aligned(16))) Vec16 {
