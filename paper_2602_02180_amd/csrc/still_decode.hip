@@ -335,18 +335,33 @@ __global__ __launch_bounds__(256) void decode_attend_kernel(DecArgs a) {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_finish_kernel(DecArgs a) {
   constexpr int DF = D, DP = 2 * D;
-  __shared__ float qs[D], phi[DP], sh[16], half[2][D];
+  constexpr int CG = D / 4, RP = 256 / CG;         // column groups of 4 floats, row parts (8 or 16)
+  __shared__ float qs[D], phi[DP], sh[16], fpart[2][DF];
+  __shared__ __attribute__((aligned(16))) float red[RP][D];
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int64_t unit = (int64_t)b * a.Hq + hq;
   const T* q = static_cast<const T*>(a.q) + unit * D;
   if (tid < D) qs[tid] = to_f32(q[tid]);
   __syncthreads();
+  // f = q W_q: feature tid % DF, the head dimension split between the block's two halves when d_f = 128
   float f = 0.f;
-  if (tid < DF) {
-    const T* wq = static_cast<const T*>(a.wq) + (int64_t)hq * D * DF + tid;
+  {
+    constexpr int XP = 256 / DF;                   // 2 (d=128) or 4 (d=64) partial sums per feature
+    const int fi = tid % DF, xp = tid / DF;
+    const T* wq = static_cast<const T*>(a.wq) + (int64_t)hq * D * DF + fi;
+    float fp = 0.f;
 #pragma unroll 8
-    for (int x = 0; x < D; ++x) f = fmaf(qs[x], to_f32(wq[(int64_t)x * DF]), f);
-    if (a.bq != nullptr) f += to_f32(static_cast<const T*>(a.bq)[(int64_t)hq * DF + tid]);
+    for (int x = xp * (D / XP); x < (xp + 1) * (D / XP); ++x) fp = fmaf(qs[x], to_f32(wq[(int64_t)x * DF]), fp);
+    if (xp >= XP - 2) fpart[xp - (XP - 2)][fi] = fp;
+    __syncthreads();
+    if (XP == 4) {
+      if (xp < 2) fpart[xp][fi] += fp;             // distinct (xp, fi) per thread
+      __syncthreads();
+    }
+    if (tid < DF) {
+      f = fpart[0][tid] + fpart[1][tid];
+      if (a.bq != nullptr) f += to_f32(static_cast<const T*>(a.bq)[(int64_t)hq * DF + tid]);
+    }
   }
   float nx2 = tid < D ? qs[tid] * qs[tid] : 0.f;
   float nf2 = tid < DF ? f * f : 0.f;
@@ -363,19 +378,21 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(DecArgs a) {
     phi[DF + tid] = round_to<T>(en / sn);
   }
   __syncthreads();
-  // N_LA[x] = sum_f phi[f] S[f][x]: thread (h2, x) sums half of the features
+  // N_LA[x] = sum_f phi[f] S[f][x]: thread (rp, cg) sums rows rp, rp + RP, ... of four columns with 16-byte
+  // loads (the state is the bulk of this kernel's traffic), the row parts are added through LDS
   const float* Sg = a.S + unit * (int64_t)(DP * (D + 1));
   {
-    constexpr int PARTS = 256 / D;                 // 2 (d=128) or 4 (d=64)
-    const int x = tid % D, h2 = tid / D;
-    float n = 0.f;
-    for (int ff = h2; ff < DP; ff += PARTS) n = fmaf(phi[ff], Sg[(int64_t)ff * D + x], n);
-    if (h2 < 2) half[h2][x] = n;
-    __syncthreads();
-    if (PARTS == 4) {
-      if (h2 >= 2) half[h2 - 2][x] += n;          // distinct (h2-2, x) per thread
-      __syncthreads();
+    const int cg = tid % CG, rp = tid / CG;
+    floatx4 n4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int ff = rp; ff < DP; ff += RP) {
+      const floatx4 sv = *reinterpret_cast<const floatx4*>(Sg + (int64_t)ff * D + 4 * cg);
+      const float pw = phi[ff];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) n4[e] = fmaf(pw, sv[e], n4[e]);
     }
+    *reinterpret_cast<floatx4*>(&red[rp][4 * cg]) = n4;
+    __syncthreads();
   }
   float dl = tid < DP ? phi[tid] * Sg[DP * D + tid] : 0.f;
   float d1 = 0.f, d2 = 0.f, d3 = 0.f;
@@ -400,7 +417,9 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(DecArgs a) {
       fs = fast_exp2(M);
       fl = 1.f;
     }
-    float nla = half[0][tid] + half[1][tid];
+    float nla = 0.f;
+#pragma unroll
+    for (int rp = 0; rp < RP; ++rp) nla += red[rp][tid];
     if (a.g != nullptr) nla *= to_f32(static_cast<const T*>(a.g)[unit * D + tid]);
     const float y = (fs * acc + fl * nla) / (fs * L + fl * dl);
     static_cast<T*>(a.out)[unit * D + tid] = from_f32<T>(y);
