@@ -305,7 +305,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   sx.out = out; sx.o_sb = p->o_sb; sx.o_st = p->o_st; sx.o_sh = p->o_sh;
   sx.map = map;
   sx.N = N; sx.Np = L.n_pad; sx.C = C; sx.lam = have_sel ? p->lambda : 0; sx.Hq = p->Hq; sx.Hkv = p->Hkv;
-  sx.cap = L.cap; sx.ntiles = (N + 127) / 128; sx.B_ = B;
+  sx.cap = L.cap; sx.ntiles = (N + still::kSaRows - 1) / still::kSaRows; sx.B_ = B;
   sx.scale = p->scale;
   if ((e = still::launch_sa(sx, p->dtype, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "sparse_attention: %s", hipGetErrorString(e));

@@ -61,6 +61,9 @@ struct LaArgs {
   float* s_final;      // nullable [B, Hq, DP*(D+1)]: state after chunk (last chunk - 2)
 };
 
+// query rows per workgroup of the sparse-attention kernel (one wave per 32 rows)
+constexpr int kSaRows = 128;
+
 struct SaArgs {
   const void* q;
   const void* k;

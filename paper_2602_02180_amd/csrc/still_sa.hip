@@ -9,7 +9,7 @@
 // exponentials, so both branches are brought to the common factor exp(-max(m, 0)) before the division
 // (any common positive factor cancels; this one can neither overflow nor lose the larger branch).
 //
-// One workgroup = 128 consecutive query rows of one (batch, query head), 4 waves x 32 rows.
+// One workgroup = kSaRows consecutive query rows of one (batch, query head), one wave per 32 rows.
 // Everything is computed transposed so that one lane owns one query row:
 //   S^T (keys x queries)  = K_tile (A operand, from LDS)  x  Q^T (B operand, registers)
 //   O^T (d    x queries) += V^T_tile (A operand, from LDS) x  P^T (B operand = S^T accumulators, in place)
@@ -20,7 +20,11 @@
 // Software pipeline inside every wave, per iteration i:
 //   request K(i+2), V(i+1)  |  S(i+1) = K(i+1) Q^T on the matrix core  |  softmax of S(i) on the vector ALU
 //   |  O += V(i) P(i)  |  wait for own requests, barrier
-// so the MFMAs of the next tile's logits run under the current tile's exponentials.
+// so the MFMAs of the next tile's logits run under the current tile's exponentials.  Most tiles are retained
+// tiles that every row of the wave sees in full; those run in a separate steady-state loop without per-tile
+// decisions, with the requests of the step spread over the S products instead of issued in one burst (a wave
+// issues in order, and a burst of direct-to-LDS requests holds up everything behind it while the texture path
+// works through it).
 // The reference m only moves when a row maximum exceeds it by more than 2^8 (the exponentials then stay
 // below 2^8, harmless in fp32/bf16), which removes almost all rescales of O.
 // Workgroups of one (batch, head) are placed on one XCD (block ids are dealt round-robin to the 8 XCDs), so
@@ -32,7 +36,7 @@ namespace still {
 template <typename T, int D>
 struct SaCfg {
   typedef Mma<T> M;
-  static constexpr int BM = 128, BN = 64, NW = 4;
+  static constexpr int BM = kSaRows, BN = 64, NW = BM / 32;
   static constexpr int EPV = 16 / sizeof(T);          // elements per 16-byte vector
   static constexpr int KVR = D / EPV;                 // vectors per K row
   static constexpr int VVR = BN / EPV;                // vectors per V^T row
@@ -54,10 +58,11 @@ struct SaCfg {
   }
 };
 
-// S^T tile (64 keys x 32 queries) = K tile x Q^T
-template <typename T, int D>
+// S^T tile (64 keys x 32 queries) = K tile x Q^T.  `between(integral_constant<int, idx>)` runs after product idx
+// has been issued (the steady-state loop uses it to spread its global->LDS requests over the products).
+template <typename T, int D, typename F>
 __device__ __forceinline__ void sa_qk(const T* __restrict__ Ks, const typename Mma<T>::frag (&qf)[D / Mma<T>::KK],
-                                      floatx16 (&st)[2], int r, int g) {
+                                      floatx16 (&st)[2], int r, int g, F&& between) {
   typedef Mma<T> M;
   typedef SaCfg<T, D> Cf;
   constexpr int KS = D / M::KK;
@@ -72,13 +77,20 @@ __device__ __forceinline__ void sa_qk(const T* __restrict__ Ks, const typename M
 #pragma unroll
   for (int i = 0; i < DEPTH; ++i) af[i] = a_at(i);
   __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int idx = 0; idx < NP; ++idx) {
+  static_for<NP>([&](auto IDX) __attribute__((always_inline)) {
+    constexpr int idx = decltype(IDX)::value;
     if (idx & 1) st[1] = M::mma(af[idx % DEPTH], qf[idx >> 1], st[1]);
     else st[0] = M::mma(af[idx % DEPTH], qf[idx >> 1], st[0]);
     if (idx + DEPTH < NP) af[idx % DEPTH] = a_at(idx + DEPTH);
+    between(IDX);
     __builtin_amdgcn_sched_barrier(0);
-  }
+  });
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void sa_qk(const T* __restrict__ Ks, const typename Mma<T>::frag (&qf)[D / Mma<T>::KK],
+                                      floatx16 (&st)[2], int r, int g) {
+  sa_qk<T, D>(Ks, qf, st, r, g, [](auto) {});
 }
 
 // MASK: 0 = every key of the tile is visible to every row of the wave, 1 = retained tile with a ragged end,
@@ -197,7 +209,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   const int kst = (int)a.k_st;
 
   // Per-lane constants of the direct-to-LDS requests.  Request j of this wave fills the 1 KB LDS segment
-  // number (wave + 4 j) of a tile; lane L lands at segment + 16 L, i.e. at LDS (row, slot); it therefore
+  // number (wave + NW j) of a tile; lane L lands at segment + 16 L, i.e. at LDS (row, slot); it therefore
   // fetches the global 16-byte column  slot ^ swizzle(row)  of the key (K) or feature row (V^T) that LDS row
   // holds.  Every request is "tile base (wave-uniform) + constant per-lane element offset", so a tile costs
   // no per-lane address arithmetic.
@@ -206,7 +218,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   int k_key[Cf::K_INSTR], k_col[Cf::K_INSTR];
 #pragma unroll
   for (int j = 0; j < Cf::K_INSTR; ++j) {
-    const int v = (wave + 4 * j) * 64 + lane;          // 16-byte vector index inside the tile
+    const int v = (wave + Cf::NW * j) * 64 + lane;          // 16-byte vector index inside the tile
     const int lrow = v / Cf::KVR, slot = v % Cf::KVR;
     k_key[j] = (lrow & ~31) + M::kappa(lrow & 31);     // LDS row lrow holds key kappa(lrow) of its 32-block
     k_col[j] = (slot ^ Cf::kswz(lrow)) * Cf::EPV;
@@ -215,7 +227,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   }
 #pragma unroll
   for (int j = 0; j < Cf::V_INSTR; ++j) {
-    const int v = (wave + 4 * j) * 64 + lane;
+    const int v = (wave + Cf::NW * j) * 64 + lane;
     const int lrow = v / Cf::VVR, slot = v % Cf::VVR;
     const int col = (slot ^ Cf::vswz(lrow)) * Cf::EPV;
     v_off_ret[j] = (uint32_t)(lrow * a.cap + col);
@@ -231,18 +243,18 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       const T* base = kret + (int64_t)kb * D;
 #pragma unroll
       for (int j = 0; j < Cf::K_INSTR; ++j)
-        async_copy16(base + k_off_ret[j], lds_address(dst + 4 * j * 64 * Cf::EPV));
+        async_copy16(base + k_off_ret[j], lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
     } else if (kb + BN <= N) {
       const T* base = kloc + (int64_t)kb * kst;
 #pragma unroll
       for (int j = 0; j < Cf::K_INSTR; ++j)
-        async_copy16(base + k_off_loc[j], lds_address(dst + 4 * j * 64 * Cf::EPV));
+        async_copy16(base + k_off_loc[j], lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
     } else {   // last tile of a ragged sequence: rows past the end re-read the last token (masked later)
 #pragma unroll
       for (int j = 0; j < Cf::K_INSTR; ++j) {
         int tok = kb + k_key[j];
         tok = tok < N ? tok : N - 1;
-        async_copy16(kloc + ((int64_t)tok * kst + k_col[j]), lds_address(dst + 4 * j * 64 * Cf::EPV));
+        async_copy16(kloc + ((int64_t)tok * kst + k_col[j]), lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
       }
     }
   };
@@ -253,12 +265,12 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       const T* base = vrett + kb;
 #pragma unroll
       for (int j = 0; j < Cf::V_INSTR; ++j)
-        async_copy16(base + v_off_ret[j], lds_address(dst + 4 * j * 64 * Cf::EPV));
+        async_copy16(base + v_off_ret[j], lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
     } else {
       const T* base = vtl + kb;
 #pragma unroll
       for (int j = 0; j < Cf::V_INSTR; ++j)
-        async_copy16(base + v_off_loc[j], lds_address(dst + 4 * j * 64 * Cf::EPV));
+        async_copy16(base + v_off_loc[j], lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
     }
   };
   // wave-uniform: does this wave use tile ti, and with which mask variant
@@ -293,6 +305,11 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   request_k(0);
   request_v(0);
   if (n_tiles > 1) request_k(1);
+  // The query loads are the only global loads the compiler knows of.  Consuming them here makes it wait for
+  // them once, before the loop; otherwise it re-waits at their first use inside every trip of the loop
+  // (s_waitcnt vmcnt(n) with small n), which also waits for the tile requests issued just before.
+#pragma unroll
+  for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(qf[s]));
   wait_async_copies();
   lds_barrier();
   floatx16 st_a[2], st_b[2];
@@ -317,7 +334,45 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
     wait_async_copies();
     lds_barrier();
   };
-  for (int ti = 0; ti < n_tiles; ti += 2) {           // two steps per trip: the S tiles swap roles, no copies
+  // Steady state over the retained set: while tiles ti and ti+1 are fully visible to this wave and the tiles
+  // requested during the step (K(ti+2), V(ti+1)) are retained ones, a step needs no per-tile decisions.  Waves
+  // may leave this loop at different tiles: both loops execute exactly one barrier per tile.
+  auto steady_step = [&](int ti, floatx16 (&st_cur)[2], floatx16 (&st_next)[2]) __attribute__((always_inline)) {
+    const T* kbase = kret + (int64_t)(ti + 2) * BN * D;
+    const T* vbase = vrett + (ti + 1) * BN;
+    T* kdst = Kl + (ti & 1) * Cf::K_ELEMS + wave_s * 64 * Cf::EPV;
+    T* vdst = Vl + ((ti + 1) & 1) * Cf::V_ELEMS + wave_s * 64 * Cf::EPV;
+    constexpr int NC = Cf::K_INSTR + Cf::V_INSTR, NP = 2 * KS;
+    auto issue = [&](auto IDX) __attribute__((always_inline)) {
+      constexpr int idx = decltype(IDX)::value;
+      static_for<NC>([&](auto CC) __attribute__((always_inline)) {
+        constexpr int c = decltype(CC)::value;
+        if constexpr ((c * NP) / NC == idx) {   // request c follows product floor(c NP / NC)
+          if constexpr (c < Cf::K_INSTR)
+            async_copy16(kbase + k_off_ret[c], lds_address(kdst + Cf::NW * c * 64 * Cf::EPV));
+          else
+            async_copy16(vbase + v_off_ret[c - Cf::K_INSTR],
+                         lds_address(vdst + Cf::NW * (c - Cf::K_INSTR) * 64 * Cf::EPV));
+        }
+      });
+    };
+    sa_qk<T, D>(Kl + ((ti + 1) & 1) * Cf::K_ELEMS, qf, st_next, r, g, issue);
+    sa_softmax_pv<T, D, 0>(Vl + (ti & 1) * Cf::V_ELEMS, st_cur, o, m_ref, lpart, ti * BN, ret_w, lo_w, t, sc2, r, g);
+    wait_async_copies();
+    lds_barrier();
+  };
+  int ti = 0;
+  {
+    // last even ti (exclusive) such that tiles ti+1 (fully visible) and ti+2, ti+3 (retained) qualify
+    int n_steady = wave_active ? ret_w / BN - 1 : 0;             // ti + 1 < ret_w / BN  for both steps of a trip
+    if (n_steady > n_ret_tiles - 3) n_steady = n_ret_tiles - 3;  // ti + 3 < n_ret_tiles
+    n_steady = __builtin_amdgcn_readfirstlane(n_steady);
+    for (; ti < n_steady; ti += 2) {
+      steady_step(ti, st_a, st_b);
+      steady_step(ti + 1, st_b, st_a);
+    }
+  }
+  for (; ti < n_tiles; ti += 2) {                     // two steps per trip: the S tiles swap roles, no copies
     step(ti, st_a, st_b);
     if (ti + 1 < n_tiles) step(ti + 1, st_b, st_a);
   }
@@ -364,7 +419,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
 }
 
 template <typename T, int D>
-__global__ __launch_bounds__(256, 2) void sa_kernel(SaArgs a) {
+__global__ __launch_bounds__(kSaRows * 2, kSaRows == 128 ? 2 : 1) void sa_kernel(SaArgs a) {
   sa_body<T, D>(a);
 }
 
@@ -375,7 +430,7 @@ static hipError_t launch_sa_t(const SaArgs& a, int B, hipStream_t stream) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cf::smem_bytes);
   if (e != hipSuccess) return e;
-  dim3 grid((unsigned)(a.ntiles * a.Hq * B)), block(256);
+  dim3 grid((unsigned)(a.ntiles * a.Hq * B)), block(64 * Cf::NW);
   hipLaunchKernelGGL(kern, grid, block, Cf::smem_bytes, stream, a);
   return hipGetLastError();
 }
