@@ -127,6 +127,12 @@ def test_c1_fp32_full():
     dict(dtype="bf16", d=128, C=128, W=128, N=1000, Hq=4, Hkv=2, B=2),
     dict(dtype="bf16", d=128, C=64, W=128, N=777),
     dict(dtype="bf16", d=64, C=128, W=33, N=1024, lam=5),
+    # long retained sets: the sparse-attention kernel's steady-state loop over fully visible retained tiles,
+    # with workgroups spanning two chunks (C = 64) and ragged ends
+    dict(dtype="f32", d=64, C=64, W=64, N=1500, lam=32),
+    dict(dtype="f32", d=128, C=64, W=128, N=1700, lam=32, Hq=1, Hkv=1),
+    dict(dtype="bf16", d=128, C=64, W=64, N=1900, lam=48, Hq=2, Hkv=1),
+    dict(dtype="bf16", d=64, C=64, W=64, N=1333, lam=40, Hq=2, Hkv=2),
 ], ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
 def test_small_shapes(kw):
     w = small("small", **kw)
