@@ -118,6 +118,7 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   L->seg = take((size_t)B * Hq * nseg * (2 * df * (d + 1)) * 4);
   L->n_la = take((size_t)B * Hq * N * d * 4);
   L->d_la = take((size_t)B * Hq * N * 4);
+  L->phik = take(nseg > 1 ? (size_t)(B * Hq * nseg * G * still::la_phik_unit_bytes((int64_t)es, df, p->C)) : 0);
   L->total = off;
   L->n_pad = (int32_t)npad;
   L->cap = (int32_t)cap;
@@ -280,6 +281,8 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   la.seg = reinterpret_cast<float*>(ws + L.seg);
   la.n_la = reinterpret_cast<float*>(ws + L.n_la);
   la.d_la = reinterpret_cast<float*>(ws + L.d_la);
+  la.phik = L.nseg > 1 ? ws + L.phik : nullptr;
+  la.phik_unit = still::la_phik_unit_bytes((int64_t)esize(p->dtype), p->d_f, C);
   still_state_layout_t SL{};
   unsigned char* stp = static_cast<unsigned char*>(state_out);
   if (state_out != nullptr) compute_state_layout(p, &SL);

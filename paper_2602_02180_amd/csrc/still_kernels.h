@@ -59,7 +59,17 @@ struct LaArgs {
   float* n_la;         // [B, Hq, N, d]
   float* d_la;         // [B, Hq, N]
   float* s_final;      // nullable [B, Hq, DP*(D+1)]: state after chunk (last chunk - 2)
+  // nullable [B, Hq, nseg, seg_chunks][phik_unit bytes]: the staged key features of every unit of the state
+  // pass (its LDS slot and softmax sums, byte for byte), which the output pass then copies instead of
+  // recomputing them
+  unsigned char* phik;
+  int64_t phik_unit;
 };
+
+// bytes of one staged key-feature unit: phi_k as [2 d_f][C + pad] elements, then [2][d_f/32][C] partial sums
+inline int64_t la_phik_unit_bytes(int64_t es, int64_t df, int64_t C) {
+  return es * 2 * df * (C + 16 / es) + 4 * 2 * (df / 32) * C;
+}
 
 // query rows per workgroup of the sparse-attention kernel (one wave per 32 rows)
 constexpr int kSaRows = 128;

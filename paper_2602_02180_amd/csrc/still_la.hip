@@ -7,11 +7,14 @@
 //
 // The chunk scan is cut into segments so that a single long sequence still fills the chip:
 //   la_state  (MODE 0): one workgroup per (batch, head, segment) sums  phi_k^T v  and  sum phi_k  over the
-//                       segment's chunks; the feature map never leaves the CU.
+//                       segment's chunks, and leaves every staged K unit (LDS slot + softmax sums) in global
+//                       memory for the output pass, which needs exactly the same units again.
 //   la_prefix          : exclusive prefix over segments (elementwise, tiny).
 //   la_out    (MODE 1): one workgroup per (batch, head, segment) starts from the prefix state and walks its
 //                       chunks: N_LA, D_LA of chunk c from the state through chunk c-2, then the state
-//                       absorbs chunk c-1.
+//                       absorbs chunk c-1.  Its producers compute the query features only; the key features
+//                       are copied from what the state pass left (they are recomputed only when the scan has
+//                       a single segment and no state pass runs).
 // Segment s of the state pass covers chunks [s*G-1, (s+1)*G-1), so the exclusive prefix handed to the
 // output pass of segment s is exactly the state through chunk s*G-2.
 //
@@ -80,6 +83,9 @@ struct LaSmem {
   static constexpr int STAT_FLOATS = 2 * NV * 32 * 4;                     // one buffer: [tile][wave][token]{nf2,max,min,nx2}
   static constexpr size_t stat_bytes = sizeof(float) * 2 * STAT_FLOATS;   // two buffers (sub-unit parity)
   static constexpr size_t sums_bytes = sizeof(float) * 2 * 2 * NV * C;    // [unit parity][half][wave][token]
+  static constexpr size_t unit_sums_bytes = sums_bytes / 2;               // one unit's sums
+  static constexpr size_t unit_bytes = phik_bytes + unit_sums_bytes;      // a staged K unit as kept in global memory
+  static_assert(phik_bytes % 1024 == 0 && unit_sums_bytes % 1024 == 0, "units are copied in 1 KB pieces");
   static constexpr size_t inv_bytes = sizeof(float) * NM * 2 * C;         // [consumer wave][half][token]
   static constexpr size_t z_bytes = sizeof(float) * DP;
   static constexpr size_t keep_bytes = NV * C;                            // [producer wave][token] flags
@@ -173,6 +179,13 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
   // m-1 and the first step of sub-unit m, two independent instruction streams that hide each other's
   // latencies.  The consumers handle sub-unit m in interval m+2.  Both roles execute n_units*NSUB + 2 barriers.
   const int M_sub = n_units * NSUB;
+  // The state pass leaves every K unit it staged (LDS slot + sums) in global memory; the output pass of the same
+  // segment needs exactly those units again (K(c_beg-1) .. K(c_beg+G-3)) and copies them straight into its slots.
+  const bool copy_k = MODE == 1 && a.phik != nullptr;
+  unsigned char* const phik_seg =
+      a.phik == nullptr ? nullptr
+                        : a.phik + ((((int64_t)b * a.Hq + hq) * a.nseg + seg) * (int64_t)G) * a.phik_unit;
+  auto phik_unit_ptr = [&](const LaUnit& x) { return phik_seg + (int64_t)(x.chunk - (c_beg - 1)) * a.phik_unit; };
   if (!consumer) {
     // ---- producer wave v: features [32v, 32v+32) of f = x W for ALL tokens.  Its 32 rows of W^T stay in
     // registers, so the projection weights are read once per unit instead of once per token tile.  The
@@ -206,6 +219,17 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 #pragma unroll
       for (int j = 0; j < 2; ++j) selv[j] = (x.valid && lane + 64 * j < a.lam) ? selc[lane + 64 * j] : -1;
     };
+    // whole staged K unit -> slot and sums, 1 KB per request, dealt over the producer waves
+    auto issue_k_copy = [&](int u) __attribute__((always_inline)) {
+      const int lane = fresh_lane_id();
+      const unsigned char* src = phik_unit_ptr(unit_at(u)) + lane * 16;
+      unsigned char* slot = smem + (u & 1) * SLOT;
+      unsigned char* sums_u = reinterpret_cast<unsigned char*>(sums + (u & 1) * (2 * NV * C));
+      for (int i = v; i < (int)(L::phik_bytes / 1024); i += NV)
+        async_copy16(src + i * 1024, lds_address(slot + i * 1024));
+      for (int i = v; i < (int)(L::unit_sums_bytes / 1024); i += NV)
+        async_copy16(src + L::phik_bytes + i * 1024, lds_address(sums_u + i * 1024));
+    };
     {
       const LaUnit x0 = unit_at(0);
       load_x(x0, 0, 0, r, g);
@@ -222,9 +246,16 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
       // then recomputed where they are used (a few integer operations each) instead of being kept in
       // registers across the whole scan, where they would not fit.
       const int lane = fresh_lane_id(), r = lane & 31, g = lane >> 5;
-      if (m >= 1) {
+      const int mp = m - 1, up = mp / NSUB, subp = mp % NSUB;
+      // A copied K unit always lands in slot 1 (K units are the odd units).  The consumers read the previous K
+      // unit until the end of interval NSUB*(up-1)+1 and this one from interval NSUB*up+2 on: with two sub-units
+      // per unit the requests go out in interval NSUB*up, with one they have to wait for interval NSUB*up+1;
+      // either way they must have landed when interval NSUB*up+1 ends.
+      const bool k_prev = m >= 1 && copy_k && unit_at(up).kind == 1;
+      if (k_prev) {
+        if (NSUB == 1) issue_k_copy(up);
+      } else if (m >= 1) {
         // ---- second step of sub-unit m-1: statistics of all waves -> exponentials -> slot
-        const int mp = m - 1, up = mp / NSUB, subp = mp % NSUB;
         const LaUnit x = unit_at(up);
         unsigned char* slot = smem + (up & 1) * SLOT;
         float* sums_u = sums + (up & 1) * (2 * NV * C);
@@ -294,13 +325,23 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
           }
         }
       }
-      if (m < M_sub) {
+      if (m < M_sub && copy_k && unit_at(m / NSUB).kind == 1) {
+        const int u = m / NSUB, sub = m % NSUB;
+        if (NSUB > 1 && sub == 0) issue_k_copy(u);
+        // warm the cache for the rows of the next Q unit while there is nothing to project
+        if (u + 1 < n_units && v < 2) {
+          const T* wp = row_ptr(unit_at(u + 1), 2 * sub + v, r, 0) + g * (128 / sizeof(T));
+          if (g * (128 / sizeof(T)) < D) async_copy4(wp, lds_address(warm));
+        }
+      } else if (m < M_sub) {
         // ---- first step of sub-unit m: projection, partial statistics
         const int u = m / NSUB, sub = m % NSUB;
         const LaUnit x = unit_at(u);
-        const bool more = m + 1 < M_sub;
-        const LaUnit xn = unit_at(more ? (m + 1) / NSUB : u);
-        const int subn = (m + 1) % NSUB;
+        // the next sub-unit that is projected (copied K units are skipped)
+        const int subn = sub + 1 < NSUB ? sub + 1 : 0;
+        const int un = sub + 1 < NSUB ? u : u + (copy_k ? 2 : 1);
+        const bool more = un < n_units;
+        const LaUnit xn = unit_at(more ? un : u);
         const T* bias = x.kind == 0 ? bq : bk;
         float* statc = stat + (m & 1) * L::STAT_FLOATS;
         if (x.kind == 1 && sub == 0) {
@@ -352,13 +393,14 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
         if (more && xn.kind != x.kind) load_w(xn.kind, r, g);
         // Warm the cache for the sub-unit after the next one: a 4-byte load per 128-byte line of its rows,
         // landing in a scratch corner of LDS (no registers are held while it is in flight).
-        if (m + 2 < M_sub && v < 2) {
+        if (!copy_k && m + 2 < M_sub && v < 2) {
           const LaUnit xw = unit_at((m + 2) / NSUB);
           const T* wp = row_ptr(xw, 2 * ((m + 2) % NSUB) + v, r, 0) + g * (128 / sizeof(T));
           if (g * (128 / sizeof(T)) < D)
             async_copy4(wp, lds_address(warm));
         }
       }
+      if (k_prev && subp == 0) wait_async_copies();
       lds_barrier();
     }
     lds_barrier();
@@ -572,6 +614,18 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
     make_inv(u, sub);
     consume_k(u, vf, IC<2 * sub>{});
     consume_k(u, vf, IC<2 * sub + 1>{});
+    if constexpr (MODE == 0 && sub == NSUB - 1) {
+      // the unit is complete in LDS and stays untouched for two more intervals: leave a copy for the output pass
+      if (a.phik != nullptr) {
+        const int lane = fresh_lane_id();
+        Vec16* dst = reinterpret_cast<Vec16*>(phik_unit_ptr(unit_at(u)));
+        const Vec16* src = reinterpret_cast<const Vec16*>(smem + (u & 1) * SLOT);
+        for (int i = wave * 64 + lane; i < (int)(L::phik_bytes / 16); i += NM * 64) dst[i] = src[i];
+        const Vec16* ssrc = reinterpret_cast<const Vec16*>(sums + (u & 1) * (2 * NV * C));
+        for (int i = wave * 64 + lane; i < (int)(L::unit_sums_bytes / 16); i += NM * 64)
+          dst[L::phik_bytes / 16 + i] = ssrc[i];
+      }
+    }
     lds_barrier();
   };
   auto consume_q_unit = [&](int u) __attribute__((always_inline)) {
@@ -680,7 +734,8 @@ static hipError_t launch_la_mode(const LaArgs& a, int dtype, int d, int B, int n
 }
 
 hipError_t launch_la_state(const LaArgs& a, int dtype, int d, int B, hipStream_t stream) {
-  return launch_la_mode<0>(a, dtype, d, B, a.nseg - 1, stream);
+  // the last segment's sum is not needed by the prefix, but its staged key features are needed by the output pass
+  return launch_la_mode<0>(a, dtype, d, B, a.phik != nullptr ? a.nseg : a.nseg - 1, stream);
 }
 
 hipError_t launch_la_prefix(const LaArgs& a, int d, int B, hipStream_t stream) {
