@@ -114,8 +114,28 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 
-// exchange with the other lane group (lane ^ 32)
-__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+// Reductions over the two lane groups (lane and lane ^ 32) without an LDS round trip: v_permlane32_swap
+// exchanges the upper 32 lanes of its first operand with the lower 32 lanes of its second; given the same value
+// twice it leaves the lower group's values in every lane of one result and the upper group's in the other.
+struct LaneGroups {
+  float lo, hi;   // value of lane (l & 31) and of lane (l & 31) + 32, in every lane
+};
+__device__ __forceinline__ LaneGroups lane_groups(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return {__uint_as_float(r[0]), __uint_as_float(r[1])};
+}
+__device__ __forceinline__ float sum32(float x) {
+  const LaneGroups p = lane_groups(x);
+  return p.lo + p.hi;
+}
+__device__ __forceinline__ float max32(float x) {
+  const LaneGroups p = lane_groups(x);
+  return fmaxf(p.lo, p.hi);
+}
+__device__ __forceinline__ float min32(float x) {
+  const LaneGroups p = lane_groups(x);
+  return fminf(p.lo, p.hi);
+}
 
 template <typename T>
 __device__ __forceinline__ float to_f32(T x) { return static_cast<float>(x); }

@@ -68,6 +68,19 @@ __device__ __forceinline__ typename Mma<T>::frag frag_scale(typename Mma<T>::fra
   }
 }
 
+// 16 bytes of raw data carried in an operand-fragment register set (16-byte fragments only)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <typename F>
+__device__ __forceinline__ F frag_from_bits(u32x4 x) {
+  if constexpr (sizeof(F) == 16) return __builtin_bit_cast(F, x);
+  else return F{};
+}
+template <typename F>
+__device__ __forceinline__ u32x4 frag_to_bits(F f) {
+  if constexpr (sizeof(F) == 16) return __builtin_bit_cast(u32x4, f);
+  else return u32x4{};
+}
+
 template <typename T, int D, int DF, int C>
 struct LaSmem {
   static constexpr int DP = 2 * DF;
@@ -219,16 +232,58 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 #pragma unroll
       for (int j = 0; j < 2; ++j) selv[j] = (x.valid && lane + 64 * j < a.lam) ? selc[lane + 64 * j] : -1;
     };
-    // whole staged K unit -> slot and sums, 1 KB per request, dealt over the producer waves
-    auto issue_k_copy = [&](int u) __attribute__((always_inline)) {
+    // A staged K unit (slot, then sums) travels global memory -> registers -> LDS in 1 KB pieces dealt over the
+    // producer waves: the loads go out in the unit's first interval, when the producers have nothing to project
+    // and their registers are free; the LDS writes follow at the top of the next interval, when the consumers
+    // have left the slot.  (Direct-to-LDS requests sustain only ~16 bytes per clock and CU and hold up the wave
+    // that issues them; ordinary 16-byte loads are four times as fast.)
+    constexpr int NPIECE_K = (int)(L::phik_bytes / 1024), NPIECE = NPIECE_K + (int)(L::unit_sums_bytes / 1024);
+    constexpr int NST = (NPIECE + NV - 1) / NV;
+    // Staging registers: the token-row fragments xb are free exactly while a unit is in flight (the rows of the
+    // next Q unit are requested only in the K unit's last interval), so with 16-byte fragments they carry the
+    // first 2*KS pieces themselves; the compiler cannot see that the two live ranges never overlap around the
+    // loop, and a separate array would be spilled.
+    // (With one sub-unit per unit the rows of the next Q unit are requested in the same interval as the staged
+    // unit, so the fragments are not free; those units are small enough for an array of their own.)
+    constexpr int NXB = (sizeof(typename M::frag) == 16 && NSUB > 1) ? (2 * KS < NST ? 2 * KS : NST) : 0;
+    u32x4 stage[NST - NXB > 0 ? NST - NXB : 1];
+    auto put_piece = [&](auto J, u32x4 x) __attribute__((always_inline)) {
+      constexpr int j = decltype(J)::value;
+      if constexpr (j < NXB) xb[j / KS][j % KS] = frag_from_bits<typename M::frag>(x);
+      else stage[j - NXB] = x;
+    };
+    auto get_piece = [&](auto J) __attribute__((always_inline)) -> u32x4 {
+      constexpr int j = decltype(J)::value;
+      if constexpr (j < NXB) return frag_to_bits<typename M::frag>(xb[j / KS][j % KS]);
+      else return stage[j - NXB];
+    };
+    auto load_k_unit = [&](int u) __attribute__((always_inline)) {
       const int lane = fresh_lane_id();
       const unsigned char* src = phik_unit_ptr(unit_at(u)) + lane * 16;
-      unsigned char* slot = smem + (u & 1) * SLOT;
-      unsigned char* sums_u = reinterpret_cast<unsigned char*>(sums + (u & 1) * (2 * NV * C));
-      for (int i = v; i < (int)(L::phik_bytes / 1024); i += NV)
-        async_copy16(src + i * 1024, lds_address(slot + i * 1024));
-      for (int i = v; i < (int)(L::unit_sums_bytes / 1024); i += NV)
-        async_copy16(src + L::phik_bytes + i * 1024, lds_address(sums_u + i * 1024));
+      static_for<NST>([&](auto J) __attribute__((always_inline)) {
+        constexpr int j = decltype(J)::value;
+        // (when the pieces divide evenly among the waves there is no test: a branch per load would break the
+        // burst into a chain of blocks)
+        if (NPIECE % NV == 0 || v + j * NV < NPIECE)
+          put_piece(J, *reinterpret_cast<const u32x4*>(src + (v + j * NV) * 1024));
+      });
+    };
+    auto store_k_unit = [&](int u) __attribute__((always_inline)) {
+      const int lane = fresh_lane_id();
+      unsigned char* slot = smem + (u & 1) * SLOT + lane * 16;
+      unsigned char* sums_u = reinterpret_cast<unsigned char*>(sums + (u & 1) * (2 * NV * C)) + lane * 16;
+      static_for<NST>([&](auto J) __attribute__((always_inline)) {
+        constexpr int j = decltype(J)::value;
+        const int i = v + j * NV;
+        if constexpr (NPIECE % NV == 0 && NPIECE_K % NV == 0) {
+          // piece j of every wave lies on the same side of the slot / sums boundary
+          if constexpr (j * NV < NPIECE_K) *reinterpret_cast<u32x4*>(slot + i * 1024) = get_piece(J);
+          else *reinterpret_cast<u32x4*>(sums_u + (i - NPIECE_K) * 1024) = get_piece(J);
+        } else {
+          if (i < NPIECE_K) *reinterpret_cast<u32x4*>(slot + i * 1024) = get_piece(J);
+          else if (i < NPIECE) *reinterpret_cast<u32x4*>(sums_u + (i - NPIECE_K) * 1024) = get_piece(J);
+        }
+      });
     };
     {
       const LaUnit x0 = unit_at(0);
@@ -248,12 +303,11 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
       const int lane = fresh_lane_id(), r = lane & 31, g = lane >> 5;
       const int mp = m - 1, up = mp / NSUB, subp = mp % NSUB;
       // A copied K unit always lands in slot 1 (K units are the odd units).  The consumers read the previous K
-      // unit until the end of interval NSUB*(up-1)+1 and this one from interval NSUB*up+2 on: with two sub-units
-      // per unit the requests go out in interval NSUB*up, with one they have to wait for interval NSUB*up+1;
-      // either way they must have landed when interval NSUB*up+1 ends.
+      // unit until the end of interval NSUB*(up-1)+1 and this one from interval NSUB*up+2 on, so it is written in
+      // interval NSUB*up+1, from registers loaded in interval NSUB*up.
       const bool k_prev = m >= 1 && copy_k && unit_at(up).kind == 1;
       if (k_prev) {
-        if (NSUB == 1) issue_k_copy(up);
+        if (subp == 0) store_k_unit(up);
       } else if (m >= 1) {
         // ---- second step of sub-unit m-1: statistics of all waves -> exponentials -> slot
         const LaUnit x = unit_at(up);
@@ -296,8 +350,8 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
             sp = M::sum_into(pf[s], sp);
             sn = M::sum_into(nf[s], sn);
           }
-          sp += xor32(sp);
-          sn += xor32(sn);
+          sp = sum32(sp);
+          sn = sum32(sn);
           const float srec = g ? sn : sp;   // lane group g records the sum of half g
           sums_u[(g * NV + v) * C + tl] = live ? srec : 1.f;
           if (x.kind == 0) {
@@ -327,20 +381,30 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
       }
       if (m < M_sub && copy_k && unit_at(m / NSUB).kind == 1) {
         const int u = m / NSUB, sub = m % NSUB;
-        if (NSUB > 1 && sub == 0) issue_k_copy(u);
-        // warm the cache for the rows of the next Q unit while there is nothing to project
-        if (u + 1 < n_units && v < 2) {
-          const T* wp = row_ptr(unit_at(u + 1), 2 * sub + v, r, 0) + g * (128 / sizeof(T));
-          if (g * (128 / sizeof(T)) < D) async_copy4(wp, lds_address(warm));
+        if (sub == 0) load_k_unit(u);
+        if (u + 1 < n_units) {
+          // The token rows of the next Q unit's first sub-unit are requested here, in the K unit's last interval,
+          // not right after their registers were last used: until now those registers carried the staged unit.
+          if (sub == NSUB - 1) {
+            load_x(unit_at(u + 1), 0, 0, r, g);
+            load_x(unit_at(u + 1), 1, 1, r, g);
+          }
+          // warm the cache for that unit's rows while there is nothing to project
+          if (v < 2) {
+            const T* wp = row_ptr(unit_at(u + 1), 2 * sub + v, r, 0) + g * (128 / sizeof(T));
+            if (g * (128 / sizeof(T)) < D) async_copy4(wp, lds_address(warm));
+          }
         }
       } else if (m < M_sub) {
         // ---- first step of sub-unit m: projection, partial statistics
         const int u = m / NSUB, sub = m % NSUB;
         const LaUnit x = unit_at(u);
         // the next sub-unit that is projected (copied K units are skipped)
+        // the next sub-unit whose rows this step requests (after a Q unit's last sub-unit in copy mode: none, the
+        // copied K unit in between does it)
         const int subn = sub + 1 < NSUB ? sub + 1 : 0;
-        const int un = sub + 1 < NSUB ? u : u + (copy_k ? 2 : 1);
-        const bool more = un < n_units;
+        const int un = sub + 1 < NSUB ? u : u + 1;
+        const bool more = un < n_units && !(copy_k && un != u);
         const LaUnit xn = unit_at(more ? un : u);
         const T* bias = x.kind == 0 ? bq : bk;
         float* statc = stat + (m & 1) * L::STAT_FLOATS;
@@ -365,7 +429,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
           if (NV == 1 || (v & 1) == j) {
 #pragma unroll
             for (int s = 0; s < KS; ++s) n2 = M::dot_into(xb[j][s], xb[j][s], n2);
-            n2 += xor32(n2);
+            n2 = sum32(n2);
           }
           // the rows are dead now: request the tile that will use the same registers
           if (more) load_x(xn, 2 * subn + j, j, r, g);
@@ -380,9 +444,9 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
             fmax = fmaxf(fmax, acc[i]);
             fmin = fminf(fmin, acc[i]);
           }
-          nf2 += xor32(nf2);
-          fmax = fmaxf(fmax, xor32(fmax));
-          fmin = fminf(fmin, xor32(fmin));
+          nf2 = sum32(nf2);
+          fmax = max32(fmax);
+          fmin = min32(fmin);
           if (g == 0) {
             floatx4 st;
             st[0] = nf2; st[1] = fmax; st[2] = fmin; st[3] = n2;
@@ -400,7 +464,6 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
             async_copy4(wp, lds_address(warm));
         }
       }
-      if (k_prev && subp == 0) wait_async_copies();
       lds_barrier();
     }
     lds_barrier();
@@ -503,7 +566,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 #pragma unroll
       for (int sh = 0; sh < HS; ++sh)
         zp += frag_dot<T>(M::load(zrow + sh * M::KK), izp + (ft >= FT ? C : 0) + sh * M::KK);
-      zp += xor32(zp);
+      zp = sum32(zp);
       if (g == 0) zsh[32 * ft + r] += zp;
     }
   };
@@ -648,7 +711,18 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
       consume_k_unit(u, vf);
       // V of the next K unit is requested BEFORE this unit's N_LA stores: the vector-memory counter retires
       // in order, so a later wait for these loads does not have to wait for the stores as well
-      if (u + 2 < n_units) load_v(u + 2, vf);
+      if (u + 2 < n_units) {
+        load_v(u + 2, vf);
+        // One interval before the producers fetch the next staged K unit, touch each of its 128-byte lines (4-byte
+        // direct-to-LDS loads into a scratch corner, no registers held): a CU can only keep a few KB of misses in
+        // flight, and 72 KB straight from HBM would take the producers several memory latencies.
+        if (copy_k) {
+          const int lane = fresh_lane_id();
+          const unsigned char* src = phik_unit_ptr(unit_at(u + 2)) + lane * 128;
+          for (int i = wave; i * 8192 < (int)L::unit_bytes; i += NM)
+            if (i * 8192 + lane * 128 < (int)L::unit_bytes) async_copy4(src + i * 8192, lds_address(warm));
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
       consume_q_unit(u + 1);
     }

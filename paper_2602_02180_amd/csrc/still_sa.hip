@@ -120,7 +120,7 @@ __device__ __forceinline__ void sa_softmax_pv(const T* __restrict__ Vs, floatx16
   for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, st[0][i]);
 #pragma unroll
   for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, st[1][i]);
-  tmax = fmaxf(tmax, xor32(tmax));
+  tmax = max32(tmax);
   const float tm = tmax * sc2;
   if (__any(tm > m_ref + TAU)) {  // wave-uniform; rare once the references have settled
     const float m_new = fmaxf(m_ref, tm);
@@ -379,7 +379,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
 
   // ---- merge epilogue
   if (wave_active && t < N) {
-    const float l = lpart + xor32(lpart);
+    const float l = sum32(lpart);
     const float m2 = m_ref;
     float fs, fl;
     if (m2 >= 0.f) {

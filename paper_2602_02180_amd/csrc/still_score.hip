@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) mraw = fmaxf(mraw, acc[j][i]);
   }
-  mraw = fmaxf(mraw, xor32(mraw));
+  mraw = max32(mraw);
   // pass 2: e = exp(scale * (x - max)); masked entries give exp2(-inf) = 0.  The sums without the diagonal
   // differ from the full sums only in the newest tile.
   const float moff = -mraw * sc2;
@@ -106,8 +106,8 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
     }
   }
   float d_all = d_old + d_new, d_no = d_old + d_new_no;
-  d_all += xor32(d_all);
-  d_no += xor32(d_no);
+  d_all = sum32(d_all);
+  d_no = sum32(d_no);
   const float inv_all = 1.0f / d_all;
   const float inv_no = d_no > 0.f ? 1.0f / d_no : 0.f;
   // pass 3: sum of a_diag * (log(a_diag + eps) - log(a_nodiag + eps)); a masked entry has a_diag = 0 and
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
     }
   }
   score *= kLn2;
-  score += xor32(score);
+  score = sum32(score);
 
   if (g == 0) {
     s_score[32 * wave + r] = score;
