@@ -211,27 +211,34 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   // Per-lane constants of the direct-to-LDS requests.  Request j of this wave fills the 1 KB LDS segment
   // number (wave + NW j) of a tile; lane L lands at segment + 16 L, i.e. at LDS (row, slot); it therefore
   // fetches the global 16-byte column  slot ^ swizzle(row)  of the key (K) or feature row (V^T) that LDS row
-  // holds.  Every request is "tile base (wave-uniform) + constant per-lane element offset", so a tile costs
-  // no per-lane address arithmetic.
+  // holds.  Every request is "tile base (wave-uniform) + constant per-lane element offset".  Only the offsets
+  // into the retained buffers (the steady-state loop's) are kept in registers for the whole kernel; the few
+  // general steps of a workgroup rebuild theirs from the lane id, which costs a handful of integer operations
+  // per request and keeps eight to sixteen registers out of the loop's allocation.
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  uint32_t k_off_ret[Cf::K_INSTR], k_off_loc[Cf::K_INSTR], v_off_ret[Cf::V_INSTR], v_off_loc[Cf::V_INSTR];
-  int k_key[Cf::K_INSTR], k_col[Cf::K_INSTR];
+  auto k_lane = [&](int lane_now, int j, int& key, int& col) __attribute__((always_inline)) {
+    const int v = (wave_s + Cf::NW * j) * 64 + lane_now;     // 16-byte vector index inside the tile
+    const int lrow = v / Cf::KVR, slot = v % Cf::KVR;
+    key = (lrow & ~31) + M::kappa(lrow & 31);                // LDS row lrow holds key kappa(lrow) of its 32-block
+    col = (slot ^ Cf::kswz(lrow)) * Cf::EPV;
+  };
+  auto v_lane = [&](int lane_now, int j, int& lrow, int& col) __attribute__((always_inline)) {
+    const int v = (wave_s + Cf::NW * j) * 64 + lane_now;
+    lrow = v / Cf::VVR;
+    col = ((v % Cf::VVR) ^ Cf::vswz(lrow)) * Cf::EPV;
+  };
+  uint32_t k_off_ret[Cf::K_INSTR], v_off_ret[Cf::V_INSTR];
 #pragma unroll
   for (int j = 0; j < Cf::K_INSTR; ++j) {
-    const int v = (wave + Cf::NW * j) * 64 + lane;          // 16-byte vector index inside the tile
-    const int lrow = v / Cf::KVR, slot = v % Cf::KVR;
-    k_key[j] = (lrow & ~31) + M::kappa(lrow & 31);     // LDS row lrow holds key kappa(lrow) of its 32-block
-    k_col[j] = (slot ^ Cf::kswz(lrow)) * Cf::EPV;
-    k_off_ret[j] = (uint32_t)(k_key[j] * D + k_col[j]);
-    k_off_loc[j] = (uint32_t)(k_key[j] * kst + k_col[j]);
+    int key, col;
+    k_lane(lane, j, key, col);
+    k_off_ret[j] = (uint32_t)(key * D + col);
   }
 #pragma unroll
   for (int j = 0; j < Cf::V_INSTR; ++j) {
-    const int v = (wave + Cf::NW * j) * 64 + lane;
-    const int lrow = v / Cf::VVR, slot = v % Cf::VVR;
-    const int col = (slot ^ Cf::vswz(lrow)) * Cf::EPV;
+    int lrow, col;
+    v_lane(lane, j, lrow, col);
     v_off_ret[j] = (uint32_t)(lrow * a.cap + col);
-    v_off_loc[j] = (uint32_t)(lrow * a.Np + col);
   }
 
   auto tile_kb = [&](int ti) { return ti < n_ret_tiles ? ti * BN : loc_lo + (ti - n_ret_tiles) * BN; };
@@ -244,17 +251,16 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
 #pragma unroll
       for (int j = 0; j < Cf::K_INSTR; ++j)
         async_copy16(base + k_off_ret[j], lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
-    } else if (kb + BN <= N) {
-      const T* base = kloc + (int64_t)kb * kst;
-#pragma unroll
-      for (int j = 0; j < Cf::K_INSTR; ++j)
-        async_copy16(base + k_off_loc[j], lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
-    } else {   // last tile of a ragged sequence: rows past the end re-read the last token (masked later)
+    } else {
+      // rows past the end of a ragged sequence re-read the last token (masked later)
+      const int lane_now = fresh_lane_id();
 #pragma unroll
       for (int j = 0; j < Cf::K_INSTR; ++j) {
-        int tok = kb + k_key[j];
+        int key, col;
+        k_lane(lane_now, j, key, col);
+        int tok = kb + key;
         tok = tok < N ? tok : N - 1;
-        async_copy16(kloc + ((int64_t)tok * kst + k_col[j]), lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
+        async_copy16(kloc + ((int64_t)tok * kst + col), lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
       }
     }
   };
@@ -268,9 +274,13 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
         async_copy16(base + v_off_ret[j], lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
     } else {
       const T* base = vtl + kb;
+      const int lane_now = fresh_lane_id();
 #pragma unroll
-      for (int j = 0; j < Cf::V_INSTR; ++j)
-        async_copy16(base + v_off_loc[j], lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
+      for (int j = 0; j < Cf::V_INSTR; ++j) {
+        int lrow, col;
+        v_lane(lane_now, j, lrow, col);
+        async_copy16(base + ((int64_t)lrow * a.Np + col), lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
+      }
     }
   };
   // wave-uniform: does this wave use tile ti, and with which mask variant
