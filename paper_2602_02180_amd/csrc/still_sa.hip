@@ -387,8 +387,41 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
     if (ti + 1 < n_tiles) step(ti + 1, st_b, st_a);
   }
 
-  // ---- merge epilogue
-  if (wave_active && t < N) {
+  // ---- merge epilogue.  In the accumulator layout a lane owns one row and four consecutive columns per register
+  // quad, so direct loads of N_LA and stores of the output would touch 32 rows with 16-32 bytes each per
+  // instruction.  Both tiles therefore pass through LDS (the K/V slots are free after the last barrier, each wave
+  // uses a private 32-row region, so no further barrier is needed): every global access is a 1 KB contiguous piece,
+  // and the row <-> column exchange happens in LDS, with the 16-byte slot index XOR-ed with the row so that neither
+  // direction meets bank conflicts.
+  {
+    constexpr int ROWB_N = D * 4, NSL = ROWB_N / 16;             // N_LA row: bytes, 16-byte slots
+    constexpr int ROWB_O = D * (int)sizeof(T), NSO = ROWB_O / 16;  // output row
+    constexpr int NREQ = 32 * ROWB_N / 1024, NOUT = 32 * ROWB_O / 1024;
+    static_assert(Cf::NW * 32 * ROWB_N <= (int)Cf::smem_bytes, "epilogue staging fits the tile slots");
+    unsigned char* reg = smem + wave_s * (32 * ROWB_N);
+    const int lane_now = fresh_lane_id();
+    const int64_t unit_row0 = ((int64_t)b * a.Hq + hq) * N;
+    // (1) N_LA rows of this wave -> LDS, in two batches (bounds the staging registers); rows past the end of the
+    //     sequence re-read the last row
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      floatx4 stg[NREQ / 2];
+#pragma unroll
+      for (int i = 0; i < NREQ / 2; ++i) {
+        const int off = (half * (NREQ / 2) + i) * 1024 + lane_now * 16;
+        const int row = off / ROWB_N, slot = (off % ROWB_N) / 16;
+        int tr = q0 + row;
+        tr = tr < N ? tr : N - 1;
+        stg[i] = *reinterpret_cast<const floatx4*>(a.n_la + (unit_row0 + tr) * D + slot * 4);
+      }
+#pragma unroll
+      for (int i = 0; i < NREQ / 2; ++i) {
+        const int off = (half * (NREQ / 2) + i) * 1024 + lane_now * 16;
+        const int row = off / ROWB_N, slot = (off % ROWB_N) / 16;
+        *reinterpret_cast<floatx4*>(reg + row * ROWB_N + ((slot ^ (row & (NSL - 1))) * 16)) = stg[i];
+      }
+    }
+    // (2) y = (fs N_SA + fl N_LA) / (fs D_SA + fl D_LA), in place in the accumulators
     const float l = sum32(lpart);
     const float m2 = m_ref;
     float fs, fl;
@@ -399,32 +432,47 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       fs = fast_exp2(m2);
       fl = 1.f;
     }
-    const int64_t rowi = ((int64_t)b * a.Hq + hq) * N + t;
-    const float dla = a.d_la[rowi];
+    const int tq = t < N ? t : N - 1;
+    const float dla = a.d_la[unit_row0 + tq];
     const float inv = 1.0f / (fs * l + fl * dla);
-    const float* nrow = a.n_la + rowi * D;
-    T* orow = static_cast<T*>(a.out) + (int64_t)b * a.o_sb + (int64_t)t * a.o_st + (int64_t)hq * a.o_sh;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const int dcol = 32 * dt + 8 * i4 + 4 * g;
-        const floatx4 nl = *reinterpret_cast<const floatx4*>(nrow + dcol);
-        float y[4];
+        const int slot = 8 * dt + 2 * i4 + g;                   // columns 32 dt + 8 i4 + 4 g .. + 3
+        const floatx4 nl = *reinterpret_cast<const floatx4*>(reg + r * ROWB_N + ((slot ^ (r & (NSL - 1))) * 16));
 #pragma unroll
-        for (int e = 0; e < 4; ++e) y[e] = (fs * o[dt][4 * i4 + e] + fl * nl[e]) * inv;
+        for (int e = 0; e < 4; ++e) o[dt][4 * i4 + e] = (fs * o[dt][4 * i4 + e] + fl * nl[e]) * inv;
+      }
+    // (3) output tile -> LDS in the storage type (all reads of step 2 were issued before: LDS is in order)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int byte = (32 * dt + 8 * i4 + 4 * g) * (int)sizeof(T);
+        unsigned char* dst = reg + r * ROWB_O + (((byte / 16) ^ (r & (NSO - 1))) * 16) + byte % 16;
         if constexpr (sizeof(T) == 2) {
           bf16x4 ov;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) ov[e] = static_cast<bf16>(y[e]);
-          *reinterpret_cast<bf16x4*>(orow + dcol) = ov;
+          for (int e = 0; e < 4; ++e) ov[e] = static_cast<bf16>(o[dt][4 * i4 + e]);
+          *reinterpret_cast<bf16x4*>(dst) = ov;
         } else {
           floatx4 ov;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) ov[e] = y[e];
-          *reinterpret_cast<floatx4*>(orow + dcol) = ov;
+          for (int e = 0; e < 4; ++e) ov[e] = o[dt][4 * i4 + e];
+          *reinterpret_cast<floatx4*>(dst) = ov;
         }
       }
+    // (4) LDS -> global, 1 KB per instruction
+    T* obase = static_cast<T*>(a.out) + (int64_t)b * a.o_sb + (int64_t)hq * a.o_sh;
+#pragma unroll
+    for (int i = 0; i < NOUT; ++i) {
+      const int off = i * 1024 + lane_now * 16;
+      const int row = off / ROWB_O, slot = (off % ROWB_O) / 16;
+      const Vec16 x = *reinterpret_cast<const Vec16*>(reg + row * ROWB_O + ((slot ^ (row & (NSO - 1))) * 16));
+      const int tr = q0 + row;
+      if (tr < N) *reinterpret_cast<Vec16*>(obase + (int64_t)tr * a.o_st + slot * Cf::EPV) = x;
+    }
   }
 }
 
