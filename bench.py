@@ -30,7 +30,7 @@ PEAK_HBM = 8.0e12
 
 # HBM bytes per launch of the dominant prefill kernel (sparse_attn_merge), measured with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE and scaled by the plain-copy calibration; see profiles/sa_kernel_c4_hbm_traffic.md.  Other configs: null.
-MEASURED_TRAFFIC = {"c4": 1.966e9}
+MEASURED_TRAFFIC = {"c4": 1.882e9}
 
 
 def sparse_branch_flops(w: synth.Workload, N: int) -> float:
