@@ -12,8 +12,13 @@
  * Conventions
  *   - Plain C ABI.  Every tensor, workspace and state pointer is DEVICE memory owned by the caller,
  *     16-byte aligned, unless marked HOST.  The library allocates and frees nothing on the device,
- *     never synchronises the stream, and keeps no global mutable state except a per-thread error text.
- *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *     never synchronises the stream, and keeps no global mutable state except, per host thread, an error
+ *     text, the timing events below and one helper stream with two events (created at the first prefill
+ *     call on a device, default priority, never destroyed while the thread stays on that device).
+ *   - All work is ordered on `stream` (a hipStream_t passed as void*; NULL = the default stream): work
+ *     enqueued on `stream` before a call precedes all of the call's kernels, work enqueued after it follows
+ *     all of them.  still_hybrid_attn_fwd runs two small layout kernels on the helper stream, forked from
+ *     and joined back into `stream` with events, so the same holds under stream capture.
  *   - Tokens and chunks are 0-indexed here (the paper counts from 1).
  *   - Every function returning still_status_t validates its arguments on the host before any launch;
  *     on failure nothing has been enqueued and still_last_error() describes the reason.
@@ -134,10 +139,18 @@ STILL_API still_status_t still_hybrid_attn_fwd(const still_params_t* p,
 /*
  * Optional per-kernel timing of still_hybrid_attn_fwd (used by the benchmark to time the dominant kernel
  * on the stream it is launched on).  While enabled on the calling thread, every prefill call records HIP
- * events (host objects created lazily, one set per thread) around each of its kernels.
- * still_profile_read waits for the last recorded call to finish and writes the duration in milliseconds
- * of up to n kernels into the HOST array ms, in launch order; still_profile_kernel_name(i) names slot i
- * (NULL past the last).  Returns STILL_ERR_STATE if no call was recorded.
+ * events (host objects created lazily, one ring of 64 sets per thread) around each of its kernels; it does
+ * not synchronise.  still_profile_read waits for the last recorded call to finish and writes, for up to n
+ * kernels in launch order, the MEAN duration in milliseconds over the calls recorded since
+ * still_profile_enable(1) (the last 64 of them if there were more) into the HOST array ms;
+ * still_profile_kernel_name(i) names slot i (NULL past the last).  Returns STILL_ERR_STATE if no call was
+ * recorded.  A kernel that a call skips (e.g. the score kernel when the selection is an input) shows as a
+ * zero-length slot.
+ * still_profile_enable(2) records the pair of the last kernel (the sparse-attention + merge kernel) only and
+ * reports 0 for the others: every recorded event is a marker in the stream, and sixteen of them per call cost
+ * a few per cent of a back-to-back run.
+ * The two layout kernels (slots 0 and 1) run on a library-owned second stream next to the score kernel
+ * (slot 2), so the durations of these three overlap and do not add up to the duration of the call.
  */
 #define STILL_PROFILE_SLOTS 8
 STILL_API void still_profile_enable(int32_t on);

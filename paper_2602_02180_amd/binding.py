@@ -201,8 +201,9 @@ def still_hybrid_attn_decode_step(p: StillParams, state, t: int, q_t, k_t, v_t, 
 STILL_PROFILE_SLOTS = 8
 
 
-def still_profile_enable(on: bool) -> None:
-    lib().still_profile_enable(1 if on else 0)
+def still_profile_enable(on) -> None:
+    """False/0 = off, True/1 = every kernel, 2 = the last (dominant) kernel only."""
+    lib().still_profile_enable(int(on))
 
 
 def still_profile_read():

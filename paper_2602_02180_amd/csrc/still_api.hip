@@ -20,24 +20,75 @@ still_status_t fail(still_status_t code, const char* fmt, ...) {
   return code;
 }
 
-// per-thread kernel timing (host-side event objects only)
+// per-thread kernel timing (host-side event objects only): one (begin, end) pair per kernel, recorded on the
+// stream that kernel runs on, in a ring of kProfRing sets so that a run of calls can be timed without a
+// synchronisation in between
+constexpr int kProfRing = 64;
 struct Profile {
-  bool on = false, created = false, recorded = false;
-  hipEvent_t ev[STILL_PROFILE_SLOTS + 1];
+  bool on = false, created = false;
+  bool last_only = false;   // record the last kernel's pair only (fewer markers in the stream)
+  int calls = 0;   // prefill calls recorded since profiling was enabled
+  hipEvent_t beg[kProfRing][STILL_PROFILE_SLOTS], end[kProfRing][STILL_PROFILE_SLOTS];
 };
 thread_local Profile g_prof;
 const char* const kSlotNames[STILL_PROFILE_SLOTS] = {"transpose_v", "transpose_w", "score_select", "gather",
                                                      "la_state",    "la_prefix",   "la_out",       "sparse_attn_merge"};
 
-void prof_mark(int slot, hipStream_t stream) {
-  if (!g_prof.on) return;
+void prof_begin(int slot, hipStream_t stream) {
+  if (!g_prof.on || (g_prof.last_only && slot != STILL_PROFILE_SLOTS - 1)) return;
   if (!g_prof.created) {
-    for (auto& e : g_prof.ev)
-      if (hipEventCreate(&e) != hipSuccess) { g_prof.on = false; return; }
+    for (int r = 0; r < kProfRing; ++r)
+      for (int i = 0; i < STILL_PROFILE_SLOTS; ++i)
+        if (hipEventCreate(&g_prof.beg[r][i]) != hipSuccess || hipEventCreate(&g_prof.end[r][i]) != hipSuccess) {
+          g_prof.on = false;
+          return;
+        }
     g_prof.created = true;
   }
-  (void)hipEventRecord(g_prof.ev[slot], stream);
-  if (slot == STILL_PROFILE_SLOTS) g_prof.recorded = true;
+  (void)hipEventRecord(g_prof.beg[g_prof.calls % kProfRing][slot], stream);
+}
+
+void prof_end(int slot, hipStream_t stream) {
+  if (!g_prof.on || !g_prof.created || (g_prof.last_only && slot != STILL_PROFILE_SLOTS - 1)) return;
+  (void)hipEventRecord(g_prof.end[g_prof.calls % kProfRing][slot], stream);
+  if (slot == STILL_PROFILE_SLOTS - 1) ++g_prof.calls;
+}
+
+// The layout kernels (transposes of v and of the projection weights) do not depend on the scores and are bound by
+// memory, the score kernel by the vector ALU: they run side by side, the layout kernels on a second stream of
+// default priority that forks from the caller's stream at the start of the call and joins it again before the
+// first kernel that reads their output.  One side stream and one event pair per host thread and device.
+struct SideStream {
+  bool ok = false;
+  int dev = -1;
+  hipStream_t s = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+thread_local SideStream g_side;
+
+SideStream* side_stream() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+  if (g_side.ok && g_side.dev == dev) return &g_side;
+  if (g_side.ok) {   // the thread moved to another device: drop the old objects
+    (void)hipEventDestroy(g_side.fork);
+    (void)hipEventDestroy(g_side.join);
+    (void)hipStreamDestroy(g_side.s);
+    g_side.ok = false;
+  }
+  if (hipStreamCreateWithFlags(&g_side.s, hipStreamNonBlocking) != hipSuccess) return nullptr;
+  if (hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) != hipSuccess) {
+    (void)hipStreamDestroy(g_side.s);
+    return nullptr;
+  }
+  if (hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) != hipSuccess) {
+    (void)hipEventDestroy(g_side.fork);
+    (void)hipStreamDestroy(g_side.s);
+    return nullptr;
+  }
+  g_side.dev = dev;
+  g_side.ok = true;
+  return &g_side;
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -219,19 +270,31 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   const bool have_sel = p->lambda > 0 && ncf > 0;
   hipError_t e;
 
-  prof_mark(0, stream);
-  // layout preparation
+  // layout preparation, on the side stream (the caller's stream if it could not be created)
+  SideStream* side = side_stream();
+  hipStream_t s2 = stream;
+  if (side != nullptr) {
+    if (hipEventRecord(side->fork, stream) == hipSuccess && hipStreamWaitEvent(side->s, side->fork, 0) == hipSuccess)
+      s2 = side->s;
+    else
+      side = nullptr;
+  }
+  prof_begin(0, s2);
   still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, N, L.n_pad, p->Hkv, d};
-  if ((e = still::launch_transpose_v(tv, p->dtype, B, stream)) != hipSuccess)
+  if ((e = still::launch_transpose_v(tv, p->dtype, B, s2)) != hipSuccess)
     return fail(STILL_ERR_HIP, "transpose_v: %s", hipGetErrorString(e));
-  prof_mark(1, stream);
+  prof_end(0, s2);
+  prof_begin(1, s2);
   still::TransposeWArgs twq{Wq, ws + L.wqt, p->Hq, d, p->d_f};
   still::TransposeWArgs twk{Wk, ws + L.wkt, p->Hq, d, p->d_f};
-  if ((e = still::launch_transpose_w(twq, p->dtype, stream)) != hipSuccess ||
-      (e = still::launch_transpose_w(twk, p->dtype, stream)) != hipSuccess)
+  if ((e = still::launch_transpose_w(twq, p->dtype, s2)) != hipSuccess ||
+      (e = still::launch_transpose_w(twk, p->dtype, s2)) != hipSuccess)
     return fail(STILL_ERR_HIP, "transpose_w: %s", hipGetErrorString(e));
+  prof_end(1, s2);
+  if (side != nullptr && (e = hipEventRecord(side->join, s2)) != hipSuccess)
+    return fail(STILL_ERR_HIP, "side stream: %s", hipGetErrorString(e));
 
-  prof_mark(2, stream);
+  prof_begin(2, stream);
   // Self-Saliency Score + Top-lambda
   still::ScoreArgs sa{};
   sa.q = q; sa.k = k;
@@ -251,8 +314,9 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
       if (e != hipSuccess) return fail(STILL_ERR_HIP, "score copy: %s", hipGetErrorString(e));
     }
   }
+  prof_end(2, stream);
 
-  prof_mark(3, stream);
+  prof_begin(3, stream);
   // retained K/V of every full chunk
   still::GatherArgs ga{};
   ga.k = k; ga.v = v;
@@ -265,6 +329,10 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   ga.kret = ws + L.kret; ga.vrett = ws + L.vrett;
   if ((e = still::launch_gather(ga, p->dtype, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "gather: %s", hipGetErrorString(e));
+  prof_end(3, stream);
+  // everything below reads the transposed copies
+  if (side != nullptr && (e = hipStreamWaitEvent(stream, side->join, 0)) != hipSuccess)
+    return fail(STILL_ERR_HIP, "side stream: %s", hipGetErrorString(e));
 
   // NP-Map + chunk linear attention
   still::LaArgs la{};
@@ -287,17 +355,20 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   unsigned char* stp = static_cast<unsigned char*>(state_out);
   if (state_out != nullptr) compute_state_layout(p, &SL);
   la.s_final = state_out != nullptr ? reinterpret_cast<float*>(stp + SL.S) : nullptr;
-  prof_mark(4, stream);
+  prof_begin(4, stream);
   if ((e = still::launch_la_state(la, p->dtype, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "la_state: %s", hipGetErrorString(e));
-  prof_mark(5, stream);
+  prof_end(4, stream);
+  prof_begin(5, stream);
   if ((e = still::launch_la_prefix(la, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "la_prefix: %s", hipGetErrorString(e));
-  prof_mark(6, stream);
+  prof_end(5, stream);
+  prof_begin(6, stream);
   if ((e = still::launch_la_out(la, p->dtype, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "la_out: %s", hipGetErrorString(e));
 
-  prof_mark(7, stream);
+  prof_end(6, stream);
+  prof_begin(7, stream);
   // sparse softmax branch + merge
   still::SaArgs sx{};
   sx.q = q; sx.k = k;
@@ -312,7 +383,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   sx.scale = p->scale;
   if ((e = still::launch_sa(sx, p->dtype, d, B, stream)) != hipSuccess)
     return fail(STILL_ERR_HIP, "sparse_attention: %s", hipGetErrorString(e));
-  prof_mark(STILL_PROFILE_SLOTS, stream);
+  prof_end(7, stream);
 
   // decode state standing after token N-1: (S, z) through chunk c_last-2 came from the linear pass above
   if (state_out != nullptr) {
@@ -338,19 +409,31 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
 
 void still_profile_enable(int32_t on) {
   g_prof.on = on != 0;
-  if (!g_prof.on) g_prof.recorded = false;
+  g_prof.last_only = on == 2;
+  g_prof.calls = 0;
 }
 
 still_status_t still_profile_read(float* ms, int32_t n) {
   if (ms == nullptr || n < 0) return fail(STILL_ERR_INVALID_ARG, "ms is NULL or n < 0");
-  if (!g_prof.recorded) return fail(STILL_ERR_STATE, "no profiled call recorded on this thread");
-  if (hipEventSynchronize(g_prof.ev[STILL_PROFILE_SLOTS]) != hipSuccess)
+  if (!g_prof.created || g_prof.calls == 0) return fail(STILL_ERR_STATE, "no profiled call recorded on this thread");
+  const int last = (g_prof.calls - 1) % kProfRing;
+  const int kept = g_prof.calls < kProfRing ? g_prof.calls : kProfRing;
+  if (hipEventSynchronize(g_prof.end[last][STILL_PROFILE_SLOTS - 1]) != hipSuccess)
     return fail(STILL_ERR_HIP, "event synchronize failed");
   for (int i = 0; i < n && i < STILL_PROFILE_SLOTS; ++i) {
-    float t = 0.f;
-    if (hipEventElapsedTime(&t, g_prof.ev[i], g_prof.ev[i + 1]) != hipSuccess)
-      return fail(STILL_ERR_HIP, "event elapsed failed for slot %d", i);
-    ms[i] = t;
+    double sum = 0.0;
+    if (g_prof.last_only && i != STILL_PROFILE_SLOTS - 1) {
+      ms[i] = 0.f;
+      continue;
+    }
+    for (int c = 0; c < kept; ++c) {
+      const int r = (g_prof.calls - 1 - c) % kProfRing;
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, g_prof.beg[r][i], g_prof.end[r][i]) != hipSuccess)
+        return fail(STILL_ERR_HIP, "event elapsed failed for slot %d", i);
+      sum += t;
+    }
+    ms[i] = (float)(sum / kept);
   }
   return STILL_OK;
 }
