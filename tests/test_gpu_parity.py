@@ -15,6 +15,7 @@ HIP path's own indices after those were checked to be a valid Top-lambda set.
 import numpy as np
 import pytest
 
+from paper_2602_02180_amd import binding as S
 from paper_2602_02180_amd import synth
 from tests import gpu_util as U
 
@@ -207,3 +208,72 @@ def test_full_size_configs_sampled_units(name, units, rows):
     assert np.all(chunk_of == np.arange(sel.shape[2])[None, None, :, None])
     # token 0 has a one-token window: the largest possible score, hence always kept
     assert np.all(sel[:, :, 0, 0] == 0)
+
+
+# ------------------------------------------------------------------ stream ordering of the two-stream launch sequence
+def test_back_to_back_calls_on_a_user_stream_are_ordered():
+    """The layout kernels run on a library-owned second stream.  Work enqueued on the caller's stream before a
+    call (here: copies that replace v and Wk in place) must still precede them, and the next call must not start
+    overwriting the workspace while the previous one reads it: three calls with changing inputs, enqueued back
+    to back on one non-default stream with a single workspace, must each give exactly what a lone call gives."""
+    import torch
+
+    w = small("order", N=2048, Hq=4, Hkv=2, dtype="bf16", d=128, C=128, W=128)
+    dev = "cuda"
+    inps = [synth.make_inputs(w, seed=100 + i) for i in range(3)]
+    lone = [U.run_hip(w, inp, want_terms=False)["out"] for inp in inps]
+
+    tens = [{n: synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v", "Wq", "Wk")} for inp in inps]
+    cur = {n: torch.empty_like(tens[0][n]) for n in tens[0]}
+    outs = [torch.full_like(cur["q"], float("nan")) for _ in range(3)]
+    p = S.make_params(B=1, N=w.N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, d_f=w.df, q=cur["q"], k=cur["k"], v=cur["v"], out=outs[0])
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        for i in range(3):
+            for n in cur:
+                cur[n].copy_(tens[i][n], non_blocking=True)       # on `stream`, right before the call
+            S.still_hybrid_attn_fwd(p, cur["q"], cur["k"], cur["v"], None, cur["Wq"], None, cur["Wk"], None, outs[i],
+                                    workspace=ws, stream=stream)
+    stream.synchronize()
+    for i in range(3):
+        got = synth.from_torch(outs[i])
+        assert np.array_equal(got, lone[i]), f"call {i} differs from the lone call"
+
+
+def test_prefill_call_replays_from_a_hip_graph():
+    """The call enqueues kernels, a device-to-device copy and event fork/join only, so it can be captured (after one
+    eager call has created the library's helper stream).  Every replay must reproduce the eager result, also after
+    the inputs changed in place."""
+    import torch
+
+    w = small("graph", N=1024, Hq=4, Hkv=2, dtype="bf16", d=128, C=128, W=128)
+    dev = "cuda"
+    inps = [synth.make_inputs(w, seed=200 + i) for i in range(3)]
+    lone = [U.run_hip(w, inp, want_terms=False)["out"] for inp in inps]
+    tens = [{n: synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v", "Wq", "Wk")} for inp in inps]
+    cur = {n: tens[0][n].clone() for n in tens[0]}
+    out = torch.full_like(cur["q"], float("nan"))
+    p = S.make_params(B=1, N=w.N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, d_f=w.df, q=cur["q"], k=cur["k"], v=cur["v"], out=out)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+
+    def call():
+        S.still_hybrid_attn_fwd(p, cur["q"], cur["k"], cur["v"], None, cur["Wq"], None, cur["Wk"], None, out,
+                                workspace=ws, stream=torch.cuda.current_stream())
+
+    call()                                   # eager: creates the helper stream, warms everything up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for i in (1, 2, 0, 1):
+        for n in cur:
+            cur[n].copy_(tens[i][n])
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(synth.from_torch(out), lone[i]), f"replay with inputs {i} differs from the eager call"
