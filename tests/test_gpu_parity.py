@@ -210,6 +210,25 @@ def test_full_size_configs_sampled_units(name, units, rows):
     assert np.all(sel[:, :, 0, 0] == 0)
 
 
+# ------------------------------------------------------------------ long segments of the chunk scan in fp32
+@pytest.mark.parametrize("kw", [
+    dict(d=64, C=64, W=64),            # one sub-unit per unit
+    dict(d=64, C=128, W=128),          # two sub-units per unit
+    dict(d=128, C=64, W=128),
+], ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
+def test_many_chunks_per_segment_fp32(kw):
+    """Enough (batch, head, chunk) work that a segment of the linear-attention scan spans several chunks, so the
+    output pass fetches several staged key-feature units per segment, in fp32 (tight tolerance)."""
+    w = small("segs", N=4096 if kw["C"] == 64 else 8192, Hq=32, Hkv=8, dtype="f32", lam=16, **kw)
+    inp = synth.make_inputs(w, seed=321)
+    hip = U.run_hip(w, inp)
+    assert hip["layout"].seg_chunks >= 3 and hip["layout"].nseg >= 2
+    units = [(0, 3), (0, 30)]
+    ref = U.oracle_units(w, inp, units, sel=hip["sel"])
+    check_terms(w, hip, ref, units, "segs")
+    check_outputs(w, hip, ref, units, "segs")
+
+
 # ------------------------------------------------------------------ stream ordering of the two-stream launch sequence
 def test_back_to_back_calls_on_a_user_stream_are_ordered():
     """The layout kernels run on a library-owned second stream.  Work enqueued on the caller's stream before a
