@@ -45,17 +45,54 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
     for (int s = 0; s < KS; ++s) qf[s] = M::load(qp + s * M::KK);
   }
 
+  // Logit band.  The waves of the workgroup need overlapping key ranges (wave w: band tiles w .. w+NT-1 of the
+  // NB = NT-1 + C/32 tiles of 32 keys that end with the chunk), and as an MFMA operand a K row is consumed 16
+  // bytes per lane and instruction, i.e. 32 rows x 32 bytes per load: fetched straight from global memory the
+  // same lines are requested over and over.  The band therefore passes through LDS, PT tiles at a time, with
+  // direct-to-LDS copies of whole 1 KB pieces (the 16-byte column index is XOR-ed with the row so that the
+  // operand reads meet no bank conflicts); every wave then takes the tiles of the pass that belong to its band.
+  constexpr int EPV = 16 / (int)sizeof(T), KVR = D / EPV;                // elements / vectors per K row
+  constexpr int PT_MAX = 32768 / (32 * D * (int)sizeof(T));              // tiles in 32 KB
+  const int NW = C / 32, NB = NT - 1 + NW;
+  constexpr int PT = PT_MAX < 8 ? PT_MAX : 8;
+  __shared__ __attribute__((aligned(16))) unsigned char s_kraw[PT * 32 * D * sizeof(T)];
+  T* s_k = reinterpret_cast<T*>(s_kraw);
+  auto swz = [](int row) { return KVR == 8 ? ((row >> 1) & 7) : (row & 15); };
+  const T* kbase = k + (int64_t)b * a.k_sb + (int64_t)kvh * a.k_sh;
+  const int band0 = c * C - 32 * (NT - 1);                               // first key of the band (may be < 0)
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+
   floatx16 acc[NT];
 #pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    acc[j] = zero16();
-    const int kb = t0 - 32 * (NT - 1 - j);
-    if (kb + 31 < 0 || kb >= N) continue;  // wave-uniform: tile entirely outside the sequence
-    int key = kb + M::kappa(r);
-    key = key < 0 ? 0 : (key >= N ? N - 1 : key);
-    const T* kp = k + (int64_t)b * a.k_sb + (int64_t)key * a.k_st + (int64_t)kvh * a.k_sh + g * M::KPL;
+  for (int j = 0; j < NT; ++j) acc[j] = zero16();
+  for (int p0 = 0; p0 < NB; p0 += PT) {
+    const int npt = NB - p0 < PT ? NB - p0 : PT;                         // tiles in this pass
+    if (p0 > 0) lds_barrier();                                           // the previous pass has been read
+    // piece i (1 KB) of the pass: lane L lands at 1024 i + 16 L = LDS (row, slot) and fetches the global column
+    // slot ^ swz(row) of the key that row holds; keys outside the sequence re-read an end token (masked later)
+    for (int i = wave_s; i < npt * 32 * KVR / 64; i += NW) {
+      const int v = i * 64 + lane;
+      const int row = v / KVR, slot = v % KVR;
+      int key = band0 + 32 * p0 + row;
+      key = key < 0 ? 0 : (key >= N ? N - 1 : key);
+      async_copy16(kbase + (int64_t)key * a.k_st + ((slot ^ swz(row)) * EPV), lds_address(s_kraw + i * 1024));
+    }
+    wait_async_copies();
+    lds_barrier();
 #pragma unroll
-    for (int s = 0; s < KS; ++s) acc[j] = M::mma(M::load(kp + s * M::KK), qf[s], acc[j]);
+    for (int j = 0; j < NT; ++j) {
+      const int bt = wave_s + j - p0;                                    // tile index inside the pass
+      const int kb = t0 - 32 * (NT - 1 - j);
+      if (bt < 0 || bt >= npt || kb + 31 < 0 || kb >= N) continue;       // wave-uniform
+      const int row = 32 * bt + M::kappa(r);
+      const T* krow = s_k + row * D;
+      const int sw = swz(row);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const int e = s * M::KK + g * M::KPL;
+        acc[j] = M::mma(M::load(krow + (((e / EPV) ^ sw) * EPV) + e % EPV), qf[s], acc[j]);
+      }
+    }
   }
 
   // window softmaxes for query t (this lane and lane^32 share the query).
