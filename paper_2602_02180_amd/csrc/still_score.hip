@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
   const int t0 = c * C + 32 * wave;
   const int t = t0 + r;
 
-  __shared__ float s_score[128];
+  __shared__ __attribute__((aligned(16))) float s_score[128];
   __shared__ int s_rank[256];
   __shared__ unsigned long long s_ball[4];
 
@@ -185,10 +185,11 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
     const float si = s_score[i];
     int part = 0;
     const int j0 = half * (C / 2);
-#pragma unroll 8
-    for (int j = j0; j < j0 + C / 2; ++j) {
-      const float sj = s_score[j];
-      part += (sj > si || (sj == si && j < i)) ? 1 : 0;
+#pragma unroll 4
+    for (int j = j0; j < j0 + C / 2; j += 4) {   // four opponents per LDS read (every lane reads the same address)
+      const floatx4 sj = *reinterpret_cast<const floatx4*>(&s_score[j]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) part += (sj[e] > si || (sj[e] == si && j + e < i)) ? 1 : 0;
     }
     s_rank[threadIdx.x] = part;
     __syncthreads();
