@@ -6,10 +6,9 @@
 //
 // One workgroup handles one chunk of one (batch, query head): each wave owns 32 consecutive
 // query tokens and evaluates the logit band  key in [t-W+1, t]  as NT tiles of 32 keys with MFMA
-// (K rows as the A operand, the wave's 32 queries as the B operand, both read straight from
-// global memory: every byte of the rows is consumed across the k-steps, so the L1/L2 lines are
-// fetched once).  In C layout every lane then holds the logits of ONE query, so the two softmaxes
-// and the score reduce inside a lane plus one exchange with the other lane group.
+// (K rows as the A operand, staged through LDS for the whole workgroup; the wave's 32 queries as
+// the B operand, from registers).  In C layout every lane then holds the logits of ONE query, so
+// the two softmaxes and the score reduce inside a lane plus one exchange with the other lane group.
 // Scores go to an LDS array; each thread ranks one token by counting (score higher, or equal with a
 // lower index) and the selected tokens are written in ascending order.
 #include "still_kernels.h"
