@@ -134,7 +134,6 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr) {
   __shared__ float s_sc[128];
   __shared__ unsigned char s_flag[128];
   __shared__ int s_list[128];
-  __shared__ float xs[D], vs[D], phi[DP], sh[16];
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int kvh = a.map.kv[hq];
   const int C = a.C, lam = a.lam, R = a.R;
@@ -176,7 +175,26 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr) {
       vret[(int64_t)row * D + x] = vring[(int64_t)slot * D + x];
     }
   }
-  // the others -> (S, z): thread f owns row f of S; thread j < DF also owns column j of Wk
+  // the others -> (S, z): thread f owns row f of S; thread j < DF also owns column j of Wk.  The tokens are
+  // taken TB at a time (in order): one set of barriers per batch instead of one per token.  Per batch:
+  //   (A) threads < d_f project the TB tokens (their column of Wk stays in registers),
+  //   (B) wave w turns token w's d_f projections into its 2 d_f features (all of a token's features sit in one
+  //       wave, two per lane, so the statistics need wave reductions only),
+  //   (C) every thread adds the TB rank-1 terms to its row of S, token by token.
+  constexpr int TB = 4;
+  __shared__ __attribute__((aligned(16))) float xs[D][TB], vs[D][TB], fs[TB][DF], phi[DP][TB];
+  __shared__ int s_rest[128];
+  __shared__ int s_nrest;
+  if (tid < C && !chosen) {
+    int before = 0;
+    for (int jx = 0; jx < tid; ++jx) before += s_flag[jx];
+    s_rest[tid - before] = tid;
+  }
+  if (tid == 0) {
+    int n = 0;
+    for (int jx = 0; jx < C; ++jx) n += s_flag[jx] ? 0 : 1;
+    s_nrest = n;
+  }
   float wcol[D];
   if (tid < DF) {
     const T* wk = static_cast<const T*>(a.wk) + (int64_t)hq * D * DF + tid;
@@ -192,41 +210,87 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr) {
     for (int x = 0; x < D; ++x) srow[x] = Sg[(int64_t)tid * D + x];
     zf = Sg[DP * D + tid];
   }
-  for (int i = 0; i < C; ++i) {
-    if (s_flag[i]) continue;                     // block-uniform
-    const int slot = (cr * C + i) % R;
-    __syncthreads();
-    if (tid < D) {
-      xs[tid] = to_f32(kring[(int64_t)slot * D + tid]);
-      vs[tid] = to_f32(vring[(int64_t)slot * D + tid]);
+  __syncthreads();
+  const int n_rest = s_nrest;
+  const int lane = tid & 63, wave = tid >> 6;
+  for (int i0 = 0; i0 < n_rest; i0 += TB) {
+    const int nb = n_rest - i0 < TB ? n_rest - i0 : TB;
+    __syncthreads();                             // the previous batch's operands have been consumed
+    for (int idx = tid; idx < TB * D; idx += 256) {
+      const int tb = idx / D, x = idx % D;
+      float xv = 0.f, vv = 0.f;
+      if (tb < nb) {
+        const int slot = (cr * C + s_rest[i0 + tb]) % R;
+        xv = to_f32(kring[(int64_t)slot * D + x]);
+        vv = to_f32(vring[(int64_t)slot * D + x]);
+      }
+      xs[x][tb] = xv;
+      vs[x][tb] = vv;
     }
     __syncthreads();
-    float f = 0.f;
+    // (A)
     if (tid < DF) {
+      float f[TB];
 #pragma unroll
-      for (int x = 0; x < D; ++x) f = fmaf(xs[x], wcol[x], f);
-      f += bias;
-    }
-    float nx2 = tid < D ? xs[tid] * xs[tid] : 0.f;
-    float nf2 = tid < DF ? f * f : 0.f;
-    float fmx = tid < DF ? f : -INFINITY, fmn = tid < DF ? f : INFINITY;
-    block_reduce4(nx2, nf2, fmx, fmn, sh, 4);
-    const float ratio = nf2 > 0.f ? sqrtf(nx2 / nf2) : 0.f;
-    const float a1 = ratio * kLog2e;
-    float ep = tid < DF ? fast_exp2(fmaf(f, a1, -fmx * a1)) : 0.f;
-    float en = tid < DF ? fast_exp2(fmaf(f, -a1, fmn * a1)) : 0.f;
-    float sp = ep, sn = en, u0 = 0.f, u1 = 0.f;
-    block_reduce4(sp, sn, u0, u1, sh, 4);
-    if (tid < DF) {
-      phi[tid] = round_to<T>(ep / sp);
-      phi[DF + tid] = round_to<T>(en / sn);
+      for (int tb = 0; tb < TB; ++tb) f[tb] = 0.f;
+#pragma unroll
+      for (int x = 0; x < D; ++x) {
+        const floatx4 x4 = *reinterpret_cast<const floatx4*>(&xs[x][0]);
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) f[tb] = fmaf(x4[tb], wcol[x], f[tb]);
+      }
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb) fs[tb][tid] = f[tb] + bias;
     }
     __syncthreads();
+    // (B) blockDim = 256 = TB waves
+    {
+      const int tb = wave;
+      float fv[DF / 64], nx2 = 0.f, nf2 = 0.f, fmx = -INFINITY, fmn = INFINITY;
+#pragma unroll
+      for (int h = 0; h < DF / 64; ++h) {
+        fv[h] = fs[tb][lane + 64 * h];
+        nf2 = fmaf(fv[h], fv[h], nf2);
+        fmx = fmaxf(fmx, fv[h]);
+        fmn = fminf(fmn, fv[h]);
+      }
+#pragma unroll
+      for (int h = 0; h < D / 64; ++h) nx2 = fmaf(xs[lane + 64 * h][tb], xs[lane + 64 * h][tb], nx2);
+      nx2 = wave_sum(nx2);
+      nf2 = wave_sum(nf2);
+      fmx = wave_max(fmx);
+      fmn = -wave_max(-fmn);
+      const float ratio = nf2 > 0.f ? sqrtf(nx2 / nf2) : 0.f;
+      const float a1 = ratio * kLog2e;
+      float ep[DF / 64], en[DF / 64], sp = 0.f, sn = 0.f;
+#pragma unroll
+      for (int h = 0; h < DF / 64; ++h) {
+        ep[h] = fast_exp2(fmaf(fv[h], a1, -fmx * a1));
+        en[h] = fast_exp2(fmaf(fv[h], -a1, fmn * a1));
+        sp += ep[h];
+        sn += en[h];
+      }
+      sp = wave_sum(sp);
+      sn = wave_sum(sn);
+      const bool live = tb < nb;
+#pragma unroll
+      for (int h = 0; h < DF / 64; ++h) {
+        phi[lane + 64 * h][tb] = live ? round_to<T>(ep[h] / sp) : 0.f;
+        phi[DF + lane + 64 * h][tb] = live ? round_to<T>(en[h] / sn) : 0.f;
+      }
+    }
+    __syncthreads();
+    // (C)
     if (tid < DP) {
-      const float pf = phi[tid];
-      zf += pf;
+      const floatx4 pf = *reinterpret_cast<const floatx4*>(&phi[tid][0]);
 #pragma unroll
-      for (int x = 0; x < D; ++x) srow[x] = fmaf(pf, vs[x], srow[x]);
+      for (int tb = 0; tb < TB; ++tb) zf += pf[tb];
+#pragma unroll
+      for (int x = 0; x < D; ++x) {
+        const floatx4 v4 = *reinterpret_cast<const floatx4*>(&vs[x][0]);
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) srow[x] = fmaf(pf[tb], v4[tb], srow[x]);
+      }
     }
   }
   if (tid < DP) {
