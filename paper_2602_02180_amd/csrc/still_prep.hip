@@ -64,19 +64,23 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     s_tok[threadIdx.x] = tok;
   }
   __syncthreads();
-  const int lane32 = threadIdx.x & 31, grp = threadIdx.x >> 5;  // 8 groups of 32 threads
-  for (int i = grp; i < 64; i += 8) {
+  // rows move in 16-byte pieces (strides and bases are multiples of 16 bytes)
+  constexpr int EPV = 16 / (int)sizeof(E), VPR = D / EPV;   // elements per piece, pieces per row
+  for (int idx = threadIdx.x; idx < 64 * VPR; idx += 256) {
+    const int i = idx / VPR, x = (idx % VPR) * EPV;
     const int tok = s_tok[i];
     const int row = r0 + i;
-    for (int x = lane32; x < D; x += 32) {
-      E kv = 0, vv = 0;
-      if (tok >= 0) {
-        kv = k[(int64_t)b * a.k_sb + (int64_t)tok * a.k_st + (int64_t)kvh * a.k_sh + x];
-        vv = v[(int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)kvh * a.v_sh + x];
-      }
-      kret[(((int64_t)b * a.Hq + hq) * a.cap + row) * D + x] = kv;
-      tile[i][x] = vv;
+    Vec16 kv, vv;
+    kv.w[0] = kv.w[1] = kv.w[2] = kv.w[3] = 0u;
+    vv = kv;
+    if (tok >= 0) {
+      kv = *reinterpret_cast<const Vec16*>(k + (int64_t)b * a.k_sb + (int64_t)tok * a.k_st + (int64_t)kvh * a.k_sh + x);
+      vv = *reinterpret_cast<const Vec16*>(v + (int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)kvh * a.v_sh + x);
     }
+    *reinterpret_cast<Vec16*>(kret + (((int64_t)b * a.Hq + hq) * a.cap + row) * D + x) = kv;
+    const E* ve = reinterpret_cast<const E*>(&vv);
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) tile[i][x + e] = ve[e];
   }
   __syncthreads();
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
