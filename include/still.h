@@ -87,6 +87,7 @@ typedef struct still_ws_layout {
   size_t n_la;     /* float   [B, Hq, N, d]                      gated linear-branch numerator N_LA        */
   size_t d_la;     /* float   [B, Hq, N]                         linear-branch normaliser D_LA             */
   size_t phik;     /* bytes   [B, Hq, nseg, seg_chunks][unit]    staged key features of the state pass     */
+  size_t vfr;      /* dtype   [B, Hkv, Npad * d]                 v in the operand order of the state update */
   size_t total;    /* bytes needed                                                                         */
   int32_t n_pad;   /* Npad                                                                                 */
   int32_t cap;     /* retained-row capacity (multiple of 64)                                               */

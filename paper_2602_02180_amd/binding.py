@@ -36,7 +36,7 @@ class StillParams(ct.Structure):
 
 class StillWsLayout(ct.Structure):
     _fields_ = [(n, ct.c_size_t) for n in
-                ("score", "sel", "vt", "kret", "vrett", "wqt", "wkt", "seg", "n_la", "d_la", "phik", "total")] + \
+                ("score", "sel", "vt", "kret", "vrett", "wqt", "wkt", "seg", "n_la", "d_la", "phik", "vfr", "total")] + \
                [(n, ct.c_int32) for n in ("n_pad", "cap", "nseg", "seg_chunks")]
 
 

@@ -170,6 +170,7 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   L->n_la = take((size_t)B * Hq * N * d * 4);
   L->d_la = take((size_t)B * Hq * N * 4);
   L->phik = take(nseg > 1 ? (size_t)(B * Hq * nseg * G * still::la_phik_unit_bytes((int64_t)es, df, p->C)) : 0);
+  L->vfr = take((size_t)B * Hkv * d * npad * es);
   L->total = off;
   L->n_pad = (int32_t)npad;
   L->cap = (int32_t)cap;
@@ -280,7 +281,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
       side = nullptr;
   }
   prof_begin(0, s2);
-  still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, N, L.n_pad, p->Hkv, d};
+  still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, ws + L.vfr, N, L.n_pad, p->Hkv, d, C};
   if ((e = still::launch_transpose_v(tv, p->dtype, B, s2)) != hipSuccess)
     return fail(STILL_ERR_HIP, "transpose_v: %s", hipGetErrorString(e));
   prof_end(0, s2);
@@ -340,7 +341,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   la.q_sb = p->q_sb; la.q_st = p->q_st; la.q_sh = p->q_sh;
   la.k_sb = p->k_sb; la.k_st = p->k_st; la.k_sh = p->k_sh;
   la.g = g; la.g_sb = p->g_sb; la.g_st = p->g_st; la.g_sh = p->g_sh;
-  la.vt = ws + L.vt; la.wqt = ws + L.wqt; la.wkt = ws + L.wkt; la.bq = bq; la.bk = bk;
+  la.vt = ws + L.vt; la.vfr = ws + L.vfr; la.wqt = ws + L.wqt; la.wkt = ws + L.wkt; la.bq = bq; la.bk = bk;
   la.sel = sel;
   la.map = map;
   la.N = N; la.Np = L.n_pad; la.C = C; la.lam = have_sel ? p->lambda : 0; la.Hq = p->Hq; la.Hkv = p->Hkv;

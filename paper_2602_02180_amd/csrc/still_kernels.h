@@ -20,8 +20,19 @@ struct TransposeVArgs {
   const void* v;
   int64_t v_sb, v_st, v_sh;
   void* vt;       // [B, Hkv, d, Np]
-  int N, Np, Hkv, d;
+  void* vfr;      // nullable: the same values in MFMA-fragment order, see vfr_offset()
+  int N, Np, Hkv, d, C;
 };
+
+// Element offset of (token tau, column x) of one (batch, kv head) in the fragment-ordered copy of v that the
+// linear-attention consumers load their "S += phi_k^T V" operand from: [chunk][x / 32][k-step][x % 32][lane
+// group][k per lane], so that the 64 lanes of one operand load read one contiguous piece (1 KB for 2-byte types).
+// KK / KPL = k per instruction / per lane of the element type's MFMA (16 / 8 for 2-byte types, 2 / 1 for fp32).
+__host__ __device__ inline int64_t vfr_offset(int tau, int x, int C, int D, int KK, int KPL) {
+  const int ch = tau / C, tc = tau % C;
+  const int s = tc / KK, g = (tc % KK) / KPL, e = tc % KPL;
+  return ((((int64_t)ch * (D / 32) + x / 32) * (C / KK) + s) * 64 + 2 * (x % 32) + g) * KPL + e;
+}
 
 struct TransposeWArgs {
   const void* w;  // [Hq, d, df]
@@ -47,6 +58,7 @@ struct LaArgs {
   const void* g;       // nullable
   int64_t g_sb, g_st, g_sh;
   const void* vt;      // [B, Hkv, d, Np]
+  const void* vfr;     // [B, Hkv, Np * d] in fragment order (vfr_offset)
   const void* wqt;     // [Hq, df, d]
   const void* wkt;
   const void* bq;      // nullable [Hq, df]

@@ -157,7 +157,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 
   const T* __restrict__ qbase = static_cast<const T*>(a.q) + (int64_t)b * a.q_sb + (int64_t)hq * a.q_sh;
   const T* __restrict__ kbase = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)kvh * a.k_sh;
-  const T* __restrict__ vt = static_cast<const T*>(a.vt) + ((int64_t)b * a.Hkv + kvh) * (int64_t)D * a.Np;
+  const T* __restrict__ vfr = static_cast<const T*>(a.vfr) + ((int64_t)b * a.Hkv + kvh) * (int64_t)D * a.Np;
   const T* __restrict__ wqt = static_cast<const T*>(a.wqt) + (int64_t)hq * DF * D;
   const T* __restrict__ wkt = static_cast<const T*>(a.wkt) + (int64_t)hq * DF * D;
   const T* __restrict__ bq = a.bq ? static_cast<const T*>(a.bq) + (int64_t)hq * DF : nullptr;
@@ -489,9 +489,11 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
   auto load_v = [&](int u, VFrag& vf) __attribute__((always_inline)) {
     const LaUnit x = unit_at(u);
     const int ch = x.valid ? x.chunk : 0;   // an absent chunk meets zero features; any finite V will do
-    const T* vrow = vt + (int64_t)col * a.Np + (int64_t)ch * C + g * M::KPL;
+    // from the fragment-ordered copy: the 64 lanes of one load read one contiguous piece (the transposed copy
+    // would give 32 rows x 32 bytes per load)
+    const T* vrow = vfr + vfr_offset(ch * C, 32 * wave, C, D, M::KK, M::KPL) + (2 * r + g) * M::KPL;
 #pragma unroll
-    for (int s = 0; s < VS; ++s) vf[s] = M::load(vrow + s * M::KK);
+    for (int s = 0; s < VS; ++s) vf[s] = M::load(vrow + s * 64 * M::KPL);
   };
 
   // reciprocal softmax sums of the 64 tokens of sub-unit `sub` of the unit in slot u&1, from the producers'

@@ -1,7 +1,8 @@
 // Layout preparation: pure data movement, no arithmetic of the method.
 //
 //   transpose_v : v [B,N,Hkv,d] -> vt [B,Hkv,d,Np] (tokens contiguous, zero padded to Np), so that
-//                 the value operand of every "contract over tokens" MFMA is k-contiguous.
+//                 the value operand of every "contract over tokens" MFMA is k-contiguous; and a second copy
+//                 in MFMA-fragment order for the kernel that loads that operand straight from global memory.
 //   transpose_w : NP-Map weights [Hq,d,df] -> [Hq,df,d] (feature rows, d contiguous).
 //   gather      : Index(k, M^SA), Index(v, M^SA) of Algorithm 1: the keys of the selected tokens of
 //                 every full chunk, flattened in chunk order, as rows of kret [B,Hq,cap,d]; the values
@@ -29,6 +30,30 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(TransposeVArgs a) {
   __syncthreads();
   for (int i = ty; i < 64; i += 4) {
     vt[(((int64_t)b * a.Hkv + h) * a.d + d0 + i) * a.Np + tok0 + tx] = tile[tx][i];
+  }
+  // second copy in fragment order: consecutive threads write consecutive elements of one (column block, k-step)
+  // piece (the 64 tokens of the tile lie in one chunk: C is a multiple of 64)
+  if (a.vfr != nullptr) {
+    constexpr int KK = sizeof(E) == 2 ? 16 : 2, KPL = sizeof(E) == 2 ? 8 : 1;
+    constexpr int PIECE = 64 * KPL;                   // elements of one (column block, k-step) piece
+    E* __restrict__ vfr = static_cast<E*>(a.vfr) + ((int64_t)b * a.Hkv + h) * (int64_t)a.Np * a.d;
+    // one thread writes the KPL consecutive elements of one (column, lane group) at once
+    for (int q = threadIdx.x; q < 64 * 64 / KPL; q += 256) {
+      const int blk = q / 64, inner = q % 64;
+      const int w2 = blk / (64 / KK), s = blk % (64 / KK);
+      const int r = inner / 2, g = inner % 2;
+      const int ti = s * KK + g * KPL, xi = 32 * w2 + r;
+      E* dst = vfr + vfr_offset(tok0 + ti, d0 + xi, a.C, a.d, KK, KPL);
+      if constexpr (KPL == 8) {
+        Vec16 pk;
+        E* pe = reinterpret_cast<E*>(&pk);
+#pragma unroll
+        for (int e = 0; e < KPL; ++e) pe[e] = tile[ti + e][xi];
+        *reinterpret_cast<Vec16*>(dst) = pk;
+      } else {
+        dst[0] = tile[ti][xi];
+      }
+    }
   }
 }
 
