@@ -149,7 +149,7 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   const int64_t nc = (N + p->C - 1) / p->C, ncf = N / p->C;
   const int64_t npad = (N + 127) / 128 * 128;
   const int64_t cap = (ncf * p->lambda + 63) / 64 * 64;
-  int64_t G = (nc * B * Hq + 511) / 512;
+  int64_t G = (nc * B * Hq + 255) / 256;   // one workgroup per CU at the size of the chip
   if (G < 2) G = 2;
   if (G > nc) G = nc;
   const int64_t nseg = (nc + G - 1) / G;
