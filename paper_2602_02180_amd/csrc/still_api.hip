@@ -341,7 +341,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   la.q_sb = p->q_sb; la.q_st = p->q_st; la.q_sh = p->q_sh;
   la.k_sb = p->k_sb; la.k_st = p->k_st; la.k_sh = p->k_sh;
   la.g = g; la.g_sb = p->g_sb; la.g_st = p->g_st; la.g_sh = p->g_sh;
-  la.vt = ws + L.vt; la.vfr = ws + L.vfr; la.wqt = ws + L.wqt; la.wkt = ws + L.wkt; la.bq = bq; la.bk = bk;
+  la.vfr = ws + L.vfr; la.wqt = ws + L.wqt; la.wkt = ws + L.wkt; la.bq = bq; la.bk = bk;
   la.sel = sel;
   la.map = map;
   la.N = N; la.Np = L.n_pad; la.C = C; la.lam = have_sel ? p->lambda : 0; la.Hq = p->Hq; la.Hkv = p->Hkv;

@@ -57,8 +57,7 @@ struct LaArgs {
   int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
   const void* g;       // nullable
   int64_t g_sb, g_st, g_sh;
-  const void* vt;      // [B, Hkv, d, Np]
-  const void* vfr;     // [B, Hkv, Np * d] in fragment order (vfr_offset)
+  const void* vfr;     // [B, Hkv, Np * d]: v in fragment order (vfr_offset)
   const void* wqt;     // [Hq, df, d]
   const void* wkt;
   const void* bq;      // nullable [Hq, df]

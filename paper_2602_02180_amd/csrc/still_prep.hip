@@ -35,7 +35,6 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(TransposeVArgs a) {
   // piece (the 64 tokens of the tile lie in one chunk: C is a multiple of 64)
   if (a.vfr != nullptr) {
     constexpr int KK = sizeof(E) == 2 ? 16 : 2, KPL = sizeof(E) == 2 ? 8 : 1;
-    constexpr int PIECE = 64 * KPL;                   // elements of one (column block, k-step) piece
     E* __restrict__ vfr = static_cast<E*>(a.vfr) + ((int64_t)b * a.Hkv + h) * (int64_t)a.Np * a.d;
     // one thread writes the KPL consecutive elements of one (column, lane group) at once
     for (int q = threadIdx.x; q < 64 * 64 / KPL; q += 256) {

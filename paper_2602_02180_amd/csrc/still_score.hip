@@ -193,7 +193,7 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
     s_rank[threadIdx.x] = part;
     __syncthreads();
     bool chosen = false;
-    if (threadIdx.x < C) chosen = s_rank[threadIdx.x] + s_rank[threadIdx.x + C] < a.lam;
+    if ((int)threadIdx.x < C) chosen = s_rank[threadIdx.x] + s_rank[threadIdx.x + C] < a.lam;
     const unsigned long long bal = __ballot(chosen);
     if (lane == 0) s_ball[wave] = bal;
     __syncthreads();
