@@ -20,16 +20,28 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(TransposeVArgs a) {
   const int nd = a.d / 64;
   const int h = blockIdx.y / nd, d0 = (blockIdx.y % nd) * 64;
   const int b = blockIdx.z;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int i = ty; i < 64; i += 4) {
+  // rows in and columns out move in 16-byte pieces (bases and strides are multiples of 16 bytes; Np is a
+  // multiple of 64)
+  constexpr int EPV = 16 / (int)sizeof(E), VPR = 64 / EPV;     // elements per piece, pieces per 64-element row
+  for (int q = threadIdx.x; q < 64 * VPR; q += 256) {
+    const int i = q / VPR, x0 = (q % VPR) * EPV;
     const int tok = tok0 + i;
-    E val = 0;
-    if (tok < a.N) val = v[(int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)h * a.v_sh + d0 + tx];
-    tile[i][tx] = val;
+    Vec16 pk;
+    pk.w[0] = pk.w[1] = pk.w[2] = pk.w[3] = 0u;
+    if (tok < a.N)
+      pk = *reinterpret_cast<const Vec16*>(v + (int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)h * a.v_sh + d0 + x0);
+    const E* pe = reinterpret_cast<const E*>(&pk);
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) tile[i][x0 + e] = pe[e];
   }
   __syncthreads();
-  for (int i = ty; i < 64; i += 4) {
-    vt[(((int64_t)b * a.Hkv + h) * a.d + d0 + i) * a.Np + tok0 + tx] = tile[tx][i];
+  for (int q = threadIdx.x; q < 64 * VPR; q += 256) {
+    const int i = q / VPR, t0 = (q % VPR) * EPV;               // column d0 + i, tokens tok0 + t0 ..
+    Vec16 pk;
+    E* pe = reinterpret_cast<E*>(&pk);
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) pe[e] = tile[t0 + e][i];
+    *reinterpret_cast<Vec16*>(vt + (((int64_t)b * a.Hkv + h) * a.d + d0 + i) * a.Np + tok0 + t0) = pk;
   }
   // second copy in fragment order: consecutive threads write consecutive elements of one (column block, k-step)
   // piece (the 64 tokens of the tile lie in one chunk: C is a multiple of 64)
