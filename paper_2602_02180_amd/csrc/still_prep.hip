@@ -70,13 +70,27 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(TransposeVArgs a) {
 
 template <typename E>
 __global__ __launch_bounds__(256) void transpose_w_kernel(TransposeWArgs a) {
-  const E* __restrict__ w = static_cast<const E*>(a.w);
-  E* __restrict__ wt = static_cast<E*>(a.wt);
-  const int h = blockIdx.x;
-  const int n = a.d * a.df;
-  for (int idx = threadIdx.x; idx < n; idx += blockDim.x) {
-    const int f = idx / a.d, x = idx % a.d;
-    wt[(int64_t)h * n + idx] = w[(int64_t)h * n + (int64_t)x * a.df + f];
+  // one 64 x 64 tile of one head per workgroup: rows of w in, rows of wt out, 16 bytes per thread and access
+  __shared__ E tile[64][65];
+  constexpr int EPV = 16 / (int)sizeof(E), VPR = 64 / EPV;
+  const int h = blockIdx.z, x0 = blockIdx.x * 64, f0 = blockIdx.y * 64;
+  const E* __restrict__ w = static_cast<const E*>(a.w) + (int64_t)h * a.d * a.df;
+  E* __restrict__ wt = static_cast<E*>(a.wt) + (int64_t)h * a.d * a.df;
+  for (int q = threadIdx.x; q < 64 * VPR; q += 256) {
+    const int i = q / VPR, j0 = (q % VPR) * EPV;               // row x0 + i of w, features f0 + j0 ..
+    const Vec16 pk = *reinterpret_cast<const Vec16*>(w + (int64_t)(x0 + i) * a.df + f0 + j0);
+    const E* pe = reinterpret_cast<const E*>(&pk);
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) tile[i][j0 + e] = pe[e];
+  }
+  __syncthreads();
+  for (int q = threadIdx.x; q < 64 * VPR; q += 256) {
+    const int j = q / VPR, i0 = (q % VPR) * EPV;               // row f0 + j of wt, columns x0 + i0 ..
+    Vec16 pk;
+    E* pe = reinterpret_cast<E*>(&pk);
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) pe[e] = tile[i0 + e][j];
+    *reinterpret_cast<Vec16*>(wt + (int64_t)(f0 + j) * a.d + x0 + i0) = pk;
   }
 }
 
@@ -135,7 +149,7 @@ hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStre
 }
 
 hipError_t launch_transpose_w(const TransposeWArgs& a, int dtype, hipStream_t stream) {
-  dim3 grid(a.Hq), block(256);
+  dim3 grid(a.d / 64, a.df / 64, a.Hq), block(256);   // d and d_f are multiples of 64
   if (dtype == 1)
     hipLaunchKernelGGL(transpose_w_kernel<uint16_t>, grid, block, 0, stream, a);
   else
