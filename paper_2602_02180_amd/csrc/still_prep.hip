@@ -133,9 +133,14 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     for (int e = 0; e < EPV; ++e) tile[i][x + e] = ve[e];
   }
   __syncthreads();
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int x = ty; x < D; x += 4) {
-    vrett[(((int64_t)b * a.Hq + hq) * D + x) * a.cap + r0 + tx] = tile[tx][x];
+  // columns out: one thread writes 16 bytes (EPV retained rows) of one feature row
+  for (int q = threadIdx.x; q < D * (64 / EPV); q += 256) {
+    const int x = q / (64 / EPV), t0 = (q % (64 / EPV)) * EPV;
+    Vec16 pk;
+    E* pe = reinterpret_cast<E*>(&pk);
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) pe[e] = tile[t0 + e][x];
+    *reinterpret_cast<Vec16*>(vrett + (((int64_t)b * a.Hq + hq) * D + x) * a.cap + r0 + t0) = pk;
   }
 }
 
