@@ -29,7 +29,8 @@ PEAK_HBM = 8.0e12
 
 
 # HBM bytes per launch of the dominant prefill kernel (sparse_attn_merge), measured with rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE and scaled by the plain-copy calibration; see profiles/sa_kernel_c4_hbm_traffic.md.  Other configs: null.
+# WRITE_SIZE and scaled by the plain-copy calibration (two counter runs plus two --calibrate-copy runs; FETCH_SIZE
+# counts 2 KiB and WRITE_SIZE 1 KiB per unit on this machine).  Other configs: null.
 MEASURED_TRAFFIC = {"c4": 1.882e9}
 
 
@@ -205,8 +206,8 @@ def main() -> int:
                          "which the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures ONE GPU only (the path shards over heads/batch with no exchange; "
-              "see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build measures ONE GPU only (the path shards over heads or batch with no exchange "
+              "between GPUs). Run with --gpus 1.", file=sys.stderr)
         return 2
 
     import torch
