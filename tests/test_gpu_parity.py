@@ -296,3 +296,44 @@ def test_prefill_call_replays_from_a_hip_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert np.array_equal(synth.from_torch(out), lone[i]), f"replay with inputs {i} differs from the eager call"
+
+
+def test_profile_modes_report_kernel_times():
+    """Timing events: every-kernel mode gives a positive time for every kernel of the call; the dominant-kernel mode
+    gives the sparse-attention kernel only (the others read 0); the mean is over the calls since enabling."""
+    import torch
+
+    w = small("prof", N=2048, Hq=4, Hkv=2, dtype="bf16", d=128, C=128, W=128)
+    inp = synth.make_inputs(w, seed=7)
+    dev = "cuda"
+    ten = {n: synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v", "Wq", "Wk")}
+    out = torch.empty_like(ten["q"])
+    p = S.make_params(B=1, N=w.N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, d_f=w.df, q=ten["q"], k=ten["k"], v=ten["v"], out=out)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+
+    def call():
+        S.still_hybrid_attn_fwd(p, ten["q"], ten["k"], ten["v"], None, ten["Wq"], None, ten["Wk"], None, out,
+                                workspace=ws)
+
+    call()
+    torch.cuda.synchronize()
+    try:
+        S.still_profile_enable(1)
+        for _ in range(3):
+            call()
+        every = S.still_profile_read()
+        assert set(every) == {S.still_profile_kernel_name(i) for i in range(S.STILL_PROFILE_SLOTS)}
+        assert all(0.0 < ms < 100.0 for ms in every.values()), every
+        S.still_profile_enable(2)
+        for _ in range(70):                      # more calls than the ring of event sets holds
+            call()
+        last = S.still_profile_read()
+        assert 0.0 < last["sparse_attn_merge"] < 100.0
+        assert all(ms == 0.0 for name, ms in last.items() if name != "sparse_attn_merge"), last
+        # same kernel, same input: the two means agree within a generous factor
+        assert 0.5 < last["sparse_attn_merge"] / every["sparse_attn_merge"] < 2.0
+    finally:
+        S.still_profile_enable(0)
+    with pytest.raises(S.StillError):
+        S.still_profile_read()
