@@ -31,7 +31,11 @@ Readings of the paper used here (each is listed with its reason in the design no
   - a one-token window gives a_nodiag = 0, so Score = ln((1+eps)/eps);
   - only full chunks are ranked; ties go to the lower index; indices kept ascending;
   - the state sums only the un-selected tokens; the gate multiplies N_LA only;
-  - f(x) = x W + b (one linear layer), phi = [softmax(u), softmax(-u)].
+  - f(x) = x W + b (one linear layer), phi = [softmax(u), softmax(-u)];
+  - optional budget on the retained tokens (the long-context evaluations of Sec. 4 cap the
+    number of selected tokens; the policy is not stated): chunks are served in order, chunk c
+    keeps min(lambda, budget left) tokens, the rest of the chunk goes to the state like any
+    un-selected token.  Unused slots of an index list hold -1.
 
 parity unpinned: the whole operator on random inputs at general lambda has no value
 printed in the paper; beyond the special cases above its correctness rests on the
@@ -126,29 +130,41 @@ def alg1_scores(q: np.ndarray, k: np.ndarray, C: int, scale: float, eps: float) 
 # Sec. 3.3: delayed selection (Top-lambda per completed chunk)
 # ----------------------------------------------------------------------------
 
-def select_top_lambda(score: np.ndarray, C: int, lam: int) -> np.ndarray:
-    """Indices (global, ascending) of the lam highest scores of every FULL chunk.
+def chunk_quota(c: int, lam: int, max_retained: Optional[int]) -> int:
+    """Tokens chunk c (0-indexed) may keep: lam, or what is left of the budget after chunks 0..c-1."""
+    if max_retained is None:
+        return lam
+    return int(min(lam, max(0, max_retained - c * lam)))
 
-    Ties go to the lower index.  Returns int64 [N // C, lam].
+
+def select_top_lambda(score: np.ndarray, C: int, lam: int, max_retained: Optional[int] = None) -> np.ndarray:
+    """Indices (global, ascending) of the highest scores of every FULL chunk: lam of them, or fewer
+    once a budget on the total number of retained tokens runs out (chunks are served in order).
+
+    Ties go to the lower index.  Returns int64 [N // C, lam]; slots a chunk does not use hold -1.
     """
     N = score.shape[0]
     ncf = N // C
-    sel = np.empty((ncf, lam), np.int64)
+    sel = np.full((ncf, lam), -1, np.int64)
+    kept = 0
     for c in range(ncf):
+        quota = lam if max_retained is None else min(lam, max(0, max_retained - kept))
         s = score[c * C:(c + 1) * C]
         order = sorted(range(C), key=lambda i: (-s[i], i))
-        sel[c] = np.sort(np.asarray(order[:lam], np.int64)) + c * C
+        sel[c, :quota] = np.sort(np.asarray(order[:quota], np.int64)) + c * C
+        kept += quota
     return sel
 
 
-def selection_gaps(score: np.ndarray, C: int, lam: int) -> np.ndarray:
-    """Per full chunk: (lam-th highest score) - ((lam+1)-th highest); +inf if lam in {0, C}."""
+def selection_gaps(score: np.ndarray, C: int, lam: int, max_retained: Optional[int] = None) -> np.ndarray:
+    """Per full chunk: (last kept score) - (first score not kept); +inf if the chunk keeps none or all."""
     ncf = score.shape[0] // C
     gaps = np.full(ncf, np.inf)
-    if 0 < lam < C:
-        for c in range(ncf):
+    for c in range(ncf):
+        quota = chunk_quota(c, lam, max_retained)
+        if 0 < quota < C:
             s = np.sort(score[c * C:(c + 1) * C])[::-1]
-            gaps[c] = s[lam - 1] - s[lam]
+            gaps[c] = s[quota - 1] - s[quota]
     return gaps
 
 
@@ -215,11 +231,11 @@ def _merge(res, t):
     res["out"][t] = (res["N_SA"][t] + f * res["N_LA"][t]) / (res["D_SA"][t] + f * res["D_LA"][t])
 
 
-def _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score):
+def _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained=None):
     if score is None:
         score = self_saliency_scores(q, k, W, scale, eps)
     if sel is None:
-        sel = select_top_lambda(score, C, lam)
+        sel = select_top_lambda(score, C, lam, max_retained)
     sel = np.asarray(sel, np.int64)
     sel = sel.reshape(q.shape[0] // C, sel.size // max(1, q.shape[0] // C))
     return score, sel
@@ -230,13 +246,14 @@ def _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score):
 # ----------------------------------------------------------------------------
 
 def still_definition(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
-                     sel=None, score=None, rows: Optional[Tuple[int, int]] = None) -> Dict:
+                     sel=None, score=None, rows: Optional[Tuple[int, int]] = None,
+                     max_retained: Optional[int] = None) -> Dict:
     """Row t in chunk c sees, through exp: the local span (previous chunk and own chunk up to t)
     plus the selected tokens of chunks <= c-2; through phi_q.phi_k: every other token of
     chunks <= c-2.  One division merges them."""
     q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk)
     N, d = q.shape
-    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score)
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained)
     phi_q = np_map(q, Wq, bq)
     phi_k = np_map(k, Wk, bk)
     rows = (0, N) if rows is None else rows
@@ -247,7 +264,7 @@ def still_definition(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None
         local = list(range(max(0, (c - 1) * C), t + 1))
         ret, lin = [], []
         for cc in range(0, c - 1):
-            chosen = set(int(i) for i in sel[cc])
+            chosen = set(int(i) for i in sel[cc] if i >= 0)
             for i in range(cc * C, (cc + 1) * C):
                 (ret if i in chosen else lin).append(i)
         sa = np.asarray(ret + local, np.int64)
@@ -273,14 +290,14 @@ def still_definition(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None
 
 def still_recurrent(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
                     sel=None, score=None, rows: Optional[Tuple[int, int]] = None,
-                    return_state: bool = False) -> Dict:
+                    return_state: bool = False, max_retained: Optional[int] = None) -> Dict:
     """Step t (1-indexed as in the paper) is written t = (a+1)C + b with 1 <= b <= C.
     When b == 1 and a >= 1 the chunk a (tokens (a-1)C+1 .. aC) is routed: its top-lambda
     keys/values join the retained part of the cache, the others are added to (s, z).
     The cache also always holds the local span aC < i <= t."""
     q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk)
     N, d = q.shape
-    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score)
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained)
     dprime = 2 * np.asarray(Wq).shape[1]
     s = np.zeros((dprime, v.shape[1]), F64)
     z = np.zeros(dprime, F64)
@@ -293,7 +310,7 @@ def still_recurrent(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
         b = t1 - (a + 1) * C
         if a >= 1 and b == 1:
             chunk0 = a - 1                      # 0-indexed chunk being routed
-            chosen = [int(i) for i in sel[chunk0]]
+            chosen = [int(i) for i in sel[chunk0] if i >= 0]
             retained.extend(chosen)
             cs = set(chosen)
             rest = np.asarray([i for i in range(chunk0 * C, (chunk0 + 1) * C) if i not in cs], np.int64)
@@ -326,29 +343,32 @@ def still_recurrent(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
 # ----------------------------------------------------------------------------
 
 def still_chunkwise(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
-                    sel=None, score=None, rows: Optional[Tuple[int, int]] = None) -> Dict:
+                    sel=None, score=None, rows: Optional[Tuple[int, int]] = None,
+                     max_retained: Optional[int] = None) -> Dict:
     """Chunk tensors; per-chunk states phi_k(k_LA)^T v_LA cumulated over chunks and delayed by
     two; chunk c attends with exp to the flattened selected keys of chunks <= c-2, to the whole
     previous chunk and causally to itself; a single division merges both branches."""
     q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk)
     N, d = q.shape
-    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score)
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained)
     T = -(-N // C)
     ncf = N // C
-    lam_eff = sel.shape[1]
     dprime = 2 * np.asarray(Wq).shape[1]
     rows = (0, N) if rows is None else rows
     res = _result(N, v.shape[1], rows)
     res["score"], res["sel"] = score, sel
 
-    # selected / unselected split per full chunk
-    k_sa = k[sel.reshape(-1)].reshape(ncf, lam_eff, d)
-    v_sa = v[sel.reshape(-1)].reshape(ncf, lam_eff, v.shape[1])
+    # selected / unselected split per full chunk (a chunk may keep fewer tokens than it has slots: slots of -1)
+    kept = [sel[c][sel[c] >= 0] for c in range(ncf)]
+    n_kept = np.concatenate([[0], np.cumsum([len(x) for x in kept])]).astype(np.int64)   # before chunk c
+    flat = np.concatenate(kept) if ncf else np.zeros(0, np.int64)
+    k_sa_flat = k[flat]
+    v_sa_flat = v[flat]
     ds = np.zeros((T, dprime, v.shape[1]), F64)
     dz = np.zeros((T, dprime), F64)
     for c in range(ncf):
         keep = np.ones(C, bool)
-        keep[sel[c] - c * C] = False
+        keep[kept[c] - c * C] = False
         idx = np.nonzero(keep)[0] + c * C
         if idx.size:
             pk = np_map(k[idx], Wk, bk)
@@ -356,14 +376,12 @@ def still_chunkwise(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
             dz[c] = pk.sum(axis=0)
     s_cum = np.cumsum(ds, axis=0)
     z_cum = np.cumsum(dz, axis=0)
-    k_sa_flat = k_sa.reshape(ncf * lam_eff, d)
-    v_sa_flat = v_sa.reshape(ncf * lam_eff, v.shape[1])
 
     c_lo, c_hi = rows[0] // C, -(-rows[1] // C)
     for c in range(c_lo, c_hi):
         t0, t1 = c * C, min(N, (c + 1) * C)
         qc = q[t0:t1]
-        n_vis = max(0, c - 1) * lam_eff                  # selected keys of chunks 0..c-2
+        n_vis = int(n_kept[min(max(0, c - 1), ncf)])     # selected keys of chunks 0..c-2
         blocks_k = [k_sa_flat[:n_vis]]
         blocks_v = [v_sa_flat[:n_vis]]
         masks = [np.ones((t1 - t0, n_vis), bool)]
@@ -410,7 +428,8 @@ def still_chunkwise(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
 
 def still_forward_units(inputs: Dict[str, np.ndarray], kv_map: np.ndarray, units, C, W, lam, scale, eps,
                         form: str = "chunkwise", sel: Optional[np.ndarray] = None,
-                        rows: Optional[Tuple[int, int]] = None) -> Dict[Tuple[int, int], Dict]:
+                        rows: Optional[Tuple[int, int]] = None,
+                        max_retained: Optional[int] = None) -> Dict[Tuple[int, int], Dict]:
     """Run one form on the listed (b, hq) units of a batched problem.
 
     inputs: q [B,N,Hq,d], k,v [B,N,Hkv,d], Wq,Wk [Hq,d,d_f], optional g [B,N,Hq,d],
@@ -426,5 +445,5 @@ def still_forward_units(inputs: Dict[str, np.ndarray], kv_map: np.ndarray, units
         s_in = None if sel is None else sel[b, h]
         out[(b, h)] = fn(inputs["q"][b, :, h], inputs["k"][b, :, kh], inputs["v"][b, :, kh], g,
                          inputs["Wq"][h], inputs["Wk"][h], C, W, lam, scale, eps, bq=bq, bk=bk,
-                         sel=s_in, rows=rows)
+                         sel=s_in, rows=rows, max_retained=max_retained)
     return out

@@ -16,6 +16,10 @@ delay, a transposed operand, a wrong tie-break) fails it:
   * NP-Map: ||u|| = ||x||, halves sum to 1, identity MLP gives softmax(x) (+) softmax(-x)
   * selection: brute force over all subsets on tiny chunks, lowest-index tie-break
   * causality: appending tokens never changes earlier rows (prefill/decode consistency)
+  * budget on the retained tokens: never exceeded at any row; a budget nobody reaches changes
+    nothing; rows before the budget fills are those of the unlimited operator; every token is
+    still seen exactly once; with whole chunks kept it is softmax attention over the first
+    chunks plus the local span, linear attention over the rest, written out independently
 
 The paper prints no worked numeric example of the operator, so there are no golden values
 from it; tests/golden/ says so.
@@ -346,3 +350,89 @@ def test_unit_driver_uses_gqa_map():
     direct = O.still_chunkwise(inp["q"][1, :, 2], inp["k"][1, :, 1], inp["v"][1, :, 1], None,
                                inp["Wq"][2], inp["Wk"][2], C=4, W=4, lam=1, scale=0.3, eps=EPS)
     np.testing.assert_array_equal(res[(1, 2)]["out"], direct["out"])
+
+
+# --------------------------------------------------------------------------- budget on retained tokens
+@pytest.mark.parametrize("form", FORMS)
+@pytest.mark.parametrize("N,C,lam,cap", [(40, 4, 2, 5), (41, 4, 3, 6), (30, 5, 2, 0), (36, 6, 6, 9)])
+def test_budget_is_never_exceeded_and_every_token_is_seen_once(form, N, C, lam, cap):
+    """One-hot values again: with a budget, row t sees through exp the local span and at most `cap`
+    selected tokens (chunks served in order until the budget is used up), every other routed token
+    through phi, nothing twice."""
+    rng = np.random.default_rng(15)
+    q = rng.standard_normal((N, 4))
+    k = rng.standard_normal((N, 4))
+    Wq = rng.standard_normal((4, 3))
+    Wk = rng.standard_normal((4, 3))
+    r = form(q, k, np.eye(N), None, Wq, Wk, C=C, W=3, lam=lam, scale=0.5, eps=EPS, max_retained=cap)
+    sel = r["sel"]
+    counts = (sel >= 0).sum(axis=1)
+    assert counts.sum() == min(cap, lam * (N // C))
+    assert np.array_equal(counts, [min(lam, max(0, cap - c * lam)) for c in range(N // C)])
+    for c in range(N // C):            # the kept ones are the best of the chunk, slots filled from the left
+        kept = sel[c][: counts[c]]
+        assert np.all(sel[c][counts[c]:] == -1) and np.all(np.diff(kept) > 0)
+        order = sorted(range(C), key=lambda i: (-r["score"][c * C + i], i))
+        assert sorted(kept.tolist()) == sorted(c * C + i for i in order[: counts[c]])
+    for t in range(N):
+        c = t // C
+        sa, la = r["N_SA"][t] > 0, r["N_LA"][t] > 0
+        assert not np.any(sa & la)
+        assert np.all((sa | la)[: t + 1]) and not np.any((sa | la)[t + 1:])
+        lo = max(0, (c - 1) * C)
+        assert sa[:lo].sum() == min(cap, max(0, c - 1) * lam)      # retained part within the budget
+        expect = np.zeros(N, bool)
+        expect[lo: t + 1] = True
+        for cc in range(0, c - 1):
+            expect[sel[cc][sel[cc] >= 0]] = True
+        assert np.array_equal(sa, expect)
+
+
+@pytest.mark.parametrize("form", FORMS)
+def test_budget_nobody_reaches_changes_nothing_and_early_rows_are_unlimited(form):
+    q, k, v, g, Wq, Wk = rand_problem(16, 64, 8)
+    kw = dict(C=8, W=6, lam=3, scale=0.35, eps=EPS)
+    free = form(q, k, v, g, Wq, Wk, **kw)
+    roomy = form(q, k, v, g, Wq, Wk, max_retained=3 * 8, **kw)
+    np.testing.assert_array_equal(free["out"], roomy["out"])
+    np.testing.assert_array_equal(free["sel"], roomy["sel"])
+    tight = form(q, k, v, g, Wq, Wk, max_retained=7, **kw)     # chunks 0,1 keep 3, chunk 2 keeps 1
+    # rows of chunk c see chunks <= c-2: identical while those chunks kept their full lam (c <= 3)
+    np.testing.assert_array_equal(free["out"][: 4 * 8], tight["out"][: 4 * 8])
+    assert np.abs(free["out"][4 * 8:] - tight["out"][4 * 8:]).max() > 1e-6
+    # a budget of zero is the operator with nothing kept
+    none = form(q, k, v, g, Wq, Wk, C=8, W=6, lam=0, scale=0.35, eps=EPS)
+    zero = form(q, k, v, g, Wq, Wk, max_retained=0, **kw)
+    np.testing.assert_allclose(zero["out"], none["out"], rtol=1e-13)
+
+
+def test_budget_forms_agree():
+    q, k, v, g, Wq, Wk = rand_problem(17, 70, 8, df=6)
+    rs = [f(q, k, v, g, Wq, Wk, C=8, W=11, lam=3, scale=0.35, eps=EPS, max_retained=10) for f in FORMS]
+    for key in ("out", "M", "N_SA", "D_SA", "N_LA", "D_LA"):
+        np.testing.assert_allclose(rs[0][key], rs[1][key], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(rs[0][key], rs[2][key], rtol=1e-11, atol=1e-13)
+    assert np.array_equal(rs[0]["sel"], rs[1]["sel"]) and np.array_equal(rs[0]["sel"], rs[2]["sel"])
+
+
+def test_budget_with_whole_chunks_kept_is_attention_sink_plus_window_plus_linear_rest():
+    """lam = C and a budget of m chunks: the first m chunks stay under softmax for good, the local span
+    slides, everything between goes through phi.  Written out directly with scipy's softmax weights and
+    the kernel-feature weights, one normaliser."""
+    N, C, m, scale = 56, 8, 2, 0.4
+    q, k, v, g, Wq, Wk = rand_problem(18, N, 8)
+    r = O.still_chunkwise(q, k, v, g, Wq, Wk, C=C, W=5, lam=C, scale=scale, eps=EPS, max_retained=m * C)
+    pq, pk = O.np_map(q, Wq), O.np_map(k, Wk)
+    for t in range(N):
+        c = t // C
+        lo = max(0, (c - 1) * C)
+        n_routed = max(0, c - 1) * C
+        sink = np.arange(min(m * C, n_routed))
+        sm = np.concatenate([sink, np.arange(lo, t + 1)])
+        lin = np.arange(min(m * C, n_routed), n_routed)
+        logit = scale * (k[sm] @ q[t])
+        a = sp_softmax(logit)                       # softmax weights inside the exp set
+        zexp = np.exp(logit - logit.max()).sum()    # their normaliser, up to exp(max)
+        w = (pk[lin] @ pq[t]) * np.exp(-logit.max())
+        y = (zexp * (a @ v[sm]) + g[t] * (w @ v[lin])) / (zexp + w.sum())
+        np.testing.assert_allclose(r["out"][t], y, rtol=1e-11, atol=1e-13)
