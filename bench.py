@@ -41,6 +41,8 @@ def sparse_branch_flops(w: synth.Workload, N: int) -> float:
     t = np.arange(N, dtype=np.int64)
     c = t // w.C
     n_ret = np.maximum(0, c - 1) * w.lam
+    if w.max_retained > 0:
+        n_ret = np.minimum(n_ret, w.max_retained)
     n_loc = t - np.maximum(0, c - 1) * w.C + 1
     return float(4 * w.d * np.sum(n_ret + n_loc)) * w.B * w.Hq
 
@@ -50,9 +52,12 @@ def path_flops(w: synth.Workload, N: int) -> float:
     output, sparse branch)."""
     d, df = w.d, w.df
     nc = N // w.C
+    kept = w.lam * max(0, nc - 2)
+    if w.max_retained > 0:
+        kept = min(kept, w.max_retained)
     per_head = (2 * d * min(w.W, N) * N            # score logits
                 + 2 * (2 * d * df) * N             # NP-Map of q and k
-                + 2 * (2 * df) * d * (w.C - w.lam) * max(0, nc - 2)   # state update, routed chunks
+                + 2 * (2 * df) * d * (w.C * max(0, nc - 2) - kept)    # state update, routed chunks
                 + 2 * (2 * df) * d * N)            # phi_q S
     return per_head * w.B * w.Hq + sparse_branch_flops(w, N)
 
@@ -75,7 +80,8 @@ def cpu_baseline(w: synth.Workload, inp, budget_s: float = 20.0):
     units_done, t0 = 0, time.perf_counter()
     order = [(b, h) for h in range(w.Hq) for b in range(w.B)]
     for (b, h) in order:
-        O.still_forward_units(inp, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps)
+        O.still_forward_units(inp, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                              max_retained=w.max_retained if w.max_retained > 0 else None)
         units_done += 1
         if time.perf_counter() - t0 > budget_s:
             break
@@ -88,6 +94,10 @@ def cpu_baseline(w: synth.Workload, inp, budget_s: float = 20.0):
                       f"numpy float64 chunk-wise form, {el:.1f} s; scaled by 1/Hq to whole-layer tokens/s"}
 
 
+def budget_tag(w: synth.Workload) -> str:
+    return f" max_retained={w.max_retained}" if w.max_retained > 0 else ""
+
+
 def decode_bench(args) -> int:
     """Config 5: B sequences with a prefilled 32K context, then single-token steps.  The contexts are drawn
     on the GPU (seeded torch generator, same distributions as synth.make_inputs) and prefilled in slices of
@@ -95,7 +105,7 @@ def decode_bench(args) -> int:
     import torch
     from paper_2602_02180_amd import binding as S
 
-    w = synth.CONFIGS["c5"]
+    w = synth.workload("c5", max_retained=args.max_retained)
     dev = "cuda"
     gen = torch.Generator(device=dev)
     gen.manual_seed(w.seed)
@@ -111,7 +121,7 @@ def decode_bench(args) -> int:
     Wq = (torch.randn(Hq, d, d, generator=gen, device=dev) / d ** 0.5).to(bf)
     Wk = (torch.randn(Hq, d, d, generator=gen, device=dev) / d ** 0.5).to(bf)
     base = dict(B=B, Hq=Hq, Hkv=Hkv, d=d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype="bf16",
-                max_tokens=max_tokens)
+                max_tokens=max_tokens, max_retained=w.max_retained)
     ps = S.make_params(N=1, **base)
     L = S.still_state_layout(ps)
     state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
@@ -173,14 +183,15 @@ def decode_bench(args) -> int:
     lat = np.array([a.elapsed_time(b) for a, b in ev])
     routing = np.array([((N + args.warmup + i) % w.C) == 0 for i in range(n_steps)])
     c = (N + args.warmup) // w.C
-    rows = (c - 1) * w.lam + (N + args.warmup - (c - 1) * w.C + 1)
+    n_ret = (c - 1) * w.lam if w.max_retained <= 0 else min((c - 1) * w.lam, w.max_retained)
+    rows = n_ret + (N + args.warmup - (c - 1) * w.C + 1)
     bytes_step = B * Hq * (rows * 2 * d * 2 + (2 * d * (d + 1)) * 4)
     ordinary = float(np.median(lat[~routing])) if (~routing).any() else float("nan")
     rec = {
         "metric": "hybrid-attn decode tokens/s @32K context, Llama-3-8B layer shape", "value": B * n_steps / el,
         "unit": "tokens/s", "n_gpus": 1, "steps": n_steps, "warmup": args.warmup, "ms_per_step": el / n_steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"c5: B={B} context={N} Hq={Hq} Hkv={Hkv} d={d} C={w.C} W={w.W} lambda={w.lam}",
+        "config": {"workload": f"c5: B={B} context={N} Hq={Hq} Hkv={Hkv} d={d} C={w.C} W={w.W} lambda={w.lam}" + budget_tag(w),
                    "median_ordinary_step_ms": ordinary,
                    "routing_step_ms": [float(x) for x in lat[routing]],
                    "prefill_of_contexts_s": t_prefill, "state_gb": state.numel() / 1e9},
@@ -198,6 +209,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 20 prefill calls, 128 decode steps)")
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--max-retained", type=int, default=0,
+                    help="budget on the retained tokens per (sequence, head); 0 (default) = none, the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc runs)")
@@ -231,7 +244,7 @@ def main() -> int:
         return decode_bench(args)
     if not args.steps:
         args.steps = 20
-    w = synth.CONFIGS[args.config]
+    w = synth.workload(args.config, max_retained=args.max_retained)
     inp = synth.make_inputs(w)
     dev = "cuda"
     q, k, v = (synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v"))
@@ -239,7 +252,7 @@ def main() -> int:
     out = torch.empty_like(q)
     N = w.N
     p = S.make_params(B=w.B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out)
+                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, max_retained=w.max_retained)
     ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
@@ -278,7 +291,8 @@ def main() -> int:
     peak = PEAK_MFMA[w.dtype]
     roofline = {"bound": "mfma", "kernel": dom, "achieved": flops / dom_s / 1e12, "peak": peak / 1e12,
                 "unit": "TFLOP/s", "frac": flops / dom_s / peak,
-                "traffic": args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC.get(args.config),
+                "traffic": args.traffic_bytes if args.traffic_bytes is not None else
+                (MEASURED_TRAFFIC.get(args.config) if w.max_retained <= 0 else None),
                 "algorithmic_flops_per_launch": flops, "avg_launch_ms": dom_ms}
     rec = {
         "metric": "hybrid-attn fwd tokens/s @32K, Llama-3-8B layer shape" if args.config == "c4"
@@ -287,7 +301,7 @@ def main() -> int:
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} N={N} Hq={w.Hq} Hkv={w.Hkv} d={w.d} C={w.C} W={w.W} "
-                               f"lambda={w.lam} heavy_frac={w.heavy_frac}",
+                               f"lambda={w.lam} heavy_frac={w.heavy_frac}" + budget_tag(w),
                    "path_gflop_per_step": path_flops(w, N) / 1e9,
                    "compulsory_hbm_mb_per_step": compulsory_bytes(w, N) / 1e6,
                    "path_frac_of_mfma_peak": path_flops(w, N) / (ms_step * 1e-3) / peak,

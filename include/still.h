@@ -66,6 +66,13 @@ typedef struct still_params {
   int32_t dtype;                 /* still_dtype_t of q, k, v, g, out, Wq, Wk, bq, bk                        */
   int32_t max_tokens;            /* capacity (tokens per sequence) of a decode state; used only by the state
                                     functions, the decode step and state_out; 0 where no state is involved  */
+  int32_t max_retained;          /* budget on the retained tokens of one (sequence, query head); <= 0: none.
+                                    The long-context evaluations of Sec. 4 cap the number of selected tokens
+                                    without stating a policy; here chunks are served in order: chunk c keeps
+                                    its min(lambda, max_retained - c*lambda) highest scores (none once the
+                                    budget is used up) and the rest of the chunk goes to the linear state like
+                                    any other un-selected token.  Slots of an index list that a chunk does not
+                                    use hold -1.  A decode state then needs only max_retained retained rows. */
   int64_t q_sb, q_st, q_sh;      /* q   [B, N, Hq,  d]                                                     */
   int64_t k_sb, k_st, k_sh;      /* k   [B, N, Hkv, d]                                                     */
   int64_t v_sb, v_st, v_sh;      /* v   [B, N, Hkv, d]                                                     */
@@ -118,9 +125,11 @@ STILL_API still_status_t still_fwd_workspace_layout(const still_params_t* p, sti
  *   out            device, dtype, strided; rows written for every (b, t < N, hq)
  *   score_out      device float [B, Hq, N] or NULL: Score of every token
  *   sel_idx        device int32 [B, Hq, N/C, lambda] or NULL: global token indices of the tokens kept
- *                  in each full chunk, ascending within a chunk
+ *                  in each full chunk, ascending within a chunk; -1 in the slots that a budget
+ *                  (max_retained) leaves unused, which are always the last slots of a chunk
  *   sel_idx_is_input  0: sel_idx (if given) is an OUTPUT.  1: sel_idx is an INPUT that replaces the
- *                  Top-lambda step (indices must lie inside their chunk, strictly ascending); test hook
+ *                  Top-lambda step (indices must lie inside their chunk, strictly ascending; with a budget
+ *                  only the first min(lambda, max_retained - c*lambda) slots of chunk c are read); test hook
  *   state_out      device, or NULL: a decode state buffer (see still_state_bytes; p->max_tokens >= N);
  *                  on return it holds the tokens 0..N-1, so the next decode step is t = N.  Its previous
  *                  contents are overwritten (no still_state_init needed)
@@ -163,9 +172,11 @@ STILL_API const char* still_profile_kernel_name(int32_t i);
  * cache-routing equation (Sec. 3.3), plus the ring of recent tokens that delayed selection needs.  One
  * opaque caller-owned device buffer of still_state_bytes(p) bytes (p->max_tokens = capacity per sequence):
  *   S    float [B, Hq, 2*d_f*(d+1)]   state through the last routed chunk: S (2*d_f x d) then z (2*d_f)
- *   Kret dtype [B, Hq, cap, d]        retained keys in routing order, cap = lambda*ceil(max_tokens/C) (+pad)
+ *   Kret dtype [B, Hq, cap, d]        retained keys in routing order, cap = lambda*ceil(max_tokens/C), or
+ *                                     max_retained if that is smaller (+pad)
  *   Vret dtype [B, Hq, cap, d]        retained values
- *   sel  int32 [B, Hq, ceil(max_tokens/C), lambda]   token indices kept per routed chunk (for inspection)
+ *   sel  int32 [B, Hq, ceil(max_tokens/C), lambda]   token indices kept per routed chunk, -1 in unused slots
+ *                                     (for inspection)
  *   ring dtype [B, Hkv, R, d] x 2     keys and values of the last R = 4*C tokens, slot = token % R
  *   sc   float [B, Hq, R]             Self-Saliency Score of the same tokens
  *   part float [B, Hq, 32, d+2]       split partials of the attention pass
@@ -189,7 +200,8 @@ STILL_API still_status_t still_state_init(const still_params_t* p, void* state, 
  * exactly the tokens 0..t-1) of every sequence in the batch:
  *   - (k_t, v_t) are appended to the ring and the token's Self-Saliency Score over its window is stored;
  *   - if t opens a new chunk c = t/C >= 2, chunk c-2 leaves the local span and is routed: its Top-lambda
- *     keys/values join the retained cache, the others are added to (s, z) through the NP-Map;
+ *     keys/values (fewer once a max_retained budget runs out) join the retained cache, the others are added
+ *     to (s, z) through the NP-Map;
  *   - y_t = (N_SA + N_LA) / (D_SA + D_LA) over the retained cache, the local span and the state.
  *
  *   q_t [B, Hq, d], k_t, v_t [B, Hkv, d], g_t [B, Hq, d] or NULL, out_t [B, Hq, d]: device, dtype, contiguous.

@@ -94,6 +94,7 @@ SideStream* side_stream() {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline size_t esize(int dtype) { return dtype == STILL_BF16 ? 2 : 4; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline int retained_budget(const still_params_t* p) { return p->max_retained > 0 ? p->max_retained : still::kNoBudget; }
 
 still_status_t validate_params(const still_params_t* p, bool need_n) {
   if (p == nullptr) return fail(STILL_ERR_INVALID_ARG, "params is NULL");
@@ -148,7 +149,7 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   const int64_t B = p->B, N = p->N, Hq = p->Hq, Hkv = p->Hkv, d = p->d, df = p->d_f;
   const int64_t nc = (N + p->C - 1) / p->C, ncf = N / p->C;
   const int64_t npad = (N + 127) / 128 * 128;
-  const int64_t cap = (ncf * p->lambda + 63) / 64 * 64;
+  const int64_t cap = ((int64_t)still::retained_rows((int)ncf, p->lambda, retained_budget(p)) + 63) / 64 * 64;
   int64_t G = (nc * B * Hq + 255) / 256;   // one workgroup per CU at the size of the chip
   if (G < 2) G = 2;
   if (G > nc) G = nc;
@@ -190,7 +191,7 @@ void compute_state_layout(const still_params_t* p, still_state_layout_t* L) {
   const size_t es = esize(p->dtype);
   const int64_t B = p->B, Hq = p->Hq, Hkv = p->Hkv, d = p->d, df = p->d_f;
   const int64_t nch = ((int64_t)p->max_tokens + p->C - 1) / p->C;
-  const int64_t cap = (nch * p->lambda + 63) / 64 * 64 + 64;
+  const int64_t cap = ((int64_t)still::retained_rows((int)nch, p->lambda, retained_budget(p)) + 63) / 64 * 64 + 64;
   const int64_t R = 4 * (int64_t)p->C;
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -216,7 +217,7 @@ void compute_state_layout(const still_params_t* p, still_state_layout_t* L) {
 
 extern "C" {
 
-int32_t still_version(void) { return 100; }
+int32_t still_version(void) { return 200; }
 
 const char* still_last_error(void) { return g_err; }
 
@@ -302,7 +303,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   sa.q_sb = p->q_sb; sa.q_st = p->q_st; sa.q_sh = p->q_sh;
   sa.k_sb = p->k_sb; sa.k_st = p->k_st; sa.k_sh = p->k_sh;
   sa.map = map;
-  sa.N = N; sa.C = C; sa.W = p->W; sa.lam = p->lambda; sa.Hq = p->Hq; sa.ncf = ncf;
+  sa.N = N; sa.C = C; sa.W = p->W; sa.lam = p->lambda; sa.Hq = p->Hq; sa.ncf = ncf; sa.rcap = retained_budget(p);
   sa.scale = p->scale; sa.eps = p->eps;
   sa.score = score;
   sa.sel = (have_sel && !sel_idx_is_input) ? sel : nullptr;
@@ -325,7 +326,8 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   ga.v_sb = p->v_sb; ga.v_st = p->v_st; ga.v_sh = p->v_sh;
   ga.map = map;
   ga.sel = sel;
-  ga.nsel = have_sel ? ncf * p->lambda : 0;
+  ga.nsel = have_sel ? still::retained_rows(ncf, p->lambda, retained_budget(p)) : 0;
+  ga.sel_stride = ncf * p->lambda;
   ga.cap = L.cap; ga.Hq = p->Hq; ga.d = d; ga.N = N;
   ga.kret = ws + L.kret; ga.vrett = ws + L.vrett;
   if ((e = still::launch_gather(ga, p->dtype, B, stream)) != hipSuccess)
@@ -345,7 +347,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   la.sel = sel;
   la.map = map;
   la.N = N; la.Np = L.n_pad; la.C = C; la.lam = have_sel ? p->lambda : 0; la.Hq = p->Hq; la.Hkv = p->Hkv;
-  la.nc = nc; la.ncf = ncf;
+  la.nc = nc; la.ncf = ncf; la.rcap = retained_budget(p);
   la.seg_chunks = L.seg_chunks; la.nseg = L.nseg;
   la.seg = reinterpret_cast<float*>(ws + L.seg);
   la.n_la = reinterpret_cast<float*>(ws + L.n_la);
@@ -380,6 +382,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   sx.out = out; sx.o_sb = p->o_sb; sx.o_st = p->o_st; sx.o_sh = p->o_sh;
   sx.map = map;
   sx.N = N; sx.Np = L.n_pad; sx.C = C; sx.lam = have_sel ? p->lambda : 0; sx.Hq = p->Hq; sx.Hkv = p->Hkv;
+  sx.rcap = retained_budget(p);
   sx.cap = L.cap; sx.ntiles = (N + still::kSaRows - 1) / still::kSaRows; sx.B_ = B;
   sx.scale = p->scale;
   if ((e = still::launch_sa(sx, p->dtype, d, B, stream)) != hipSuccess)
@@ -398,7 +401,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
     sf.kring = stp + SL.kring; sf.vring = stp + SL.vring;
     sf.score_ring = reinterpret_cast<float*>(stp + SL.score);
     sf.N = N; sf.R = SL.R; sf.Hq = p->Hq; sf.Hkv = p->Hkv; sf.d = d; sf.lam = have_sel ? p->lambda : 0;
-    sf.cap = SL.cap; sf.ncf = ncf; sf.nchunks = SL.n_chunks;
+    sf.cap = SL.cap; sf.ncf = ncf; sf.nchunks = SL.n_chunks; sf.rcap = retained_budget(p);
     const int n_routed = nc >= 2 ? nc - 2 : 0;
     if (!need_scores) return fail(STILL_ERR_INVALID_ARG, "state_out needs the scores: do not combine it with sel_idx_is_input unless score_out is given");
     if ((e = still::launch_state_fill(sf, p->dtype, B, n_routed, stream)) != hipSuccess)
@@ -495,10 +498,10 @@ still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* stat
   a.q = q_t; a.k = k_t; a.v = v_t; a.g = g_t; a.wq = Wq; a.wk = Wk; a.bq = bq; a.bk = bk; a.out = out_t;
   fill_map(p, &a.map);
   a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.C = p->C; a.W = p->W; a.lam = p->lambda;
-  a.cap = L.cap; a.R = L.R; a.nchunks = L.n_chunks; a.t = t;
+  a.cap = L.cap; a.R = L.R; a.nchunks = L.n_chunks; a.t = t; a.rcap = retained_budget(p);
   a.scale = p->scale; a.eps = p->eps;
   const int c = t / p->C;
-  const int rows = (c >= 1 ? c - 1 : 0) * p->lambda + (t - (c >= 1 ? c - 1 : 0) * p->C + 1);
+  const int rows = still::retained_rows(c >= 1 ? c - 1 : 0, p->lambda, a.rcap) + (t - (c >= 1 ? c - 1 : 0) * p->C + 1);
   int nsplit = (1024 + p->B * p->Hq - 1) / (p->B * p->Hq);
   if (nsplit > 32) nsplit = 32;
   if (nsplit > (rows + 63) / 64) nsplit = (rows + 63) / 64;

@@ -137,6 +137,7 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr) {
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int kvh = a.map.kv[hq];
   const int C = a.C, lam = a.lam, R = a.R;
+  const int quota = chunk_quota(cr, lam, a.rcap);   // what the budget on retained tokens leaves this chunk
   const int64_t unit = (int64_t)b * a.Hq + hq;
   const T* kring = static_cast<const T*>(a.kring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)R * D;
   const T* vring = static_cast<const T*>(a.vring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)R * D;
@@ -151,24 +152,25 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr) {
       const float sj = s_sc[jx];
       rank += (sj > si || (sj == si && jx < tid)) ? 1 : 0;
     }
-    chosen = rank < lam;
+    chosen = rank < quota;
     s_flag[tid] = chosen ? 1 : 0;
   }
   __syncthreads();
   if (chosen) {
     int pos = 0;
     for (int jx = 0; jx < tid; ++jx) pos += s_flag[jx];
-    if (pos < lam) {
+    if (pos < quota) {
       a.sel[(unit * a.nchunks + cr) * lam + pos] = cr * C + tid;
       s_list[pos] = tid;
     }
   }
+  if (tid >= quota && tid < lam) a.sel[(unit * a.nchunks + cr) * lam + tid] = -1;
   __syncthreads();
   // selected rows -> retained cache (rows cr*lam ..)
   {
     T* kret = static_cast<T*>(a.kret) + (unit * a.cap + (int64_t)cr * lam) * D;
     T* vret = static_cast<T*>(a.vret) + (unit * a.cap + (int64_t)cr * lam) * D;
-    for (int idx = tid; idx < lam * D; idx += 256) {
+    for (int idx = tid; idx < quota * D; idx += 256) {
       const int row = idx / D, x = idx % D;
       const int slot = (cr * C + s_list[row]) % R;
       kret[(int64_t)row * D + x] = kring[(int64_t)slot * D + x];
@@ -318,7 +320,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const int kvh = a.map.kv[hq];
   const int64_t unit = (int64_t)b * a.Hq + hq;
   const int c = a.t / a.C;
-  const int n_ret = (c >= 1 ? c - 1 : 0) * a.lam;
+  const int n_ret = retained_rows(c >= 1 ? c - 1 : 0, a.lam, a.rcap);
   const int lo = (c >= 1 ? c - 1 : 0) * a.C;
   const int nr = n_ret + (a.t - lo + 1);
   int per = (nr + a.nsplit - 1) / a.nsplit;
@@ -524,7 +526,9 @@ __global__ void state_fill_retained_kernel(StateFillArgs a) {
   const int kvh = a.map.kv[hq];
   const int cr = row / a.lam, pos = row % a.lam;
   int tok = a.sel[(unit * a.ncf + cr) * a.lam + pos];
-  if (threadIdx.x == 0) a.sel_state[(unit * a.nchunks + cr) * a.lam + pos] = tok;
+  const bool used = pos < chunk_quota(cr, a.lam, a.rcap);   // the budget on retained tokens leaves later slots empty
+  if (threadIdx.x == 0) a.sel_state[(unit * a.nchunks + cr) * a.lam + pos] = used ? tok : -1;
+  if (!used) return;
   if (tok < 0 || tok >= a.N) tok = 0;
   const T* k = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)tok * a.k_st + (int64_t)kvh * a.k_sh;
   const T* v = static_cast<const T*>(a.v) + (int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)kvh * a.v_sh;

@@ -11,10 +11,24 @@ struct ScoreArgs {
   int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
   HeadMap map;
   int N, C, W, lam, Hq, ncf;
+  int rcap;       // budget on the retained tokens of one (batch, head): see chunk_quota()
   float scale, eps;
   float* score;   // [B, Hq, N]
   int32_t* sel;   // [B, Hq, ncf, lam] or nullptr (no selection)
 };
+
+// Tokens that chunk c keeps when at most rcap tokens may be retained in total and chunks are served in order:
+// lam until the budget is used up, then what is left of it, then none.  Retained row c * lam + pos therefore
+// stays the row of slot pos of chunk c, and the rows in use are exactly those below min(chunks * lam, rcap).
+__host__ __device__ inline int chunk_quota(int c, int lam, int rcap) {
+  const int left = rcap - c * lam;
+  return left >= lam ? lam : (left > 0 ? left : 0);
+}
+__host__ __device__ inline int retained_rows(int chunks, int lam, int rcap) {
+  const int r = chunks * lam;
+  return r < rcap ? r : rcap;
+}
+constexpr int kNoBudget = 1 << 30;
 
 struct TransposeVArgs {
   const void* v;
@@ -45,8 +59,8 @@ struct GatherArgs {
   const void* v;
   int64_t k_sb, k_st, k_sh, v_sb, v_st, v_sh;
   HeadMap map;
-  const int32_t* sel;  // [B, Hq, nsel]
-  int nsel, cap, Hq, d, N;
+  const int32_t* sel;  // [B, Hq, sel_stride]; the first nsel entries of each list are gathered
+  int nsel, sel_stride, cap, Hq, d, N;
   void* kret;          // [B, Hq, cap, d]
   void* vrett;         // [B, Hq, d, cap]
 };
@@ -64,7 +78,7 @@ struct LaArgs {
   const void* bk;
   const int32_t* sel;  // [B, Hq, ncf, lam]
   HeadMap map;
-  int N, Np, C, lam, Hq, Hkv, nc, ncf;
+  int N, Np, C, lam, Hq, Hkv, nc, ncf, rcap;
   int seg_chunks, nseg;
   float* seg;          // [B, Hq, nseg, DP*(D+1)]: S (DP x D) then z (DP)
   float* n_la;         // [B, Hq, N, d]
@@ -97,7 +111,7 @@ struct SaArgs {
   void* out;
   int64_t o_sb, o_st, o_sh;
   HeadMap map;
-  int N, Np, C, lam, Hq, Hkv, cap, ntiles, B_;
+  int N, Np, C, lam, Hq, Hkv, cap, ntiles, B_, rcap;
   float scale;
 };
 
@@ -120,7 +134,7 @@ struct DecArgs {
   const void* bk;
   void* out;           // [B, Hq, d]
   HeadMap map;
-  int B, Hq, Hkv, C, W, lam, cap, R, nchunks, t, nsplit;
+  int B, Hq, Hkv, C, W, lam, cap, R, nchunks, t, nsplit, rcap;
   float scale, eps;
 };
 
@@ -137,7 +151,7 @@ struct StateFillArgs {
   void* kring;
   void* vring;
   float* score_ring;
-  int N, R, Hq, Hkv, d, lam, cap, ncf, nchunks;
+  int N, R, Hq, Hkv, d, lam, cap, ncf, nchunks, rcap;
 };
 
 hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hipStream_t stream);

@@ -230,7 +230,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
     auto load_sel = [&](const LaUnit& x, int lane) __attribute__((always_inline)) {
       const int32_t* selc = a.sel + (((int64_t)b * a.Hq + hq) * a.ncf + (x.valid ? x.chunk : 0)) * a.lam;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) selv[j] = (x.valid && lane + 64 * j < a.lam) ? selc[lane + 64 * j] : -1;
+      for (int j = 0; j < 2; ++j) selv[j] = (x.valid && lane + 64 * j < chunk_quota(x.chunk, a.lam, a.rcap)) ? selc[lane + 64 * j] : -1;
     };
     // A staged K unit (slot, then sums) travels global memory -> registers -> LDS in 1 KB pieces dealt over the
     // producer waves: the loads go out in the unit's first interval, when the producers have nothing to project

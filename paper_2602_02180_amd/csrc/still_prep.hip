@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     const int row = r0 + threadIdx.x;
     int tok = -1;
     if (row < a.nsel) {
-      tok = a.sel[((int64_t)b * a.Hq + hq) * a.nsel + row];
+      tok = a.sel[((int64_t)b * a.Hq + hq) * a.sel_stride + row];
       if (tok < 0 || tok >= a.N) tok = -1;  // caller-supplied indices are never trusted for addressing
     }
     s_tok[threadIdx.x] = tok;

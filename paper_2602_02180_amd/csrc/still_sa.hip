@@ -192,12 +192,12 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   const int t = q0 + r;
   const bool wave_active = q0 < N;
   const int cw = q0 / C;
-  const int ret_w = (cw >= 1 ? cw - 1 : 0) * lam;     // retained keys visible to this wave
+  const int ret_w = retained_rows(cw >= 1 ? cw - 1 : 0, lam, a.rcap);   // retained keys visible to this wave
   const int lo_w = (cw >= 1 ? cw - 1 : 0) * C;        // first local key of this wave
   const int c_first = row0 / C;
   const int last_row = (row0 + Cf::BM - 1 < N - 1) ? row0 + Cf::BM - 1 : N - 1;
   const int c_last = last_row / C;
-  const int ret_max = (c_last >= 1 ? c_last - 1 : 0) * lam;
+  const int ret_max = retained_rows(c_last >= 1 ? c_last - 1 : 0, lam, a.rcap);
   const int loc_lo = (c_first >= 1 ? c_first - 1 : 0) * C;
   const int n_ret_tiles = (ret_max + BN - 1) / BN;
   const int n_tiles = n_ret_tiles + (last_row + 1 - loc_lo + BN - 1) / BN;

@@ -193,15 +193,18 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
     s_rank[threadIdx.x] = part;
     __syncthreads();
     bool chosen = false;
-    if ((int)threadIdx.x < C) chosen = s_rank[threadIdx.x] + s_rank[threadIdx.x + C] < a.lam;
+    const int quota = chunk_quota(c, a.lam, a.rcap);
+    int32_t* selc = a.sel + (((int64_t)b * a.Hq + hq) * a.ncf + c) * a.lam;
+    if ((int)threadIdx.x < C) chosen = s_rank[threadIdx.x] + s_rank[threadIdx.x + C] < quota;
+    if ((int)threadIdx.x >= quota && (int)threadIdx.x < a.lam) selc[threadIdx.x] = -1;   // slots the budget leaves empty
     const unsigned long long bal = __ballot(chosen);
     if (lane == 0) s_ball[wave] = bal;
     __syncthreads();
     if (chosen) {
       int pos = __popcll(bal & ((1ull << lane) - 1ull));
       for (int w = 0; w < wave; ++w) pos += __popcll(s_ball[w]);
-      if (pos < a.lam)  // NaN scores can flag more than lam tokens; never write past the chunk's slots
-        a.sel[(((int64_t)b * a.Hq + hq) * a.ncf + c) * a.lam + pos] = c * C + threadIdx.x;
+      if (pos < quota)  // NaN scores can flag more tokens than the quota; never write past the chunk's slots
+        selc[pos] = c * C + threadIdx.x;
     }
   }
 }

@@ -38,6 +38,7 @@ class Workload:
     d_f: int = 0    # NP-Map inner width (0 => d)
     eps: float = 1e-6
     decode_steps: int = 0
+    max_retained: int = 0     # budget on the retained tokens per (sequence, head); 0 => none
 
     @property
     def df(self) -> int:

@@ -29,7 +29,8 @@ def run_hip(w: synth.Workload, inp: Dict[str, np.ndarray], sel_in: Optional[np.n
     B, N = q.shape[0], q.shape[1]
     out = torch.full_like(q, float("nan"))
     p = S.make_params(B=B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, g=g, kv_head_of_q=kv_map)
+                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, g=g, kv_head_of_q=kv_map,
+                      max_retained=w.max_retained)
     ncf = N // w.C
     score = torch.full((B, w.Hq, N), float("nan"), dtype=torch.float32, device=dev)
     sel = torch.full((B, w.Hq, max(ncf, 1), max(w.lam, 1)), -1, dtype=torch.int32, device=dev)
@@ -56,24 +57,34 @@ def oracle_units(w: synth.Workload, inp, units: Iterable[Tuple[int, int]], sel: 
                  kv_map: Optional[np.ndarray] = None, rows=None, N: Optional[int] = None):
     kv_map = synth.kv_head_map(w) if kv_map is None else kv_map
     return O.still_forward_units(inp, kv_map, list(units), C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                                 form="chunkwise", sel=sel, rows=rows)
+                                 form="chunkwise", sel=sel, rows=rows, max_retained=budget(w))
+
+
+def budget(w: synth.Workload) -> Optional[int]:
+    return w.max_retained if w.max_retained > 0 else None
 
 
 def selection_report(score_ref: np.ndarray, sel_ref: np.ndarray, sel_hip: np.ndarray, C: int, lam: int,
-                     gap_tol: float = 1e-5):
+                     gap_tol: float = 1e-5, max_retained: Optional[int] = None):
     """Chunks whose oracle gap (lam-th vs (lam+1)-th score) exceeds gap_tol must match exactly.
     Returns (n_chunks, n_clear, n_clear_mismatch, n_tie_mismatch)."""
-    gaps = O.selection_gaps(score_ref, C, lam)
+    gaps = O.selection_gaps(score_ref, C, lam, max_retained)
     n = sel_ref.shape[0]
     clear = gaps > gap_tol
     mism = np.array([not np.array_equal(sel_ref[c], sel_hip[c]) for c in range(n)], dtype=bool)
     return n, int(clear.sum()), int((mism & clear).sum()), int((mism & ~clear).sum())
 
 
-def selection_is_valid(score_ref: np.ndarray, sel_hip: np.ndarray, C: int, tol: float) -> bool:
-    """Every kept token scores at least (every dropped token's score - tol); indices ascending, in chunk."""
+def selection_is_valid(score_ref: np.ndarray, sel_hip: np.ndarray, C: int, tol: float,
+                       max_retained: Optional[int] = None) -> bool:
+    """Every kept token scores at least (every dropped token's score - tol); indices ascending, in chunk;
+    each chunk keeps exactly its quota, in its first slots, the other slots hold -1."""
+    lam = sel_hip.shape[1]
     for c in range(sel_hip.shape[0]):
-        idx = sel_hip[c]
+        quota = O.chunk_quota(c, lam, max_retained)
+        if np.any(sel_hip[c][quota:] != -1) or np.any(sel_hip[c][:quota] < 0):
+            return False
+        idx = sel_hip[c][:quota]
         if idx.size == 0:
             continue
         if np.any(np.diff(idx) <= 0) or idx[0] < c * C or idx[-1] >= (c + 1) * C:

@@ -77,9 +77,11 @@ def check_scores_and_selection(w, hip, ref_units, units, what):
         ref = ref_units[(b, h)]
         err = float(np.max(np.abs(hip["score"][b, h] - ref["score"])))
         worst = max(worst, err)
-        n, clear, bad, tie = U.selection_report(ref["score"], ref["sel"], hip["sel"][b, h], w.C, w.lam)
+        n, clear, bad, tie = U.selection_report(ref["score"], ref["sel"], hip["sel"][b, h], w.C, w.lam,
+                                                max_retained=U.budget(w))
         stot, sclear, sbad, stie = stot + n, sclear + clear, sbad + bad, stie + tie
-        assert U.selection_is_valid(ref["score"], hip["sel"][b, h], w.C, tol=1e-4), f"unit {(b, h)}: not a top set"
+        assert U.selection_is_valid(ref["score"], hip["sel"][b, h], w.C, tol=1e-4, max_retained=U.budget(w)), \
+            f"unit {(b, h)}: not a top set"
     print(f"[{w.name}:{what}] score max-abs err {worst:.3e}; chunks {stot}, clear-gap {sclear}, "
           f"mismatch on clear {sbad}, mismatch on near-ties {stie} "
           f"(rate {stie / max(1, stot - sclear):.3f} of near-tie chunks)")
@@ -138,6 +140,22 @@ def test_c1_fp32_full():
 def test_small_shapes(kw):
     w = small("small", **kw)
     run_case(w, synth.make_inputs(w, seed=1234))
+
+
+# budget on the retained tokens: chunks keep lam until it is used up (one chunk may keep a part), then nothing
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f32", d=64, C=64, W=64, N=1024, lam=16, max_retained=40),           # 16, 16, 8, 0, ...
+    dict(dtype="f32", d=64, C=64, W=64, N=900, lam=16, max_retained=1000),          # never reached
+    dict(dtype="f32", d=128, C=64, W=128, N=1100, lam=32, max_retained=192, Hq=1, Hkv=1),
+    dict(dtype="bf16", d=128, C=128, W=128, N=2000, lam=16, max_retained=100, Hq=4, Hkv=2, B=2),
+    dict(dtype="bf16", d=64, C=64, W=64, N=1900, lam=48, max_retained=300, Hq=2, Hkv=2),
+    dict(dtype="bf16", d=128, C=64, W=64, N=1500, lam=64, max_retained=128),        # whole chunks kept: sink
+], ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
+def test_retained_budget(kw):
+    w = small("budget", **kw)
+    hip = run_case(w, synth.make_inputs(w, seed=4321))
+    kept = (hip["sel"] >= 0).sum(axis=(2, 3))
+    assert np.all(kept == min(w.max_retained, w.lam * (w.N // w.C)))
 
 
 @pytest.mark.parametrize("lam", [0, 1, 64])

@@ -44,6 +44,20 @@ def test_workspace_layout_is_consistent():
     assert L.n_la - L.seg >= 1 * 4 * L.nseg * (2 * 64 * 65) * 4
 
 
+def test_retained_budget_bounds_the_retained_rows_of_workspace_and_state():
+    free = S.still_fwd_workspace_layout(params(N=8192))
+    tight = S.still_fwd_workspace_layout(params(N=8192, max_retained=100))
+    assert free.cap == (8192 // 64) * 16 and tight.cap == 128
+    assert tight.total < free.total
+    roomy = S.still_fwd_workspace_layout(params(N=8192, max_retained=1 << 20))
+    assert roomy.cap == free.cap and roomy.total == free.total
+    # a decode state no longer grows with the context once the budget is set
+    s_free = S.still_state_layout(params(N=1, max_tokens=1 << 20))
+    s_tight = S.still_state_layout(params(N=1, max_tokens=1 << 20, max_retained=896))
+    assert s_free.cap >= (1 << 20) // 64 * 16 and s_tight.cap == 896 + 64
+    assert s_tight.kret < s_tight.vret and s_tight.vret - s_tight.kret == 1 * 4 * s_tight.cap * 64 * 2
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(d=96), S.STILL_ERR_UNSUPPORTED),
     (dict(C=32), S.STILL_ERR_UNSUPPORTED),
