@@ -214,6 +214,30 @@ STILL_API still_status_t still_hybrid_attn_decode_step(const still_params_t* p, 
                                                        const void* Wq, const void* bq, const void* Wk, const void* bk,
                                                        void* out_t, void* stream);
 
+/*
+ * The same decode step (recurrent form, Sec. 3.3) for sequences that are NOT in lock step, as a serving loop
+ * with continuous batching needs: sequence b appends the token with index t_dev[b] (its state must hold exactly
+ * the tokens 0..t_dev[b]-1 of that sequence).  Every sequence owns its slice of each state region, so sequences
+ * at different positions never interact; a sequence whose new token opens a chunk c >= 2 routes its own chunk
+ * c-2 in this call, the others do not.
+ *
+ *   t_dev   DEVICE int32 [B], read by the kernels of this call (the caller may advance it with a kernel of its
+ *           own between calls, so a captured graph of the step can be replayed).  An entry outside
+ *           [0, p->max_tokens) marks a sequence that sits this step out: its state and its row of out_t are
+ *           left untouched.
+ *   t_max   HOST upper bound of the entries of t_dev, 0 <= t_max < p->max_tokens (p->max_tokens - 1 is always
+ *           valid); it only sizes the launch (how many workgroups share one sequence's cache rows), a tight
+ *           bound gives the best split.  Entries above t_max still give correct results.
+ * All other arguments as for still_hybrid_attn_decode_step.  Returns STILL_ERR_STATE when t_max is outside
+ * [0, p->max_tokens).
+ */
+STILL_API still_status_t still_hybrid_attn_decode_step_at(const still_params_t* p, void* state,
+                                                          const int32_t* t_dev, int32_t t_max,
+                                                          const void* q_t, const void* k_t, const void* v_t,
+                                                          const void* g_t,
+                                                          const void* Wq, const void* bq, const void* Wk, const void* bk,
+                                                          void* out_t, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -81,6 +81,8 @@ def lib() -> ct.CDLL:
         L.still_state_init.argtypes = [pp, vp, vp]
         L.still_hybrid_attn_decode_step.restype = ct.c_int
         L.still_hybrid_attn_decode_step.argtypes = [pp, vp, ct.c_int32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.still_hybrid_attn_decode_step_at.restype = ct.c_int
+        L.still_hybrid_attn_decode_step_at.argtypes = [pp, vp, vp, ct.c_int32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.still_profile_enable.restype = None
         L.still_profile_enable.argtypes = [ct.c_int32]
         L.still_profile_read.restype = ct.c_int
@@ -198,6 +200,19 @@ def still_hybrid_attn_decode_step(p: StillParams, state, t: int, q_t, k_t, v_t, 
     _check(lib().still_hybrid_attn_decode_step(ct.byref(p), _ptr(state), t, _ptr(q_t), _ptr(k_t), _ptr(v_t),
                                                _ptr(g_t), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(out_t),
                                                stream.cuda_stream))
+
+
+def still_hybrid_attn_decode_step_at(p: StillParams, state, t_dev, t_max: int, q_t, k_t, v_t, g_t, Wq, bq, Wk, bk,
+                                     out_t, stream=None) -> None:
+    """t_dev: int32 device tensor [B] with each sequence's token index; t_max: host upper bound of them."""
+    import torch
+
+    assert t_dev.dtype == torch.int32 and t_dev.is_cuda and t_dev.is_contiguous()
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(lib().still_hybrid_attn_decode_step_at(ct.byref(p), _ptr(state), _ptr(t_dev), t_max, _ptr(q_t), _ptr(k_t),
+                                                  _ptr(v_t), _ptr(g_t), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk),
+                                                  _ptr(out_t), stream.cuda_stream))
 
 
 STILL_PROFILE_SLOTS = 8

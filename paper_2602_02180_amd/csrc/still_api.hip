@@ -472,10 +472,15 @@ still_status_t still_state_init(const still_params_t* p, void* state, void* stre
   return STILL_OK;
 }
 
-still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* state, int32_t t, const void* q_t,
-                                             const void* k_t, const void* v_t, const void* g_t, const void* Wq,
-                                             const void* bq, const void* Wk, const void* bk, void* out_t,
-                                             void* stream_v) {
+}  // extern "C"
+
+namespace {
+
+// One decode step.  t_dev == nullptr: every sequence is at token t.  Otherwise t_dev holds each sequence's own
+// token index on the device and t is an upper bound of them, used only to size the launch.
+still_status_t decode_step(const still_params_t* p, void* state, int32_t t, const int32_t* t_dev, const void* q_t,
+                           const void* k_t, const void* v_t, const void* g_t, const void* Wq, const void* bq,
+                           const void* Wk, const void* bk, void* out_t, void* stream_v) {
   still_status_t st = validate_state_params(p);
   if (st != STILL_OK) return st;
   if (!state || !q_t || !k_t || !v_t || !Wq || !Wk || !out_t)
@@ -500,6 +505,7 @@ still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* stat
   a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.C = p->C; a.W = p->W; a.lam = p->lambda;
   a.cap = L.cap; a.R = L.R; a.nchunks = L.n_chunks; a.t = t; a.rcap = retained_budget(p);
   a.scale = p->scale; a.eps = p->eps;
+  a.tpos = t_dev; a.max_tokens = p->max_tokens;
   const int c = t / p->C;
   const int rows = still::retained_rows(c >= 1 ? c - 1 : 0, p->lambda, a.rcap) + (t - (c >= 1 ? c - 1 : 0) * p->C + 1);
   int nsplit = (1024 + p->B * p->Hq - 1) / (p->B * p->Hq);
@@ -507,11 +513,32 @@ still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* stat
   if (nsplit > (rows + 63) / 64) nsplit = (rows + 63) / 64;
   if (nsplit < 1) nsplit = 1;
   a.nsplit = nsplit;
-  const bool route = (t % p->C == 0) && c >= 2;
+  // with per-sequence positions any sequence at a chunk start >= 2C routes; the others leave the kernel at once
+  const bool route = t_dev != nullptr ? c >= 2 : ((t % p->C == 0) && c >= 2);
   hipError_t e = still::launch_decode_step(a, p->dtype, p->d, route, static_cast<hipStream_t>(stream_v));
   if (e != hipSuccess) return fail(STILL_ERR_HIP, "decode_step: %s", hipGetErrorString(e));
   g_err[0] = 0;
   return STILL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+still_status_t still_hybrid_attn_decode_step(const still_params_t* p, void* state, int32_t t, const void* q_t,
+                                             const void* k_t, const void* v_t, const void* g_t, const void* Wq,
+                                             const void* bq, const void* Wk, const void* bk, void* out_t,
+                                             void* stream_v) {
+  return decode_step(p, state, t, nullptr, q_t, k_t, v_t, g_t, Wq, bq, Wk, bk, out_t, stream_v);
+}
+
+still_status_t still_hybrid_attn_decode_step_at(const still_params_t* p, void* state, const int32_t* t_dev,
+                                                int32_t t_max, const void* q_t, const void* k_t, const void* v_t,
+                                                const void* g_t, const void* Wq, const void* bq, const void* Wk,
+                                                const void* bk, void* out_t, void* stream_v) {
+  if (t_dev == nullptr) return fail(STILL_ERR_INVALID_ARG, "t_dev is NULL");
+  if ((reinterpret_cast<uintptr_t>(t_dev) & 3) != 0) return fail(STILL_ERR_INVALID_ARG, "t_dev is not 4-byte aligned");
+  return decode_step(p, state, t_max, t_dev, q_t, k_t, v_t, g_t, Wq, bq, Wk, bk, out_t, stream_v);
 }
 
 }  // extern "C"

@@ -74,7 +74,9 @@ __device__ __forceinline__ void block_reduce4(float& a, float& b, float& c, floa
 template <typename T>
 __global__ void decode_append_kernel(DecArgs a, int D) {
   const int h = blockIdx.x, b = blockIdx.y;
-  const int slot = a.t % a.R;
+  const int t = step_index(a, b);
+  if (t < 0) return;
+  const int slot = t % a.R;
   const T* k = static_cast<const T*>(a.k) + ((int64_t)b * a.Hkv + h) * D;
   const T* v = static_cast<const T*>(a.v) + ((int64_t)b * a.Hkv + h) * D;
   T* kr = static_cast<T*>(a.kring) + (((int64_t)b * a.Hkv + h) * a.R + slot) * D;
@@ -91,8 +93,10 @@ __global__ __launch_bounds__(128) void decode_score_kernel(DecArgs a) {
   __shared__ float sh[16];
   const int hq = blockIdx.x, b = blockIdx.y;
   const int kvh = a.map.kv[hq];
+  const int t = step_index(a, b);
+  if (t < 0) return;
   const int j = threadIdx.x;              // window key t - j
-  const int pj = a.t - j;
+  const int pj = t - j;
   const bool valid = j < a.W && pj >= 0;
   const T* q = static_cast<const T*>(a.q) + ((int64_t)b * a.Hq + hq) * D;
   const T* krow = j == 0 ? static_cast<const T*>(a.k) + ((int64_t)b * a.Hkv + kvh) * D
@@ -124,17 +128,23 @@ __global__ __launch_bounds__(128) void decode_score_kernel(DecArgs a) {
   float term = valid ? ad * (fast_log2(ad + a.eps) - fast_log2(an + a.eps)) : 0.f;
   float z0 = 0.f, z1 = 0.f, z2 = 0.f;
   block_reduce4(term, z0, z1, z2, sh, 2);
-  if (threadIdx.x == 0) a.score[((int64_t)b * a.Hq + hq) * a.R + a.t % a.R] = term * kLn2;
+  if (threadIdx.x == 0) a.score[((int64_t)b * a.Hq + hq) * a.R + t % a.R] = term * kLn2;
 }
 
 // ---------------------------------------------------------------- routing of chunk cr = t/C - 2
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr) {
+__global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr_all) {
   constexpr int DF = D, DP = 2 * D;
   __shared__ float s_sc[128];
   __shared__ unsigned char s_flag[128];
   __shared__ int s_list[128];
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  int cr = cr_all;
+  if (a.tpos != nullptr) {   // per-sequence positions: only a sequence whose new token opens a chunk c >= 2 routes
+    const int t = step_index(a, b);
+    if (t < 0 || t % a.C != 0 || t / a.C < 2) return;
+    cr = t / a.C - 2;
+  }
   const int kvh = a.map.kv[hq];
   const int C = a.C, lam = a.lam, R = a.R;
   const int quota = chunk_quota(cr, lam, a.rcap);   // what the budget on retained tokens leaves this chunk
@@ -319,10 +329,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const int sub = lane % LPR, grp = lane / LPR;
   const int kvh = a.map.kv[hq];
   const int64_t unit = (int64_t)b * a.Hq + hq;
-  const int c = a.t / a.C;
+  const int t = step_index(a, b);
+  if (t < 0) return;
+  const int c = t / a.C;
   const int n_ret = retained_rows(c >= 1 ? c - 1 : 0, a.lam, a.rcap);
   const int lo = (c >= 1 ? c - 1 : 0) * a.C;
-  const int nr = n_ret + (a.t - lo + 1);
+  const int nr = n_ret + (t - lo + 1);
   int per = (nr + a.nsplit - 1) / a.nsplit;
   per = (per + NG - 1) / NG * NG;
   const int r_beg = split * per;
@@ -409,6 +421,7 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(DecArgs a) {
   __shared__ float qs[D], phi[DP], sh[16], fpart[2][DF];
   __shared__ __attribute__((aligned(16))) float red[RP][D];
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  if (step_index(a, b) < 0) return;
   const int64_t unit = (int64_t)b * a.Hq + hq;
   const T* q = static_cast<const T*>(a.q) + unit * D;
   if (tid < D) qs[tid] = to_f32(q[tid]);

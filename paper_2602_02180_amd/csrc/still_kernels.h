@@ -135,8 +135,18 @@ struct DecArgs {
   void* out;           // [B, Hq, d]
   HeadMap map;
   int B, Hq, Hkv, C, W, lam, cap, R, nchunks, t, nsplit, rcap;
+  const int32_t* tpos;     // nullable, device [B]: index of each sequence's new token (t is then ignored)
+  int max_tokens;
   float scale, eps;
 };
+
+// Index of the new token of sequence b: the same for every sequence, or the caller's per-sequence entry.  An
+// entry outside [0, max_tokens) marks a sequence that sits this step out (-1 is returned).
+__device__ inline int step_index(const DecArgs& a, int b) {
+  if (a.tpos == nullptr) return a.t;
+  const int t = a.tpos[b];
+  return (t >= 0 && t < a.max_tokens) ? t : -1;
+}
 
 struct StateFillArgs {
   const void* k;

@@ -55,8 +55,47 @@ def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False):
     return synth.from_torch(out), sel
 
 
-def check_decode(w, inp, n_prefill, n_total, with_gate=False):
-    got, sel_h = run_decode(w, inp, n_prefill, n_total, with_gate=with_gate)
+def run_decode_staggered(w, inp, n_total, offsets, tight_bound=True):
+    """Sequence b joins at step offsets[b] with an empty state and then appends one token per step through
+    still_hybrid_attn_decode_step_at; before joining and after its last token it sits the step out (-1)."""
+    import torch
+
+    dev = "cuda"
+    full = {k: synth.to_torch(inp[k], w.dtype, dev) for k in ("q", "k", "v", "Wq", "Wk")}
+    B = w.B
+    out = torch.full((B, n_total, w.Hq, w.d), float("nan"), dtype=full["q"].dtype, device=dev)
+    ps = S.make_params(B=B, N=1, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                       dtype=w.dtype, d_f=w.df, max_tokens=n_total, max_retained=w.max_retained)
+    state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
+    S.still_state_init(ps, state)
+    ar = torch.arange(B, device=dev)
+    sentinel = torch.full((B, w.Hq, w.d), 12345.0, dtype=full["q"].dtype, device=dev)
+    for s in range(n_total + max(offsets)):
+        pos = [s - o if 0 <= s - o < n_total else -1 for o in offsets]
+        live = [b for b in range(B) if pos[b] >= 0]
+        t_dev = torch.tensor(pos, dtype=torch.int32, device=dev)
+        rd = torch.tensor([max(p, 0) for p in pos], device=dev)
+        qt, kt, vt = (full[n][ar, rd].contiguous() for n in ("q", "k", "v"))
+        ot = sentinel.clone()
+        t_max = max(pos) if tight_bound else n_total - 1
+        S.still_hybrid_attn_decode_step_at(ps, state, t_dev, t_max, qt, kt, vt, None, full["Wq"], None, full["Wk"],
+                                           None, ot)
+        for b in range(B):
+            if pos[b] >= 0:
+                out[b, pos[b]] = ot[b]
+            else:
+                assert torch.equal(ot[b], sentinel[b]), f"step {s}: idle sequence {b} was written"
+        assert live
+    torch.cuda.synchronize()
+    L = S.still_state_layout(ps)
+    n_routed = max(0, (n_total - 1) // w.C - 1)
+    sel = state[L.sel:L.sel + B * w.Hq * L.n_chunks * max(w.lam, 1) * 4].view(torch.int32)
+    sel = sel.reshape(B, w.Hq, L.n_chunks, max(w.lam, 1)).cpu().numpy().astype(np.int64)[:, :, :n_routed, :w.lam]
+    return synth.from_torch(out), sel
+
+
+def check_decode(w, inp, n_prefill, n_total, with_gate=False, result=None):
+    got, sel_h = result if result is not None else run_decode(w, inp, n_prefill, n_total, with_gate=with_gate)
     kv_map = synth.kv_head_map(w)
     sub = {k: (v[:, :n_total] if k in ("q", "k", "v", "g") else v) for k, v in inp.items() if k != "heavy"}
     if not with_gate:
@@ -190,3 +229,73 @@ def test_decode_at_long_context_sampled_unit():
     err = float(np.max(np.abs(x - y) / (2e-2 + 2.0 ** -8 * np.abs(y))))
     print(f"[decode long] routed chunks {n_routed}, near-tie flips {mism}, bf16-bar-fraction {err:.3f}")
     assert np.all(np.isfinite(x)) and err <= 1.0
+
+
+@pytest.mark.parametrize("kw,n_total,offsets,tight", [
+    (dict(dtype="f32", d=64, C=64, W=64, B=3), 300, [0, 37, 100], True),
+    (dict(dtype="f32", d=64, C=64, W=64, B=3, lam=16, max_retained=24), 300, [64, 0, 1], False),
+    (dict(dtype="bf16", d=128, C=128, W=128, B=4, Hq=4, Hkv=2), 520, [0, 128, 5, 300], True),
+])
+def test_decode_sequences_at_their_own_positions(kw, n_total, offsets, tight):
+    """Continuous batching: every sequence of the batch is at a different token, routes its chunks at its own
+    steps, and some sequences sit steps out; each must still follow the oracle on its own tokens."""
+    w = wl("decat", **kw)
+    inp = synth.make_inputs(w, seed=24, n_tokens=n_total)
+    check_decode(w, inp, 0, n_total, result=run_decode_staggered(w, inp, n_total, offsets, tight_bound=tight))
+
+
+def test_decode_step_at_replays_from_a_hip_graph():
+    """One captured step, replayed for every token: the positions live on the device and are advanced there, the
+    token inputs are copied into the captured buffers.  Every replay must give the bits of the eager lock-step run
+    (same kernels, same launch shape: the bound passed at capture is the last position)."""
+    import torch
+
+    n_total = 200
+    w = wl("decgraph", dtype="bf16", d=128, C=64, W=64, B=2, Hq=4, Hkv=2)
+    inp = synth.make_inputs(w, seed=25, n_tokens=n_total)
+    dev = "cuda"
+    full = {k: synth.to_torch(inp[k], w.dtype, dev) for k in ("q", "k", "v", "Wq", "Wk")}
+    ps = S.make_params(B=w.B, N=1, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                       dtype=w.dtype, d_f=w.df, max_tokens=n_total)
+
+    def fresh_state():
+        st = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
+        S.still_state_init(ps, st)
+        return st
+
+    # eager reference with the same launch shape (t_max = n_total - 1 at every step)
+    state = fresh_state()
+    eager = torch.empty(w.B, n_total, w.Hq, w.d, dtype=full["q"].dtype, device=dev)
+    for t in range(n_total):
+        t_dev = torch.full((w.B,), t, dtype=torch.int32, device=dev)
+        ot = torch.empty(w.B, w.Hq, w.d, dtype=full["q"].dtype, device=dev)
+        S.still_hybrid_attn_decode_step_at(ps, state, t_dev, n_total - 1, full["q"][:, t].contiguous(),
+                                           full["k"][:, t].contiguous(), full["v"][:, t].contiguous(), None,
+                                           full["Wq"], None, full["Wk"], None, ot)
+        eager[:, t] = ot
+    torch.cuda.synchronize()
+
+    state = fresh_state()
+    t_dev = torch.zeros(w.B, dtype=torch.int32, device=dev)
+    qt, kt, vt = (full[n][:, 0].contiguous() for n in ("q", "k", "v"))
+    ot = torch.empty_like(qt)
+
+    def call():
+        S.still_hybrid_attn_decode_step_at(ps, state, t_dev, n_total - 1, qt, kt, vt, None, full["Wq"], None,
+                                           full["Wk"], None, ot, stream=torch.cuda.current_stream())
+
+    t_dev.fill_(-1)          # warm-up call in which every sequence sits out: the state stays empty
+    call()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    t_dev.fill_(0)
+    for t in range(n_total):
+        qt.copy_(full["q"][:, t]); kt.copy_(full["k"][:, t]); vt.copy_(full["v"][:, t])
+        ot.fill_(float("nan"))
+        graph.replay()
+        if t % 50 == 0:
+            torch.cuda.synchronize()       # the program's own synchronisations between replays
+        assert torch.equal(ot, eager[:, t]), f"replay for token {t} differs from the eager step"
+        t_dev.add_(1)
