@@ -35,7 +35,11 @@ Readings of the paper used here (each is listed with its reason in the design no
   - optional budget on the retained tokens (the long-context evaluations of Sec. 4 cap the
     number of selected tokens; the policy is not stated): chunks are served in order, chunk c
     keeps min(lambda, budget left) tokens, the rest of the chunk goes to the state like any
-    un-selected token.  Unused slots of an index list hold -1.
+    un-selected token.  Unused slots of an index list hold -1;
+  - optional group-shared selection (a variant, not the paper's method, which ranks per head
+    and never mentions grouped-query attention): the query heads that read one kv head rank
+    each chunk by the SUM of their scores and all keep the same tokens, so the retained keys
+    and values exist once per kv head.
 
 parity unpinned: the whole operator on random inputs at general lambda has no value
 printed in the paper; beyond the special cases above its correctness rests on the
@@ -154,6 +158,12 @@ def select_top_lambda(score: np.ndarray, C: int, lam: int, max_retained: Optiona
         sel[c, :quota] = np.sort(np.asarray(order[:quota], np.int64)) + c * C
         kept += quota
     return sel
+
+
+def group_rank_score(scores: np.ndarray) -> np.ndarray:
+    """Score that a group of query heads sharing one kv head ranks by: the sum of their Self-Saliency Scores.
+    scores [G, N] -> [N].  Feeding it to select_top_lambda gives the one index list all G heads use."""
+    return np.sum(np.asarray(scores, F64), axis=0)
 
 
 def selection_gaps(score: np.ndarray, C: int, lam: int, max_retained: Optional[int] = None) -> np.ndarray:
@@ -429,21 +439,36 @@ def still_chunkwise(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
 def still_forward_units(inputs: Dict[str, np.ndarray], kv_map: np.ndarray, units, C, W, lam, scale, eps,
                         form: str = "chunkwise", sel: Optional[np.ndarray] = None,
                         rows: Optional[Tuple[int, int]] = None,
-                        max_retained: Optional[int] = None) -> Dict[Tuple[int, int], Dict]:
+                        max_retained: Optional[int] = None,
+                        shared_selection: bool = False) -> Dict[Tuple[int, int], Dict]:
     """Run one form on the listed (b, hq) units of a batched problem.
 
     inputs: q [B,N,Hq,d], k,v [B,N,Hkv,d], Wq,Wk [Hq,d,d_f], optional g [B,N,Hq,d],
     optional bq,bk [Hq,d_f].  sel (optional) [B,Hq,N//C,lam] overrides the selection.
+    shared_selection: the heads that read one kv head rank by the sum of their scores and share one list.
+    Every result carries "rank_score": the score its selection was ranked by (its own, or the group's sum).
     """
     fn = {"chunkwise": still_chunkwise, "recurrent": still_recurrent, "definition": still_definition}[form]
     out = {}
+    group_cache: Dict[Tuple[int, int], np.ndarray] = {}
     for (b, h) in units:
         kh = int(kv_map[h])
+        rank = None
+        if shared_selection:
+            if (b, kh) not in group_cache:
+                members = [hh for hh in range(len(kv_map)) if int(kv_map[hh]) == kh]
+                group_cache[(b, kh)] = group_rank_score(np.stack([
+                    self_saliency_scores(np.asarray(inputs["q"][b, :, hh], F64), np.asarray(inputs["k"][b, :, kh], F64),
+                                         W, scale, eps) for hh in members]))
+            rank = group_cache[(b, kh)]
         g = inputs["g"][b, :, h] if inputs.get("g") is not None else None
         bq = inputs["bq"][h] if inputs.get("bq") is not None else None
         bk = inputs["bk"][h] if inputs.get("bk") is not None else None
         s_in = None if sel is None else sel[b, h]
+        if s_in is None and rank is not None:
+            s_in = select_top_lambda(rank, C, lam, max_retained)
         out[(b, h)] = fn(inputs["q"][b, :, h], inputs["k"][b, :, kh], inputs["v"][b, :, kh], g,
                          inputs["Wq"][h], inputs["Wk"][h], C, W, lam, scale, eps, bq=bq, bk=bk,
                          sel=s_in, rows=rows, max_retained=max_retained)
+        out[(b, h)]["rank_score"] = out[(b, h)]["score"] if rank is None else rank
     return out

@@ -436,3 +436,53 @@ def test_budget_with_whole_chunks_kept_is_attention_sink_plus_window_plus_linear
         w = (pk[lin] @ pq[t]) * np.exp(-logit.max())
         y = (zexp * (a @ v[sm]) + g[t] * (w @ v[lin])) / (zexp + w.sum())
         np.testing.assert_allclose(r["out"][t], y, rtol=1e-11, atol=1e-13)
+
+
+# --------------------------------------------------------------------------- group-shared selection (variant)
+def _gqa_inputs(seed, B, N, Hq, Hkv, d):
+    rng = np.random.default_rng(seed)
+    return {"q": rng.standard_normal((B, N, Hq, d)), "k": rng.standard_normal((B, N, Hkv, d)),
+            "v": rng.standard_normal((B, N, Hkv, d)), "Wq": rng.standard_normal((Hq, d, d)) / np.sqrt(d),
+            "Wk": rng.standard_normal((Hq, d, d)) / np.sqrt(d)}
+
+
+def test_group_shared_selection_ranks_by_the_summed_score_and_is_one_list_per_kv_head():
+    B, N, Hq, Hkv, d, C, lam = 2, 40, 6, 2, 4, 5, 2
+    inp = _gqa_inputs(19, B, N, Hq, Hkv, d)
+    kv_map = np.array([0, 1, 0, 1, 1, 0])                     # an irregular map: groups {0,2,5} and {1,3,4}
+    units = [(b, h) for b in range(B) for h in range(Hq)]
+    kw = dict(C=C, W=4, lam=lam, scale=0.5, eps=EPS)
+    own = O.still_forward_units(inp, kv_map, units, **kw)
+    shared = O.still_forward_units(inp, kv_map, units, shared_selection=True, **kw)
+    for b in range(B):
+        for kh in range(Hkv):
+            members = [h for h in range(Hq) if kv_map[h] == kh]
+            total = sum(own[(b, h)]["score"] for h in members)           # per-head scores are untouched
+            for h in members:
+                np.testing.assert_array_equal(shared[(b, h)]["score"], own[(b, h)]["score"])
+                np.testing.assert_allclose(shared[(b, h)]["rank_score"], total, rtol=1e-14)
+                np.testing.assert_array_equal(shared[(b, h)]["sel"], shared[(b, members[0])]["sel"])
+            # brute force: no other lam-subset of a chunk has a larger summed score
+            sel = shared[(b, members[0])]["sel"]
+            for c in range(N // C):
+                best = max(itertools.combinations(range(c * C, (c + 1) * C), lam), key=lambda s: total[list(s)].sum())
+                assert sorted(sel[c].tolist()) == sorted(best)
+    # the outputs are those of the per-head operator run with the shared lists
+    for (b, h) in units:
+        again = O.still_forward_units(inp, kv_map, [(b, h)],
+                                      sel=np.broadcast_to(shared[(b, h)]["sel"], (B, Hq) + shared[(b, h)]["sel"].shape),
+                                      **kw)[(b, h)]
+        np.testing.assert_array_equal(again["out"], shared[(b, h)]["out"])
+    assert any(not np.array_equal(own[u]["sel"], shared[u]["sel"]) for u in units)
+
+
+def test_group_shared_selection_with_one_head_per_group_is_the_per_head_operator():
+    inp = _gqa_inputs(20, 1, 48, 3, 3, 4)
+    kv_map = np.arange(3)
+    units = [(0, h) for h in range(3)]
+    kw = dict(C=8, W=5, lam=3, scale=0.5, eps=EPS, max_retained=7)
+    own = O.still_forward_units(inp, kv_map, units, **kw)
+    shared = O.still_forward_units(inp, kv_map, units, shared_selection=True, **kw)
+    for u in units:
+        np.testing.assert_array_equal(own[u]["sel"], shared[u]["sel"])
+        np.testing.assert_array_equal(own[u]["out"], shared[u]["out"])
