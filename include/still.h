@@ -73,6 +73,11 @@ typedef struct still_params {
                                     budget is used up) and the rest of the chunk goes to the linear state like
                                     any other un-selected token.  Slots of an index list that a chunk does not
                                     use hold -1.  A decode state then needs only max_retained retained rows. */
+  int32_t shared_selection;      /* 0: every query head ranks by its own score (the paper's method).
+                                    1: a variant for grouped-query attention, which the paper does not mention:
+                                    the query heads that read one kv head rank each chunk by the SUM of their
+                                    scores (added in ascending head order) and keep the same tokens; sel_idx
+                                    still has one list per query head, the lists of a group being equal.     */
   int64_t q_sb, q_st, q_sh;      /* q   [B, N, Hq,  d]                                                     */
   int64_t k_sb, k_st, k_sh;      /* k   [B, N, Hkv, d]                                                     */
   int64_t v_sb, v_st, v_sh;      /* v   [B, N, Hkv, d]                                                     */

@@ -25,7 +25,7 @@ class StillParams(ct.Structure):
         ("B", ct.c_int32), ("N", ct.c_int32), ("Hq", ct.c_int32), ("Hkv", ct.c_int32), ("d", ct.c_int32),
         ("d_f", ct.c_int32), ("C", ct.c_int32), ("W", ct.c_int32), ("lam", ct.c_int32),
         ("scale", ct.c_float), ("eps", ct.c_float), ("dtype", ct.c_int32), ("max_tokens", ct.c_int32),
-        ("max_retained", ct.c_int32),
+        ("max_retained", ct.c_int32), ("shared_selection", ct.c_int32),
         ("q_sb", ct.c_int64), ("q_st", ct.c_int64), ("q_sh", ct.c_int64),
         ("k_sb", ct.c_int64), ("k_st", ct.c_int64), ("k_sh", ct.c_int64),
         ("v_sb", ct.c_int64), ("v_st", ct.c_int64), ("v_sh", ct.c_int64),
@@ -110,7 +110,7 @@ def _strides(t):
 
 
 def make_params(*, B, N, Hq, Hkv, d, C, W, lam, scale, eps, dtype, d_f=None, q=None, k=None, v=None, out=None,
-                g=None, kv_head_of_q=None, max_tokens=0, max_retained=0) -> StillParams:
+                g=None, kv_head_of_q=None, max_tokens=0, max_retained=0, shared_selection=0) -> StillParams:
     """Fill a still_params_t; strides are taken from the torch tensors ([B, N, H, d])."""
     p = StillParams()
     p.B, p.N, p.Hq, p.Hkv, p.d, p.d_f = B, N, Hq, Hkv, d, (d_f or d)
@@ -118,6 +118,7 @@ def make_params(*, B, N, Hq, Hkv, d, C, W, lam, scale, eps, dtype, d_f=None, q=N
     p.dtype = DTYPE_CODE[dtype] if isinstance(dtype, str) else dtype
     p.max_tokens = max_tokens
     p.max_retained = max_retained
+    p.shared_selection = int(shared_selection)
     p.q_sb, p.q_st, p.q_sh = _strides(q)
     p.k_sb, p.k_st, p.k_sh = _strides(k)
     p.v_sb, p.v_st, p.v_sh = _strides(v)

@@ -306,11 +306,17 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   sa.N = N; sa.C = C; sa.W = p->W; sa.lam = p->lambda; sa.Hq = p->Hq; sa.ncf = ncf; sa.rcap = retained_budget(p);
   sa.scale = p->scale; sa.eps = p->eps;
   sa.score = score;
-  sa.sel = (have_sel && !sel_idx_is_input) ? sel : nullptr;
+  const bool group_sel = p->shared_selection != 0;
+  sa.sel = (have_sel && !sel_idx_is_input && !group_sel) ? sel : nullptr;
   const bool need_scores = !sel_idx_is_input || score_out != nullptr;
   if (need_scores) {
     if ((e = still::launch_score(sa, p->dtype, d, B, nc, stream)) != hipSuccess)
       return fail(STILL_ERR_HIP, "score_select: %s", hipGetErrorString(e));
+    if (have_sel && !sel_idx_is_input && group_sel) {
+      sa.sel = sel;
+      if ((e = still::launch_group_select(sa, B, p->Hkv, stream)) != hipSuccess)
+        return fail(STILL_ERR_HIP, "group_select: %s", hipGetErrorString(e));
+    }
     if (score_out != nullptr) {
       e = hipMemcpyAsync(score_out, score, (size_t)B * p->Hq * N * sizeof(float), hipMemcpyDeviceToDevice, stream);
       if (e != hipSuccess) return fail(STILL_ERR_HIP, "score copy: %s", hipGetErrorString(e));
@@ -505,7 +511,7 @@ still_status_t decode_step(const still_params_t* p, void* state, int32_t t, cons
   a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.C = p->C; a.W = p->W; a.lam = p->lambda;
   a.cap = L.cap; a.R = L.R; a.nchunks = L.n_chunks; a.t = t; a.rcap = retained_budget(p);
   a.scale = p->scale; a.eps = p->eps;
-  a.tpos = t_dev; a.max_tokens = p->max_tokens;
+  a.tpos = t_dev; a.max_tokens = p->max_tokens; a.shared = p->shared_selection != 0;
   const int c = t / p->C;
   const int rows = still::retained_rows(c >= 1 ? c - 1 : 0, p->lambda, a.rcap) + (t - (c >= 1 ? c - 1 : 0) * p->C + 1);
   int nsplit = (1024 + p->B * p->Hq - 1) / (p->B * p->Hq);

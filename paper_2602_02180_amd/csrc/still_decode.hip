@@ -152,7 +152,16 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr_all
   const T* kring = static_cast<const T*>(a.kring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)R * D;
   const T* vring = static_cast<const T*>(a.vring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)R * D;
 
-  if (tid < C) s_sc[tid] = a.score[unit * R + (cr * C + tid) % R];
+  if (tid < C) {
+    const int slot = (cr * C + tid) % R;
+    float s = a.score[unit * R + slot];
+    if (a.shared) {   // group-shared selection: rank by the sum over the heads of this kv head, ascending head order
+      s = 0.f;
+      for (int h = 0; h < a.Hq; ++h)
+        if (a.map.kv[h] == kvh) s += a.score[((int64_t)b * a.Hq + h) * R + slot];
+    }
+    s_sc[tid] = s;
+  }
   __syncthreads();
   bool chosen = false;
   if (tid < C) {

@@ -135,6 +135,7 @@ struct DecArgs {
   void* out;           // [B, Hq, d]
   HeadMap map;
   int B, Hq, Hkv, C, W, lam, cap, R, nchunks, t, nsplit, rcap;
+  int shared;              // 1: the query heads of one kv head rank by their summed score (one list per group)
   const int32_t* tpos;     // nullable, device [B]: index of each sequence's new token (t is then ignored)
   int max_tokens;
   float scale, eps;
@@ -168,6 +169,7 @@ hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hi
 hipError_t launch_state_fill(const StateFillArgs& a, int dtype, int B, int n_routed, hipStream_t stream);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
 hipError_t launch_score(const ScoreArgs& a, int dtype, int d, int B, int nc, hipStream_t stream);
+hipError_t launch_group_select(const ScoreArgs& a, int B, int Hkv, hipStream_t stream);
 hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStream_t stream);
 hipError_t launch_transpose_w(const TransposeWArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_gather(const GatherArgs& a, int dtype, int B, hipStream_t stream);

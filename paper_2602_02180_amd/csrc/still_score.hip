@@ -209,6 +209,47 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
   }
 }
 
+// Group-shared Top-lambda, a variant (the paper ranks per head and does not mention grouped-query attention): the
+// query heads that read one kv head rank a chunk by the sum of their Self-Saliency Scores, added in ascending head
+// order, and all receive the same list, so the retained keys and values could be kept once per kv head.
+// One workgroup of C threads per (full chunk, kv head, batch); reads the scores the score kernel has written.
+__global__ __launch_bounds__(128) void group_select_kernel(ScoreArgs a) {
+  __shared__ float s_sum[128];
+  __shared__ unsigned long long s_ball[2];
+  const int c = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int C = a.C, i = threadIdx.x, lane = i & 63, wave = i >> 6;
+  float s = 0.f;
+  for (int h = 0; h < a.Hq; ++h)
+    if (a.map.kv[h] == kvh) s += a.score[((int64_t)b * a.Hq + h) * a.N + c * C + i];
+  s_sum[i] = s;
+  __syncthreads();
+  int rank = 0;
+#pragma unroll 4
+  for (int j = 0; j < C; ++j) {
+    const float sj = s_sum[j];
+    rank += (sj > s || (sj == s && j < i)) ? 1 : 0;
+  }
+  const int quota = chunk_quota(c, a.lam, a.rcap);
+  const bool chosen = rank < quota;
+  const unsigned long long bal = __ballot(chosen);
+  if (lane == 0) s_ball[wave] = bal;
+  __syncthreads();
+  int pos = __popcll(bal & ((1ull << lane) - 1ull));
+  if (wave == 1) pos += __popcll(s_ball[0]);
+  for (int h = 0; h < a.Hq; ++h) {
+    if (a.map.kv[h] != kvh) continue;
+    int32_t* selc = a.sel + (((int64_t)b * a.Hq + h) * a.ncf + c) * a.lam;
+    if (chosen && pos < quota) selc[pos] = c * C + i;
+    if (i >= quota && i < a.lam) selc[i] = -1;
+  }
+}
+
+hipError_t launch_group_select(const ScoreArgs& a, int B, int Hkv, hipStream_t stream) {
+  if (a.ncf <= 0 || a.sel == nullptr) return hipSuccess;
+  hipLaunchKernelGGL(group_select_kernel, dim3(a.ncf, Hkv, B), dim3(a.C), 0, stream, a);
+  return hipGetLastError();
+}
+
 template <typename T, int D>
 static hipError_t launch_score_t(const ScoreArgs& a, int B, int nc, hipStream_t stream) {
   dim3 grid(nc * a.Hq, 1, B), block((a.C / 32) * 64);

@@ -39,6 +39,7 @@ class Workload:
     eps: float = 1e-6
     decode_steps: int = 0
     max_retained: int = 0     # budget on the retained tokens per (sequence, head); 0 => none
+    shared_selection: bool = False   # variant: the heads of one kv head rank by their summed score
 
     @property
     def df(self) -> int:

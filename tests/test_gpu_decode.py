@@ -26,7 +26,7 @@ def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False):
     B = w.B
     out = torch.full((B, n_total, w.Hq, w.d), float("nan"), dtype=full["q"].dtype, device=dev)
     base = dict(B=B, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype=w.dtype,
-                d_f=w.df, kv_head_of_q=kv_map, max_tokens=n_total, max_retained=w.max_retained)
+                d_f=w.df, kv_head_of_q=kv_map, max_tokens=n_total, max_retained=w.max_retained, shared_selection=w.shared_selection)
     ps = S.make_params(N=1, **base)
     state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
     S.still_state_init(ps, state)
@@ -65,7 +65,7 @@ def run_decode_staggered(w, inp, n_total, offsets, tight_bound=True):
     B = w.B
     out = torch.full((B, n_total, w.Hq, w.d), float("nan"), dtype=full["q"].dtype, device=dev)
     ps = S.make_params(B=B, N=1, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                       dtype=w.dtype, d_f=w.df, max_tokens=n_total, max_retained=w.max_retained)
+                       dtype=w.dtype, d_f=w.df, max_tokens=n_total, max_retained=w.max_retained, shared_selection=w.shared_selection)
     state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
     S.still_state_init(ps, state)
     ar = torch.arange(B, device=dev)
@@ -104,12 +104,12 @@ def check_decode(w, inp, n_prefill, n_total, with_gate=False, result=None):
     for b in range(w.B):
         for h in range(w.Hq):
             own = O.still_forward_units(sub, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                                        max_retained=U.budget(w))[(b, h)]
+                                        max_retained=U.budget(w), shared_selection=w.shared_selection)[(b, h)]
             n_routed = sel_h.shape[2]
             ncf = n_total // w.C
             sel_full = own["sel"].copy()
             # routed chunks: the HIP path's choice must be the oracle's wherever the gap is clear
-            gaps = O.selection_gaps(own["score"], w.C, w.lam, U.budget(w))
+            gaps = O.selection_gaps(own["rank_score"], w.C, w.lam, U.budget(w))
             for c in range(n_routed):
                 if gaps[c] > 1e-5:
                     assert np.array_equal(sel_h[b, h, c], own["sel"][c]), (b, h, c)
@@ -168,12 +168,28 @@ def test_decode_continues_prefill(kw, n_prefill, n_total):
     (dict(dtype="bf16", d=128, C=128, W=128, lam=16, max_retained=24, Hq=4, Hkv=2), 700, 1100),  # full at prefill
 ])
 def test_decode_with_retained_budget(kw, n_prefill, n_total):
+    _decode_with_retained_budget(kw, n_prefill, n_total)
+
+
+@pytest.mark.parametrize("kw,n_prefill,n_total", [
+    (dict(dtype="f32", d=64, C=64, W=64, Hq=4, Hkv=2), 0, 330),
+    (dict(dtype="f32", d=64, C=64, W=64, Hq=4, Hkv=2, max_retained=40), 200, 460),
+    (dict(dtype="bf16", d=128, C=128, W=128, Hq=8, Hkv=2, B=2), 700, 1000),
+])
+def test_decode_with_group_shared_selection(kw, n_prefill, n_total):
+    """Variant: one list per kv head, ranked by the summed score of its query heads, in prefill and decode alike."""
+    w = wl("decs", shared_selection=True, **kw)
+    inp = synth.make_inputs(w, seed=26, n_tokens=n_total)
+    check_decode(w, inp, n_prefill, n_total)
+
+
+def _decode_with_retained_budget(kw, n_prefill, n_total):
     """The state's retained rows stop growing at the budget; outputs keep following the oracle."""
     w = wl("decb", **kw)
     inp = synth.make_inputs(w, seed=23, n_tokens=n_total)
     check_decode(w, inp, n_prefill, n_total)
     p = S.make_params(B=w.B, N=1, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                      dtype=w.dtype, max_tokens=1 << 20, max_retained=w.max_retained)
+                      dtype=w.dtype, max_tokens=1 << 20, max_retained=w.max_retained, shared_selection=w.shared_selection)
     assert S.still_state_layout(p).cap <= (w.max_retained + 63) // 64 * 64 + 64
 
 
@@ -211,7 +227,7 @@ def test_decode_at_long_context_sampled_unit():
     b, h = 1, 21
     own = O.still_forward_units(inp, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
                                 rows=(n_prefill, n_total))[(b, h)]
-    gaps = O.selection_gaps(own["score"], w.C, w.lam, U.budget(w))
+    gaps = O.selection_gaps(own["rank_score"], w.C, w.lam, U.budget(w))
     n_routed = sel_h.shape[2]
     sel_full = own["sel"].copy()
     mism = 0

@@ -77,10 +77,10 @@ def check_scores_and_selection(w, hip, ref_units, units, what):
         ref = ref_units[(b, h)]
         err = float(np.max(np.abs(hip["score"][b, h] - ref["score"])))
         worst = max(worst, err)
-        n, clear, bad, tie = U.selection_report(ref["score"], ref["sel"], hip["sel"][b, h], w.C, w.lam,
+        n, clear, bad, tie = U.selection_report(ref["rank_score"], ref["sel"], hip["sel"][b, h], w.C, w.lam,
                                                 max_retained=U.budget(w))
         stot, sclear, sbad, stie = stot + n, sclear + clear, sbad + bad, stie + tie
-        assert U.selection_is_valid(ref["score"], hip["sel"][b, h], w.C, tol=1e-4, max_retained=U.budget(w)), \
+        assert U.selection_is_valid(ref["rank_score"], hip["sel"][b, h], w.C, tol=1e-4, max_retained=U.budget(w)), \
             f"unit {(b, h)}: not a top set"
     print(f"[{w.name}:{what}] score max-abs err {worst:.3e}; chunks {stot}, clear-gap {sclear}, "
           f"mismatch on clear {sbad}, mismatch on near-ties {stie} "
@@ -156,6 +156,22 @@ def test_retained_budget(kw):
     hip = run_case(w, synth.make_inputs(w, seed=4321))
     kept = (hip["sel"] >= 0).sum(axis=(2, 3))
     assert np.all(kept == min(w.max_retained, w.lam * (w.N // w.C)))
+
+
+# variant: the query heads of one kv head rank by their summed score and share one list
+@pytest.mark.parametrize("kw,kv_map", [
+    (dict(dtype="f32", d=64, C=64, W=64, N=700, Hq=4, Hkv=2), None),
+    (dict(dtype="f32", d=64, C=128, W=100, N=900, Hq=6, Hkv=2, lam=20, max_retained=50), [0, 1, 0, 1, 1, 0]),
+    (dict(dtype="bf16", d=128, C=128, W=128, N=1300, Hq=8, Hkv=2, B=2), None),
+], ids=["f32-regular", "f32-irregular-map-budget", "bf16-groups-of-4"])
+def test_group_shared_selection(kw, kv_map):
+    w = small("shared", shared_selection=True, **kw)
+    kv = None if kv_map is None else np.asarray(kv_map, np.int32)
+    hip = run_case(w, synth.make_inputs(w, seed=555), kv_map=kv)
+    kv = synth.kv_head_map(w) if kv is None else kv
+    for h in range(w.Hq):
+        first = int(np.nonzero(kv == kv[h])[0][0])
+        assert np.array_equal(hip["sel"][:, h], hip["sel"][:, first]), "lists of one group differ"
 
 
 @pytest.mark.parametrize("lam", [0, 1, 64])
