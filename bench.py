@@ -81,7 +81,8 @@ def cpu_baseline(w: synth.Workload, inp, budget_s: float = 20.0):
     order = [(b, h) for h in range(w.Hq) for b in range(w.B)]
     for (b, h) in order:
         O.still_forward_units(inp, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                              max_retained=w.max_retained if w.max_retained > 0 else None)
+                              max_retained=w.max_retained if w.max_retained > 0 else None,
+                              shared_selection=w.shared_selection)
         units_done += 1
         if time.perf_counter() - t0 > budget_s:
             break
@@ -95,7 +96,8 @@ def cpu_baseline(w: synth.Workload, inp, budget_s: float = 20.0):
 
 
 def budget_tag(w: synth.Workload) -> str:
-    return f" max_retained={w.max_retained}" if w.max_retained > 0 else ""
+    return (f" max_retained={w.max_retained}" if w.max_retained > 0 else "") + \
+        (" shared_selection" if w.shared_selection else "")
 
 
 def decode_bench(args) -> int:
@@ -105,7 +107,7 @@ def decode_bench(args) -> int:
     import torch
     from paper_2602_02180_amd import binding as S
 
-    w = synth.workload("c5", max_retained=args.max_retained)
+    w = synth.workload("c5", max_retained=args.max_retained, shared_selection=args.shared_selection)
     dev = "cuda"
     gen = torch.Generator(device=dev)
     gen.manual_seed(w.seed)
@@ -121,7 +123,7 @@ def decode_bench(args) -> int:
     Wq = (torch.randn(Hq, d, d, generator=gen, device=dev) / d ** 0.5).to(bf)
     Wk = (torch.randn(Hq, d, d, generator=gen, device=dev) / d ** 0.5).to(bf)
     base = dict(B=B, Hq=Hq, Hkv=Hkv, d=d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype="bf16",
-                max_tokens=max_tokens, max_retained=w.max_retained)
+                max_tokens=max_tokens, max_retained=w.max_retained, shared_selection=w.shared_selection)
     ps = S.make_params(N=1, **base)
     L = S.still_state_layout(ps)
     state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
@@ -131,7 +133,8 @@ def decode_bench(args) -> int:
     pslice = S.make_params(N=1, **{**base, "B": SB})
     Ls = S.still_state_layout(pslice)
     st_slice = torch.empty(S.still_state_bytes(pslice), dtype=torch.uint8, device=dev)
-    regions = [("S", 4 * 2 * d * (d + 1) * Hq), ("kret", 2 * L.cap * d * Hq), ("vret", 2 * L.cap * d * Hq),
+    slices = Hkv if w.shared_selection else Hq      # retained rows: per query head, or once per kv head
+    regions = [("S", 4 * 2 * d * (d + 1) * Hq), ("kret", 2 * L.cap * d * slices), ("vret", 2 * L.cap * d * slices),
                ("sel", 4 * L.n_chunks * w.lam * Hq), ("kring", 2 * L.R * d * Hkv), ("vring", 2 * L.R * d * Hkv),
                ("score", 4 * L.R * Hq), ("part", 4 * 32 * (d + 2) * Hq)]
     t_prefill = 0.0
@@ -185,7 +188,7 @@ def decode_bench(args) -> int:
     c = (N + args.warmup) // w.C
     n_ret = (c - 1) * w.lam if w.max_retained <= 0 else min((c - 1) * w.lam, w.max_retained)
     rows = n_ret + (N + args.warmup - (c - 1) * w.C + 1)
-    bytes_step = B * Hq * (rows * 2 * d * 2 + (2 * d * (d + 1)) * 4)
+    bytes_step = B * (slices * rows * 2 * d * 2 + Hq * (2 * d * (d + 1)) * 4)
     ordinary = float(np.median(lat[~routing])) if (~routing).any() else float("nan")
     rec = {
         "metric": "hybrid-attn decode tokens/s @32K context, Llama-3-8B layer shape", "value": B * n_steps / el,
@@ -211,6 +214,9 @@ def main() -> int:
     ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--max-retained", type=int, default=0,
                     help="budget on the retained tokens per (sequence, head); 0 (default) = none, the headline workload")
+    ap.add_argument("--shared-selection", action="store_true",
+                    help="variant: the query heads of one kv head rank by their summed score and share one retained "
+                         "set (not the paper's method; side figures only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc runs)")
@@ -244,7 +250,7 @@ def main() -> int:
         return decode_bench(args)
     if not args.steps:
         args.steps = 20
-    w = synth.workload(args.config, max_retained=args.max_retained)
+    w = synth.workload(args.config, max_retained=args.max_retained, shared_selection=args.shared_selection)
     inp = synth.make_inputs(w)
     dev = "cuda"
     q, k, v = (synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v"))
@@ -252,7 +258,8 @@ def main() -> int:
     out = torch.empty_like(q)
     N = w.N
     p = S.make_params(B=w.B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, max_retained=w.max_retained)
+                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, max_retained=w.max_retained,
+                      shared_selection=w.shared_selection)
     ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
@@ -292,7 +299,7 @@ def main() -> int:
     roofline = {"bound": "mfma", "kernel": dom, "achieved": flops / dom_s / 1e12, "peak": peak / 1e12,
                 "unit": "TFLOP/s", "frac": flops / dom_s / peak,
                 "traffic": args.traffic_bytes if args.traffic_bytes is not None else
-                (MEASURED_TRAFFIC.get(args.config) if w.max_retained <= 0 else None),
+                (MEASURED_TRAFFIC.get(args.config) if w.max_retained <= 0 and not w.shared_selection else None),
                 "algorithmic_flops_per_launch": flops, "avg_launch_ms": dom_ms}
     rec = {
         "metric": "hybrid-attn fwd tokens/s @32K, Llama-3-8B layer shape" if args.config == "c4"

@@ -77,7 +77,9 @@ typedef struct still_params {
                                     1: a variant for grouped-query attention, which the paper does not mention:
                                     the query heads that read one kv head rank each chunk by the SUM of their
                                     scores (added in ascending head order) and keep the same tokens; sel_idx
-                                    still has one list per query head, the lists of a group being equal.     */
+                                    still has one list per query head, the lists of a group being equal.  A
+                                    decode state then holds the retained rows once per kv head, and a decode
+                                    step reads each of them once for the whole group.                        */
   int64_t q_sb, q_st, q_sh;      /* q   [B, N, Hq,  d]                                                     */
   int64_t k_sb, k_st, k_sh;      /* k   [B, N, Hkv, d]                                                     */
   int64_t v_sb, v_st, v_sh;      /* v   [B, N, Hkv, d]                                                     */
@@ -177,7 +179,7 @@ STILL_API const char* still_profile_kernel_name(int32_t i);
  * cache-routing equation (Sec. 3.3), plus the ring of recent tokens that delayed selection needs.  One
  * opaque caller-owned device buffer of still_state_bytes(p) bytes (p->max_tokens = capacity per sequence):
  *   S    float [B, Hq, 2*d_f*(d+1)]   state through the last routed chunk: S (2*d_f x d) then z (2*d_f)
- *   Kret dtype [B, Hq, cap, d]        retained keys in routing order, cap = lambda*ceil(max_tokens/C), or
+ *   Kret dtype [B, Hq, cap, d]        ([B, Hkv, cap, d] with shared_selection) retained keys in routing order, cap = lambda*ceil(max_tokens/C), or
  *                                     max_retained if that is smaller (+pad)
  *   Vret dtype [B, Hq, cap, d]        retained values
  *   sel  int32 [B, Hq, ceil(max_tokens/C), lambda]   token indices kept per routed chunk, -1 in unused slots

@@ -199,9 +199,10 @@ void compute_state_layout(const still_params_t* p, still_state_layout_t* L) {
     off = align_up(off + (bytes ? bytes : 16), 256);
     return o;
   };
+  const int64_t slices = p->shared_selection ? Hkv : Hq;   // group-shared selection: retained rows once per kv head
   L->S = take((size_t)B * Hq * (2 * df * (d + 1)) * 4);
-  L->kret = take((size_t)B * Hq * cap * d * es);
-  L->vret = take((size_t)B * Hq * cap * d * es);
+  L->kret = take((size_t)B * slices * cap * d * es);
+  L->vret = take((size_t)B * slices * cap * d * es);
   L->sel = take((size_t)B * Hq * nch * p->lambda * 4);
   L->kring = take((size_t)B * Hkv * R * d * es);
   L->vring = take((size_t)B * Hkv * R * d * es);
@@ -408,6 +409,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
     sf.score_ring = reinterpret_cast<float*>(stp + SL.score);
     sf.N = N; sf.R = SL.R; sf.Hq = p->Hq; sf.Hkv = p->Hkv; sf.d = d; sf.lam = have_sel ? p->lambda : 0;
     sf.cap = SL.cap; sf.ncf = ncf; sf.nchunks = SL.n_chunks; sf.rcap = retained_budget(p);
+    sf.shared = p->shared_selection != 0;
     const int n_routed = nc >= 2 ? nc - 2 : 0;
     if (!need_scores) return fail(STILL_ERR_INVALID_ARG, "state_out needs the scores: do not combine it with sel_idx_is_input unless score_out is given");
     if ((e = still::launch_state_fill(sf, p->dtype, B, n_routed, stream)) != hipSuccess)
@@ -514,7 +516,8 @@ still_status_t decode_step(const still_params_t* p, void* state, int32_t t, cons
   a.tpos = t_dev; a.max_tokens = p->max_tokens; a.shared = p->shared_selection != 0;
   const int c = t / p->C;
   const int rows = still::retained_rows(c >= 1 ? c - 1 : 0, p->lambda, a.rcap) + (t - (c >= 1 ? c - 1 : 0) * p->C + 1);
-  int nsplit = (1024 + p->B * p->Hq - 1) / (p->B * p->Hq);
+  const int units = p->B * (p->shared_selection ? p->Hkv : p->Hq);   // workgroups per split
+  int nsplit = (1024 + units - 1) / units;
   if (nsplit > 32) nsplit = 32;
   if (nsplit > (rows + 63) / 64) nsplit = (rows + 63) / 64;
   if (nsplit < 1) nsplit = 1;

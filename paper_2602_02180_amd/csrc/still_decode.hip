@@ -186,9 +186,10 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr_all
   if (tid >= quota && tid < lam) a.sel[(unit * a.nchunks + cr) * lam + tid] = -1;
   __syncthreads();
   // selected rows -> retained cache (rows cr*lam ..)
-  {
-    T* kret = static_cast<T*>(a.kret) + (unit * a.cap + (int64_t)cr * lam) * D;
-    T* vret = static_cast<T*>(a.vret) + (unit * a.cap + (int64_t)cr * lam) * D;
+  if (writes_retained(a.shared != 0, a.map, hq)) {
+    const int64_t slice = retained_slice(a.shared != 0, b, hq, kvh, a.Hq, a.Hkv);
+    T* kret = static_cast<T*>(a.kret) + (slice * a.cap + (int64_t)cr * lam) * D;
+    T* vret = static_cast<T*>(a.vret) + (slice * a.cap + (int64_t)cr * lam) * D;
     for (int idx = tid; idx < quota * D; idx += 256) {
       const int row = idx / D, x = idx % D;
       const int slot = (cr * C + s_list[row]) % R;
@@ -349,8 +350,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const int r_beg = split * per;
   const int r_end = r_beg + per < nr ? r_beg + per : nr;
 
-  const T* kret = static_cast<const T*>(a.kret) + unit * (int64_t)a.cap * D;
-  const T* vret = static_cast<const T*>(a.vret) + unit * (int64_t)a.cap * D;
+  const int64_t slice = retained_slice(a.shared != 0, b, hq, kvh, a.Hq, a.Hkv);
+  const T* kret = static_cast<const T*>(a.kret) + slice * (int64_t)a.cap * D;
+  const T* vret = static_cast<const T*>(a.vret) + slice * (int64_t)a.cap * D;
   const T* kring = static_cast<const T*>(a.kring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)a.R * D;
   const T* vring = static_cast<const T*>(a.vring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)a.R * D;
 
@@ -419,6 +421,129 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     }
     part[0] = M;
     part[1] = L;
+  }
+}
+
+// ---------------------------------------------------------------- the same, group-shared selection
+// With one retained set per kv head, the query heads of a group attend to the same rows: one workgroup per
+// (split, kv head, sequence) reads every key/value row once and serves up to GH query heads from it (a larger
+// group takes another pass over the rows).  Partials are written per query head, as above.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_attend_shared_kernel(DecArgs a) {
+  constexpr int GH = 4;
+  constexpr int EPV = 16 / sizeof(T);
+  constexpr int LPR = D / EPV;        // lanes per row
+  constexpr int RPW = 64 / LPR;       // rows per wave step
+  constexpr int NG = 4 * RPW;         // row groups per block
+  __shared__ float s_m[GH][NG], s_l[GH][NG], s_acc[GH][NG][D];
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int sub = lane % LPR, grp = lane / LPR;
+  const int t = step_index(a, b);
+  if (t < 0) return;
+  const int c = t / a.C;
+  const int n_ret = retained_rows(c >= 1 ? c - 1 : 0, a.lam, a.rcap);
+  const int lo = (c >= 1 ? c - 1 : 0) * a.C;
+  const int nr = n_ret + (t - lo + 1);
+  int per = (nr + a.nsplit - 1) / a.nsplit;
+  per = (per + NG - 1) / NG * NG;
+  const int r_beg = split * per;
+  const int r_end = r_beg + per < nr ? r_beg + per : nr;
+  const int64_t slice = (int64_t)b * a.Hkv + kvh;
+  const T* kret = static_cast<const T*>(a.kret) + slice * (int64_t)a.cap * D;
+  const T* vret = static_cast<const T*>(a.vret) + slice * (int64_t)a.cap * D;
+  const T* kring = static_cast<const T*>(a.kring) + slice * (int64_t)a.R * D;
+  const T* vring = static_cast<const T*>(a.vring) + slice * (int64_t)a.R * D;
+  const float sc2 = a.scale * kLog2e;
+
+  int h_next = 0;
+  while (h_next < a.Hq) {
+    int heads[GH];   // the next (up to GH) query heads of this kv head, ascending; -1 = none left
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      while (h_next < a.Hq && a.map.kv[h_next] != kvh) ++h_next;
+      heads[g] = h_next < a.Hq ? h_next++ : -1;
+    }
+    if (heads[0] < 0) break;
+    float qv[GH][EPV], m2[GH], l[GH], acc[GH][EPV];
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      load16<T>(static_cast<const T*>(a.q) + ((int64_t)b * a.Hq + (heads[g] >= 0 ? heads[g] : heads[0])) * D + sub * EPV, qv[g]);
+      m2[g] = -INFINITY;
+      l[g] = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) acc[g][e] = 0.f;
+    }
+    for (int r0 = r_beg + wave * RPW; r0 < r_end; r0 += NG) {
+      const int row = r0 + grp;
+      const bool valid = row < r_end;
+      const T *kp, *vp;
+      if (row < n_ret || !valid) {
+        const int rr = valid ? row : 0;
+        kp = kret + (int64_t)rr * D;
+        vp = vret + (int64_t)rr * D;
+      } else {
+        const int slot = (lo + (row - n_ret)) % a.R;
+        kp = kring + (int64_t)slot * D;
+        vp = vring + (int64_t)slot * D;
+      }
+      float kv[EPV], vv[EPV];
+      load16<T>(kp + sub * EPV, kv);
+      load16<T>(vp + sub * EPV, vv);
+#pragma unroll
+      for (int g = 0; g < GH; ++g) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) dot = fmaf(qv[g][e], kv[e], dot);
+#pragma unroll
+        for (int o = LPR / 2; o >= 1; o >>= 1) dot += __shfl_xor(dot, o, 64);
+        const float x2 = valid ? dot * sc2 : -INFINITY;
+        const float m_new = fmaxf(m2[g], x2);
+        const float m_sub = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = fast_exp2(m2[g] - m_sub);
+        const float pv = fast_exp2(x2 - m_sub);
+        l[g] = l[g] * alpha + pv;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) acc[g][e] = fmaf(pv, vv[e], acc[g][e] * alpha);
+        m2[g] = m_new;
+      }
+    }
+    const int gidx = wave * RPW + grp;
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      if (sub == 0) {
+        s_m[g][gidx] = m2[g];
+        s_l[g][gidx] = l[g];
+      }
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) s_acc[g][gidx][sub * EPV + e] = acc[g][e];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      if (heads[g] < 0) continue;
+      float M = -INFINITY;
+      for (int gi = 0; gi < NG; ++gi) M = fmaxf(M, s_m[g][gi]);
+      float* part = a.part + (((int64_t)b * a.Hq + heads[g]) * 32 + split) * (int64_t)(D + 2);
+      if (tid < D) {
+        float av = 0.f;
+        for (int gi = 0; gi < NG; ++gi) {
+          const float w = s_m[g][gi] == -INFINITY ? 0.f : fast_exp2(s_m[g][gi] - M);
+          av = fmaf(w, s_acc[g][gi][tid], av);
+        }
+        part[2 + tid] = av;
+      }
+      if (tid == 128 + g) {
+        float L = 0.f;
+        for (int gi = 0; gi < NG; ++gi) {
+          const float w = s_m[g][gi] == -INFINITY ? 0.f : fast_exp2(s_m[g][gi] - M);
+          L = fmaf(w, s_l[g][gi], L);
+        }
+        part[0] = M;
+        part[1] = L;
+      }
+    }
+    __syncthreads();   // the partial tables are reused by the next pass
   }
 }
 
@@ -550,12 +675,13 @@ __global__ void state_fill_retained_kernel(StateFillArgs a) {
   int tok = a.sel[(unit * a.ncf + cr) * a.lam + pos];
   const bool used = pos < chunk_quota(cr, a.lam, a.rcap);   // the budget on retained tokens leaves later slots empty
   if (threadIdx.x == 0) a.sel_state[(unit * a.nchunks + cr) * a.lam + pos] = used ? tok : -1;
-  if (!used) return;
+  if (!used || !writes_retained(a.shared != 0, a.map, hq)) return;
   if (tok < 0 || tok >= a.N) tok = 0;
   const T* k = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)tok * a.k_st + (int64_t)kvh * a.k_sh;
   const T* v = static_cast<const T*>(a.v) + (int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)kvh * a.v_sh;
-  T* kr = static_cast<T*>(a.kret) + (unit * a.cap + row) * a.d;
-  T* vr = static_cast<T*>(a.vret) + (unit * a.cap + row) * a.d;
+  const int64_t slice = retained_slice(a.shared != 0, b, hq, kvh, a.Hq, a.Hkv);
+  T* kr = static_cast<T*>(a.kret) + (slice * a.cap + row) * a.d;
+  T* vr = static_cast<T*>(a.vret) + (slice * a.cap + row) * a.d;
   for (int x = threadIdx.x; x < a.d; x += blockDim.x) {
     kr[x] = k[x];
     vr[x] = v[x];
@@ -583,7 +709,12 @@ hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hi
     STILL_DISPATCH(dtype, d, CALL_ROUTE)
   }
 #define CALL_ATT(TT, DD) hipLaunchKernelGGL((decode_attend_kernel<TT, DD>), dim3(a.nsplit, a.Hq, a.B), dim3(256), 0, stream, a);
-  STILL_DISPATCH(dtype, d, CALL_ATT)
+#define CALL_ATT_SHARED(TT, DD) hipLaunchKernelGGL((decode_attend_shared_kernel<TT, DD>), dim3(a.nsplit, a.Hkv, a.B), dim3(256), 0, stream, a);
+  if (a.shared) {
+    STILL_DISPATCH(dtype, d, CALL_ATT_SHARED)
+  } else {
+    STILL_DISPATCH(dtype, d, CALL_ATT)
+  }
 #define CALL_FIN(TT, DD) hipLaunchKernelGGL((decode_finish_kernel<TT, DD>), dim3(a.Hq, a.B), dim3(256), 0, stream, a);
   STILL_DISPATCH(dtype, d, CALL_FIN)
   return hipGetLastError();

@@ -149,6 +149,18 @@ __device__ inline int step_index(const DecArgs& a, int b) {
   return (t >= 0 && t < a.max_tokens) ? t : -1;
 }
 
+// Retained rows of a decode state: one slice per (sequence, query head), or, with group-shared selection, one per
+// (sequence, kv head), written by the lowest query head of the group only.
+__device__ inline int64_t retained_slice(bool shared, int b, int hq, int kvh, int Hq, int Hkv) {
+  return shared ? (int64_t)b * Hkv + kvh : (int64_t)b * Hq + hq;
+}
+__device__ inline bool writes_retained(bool shared, const HeadMap& map, int hq) {
+  if (!shared) return true;
+  for (int h = 0; h < hq; ++h)
+    if (map.kv[h] == map.kv[hq]) return false;
+  return true;
+}
+
 struct StateFillArgs {
   const void* k;
   const void* v;
@@ -162,7 +174,7 @@ struct StateFillArgs {
   void* kring;
   void* vring;
   float* score_ring;
-  int N, R, Hq, Hkv, d, lam, cap, ncf, nchunks, rcap;
+  int N, R, Hq, Hkv, d, lam, cap, ncf, nchunks, rcap, shared;
 };
 
 hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hipStream_t stream);
