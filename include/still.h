@@ -86,6 +86,15 @@ typedef struct still_params {
   int64_t o_sb, o_st, o_sh;      /* out [B, N, Hq,  d]                                                     */
   int64_t g_sb, g_st, g_sh;      /* g   [B, N, Hq,  d] (ignored when g == NULL)                            */
   const int32_t* kv_head_of_q;   /* HOST, Hq entries in [0,Hkv), or NULL => hq / (Hq / Hkv)                */
+  const int32_t* seq_len;        /* DEVICE, B entries, or NULL: prefill of a right-padded batch.  Sequence b has
+                                    seq_len[b] tokens (clamped to [1, N]); its rows t >= seq_len[b] are padding:
+                                    their q, k, v are never read as part of a real row's result (they may hold
+                                    anything), their rows of out are not written, and their entries of score_out
+                                    and sel_idx are unspecified.  Rows t < seq_len[b] get exactly the result of a
+                                    call with that sequence alone (the operator is causal), and state_out holds,
+                                    for every sequence, the state after ITS last token, so decoding continues
+                                    with still_hybrid_attn_decode_step_at at t_dev[b] = seq_len[b].  Ignored by
+                                    the decode functions.                                                     */
 } still_params_t;
 
 /* Byte offsets of the regions still_hybrid_attn_fwd lays out inside its workspace (for tests/tools). */

@@ -32,6 +32,7 @@ class StillParams(ct.Structure):
         ("o_sb", ct.c_int64), ("o_st", ct.c_int64), ("o_sh", ct.c_int64),
         ("g_sb", ct.c_int64), ("g_st", ct.c_int64), ("g_sh", ct.c_int64),
         ("kv_head_of_q", ct.POINTER(ct.c_int32)),
+        ("seq_len", ct.c_void_p),
     ]
 
 
@@ -110,7 +111,7 @@ def _strides(t):
 
 
 def make_params(*, B, N, Hq, Hkv, d, C, W, lam, scale, eps, dtype, d_f=None, q=None, k=None, v=None, out=None,
-                g=None, kv_head_of_q=None, max_tokens=0, max_retained=0, shared_selection=0) -> StillParams:
+                g=None, kv_head_of_q=None, max_tokens=0, max_retained=0, shared_selection=0, seq_len=None) -> StillParams:
     """Fill a still_params_t; strides are taken from the torch tensors ([B, N, H, d])."""
     p = StillParams()
     p.B, p.N, p.Hq, p.Hkv, p.d, p.d_f = B, N, Hq, Hkv, d, (d_f or d)
@@ -119,6 +120,10 @@ def make_params(*, B, N, Hq, Hkv, d, C, W, lam, scale, eps, dtype, d_f=None, q=N
     p.max_tokens = max_tokens
     p.max_retained = max_retained
     p.shared_selection = int(shared_selection)
+    if seq_len is not None:   # int32 device tensor [B]; kept alive by the params object
+        assert seq_len.is_cuda and seq_len.is_contiguous() and seq_len.numel() == B and str(seq_len.dtype) == "torch.int32"
+        p._seq_len_keepalive = seq_len
+        p.seq_len = seq_len.data_ptr()
     p.q_sb, p.q_st, p.q_sh = _strides(q)
     p.k_sb, p.k_st, p.k_sh = _strides(k)
     p.v_sb, p.v_st, p.v_sh = _strides(v)

@@ -250,6 +250,8 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   const void* ptrs[] = {q, k, v, g, Wq, bq, Wk, bk, out, score_out, sel_idx, workspace};
   for (const void* x : ptrs)
     if (x != nullptr && !aligned16(x)) return fail(STILL_ERR_INVALID_ARG, "pointer %p is not 16-byte aligned", x);
+  if (p->seq_len != nullptr && (reinterpret_cast<uintptr_t>(p->seq_len) & 3) != 0)
+    return fail(STILL_ERR_INVALID_ARG, "seq_len is not 4-byte aligned");
   if (sel_idx_is_input && sel_idx == nullptr && p->lambda > 0 && p->N >= p->C)
     return fail(STILL_ERR_INVALID_ARG, "sel_idx_is_input set but sel_idx is NULL");
   if (state_out != nullptr) {
@@ -283,7 +285,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
       side = nullptr;
   }
   prof_begin(0, s2);
-  still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, ws + L.vfr, N, L.n_pad, p->Hkv, d, C};
+  still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, ws + L.vfr, N, L.n_pad, p->Hkv, d, C, p->seq_len};
   if ((e = still::launch_transpose_v(tv, p->dtype, B, s2)) != hipSuccess)
     return fail(STILL_ERR_HIP, "transpose_v: %s", hipGetErrorString(e));
   prof_end(0, s2);
@@ -335,6 +337,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   ga.sel = sel;
   ga.nsel = have_sel ? still::retained_rows(ncf, p->lambda, retained_budget(p)) : 0;
   ga.sel_stride = ncf * p->lambda;
+  ga.C = C; ga.lam = p->lambda; ga.rcap = retained_budget(p); ga.seq_len = p->seq_len;
   ga.cap = L.cap; ga.Hq = p->Hq; ga.d = d; ga.N = N;
   ga.kret = ws + L.kret; ga.vrett = ws + L.vrett;
   if ((e = still::launch_gather(ga, p->dtype, B, stream)) != hipSuccess)
@@ -354,7 +357,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   la.sel = sel;
   la.map = map;
   la.N = N; la.Np = L.n_pad; la.C = C; la.lam = have_sel ? p->lambda : 0; la.Hq = p->Hq; la.Hkv = p->Hkv;
-  la.nc = nc; la.ncf = ncf; la.rcap = retained_budget(p);
+  la.nc = nc; la.ncf = ncf; la.rcap = retained_budget(p); la.seq_len = p->seq_len;
   la.seg_chunks = L.seg_chunks; la.nseg = L.nseg;
   la.seg = reinterpret_cast<float*>(ws + L.seg);
   la.n_la = reinterpret_cast<float*>(ws + L.n_la);
@@ -389,7 +392,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   sx.out = out; sx.o_sb = p->o_sb; sx.o_st = p->o_st; sx.o_sh = p->o_sh;
   sx.map = map;
   sx.N = N; sx.Np = L.n_pad; sx.C = C; sx.lam = have_sel ? p->lambda : 0; sx.Hq = p->Hq; sx.Hkv = p->Hkv;
-  sx.rcap = retained_budget(p);
+  sx.rcap = retained_budget(p); sx.seq_len = p->seq_len;
   sx.cap = L.cap; sx.ntiles = (N + still::kSaRows - 1) / still::kSaRows; sx.B_ = B;
   sx.scale = p->scale;
   if ((e = still::launch_sa(sx, p->dtype, d, B, stream)) != hipSuccess)
@@ -409,7 +412,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
     sf.score_ring = reinterpret_cast<float*>(stp + SL.score);
     sf.N = N; sf.R = SL.R; sf.Hq = p->Hq; sf.Hkv = p->Hkv; sf.d = d; sf.lam = have_sel ? p->lambda : 0;
     sf.cap = SL.cap; sf.ncf = ncf; sf.nchunks = SL.n_chunks; sf.rcap = retained_budget(p);
-    sf.shared = p->shared_selection != 0;
+    sf.shared = p->shared_selection != 0; sf.C = C; sf.seq_len = p->seq_len;
     const int n_routed = nc >= 2 ? nc - 2 : 0;
     if (!need_scores) return fail(STILL_ERR_INVALID_ARG, "state_out needs the scores: do not combine it with sel_idx_is_input unless score_out is given");
     if ((e = still::launch_state_fill(sf, p->dtype, B, n_routed, stream)) != hipSuccess)

@@ -648,9 +648,10 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(DecArgs a) {
 template <typename T>
 __global__ void state_fill_ring_kernel(StateFillArgs a) {
   const int h = blockIdx.y, b = blockIdx.z;     // grid.y = max(Hq, Hkv)
-  const int first = a.N > a.R ? a.N - a.R : 0;
+  const int n_tok = seq_tokens(a.seq_len, b, a.N);
+  const int first = n_tok > a.R ? n_tok - a.R : 0;
   const int tok = first + blockIdx.x;
-  if (tok >= a.N) return;
+  if (tok >= n_tok) return;
   const int slot = tok % a.R;
   if (h < a.Hkv) {
     const T* k = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)tok * a.k_st + (int64_t)h * a.k_sh;
@@ -672,6 +673,7 @@ __global__ void state_fill_retained_kernel(StateFillArgs a) {
   const int64_t unit = (int64_t)b * a.Hq + hq;
   const int kvh = a.map.kv[hq];
   const int cr = row / a.lam, pos = row % a.lam;
+  if (cr >= (seq_tokens(a.seq_len, b, a.N) + a.C - 1) / a.C - 2) return;   // not yet routed in this sequence
   int tok = a.sel[(unit * a.ncf + cr) * a.lam + pos];
   const bool used = pos < chunk_quota(cr, a.lam, a.rcap);   // the budget on retained tokens leaves later slots empty
   if (threadIdx.x == 0) a.sel_state[(unit * a.nchunks + cr) * a.lam + pos] = used ? tok : -1;

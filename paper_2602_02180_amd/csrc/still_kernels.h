@@ -30,12 +30,22 @@ __host__ __device__ inline int retained_rows(int chunks, int lam, int rcap) {
 }
 constexpr int kNoBudget = 1 << 30;
 
+// Tokens of sequence b: N for every sequence, or, for a right-padded batch, the caller's per-sequence count
+// (device array, clamped to [1, N]).  Rows at and beyond it are padding: never read as keys or values by a real
+// row, never written as outputs.
+__device__ inline int seq_tokens(const int32_t* seq_len, int b, int N) {
+  if (seq_len == nullptr) return N;
+  const int n = seq_len[b];
+  return n < 1 ? 1 : (n > N ? N : n);
+}
+
 struct TransposeVArgs {
   const void* v;
   int64_t v_sb, v_st, v_sh;
   void* vt;       // [B, Hkv, d, Np]
   void* vfr;      // nullable: the same values in MFMA-fragment order, see vfr_offset()
   int N, Np, Hkv, d, C;
+  const int32_t* seq_len;   // nullable, device [B]: see seq_tokens()
 };
 
 // Element offset of (token tau, column x) of one (batch, kv head) in the fragment-ordered copy of v that the
@@ -61,6 +71,8 @@ struct GatherArgs {
   HeadMap map;
   const int32_t* sel;  // [B, Hq, sel_stride]; the first nsel entries of each list are gathered
   int nsel, sel_stride, cap, Hq, d, N;
+  int C, lam, rcap;
+  const int32_t* seq_len;   // nullable, device [B]: rows of chunks beyond a sequence's full chunks are zero
   void* kret;          // [B, Hq, cap, d]
   void* vrett;         // [B, Hq, d, cap]
 };
@@ -79,6 +91,7 @@ struct LaArgs {
   const int32_t* sel;  // [B, Hq, ncf, lam]
   HeadMap map;
   int N, Np, C, lam, Hq, Hkv, nc, ncf, rcap;
+  const int32_t* seq_len;   // nullable, device [B]
   int seg_chunks, nseg;
   float* seg;          // [B, Hq, nseg, DP*(D+1)]: S (DP x D) then z (DP)
   float* n_la;         // [B, Hq, N, d]
@@ -112,6 +125,7 @@ struct SaArgs {
   int64_t o_sb, o_st, o_sh;
   HeadMap map;
   int N, Np, C, lam, Hq, Hkv, cap, ntiles, B_, rcap;
+  const int32_t* seq_len;   // nullable, device [B]
   float scale;
 };
 
@@ -174,7 +188,8 @@ struct StateFillArgs {
   void* kring;
   void* vring;
   float* score_ring;
-  int N, R, Hq, Hkv, d, lam, cap, ncf, nchunks, rcap, shared;
+  int N, R, Hq, Hkv, d, lam, cap, ncf, nchunks, rcap, shared, C;
+  const int32_t* seq_len;   // nullable, device [B]
 };
 
 hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hipStream_t stream);

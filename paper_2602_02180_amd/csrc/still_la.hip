@@ -152,7 +152,8 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
   const int r = lane & 31, g = lane >> 5;
   const bool consumer = wave < NM;
   const int kvh = a.map.kv[hq];
-  const int N = a.N;
+  const int N = seq_tokens(a.seq_len, b, a.N);   // this sequence's tokens (a right-padded batch has shorter ones)
+  const int nc_b = (N + C - 1) / C, ncf_b = N / C;
   const int G = a.seg_chunks;
 
   const T* __restrict__ qbase = static_cast<const T*>(a.q) + (int64_t)b * a.q_sb + (int64_t)hq * a.q_sh;
@@ -167,7 +168,8 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 
   // chunk range and pipeline slots of this workgroup
   const int c_beg = seg * G;
-  const int c_end = MODE == 1 ? (c_beg + G < a.nc ? c_beg + G : a.nc) : c_beg + G;
+  const int c_end = MODE == 1 ? (c_beg + G < nc_b ? c_beg + G : nc_b) : c_beg + G;
+  if (MODE == 1 && c_beg >= nc_b) return;   // the whole segment is padding (uniform over the workgroup)
   // Unit list.  Output pass: Q(c_beg), then for every later chunk c of the segment K(c-2), Q(c): the
   // outputs of chunk c see the state through chunk c-2.  State pass: K(c_beg-1) .. K(c_beg+G-2).
   const int n_units = MODE == 1 ? 2 * (c_end - c_beg) - 1 : G;
@@ -181,7 +183,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
         x.kind = 1; x.chunk = c_beg + j - 2; x.valid = x.chunk >= 0;
       }
     } else {
-      x.kind = 1; x.chunk = c_beg + u - 1; x.valid = x.chunk >= 0 && x.chunk < a.ncf;
+      x.kind = 1; x.chunk = c_beg + u - 1; x.valid = x.chunk >= 0 && x.chunk < ncf_b;
     }
     return x;
   };
@@ -582,7 +584,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
     const int col = 32 * wave + r;
     const LaUnit x = unit_at(u);
     const T* phiq = reinterpret_cast<const T*>(smem + (u & 1) * SLOT);
-    float* nrow = a.n_la + ((int64_t)b * a.Hq + hq) * (int64_t)N * D;
+    float* nrow = a.n_la + ((int64_t)b * a.Hq + hq) * (int64_t)a.N * D;
     // The operand-type copies of S are made again for every token tile: kept across tiles (the state does
     // not change between them) they would need as many registers as the state itself.
 #pragma unroll
@@ -662,7 +664,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 #pragma unroll
       for (int m = 1; m < LPT; m <<= 1) dla += __shfl_xor(dla, m, 64);
       const int tok = x.chunk * C + tl;
-      if (sl == 0 && tok < N) a.d_la[((int64_t)b * a.Hq + hq) * N + tok] = dla;
+      if (sl == 0 && tok < N) a.d_la[((int64_t)b * a.Hq + hq) * a.N + tok] = dla;
     }
   };
 
@@ -750,7 +752,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
   // ---- write the state
   float* dst = nullptr;
   if (MODE == 0) dst = segp;
-  if (MODE == 1 && a.s_final != nullptr && c_end == a.nc)
+  if (MODE == 1 && a.s_final != nullptr && c_end == nc_b)
     dst = a.s_final + ((int64_t)b * a.Hq + hq) * (int64_t)(DP * (D + 1));
   if (dst != nullptr) {
 #pragma unroll

@@ -20,6 +20,7 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(TransposeVArgs a) {
   const int nd = a.d / 64;
   const int h = blockIdx.y / nd, d0 = (blockIdx.y % nd) * 64;
   const int b = blockIdx.z;
+  const int n_tok = seq_tokens(a.seq_len, b, a.N);   // padding rows of a shorter sequence are written as zeros
   // rows in and columns out move in 16-byte pieces (bases and strides are multiples of 16 bytes; Np is a
   // multiple of 64)
   constexpr int EPV = 16 / (int)sizeof(E), VPR = 64 / EPV;     // elements per piece, pieces per 64-element row
@@ -28,7 +29,7 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(TransposeVArgs a) {
     const int tok = tok0 + i;
     Vec16 pk;
     pk.w[0] = pk.w[1] = pk.w[2] = pk.w[3] = 0u;
-    if (tok < a.N)
+    if (tok < n_tok)
       pk = *reinterpret_cast<const Vec16*>(v + (int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)h * a.v_sh + d0 + x0);
     const E* pe = reinterpret_cast<const E*>(&pk);
 #pragma unroll
@@ -107,7 +108,12 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   if (threadIdx.x < 64) {
     const int row = r0 + threadIdx.x;
     int tok = -1;
-    if (row < a.nsel) {
+    int nsel = a.nsel;
+    if (a.seq_len != nullptr) {   // right-padded batch: only the full chunks of this sequence have real selections
+      const int own = retained_rows(seq_tokens(a.seq_len, b, a.N) / a.C, a.lam, a.rcap);
+      nsel = own < nsel ? own : nsel;
+    }
+    if (row < nsel) {
       tok = a.sel[((int64_t)b * a.Hq + hq) * a.sel_stride + row];
       if (tok < 0 || tok >= a.N) tok = -1;  // caller-supplied indices are never trusted for addressing
     }

@@ -184,10 +184,11 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   const int b = unit / a.Hq, hq = unit % a.Hq;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
-  const int N = a.N, C = a.C, lam = a.lam;
+  const int N = seq_tokens(a.seq_len, b, a.N), C = a.C, lam = a.lam;
   const int kvh = a.map.kv[hq];
 
   const int row0 = tile * Cf::BM;
+  if (row0 >= N) return;   // a tile of padding rows in a right-padded batch (uniform over the workgroup)
   const int q0 = row0 + 32 * wave;
   const int t = q0 + r;
   const bool wave_active = q0 < N;
@@ -400,7 +401,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
     static_assert(Cf::NW * 32 * ROWB_N <= (int)Cf::smem_bytes, "epilogue staging fits the tile slots");
     unsigned char* reg = smem + wave_s * (32 * ROWB_N);
     const int lane_now = fresh_lane_id();
-    const int64_t unit_row0 = ((int64_t)b * a.Hq + hq) * N;
+    const int64_t unit_row0 = ((int64_t)b * a.Hq + hq) * a.N;
     // (1) N_LA rows of this wave -> LDS, in two batches (bounds the staging registers); rows past the end of the
     //     sequence re-read the last row
 #pragma unroll

@@ -315,3 +315,82 @@ def test_decode_step_at_replays_from_a_hip_graph():
             torch.cuda.synchronize()       # the program's own synchronisations between replays
         assert torch.equal(ot, eager[:, t]), f"replay for token {t} differs from the eager step"
         t_dev.add_(1)
+
+
+@pytest.mark.parametrize("kw,lens,steps", [
+    (dict(dtype="f32", d=64, C=64, W=64, B=3), [1000, 517, 130], 70),
+    (dict(dtype="bf16", d=128, C=128, W=128, B=4, Hq=4, Hkv=2), [900, 1300, 128, 40], 140),
+    (dict(dtype="f32", d=64, C=64, W=64, B=2, lam=16, max_retained=40, shared_selection=True, Hq=4, Hkv=2),
+     [640, 300], 70),
+])
+def test_right_padded_prefill_then_decode_at_own_positions(kw, lens, steps):
+    """A batch of sequences of different lengths, right-padded (the padding holds NaN): every real row must equal
+    the oracle on that sequence alone, padding rows of `out` stay untouched, and the exported state lets every
+    sequence go on decoding from its own length."""
+    import torch
+
+    w = wl("varlen", **kw)
+    dev = "cuda"
+    n_pad = max(lens)
+    n_all = n_pad + steps
+    inp = synth.make_inputs(w, seed=27, n_tokens=n_all)
+    full = {k: synth.to_torch(inp[k], w.dtype, dev) for k in ("q", "k", "v", "Wq", "Wk")}
+    q0, k0, v0 = (full[n][:, :n_pad].clone() for n in ("q", "k", "v"))
+    for b, n in enumerate(lens):
+        for x in (q0, k0, v0):
+            x[b, n:] = float("nan")
+    o0 = torch.full_like(q0, 768.0)
+    seq_len = torch.tensor(lens, dtype=torch.int32, device=dev)
+    base = dict(B=w.B, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype=w.dtype,
+                d_f=w.df, max_tokens=n_all, max_retained=w.max_retained, shared_selection=w.shared_selection)
+    ps = S.make_params(N=1, **base)
+    state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
+    S.still_state_init(ps, state)
+    p0 = S.make_params(N=n_pad, q=q0, k=k0, v=v0, out=o0, seq_len=seq_len, **base)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p0), dtype=torch.uint8, device=dev)
+    S.still_hybrid_attn_fwd(p0, q0, k0, v0, None, full["Wq"], None, full["Wk"], None, o0, state_out=state,
+                            workspace=ws)
+    dec = torch.empty(w.B, steps, w.Hq, w.d, dtype=q0.dtype, device=dev)
+    ar = torch.arange(w.B, device=dev)
+    for s in range(steps):
+        t_dev = seq_len + s
+        idx = t_dev.long()
+        qt, kt, vt = (full[n][ar, idx].contiguous() for n in ("q", "k", "v"))
+        ot = torch.empty_like(qt)
+        S.still_hybrid_attn_decode_step_at(ps, state, t_dev, max(lens) + s, qt, kt, vt, None, full["Wq"], None,
+                                           full["Wk"], None, ot)
+        dec[:, s] = ot
+    torch.cuda.synchronize()
+    pre, dec = synth.from_torch(o0), synth.from_torch(dec)
+    L = S.still_state_layout(ps)
+    sel_state = state[L.sel:L.sel + w.B * w.Hq * L.n_chunks * w.lam * 4].view(torch.int32)
+    sel_state = sel_state.reshape(w.B, w.Hq, L.n_chunks, w.lam).cpu().numpy().astype(np.int64)
+    kv_map = synth.kv_head_map(w)
+    worst = 0.0
+    for b, n in enumerate(lens):
+        assert np.all(pre[b, n:] == 768.0), f"sequence {b}: padding rows of out were written"
+        total = n + steps
+        one = {k: (v[b:b + 1, :total] if k in ("q", "k", "v") else v) for k, v in inp.items() if k != "heavy"}
+        for h in range(w.Hq):
+            own = O.still_forward_units(one, kv_map, [(0, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                                        max_retained=U.budget(w), shared_selection=w.shared_selection)[(0, h)]
+            n_routed = max(0, (total - 1) // w.C - 1)
+            gaps = O.selection_gaps(own["rank_score"], w.C, w.lam, U.budget(w))
+            sel_full = own["sel"].copy()
+            for c in range(n_routed):
+                if gaps[c] > 1e-5:
+                    assert np.array_equal(sel_state[b, h, c], own["sel"][c]), (b, h, c)
+                sel_full[c] = sel_state[b, h, c]
+            ref = O.still_forward_units(one, kv_map, [(0, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                                        sel=np.broadcast_to(sel_full, (1, w.Hq) + sel_full.shape))[(0, h)]
+            x = np.concatenate([pre[b, :n, h], dec[b, :, h]]).astype(np.float64)
+            y = ref["out"][:total]
+            assert np.all(np.isfinite(x)), (b, h)
+            if w.dtype == "f32":
+                err = max(U.rel_err(x, y), U.row_rel_err(x, y))
+                assert err <= 1e-4, (b, h, err)
+            else:
+                err = float(np.max(np.abs(x - y) / (2e-2 + 2.0 ** -8 * np.abs(y))))
+                assert err <= 1.0, (b, h, err)
+            worst = max(worst, err)
+    print(f"[varlen {lens} + {steps} decode steps] worst error measure {worst:.3e}")
