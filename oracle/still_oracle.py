@@ -160,6 +160,19 @@ def select_top_lambda(score: np.ndarray, C: int, lam: int, max_retained: Optiona
     return sel
 
 
+def global_scores(q: np.ndarray, k: np.ndarray, scale: float, eps: float) -> np.ndarray:
+    """The score with the window set replaced by the whole causal prefix {0..t}: the "global" reference of the
+    local-versus-global consistency study of Sec. 3.1.  Same two softmaxes, same formula."""
+    return self_saliency_scores(q, k, W=max(1, q.shape[0]), scale=scale, eps=eps)
+
+
+def selection_overlap(score_a: np.ndarray, score_b: np.ndarray, C: int, lam: int) -> np.ndarray:
+    """Per full chunk: how many tokens the Top-lambda sets under two scores have in common (int64 [N // C])."""
+    sa = select_top_lambda(score_a, C, lam)
+    sb = select_top_lambda(score_b, C, lam)
+    return np.asarray([len(set(sa[c].tolist()) & set(sb[c].tolist())) for c in range(sa.shape[0])], np.int64)
+
+
 def group_rank_score(scores: np.ndarray) -> np.ndarray:
     """Score that a group of query heads sharing one kv head ranks by: the sum of their Self-Saliency Scores.
     scores [G, N] -> [N].  Feeding it to select_top_lambda gives the one index list all G heads use."""

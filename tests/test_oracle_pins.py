@@ -486,3 +486,39 @@ def test_group_shared_selection_with_one_head_per_group_is_the_per_head_operator
     for u in units:
         np.testing.assert_array_equal(own[u]["sel"], shared[u]["sel"])
         np.testing.assert_array_equal(own[u]["out"], shared[u]["out"])
+
+
+# --------------------------------------------------------------------------- global score, overlap of selections
+def test_global_score_is_the_score_over_the_whole_prefix():
+    """Closed form through the self-weight over ALL earlier keys, and the uniform closed value with n = t + 1."""
+    q, k, *_ = rand_problem(21, 50, 8)
+    eps = 1e-13
+    s = O.global_scores(q, k, scale=0.5, eps=eps)
+    for t in range(1, 50):
+        p = sp_softmax(0.5 * (k[:t + 1] @ q[t]))[-1]
+        assert s[t] == pytest.approx(p * np.log((p + eps) / eps) + (1 - p) * np.log1p(-p), rel=1e-8, abs=1e-9)
+    k1 = np.ones((30, 8))
+    u = O.global_scores(q[:30], k1, scale=0.3, eps=EPS)
+    for t in range(1, 30):
+        n = t + 1
+        expect = ((n - 1) / n) * np.log((1 / n + EPS) / (1 / (n - 1) + EPS)) + (1 / n) * np.log((1 / n + EPS) / EPS)
+        assert u[t] == pytest.approx(expect, rel=1e-10)
+    assert u[0] == pytest.approx(np.log((1 + EPS) / EPS), rel=1e-12)
+    # a window that already covers the prefix gives the same numbers
+    np.testing.assert_array_equal(O.global_scores(q, k, 0.5, EPS), O.self_saliency_scores(q, k, W=50, scale=0.5, eps=EPS))
+    np.testing.assert_array_equal(O.global_scores(q, k, 0.5, EPS)[:7], O.self_saliency_scores(q, k, W=7, scale=0.5, eps=EPS)[:7])
+
+
+def test_selection_overlap_counts_common_tokens():
+    rng = np.random.default_rng(22)
+    a = rng.standard_normal(40)
+    assert O.selection_overlap(a, a, C=8, lam=3).tolist() == [3] * 5
+    assert O.selection_overlap(a, -a, C=8, lam=3).tolist() == [0] * 5          # best three vs worst three of eight
+    assert O.selection_overlap(a, -a, C=8, lam=8).tolist() == [8] * 5
+    b = rng.standard_normal(40)
+    got = O.selection_overlap(a, b, C=8, lam=4)
+    for c in range(5):
+        ta = set(np.argsort(-a[8 * c:8 * c + 8], kind="stable")[:4].tolist())
+        tb = set(np.argsort(-b[8 * c:8 * c + 8], kind="stable")[:4].tolist())
+        assert got[c] == len(ta & tb)
+    assert O.selection_overlap(a[:37], b[:37], C=8, lam=4).shape == (4,)        # the partial chunk is not ranked
