@@ -100,6 +100,80 @@ def budget_tag(w: synth.Workload) -> str:
         (" shared_selection" if w.shared_selection else "")
 
 
+def global_score_bench(args) -> int:
+    """Second workload on the score step (consistency study of Sec. 3.1): still_global_score over the whole causal
+    prefix at the shape of the chosen config, then the overlap of the local and the global Top-lambda sets."""
+    import torch
+    from paper_2602_02180_amd import binding as S
+
+    w = synth.workload(args.config if args.config != "c5" else "c4")
+    inp = synth.make_inputs(w)
+    dev = "cuda"
+    q, k, v = (synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v"))
+    Wq, Wk = synth.to_torch(inp["Wq"], w.dtype, dev), synth.to_torch(inp["Wk"], w.dtype, dev)
+    out = torch.empty_like(q)
+    N = w.N
+    p = S.make_params(B=w.B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out)
+    glob = torch.empty(w.B, w.Hq, N, dtype=torch.float32, device=dev)
+    steps = args.steps if args.steps else 5
+    for _ in range(min(args.warmup, 2)):
+        S.still_global_score(p, q, k, glob)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        S.still_global_score(p, q, k, glob)
+    ev1.record()
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    ker_ms = ev0.elapsed_time(ev1) / steps
+    # local scores from one prefill call, then the overlap of the two selections
+    local = torch.empty_like(glob)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    S.still_hybrid_attn_fwd(p, q, k, v, None, Wq, None, Wk, None, out, score_out=local, workspace=ws)
+    ov = torch.zeros(w.B, w.Hq, N // w.C, dtype=torch.int32, device=dev)
+    S.still_selection_overlap(p, local, glob, ov)
+    torch.cuda.synchronize()
+    overlap = float(ov.float().mean().item()) / max(w.lam, 1)
+    # two passes over the causal logits (key tiles of 64, as the kernel walks them)
+    pairs = float(np.sum((np.arange(N) // 64 + 1) * 64)) * w.B * w.Hq
+    flops = 2 * 2 * w.d * pairs
+    # The kernel is bound by vector-ALU issue, not by the matrix units: per query-key pair the two passes issue
+    # about 17 ordinary lane operations and 4 transcendental ones (2 exp2, 2 log2), which occupy the pipe four
+    # times as long: 33 issue slots per pair.  Peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T slots/s
+    # (the 157.3 TFLOP/s fp32 vector figure counts a fused multiply-add as two and packed issue as two more).
+    slots = 33.0 * pairs
+    peak_alu = 256 * 4 * 16 * 2.4e9
+    rec = {
+        "metric": f"global-score tokens/s ({w.name} shape)", "value": w.B * N * steps / el, "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": min(args.warmup, 2), "ms_per_step": el / steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"global score + overlap, {w.name}: B={w.B} N={N} Hq={w.Hq} Hkv={w.Hkv} d={w.d} "
+                               f"C={w.C} W={w.W} lambda={w.lam} heavy_frac={w.heavy_frac}",
+                   "overlap_at_lambda_local_vs_global": overlap},
+        "roofline": {"bound": "alu", "kernel": "global_score", "achieved": slots / (ker_ms * 1e-3) / 1e12,
+                     "peak": peak_alu / 1e12, "unit": "T issue slots/s", "frac": slots / (ker_ms * 1e-3) / peak_alu,
+                     "traffic": None, "algorithmic_slots_per_launch": slots, "mfma_flops_per_launch": flops,
+                     "mfma_frac": flops / (ker_ms * 1e-3) / PEAK_MFMA[w.dtype], "avg_launch_ms": ker_ms},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import still_oracle as O
+        n_s = min(N, 4096)
+        qq, kk = inp["q"][0, :n_s, 0].astype(np.float64), inp["k"][0, :n_s, 0].astype(np.float64)
+        t0 = time.perf_counter()
+        O.global_scores(qq, kk, w.scale, w.eps)
+        el_c = time.perf_counter() - t0
+        pair_rate = n_s * (n_s + 1) / 2 / el_c
+        rec["cpu_baseline"] = {"value": pair_rate / ((N + 1) / 2 * w.Hq), "unit": "tokens/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f"rows 0..{n_s - 1} of one (batch, head) unit, {el_c:.1f} s; its query-key pair "
+                                         f"rate scaled to all {N} rows of {w.Hq} heads"}
+    print(json.dumps(rec))
+    return 0
+
+
 def decode_bench(args) -> int:
     """Config 5: B sequences with a prefilled 32K context, then single-token steps.  The contexts are drawn
     on the GPU (seeded torch generator, same distributions as synth.make_inputs) and prefilled in slices of
@@ -217,6 +291,9 @@ def main() -> int:
     ap.add_argument("--shared-selection", action="store_true",
                     help="variant: the query heads of one kv head rank by their summed score and share one retained "
                          "set (not the paper's method; side figures only)")
+    ap.add_argument("--global-score", action="store_true",
+                    help="second workload: the score over the whole causal prefix and its overlap with the local "
+                         "selection (consistency study), at the prefill shape of --config")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc runs)")
@@ -246,6 +323,8 @@ def main() -> int:
         print(json.dumps({"calibrate_copy_bytes": 1 << 30, "launches": 4}))
         return 0
 
+    if args.global_score:
+        return global_score_bench(args)
     if args.config == "c5":
         return decode_bench(args)
     if not args.steps:

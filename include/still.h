@@ -254,6 +254,24 @@ STILL_API still_status_t still_hybrid_attn_decode_step_at(const still_params_t* 
                                                           const void* Wq, const void* bq, const void* Wk, const void* bk,
                                                           void* out_t, void* stream);
 
+/*
+ * Local-versus-global consistency study of Sec. 3.1 (the figure that compares the window-local Self-Saliency
+ * Score with the score over the whole context): a second workload on the score step, not part of the layer.
+ *
+ * still_global_score: the score equation with the window set replaced by the whole causal prefix {0..t}, for every
+ *   (b, hq, t).  q, k: device, dtype, strided as in `p` (W, C, lambda, d_f are ignored); score_out: device float
+ *   [B, Hq, N].  Cost is quadratic in N (two passes over the causal logits).
+ * still_selection_overlap: for every full chunk, the number of tokens that the Top-lambda sets under two scores
+ *   have in common (ties to the lower index, as in the selection step).  score_a, score_b: device float [B, Hq, N]
+ *   (for instance score_out of the prefill and of still_global_score); overlap: device int32 [B, Hq, N/C].
+ *   overlap / lambda averaged over chunks is the consistency figure.
+ * Both validate on the host and return the usual codes; neither needs a workspace.
+ */
+STILL_API still_status_t still_global_score(const still_params_t* p, const void* q, const void* k, float* score_out,
+                                            void* stream);
+STILL_API still_status_t still_selection_overlap(const still_params_t* p, const float* score_a, const float* score_b,
+                                                 int32_t* overlap, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -84,6 +84,10 @@ def lib() -> ct.CDLL:
         L.still_hybrid_attn_decode_step.argtypes = [pp, vp, ct.c_int32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.still_hybrid_attn_decode_step_at.restype = ct.c_int
         L.still_hybrid_attn_decode_step_at.argtypes = [pp, vp, vp, ct.c_int32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.still_global_score.restype = ct.c_int
+        L.still_global_score.argtypes = [pp, vp, vp, vp, vp]
+        L.still_selection_overlap.restype = ct.c_int
+        L.still_selection_overlap.argtypes = [pp, vp, vp, vp, vp]
         L.still_profile_enable.restype = None
         L.still_profile_enable.argtypes = [ct.c_int32]
         L.still_profile_read.restype = ct.c_int
@@ -219,6 +223,23 @@ def still_hybrid_attn_decode_step_at(p: StillParams, state, t_dev, t_max: int, q
     _check(lib().still_hybrid_attn_decode_step_at(ct.byref(p), _ptr(state), _ptr(t_dev), t_max, _ptr(q_t), _ptr(k_t),
                                                   _ptr(v_t), _ptr(g_t), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk),
                                                   _ptr(out_t), stream.cuda_stream))
+
+
+def still_global_score(p: StillParams, q, k, score_out, stream=None) -> None:
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(lib().still_global_score(ct.byref(p), _ptr(q), _ptr(k), _ptr(score_out), stream.cuda_stream))
+
+
+def still_selection_overlap(p: StillParams, score_a, score_b, overlap, stream=None) -> None:
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(lib().still_selection_overlap(ct.byref(p), _ptr(score_a), _ptr(score_b), _ptr(overlap),
+                                         stream.cuda_stream))
 
 
 STILL_PROFILE_SLOTS = 8

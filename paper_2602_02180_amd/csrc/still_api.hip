@@ -553,4 +553,45 @@ still_status_t still_hybrid_attn_decode_step_at(const still_params_t* p, void* s
   return decode_step(p, state, t_max, t_dev, q_t, k_t, v_t, g_t, Wq, bq, Wk, bk, out_t, stream_v);
 }
 
+still_status_t still_global_score(const still_params_t* p, const void* q, const void* k, float* score_out,
+                                  void* stream_v) {
+  still_status_t st = validate_params(p, true);
+  if (st != STILL_OK) return st;
+  {
+    const int64_t unit = 16 / (int64_t)esize(p->dtype);
+    const int64_t s[] = {p->q_sb, p->q_st, p->q_sh, p->k_sb, p->k_st, p->k_sh};
+    for (int64_t x : s)
+      if (x < 0 || x % unit != 0) return fail(STILL_ERR_INVALID_ARG, "stride %lld is negative or not a multiple of 16 bytes", (long long)x);
+    if (p->q_st < p->d || p->k_st < p->d) return fail(STILL_ERR_INVALID_ARG, "token stride smaller than d");
+  }
+  if (!q || !k || !score_out) return fail(STILL_ERR_INVALID_ARG, "a required pointer (q, k, score_out) is NULL");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(score_out))
+    return fail(STILL_ERR_INVALID_ARG, "q, k and score_out must be 16-byte aligned");
+  still::GScoreArgs ga{};
+  ga.q = q; ga.k = k;
+  ga.q_sb = p->q_sb; ga.q_st = p->q_st; ga.q_sh = p->q_sh;
+  ga.k_sb = p->k_sb; ga.k_st = p->k_st; ga.k_sh = p->k_sh;
+  fill_map(p, &ga.map);
+  ga.N = p->N; ga.Hq = p->Hq; ga.scale = p->scale; ga.eps = p->eps; ga.score = score_out;
+  hipError_t e = still::launch_global_score(ga, p->dtype, p->d, p->B, static_cast<hipStream_t>(stream_v));
+  if (e != hipSuccess) return fail(STILL_ERR_HIP, "global_score: %s", hipGetErrorString(e));
+  g_err[0] = 0;
+  return STILL_OK;
+}
+
+still_status_t still_selection_overlap(const still_params_t* p, const float* score_a, const float* score_b,
+                                       int32_t* overlap, void* stream_v) {
+  still_status_t st = validate_params(p, true);
+  if (st != STILL_OK) return st;
+  if (!score_a || !score_b || !overlap) return fail(STILL_ERR_INVALID_ARG, "a required pointer (score_a, score_b, overlap) is NULL");
+  if ((reinterpret_cast<uintptr_t>(score_a) & 3) || (reinterpret_cast<uintptr_t>(score_b) & 3) ||
+      (reinterpret_cast<uintptr_t>(overlap) & 3))
+    return fail(STILL_ERR_INVALID_ARG, "score_a, score_b and overlap must be 4-byte aligned");
+  hipError_t e = still::launch_topk_overlap(score_a, score_b, overlap, p->N, p->C, p->lambda, p->Hq, p->B,
+                                            static_cast<hipStream_t>(stream_v));
+  if (e != hipSuccess) return fail(STILL_ERR_HIP, "selection_overlap: %s", hipGetErrorString(e));
+  g_err[0] = 0;
+  return STILL_OK;
+}
+
 }  // extern "C"

@@ -39,6 +39,16 @@ __device__ inline int seq_tokens(const int32_t* seq_len, int b, int N) {
   return n < 1 ? 1 : (n > N ? N : n);
 }
 
+struct GScoreArgs {
+  const void* q;
+  const void* k;
+  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
+  HeadMap map;
+  int N, Hq;
+  float scale, eps;
+  float* score;   // [B, Hq, N]
+};
+
 struct TransposeVArgs {
   const void* v;
   int64_t v_sb, v_st, v_sh;
@@ -196,6 +206,9 @@ hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hi
 hipError_t launch_state_fill(const StateFillArgs& a, int dtype, int B, int n_routed, hipStream_t stream);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
 hipError_t launch_score(const ScoreArgs& a, int dtype, int d, int B, int nc, hipStream_t stream);
+hipError_t launch_global_score(const GScoreArgs& a, int dtype, int d, int B, hipStream_t stream);
+hipError_t launch_topk_overlap(const float* sa, const float* sb, int32_t* overlap, int N, int C, int lam, int Hq,
+                               int B, hipStream_t stream);
 hipError_t launch_group_select(const ScoreArgs& a, int B, int Hkv, hipStream_t stream);
 hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStream_t stream);
 hipError_t launch_transpose_w(const TransposeWArgs& a, int dtype, hipStream_t stream);

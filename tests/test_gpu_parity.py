@@ -371,3 +371,52 @@ def test_profile_modes_report_kernel_times():
         S.still_profile_enable(0)
     with pytest.raises(S.StillError):
         S.still_profile_read()
+
+
+# ------------------------------------------------------------------ local-versus-global consistency workload
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f32", d=64, N=700, Hq=2, Hkv=1),
+    dict(dtype="f32", d=128, N=333, Hq=2, Hkv=2),
+    dict(dtype="bf16", d=128, N=1500, Hq=4, Hkv=2, B=2, C=128, W=128),
+    dict(dtype="bf16", d=64, N=129, Hq=2, Hkv=1),
+    dict(dtype="f32", d=64, N=1, Hq=1, Hkv=1),
+], ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
+def test_global_score_and_selection_overlap(kw):
+    """Score over the whole causal prefix against the oracle's two-softmax form, then the per-chunk overlap of the
+    Top-lambda sets under the local and the global score (exact wherever both oracle gaps are clear)."""
+    import torch
+    from oracle import still_oracle as O
+
+    w = small("gscore", **kw)
+    inp = synth.make_inputs(w, seed=31)
+    dev = "cuda"
+    q, k = synth.to_torch(inp["q"], w.dtype, dev), synth.to_torch(inp["k"], w.dtype, dev)
+    p = S.make_params(B=w.B, N=w.N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, q=q, k=k)
+    glob = torch.full((w.B, w.Hq, w.N), float("nan"), dtype=torch.float32, device=dev)
+    S.still_global_score(p, q, k, glob)
+    local = torch.from_numpy(U.run_hip(w, inp, want_terms=False)["score"]).to(dev)
+    ncf = w.N // w.C
+    ov = torch.full((w.B, w.Hq, max(ncf, 1)), -1, dtype=torch.int32, device=dev)
+    S.still_selection_overlap(p, local, glob, ov)
+    torch.cuda.synchronize()
+    glob_h, ov_h, local_h = glob.cpu().numpy(), ov.cpu().numpy(), local.cpu().numpy()
+    kv = synth.kv_head_map(w)
+    worst, exact, total = 0.0, 0, 0
+    for b in range(w.B):
+        for h in range(w.Hq):
+            qq, kk = inp["q"][b, :, h].astype(np.float64), inp["k"][b, :, kv[h]].astype(np.float64)
+            ref_g = O.global_scores(qq, kk, w.scale, w.eps)
+            worst = max(worst, float(np.max(np.abs(glob_h[b, h] - ref_g))))
+            if ncf == 0:
+                continue
+            ref_l = O.self_saliency_scores(qq, kk, w.W, w.scale, w.eps)
+            ref_ov = O.selection_overlap(ref_l, ref_g, w.C, w.lam)
+            clear = (O.selection_gaps(ref_l, w.C, w.lam) > 1e-5) & (O.selection_gaps(ref_g, w.C, w.lam) > 1e-4)
+            assert np.array_equal(ov_h[b, h, :ncf][clear], ref_ov[clear]), (b, h)
+            # whatever the near-ties do, the count is that of the device's own two rankings
+            own = O.selection_overlap(local_h[b, h].astype(np.float64), glob_h[b, h].astype(np.float64), w.C, w.lam)
+            assert np.array_equal(ov_h[b, h, :ncf], own), (b, h)
+            exact += int(clear.sum()); total += ncf
+    print(f"[gscore {w.dtype} d={w.d} N={w.N}] global score max-abs err {worst:.3e}; chunks with clear gaps {exact}/{total}")
+    assert worst <= 5e-5, worst      # the bar of the window-local score
