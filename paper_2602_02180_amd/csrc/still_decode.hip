@@ -72,10 +72,7 @@ __device__ __forceinline__ void block_reduce4(float& a, float& b, float& c, floa
 
 // ---------------------------------------------------------------- append
 template <typename T>
-__global__ void decode_append_kernel(DecArgs a, int D) {
-  const int h = blockIdx.x, b = blockIdx.y;
-  const int t = step_index(a, b);
-  if (t < 0) return;
+__device__ __forceinline__ void decode_append(const DecArgs& a, int h, int b, int t, int D) {
   const int slot = t % a.R;
   const T* k = static_cast<const T*>(a.k) + ((int64_t)b * a.Hkv + h) * D;
   const T* v = static_cast<const T*>(a.v) + ((int64_t)b * a.Hkv + h) * D;
@@ -87,14 +84,23 @@ __global__ void decode_append_kernel(DecArgs a, int D) {
   }
 }
 
-// ---------------------------------------------------------------- score of the new token
+// ---------------------------------------------------------------- score of the new token (+ append)
+// Workgroups 0 .. Hq-1 of a sequence score the new token for one query head each; workgroups Hq .. Hq+Hkv-1 copy
+// the new key/value rows of one kv head into the ring.  The two do not depend on each other within the step: the
+// score reads the new key from the caller's k_t, and the ring slot being overwritten (token t - R) lies outside
+// every window (W <= 128 < R).
 template <typename T, int D>
 __global__ __launch_bounds__(128) void decode_score_kernel(DecArgs a) {
   __shared__ float sh[16];
-  const int hq = blockIdx.x, b = blockIdx.y;
-  const int kvh = a.map.kv[hq];
+  const int b = blockIdx.y;
   const int t = step_index(a, b);
   if (t < 0) return;
+  if ((int)blockIdx.x >= a.Hq) {
+    decode_append<T>(a, blockIdx.x - a.Hq, b, t, D);
+    return;
+  }
+  const int hq = blockIdx.x;
+  const int kvh = a.map.kv[hq];
   const int j = threadIdx.x;              // window key t - j
   const int pj = t - j;
   const bool valid = j < a.W && pj >= 0;
@@ -699,11 +705,7 @@ __global__ void state_fill_retained_kernel(StateFillArgs a) {
   }
 
 hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hipStream_t stream) {
-  if (dtype == 1)
-    hipLaunchKernelGGL(decode_append_kernel<bf16>, dim3(a.Hkv, a.B), dim3(128), 0, stream, a, d);
-  else
-    hipLaunchKernelGGL(decode_append_kernel<float>, dim3(a.Hkv, a.B), dim3(128), 0, stream, a, d);
-#define CALL_SCORE(TT, DD) hipLaunchKernelGGL((decode_score_kernel<TT, DD>), dim3(a.Hq, a.B), dim3(128), 0, stream, a);
+#define CALL_SCORE(TT, DD) hipLaunchKernelGGL((decode_score_kernel<TT, DD>), dim3(a.Hq + a.Hkv, a.B), dim3(128), 0, stream, a);
   STILL_DISPATCH(dtype, d, CALL_SCORE)
   if (route) {
     const int cr = a.t / a.C - 2;
