@@ -102,3 +102,25 @@ def test_fwd_rejects_null_and_misaligned_pointers_without_launching():
     rc = lib.still_hybrid_attn_fwd(ctypes.byref(p), fake, fake, fake, null, fake, null, fake, null, fake, null,
                                    null, 0, null, fake, 16, null)
     assert rc == S.STILL_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_public_header_is_plain_c_and_matches_the_binding(tmp_path):
+    """include/still.h compiles as C99 on its own, and the struct sizes the C compiler sees are the ones the ctypes
+    binding marshals (a field added on one side only would shift every later field)."""
+    import shutil
+    import subprocess
+
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "still.h"\n'
+                   'int main(void) { printf("%zu %zu %zu %zu %zu\\n", sizeof(still_params_t), sizeof(still_ws_layout_t),\n'
+                   '  sizeof(still_state_layout_t), offsetof(still_params_t, q_sb), offsetof(still_params_t, seq_len));\n'
+                   '  return 0; }\n')
+    exe = tmp_path / "sizes"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got == [ctypes.sizeof(S.StillParams), ctypes.sizeof(S.StillWsLayout), ctypes.sizeof(S.StillStateLayout),
+                   S.StillParams.q_sb.offset, S.StillParams.seq_len.offset]
