@@ -145,7 +145,8 @@ STILL_API still_status_t still_fwd_workspace_layout(const still_params_t* p, sti
  *                  (max_retained) leaves unused, which are always the last slots of a chunk
  *   sel_idx_is_input  0: sel_idx (if given) is an OUTPUT.  1: sel_idx is an INPUT that replaces the
  *                  Top-lambda step (indices must lie inside their chunk, strictly ascending; with a budget
- *                  only the first min(lambda, max_retained - c*lambda) slots of chunk c are read); test hook
+ *                  only the first min(lambda, max_retained - c*lambda) slots of chunk c are read; with
+ *                  shared_selection the lists of the query heads of one kv head must be equal); test hook
  *   state_out      device, or NULL: a decode state buffer (see still_state_bytes; p->max_tokens >= N);
  *                  on return it holds the tokens 0..N-1, so the next decode step is t = N.  Its previous
  *                  contents are overwritten (no still_state_init needed)

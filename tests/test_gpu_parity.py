@@ -174,6 +174,24 @@ def test_group_shared_selection(kw, kv_map):
         assert np.array_equal(hip["sel"][:, h], hip["sel"][:, first]), "lists of one group differ"
 
 
+def test_full_size_config4_with_budget_and_group_shared_selection():
+    """Config 4 at full size in the launch configuration of the bench, with the budget of the paper's long-context
+    setting (896 retained tokens, chunk 128) and one retained set per kv head: sampled units against the oracle."""
+    w = synth.workload("c4", max_retained=896, shared_selection=True)
+    inp = synth.make_inputs(w)
+    units = [(0, 2), (0, 29)]
+    ref = U.oracle_units(w, inp, units)
+    hip = U.run_hip(w, inp)
+    check_scores_and_selection(w, hip, ref, units, "e2e")
+    ref_h = U.oracle_units(w, inp, units, sel=hip["sel"])
+    check_terms(w, hip, ref_h, units, "e2e")
+    check_outputs(w, hip, ref_h, units, "e2e")
+    assert np.all(np.isfinite(hip["out"]))
+    kept = (hip["sel"] >= 0).sum(axis=(2, 3))
+    assert np.all(kept == 896)
+    assert np.array_equal(hip["sel"][0, 0], hip["sel"][0, 3]) and np.array_equal(hip["sel"][0, 28], hip["sel"][0, 31])
+
+
 @pytest.mark.parametrize("lam", [0, 1, 64])
 def test_lambda_extremes(lam):
     w = small("lam", lam=lam, N=448, dtype="f32")
