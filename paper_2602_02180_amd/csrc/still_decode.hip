@@ -203,14 +203,19 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr_all
       vret[(int64_t)row * D + x] = vring[(int64_t)slot * D + x];
     }
   }
-  // the others -> (S, z): thread f owns row f of S; thread j < DF also owns column j of Wk.  The tokens are
-  // taken TB at a time (in order): one set of barriers per batch instead of one per token.  Per batch:
-  //   (A) threads < d_f project the TB tokens (their column of Wk stays in registers),
+  // the others -> (S, z): thread f owns row f of S; thread tid also owns the slice part = tid / d_f of column
+  // tid % d_f of Wk (a whole column per thread would cost 128 more registers and halve the occupancy).  The tokens
+  // are taken TB at a time (in order): one set of barriers per batch instead of one per token.  Per batch:
+  //   (A) every thread projects the TB tokens onto its slice of its column; the slices are added in (B),
   //   (B) wave w turns token w's d_f projections into its 2 d_f features (all of a token's features sit in one
   //       wave, two per lane, so the statistics need wave reductions only),
   //   (C) every thread adds the TB rank-1 terms to its row of S, token by token.
+  // The key/value rows of the next batch are loaded into registers before (A), so their latency hides behind
+  // the arithmetic of the current batch.
   constexpr int TB = 4;
-  __shared__ __attribute__((aligned(16))) float xs[D][TB], vs[D][TB], fs[TB][DF], phi[DP][TB];
+  constexpr int XP = 256 / DF, XS = D / XP;          // slices per column, rows per slice
+  constexpr int NLD = TB * D / 256;                  // row elements per thread and batch
+  __shared__ __attribute__((aligned(16))) float xs[D][TB], vs[D][TB], fpart[XP][TB][DF], phi[DP][TB];
   __shared__ int s_rest[128];
   __shared__ int s_nrest;
   if (tid < C && !chosen) {
@@ -223,13 +228,18 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr_all
     for (int jx = 0; jx < C; ++jx) n += s_flag[jx] ? 0 : 1;
     s_nrest = n;
   }
-  float wcol[D];
-  if (tid < DF) {
-    const T* wk = static_cast<const T*>(a.wk) + (int64_t)hq * D * DF + tid;
+  const int fi = tid % DF, part = tid / DF;
+  float wcol[XS];
+  {
+    const T* wk = static_cast<const T*>(a.wk) + (int64_t)hq * D * DF + (int64_t)(part * XS) * DF + fi;
 #pragma unroll
-    for (int x = 0; x < D; ++x) wcol[x] = to_f32(wk[(int64_t)x * DF]);
+    for (int x = 0; x < XS; ++x) wcol[x] = to_f32(wk[(int64_t)x * DF]);
   }
-  const float bias = (a.bk != nullptr && tid < DF) ? to_f32(static_cast<const T*>(a.bk)[(int64_t)hq * DF + tid]) : 0.f;
+  const int lane = tid & 63, wave = tid >> 6;
+  float bias[DF / 64];
+#pragma unroll
+  for (int h = 0; h < DF / 64; ++h)
+    bias[h] = a.bk != nullptr ? to_f32(static_cast<const T*>(a.bk)[(int64_t)hq * DF + lane + 64 * h]) : 0.f;
   float* Sg = a.S + unit * (int64_t)(DP * (D + 1));
   float srow[D];
   float zf = 0.f;
@@ -240,35 +250,45 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr_all
   }
   __syncthreads();
   const int n_rest = s_nrest;
-  const int lane = tid & 63, wave = tid >> 6;
+  float xn[NLD], vn[NLD];                            // this thread's elements of the next batch's rows
+  auto fetch = [&](int i0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int idx = tid + 256 * i, tb = idx / D, x = idx % D;
+      xn[i] = 0.f;
+      vn[i] = 0.f;
+      if (i0 + tb < n_rest) {
+        const int slot = (cr * C + s_rest[i0 + tb]) % R;
+        xn[i] = to_f32(kring[(int64_t)slot * D + x]);
+        vn[i] = to_f32(vring[(int64_t)slot * D + x]);
+      }
+    }
+  };
+  fetch(0);
   for (int i0 = 0; i0 < n_rest; i0 += TB) {
     const int nb = n_rest - i0 < TB ? n_rest - i0 : TB;
     __syncthreads();                             // the previous batch's operands have been consumed
-    for (int idx = tid; idx < TB * D; idx += 256) {
-      const int tb = idx / D, x = idx % D;
-      float xv = 0.f, vv = 0.f;
-      if (tb < nb) {
-        const int slot = (cr * C + s_rest[i0 + tb]) % R;
-        xv = to_f32(kring[(int64_t)slot * D + x]);
-        vv = to_f32(vring[(int64_t)slot * D + x]);
-      }
-      xs[x][tb] = xv;
-      vs[x][tb] = vv;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int idx = tid + 256 * i, tb = idx / D, x = idx % D;
+      xs[x][tb] = xn[i];
+      vs[x][tb] = vn[i];
     }
     __syncthreads();
+    if (i0 + TB < n_rest) fetch(i0 + TB);
     // (A)
-    if (tid < DF) {
+    {
       float f[TB];
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) f[tb] = 0.f;
 #pragma unroll
-      for (int x = 0; x < D; ++x) {
-        const floatx4 x4 = *reinterpret_cast<const floatx4*>(&xs[x][0]);
+      for (int x = 0; x < XS; ++x) {
+        const floatx4 x4 = *reinterpret_cast<const floatx4*>(&xs[part * XS + x][0]);
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) f[tb] = fmaf(x4[tb], wcol[x], f[tb]);
       }
 #pragma unroll
-      for (int tb = 0; tb < TB; ++tb) fs[tb][tid] = f[tb] + bias;
+      for (int tb = 0; tb < TB; ++tb) fpart[part][tb][fi] = f[tb];
     }
     __syncthreads();
     // (B) blockDim = 256 = TB waves
@@ -277,7 +297,10 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr_all
       float fv[DF / 64], nx2 = 0.f, nf2 = 0.f, fmx = -INFINITY, fmn = INFINITY;
 #pragma unroll
       for (int h = 0; h < DF / 64; ++h) {
-        fv[h] = fs[tb][lane + 64 * h];
+        float s = 0.f;
+#pragma unroll
+        for (int pp = 0; pp < XP; ++pp) s += fpart[pp][tb][lane + 64 * h];   // slices in ascending order
+        fv[h] = s + bias[h];
         nf2 = fmaf(fv[h], fv[h], nf2);
         fmx = fmaxf(fmx, fv[h]);
         fmn = fminf(fmn, fv[h]);
