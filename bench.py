@@ -229,6 +229,9 @@ def decode_bench(args) -> int:
         S.still_hybrid_attn_fwd(pf, q, k, v, None, Wq, None, Wk, None, o, state_out=st_slice, workspace=ws)
         torch.cuda.synchronize()
         t_prefill += time.perf_counter() - t0
+        if b0 == 0 and not args.no_cpu_baseline:   # sequence 0 of the batch, for the oracle leg below
+            cpu_ctx = {"q": q[0, :, :8].float().cpu().numpy(), "k": k[0].float().cpu().numpy(),
+                       "v": v[0].float().cpu().numpy()}
         for name, per_seq in regions:   # every region is [B, ...]: copy the slice's sequences into place
             src0, dst0 = getattr(Ls, name), getattr(L, name)
             state[dst0 + b0 * per_seq: dst0 + (b0 + SB) * per_seq] = st_slice[src0: src0 + SB * per_seq]
@@ -276,8 +279,45 @@ def decode_bench(args) -> int:
                      "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": bytes_step / (ordinary * 1e-3) / PEAK_HBM,
                      "traffic": args.traffic_bytes, "algorithmic_bytes_per_step": bytes_step},
     }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = decode_cpu_baseline(w, cpu_ctx, toks, Wq, Wk, args.warmup, n_steps)
     print(json.dumps(rec))
     return 0
+
+
+def decode_cpu_baseline(w, ctx, toks, Wq, Wk, warmup, n_steps, budget_s: float = 20.0):
+    """The oracle has no incremental form: its decode is the chunk-wise form on the concatenated sequence with only the
+    decoded rows requested (scores, selection and states of the whole prefix are recomputed).  Timed on query heads of
+    sequence 0 until ~budget_s."""
+    from oracle import still_oracle as O
+
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:  # pragma: no cover
+        cores = os.cpu_count() or 1
+    n_dec = warmup + n_steps
+    G = w.Hq // w.Hkv
+    units_done, t0 = 0, time.perf_counter()
+    for h in range(ctx["q"].shape[1]):
+        qd = np.stack([toks[i][0][0, h].float().cpu().numpy() for i in range(n_dec)])
+        kd = np.stack([toks[i][1][0, h // G].float().cpu().numpy() for i in range(n_dec)])
+        vd = np.stack([toks[i][2][0, h // G].float().cpu().numpy() for i in range(n_dec)])
+        q = np.concatenate([ctx["q"][:, h], qd]).astype(np.float64)
+        k = np.concatenate([ctx["k"][:, h // G], kd]).astype(np.float64)
+        v = np.concatenate([ctx["v"][:, h // G], vd]).astype(np.float64)
+        O.still_chunkwise(q, k, v, None, Wq[h].float().cpu().numpy().astype(np.float64),
+                          Wk[h].float().cpu().numpy().astype(np.float64), w.C, w.W, w.lam, w.scale, w.eps,
+                          rows=(w.N, w.N + n_dec), max_retained=w.max_retained if w.max_retained > 0 else None)
+        units_done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    el = time.perf_counter() - t0
+    # one decoded token of one sequence needs one row from each of the Hq heads
+    return {"value": units_done * n_dec / el / w.Hq, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{units_done} query heads of sequence 0, {n_dec} decoded rows each after the {w.N}-token context, "
+                      f"chunk-wise form with a row range (the prefix's scores, selection and states are recomputed every "
+                      f"time: the oracle has no incremental state), {el:.1f} s; scaled by 1/Hq to tokens/s"}
 
 
 def main() -> int:
