@@ -185,12 +185,13 @@ STILL_API still_status_t still_profile_read(float* ms, int32_t n);
 STILL_API const char* still_profile_kernel_name(int32_t i);
 
 /*
- * Decode state of B sequences that advance in lock step: the salient cache h and the state (s, z) of the
- * cache-routing equation (Sec. 3.3), plus the ring of recent tokens that delayed selection needs.  One
+ * Decode state of B sequences (in lock step, or each at its own token: every region below is sliced per
+ * sequence): the salient cache h and the state (s, z) of the cache-routing equation (Sec. 3.3), plus the ring of
+ * recent tokens that delayed selection needs.  One
  * opaque caller-owned device buffer of still_state_bytes(p) bytes (p->max_tokens = capacity per sequence):
  *   S    float [B, Hq, 2*d_f*(d+1)]   state through the last routed chunk: S (2*d_f x d) then z (2*d_f)
- *   Kret dtype [B, Hq, cap, d]        ([B, Hkv, cap, d] with shared_selection) retained keys in routing order, cap = lambda*ceil(max_tokens/C), or
- *                                     max_retained if that is smaller (+pad)
+ *   Kret dtype [B, Hq, cap, d]        retained keys in routing order ([B, Hkv, cap, d] with shared_selection);
+ *                                     cap = lambda*ceil(max_tokens/C), or max_retained if that is smaller (+pad)
  *   Vret dtype [B, Hq, cap, d]        retained values
  *   sel  int32 [B, Hq, ceil(max_tokens/C), lambda]   token indices kept per routed chunk, -1 in unused slots
  *                                     (for inspection)
