@@ -244,8 +244,9 @@ STILL_API still_status_t still_hybrid_attn_decode_step(const still_params_t* p, 
  *           [0, p->max_tokens) marks a sequence that sits this step out: its state and its row of out_t are
  *           left untouched.
  *   t_max   HOST upper bound of the entries of t_dev, 0 <= t_max < p->max_tokens (p->max_tokens - 1 is always
- *           valid); it only sizes the launch (how many workgroups share one sequence's cache rows), a tight
- *           bound gives the best split.  Entries above t_max still give correct results.
+ *           valid); it sizes the launch (how many workgroups share one sequence's cache rows; whether the routing
+ *           kernel is launched at all), a tight bound gives the best split.  An entry above t_max is a caller
+ *           error: that sequence's result is undefined.
  * All other arguments as for still_hybrid_attn_decode_step.  Returns STILL_ERR_STATE when t_max is outside
  * [0, p->max_tokens).
  */
