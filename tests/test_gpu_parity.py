@@ -438,3 +438,37 @@ def test_global_score_and_selection_overlap(kw):
             exact += int(clear.sum()); total += ncf
     print(f"[gscore {w.dtype} d={w.d} N={w.N}] global score max-abs err {worst:.3e}; chunks with clear gaps {exact}/{total}")
     assert worst <= 5e-5, worst      # the bar of the window-local score
+
+
+def test_128k_context_last_rows_and_selection():
+    """Four times the longest benchmark context (N = 131072 at the config-4 layer shape, 5.4 GB of workspace): 64-bit
+    offsets, grid sizes and the retained prefix of 16 K rows per head hold; the last rows of a unit, which see all
+    of it, match the oracle, and the selection of all 1024 chunks is exact where the gap is clear."""
+    import torch
+
+    w = synth.workload("c4", N=131072)
+    inp = synth.make_inputs(w)
+    dev = "cuda"
+    q, k, v = (synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v"))
+    Wq, Wk = synth.to_torch(inp["Wq"], w.dtype, dev), synth.to_torch(inp["Wk"], w.dtype, dev)
+    out = torch.full_like(q, float("nan"))
+    p = S.make_params(B=w.B, N=w.N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    sel = torch.full((w.B, w.Hq, w.N // w.C, w.lam), -1, dtype=torch.int32, device=dev)
+    S.still_hybrid_attn_fwd(p, q, k, v, None, Wq, None, Wk, None, out, sel_idx=sel, workspace=ws)
+    torch.cuda.synchronize()
+    o = synth.from_torch(out)
+    assert np.all(np.isfinite(o))
+    sel_h = sel.cpu().numpy().astype(np.int64)
+    rows, unit = (w.N - 200, w.N), (0, 21)
+    own = U.oracle_units(w, inp, [unit], rows=(0, 1))[unit]
+    n, clear, bad, tie = U.selection_report(own["rank_score"], own["sel"], sel_h[unit], w.C, w.lam)
+    print(f"[128k] chunks {n}, clear-gap {clear}, mismatch on clear {bad}, on near-ties {tie}")
+    assert bad == 0
+    ref = U.oracle_units(w, inp, [unit], sel=sel_h, rows=rows)[unit]
+    x = o[0, rows[0]:rows[1], unit[1]].astype(np.float64)
+    y = ref["out"][rows[0]:rows[1]]
+    frac = float(np.max(np.abs(x - y) / (BF16_ABS + BF16_ULP * np.abs(y))))
+    print(f"[128k] last rows: bf16-bar-fraction {frac:.3f}")
+    assert frac <= 1.0
