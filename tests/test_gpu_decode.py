@@ -394,3 +394,70 @@ def test_right_padded_prefill_then_decode_at_own_positions(kw, lens, steps):
                 assert err <= 1.0, (b, h, err)
             worst = max(worst, err)
     print(f"[varlen {lens} + {steps} decode steps] worst error measure {worst:.3e}")
+
+
+def test_decode_in_the_benchmark_launch_configuration():
+    """Config 5's launch shape (B = 64 sequences, 32K context, one workgroup per (sequence, head) and no split of the
+    cache rows): the state of two prefilled sequences is replicated 32 times, 130 steps are decoded for all 64, and
+    a sampled unit of a late copy is compared with the oracle."""
+    import torch
+
+    w = synth.workload("c4", B=2)
+    n_prefill, steps, B = w.N, 130, 64
+    n_total = n_prefill + steps
+    inp = synth.make_inputs(w, n_tokens=n_total)
+    dev = "cuda"
+    full = {k: synth.to_torch(inp[k], w.dtype, dev) for k in ("q", "k", "v", "Wq", "Wk")}
+    base = dict(Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype=w.dtype,
+                d_f=w.df, max_tokens=n_total)
+    p2 = S.make_params(B=2, N=1, **base)
+    p64 = S.make_params(B=B, N=1, **base)
+    L2, L64 = S.still_state_layout(p2), S.still_state_layout(p64)
+    st2 = torch.empty(S.still_state_bytes(p2), dtype=torch.uint8, device=dev)
+    q0, k0, v0 = (full[n][:, :n_prefill].contiguous() for n in ("q", "k", "v"))
+    o0 = torch.empty_like(q0)
+    pf = S.make_params(B=2, N=n_prefill, q=q0, k=k0, v=v0, out=o0, **base)
+    ws = torch.empty(S.still_fwd_workspace_bytes(pf), dtype=torch.uint8, device=dev)
+    S.still_hybrid_attn_fwd(pf, q0, k0, v0, None, full["Wq"], None, full["Wk"], None, o0, state_out=st2, workspace=ws)
+    del ws, o0
+    st = torch.empty(S.still_state_bytes(p64), dtype=torch.uint8, device=dev)
+    S.still_state_init(p64, st)
+    es, d, Hq, Hkv = 2, w.d, w.Hq, w.Hkv
+    assert L2.cap == L64.cap and L2.R == L64.R
+    per_seq = {"S": 4 * 2 * d * (d + 1) * Hq, "kret": es * L64.cap * d * Hq, "vret": es * L64.cap * d * Hq,
+               "sel": 4 * L64.n_chunks * w.lam * Hq, "kring": es * L64.R * d * Hkv, "vring": es * L64.R * d * Hkv,
+               "score": 4 * L64.R * Hq}
+    for name, n in per_seq.items():
+        src = st2[getattr(L2, name): getattr(L2, name) + 2 * n].reshape(2, n)
+        st[getattr(L64, name): getattr(L64, name) + B * n].reshape(B // 2, 2, n).copy_(src.unsqueeze(0).expand(B // 2, 2, n))
+    nsplit_rows = (n_prefill // w.C - 1) * w.lam + 2 * w.C
+    assert (1024 + B * Hq - 1) // (B * Hq) == 1 and nsplit_rows > 64      # one workgroup per unit, as in the bench
+    b_probe, h = 37, 21                                                   # a copy of sequence 1
+    got = torch.empty(steps, w.d, dtype=full["q"].dtype, device=dev)
+    for s in range(steps):
+        t = n_prefill + s
+        qt, kt, vt = (full[n][:, t].repeat(B // 2, 1, 1).contiguous() for n in ("q", "k", "v"))
+        ot = torch.empty_like(qt)
+        S.still_hybrid_attn_decode_step(p64, st, t, qt, kt, vt, None, full["Wq"], None, full["Wk"], None, ot)
+        got[s] = ot[b_probe, h]
+    torch.cuda.synchronize()
+    n_routed = max(0, (n_total - 1) // w.C - 1)
+    sel_state = st[L64.sel: L64.sel + B * Hq * L64.n_chunks * w.lam * 4].view(torch.int32)
+    sel_state = sel_state.reshape(B, Hq, L64.n_chunks, w.lam)[b_probe, h, :n_routed].cpu().numpy().astype(np.int64)
+    kv_map = synth.kv_head_map(w)
+    own = O.still_forward_units(inp, kv_map, [(1, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                                rows=(n_prefill, n_total))[(1, h)]
+    gaps = O.selection_gaps(own["rank_score"], w.C, w.lam)
+    sel_full = own["sel"].copy()
+    for c in range(n_routed):
+        assert np.array_equal(sel_state[c], own["sel"][c]) or gaps[c] <= 1e-5, c
+        sel_full[c] = sel_state[c]
+    sel_arr = np.zeros((2, Hq) + sel_full.shape, np.int64)
+    sel_arr[1, h] = sel_full
+    ref = O.still_forward_units(inp, kv_map, [(1, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                                sel=sel_arr, rows=(n_prefill, n_total))[(1, h)]
+    x = synth.from_torch(got).astype(np.float64)
+    y = ref["out"][n_prefill:n_total]
+    err = float(np.max(np.abs(x - y) / (2e-2 + 2.0 ** -8 * np.abs(y))))
+    print(f"[decode B=64] bf16-bar-fraction {err:.3f}")
+    assert np.all(np.isfinite(x)) and err <= 1.0
