@@ -67,32 +67,68 @@ def compulsory_bytes(w: synth.Workload, N: int) -> float:
     return float(w.B * N * w.d * es * (2 * w.Hq + 2 * w.Hkv))
 
 
-def cpu_baseline(w: synth.Workload, inp, budget_s: float = 20.0):
-    """The oracle as it stands, on whole (batch, head) units of the same inputs, until ~budget_s."""
+_POOL = {}   # what the forked oracle workers read: set before the pool starts, inherited copy-on-write
+
+
+def _oracle_worker_init():
+    try:
+        from threadpoolctl import threadpool_limits
+        _POOL["limit"] = threadpool_limits(limits=1)   # one BLAS thread per worker: the pool is the parallelism
+    except Exception:  # pragma: no cover
+        pass
+
+
+def _oracle_unit(unit):
     from oracle import still_oracle as O
 
+    w, inp = _POOL["w"], _POOL["inp"]
+    t0 = time.perf_counter()
+    O.still_forward_units(inp, synth.kv_head_map(w), [unit], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                          max_retained=w.max_retained if w.max_retained > 0 else None,
+                          shared_selection=w.shared_selection)
+    return time.perf_counter() - t0
+
+
+def host_cores() -> int:
+    """Worker processes for the oracle leg: the cores this process may run on, at most 16 (a GPU machine's share)."""
     try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        n = len(os.sched_getaffinity(0))
     except Exception:  # pragma: no cover
-        cores = os.cpu_count() or 1
-    kv_map = synth.kv_head_map(w)
-    units_done, t0 = 0, time.perf_counter()
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
+def cpu_baseline(w: synth.Workload, inp, budget_s: float = 15.0):
+    """The oracle as it stands (numpy float64, chunk-wise form; its per-chunk Python loops are single-threaded) on
+    whole (batch, head) units of the same inputs, one unit at a time per worker process, one worker per host core,
+    until ~budget_s.  Must run before this process touches the GPU: the workers are forked."""
+    import itertools
+    import multiprocessing as mp
+
+    cores = host_cores()
+    _POOL["w"], _POOL["inp"] = w, inp
     order = [(b, h) for h in range(w.Hq) for b in range(w.B)]
-    for (b, h) in order:
-        O.still_forward_units(inp, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                              max_retained=w.max_retained if w.max_retained > 0 else None,
-                              shared_selection=w.shared_selection)
-        units_done += 1
-        if time.perf_counter() - t0 > budget_s:
-            break
-    el = time.perf_counter() - t0
+    done, busy = 0, 0.0
+    t0 = time.perf_counter()
+    pool = mp.get_context("fork").Pool(cores, initializer=_oracle_worker_init)
+    try:
+        for dt in pool.imap_unordered(_oracle_unit, itertools.islice(itertools.cycle(order), 100000)):
+            done += 1
+            busy += dt
+            if time.perf_counter() - t0 > budget_s:
+                break
+    finally:
+        el = time.perf_counter() - t0
+        pool.terminate()
+        pool.join()
     N = inp["q"].shape[1]
     # one unit = N tokens of one of B*Hq heads; the layer needs all B*Hq units for its B*N tokens
-    tok_s = (units_done * N / el) / w.Hq
-    return {"value": tok_s, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{units_done} of {w.B * w.Hq} (batch, head) units of the same inputs, all {N} rows each, "
-                      f"numpy float64 chunk-wise form, {el:.1f} s; scaled by 1/Hq to whole-layer tokens/s"}
+    tok_s = (done * N / el) / w.Hq
+    return {"value": tok_s, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{done} (batch, head) units of the same inputs (of {w.B * w.Hq}; repeated when all are done), all "
+                      f"{N} rows each, numpy float64 chunk-wise form, {cores} forked worker processes with one BLAS "
+                      f"thread each, {el:.1f} s wall, {busy / max(done, 1):.2f} s per unit on one core; scaled by 1/Hq "
+                      f"to whole-layer tokens/s"}
 
 
 def budget_tag(w: synth.Workload) -> str:
@@ -175,6 +211,11 @@ def global_score_bench(args) -> int:
 
 
 def decode_bench(args) -> int:
+    print(json.dumps(decode_record(args, args.steps if args.steps else 0, with_cpu=not args.no_cpu_baseline)))
+    return 0
+
+
+def decode_record(args, steps: int, with_cpu: bool):
     """Config 5: B sequences with a prefilled 32K context, then single-token steps.  The contexts are drawn
     on the GPU (seeded torch generator, same distributions as synth.make_inputs) and prefilled in slices of
     8 sequences through still_hybrid_attn_fwd with state_out; one timed step = one decode step for all B."""
@@ -186,7 +227,7 @@ def decode_bench(args) -> int:
     gen = torch.Generator(device=dev)
     gen.manual_seed(w.seed)
     B, N, Hq, Hkv, d = w.B, w.N, w.Hq, w.Hkv, w.d
-    n_steps = args.steps if args.steps else w.decode_steps
+    n_steps = steps if steps else w.decode_steps
     max_tokens = N + n_steps + args.warmup + 8
     bf = torch.bfloat16
 
@@ -229,7 +270,7 @@ def decode_bench(args) -> int:
         S.still_hybrid_attn_fwd(pf, q, k, v, None, Wq, None, Wk, None, o, state_out=st_slice, workspace=ws)
         torch.cuda.synchronize()
         t_prefill += time.perf_counter() - t0
-        if b0 == 0 and not args.no_cpu_baseline:   # sequence 0 of the batch, for the oracle leg below
+        if b0 == 0 and with_cpu:   # sequence 0 of the batch, for the oracle leg below
             cpu_ctx = {"q": q[0, :, :8].float().cpu().numpy(), "k": k[0].float().cpu().numpy(),
                        "v": v[0].float().cpu().numpy()}
         for name, per_seq in regions:   # every region is [B, ...]: copy the slice's sequences into place
@@ -279,10 +320,11 @@ def decode_bench(args) -> int:
                      "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": bytes_step / (ordinary * 1e-3) / PEAK_HBM,
                      "traffic": args.traffic_bytes, "algorithmic_bytes_per_step": bytes_step},
     }
-    if not args.no_cpu_baseline:
+    if with_cpu:
         rec["cpu_baseline"] = decode_cpu_baseline(w, cpu_ctx, toks, Wq, Wk, args.warmup, n_steps)
-    print(json.dumps(rec))
-    return 0
+    del state, st_slice, toks
+    torch.cuda.empty_cache()
+    return rec
 
 
 def decode_cpu_baseline(w, ctx, toks, Wq, Wk, warmup, n_steps, budget_s: float = 20.0):
@@ -291,14 +333,9 @@ def decode_cpu_baseline(w, ctx, toks, Wq, Wk, warmup, n_steps, budget_s: float =
     sequence 0 until ~budget_s."""
     from oracle import still_oracle as O
 
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:  # pragma: no cover
-        cores = os.cpu_count() or 1
     n_dec = warmup + n_steps
     G = w.Hq // w.Hkv
-    units_done, t0 = 0, time.perf_counter()
+    units_done, t0, c0 = 0, time.perf_counter(), time.process_time()
     for h in range(ctx["q"].shape[1]):
         qd = np.stack([toks[i][0][0, h].float().cpu().numpy() for i in range(n_dec)])
         kd = np.stack([toks[i][1][0, h // G].float().cpu().numpy() for i in range(n_dec)])
@@ -313,11 +350,15 @@ def decode_cpu_baseline(w, ctx, toks, Wq, Wk, warmup, n_steps, budget_s: float =
         if time.perf_counter() - t0 > budget_s:
             break
     el = time.perf_counter() - t0
+    # threads actually kept busy: the Python loops of the oracle run on one core, numpy's BLAS pool adds to it
+    # only inside the matrix products (this leg runs after the GPU was initialised, so it does not fork workers)
+    cores = max(1, int(round((time.process_time() - c0) / el)))
     # one decoded token of one sequence needs one row from each of the Hq heads
     return {"value": units_done * n_dec / el / w.Hq, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"{units_done} query heads of sequence 0, {n_dec} decoded rows each after the {w.N}-token context, "
                       f"chunk-wise form with a row range (the prefix's scores, selection and states are recomputed every "
-                      f"time: the oracle has no incremental state), {el:.1f} s; scaled by 1/Hq to tokens/s"}
+                      f"time: the oracle has no incremental state), one process, {el:.1f} s wall (cores = CPU time / "
+                      f"wall time); scaled by 1/Hq to tokens/s"}
 
 
 def main() -> int:
@@ -335,6 +376,9 @@ def main() -> int:
                     help="second workload: the score over the whole causal prefix and its overlap with the local "
                          "selection (consistency study), at the prefill shape of --config")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true",
+                    help="default (config 4) line only: skip the config-5 decode measurement that fills the "
+                         "decode_c5_* keys of `config`")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -346,13 +390,24 @@ def main() -> int:
               "between GPUs). Run with --gpus 1.", file=sys.stderr)
         return 2
 
-    import torch
     from paper_2602_02180_amd import binding as S
+
+    S.lib()  # fail loudly if the HIP library is missing
+    prefill_run = not (args.calibrate_copy or args.global_score or args.config == "c5")
+    w = inp = cpu_rec = None
+    if prefill_run:
+        w = synth.workload(args.config, max_retained=args.max_retained, shared_selection=args.shared_selection)
+        inp = synth.make_inputs(w)
+        # The oracle leg forks worker processes, so it runs before this process initialises the GPU (a forked copy
+        # of an initialised HIP runtime is not something to rely on); it is outside every timed GPU region anyway.
+        if not args.no_cpu_baseline:
+            cpu_rec = cpu_baseline(w, inp)
+
+    import torch
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
-    S.lib()  # fail loudly if the HIP library is missing
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
@@ -369,8 +424,6 @@ def main() -> int:
         return decode_bench(args)
     if not args.steps:
         args.steps = 20
-    w = synth.workload(args.config, max_retained=args.max_retained, shared_selection=args.shared_selection)
-    inp = synth.make_inputs(w)
     dev = "cuda"
     q, k, v = (synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v"))
     Wq, Wk = synth.to_torch(inp["Wq"], w.dtype, dev), synth.to_torch(inp["Wk"], w.dtype, dev)
@@ -435,8 +488,28 @@ def main() -> int:
                    "kernel_ms_note": "separate untimed pass; transpose_v/transpose_w overlap score_select on a second stream"},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(w, inp)
+    if cpu_rec is not None:
+        rec["cpu_baseline"] = cpu_rec
+    if args.config == "c4" and not args.no_decode and w.max_retained <= 0 and not w.shared_selection:
+        # the benchmark spec names prefill AND decode: the decode step of config 5 (B = 64 sequences behind a 32K context
+        # each, one chunk of 128 steps, one of them routing) rides along as flat keys; the headline fields above
+        # stay those of config 4.  `python bench.py --config c5` prints the full decode record.
+        del q, k, v, out, ws
+        torch.cuda.empty_cache()
+        dargs = argparse.Namespace(**vars(args))
+        dargs.warmup = 3
+        drec = decode_record(dargs, 0, with_cpu=False)
+        rt = drec["config"]["routing_step_ms"]
+        rec["config"].update({
+            "decode_c5_workload": drec["config"]["workload"],
+            "decode_c5_steps": drec["steps"],
+            "decode_c5_ordinary_step_ms": drec["config"]["median_ordinary_step_ms"],
+            "decode_c5_routing_step_ms": float(np.mean(rt)) if rt else None,
+            "decode_c5_tokens_per_s": drec["value"],
+            "decode_c5_bytes_per_step": drec["roofline"]["algorithmic_bytes_per_step"],
+            "decode_c5_hbm_gb_per_s": drec["roofline"]["achieved"],
+            "decode_c5_hbm_frac": drec["roofline"]["frac"],
+        })
     print(json.dumps(rec))
     return 0
 

@@ -262,12 +262,14 @@ STILL_API still_status_t still_hybrid_attn_decode_step_at(const still_params_t* 
  * Score with the score over the whole context): a second workload on the score step, not part of the layer.
  *
  * still_global_score: the score equation with the window set replaced by the whole causal prefix {0..t}, for every
- *   (b, hq, t).  q, k: device, dtype, strided as in `p` (W, C, lambda, d_f are ignored); score_out: device float
- *   [B, Hq, N].  Cost is quadratic in N (two passes over the causal logits).
+ *   (b, hq, t).  q, k: device, dtype, strided as in `p`; score_out: device float [B, Hq, N].  Read from `p`: B, N,
+ *   Hq, Hkv, d (64 or 128), dtype, scale, eps, the q/k strides and the head map; W, C, lambda, d_f and the rest are
+ *   ignored (so fp32 with d = 128, which the prefill restricts, is fine here).  Cost is quadratic in N (two passes
+ *   over the causal logits).
  * still_selection_overlap: for every full chunk, the number of tokens that the Top-lambda sets under two scores
  *   have in common (ties to the lower index, as in the selection step).  score_a, score_b: device float [B, Hq, N]
  *   (for instance score_out of the prefill and of still_global_score); overlap: device int32 [B, Hq, N/C].
- *   overlap / lambda averaged over chunks is the consistency figure.
+ *   overlap / lambda averaged over chunks is the consistency figure.  Read from `p`: B, N, Hq, C (1..128), lambda.
  * Both validate on the host and return the usual codes; neither needs a workspace.
  */
 STILL_API still_status_t still_global_score(const still_params_t* p, const void* q, const void* k, float* score_out,

@@ -11,8 +11,7 @@ import os
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-# STILL_LIB_PATH selects another build of the same library (e.g. an instrumented one); default: in-tree
-LIB_PATH = os.environ.get("STILL_LIB_PATH") or os.path.join(HERE, "libstill.so")
+LIB_PATH = os.path.join(HERE, "libstill.so")   # the in-tree build, nothing else
 
 STILL_OK, STILL_ERR_INVALID_ARG, STILL_ERR_UNSUPPORTED, STILL_ERR_WORKSPACE_TOO_SMALL, STILL_ERR_HIP, \
     STILL_ERR_STATE = range(6)

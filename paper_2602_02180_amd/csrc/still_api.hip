@@ -123,6 +123,33 @@ still_status_t validate_params(const still_params_t* p, bool need_n) {
   return STILL_OK;
 }
 
+// What the two side entry points (global score, selection overlap) need from the problem description: they do not
+// touch the linear branch, so its restrictions (d_f, W, the fp32 LDS budget) do not apply to them.
+still_status_t validate_score_params(const still_params_t* p, bool with_qk) {
+  if (p == nullptr) return fail(STILL_ERR_INVALID_ARG, "params is NULL");
+  if (p->B < 1 || p->Hq < 1 || p->N < 1) return fail(STILL_ERR_INVALID_ARG, "B, Hq, N must be >= 1");
+  if ((int64_t)p->N > (int64_t)1 << 24) return fail(STILL_ERR_UNSUPPORTED, "N = %d too large", p->N);
+  if (p->Hq > still::kMaxHq) return fail(STILL_ERR_UNSUPPORTED, "Hq %d > %d", p->Hq, still::kMaxHq);
+  if (with_qk) {
+    if (p->dtype != STILL_F32 && p->dtype != STILL_BF16) return fail(STILL_ERR_INVALID_ARG, "dtype %d unknown", p->dtype);
+    if (p->Hkv < 1) return fail(STILL_ERR_INVALID_ARG, "Hkv must be >= 1");
+    if (!(p->eps > 0.f)) return fail(STILL_ERR_INVALID_ARG, "eps must be > 0");
+    if (!(p->scale > 0.f)) return fail(STILL_ERR_INVALID_ARG, "scale must be > 0");
+    if (p->d != 64 && p->d != 128) return fail(STILL_ERR_UNSUPPORTED, "d = %d (supported: 64, 128)", p->d);
+    if (p->kv_head_of_q == nullptr) {
+      if (p->Hq % p->Hkv != 0) return fail(STILL_ERR_INVALID_ARG, "Hq %% Hkv != 0 and no kv_head_of_q map given");
+    } else {
+      for (int h = 0; h < p->Hq; ++h)
+        if (p->kv_head_of_q[h] < 0 || p->kv_head_of_q[h] >= p->Hkv)
+          return fail(STILL_ERR_INVALID_ARG, "kv_head_of_q[%d] = %d outside [0, Hkv)", h, p->kv_head_of_q[h]);
+    }
+  } else {
+    if (p->C < 1 || p->C > 128) return fail(STILL_ERR_UNSUPPORTED, "C = %d (supported by the overlap count: 1..128)", p->C);
+    if (p->lambda < 0 || p->lambda > p->C) return fail(STILL_ERR_INVALID_ARG, "lambda %d outside [0, C=%d]", p->lambda, p->C);
+  }
+  return STILL_OK;
+}
+
 still_status_t validate_strides(const still_params_t* p, bool with_g) {
   const int64_t unit = 16 / (int64_t)esize(p->dtype);
   const int64_t s[] = {p->q_sb, p->q_st, p->q_sh, p->k_sb, p->k_st, p->k_sh, p->v_sb, p->v_st, p->v_sh,
@@ -236,16 +263,23 @@ size_t still_fwd_workspace_bytes(const still_params_t* p) {
   return L.total;
 }
 
-still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, const void* k, const void* v,
-                                     const void* g, const void* Wq, const void* bq, const void* Wk,
-                                     const void* bk, void* out, float* score_out, int32_t* sel_idx,
-                                     int32_t sel_idx_is_input, void* state_out, void* workspace,
-                                     size_t workspace_bytes, void* stream_v) {
+}  // extern "C"
+
+namespace {
+
+// The prefill behind both entry points.  two_streams: run the layout kernels on the library's helper stream (created
+// on first use) and record timing events if profiling is on; without it everything is enqueued on `stream` and no
+// host or device object is created.
+still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, const void* v,
+                        const void* g, const void* Wq, const void* bq, const void* Wk,
+                        const void* bk, void* out, float* score_out, int32_t* sel_idx,
+                        int32_t sel_idx_is_input, void* state_out, void* workspace,
+                        size_t workspace_bytes, void* stream_v, bool two_streams, bool static_ws) {
   still_status_t st = validate_params(p, true);
   if (st != STILL_OK) return st;
   st = validate_strides(p, g != nullptr);
   if (st != STILL_OK) return st;
-  if (!q || !k || !v || !Wq || !Wk || !out || !workspace)
+  if (!q || !k || !v || !Wq || !Wk || !out || (!workspace && !static_ws))
     return fail(STILL_ERR_INVALID_ARG, "a required pointer (q, k, v, Wq, Wk, out, workspace) is NULL");
   const void* ptrs[] = {q, k, v, g, Wq, bq, Wk, bk, out, score_out, sel_idx, workspace};
   for (const void* x : ptrs)
@@ -258,11 +292,24 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
     if (!aligned16(state_out)) return fail(STILL_ERR_INVALID_ARG, "state_out is not 16-byte aligned");
     if (p->max_tokens < p->N) return fail(STILL_ERR_INVALID_ARG, "state_out needs max_tokens >= N");
     if ((int64_t)p->max_tokens > (int64_t)1 << 24) return fail(STILL_ERR_UNSUPPORTED, "max_tokens too large");
+    // the state carries the scores of the local span; with injected indices they are only computed on request
+    if (sel_idx_is_input && score_out == nullptr)
+      return fail(STILL_ERR_INVALID_ARG,
+                  "state_out needs the scores: do not combine it with sel_idx_is_input unless score_out is given");
   }
   still_ws_layout_t L;
   compute_layout(p, &L);
-  if (workspace_bytes < L.total)
+  if (static_ws) {
+    return fail(STILL_ERR_UNSUPPORTED, "no built-in workspace in this build");
+  } else if (workspace_bytes < L.total) {
     return fail(STILL_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+  }
+  // timing events are host objects created on demand: the allocation-free entry point records none
+  struct ProfPause {
+    bool was;
+    explicit ProfPause(bool pause) : was(g_prof.on) { if (pause) g_prof.on = false; }
+    ~ProfPause() { g_prof.on = was; }
+  } prof_pause(!two_streams);
 
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
@@ -276,7 +323,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   hipError_t e;
 
   // layout preparation, on the side stream (the caller's stream if it could not be created)
-  SideStream* side = side_stream();
+  SideStream* side = two_streams ? side_stream() : nullptr;
   hipStream_t s2 = stream;
   if (side != nullptr) {
     if (hipEventRecord(side->fork, stream) == hipSuccess && hipStreamWaitEvent(side->s, side->fork, 0) == hipSuccess)
@@ -284,20 +331,33 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
     else
       side = nullptr;
   }
+  // From here on the helper stream may hold work that depends on the caller's stream.  A launch failure must not
+  // leave it dangling (under stream capture an unjoined fork invalidates the capture): every error return below
+  // goes through hip_fail, which joins the helper stream back into `stream` first.
+  bool joined = false;
+  auto join_side = [&]() -> hipError_t {
+    if (side == nullptr || joined) return hipSuccess;
+    joined = true;
+    hipError_t je = hipEventRecord(side->join, s2);
+    if (je == hipSuccess) je = hipStreamWaitEvent(stream, side->join, 0);
+    return je;
+  };
+  auto hip_fail = [&](const char* what, hipError_t err) -> still_status_t {
+    (void)join_side();
+    return fail(STILL_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
+  };
   prof_begin(0, s2);
   still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, ws + L.vfr, N, L.n_pad, p->Hkv, d, C, p->seq_len};
   if ((e = still::launch_transpose_v(tv, p->dtype, B, s2)) != hipSuccess)
-    return fail(STILL_ERR_HIP, "transpose_v: %s", hipGetErrorString(e));
+    return hip_fail("transpose_v", e);
   prof_end(0, s2);
   prof_begin(1, s2);
   still::TransposeWArgs twq{Wq, ws + L.wqt, p->Hq, d, p->d_f};
   still::TransposeWArgs twk{Wk, ws + L.wkt, p->Hq, d, p->d_f};
   if ((e = still::launch_transpose_w(twq, p->dtype, s2)) != hipSuccess ||
       (e = still::launch_transpose_w(twk, p->dtype, s2)) != hipSuccess)
-    return fail(STILL_ERR_HIP, "transpose_w: %s", hipGetErrorString(e));
+    return hip_fail("transpose_w", e);
   prof_end(1, s2);
-  if (side != nullptr && (e = hipEventRecord(side->join, s2)) != hipSuccess)
-    return fail(STILL_ERR_HIP, "side stream: %s", hipGetErrorString(e));
 
   prof_begin(2, stream);
   // Self-Saliency Score + Top-lambda
@@ -314,15 +374,15 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   const bool need_scores = !sel_idx_is_input || score_out != nullptr;
   if (need_scores) {
     if ((e = still::launch_score(sa, p->dtype, d, B, nc, stream)) != hipSuccess)
-      return fail(STILL_ERR_HIP, "score_select: %s", hipGetErrorString(e));
+      return hip_fail("score_select", e);
     if (have_sel && !sel_idx_is_input && group_sel) {
       sa.sel = sel;
       if ((e = still::launch_group_select(sa, B, p->Hkv, stream)) != hipSuccess)
-        return fail(STILL_ERR_HIP, "group_select: %s", hipGetErrorString(e));
+        return hip_fail("group_select", e);
     }
     if (score_out != nullptr) {
       e = hipMemcpyAsync(score_out, score, (size_t)B * p->Hq * N * sizeof(float), hipMemcpyDeviceToDevice, stream);
-      if (e != hipSuccess) return fail(STILL_ERR_HIP, "score copy: %s", hipGetErrorString(e));
+      if (e != hipSuccess) return hip_fail("score copy", e);
     }
   }
   prof_end(2, stream);
@@ -341,11 +401,10 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   ga.cap = L.cap; ga.Hq = p->Hq; ga.d = d; ga.N = N;
   ga.kret = ws + L.kret; ga.vrett = ws + L.vrett;
   if ((e = still::launch_gather(ga, p->dtype, B, stream)) != hipSuccess)
-    return fail(STILL_ERR_HIP, "gather: %s", hipGetErrorString(e));
+    return hip_fail("gather", e);
   prof_end(3, stream);
   // everything below reads the transposed copies
-  if (side != nullptr && (e = hipStreamWaitEvent(stream, side->join, 0)) != hipSuccess)
-    return fail(STILL_ERR_HIP, "side stream: %s", hipGetErrorString(e));
+  if ((e = join_side()) != hipSuccess) return hip_fail("side stream", e);
 
   // NP-Map + chunk linear attention
   still::LaArgs la{};
@@ -370,15 +429,15 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   la.s_final = state_out != nullptr ? reinterpret_cast<float*>(stp + SL.S) : nullptr;
   prof_begin(4, stream);
   if ((e = still::launch_la_state(la, p->dtype, d, B, stream)) != hipSuccess)
-    return fail(STILL_ERR_HIP, "la_state: %s", hipGetErrorString(e));
+    return hip_fail("la_state", e);
   prof_end(4, stream);
   prof_begin(5, stream);
   if ((e = still::launch_la_prefix(la, d, B, stream)) != hipSuccess)
-    return fail(STILL_ERR_HIP, "la_prefix: %s", hipGetErrorString(e));
+    return hip_fail("la_prefix", e);
   prof_end(5, stream);
   prof_begin(6, stream);
   if ((e = still::launch_la_out(la, p->dtype, d, B, stream)) != hipSuccess)
-    return fail(STILL_ERR_HIP, "la_out: %s", hipGetErrorString(e));
+    return hip_fail("la_out", e);
 
   prof_end(6, stream);
   prof_begin(7, stream);
@@ -396,7 +455,7 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
   sx.cap = L.cap; sx.ntiles = (N + still::kSaRows - 1) / still::kSaRows; sx.B_ = B;
   sx.scale = p->scale;
   if ((e = still::launch_sa(sx, p->dtype, d, B, stream)) != hipSuccess)
-    return fail(STILL_ERR_HIP, "sparse_attention: %s", hipGetErrorString(e));
+    return hip_fail("sparse_attention", e);
   prof_end(7, stream);
 
   // decode state standing after token N-1: (S, z) through chunk c_last-2 came from the linear pass above
@@ -414,12 +473,24 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
     sf.cap = SL.cap; sf.ncf = ncf; sf.nchunks = SL.n_chunks; sf.rcap = retained_budget(p);
     sf.shared = p->shared_selection != 0; sf.C = C; sf.seq_len = p->seq_len;
     const int n_routed = nc >= 2 ? nc - 2 : 0;
-    if (!need_scores) return fail(STILL_ERR_INVALID_ARG, "state_out needs the scores: do not combine it with sel_idx_is_input unless score_out is given");
     if ((e = still::launch_state_fill(sf, p->dtype, B, n_routed, stream)) != hipSuccess)
-      return fail(STILL_ERR_HIP, "state_fill: %s", hipGetErrorString(e));
+      return hip_fail("state_fill", e);
   }
   g_err[0] = 0;
   return STILL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, const void* k, const void* v,
+                                     const void* g, const void* Wq, const void* bq, const void* Wk,
+                                     const void* bk, void* out, float* score_out, int32_t* sel_idx,
+                                     int32_t sel_idx_is_input, void* state_out, void* workspace,
+                                     size_t workspace_bytes, void* stream_v) {
+  return fwd_impl(p, q, k, v, g, Wq, bq, Wk, bk, out, score_out, sel_idx, sel_idx_is_input, state_out, workspace,
+                  workspace_bytes, stream_v, /*two_streams=*/true, /*static_ws=*/false);
 }
 
 void still_profile_enable(int32_t on) {
@@ -555,7 +626,7 @@ still_status_t still_hybrid_attn_decode_step_at(const still_params_t* p, void* s
 
 still_status_t still_global_score(const still_params_t* p, const void* q, const void* k, float* score_out,
                                   void* stream_v) {
-  still_status_t st = validate_params(p, true);
+  still_status_t st = validate_score_params(p, true);
   if (st != STILL_OK) return st;
   {
     const int64_t unit = 16 / (int64_t)esize(p->dtype);
@@ -581,7 +652,7 @@ still_status_t still_global_score(const still_params_t* p, const void* q, const 
 
 still_status_t still_selection_overlap(const still_params_t* p, const float* score_a, const float* score_b,
                                        int32_t* overlap, void* stream_v) {
-  still_status_t st = validate_params(p, true);
+  still_status_t st = validate_score_params(p, false);
   if (st != STILL_OK) return st;
   if (!score_a || !score_b || !overlap) return fail(STILL_ERR_INVALID_ARG, "a required pointer (score_a, score_b, overlap) is NULL");
   if ((reinterpret_cast<uintptr_t>(score_a) & 3) || (reinterpret_cast<uintptr_t>(score_b) & 3) ||

@@ -4,10 +4,11 @@ dtype-rounded inputs.
 Bars (from the benchmark spec):
   * selected-index sets bit-exact wherever the oracle's gap between the lambda-th and the
     (lambda+1)-th score exceeds 1e-5; the mismatch rate among near-ties is printed;
-  * outputs within 1e-4 relative on fp32 (max-normalised and per row); on bf16 within 2e-2 absolute
-    plus one bf16 ulp (2^-8 relative) of the reference value: the synthetic values reach |y| ~ 20,
-    where merely storing the exact result in bf16 already moves it by up to 2^-9 * 20 = 0.04, so a
-    purely absolute 2e-2 cannot hold for any bf16 output; the plain max-abs error is printed too.
+  * outputs within 1e-4 relative on fp32 (max-normalised and per row); on bf16 within the stated
+    2e-2 absolute wherever |ref| < 4, and elsewhere within 2e-2 plus the half unit in the last
+    place that storing ANY result in bf16 adds (tests/gpu_util.py: assert_bf16_bar, the one place
+    where that bar is written down); the plain max-abs error and the share of elements under the
+    plain bar are printed too.
 Output parity is run twice: with the oracle's indices injected into the HIP path (isolates the
 gather / linear / softmax / merge kernels) and end to end, where the oracle is re-run with the
 HIP path's own indices after those were checked to be a valid Top-lambda set.
@@ -22,8 +23,6 @@ from tests import gpu_util as U
 pytestmark = pytest.mark.gpu
 
 F32_REL = 1e-4
-BF16_ABS = 2e-2
-BF16_ULP = 2.0 ** -8
 
 
 def small(name, **kw):
@@ -37,7 +36,8 @@ def all_units(w):
 
 
 def check_outputs(w, hip, ref_units, units, what):
-    worst_rel = worst_row = worst_abs = worst_excess = 0.0
+    worst_rel = worst_row = worst_abs = 0.0
+    reports = []
     for (b, h) in units:
         ref = ref_units[(b, h)]
         r0, r1 = ref["rows"]
@@ -47,13 +47,15 @@ def check_outputs(w, hip, ref_units, units, what):
         worst_rel = max(worst_rel, U.rel_err(x, y))
         worst_row = max(worst_row, U.row_rel_err(x, y))
         worst_abs = max(worst_abs, float(np.max(np.abs(x - y))))
-        worst_excess = max(worst_excess, float(np.max(np.abs(x - y) / (BF16_ABS + BF16_ULP * np.abs(y)))))
-    print(f"[{w.name}:{what}] out: max-rel {worst_rel:.3e} row-rel {worst_row:.3e} max-abs {worst_abs:.3e} "
-          f"bf16-bar-fraction {worst_excess:.3f}")
+        if w.dtype != "f32":
+            reports.append(U.bf16_bar_report(x, y))
+    print(f"[{w.name}:{what}] out: max-rel {worst_rel:.3e} row-rel {worst_row:.3e} max-abs {worst_abs:.3e}")
     if w.dtype == "f32":
         assert worst_rel <= F32_REL and worst_row <= F32_REL, (worst_rel, worst_row)
     else:
-        assert worst_excess <= 1.0, (worst_abs, worst_excess)
+        rep = U.merge_bf16_reports(reports)
+        print(f"[{w.name}:{what}] bf16 bar: {U.bf16_report_text(rep)}")
+        assert rep["bar_fraction"] <= 1.0, rep
 
 
 def check_terms(w, hip, ref_units, units, what):
@@ -314,6 +316,37 @@ def test_back_to_back_calls_on_a_user_stream_are_ordered():
         assert np.array_equal(got, lone[i]), f"call {i} differs from the lone call"
 
 
+def test_rejected_call_enqueues_nothing():
+    """state_out + injected indices without score_out is an argument error: the call must return INVALID_ARG with
+    nothing enqueued, i.e. a sentinel-filled `out` (and state) stays untouched; the same call with score_out works."""
+    import torch
+
+    w = small("reject", N=512, Hq=2, Hkv=1, dtype="f32")
+    inp = synth.make_inputs(w, seed=41)
+    dev = "cuda"
+    ten = {n: synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v", "Wq", "Wk")}
+    out = torch.full_like(ten["q"], -123.0)
+    p = S.make_params(B=1, N=w.N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, d_f=w.df, q=ten["q"], k=ten["k"], v=ten["v"], out=out, max_tokens=w.N)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    state = torch.full((S.still_state_bytes(p),), 0x5A, dtype=torch.uint8, device=dev)
+    good = U.run_hip(w, inp, want_terms=False)
+    sel = torch.from_numpy(good["sel"].astype(np.int32)).to(dev)
+    torch.cuda.synchronize()
+    with pytest.raises(S.StillError) as e:
+        S.still_hybrid_attn_fwd(p, ten["q"], ten["k"], ten["v"], None, ten["Wq"], None, ten["Wk"], None, out,
+                                sel_idx=sel, sel_idx_is_input=True, state_out=state, workspace=ws)
+    assert e.value.code == S.STILL_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert bool(torch.all(out == -123.0)), "a rejected call wrote to out"
+    assert bool(torch.all(state == 0x5A)), "a rejected call wrote to the state"
+    score = torch.empty((1, w.Hq, w.N), dtype=torch.float32, device=dev)
+    S.still_hybrid_attn_fwd(p, ten["q"], ten["k"], ten["v"], None, ten["Wq"], None, ten["Wk"], None, out,
+                            score_out=score, sel_idx=sel, sel_idx_is_input=True, state_out=state, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(synth.from_torch(out), good["out"])
+
+
 def test_prefill_call_replays_from_a_hip_graph():
     """The call enqueues kernels, a device-to-device copy and event fork/join only, so it can be captured (after one
     eager call has created the library's helper stream).  Every replay must reproduce the eager result, also after
@@ -398,6 +431,7 @@ def test_profile_modes_report_kernel_times():
     dict(dtype="bf16", d=128, N=1500, Hq=4, Hkv=2, B=2, C=128, W=128),
     dict(dtype="bf16", d=64, N=129, Hq=2, Hkv=1),
     dict(dtype="f32", d=64, N=1, Hq=1, Hkv=1),
+    dict(dtype="f32", d=128, N=400, Hq=2, Hkv=1, C=128, W=128),     # a shape the prefill's linear branch restricts
 ], ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
 def test_global_score_and_selection_overlap(kw):
     """Score over the whole causal prefix against the oracle's two-softmax form, then the per-chunk overlap of the
@@ -413,13 +447,19 @@ def test_global_score_and_selection_overlap(kw):
                       dtype=w.dtype, q=q, k=k)
     glob = torch.full((w.B, w.Hq, w.N), float("nan"), dtype=torch.float32, device=dev)
     S.still_global_score(p, q, k, glob)
-    local = torch.from_numpy(U.run_hip(w, inp, want_terms=False)["score"]).to(dev)
+    kv = synth.kv_head_map(w)
+    if not (w.dtype == "f32" and w.d == 128 and w.C == 128):
+        local = torch.from_numpy(U.run_hip(w, inp, want_terms=False)["score"]).to(dev)
+    else:                              # a shape only the side entry points take: local scores from the oracle
+        loc = np.stack([np.stack([O.self_saliency_scores(inp["q"][b, :, h].astype(np.float64),
+                                                         inp["k"][b, :, kv[h]].astype(np.float64), w.W, w.scale, w.eps)
+                                  for h in range(w.Hq)]) for b in range(w.B)])
+        local = torch.from_numpy(loc.astype(np.float32)).to(dev)
     ncf = w.N // w.C
     ov = torch.full((w.B, w.Hq, max(ncf, 1)), -1, dtype=torch.int32, device=dev)
     S.still_selection_overlap(p, local, glob, ov)
     torch.cuda.synchronize()
     glob_h, ov_h, local_h = glob.cpu().numpy(), ov.cpu().numpy(), local.cpu().numpy()
-    kv = synth.kv_head_map(w)
     worst, exact, total = 0.0, 0, 0
     for b in range(w.B):
         for h in range(w.Hq):
@@ -469,6 +509,4 @@ def test_128k_context_last_rows_and_selection():
     ref = U.oracle_units(w, inp, [unit], sel=sel_h, rows=rows)[unit]
     x = o[0, rows[0]:rows[1], unit[1]].astype(np.float64)
     y = ref["out"][rows[0]:rows[1]]
-    frac = float(np.max(np.abs(x - y) / (BF16_ABS + BF16_ULP * np.abs(y))))
-    print(f"[128k] last rows: bf16-bar-fraction {frac:.3f}")
-    assert frac <= 1.0
+    U.assert_bf16_bar(x, y, "128k last rows")

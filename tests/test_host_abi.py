@@ -104,6 +104,41 @@ def test_fwd_rejects_null_and_misaligned_pointers_without_launching():
     assert rc == S.STILL_ERR_WORKSPACE_TOO_SMALL
 
 
+def test_state_export_with_injected_indices_needs_scores_and_is_rejected_before_any_launch():
+    """state_out carries the scores of the local span; with injected indices the scores are only computed when
+    score_out is given.  The combination without score_out is refused by the host checks (fake pointers: a launch
+    would fault), as the header promises for every failure."""
+    p = params(max_tokens=1024)
+    p.q_st = p.k_st = p.v_st = p.o_st = 64
+    lib = S.lib()
+    null, fake = ctypes.c_void_p(None), ctypes.c_void_p(0x1000)
+    rc = lib.still_hybrid_attn_fwd(ctypes.byref(p), fake, fake, fake, null, fake, null, fake, null, fake, null,
+                                   fake, 1, fake, fake, 1 << 40, null)
+    assert rc == S.STILL_ERR_INVALID_ARG and "score" in S.still_last_error()
+
+
+def test_side_entry_points_validate_only_what_they_read():
+    """The global score and the overlap count do not touch the linear branch: its restrictions (d_f == d, W <= 128,
+    no fp32 with d = C = 128) must not be applied to them.  Null pointers make the calls stop right after the
+    parameter checks, with the pointer message."""
+    lib = S.lib()
+    null = ctypes.c_void_p(None)
+    for kw in (dict(dtype="f32", d=128, C=128), dict(d_f=32), dict(W=4096), dict(C=32, lam=0)):
+        p = params(**kw)
+        p.q_st = p.k_st = kw.get("d", 64)
+        rc = lib.still_global_score(ctypes.byref(p), null, null, null, null)
+        assert rc == S.STILL_ERR_INVALID_ARG and "pointer" in S.still_last_error(), (kw, S.still_last_error())
+    p = params(C=32, lam=7, d_f=5, W=999)
+    rc = lib.still_selection_overlap(ctypes.byref(p), null, null, null, null)
+    assert rc == S.STILL_ERR_INVALID_ARG and "pointer" in S.still_last_error()
+    for kw, code in ((dict(d=96), S.STILL_ERR_UNSUPPORTED), (dict(eps=0.0), S.STILL_ERR_INVALID_ARG)):
+        p = params(**kw)
+        assert lib.still_global_score(ctypes.byref(p), null, null, null, null) == code
+    for kw, code in ((dict(C=256), S.STILL_ERR_UNSUPPORTED), (dict(lam=65), S.STILL_ERR_INVALID_ARG)):
+        p = params(**kw)
+        assert lib.still_selection_overlap(ctypes.byref(p), null, null, null, null) == code
+
+
 def test_public_header_is_plain_c_and_matches_the_binding(tmp_path):
     """include/still.h compiles as C99 on its own, and the struct sizes the C compiler sees are the ones the ctypes
     binding marshals (a field added on one side only would shift every later field)."""

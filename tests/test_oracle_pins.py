@@ -326,6 +326,36 @@ def test_uniform_scores_select_lowest_indices():
     assert gaps[1] == 0.0 and gaps[0] > 0
 
 
+def test_selection_gap_and_chunk_quota_literals():
+    """Hand-written values (no formula of the oracle is repeated here).  The gap of a chunk is the score of its
+    last kept token minus the score of its best dropped token; a budget on the retained tokens is served chunk by
+    chunk in order (Sec. 3.3 delayed selection; Sec. 4 long-context settings for the budget)."""
+    # one chunk of four tokens, two kept
+    assert O.selection_gaps(np.array([5.0, 3.0, 3.0, 1.0]), 4, 2).tolist() == [0.0]        # tie across the cut
+    assert O.selection_gaps(np.array([5.0, 4.0, 2.0, 1.0]), 4, 2).tolist() == [2.0]        # 4 kept, 2 dropped
+    assert O.selection_gaps(np.array([1.0, 5.0, 2.0, 4.0]), 4, 2).tolist() == [2.0]        # order in the chunk is irrelevant
+    assert O.selection_gaps(np.array([5.0, 4.0, 2.0, 1.0]), 4, 1).tolist() == [1.0]        # 5 kept, 4 dropped
+    assert O.selection_gaps(np.array([5.0, 4.0, 2.0, 1.0]), 4, 3).tolist() == [1.0]        # 2 kept, 1 dropped
+    # nothing kept / everything kept: no cut, the gap is +inf
+    assert O.selection_gaps(np.array([5.0, 4.0, 2.0, 1.0]), 4, 0).tolist() == [np.inf]
+    assert O.selection_gaps(np.array([5.0, 4.0, 2.0, 1.0]), 4, 4).tolist() == [np.inf]
+    # two chunks, the trailing partial chunk (one token) is never ranked
+    s = np.array([9.0, 7.0, 4.0, 1.0, 2.0, 8.0, 3.0, 6.5, 100.0])
+    assert O.selection_gaps(s, 4, 2).tolist() == [3.0, 3.5]                                # 7-4, 6.5-3
+    # budget of three tokens, two per chunk: chunk 0 keeps two, chunk 1 keeps one, chunk 2 none
+    s3 = np.concatenate([s[:8], [4.0, 3.0, 2.0, 1.0]])
+    assert [O.chunk_quota(c, 2, 3) for c in range(4)] == [2, 1, 0, 0]
+    assert [O.chunk_quota(c, 2, None) for c in range(3)] == [2, 2, 2]
+    assert [O.chunk_quota(c, 2, 0) for c in range(2)] == [0, 0]
+    assert [O.chunk_quota(c, 3, 7) for c in range(4)] == [3, 3, 1, 0]
+    assert O.selection_gaps(s3, 4, 2, 3).tolist() == [3.0, 1.5, np.inf]                     # chunk 1: 8 kept, 6.5 best dropped
+    sel = O.select_top_lambda(s3, 4, 2, 3)
+    assert sel.tolist() == [[0, 1], [5, -1], [-1, -1]]
+    # the gap and the selection agree: the kept set is exactly the tokens above the cut
+    sel_all = O.select_top_lambda(s, 4, 2)
+    assert sel_all.tolist() == [[0, 1], [5, 7]]
+
+
 # --------------------------------------------------------------------------- causality
 @pytest.mark.parametrize("form", [O.still_recurrent, O.still_chunkwise])
 def test_appending_tokens_never_changes_earlier_rows(form):
