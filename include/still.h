@@ -164,6 +164,29 @@ STILL_API still_status_t still_hybrid_attn_fwd(const still_params_t* p,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same prefill for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture that has no buffer to hand, tight serving loops, harnesses that forbid hipMalloc.  It is
+ * still_hybrid_attn_fwd with the workspace taken from a fixed array of STILL_STATIC_WORKSPACE_BYTES that is part of
+ * the library's device code (every GPU the library runs on holds one copy until the process ends), with every kernel
+ * on `stream` (no helper stream, no timing events): the call creates no stream, event or allocation of any kind.
+ * Same arguments, same results (bit for bit: the same kernels run in the same order).
+ *
+ *   - Problems whose still_fwd_workspace_bytes(p) exceeds STILL_STATIC_WORKSPACE_BYTES are refused with
+ *     STILL_ERR_WORKSPACE_TOO_SMALL before anything is enqueued (use still_hybrid_attn_fwd for those).
+ *   - All calls on one GPU share that GPU's array: two calls whose kernels may overlap in time (different streams,
+ *     different host threads) race; calls on one stream are ordered and safe.  Nothing in the array has to start at
+ *     zero and nothing in it survives a call.
+ *   - The first call on a device looks up the array's address (hipGetSymbolAddress); make that call outside a
+ *     stream capture.
+ */
+#define STILL_STATIC_WORKSPACE_BYTES (32u << 20)
+STILL_API still_status_t still_hybrid_attn_fwd_static(const still_params_t* p,
+                                            const void* q, const void* k, const void* v, const void* g,
+                                            const void* Wq, const void* bq, const void* Wk, const void* bk,
+                                            void* out, float* score_out, int32_t* sel_idx,
+                                            int32_t sel_idx_is_input, void* state_out, void* stream);
+
+/*
  * Optional per-kernel timing of still_hybrid_attn_fwd (used by the benchmark to time the dominant kernel
  * on the stream it is launched on).  While enabled on the calling thread, every prefill call records HIP
  * events (host objects created lazily, one ring of 64 sets per thread) around each of its kernels; it does

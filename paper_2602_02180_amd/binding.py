@@ -73,6 +73,8 @@ def lib() -> ct.CDLL:
         L.still_hybrid_attn_fwd.restype = ct.c_int
         L.still_hybrid_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ct.c_int32, vp, vp,
                                             ct.c_size_t, vp]
+        L.still_hybrid_attn_fwd_static.restype = ct.c_int
+        L.still_hybrid_attn_fwd_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ct.c_int32, vp, vp]
         L.still_state_bytes.restype = ct.c_size_t
         L.still_state_bytes.argtypes = [pp]
         L.still_state_layout.restype = ct.c_int
@@ -177,6 +179,21 @@ def still_hybrid_attn_fwd(p: StillParams, q, k, v, g, Wq, bq, Wk, bk, out, score
         ct.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(out),
         _ptr(score_out), _ptr(sel_idx), 1 if sel_idx_is_input else 0, _ptr(state_out), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), stream.cuda_stream))
+
+
+STILL_STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def still_hybrid_attn_fwd_static(p: StillParams, q, k, v, g, Wq, bq, Wk, bk, out, score_out=None, sel_idx=None,
+                                 sel_idx_is_input: bool = False, state_out=None, stream=None) -> None:
+    """The prefill with the library's built-in scratch array as workspace (allocates nothing)."""
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(lib().still_hybrid_attn_fwd_static(
+        ct.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(out),
+        _ptr(score_out), _ptr(sel_idx), 1 if sel_idx_is_input else 0, _ptr(state_out), stream.cuda_stream))
 
 
 def still_state_bytes(p: StillParams) -> int:

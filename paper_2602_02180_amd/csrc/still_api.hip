@@ -6,6 +6,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "still_kernels.h"
 
 namespace {
@@ -267,6 +269,34 @@ size_t still_fwd_workspace_bytes(const still_params_t* p) {
 
 namespace {
 
+// Scratch of the allocation-free entry point: one fixed array in device memory per GPU, part of the library's code
+// object (it exists from the moment the library is loaded on a device until the process ends).  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the address each device holds it at is looked up once per
+// device and kept here.
+constexpr size_t kStaticWorkspaceBytes = (size_t)STILL_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+still_status_t static_workspace(void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(STILL_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(STILL_ERR_UNSUPPORTED, "device index %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* sym = nullptr;
+    e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || sym == nullptr)
+      return fail(STILL_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = sym;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return STILL_OK;
+}
+
 // The prefill behind both entry points.  two_streams: run the layout kernels on the library's helper stream (created
 // on first use) and record timing events if profiling is on; without it everything is enqueued on `stream` and no
 // host or device object is created.
@@ -300,7 +330,12 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   still_ws_layout_t L;
   compute_layout(p, &L);
   if (static_ws) {
-    return fail(STILL_ERR_UNSUPPORTED, "no built-in workspace in this build");
+    if (L.total > kStaticWorkspaceBytes)
+      return fail(STILL_ERR_WORKSPACE_TOO_SMALL,
+                  "this problem needs %zu bytes of workspace, the built-in scratch array holds %zu: use "
+                  "still_hybrid_attn_fwd with a caller-owned workspace", L.total, kStaticWorkspaceBytes);
+    st = static_workspace(&workspace);
+    if (st != STILL_OK) return st;
   } else if (workspace_bytes < L.total) {
     return fail(STILL_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
   }
@@ -491,6 +526,14 @@ still_status_t still_hybrid_attn_fwd(const still_params_t* p, const void* q, con
                                      size_t workspace_bytes, void* stream_v) {
   return fwd_impl(p, q, k, v, g, Wq, bq, Wk, bk, out, score_out, sel_idx, sel_idx_is_input, state_out, workspace,
                   workspace_bytes, stream_v, /*two_streams=*/true, /*static_ws=*/false);
+}
+
+still_status_t still_hybrid_attn_fwd_static(const still_params_t* p, const void* q, const void* k, const void* v,
+                                            const void* g, const void* Wq, const void* bq, const void* Wk,
+                                            const void* bk, void* out, float* score_out, int32_t* sel_idx,
+                                            int32_t sel_idx_is_input, void* state_out, void* stream_v) {
+  return fwd_impl(p, q, k, v, g, Wq, bq, Wk, bk, out, score_out, sel_idx, sel_idx_is_input, state_out, nullptr, 0,
+                  stream_v, /*two_streams=*/false, /*static_ws=*/true);
 }
 
 void still_profile_enable(int32_t on) {

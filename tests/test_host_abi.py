@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_symbols()
     assert {"still_hybrid_attn_fwd", "still_hybrid_attn_decode_step", "still_fwd_workspace_bytes",
             "still_state_bytes", "still_state_init", "still_last_error", "still_version",
-            "still_hybrid_attn_decode_step_at"} <= set(names)
+            "still_hybrid_attn_decode_step_at", "still_hybrid_attn_fwd_static"} <= set(names)
     lib = S.lib()
     for n in names:
         assert hasattr(lib, n), n
