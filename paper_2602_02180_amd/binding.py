@@ -62,6 +62,12 @@ def lib() -> ct.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2602_02180_amd.build`")
+        # torch first: its wheel carries its own copy of the HIP runtime, and the process must end up with ONE
+        # runtime.  Loaded after torch, this library's runtime dependency resolves to the copy torch brought;
+        # loaded before it, the system copy comes in as a second runtime and every launch from here fails with
+        # "no ROCm-capable device".  Importing torch does not touch the GPU.
+        import torch  # noqa: F401
+
         L = ct.CDLL(LIB_PATH)
         vp, pp = ct.c_void_p, ct.POINTER(StillParams)
         L.still_version.restype = ct.c_int32
