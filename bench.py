@@ -3,7 +3,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c4] [--no-cpu-baseline]
 
-One step = one still_hybrid_attn_fwd call (score + selection + gather + NP-Map linear attention +
+One step = one still_hybrid_attn_fwd call (score + selection + gather + NP-Map linear-attention state scan +
 sparse softmax + merge) over one batch of seeded synthetic input that is already resident in HBM.
 Prints ONE JSON line: whole-job tokens/s, the roofline record of the dominant kernel (the sparse
 softmax + merge kernel, timed with HIP events inside the timed steps on the stream it runs on), and
@@ -45,6 +45,13 @@ def sparse_branch_flops(w: synth.Workload, N: int) -> float:
         n_ret = np.minimum(n_ret, w.max_retained)
     n_loc = t - np.maximum(0, c - 1) * w.C + 1
     return float(4 * w.d * np.sum(n_ret + n_loc)) * w.B * w.Hq
+
+
+def linear_rows_flops(w: synth.Workload, N: int) -> float:
+    """Algorithmic flops of the rows' linear terms, which the same kernel computes: NP-Map of q (2 d d_f) and
+    phi_q S (2 * 2 d_f * d) for every row that has a state (chunks >= 2)."""
+    rows = max(0, N - 2 * w.C)
+    return float((2 * w.d * w.df + 2 * (2 * w.df) * w.d) * rows) * w.B * w.Hq
 
 
 def path_flops(w: synth.Workload, N: int) -> float:
@@ -466,13 +473,14 @@ def main() -> int:
     tok_s = w.B * N * args.steps / el
     dom = "sparse_attn_merge"
     dom_s = dom_ms * 1e-3
-    flops = sparse_branch_flops(w, N)
+    flops = sparse_branch_flops(w, N) + linear_rows_flops(w, N)
     peak = PEAK_MFMA[w.dtype]
     roofline = {"bound": "mfma", "kernel": dom, "achieved": flops / dom_s / 1e12, "peak": peak / 1e12,
                 "unit": "TFLOP/s", "frac": flops / dom_s / peak,
                 "traffic": args.traffic_bytes if args.traffic_bytes is not None else
                 (MEASURED_TRAFFIC.get(args.config) if w.max_retained <= 0 and not w.shared_selection else None),
-                "algorithmic_flops_per_launch": flops, "avg_launch_ms": dom_ms}
+                "algorithmic_flops_per_launch": flops, "sparse_branch_flops": sparse_branch_flops(w, N),
+                "linear_rows_flops": linear_rows_flops(w, N), "avg_launch_ms": dom_ms}
     rec = {
         "metric": "hybrid-attn fwd tokens/s @32K, Llama-3-8B layer shape" if args.config == "c4"
         else f"hybrid-attn fwd tokens/s ({args.config})",

@@ -51,7 +51,7 @@ typedef enum { STILL_F32 = 0, STILL_BF16 = 1 } still_dtype_t;
  * number lambda, small constant eps; plus what the paper leaves implicit: batch, GQA head map, the
  * score window W of the window-set equation, and the logit scale).
  *
- * Supported by the kernels: d in {64,128}; d_f == d; C in {64,128}; 1 <= W <= 128; 0 <= lambda <= C;
+ * Supported by the kernels (both dtypes): d in {64,128}; d_f == d; C in {64,128}; 1 <= W <= 128; 0 <= lambda <= C;
  * Hq <= 128; Hq % Hkv == 0 when kv_head_of_q is NULL.  N >= 1 need not be a multiple of C: the trailing
  * partial chunk is never ranked.  Anything else returns STILL_ERR_UNSUPPORTED.
  *
@@ -80,6 +80,9 @@ typedef struct still_params {
                                     still has one list per query head, the lists of a group being equal.  A
                                     decode state then holds the retained rows once per kv head, and a decode
                                     step reads each of them once for the whole group.                        */
+  int32_t emit_terms;            /* inspection hook, normally 0.  1: the prefill also leaves the linear-branch
+                                    terms of every row in the workspace (regions n_la, d_la of the layout), which
+                                    then needs room for them; the results are the same either way.             */
   int64_t q_sb, q_st, q_sh;      /* q   [B, N, Hq,  d]                                                     */
   int64_t k_sb, k_st, k_sh;      /* k   [B, N, Hkv, d]                                                     */
   int64_t v_sb, v_st, v_sh;      /* v   [B, N, Hkv, d]                                                     */
@@ -105,11 +108,12 @@ typedef struct still_ws_layout {
   size_t kret;     /* dtype   [B, Hq, cap, d]                    retained keys in routing order            */
   size_t vrett;    /* dtype   [B, Hq, d, cap]                    retained values, transposed               */
   size_t wqt;      /* dtype   [Hq, d_f, d]                       Wq transposed                             */
-  size_t wkt;      /* dtype   [Hq, d_f, d]                       Wk transposed                             */
+  size_t wkf;      /* dtype   [Hq, d_f * d]                      Wk transposed, in matrix-operand order    */
   size_t seg;      /* float   [B, Hq, nseg, 2*d_f*(d+1)]         per-segment linear-attention states       */
-  size_t n_la;     /* float   [B, Hq, N, d]                      gated linear-branch numerator N_LA        */
-  size_t d_la;     /* float   [B, Hq, N]                         linear-branch normaliser D_LA             */
-  size_t phik;     /* bytes   [B, Hq, nseg, seg_chunks][unit]    staged key features of the state pass     */
+  size_t snap;     /* dtype   [B, Hq, ceil(N/C), d, 2*d_f]       S^T through chunk c-2, for the rows of chunk c */
+  size_t zsnap;    /* float   [B, Hq, ceil(N/C), 2*d_f]          z through chunk c-2                       */
+  size_t n_la;     /* float   [B, Hq, N, d]                      gated linear-branch numerator N_LA (emit_terms) */
+  size_t d_la;     /* float   [B, Hq, N]                         linear-branch normaliser D_LA (emit_terms) */
   size_t vfr;      /* dtype   [B, Hkv, Npad * d]                 v in the operand order of the state update */
   size_t total;    /* bytes needed                                                                         */
   int32_t n_pad;   /* Npad                                                                                 */
@@ -287,8 +291,7 @@ STILL_API still_status_t still_hybrid_attn_decode_step_at(const still_params_t* 
  * still_global_score: the score equation with the window set replaced by the whole causal prefix {0..t}, for every
  *   (b, hq, t).  q, k: device, dtype, strided as in `p`; score_out: device float [B, Hq, N].  Read from `p`: B, N,
  *   Hq, Hkv, d (64 or 128), dtype, scale, eps, the q/k strides and the head map; W, C, lambda, d_f and the rest are
- *   ignored (so fp32 with d = 128, which the prefill restricts, is fine here).  Cost is quadratic in N (two passes
- *   over the causal logits).
+ *   ignored.  Cost is quadratic in N (two passes over the causal logits).
  * still_selection_overlap: for every full chunk, the number of tokens that the Top-lambda sets under two scores
  *   have in common (ties to the lower index, as in the selection step).  score_a, score_b: device float [B, Hq, N]
  *   (for instance score_out of the prefill and of still_global_score); overlap: device int32 [B, Hq, N/C].

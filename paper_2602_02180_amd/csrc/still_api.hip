@@ -34,7 +34,7 @@ struct Profile {
 };
 thread_local Profile g_prof;
 const char* const kSlotNames[STILL_PROFILE_SLOTS] = {"transpose_v", "transpose_w", "score_select", "gather",
-                                                     "la_state",    "la_prefix",   "la_out",       "sparse_attn_merge"};
+                                                     "la_sums",     "la_prefix",   "la_states",    "sparse_attn_merge"};
 
 void prof_begin(int slot, hipStream_t stream) {
   if (!g_prof.on || (g_prof.last_only && slot != STILL_PROFILE_SLOTS - 1)) return;
@@ -119,8 +119,6 @@ still_status_t validate_params(const still_params_t* p, bool need_n) {
   if (p->d_f != p->d) return fail(STILL_ERR_UNSUPPORTED, "d_f = %d (supported: d_f == d)", p->d_f);
   if (p->C != 64 && p->C != 128) return fail(STILL_ERR_UNSUPPORTED, "C = %d (supported: 64, 128)", p->C);
   if (p->W > 128) return fail(STILL_ERR_UNSUPPORTED, "W = %d (supported: 1..128)", p->W);
-  if (p->dtype == STILL_F32 && p->d == 128 && p->C == 128)
-    return fail(STILL_ERR_UNSUPPORTED, "fp32 with d = 128 and C = 128 exceeds the LDS budget of the linear branch");
   if (need_n && (int64_t)p->N > (int64_t)1 << 24) return fail(STILL_ERR_UNSUPPORTED, "N = %d too large", p->N);
   return STILL_OK;
 }
@@ -182,6 +180,9 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   int64_t G = (nc * B * Hq + 255) / 256;   // one workgroup per CU at the size of the chip
   if (G < 2) G = 2;
   if (G > nc) G = nc;
+  // the scan walks in rounds of RT tokens: a segment is a whole number of rounds
+  const int64_t per_round = still::la_round_tokens((int)es, (int)d) / p->C;
+  if (per_round > 1) G = (G + per_round - 1) / per_round * per_round;
   const int64_t nseg = (nc + G - 1) / G;
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -195,11 +196,12 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   L->kret = take((size_t)B * Hq * cap * d * es);
   L->vrett = take((size_t)B * Hq * cap * d * es);
   L->wqt = take((size_t)Hq * df * d * es);
-  L->wkt = take((size_t)Hq * df * d * es);
+  L->wkf = take((size_t)Hq * df * d * es);
   L->seg = take((size_t)B * Hq * nseg * (2 * df * (d + 1)) * 4);
-  L->n_la = take((size_t)B * Hq * N * d * 4);
-  L->d_la = take((size_t)B * Hq * N * 4);
-  L->phik = take(nseg > 1 ? (size_t)(B * Hq * nseg * G * still::la_phik_unit_bytes((int64_t)es, df, p->C)) : 0);
+  L->snap = take((size_t)B * Hq * nc * d * (2 * df) * es);
+  L->zsnap = take((size_t)B * Hq * nc * (2 * df) * 4);
+  L->n_la = take(p->emit_terms ? (size_t)B * Hq * N * d * 4 : 0);
+  L->d_la = take(p->emit_terms ? (size_t)B * Hq * N * 4 : 0);
   L->vfr = take((size_t)B * Hkv * d * npad * es);
   L->total = off;
   L->n_pad = (int32_t)npad;
@@ -387,8 +389,8 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
     return hip_fail("transpose_v", e);
   prof_end(0, s2);
   prof_begin(1, s2);
-  still::TransposeWArgs twq{Wq, ws + L.wqt, p->Hq, d, p->d_f};
-  still::TransposeWArgs twk{Wk, ws + L.wkt, p->Hq, d, p->d_f};
+  still::TransposeWArgs twq{Wq, ws + L.wqt, p->Hq, d, p->d_f, 0};   // rows of W_q^T: tiles of the query feature map
+  still::TransposeWArgs twk{Wk, ws + L.wkf, p->Hq, d, p->d_f, 1};   // W_k^T in operand order: the key projection
   if ((e = still::launch_transpose_w(twq, p->dtype, s2)) != hipSuccess ||
       (e = still::launch_transpose_w(twk, p->dtype, s2)) != hipSuccess)
     return hip_fail("transpose_w", e);
@@ -441,48 +443,48 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   // everything below reads the transposed copies
   if ((e = join_side()) != hipSuccess) return hip_fail("side stream", e);
 
-  // NP-Map + chunk linear attention
+  // NP-Map of the keys + scan of the linear-attention state: segment sums, prefix, per-chunk states
   still::LaArgs la{};
-  la.q = q; la.k = k;
-  la.q_sb = p->q_sb; la.q_st = p->q_st; la.q_sh = p->q_sh;
+  la.k = k;
   la.k_sb = p->k_sb; la.k_st = p->k_st; la.k_sh = p->k_sh;
-  la.g = g; la.g_sb = p->g_sb; la.g_st = p->g_st; la.g_sh = p->g_sh;
-  la.vfr = ws + L.vfr; la.wqt = ws + L.wqt; la.wkt = ws + L.wkt; la.bq = bq; la.bk = bk;
+  la.vfr = ws + L.vfr; la.wkf = ws + L.wkf; la.bk = bk;
   la.sel = sel;
   la.map = map;
   la.N = N; la.Np = L.n_pad; la.C = C; la.lam = have_sel ? p->lambda : 0; la.Hq = p->Hq; la.Hkv = p->Hkv;
   la.nc = nc; la.ncf = ncf; la.rcap = retained_budget(p); la.seq_len = p->seq_len;
   la.seg_chunks = L.seg_chunks; la.nseg = L.nseg;
   la.seg = reinterpret_cast<float*>(ws + L.seg);
-  la.n_la = reinterpret_cast<float*>(ws + L.n_la);
-  la.d_la = reinterpret_cast<float*>(ws + L.d_la);
-  la.phik = L.nseg > 1 ? ws + L.phik : nullptr;
-  la.phik_unit = still::la_phik_unit_bytes((int64_t)esize(p->dtype), p->d_f, C);
+  la.snap = ws + L.snap;
+  la.zsnap = reinterpret_cast<float*>(ws + L.zsnap);
   still_state_layout_t SL{};
   unsigned char* stp = static_cast<unsigned char*>(state_out);
   if (state_out != nullptr) compute_state_layout(p, &SL);
   la.s_final = state_out != nullptr ? reinterpret_cast<float*>(stp + SL.S) : nullptr;
   prof_begin(4, stream);
-  if ((e = still::launch_la_state(la, p->dtype, d, B, stream)) != hipSuccess)
-    return hip_fail("la_state", e);
+  if ((e = still::launch_la_sums(la, p->dtype, d, B, stream)) != hipSuccess)
+    return hip_fail("la_sums", e);
   prof_end(4, stream);
   prof_begin(5, stream);
   if ((e = still::launch_la_prefix(la, d, B, stream)) != hipSuccess)
     return hip_fail("la_prefix", e);
   prof_end(5, stream);
   prof_begin(6, stream);
-  if ((e = still::launch_la_out(la, p->dtype, d, B, stream)) != hipSuccess)
-    return hip_fail("la_out", e);
-
+  if ((e = still::launch_la_states(la, p->dtype, d, B, stream)) != hipSuccess)
+    return hip_fail("la_states", e);
   prof_end(6, stream);
+
   prof_begin(7, stream);
-  // sparse softmax branch + merge
+  // sparse softmax branch, the rows' linear terms, merge
   still::SaArgs sx{};
   sx.q = q; sx.k = k;
   sx.q_sb = p->q_sb; sx.q_st = p->q_st; sx.q_sh = p->q_sh;
   sx.k_sb = p->k_sb; sx.k_st = p->k_st; sx.k_sh = p->k_sh;
   sx.vt = ws + L.vt; sx.kret = ws + L.kret; sx.vrett = ws + L.vrett;
-  sx.n_la = la.n_la; sx.d_la = la.d_la;
+  sx.wqt = ws + L.wqt; sx.bq = bq;
+  sx.g = g; sx.g_sb = p->g_sb; sx.g_st = p->g_st; sx.g_sh = p->g_sh;
+  sx.snap = la.snap; sx.zsnap = la.zsnap; sx.nc = nc;
+  sx.n_la_out = p->emit_terms ? reinterpret_cast<float*>(ws + L.n_la) : nullptr;
+  sx.d_la_out = p->emit_terms ? reinterpret_cast<float*>(ws + L.d_la) : nullptr;
   sx.out = out; sx.o_sb = p->o_sb; sx.o_st = p->o_st; sx.o_sh = p->o_sh;
   sx.map = map;
   sx.N = N; sx.Np = L.n_pad; sx.C = C; sx.lam = have_sel ? p->lambda : 0; sx.Hq = p->Hq; sx.Hkv = p->Hkv;

@@ -70,9 +70,22 @@ __host__ __device__ inline int64_t vfr_offset(int tau, int x, int C, int D, int 
 
 struct TransposeWArgs {
   const void* w;  // [Hq, d, df]
-  void* wt;       // [Hq, df, d]
+  void* wt;       // [Hq, df, d], or (frag) the same rows in MFMA operand order, see wfrag_offset()
   int Hq, d, df;
+  int frag;
 };
+
+// Element offset, inside one head's copy, of W^T[f][x] in the operand order of the key projection f^T = W^T x^T:
+// [feature tile f / 32][k-step x / KK][lane = 32 g + m][k per lane], with feature 32 ft + kappa(m) in MFMA row m,
+// so that the 64 lanes of one operand load read one contiguous piece.
+template <typename M>
+__host__ __device__ inline int wfrag_offset(int ft, int s, int lane, int d) {
+  return ((ft * (d / M::KK) + s) * 64 + lane) * M::KPL;
+}
+
+// Tokens per round of the linear-attention state scan: the round's feature image [2 d_f][round] is double
+// buffered in LDS, so wide features in a wide type take shorter rounds.
+__host__ __device__ constexpr int la_round_tokens(int es, int d) { return es * 2 * d <= 512 ? 128 : 64; }
 
 struct GatherArgs {
   const void* k;
@@ -88,36 +101,21 @@ struct GatherArgs {
 };
 
 struct LaArgs {
-  const void* q;
   const void* k;
-  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
-  const void* g;       // nullable
-  int64_t g_sb, g_st, g_sh;
+  int64_t k_sb, k_st, k_sh;
   const void* vfr;     // [B, Hkv, Np * d]: v in fragment order (vfr_offset)
-  const void* wqt;     // [Hq, df, d]
-  const void* wkt;
-  const void* bq;      // nullable [Hq, df]
-  const void* bk;
+  const void* wkf;     // [Hq, df * d]: Wk^T in operand order (wfrag_offset)
+  const void* bk;      // nullable [Hq, df]
   const int32_t* sel;  // [B, Hq, ncf, lam]
   HeadMap map;
   int N, Np, C, lam, Hq, Hkv, nc, ncf, rcap;
   const int32_t* seq_len;   // nullable, device [B]
   int seg_chunks, nseg;
   float* seg;          // [B, Hq, nseg, DP*(D+1)]: S (DP x D) then z (DP)
-  float* n_la;         // [B, Hq, N, d]
-  float* d_la;         // [B, Hq, N]
-  float* s_final;      // nullable [B, Hq, DP*(D+1)]: state after chunk (last chunk - 2)
-  // nullable [B, Hq, nseg, seg_chunks][phik_unit bytes]: the staged key features of every unit of the state
-  // pass (its LDS slot and softmax sums, byte for byte), which the output pass then copies instead of
-  // recomputing them
-  unsigned char* phik;
-  int64_t phik_unit;
+  void* snap;          // [B, Hq, nc][D][DP] storage type: S^T through chunk c-2, for the rows of chunk c
+  float* zsnap;        // [B, Hq, nc][DP]: z through chunk c-2
+  float* s_final;      // nullable [B, Hq, DP*(D+1)]: fp32 state through chunk (last chunk - 2)
 };
-
-// bytes of one staged key-feature unit: phi_k as [2 d_f][C + pad] elements, then [2][d_f/32][C] partial sums
-inline int64_t la_phik_unit_bytes(int64_t es, int64_t df, int64_t C) {
-  return es * 2 * df * (C + 16 / es) + 4 * 2 * (df / 32) * C;
-}
 
 // query rows per workgroup of the sparse-attention kernel (one wave per 32 rows)
 constexpr int kSaRows = 128;
@@ -129,12 +127,18 @@ struct SaArgs {
   const void* vt;      // [B, Hkv, d, Np]
   const void* kret;    // [B, Hq, cap, d]
   const void* vrett;   // [B, Hq, d, cap]
-  const float* n_la;   // [B, Hq, N, d]
-  const float* d_la;   // [B, Hq, N]
+  const void* wqt;     // [Hq, df, d]: Wq^T
+  const void* bq;      // nullable [Hq, df]
+  const void* g;       // nullable gate [B, N, Hq, d]
+  int64_t g_sb, g_st, g_sh;
+  const void* snap;    // [B, Hq, nc][D][DP]: see LaArgs
+  const float* zsnap;  // [B, Hq, nc][DP]
+  float* n_la_out;     // nullable [B, Hq, N, d]: the gated linear numerator of every row (inspection)
+  float* d_la_out;     // nullable [B, Hq, N]
   void* out;
   int64_t o_sb, o_st, o_sh;
   HeadMap map;
-  int N, Np, C, lam, Hq, Hkv, cap, ntiles, B_, rcap;
+  int N, Np, C, lam, Hq, Hkv, cap, ntiles, B_, rcap, nc;
   const int32_t* seq_len;   // nullable, device [B]
   float scale;
 };
@@ -213,9 +217,9 @@ hipError_t launch_group_select(const ScoreArgs& a, int B, int Hkv, hipStream_t s
 hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStream_t stream);
 hipError_t launch_transpose_w(const TransposeWArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_gather(const GatherArgs& a, int dtype, int B, hipStream_t stream);
-hipError_t launch_la_state(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
+hipError_t launch_la_sums(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
 hipError_t launch_la_prefix(const LaArgs& a, int d, int B, hipStream_t stream);
-hipError_t launch_la_out(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
+hipError_t launch_la_states(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
 hipError_t launch_sa(const SaArgs& a, int dtype, int d, int B, hipStream_t stream);
 
 }  // namespace still

@@ -3,7 +3,8 @@
 //   transpose_v : v [B,N,Hkv,d] -> vt [B,Hkv,d,Np] (tokens contiguous, zero padded to Np), so that
 //                 the value operand of every "contract over tokens" MFMA is k-contiguous; and a second copy
 //                 in MFMA-fragment order for the kernel that loads that operand straight from global memory.
-//   transpose_w : NP-Map weights [Hq,d,df] -> [Hq,df,d] (feature rows, d contiguous).
+//   transpose_w : NP-Map weights [Hq,d,df] -> [Hq,df,d] (feature rows, d contiguous), or the same rows in the
+//                 operand order of the key projection.
 //   gather      : Index(k, M^SA), Index(v, M^SA) of Algorithm 1: the keys of the selected tokens of
 //                 every full chunk, flattened in chunk order, as rows of kret [B,Hq,cap,d]; the values
 //                 transposed into vrett [B,Hq,d,cap].  Rows beyond the selected count are zero.
@@ -95,6 +96,21 @@ __global__ __launch_bounds__(256) void transpose_w_kernel(TransposeWArgs a) {
   }
 }
 
+// W [Hq, d, df] -> W^T in the operand order of the key projection (wfrag_offset): one element per thread (the
+// weights of all heads are a few hundred KB)
+template <typename T>
+__global__ __launch_bounds__(256) void w_frag_kernel(TransposeWArgs a) {
+  typedef Mma<T> M;
+  const int h = blockIdx.y;
+  const int idx = blockIdx.x * 256 + threadIdx.x;      // position in the head's output
+  if (idx >= a.d * a.df) return;
+  const int e = idx % M::KPL, lane = (idx / M::KPL) % 64, blk = idx / (64 * M::KPL);
+  const int s = blk % (a.d / M::KK), ft = blk / (a.d / M::KK);
+  const int m = lane & 31, g = lane >> 5;
+  const int x = s * M::KK + g * M::KPL + e, f = 32 * ft + M::kappa(m);
+  static_cast<T*>(a.wt)[(int64_t)h * a.d * a.df + idx] = static_cast<const T*>(a.w)[((int64_t)h * a.d + x) * a.df + f];
+}
+
 template <typename E, int D>
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   __shared__ E tile[64][D + 2];
@@ -160,6 +176,14 @@ hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStre
 }
 
 hipError_t launch_transpose_w(const TransposeWArgs& a, int dtype, hipStream_t stream) {
+  if (a.frag) {
+    dim3 fgrid((a.d * a.df + 255) / 256, a.Hq), fblock(256);
+    if (dtype == 1)
+      hipLaunchKernelGGL(w_frag_kernel<bf16>, fgrid, fblock, 0, stream, a);
+    else
+      hipLaunchKernelGGL(w_frag_kernel<float>, fgrid, fblock, 0, stream, a);
+    return hipGetLastError();
+  }
   dim3 grid(a.d / 64, a.df / 64, a.Hq), block(256);   // d and d_f are multiples of 64
   if (dtype == 1)
     hipLaunchKernelGGL(transpose_w_kernel<uint16_t>, grid, block, 0, stream, a);

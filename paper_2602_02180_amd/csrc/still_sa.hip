@@ -3,11 +3,18 @@
 // Paper: Sec. 3.3 output equations.  Row t of chunk c attends with exp(scale q.k) to
 //   (i)  the retained keys/values of chunks <= c-2 (Algorithm 1: flattened selected K/V under M^Chunk),
 //   (ii) the whole previous chunk and its own chunk up to t (s_prev, s_in with the causal mask),
-// giving N_SA, D_SA; the epilogue adds the linear-attention terms and divides once:
+// giving N_SA, D_SA; the linear-attention terms share the normaliser:
 //   y = (N_SA + N_LA) / (D_SA + D_LA).
-// The softmax sums are kept relative to a per-row reference m (online softmax); the linear terms are not
-// exponentials, so both branches are brought to the common factor exp(-max(m, 0)) before the division
-// (any common positive factor cancels; this one can neither overflow nor lose the larger branch).
+// The linear branch of a row, N_LA = g * phi_q(q) S and D_LA = phi_q(q) z with (S, z) the state through chunk
+// c-2 (Algorithm 1's linear branch; NP-Map of Sec. 3.2), is computed HERE, in a prologue, from the per-chunk
+// states the scan kernel left in memory: the query fragments are already in registers, phi_q^T (features x
+// queries) comes out of the same "tile x Q^T" product as the logits with W_q^T in the role of the key tile, a lane
+// owns one query so the NP-Map's statistics are per-lane reductions, and phi_q^T is then the second operand of
+// "S^T tile x phi_q^T" exactly as the softmax weights are of "V^T tile x P^T".  The result initialises the online
+// softmax: the linear terms enter as if they were one more key with logit 0, weight D_LA and value N_LA / D_LA
+// (reference m = 0, running sum D_LA, accumulator N_LA).  From then on the usual rescaling keeps both branches
+// under the common factor exp(-max(m, 0)) (any common positive factor cancels; this one can neither overflow nor
+// lose the larger branch), and the epilogue is a single division.  N_LA never touches memory.
 //
 // One workgroup = kSaRows consecutive query rows of one (batch, query head), one wave per 32 rows.
 // Everything is computed transposed so that one lane owns one query row:
@@ -44,7 +51,8 @@ struct SaCfg {
   static constexpr int V_ELEMS = D * BN;              // one V^T tile
   static constexpr int K_INSTR = K_ELEMS / EPV / 64 / NW;   // direct-to-LDS requests per wave and tile
   static constexpr int V_INSTR = V_ELEMS / EPV / 64 / NW;
-  static constexpr size_t smem_bytes = 2 * sizeof(T) * (K_ELEMS + V_ELEMS);
+  static constexpr size_t tile_bytes = 2 * sizeof(T) * (K_ELEMS + V_ELEMS);
+  static constexpr size_t smem_bytes = tile_bytes + 2 * (2 * D) * sizeof(float);   // + z of up to two chunks
   // swizzles: XOR applied to the 16-byte column index of a row
   // (a 128-byte row holds 8 columns and two rows share a pass over the banks; longer rows hold >= 16)
   static __device__ __forceinline__ int kswz(int row) { return KVR == 8 ? ((row >> 1) & 7) : (row & 15); }
@@ -312,6 +320,223 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   float m_ref = -INFINITY, lpart = 0.f;
   const float sc2 = a.scale * kLog2e;
 
+  // ---- linear branch of the rows (see the header): o = g * phi_q(q) S, lpart = phi_q(q) z, m_ref = 0.
+  // Chunks 0 and 1 have no state.  Control flow is uniform over the workgroup (all waves deal the tile requests
+  // and meet at the barriers); a wave computes only for its own chunk.
+  {
+    constexpr int DF = D, DP = 2 * D;
+    constexpr int NWT = DF / 64, NST = DP / 64;        // W_q^T tiles (64 features x d), state tiles (d x 64 features)
+    constexpr int SPT = M::STEPS_PER_TILE;
+    const int la_lo = c_first >= 2 ? c_first : 2, la_hi = c_last;
+    bool la_done = false;
+    if (la_lo <= la_hi) {
+      const int64_t unit = (int64_t)b * a.Hq + hq;
+      float* zl = reinterpret_cast<float*>(smem + Cf::tile_bytes);       // [chunk - la_lo][DP]
+      const bool mine = wave_active && cw >= 2;                          // this wave has linear terms
+      const T* wq_h = static_cast<const T*>(a.wqt) + (int64_t)hq * DF * D;
+      auto request_w = [&](int wt, T* slot) {       // W_q^T rows [64 wt, +64): laid out like a tile of retained keys
+        const T* base = wq_h + (int64_t)wt * 64 * D;
+        T* dst = slot + wave_s * 64 * Cf::EPV;
+#pragma unroll
+        for (int j = 0; j < Cf::K_INSTR; ++j)
+          async_copy16(base + k_off_ret[j], lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
+      };
+      auto request_s = [&](int cc, int jt, T* slot) {   // S^T[:, 64 jt .. +64) of chunk cc: like a V^T tile, row stride DP
+        const T* base = static_cast<const T*>(a.snap) + (unit * a.nc + cc) * (int64_t)(D * DP) + 64 * jt;
+        T* dst = slot + wave_s * 64 * Cf::EPV;
+        const int lane_now = fresh_lane_id();
+#pragma unroll
+        for (int j = 0; j < Cf::V_INSTR; ++j) {
+          int lrow, col;
+          v_lane(lane_now, j, lrow, col);
+          async_copy16(base + (lrow * DP + col), lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
+        }
+      };
+      auto slot_of = [&](int jt) -> T* {              // state tiles 0, 1 use the V slots, 2, 3 the K slots
+        return jt < 2 ? Vl + jt * Cf::V_ELEMS : Kl + (jt - 2) * Cf::K_ELEMS;
+      };
+      // stage 1: W_q^T, z of the chunks, the first two state tiles of the first chunk
+#pragma unroll
+      for (int wt = 0; wt < NWT; ++wt) request_w(wt, Kl + wt * Cf::K_ELEMS);
+      request_s(la_lo, 0, slot_of(0));
+      request_s(la_lo, 1, slot_of(1));
+      for (int i = tid; i < (la_hi - la_lo + 1) * DP; i += Cf::NW * 64)
+        zl[i] = a.zsnap[(unit * a.nc + la_lo) * DP + i];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(qf[s]));
+      wait_async_copies();
+      lds_barrier();
+
+      // phi_q^T of this wave's 32 queries, as operand fragments (un-normalised exponentials; the two normalisers
+      // are applied to the accumulator): f^T = W_q^T Q^T, statistics per lane, u = f * ||q|| / ||f||
+      typename M::frag pfr[NWT][2][SPT], nfr[NWT][2][SPT];
+      float ip = 0.f, in = 0.f, sn_keep = 1.f, dla = 0.f;
+      if (mine) {
+        floatx16 f[NWT][2];
+#pragma unroll
+        for (int wt = 0; wt < NWT; ++wt) sa_qk<T, D>(Kl + wt * Cf::K_ELEMS, qf, f[wt], r, g);
+        if (a.bq != nullptr) {
+          const T* bq = static_cast<const T*>(a.bq) + (int64_t)hq * DF;
+#pragma unroll
+          for (int wt = 0; wt < NWT; ++wt)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) f[wt][mt][i] += to_f32(bq[64 * wt + 32 * mt + M::pos_of_reg(i, g)]);
+        }
+        float nx2 = 0.f, nf2 = 0.f, fmax = -INFINITY, fmin = INFINITY;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) nx2 = M::dot_into(qf[s], qf[s], nx2);
+#pragma unroll
+        for (int wt = 0; wt < NWT; ++wt)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              nf2 = fmaf(f[wt][mt][i], f[wt][mt][i], nf2);
+              fmax = fmaxf(fmax, f[wt][mt][i]);
+              fmin = fminf(fmin, f[wt][mt][i]);
+            }
+        nx2 = sum32(nx2);
+        nf2 = sum32(nf2);
+        fmax = max32(fmax);
+        fmin = min32(fmin);
+        const float ratio = nf2 > 0.f ? __builtin_amdgcn_sqrtf(nx2 * fast_rcp(nf2)) : 0.f;
+        const float a1 = ratio * kLog2e;
+        const float bp = -fmax * a1, bn = fmin * a1;
+        const float* zc = zl + (cw - la_lo) * DP;
+        float sp = 0.f, sn = 0.f, dp = 0.f, dn = 0.f;
+#pragma unroll
+        for (int wt = 0; wt < NWT; ++wt)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt) {
+            floatx16 ep, en;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              ep[i] = fast_exp2(fmaf(f[wt][mt][i], a1, bp));
+              en[i] = fast_exp2(fmaf(f[wt][mt][i], -a1, bn));
+              sp += ep[i];
+              sn += en[i];
+            }
+            // D_LA: the same weights against z (positions of one register octet are consecutive features)
+#pragma unroll
+            for (int o8 = 0; o8 < 2; ++o8) {
+              const int fbase = 64 * wt + 32 * mt + (M::KPL == 8 ? 16 * o8 + 8 * g : 0);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                const int i = 8 * o8 + e;
+                const int fi = M::KPL == 8 ? fbase + e : 64 * wt + 32 * mt + M::pos_of_reg(i, g);
+                dp = fmaf(ep[i], zc[fi], dp);
+                dn = fmaf(en[i], zc[DF + fi], dn);
+              }
+            }
+#pragma unroll
+            for (int s = 0; s < SPT; ++s) {
+              pfr[wt][mt][s] = M::from_acc(ep, s);
+              nfr[wt][mt][s] = M::from_acc(en, s);
+            }
+          }
+        sp = sum32(sp);
+        sn = sum32(sn);
+        ip = fast_rcp(sp);
+        in = fast_rcp(sn);
+        sn_keep = sn;
+        dla = sum32(dp) * ip + sum32(dn) * in;
+      }
+      lds_barrier();   // every wave has read W_q^T: the K slots are free
+
+      // "S^T tile x phi_q^T" into the accumulator, tile jt from its slot (a wave joins only for its own chunk)
+      auto la_pv = [&](int jt_c, const T* Vs) __attribute__((always_inline)) {
+        static_for<NST>([&](auto JT) __attribute__((always_inline)) {
+          constexpr int jt = decltype(JT)::value;
+          if (jt == jt_c) {
+            constexpr int wt = jt % NWT;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+              for (int s = 0; s < SPT; ++s) {
+                const typename M::frag pf = jt < NWT ? pfr[wt][mt][s] : nfr[wt][mt][s];
+                const int e = 32 * mt + s * M::KK + g * M::KPL;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) o[dt] = M::mma(M::load(Vs + Cf::voff(32 * dt + r, e)), pf, o[dt]);
+              }
+            if (jt == NWT - 1) {       // the positive half is complete: (ip / in) A now, + B and * in later = ip A + in B
+              const float k1 = ip * sn_keep;
+#pragma unroll
+              for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[dt][i] *= k1;
+            }
+          }
+        });
+      };
+      for (int cc = la_lo; cc <= la_hi; ++cc) {
+        const bool now = mine && cw == cc;
+        if (cc > la_lo) {               // second chunk of the workgroup: its first two tiles (the V slots are free)
+          request_s(cc, 0, slot_of(0));
+          request_s(cc, 1, slot_of(1));
+          wait_async_copies();
+          lds_barrier();
+        }
+        if (NST > 2) {                  // the other two tiles go to the K slots while the first two are used
+          request_s(cc, 2, slot_of(2));
+          request_s(cc, 3, slot_of(3));
+        }
+        if (now) {
+          la_pv(0, slot_of(0));
+          la_pv(1, slot_of(1));
+        }
+        wait_async_copies();
+        lds_barrier();
+        if (NST > 2) {
+          if (now) {
+            la_pv(2, slot_of(2));
+            la_pv(3, slot_of(3));
+          }
+          lds_barrier();
+        }
+      }
+      if (mine) {
+        la_done = true;
+        const int tq = t < N ? t : N - 1;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const int x0 = 32 * dt + 8 * i4 + 4 * g;     // four consecutive columns per register quad
+            float gv[4] = {1.f, 1.f, 1.f, 1.f};
+            if (a.g != nullptr) {
+              const T* gp = static_cast<const T*>(a.g) + (int64_t)b * a.g_sb + (int64_t)tq * a.g_st +
+                            (int64_t)hq * a.g_sh + x0;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) gv[e] = to_f32(gp[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[dt][4 * i4 + e] *= in * gv[e];
+            if (a.n_la_out != nullptr && t < N) {
+              floatx4 nv;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) nv[e] = o[dt][4 * i4 + e];
+              *reinterpret_cast<floatx4*>(a.n_la_out + (unit * a.N + t) * D + x0) = nv;
+            }
+          }
+        if (a.d_la_out != nullptr && t < N && g == 0) a.d_la_out[unit * a.N + t] = dla;
+        // one more "key": logit 0, weight D_LA, value N_LA / D_LA (an all-kept context has D_LA = 0: no such key)
+        if (dla > 0.f) {
+          m_ref = 0.f;
+          lpart = g == 0 ? dla : 0.f;
+        }
+      }
+    }
+    if ((a.n_la_out != nullptr || a.d_la_out != nullptr) && !la_done && wave_active && t < N) {
+      // (inspection only) rows without linear terms read as zeros
+      const int64_t unit = (int64_t)b * a.Hq + hq;
+      if (a.d_la_out != nullptr && g == 0) a.d_la_out[unit * a.N + t] = 0.f;
+      if (a.n_la_out != nullptr)
+        for (int x = g * (D / 2); x < (g + 1) * (D / 2); ++x) a.n_la_out[(unit * a.N + t) * D + x] = 0.f;
+    }
+  }
+
   // ---- prologue: K(0), V(0), K(1) resident; S(0) computed
   request_k(0);
   request_v(0);
@@ -388,64 +613,24 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
     if (ti + 1 < n_tiles) step(ti + 1, st_b, st_a);
   }
 
-  // ---- merge epilogue.  In the accumulator layout a lane owns one row and four consecutive columns per register
-  // quad, so direct loads of N_LA and stores of the output would touch 32 rows with 16-32 bytes each per
-  // instruction.  Both tiles therefore pass through LDS (the K/V slots are free after the last barrier, each wave
-  // uses a private 32-row region, so no further barrier is needed): every global access is a 1 KB contiguous piece,
-  // and the row <-> column exchange happens in LDS, with the 16-byte slot index XOR-ed with the row so that neither
-  // direction meets bank conflicts.
+  // ---- epilogue: y = (N_SA + N_LA) / (D_SA + D_LA), both branches already under one factor in the accumulator.
+  // In the accumulator layout a lane owns one row and four consecutive columns per register quad, so direct
+  // stores of the output would touch 32 rows with 8-16 bytes each per instruction.  The tile therefore passes
+  // through LDS (the K/V slots are free after the last barrier, each wave uses a private 32-row region, so no
+  // further barrier is needed): every global store is a 1 KB contiguous piece, and the row <-> column exchange
+  // happens in LDS, with the 16-byte slot index XOR-ed with the row so that neither direction meets bank conflicts.
   {
-    constexpr int ROWB_N = D * 4, NSL = ROWB_N / 16;             // N_LA row: bytes, 16-byte slots
-    constexpr int ROWB_O = D * (int)sizeof(T), NSO = ROWB_O / 16;  // output row
-    constexpr int NREQ = 32 * ROWB_N / 1024, NOUT = 32 * ROWB_O / 1024;
-    static_assert(Cf::NW * 32 * ROWB_N <= (int)Cf::smem_bytes, "epilogue staging fits the tile slots");
-    unsigned char* reg = smem + wave_s * (32 * ROWB_N);
+    constexpr int ROWB_O = D * (int)sizeof(T), NSO = ROWB_O / 16;  // output row: bytes, 16-byte slots
+    constexpr int NOUT = 32 * ROWB_O / 1024;
+    static_assert(Cf::NW * 32 * ROWB_O <= (int)Cf::tile_bytes, "epilogue staging fits the tile slots");
+    unsigned char* reg = smem + wave_s * (32 * ROWB_O);
     const int lane_now = fresh_lane_id();
-    const int64_t unit_row0 = ((int64_t)b * a.Hq + hq) * a.N;
-    // (1) N_LA rows of this wave -> LDS, in two batches (bounds the staging registers); rows past the end of the
-    //     sequence re-read the last row
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      floatx4 stg[NREQ / 2];
-#pragma unroll
-      for (int i = 0; i < NREQ / 2; ++i) {
-        const int off = (half * (NREQ / 2) + i) * 1024 + lane_now * 16;
-        const int row = off / ROWB_N, slot = (off % ROWB_N) / 16;
-        int tr = q0 + row;
-        tr = tr < N ? tr : N - 1;
-        stg[i] = *reinterpret_cast<const floatx4*>(a.n_la + (unit_row0 + tr) * D + slot * 4);
-      }
-#pragma unroll
-      for (int i = 0; i < NREQ / 2; ++i) {
-        const int off = (half * (NREQ / 2) + i) * 1024 + lane_now * 16;
-        const int row = off / ROWB_N, slot = (off % ROWB_N) / 16;
-        *reinterpret_cast<floatx4*>(reg + row * ROWB_N + ((slot ^ (row & (NSL - 1))) * 16)) = stg[i];
-      }
-    }
-    // (2) y = (fs N_SA + fl N_LA) / (fs D_SA + fl D_LA), in place in the accumulators
-    const float l = sum32(lpart);
-    const float m2 = m_ref;
-    float fs, fl;
-    if (m2 >= 0.f) {
-      fs = 1.f;
-      fl = fast_exp2(-m2);
-    } else {
-      fs = fast_exp2(m2);
-      fl = 1.f;
-    }
-    const int tq = t < N ? t : N - 1;
-    const float dla = a.d_la[unit_row0 + tq];
-    const float inv = 1.0f / (fs * l + fl * dla);
+    const float inv = 1.0f / sum32(lpart);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int slot = 8 * dt + 2 * i4 + g;                   // columns 32 dt + 8 i4 + 4 g .. + 3
-        const floatx4 nl = *reinterpret_cast<const floatx4*>(reg + r * ROWB_N + ((slot ^ (r & (NSL - 1))) * 16));
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[dt][4 * i4 + e] = (fs * o[dt][4 * i4 + e] + fl * nl[e]) * inv;
-      }
-    // (3) output tile -> LDS in the storage type (all reads of step 2 were issued before: LDS is in order)
+      for (int i = 0; i < 16; ++i) o[dt][i] *= inv;
+    // output tile -> LDS in the storage type
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -464,7 +649,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
           *reinterpret_cast<floatx4*>(dst) = ov;
         }
       }
-    // (4) LDS -> global, 1 KB per instruction
+    // LDS -> global, 1 KB per instruction
     T* obase = static_cast<T*>(a.out) + (int64_t)b * a.o_sb + (int64_t)hq * a.o_sh;
 #pragma unroll
     for (int i = 0; i < NOUT; ++i) {

@@ -14,7 +14,8 @@ from paper_2602_02180_amd import synth
 
 def run_hip(w: synth.Workload, inp: Dict[str, np.ndarray], sel_in: Optional[np.ndarray] = None,
             kv_map: Optional[np.ndarray] = None, want_terms: bool = True) -> Dict[str, np.ndarray]:
-    """One still_hybrid_attn_fwd call; returns out, score, sel and (from the workspace) N_LA, D_LA."""
+    """One still_hybrid_attn_fwd call; returns out, score, sel and (want_terms: the call is made with the
+    emit_terms inspection hook, and the linear-branch terms are read from the workspace) N_LA, D_LA."""
     import torch
 
     dev = "cuda"
@@ -30,7 +31,7 @@ def run_hip(w: synth.Workload, inp: Dict[str, np.ndarray], sel_in: Optional[np.n
     out = torch.full_like(q, float("nan"))
     p = S.make_params(B=B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
                       dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, g=g, kv_head_of_q=kv_map,
-                      max_retained=w.max_retained, shared_selection=w.shared_selection)
+                      max_retained=w.max_retained, shared_selection=w.shared_selection, emit_terms=want_terms)
     ncf = N // w.C
     score = torch.full((B, w.Hq, N), float("nan"), dtype=torch.float32, device=dev)
     sel = torch.full((B, w.Hq, max(ncf, 1), max(w.lam, 1)), -1, dtype=torch.int32, device=dev)
