@@ -112,6 +112,7 @@ typedef struct still_ws_layout {
   size_t seg;      /* float   [B, Hq, nseg, 2*d_f*(d+1)]         per-segment linear-attention states       */
   size_t snap;     /* dtype   [B, Hq, ceil(N/C), d, 2*d_f]       S^T through chunk c-2, for the rows of chunk c */
   size_t zsnap;    /* float   [B, Hq, ceil(N/C), 2*d_f]          z through chunk c-2                       */
+  size_t kmask;    /* uint32  [B, Hq, N/C, C/32]                 the selection as one bit per token        */
   size_t n_la;     /* float   [B, Hq, N, d]                      gated linear-branch numerator N_LA (emit_terms) */
   size_t d_la;     /* float   [B, Hq, N]                         linear-branch normaliser D_LA (emit_terms) */
   size_t vfr;      /* dtype   [B, Hkv, Npad * d]                 v in the operand order of the state update */

@@ -200,6 +200,7 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   L->seg = take((size_t)B * Hq * nseg * (2 * df * (d + 1)) * 4);
   L->snap = take((size_t)B * Hq * nc * d * (2 * df) * es);
   L->zsnap = take((size_t)B * Hq * nc * (2 * df) * 4);
+  L->kmask = take((size_t)B * Hq * ncf * (p->C / 32) * 4);
   L->n_la = take(p->emit_terms ? (size_t)B * Hq * N * d * 4 : 0);
   L->d_la = take(p->emit_terms ? (size_t)B * Hq * N * 4 : 0);
   L->vfr = take((size_t)B * Hkv * d * npad * es);
@@ -448,10 +449,10 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   la.k = k;
   la.k_sb = p->k_sb; la.k_st = p->k_st; la.k_sh = p->k_sh;
   la.vfr = ws + L.vfr; la.wkf = ws + L.wkf; la.bk = bk;
-  la.sel = sel;
+  la.kmask = reinterpret_cast<const uint32_t*>(ws + L.kmask);
   la.map = map;
-  la.N = N; la.Np = L.n_pad; la.C = C; la.lam = have_sel ? p->lambda : 0; la.Hq = p->Hq; la.Hkv = p->Hkv;
-  la.nc = nc; la.ncf = ncf; la.rcap = retained_budget(p); la.seq_len = p->seq_len;
+  la.N = N; la.Np = L.n_pad; la.C = C; la.Hq = p->Hq; la.Hkv = p->Hkv;
+  la.nc = nc; la.ncf = ncf; la.seq_len = p->seq_len;
   la.seg_chunks = L.seg_chunks; la.nseg = L.nseg;
   la.seg = reinterpret_cast<float*>(ws + L.seg);
   la.snap = ws + L.snap;
@@ -461,6 +462,10 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   if (state_out != nullptr) compute_state_layout(p, &SL);
   la.s_final = state_out != nullptr ? reinterpret_cast<float*>(stp + SL.S) : nullptr;
   prof_begin(4, stream);
+  still::KeepMaskArgs km{sel, reinterpret_cast<uint32_t*>(ws + L.kmask), p->Hq, ncf, C, have_sel ? p->lambda : 0,
+                         retained_budget(p)};
+  if ((e = still::launch_keep_mask(km, B, stream)) != hipSuccess)
+    return hip_fail("keep_mask", e);
   if ((e = still::launch_la_sums(la, p->dtype, d, B, stream)) != hipSuccess)
     return hip_fail("la_sums", e);
   prof_end(4, stream);

@@ -100,15 +100,24 @@ struct GatherArgs {
   void* vrett;         // [B, Hq, d, cap]
 };
 
+// Top-lambda lists -> one bit per token of every full chunk (set = kept by the softmax branch, so the token does
+// NOT enter the linear state).  Entries outside their chunk are ignored (caller-supplied lists are never trusted for
+// addressing); slots beyond a chunk's quota are not read.
+struct KeepMaskArgs {
+  const int32_t* sel;   // [B, Hq, ncf, lam], nullable when lam == 0
+  uint32_t* kmask;      // [B, Hq, ncf, C/32]
+  int Hq, ncf, C, lam, rcap;
+};
+
 struct LaArgs {
   const void* k;
   int64_t k_sb, k_st, k_sh;
   const void* vfr;     // [B, Hkv, Np * d]: v in fragment order (vfr_offset)
   const void* wkf;     // [Hq, df * d]: Wk^T in operand order (wfrag_offset)
   const void* bk;      // nullable [Hq, df]
-  const int32_t* sel;  // [B, Hq, ncf, lam]
+  const uint32_t* kmask;  // [B, Hq, ncf, C/32]: bit = token kept by the softmax branch (see KeepMaskArgs)
   HeadMap map;
-  int N, Np, C, lam, Hq, Hkv, nc, ncf, rcap;
+  int N, Np, C, Hq, Hkv, nc, ncf;
   const int32_t* seq_len;   // nullable, device [B]
   int seg_chunks, nseg;
   float* seg;          // [B, Hq, nseg, DP*(D+1)]: S (DP x D) then z (DP)
@@ -217,6 +226,7 @@ hipError_t launch_group_select(const ScoreArgs& a, int B, int Hkv, hipStream_t s
 hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStream_t stream);
 hipError_t launch_transpose_w(const TransposeWArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_gather(const GatherArgs& a, int dtype, int B, hipStream_t stream);
+hipError_t launch_keep_mask(const KeepMaskArgs& a, int B, hipStream_t stream);
 hipError_t launch_la_sums(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
 hipError_t launch_la_prefix(const LaArgs& a, int d, int B, hipStream_t stream);
 hipError_t launch_la_states(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);

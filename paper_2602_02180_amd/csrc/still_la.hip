@@ -25,7 +25,11 @@
 //     matrix core with one lane per token (the token's statistics ||f||^2, max f, min f, ||x||^2 and both softmax
 //     sums are then plain per-lane reductions plus one exchange between the two lane groups: no exchange between
 //     waves), the two exponential halves normalised and written into the round's LDS image [feature][token].
-//     The rows of W^T come from a copy in operand order (1 KB contiguous per load, cache resident).
+//     The rows of W^T come from a copy in operand order, resident in LDS for the whole scan where it fits next to
+//     the two images (every storage type and width but fp32 with d = 128, which reads it from global memory).
+//   The image is unpadded: its 16-byte pieces are XOR-swizzled by the feature row (piece ^ swz(row)), chosen so that
+//     the operand reads of 32 rows at one token position, the producers' column stores and the row sums for z all
+//     spread over the banks.
 //   consumer waves (d/32): wave w keeps the fp32 state columns [32w, 32w+32) of S (2 d_f x d) in MFMA
 //     accumulators for the whole scan: S += phi_k^T V with phi_k^T from the LDS image (read a fixed number of
 //     products ahead) and V from a copy in operand order; z (one feature row per lane) is the row sum of the same
@@ -47,10 +51,18 @@ struct LaCfg {
   static constexpr int PTOK = RT < C ? RT : C;      // tokens per part: a part never crosses a chunk boundary
   static constexpr int NPART = RT / PTOK;           // parts per round (1 or 2)
   static constexpr int HS = PTOK / M::KK;           // k-steps (token groups) per part
-  static constexpr int PAD = 16 / (int)sizeof(T);
-  static constexpr int KSTRIDE = RT + PAD;          // image row stride (elements)
-  static constexpr size_t phi_bytes = sizeof(T) * DP * KSTRIDE;
-  static constexpr size_t smem_bytes = 2 * phi_bytes + NPW * 32;   // two images + one keep table per producer
+  static constexpr int EPV = 16 / (int)sizeof(T);   // elements per 16-byte piece
+  static constexpr int RSTRIDE = RT;                // image row stride (elements): unpadded, swizzled
+  static constexpr size_t phi_bytes = sizeof(T) * DP * RSTRIDE;
+  static constexpr size_t w_bytes = sizeof(T) * DF * D;
+  static constexpr bool W_LDS = 2 * phi_bytes + w_bytes <= 160 * 1024;
+  static constexpr size_t smem_bytes = 2 * phi_bytes + (W_LDS ? w_bytes : 0);
+  // XOR applied to the index of a row's 16-byte piece: bits (0, 1, 3) of the row go to bits (2, 0, 1)
+  static __device__ __forceinline__ int swz(int row) { return ((row & 1) << 2) | ((row >> 1) & 1) | ((row >> 2) & 2); }
+  // byte offset of element (row, tok) inside an image
+  static __device__ __forceinline__ int img_off(int row, int tok) {
+    return (row * RSTRIDE + (((tok / EPV) ^ swz(row)) * EPV) + tok % EPV) * (int)sizeof(T);
+  }
   static_assert(NPART == 1 || NPART == 2, "a round holds one or two chunks, or a part of one");
   static_assert(DP / NCW == 64, "one feature row of z per consumer lane");
 };
@@ -62,11 +74,11 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
   typedef Mma<T> M;
   typedef LaCfg<T, D, C> L;
   constexpr int DF = L::DF, DP = L::DP, RT = L::RT, NCW = L::NCW, FT = L::FT, PT = L::PT, KS = L::KS;
-  constexpr int PTOK = L::PTOK, NPART = L::NPART, HS = L::HS, KSTRIDE = L::KSTRIDE;
+  constexpr int PTOK = L::PTOK, NPART = L::NPART, HS = L::HS;
   constexpr int SPT = M::STEPS_PER_TILE;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned char* keep = smem + 2 * L::phi_bytes;
+  T* wl = reinterpret_cast<T*>(smem + 2 * L::phi_bytes);      // W_k^T in operand order (when it fits)
 
   int seg, hq;
   head_major_block(blockIdx.x, a.Hq, hq, seg);
@@ -84,16 +96,22 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
   const int64_t unit = (int64_t)b * a.Hq + hq;
   float* __restrict__ segp = a.seg + (unit * a.nseg + seg) * (int64_t)(DP * (D + 1));
 
+  if (L::W_LDS) {
+    const Vec16* src = reinterpret_cast<const Vec16*>(static_cast<const T*>(a.wkf) + (int64_t)hq * DF * D);
+    Vec16* dst = reinterpret_cast<Vec16*>(wl);
+    for (int i = threadIdx.x; i < (int)(L::w_bytes / 16); i += (NCW + L::NPW) * 64) dst[i] = src[i];
+    __syncthreads();
+  }
+
   if (wave >= NCW) {
     // ------------------------------------------------------------------ producer wave v
     const int v = wave - NCW;
     const T* __restrict__ kbase = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)kvh * a.k_sh;
     const T* __restrict__ wkf = static_cast<const T*>(a.wkf) + (int64_t)hq * DF * D;
     const T* __restrict__ bk = a.bk ? static_cast<const T*>(a.bk) + (int64_t)hq * DF : nullptr;
-    unsigned char* kt = keep + v * 32;           // this wave's private table: 1 = token goes to the linear state
 
     typename M::frag xb[KS];                     // the tile's token rows (B operand of f^T = W^T x^T)
-    int32_t selv[2];                             // Top-lambda list of the tile's chunk, entries lane and lane + 64
+    uint32_t kw;                                 // bit r: token r of the tile is kept by the softmax branch
     auto load_x = [&](int tokw) __attribute__((always_inline)) {
       int tok = tokw + r;
       tok = tok < N ? tok : N - 1;
@@ -102,46 +120,48 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 #pragma unroll
       for (int s = 0; s < KS; ++s) xb[s] = M::load(xp + s * M::KK);
     };
-    auto load_sel = [&](int tokw) __attribute__((always_inline)) {
+    // one word of the chunk's keep mask per 32-token tile; all ones for a chunk that is not routed (nothing of it
+    // goes to the state)
+    auto load_keep = [&](int tokw) __attribute__((always_inline)) {
       const int cc = floor_div(tokw, C);
-      const bool valid = cc >= 0 && cc < ncf_b;
-      const int32_t* selc = a.sel + (unit * a.ncf + (valid ? cc : 0)) * a.lam;
-      const int quota = valid ? chunk_quota(cc, a.lam, a.rcap) : 0;
+      const bool valid = cc >= 0 && cc < ncf_b;          // only full chunks are ever routed
+      kw = valid ? a.kmask[(unit * a.ncf + cc) * (C / 32) + (tokw - cc * C) / 32] : 0xffffffffu;
+    };
+    const T* wsrc = L::W_LDS ? wl : wkf;
+    // f^T (features x tokens) = W^T x^T, all features of the tile's 32 tokens, and ||x||^2.  The W^T fragments are
+    // read WDEPTH products ahead of their use (the scheduling barriers pin that order) and consecutive products go
+    // to different accumulators, so a product waits neither for its own read nor for its predecessor.
+    floatx16 f[FT];
+    float nx2;
+    auto project = [&]() __attribute__((always_inline)) {
+      constexpr int NPJ = FT * KS, WDEPTH = NPJ < 8 ? NPJ : 8;
+      auto w_at = [&](int idx) { return M::load(wsrc + wfrag_offset<M>(idx % FT, idx / FT, lane, D)); };
+      typename M::frag wf[WDEPTH];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) selv[j] = (lane + 64 * j < quota) ? selc[lane + 64 * j] : -1;
+      for (int i = 0; i < WDEPTH; ++i) wf[i] = w_at(i);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int idx = 0; idx < NPJ; ++idx) {
+        f[idx % FT] = M::mma(wf[idx % WDEPTH], xb[idx / FT], idx < FT ? zero16() : f[idx % FT]);
+        if (idx + WDEPTH < NPJ) wf[idx % WDEPTH] = w_at(idx + WDEPTH);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      float n4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < KS; ++s) n4[s & 3] = M::dot_into(xb[s], xb[s], n4[s & 3]);
+      nx2 = sum32((n4[0] + n4[1]) + (n4[2] + n4[3]));
     };
     load_x(seg_tok0 + 32 * v);
-    load_sel(seg_tok0 + 32 * v);
+    load_keep(seg_tok0 + 32 * v);
 
 #pragma unroll 1
     for (int it = 0; it < R; ++it) {
       const int tokw = seg_tok0 + it * RT + 32 * v;      // first token of this wave's tile
-      const int cc = floor_div(tokw, C);
-      const bool valid = cc >= 0 && cc < ncf_b;          // only full chunks are ever routed
-      // keep table of the tile from the list requested a round ago (a wave's own LDS accesses are in order)
-      if (lane < 32) kt[lane] = valid ? 1 : 0;
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const unsigned off = (unsigned)(selv[j] - tokw);
-        if (selv[j] >= 0 && off < 32u) kt[off] = 0;
-      }
-      // f^T (features x tokens) = W^T x^T, all features of the tile's 32 tokens
-      floatx16 f[FT];
-#pragma unroll
-      for (int ft = 0; ft < FT; ++ft) {
-        f[ft] = zero16();
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-          f[ft] = M::mma(M::load(wkf + wfrag_offset<M>(ft, s, lane, D)), xb[s], f[ft]);
-      }
-      float nx2 = 0.f;
-#pragma unroll
-      for (int s = 0; s < KS; ++s) nx2 = M::dot_into(xb[s], xb[s], nx2);
-      nx2 = sum32(nx2);
-      // the rows are dead now: request the next round's
-      if (it + 1 < R) {
+      const bool live = ((kw >> r) & 1u) == 0u;
+      project();
+      if (it + 1 < R) {               // the rows are dead now: request the next round's
         load_x(tokw + RT);
-        load_sel(tokw + RT);
+        load_keep(tokw + RT);
       }
       if (bk != nullptr) {
 #pragma unroll
@@ -149,50 +169,90 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) f[ft][i] += to_f32(bk[32 * ft + M::pos_of_reg(i, g)]);
       }
-      float nf2 = 0.f, fmax = -INFINITY, fmin = INFINITY;
+      // per-token statistics over this lane's half of the features (four partial chains each), then the other half
+      float nf2, fmax, fmin;
+      {
+        float q4[4] = {0.f, 0.f, 0.f, 0.f}, mx4[4], mn4[4];
 #pragma unroll
-      for (int ft = 0; ft < FT; ++ft)
+        for (int c = 0; c < 4; ++c) mx4[c] = -INFINITY, mn4[c] = INFINITY;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          nf2 = fmaf(f[ft][i], f[ft][i], nf2);
-          fmax = fmaxf(fmax, f[ft][i]);
-          fmin = fminf(fmin, f[ft][i]);
-        }
-      nf2 = sum32(nf2);
-      fmax = max32(fmax);
-      fmin = min32(fmin);
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            q4[i & 3] = fmaf(f[ft][i], f[ft][i], q4[i & 3]);
+            mx4[i & 3] = fmaxf(mx4[i & 3], f[ft][i]);
+            mn4[i & 3] = fminf(mn4[i & 3], f[ft][i]);
+          }
+        nf2 = sum32((q4[0] + q4[1]) + (q4[2] + q4[3]));
+        fmax = max32(fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3])));
+        fmin = min32(fminf(fminf(mn4[0], mn4[1]), fminf(mn4[2], mn4[3])));
+      }
       // u = f * ratio with ratio = ||x|| / ||f|| >= 0, so max/min of u are ratio * max/min of f;
       // exp(u - umax) = exp2(f * a1 - fmax * a1),  exp(umin - u) = exp2(fmin * a1 - f * a1).
       // Tokens kept by the softmax branch (and every token of a chunk that is not routed) get -inf offsets,
       // i.e. zero features.
       const float ratio = nf2 > 0.f ? __builtin_amdgcn_sqrtf(nx2 * fast_rcp(nf2)) : 0.f;
       const float a1 = ratio * kLog2e;
-      const bool live = kt[r] != 0;
       const float bp = live ? -fmax * a1 : -INFINITY, bn = live ? fmin * a1 : -INFINITY;
       floatx16 ep[FT], en[FT];
-      float sp = 0.f, sn = 0.f;
+      float sp, sn;
+      {
+        float p4[4] = {0.f, 0.f, 0.f, 0.f}, n4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ft = 0; ft < FT; ++ft)
+        for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          ep[ft][i] = fast_exp2(fmaf(f[ft][i], a1, bp));
-          en[ft][i] = fast_exp2(fmaf(f[ft][i], -a1, bn));
-          sp += ep[ft][i];
-          sn += en[ft][i];
-        }
-      sp = sum32(sp);
-      sn = sum32(sn);
+          for (int i = 0; i < 16; ++i) {
+            ep[ft][i] = fast_exp2(fmaf(f[ft][i], a1, bp));
+            en[ft][i] = fast_exp2(fmaf(f[ft][i], -a1, bn));
+            p4[i & 3] += ep[ft][i];
+            n4[i & 3] += en[ft][i];
+          }
+        sp = sum32((p4[0] + p4[1]) + (p4[2] + p4[3]));
+        sn = sum32((n4[0] + n4[1]) + (n4[2] + n4[3]));
+      }
       const float ip = sp > 0.f ? fast_rcp(sp) : 0.f, in = sn > 0.f ? fast_rcp(sn) : 0.f;
       // normalised features -> image [feature][token]
-      T* img = reinterpret_cast<T*>(smem + (it & 1) * L::phi_bytes) + 32 * v + r;
+      unsigned char* img = smem + (it & 1) * L::phi_bytes;
+      const int tc = 32 * v + r;
+      if constexpr (sizeof(T) == 2) {
+        // Two features of one token share a register after the conversion; neighbouring lanes (tokens r, r ^ 1)
+        // swap halves so that the even lane holds feature f of both tokens and the odd lane feature f + 1: one
+        // 4-byte store per lane and feature pair instead of two 2-byte ones.  The row's swizzle depends on the
+        // register pair (compile time), the lane group and the lane's parity.
+        const int odd = r & 1;
+        const uint32_t psel = odd ? 0x03020706u : 0x05040100u;
+        const int lane_sw = (odd << 2) | (g << 1);
+        const int piece = tc >> 3;
+        unsigned char* base0 = img + (8 * g + odd) * (L::RSTRIDE * 2) + (((piece ^ lane_sw) << 4) | (((tc >> 1) & 3) << 2));
+        unsigned char* base1 = img + (8 * g + odd) * (L::RSTRIDE * 2) + (((piece ^ lane_sw ^ 1) << 4) | (((tc >> 1) & 3) << 2));
+        auto put_pair = [&](float v0, float v1, int row_c, int ci) __attribute__((always_inline)) {
+          typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+          bf16x2 pk;
+          pk[0] = static_cast<__bf16>(v0);
+          pk[1] = static_cast<__bf16>(v1);
+          const uint32_t x = __builtin_bit_cast(uint32_t, pk);
+          const uint32_t y = (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true);   // lane ^ 1
+          const uint32_t w2 = __builtin_amdgcn_perm(y, x, psel);
+          *reinterpret_cast<uint32_t*>((ci ? base1 : base0) + row_c * (L::RSTRIDE * 2)) = w2;
+        };
 #pragma unroll
-      for (int ft = 0; ft < FT; ++ft)
+        for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int fr = 32 * ft + M::pos_of_reg(i, g);
-          img[fr * KSTRIDE] = from_f32<T>(ep[ft][i] * ip);
-          img[(DF + fr) * KSTRIDE] = from_f32<T>(en[ft][i] * in);
-        }
+          for (int i = 0; i < 16; i += 2) {
+            const int row_c = 32 * ft + 16 * (i >> 3) + (i & 6);     // compile-time part of the feature row
+            put_pair(ep[ft][i] * ip, ep[ft][i + 1] * ip, row_c, (i >> 1) & 1);
+            put_pair(en[ft][i] * in, en[ft][i + 1] * in, DF + row_c, (i >> 1) & 1);
+          }
+      } else {
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int fr = 32 * ft + M::pos_of_reg(i, g);
+            *reinterpret_cast<T*>(img + L::img_off(fr, tc)) = from_f32<T>(ep[ft][i] * ip);
+            *reinterpret_cast<T*>(img + L::img_off(DF + fr, tc)) = from_f32<T>(en[ft][i] * in);
+          }
+      }
       lds_barrier();
     }
     return;
@@ -261,10 +321,15 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
     if (gp + 1 < NP) load_v(gp + 1, vnext);
     __builtin_amdgcn_sched_barrier(0);
     const int lane_now = fresh_lane_id(), rr = lane_now & 31, gg = lane_now >> 5;
-    const T* img = reinterpret_cast<const T*>(smem + (rd & 1) * L::phi_bytes) + part * PTOK;
-    const T* abase = img + M::kappa(rr) * KSTRIDE + gg * M::KPL;
+    const unsigned char* img = smem + (rd & 1) * L::phi_bytes;
+    const int arow = M::kappa(rr), asw = L::swz(arow);     // feature tiles start at multiples of 32: same swizzle
+    const int tok_l = part * PTOK + gg * M::KPL;           // this lane's first token of k-step 0
     constexpr int NSTEP = HS * PT;
-    auto a_at = [&](int idx) { return M::load(abase + (32 * (idx % PT)) * KSTRIDE + (idx / PT) * M::KK); };
+    auto a_at = [&](int idx) {
+      const int tok = tok_l + (idx / PT) * M::KK;
+      return M::load(reinterpret_cast<const T*>(
+          img + ((32 * (idx % PT) + arow) * L::RSTRIDE + (((tok / L::EPV) ^ asw) * L::EPV) + tok % L::EPV) * (int)sizeof(T)));
+    };
     typename M::frag af[ADEPTH];
 #pragma unroll
     for (int i = 0; i < ADEPTH; ++i) af[i] = a_at(i);
@@ -275,12 +340,24 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
       if (idx + ADEPTH < NSTEP) af[idx % ADEPTH] = a_at(idx + ADEPTH);
       __builtin_amdgcn_sched_barrier(0);
     }
-    // z: this lane's feature row of the image, summed over the part's tokens
+    // z: this lane's feature row of the image, summed over the part's tokens.  The swizzle only permutes the
+    // part's 16-byte pieces among themselves (a part is an aligned block of at least 8 pieces), and the order of a
+    // sum is free: lane l starts at piece l, so that the lanes of one read spread over the banks.
     {
-      const T* zrow = img + (64 * wave + lane_now) * KSTRIDE;
+      constexpr int NPC = PTOK / L::EPV;
+      static_assert(NPC >= 8 && (NPC & (NPC - 1)) == 0, "the swizzle stays inside a part");
+      const T* zrow = reinterpret_cast<const T*>(img) + (64 * wave + lane_now) * L::RSTRIDE + part * PTOK;
       float zp = 0.f;
 #pragma unroll
-      for (int s = 0; s < PTOK / M::KPL; ++s) zp = M::sum_into(M::load(zrow + s * M::KPL), zp);
+      for (int j = 0; j < NPC; ++j) {
+        const T* pc = zrow + ((j + lane_now) & (NPC - 1)) * L::EPV;
+        if constexpr (M::KPL == 8) {
+          zp = M::sum_into(M::load(pc), zp);
+        } else {
+          const floatx4 x = *reinterpret_cast<const floatx4*>(pc);
+          zp += (x[0] + x[1]) + (x[2] + x[3]);
+        }
+      }
       z += zp;
     }
     const int ptok_end = seg_tok0 + (gp + 1) * PTOK;

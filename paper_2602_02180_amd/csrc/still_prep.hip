@@ -5,6 +5,7 @@
 //                 in MFMA-fragment order for the kernel that loads that operand straight from global memory.
 //   transpose_w : NP-Map weights [Hq,d,df] -> [Hq,df,d] (feature rows, d contiguous), or the same rows in the
 //                 operand order of the key projection.
+//   keep_mask   : the Top-lambda lists as one bit per token (what the state scan tests).
 //   gather      : Index(k, M^SA), Index(v, M^SA) of Algorithm 1: the keys of the selected tokens of
 //                 every full chunk, flattened in chunk order, as rows of kret [B,Hq,cap,d]; the values
 //                 transposed into vrett [B,Hq,d,cap].  Rows beyond the selected count are zero.
@@ -164,6 +165,27 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     for (int e = 0; e < EPV; ++e) pe[e] = tile[t0 + e][x];
     *reinterpret_cast<Vec16*>(vrett + (((int64_t)b * a.Hq + hq) * D + x) * a.cap + r0 + t0) = pk;
   }
+}
+
+// one thread per (batch, head, full chunk): the chunk's list as a bit mask
+__global__ __launch_bounds__(128) void keep_mask_kernel(KeepMaskArgs a) {
+  const int c = blockIdx.x * 128 + threadIdx.x, hq = blockIdx.y, b = blockIdx.z;
+  if (c >= a.ncf) return;
+  const int64_t chunk = ((int64_t)b * a.Hq + hq) * a.ncf + c;
+  uint32_t m[4] = {0u, 0u, 0u, 0u};
+  const int quota = chunk_quota(c, a.lam, a.rcap);
+  for (int j = 0; j < quota; ++j) {
+    const unsigned off = (unsigned)(a.sel[chunk * a.lam + j] - c * a.C);
+    if (off < (unsigned)a.C) m[off >> 5] |= 1u << (off & 31);
+  }
+  for (int i = 0; i < a.C / 32; ++i) a.kmask[chunk * (a.C / 32) + i] = m[i];
+}
+
+hipError_t launch_keep_mask(const KeepMaskArgs& a, int B, hipStream_t stream) {
+  if (a.ncf <= 0) return hipSuccess;
+  dim3 grid((a.ncf + 127) / 128, a.Hq, B), block(128);
+  hipLaunchKernelGGL(keep_mask_kernel, grid, block, 0, stream, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStream_t stream) {
