@@ -95,22 +95,34 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
   }
 
   // window softmaxes for query t (this lane and lane^32 share the query).
-  // A tile whose 32 keys are inside the window of all 32 queries of the wave needs no mask; only the oldest
-  // tile(s) (window start) and the newest one (causal limit, and the only one that can hold the diagonal key)
-  // do.  Which tiles those are is wave-uniform.
+  // The band is 32 keys longer than any window (W <= 32 (NT-1)): a slot of the oldest tile (position p) is inside
+  // query r's window only if p > r, the same slot of the newest tile only if p <= r (causal limit), so at most one
+  // of the two is ever alive.  They are merged into one value per slot, and the exponentials and logarithms run
+  // over NT-1 tiles.  The merged tile is the only one that can hold the diagonal key (slot p == r).  Of the
+  // others only those at the window start of the wave's first chunk rows need a mask; which, is wave-uniform.
   const int lo = (t - W + 1) > 0 ? (t - W + 1) : 0;
   const int lo_max = (t0 + 32 - W) > 0 ? (t0 + 32 - W) : 0;   // window start of the wave's last query
   const float sc2 = a.scale * kLog2e;
+  {
+    const int kb_old = t0 - 32 * (NT - 1);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int p = M::pos_of_reg(i, g);
+      const int key_old = kb_old + p, key_new = t0 + p;
+      const float v_old = (key_old >= lo) ? acc[0][i] : -INFINITY;         // key_old <= t always
+      acc[NT - 1][i] = (key_new <= t) ? (key_new >= lo ? acc[NT - 1][i] : -INFINITY) : v_old;
+    }
+  }
   bool full[NT];
 #pragma unroll
-  for (int j = 0; j < NT; ++j) {
+  for (int j = 1; j < NT; ++j) {
     const int kb = t0 - 32 * (NT - 1 - j);
-    full[j] = j < NT - 1 && kb >= lo_max && kb >= 0;
+    full[j] = j == NT - 1 || (kb >= lo_max && kb >= 0);
   }
   // pass 1: masked logits (raw, the positive scale commutes with the maximum) and their maximum
   float mraw = -INFINITY;
 #pragma unroll
-  for (int j = 0; j < NT; ++j) {
+  for (int j = 1; j < NT; ++j) {
     const int kb = t0 - 32 * (NT - 1 - j);
     if (!full[j]) {
 #pragma unroll
@@ -124,11 +136,11 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
   }
   mraw = max32(mraw);
   // pass 2: e = exp(scale * (x - max)); masked entries give exp2(-inf) = 0.  The sums without the diagonal
-  // differ from the full sums only in the newest tile.
+  // differ from the full sums only in the merged tile.
   const float moff = -mraw * sc2;
   float d_old = 0.f, d_new = 0.f, d_new_no = 0.f;
 #pragma unroll
-  for (int j = 0; j < NT; ++j) {
+  for (int j = 1; j < NT; ++j) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const float e = fast_exp2(fmaf(acc[j][i], sc2, moff));
@@ -137,7 +149,7 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
         d_old += e;
       } else {
         d_new += e;
-        d_new_no += (M::pos_of_reg(i, g) == r) ? 0.f : e;   // key t0 + pos is the query itself iff pos == r
+        d_new_no += (M::pos_of_reg(i, g) == r) ? 0.f : e;   // slot p == r of the merged tile is the query itself
       }
     }
   }
@@ -146,25 +158,18 @@ __global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
   d_no = sum32(d_no);
   const float inv_all = 1.0f / d_all;
   const float inv_no = d_no > 0.f ? 1.0f / d_no : 0.f;
-  // pass 3: sum of a_diag * (log(a_diag + eps) - log(a_nodiag + eps)); a masked entry has a_diag = 0 and
-  // is skipped explicitly (with eps = 0 its term would be 0 * (inf - inf))
+  // pass 3: sum of a_diag * (log(a_diag + eps) - log(a_nodiag + eps)).  A masked entry has a_diag = a_nodiag = 0:
+  // its term is 0 * (log eps - log eps) = 0 (eps > 0 is checked on the host).
   float score = 0.f;
 #pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    const int kb = t0 - 32 * (NT - 1 - j);
+  for (int j = 1; j < NT; ++j) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const float e = acc[j][i];
       const float ad = e * inv_all;
       float an = e * inv_no;
       if (j == NT - 1) an = (M::pos_of_reg(i, g) == r) ? 0.f : an;
-      const float term = ad * (fast_log2(ad + a.eps) - fast_log2(an + a.eps));
-      if (full[j]) {
-        score += term;
-      } else {
-        const int key = kb + M::pos_of_reg(i, g);
-        score += (key >= lo && key <= t) ? term : 0.f;
-      }
+      score = fmaf(ad, fast_log2(ad + a.eps) - fast_log2(an + a.eps), score);
     }
   }
   score *= kLn2;
@@ -253,7 +258,7 @@ hipError_t launch_group_select(const ScoreArgs& a, int B, int Hkv, hipStream_t s
 template <typename T, int D>
 static hipError_t launch_score_t(const ScoreArgs& a, int B, int nc, hipStream_t stream) {
   dim3 grid(nc * a.Hq, 1, B), block((a.C / 32) * 64);
-  if (a.W <= 65)
+  if (a.W <= 64)   // the band must be at least 32 keys longer than the window less one: W <= 32 (NT - 1)
     hipLaunchKernelGGL((score_select_kernel<T, D, 3>), grid, block, 0, stream, a);
   else
     hipLaunchKernelGGL((score_select_kernel<T, D, 5>), grid, block, 0, stream, a);

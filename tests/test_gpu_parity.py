@@ -132,6 +132,14 @@ def test_c1_fp32_full():
     dict(dtype="bf16", d=128, C=128, W=128, N=1000, Hq=4, Hkv=2, B=2),
     dict(dtype="bf16", d=128, C=64, W=128, N=777),
     dict(dtype="bf16", d=64, C=128, W=33, N=1024, lam=5),
+    # window lengths around the band tiles of the score kernel (a one-key window gives every token the same score:
+    # the selection is then decided by the tie-break alone)
+    dict(dtype="f32", d=64, C=64, W=1, N=200),
+    dict(dtype="f32", d=64, C=64, W=5, N=300),
+    dict(dtype="f32", d=64, C=64, W=31, N=300),
+    dict(dtype="f32", d=64, C=128, W=32, N=400),
+    dict(dtype="f32", d=128, C=64, W=65, N=300),
+    dict(dtype="bf16", d=128, C=128, W=66, N=600),
     # long retained sets: the sparse-attention kernel's steady-state loop over fully visible retained tiles,
     # with workgroups spanning two chunks (C = 64) and ragged ends
     dict(dtype="f32", d=64, C=64, W=64, N=1500, lam=32),
