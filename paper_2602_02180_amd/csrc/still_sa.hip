@@ -371,10 +371,18 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       // are applied to the accumulator): f^T = W_q^T Q^T, statistics per lane, u = f * ||q|| / ||f||
       typename M::frag pfr[NWT][2][SPT], nfr[NWT][2][SPT];
       float ip = 0.f, in = 0.f, sn_keep = 1.f, dla = 0.f;
+      floatx16 f[NWT][2];
       if (mine) {
-        floatx16 f[NWT][2];
 #pragma unroll
         for (int wt = 0; wt < NWT; ++wt) sa_qk<T, D>(Kl + wt * Cf::K_ELEMS, qf, f[wt], r, g);
+      }
+      lds_barrier();   // every wave has read W_q^T: the K slots are free
+      // the other two state tiles of the first chunk travel to the K slots under the feature map's vector work
+      if (NST > 2) {
+        request_s(la_lo, 2, slot_of(2));
+        request_s(la_lo, 3, slot_of(3));
+      }
+      if (mine) {
         if (a.bq != nullptr) {
           const T* bq = static_cast<const T*>(a.bq) + (int64_t)hq * DF;
 #pragma unroll
@@ -384,28 +392,35 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
 #pragma unroll
               for (int i = 0; i < 16; ++i) f[wt][mt][i] += to_f32(bq[64 * wt + 32 * mt + M::pos_of_reg(i, g)]);
         }
-        float nx2 = 0.f, nf2 = 0.f, fmax = -INFINITY, fmin = INFINITY;
+        // statistics of the query's features: four partial chains each, then the other lane group's half
+        float nx2, nf2, fmax, fmin;
+        {
+          float x4[4] = {0.f, 0.f, 0.f, 0.f}, q4[4] = {0.f, 0.f, 0.f, 0.f}, mx4[4], mn4[4];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) nx2 = M::dot_into(qf[s], qf[s], nx2);
+          for (int c = 0; c < 4; ++c) mx4[c] = -INFINITY, mn4[c] = INFINITY;
 #pragma unroll
-        for (int wt = 0; wt < NWT; ++wt)
+          for (int s = 0; s < KS; ++s) x4[s & 3] = M::dot_into(qf[s], qf[s], x4[s & 3]);
 #pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
+          for (int wt = 0; wt < NWT; ++wt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              nf2 = fmaf(f[wt][mt][i], f[wt][mt][i], nf2);
-              fmax = fmaxf(fmax, f[wt][mt][i]);
-              fmin = fminf(fmin, f[wt][mt][i]);
-            }
-        nx2 = sum32(nx2);
-        nf2 = sum32(nf2);
-        fmax = max32(fmax);
-        fmin = min32(fmin);
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) {
+                q4[i & 3] = fmaf(f[wt][mt][i], f[wt][mt][i], q4[i & 3]);
+                mx4[i & 3] = fmaxf(mx4[i & 3], f[wt][mt][i]);
+                mn4[i & 3] = fminf(mn4[i & 3], f[wt][mt][i]);
+              }
+          nx2 = sum32((x4[0] + x4[1]) + (x4[2] + x4[3]));
+          nf2 = sum32((q4[0] + q4[1]) + (q4[2] + q4[3]));
+          fmax = max32(fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3])));
+          fmin = min32(fminf(fminf(mn4[0], mn4[1]), fminf(mn4[2], mn4[3])));
+        }
         const float ratio = nf2 > 0.f ? __builtin_amdgcn_sqrtf(nx2 * fast_rcp(nf2)) : 0.f;
         const float a1 = ratio * kLog2e;
         const float bp = -fmax * a1, bn = fmin * a1;
         const float* zc = zl + (cw - la_lo) * DP;
-        float sp = 0.f, sn = 0.f, dp = 0.f, dn = 0.f;
+        float sp4[4] = {0.f, 0.f, 0.f, 0.f}, sn4[4] = {0.f, 0.f, 0.f, 0.f};
+        float dp4[4] = {0.f, 0.f, 0.f, 0.f}, dn4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int wt = 0; wt < NWT; ++wt)
 #pragma unroll
@@ -415,19 +430,29 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
             for (int i = 0; i < 16; ++i) {
               ep[i] = fast_exp2(fmaf(f[wt][mt][i], a1, bp));
               en[i] = fast_exp2(fmaf(f[wt][mt][i], -a1, bn));
-              sp += ep[i];
-              sn += en[i];
+              sp4[i & 3] += ep[i];
+              sn4[i & 3] += en[i];
             }
-            // D_LA: the same weights against z (positions of one register octet are consecutive features)
+            // D_LA: the same weights against z.  The features of four consecutive registers are consecutive (both
+            // operand conventions), and every lane of a group reads the same address: 16-byte broadcast reads.
 #pragma unroll
-            for (int o8 = 0; o8 < 2; ++o8) {
-              const int fbase = 64 * wt + 32 * mt + (M::KPL == 8 ? 16 * o8 + 8 * g : 0);
+            for (int i4 = 0; i4 < 4; ++i4) {
+              const int fi = 64 * wt + 32 * mt + M::pos_of_reg(4 * i4, g);
+              if constexpr (M::KPL == 8) {
+                const floatx4 zp = *reinterpret_cast<const floatx4*>(zc + fi);
+                const floatx4 zn = *reinterpret_cast<const floatx4*>(zc + DF + fi);
 #pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                const int i = 8 * o8 + e;
-                const int fi = M::KPL == 8 ? fbase + e : 64 * wt + 32 * mt + M::pos_of_reg(i, g);
-                dp = fmaf(ep[i], zc[fi], dp);
-                dn = fmaf(en[i], zc[DF + fi], dn);
+                for (int e = 0; e < 4; ++e) {
+                  dp4[e] = fmaf(ep[4 * i4 + e], zp[e], dp4[e]);
+                  dn4[e] = fmaf(en[4 * i4 + e], zn[e], dn4[e]);
+                }
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const int fe = 64 * wt + 32 * mt + M::pos_of_reg(4 * i4 + e, g);
+                  dp4[e] = fmaf(ep[4 * i4 + e], zc[fe], dp4[e]);
+                  dn4[e] = fmaf(en[4 * i4 + e], zc[DF + fe], dn4[e]);
+                }
               }
             }
 #pragma unroll
@@ -436,30 +461,39 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
               nfr[wt][mt][s] = M::from_acc(en, s);
             }
           }
-        sp = sum32(sp);
-        sn = sum32(sn);
+        const float sp = sum32((sp4[0] + sp4[1]) + (sp4[2] + sp4[3]));
+        const float sn = sum32((sn4[0] + sn4[1]) + (sn4[2] + sn4[3]));
         ip = fast_rcp(sp);
         in = fast_rcp(sn);
         sn_keep = sn;
-        dla = sum32(dp) * ip + sum32(dn) * in;
+        dla = sum32((dp4[0] + dp4[1]) + (dp4[2] + dp4[3])) * ip + sum32((dn4[0] + dn4[1]) + (dn4[2] + dn4[3])) * in;
       }
-      lds_barrier();   // every wave has read W_q^T: the K slots are free
 
-      // "S^T tile x phi_q^T" into the accumulator, tile jt from its slot (a wave joins only for its own chunk)
+      // "S^T tile x phi_q^T" into the accumulator, tile jt from its slot (a wave joins only for its own chunk).  The
+      // S^T fragments are read PDEPTH products ahead of their use (the scheduling barriers pin that order).
       auto la_pv = [&](int jt_c, const T* Vs) __attribute__((always_inline)) {
         static_for<NST>([&](auto JT) __attribute__((always_inline)) {
           constexpr int jt = decltype(JT)::value;
           if (jt == jt_c) {
             constexpr int wt = jt % NWT;
+            constexpr int NPV = 2 * SPT * DT;                       // product idx: (mt, s) = idx / DT, dt = idx % DT
+            constexpr int PDEPTH = NPV < 8 ? NPV : 8;
+            auto a_at = [&](int idx) {
+              const int ms = idx / DT;
+              return M::load(Vs + Cf::voff(32 * (idx % DT) + r, 32 * (ms / SPT) + (ms % SPT) * M::KK + g * M::KPL));
+            };
+            typename M::frag af[PDEPTH];
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+            for (int i = 0; i < PDEPTH; ++i) af[i] = a_at(i);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-              for (int s = 0; s < SPT; ++s) {
-                const typename M::frag pf = jt < NWT ? pfr[wt][mt][s] : nfr[wt][mt][s];
-                const int e = 32 * mt + s * M::KK + g * M::KPL;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) o[dt] = M::mma(M::load(Vs + Cf::voff(32 * dt + r, e)), pf, o[dt]);
-              }
+            for (int idx = 0; idx < NPV; ++idx) {
+              const int ms = idx / DT;
+              const typename M::frag pf = jt < NWT ? pfr[wt][ms / SPT][ms % SPT] : nfr[wt][ms / SPT][ms % SPT];
+              o[idx % DT] = M::mma(af[idx % PDEPTH], pf, o[idx % DT]);
+              if (idx + PDEPTH < NPV) af[idx % PDEPTH] = a_at(idx + PDEPTH);
+              __builtin_amdgcn_sched_barrier(0);
+            }
             if (jt == NWT - 1) {       // the positive half is complete: (ip / in) A now, + B and * in later = ip A + in B
               const float k1 = ip * sn_keep;
 #pragma unroll
@@ -472,29 +506,31 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       };
       for (int cc = la_lo; cc <= la_hi; ++cc) {
         const bool now = mine && cw == cc;
-        if (cc > la_lo) {               // second chunk of the workgroup: its first two tiles (the V slots are free)
+        if (cc > la_lo) {               // second chunk of the workgroup (all four slots are free)
           request_s(cc, 0, slot_of(0));
           request_s(cc, 1, slot_of(1));
+          if (NST > 2) {
+            request_s(cc, 2, slot_of(2));
+            request_s(cc, 3, slot_of(3));
+          }
           wait_async_copies();
           lds_barrier();
-        }
-        if (NST > 2) {                  // the other two tiles go to the K slots while the first two are used
-          request_s(cc, 2, slot_of(2));
-          request_s(cc, 3, slot_of(3));
         }
         if (now) {
           la_pv(0, slot_of(0));
           la_pv(1, slot_of(1));
         }
-        wait_async_copies();
-        lds_barrier();
         if (NST > 2) {
+          if (cc == la_lo) {            // the first chunk's tiles 2, 3 were requested above, under the vector work
+            wait_async_copies();
+            lds_barrier();
+          }
           if (now) {
             la_pv(2, slot_of(2));
             la_pv(3, slot_of(3));
           }
-          lds_barrier();
         }
+        lds_barrier();                  // the slots may be refilled
       }
       if (mine) {
         la_done = true;
