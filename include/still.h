@@ -83,6 +83,10 @@ typedef struct still_params {
   int32_t emit_terms;            /* inspection hook, normally 0.  1: the prefill also leaves the linear-branch
                                     terms of every row in the workspace (regions n_la, d_la of the layout), which
                                     then needs room for them; the results are the same either way.             */
+  int32_t gate_activation;       /* 0: g multiplies the linear numerator as given (already activated).
+                                    1: g holds a pre-activation (x W_g of Sec. 3.2) and the kernels apply the
+                                    logistic function 1 / (1 + exp(-g)) where they read it; the paper names no
+                                    activation, this one is an option of this library.  Prefill and decode.   */
   int64_t q_sb, q_st, q_sh;      /* q   [B, N, Hq,  d]                                                     */
   int64_t k_sb, k_st, k_sh;      /* k   [B, N, Hkv, d]                                                     */
   int64_t v_sb, v_st, v_sh;      /* v   [B, N, Hkv, d]                                                     */

@@ -228,12 +228,25 @@ def np_map_u(x: np.ndarray, Wm: np.ndarray, b: Optional[np.ndarray] = None) -> n
 # shared result container
 # ----------------------------------------------------------------------------
 
-def _prep(q, k, v, g, Wq, Wk, bq, bk):
+def gate_activate(g: Optional[np.ndarray], gate_activation: str = "none") -> Optional[np.ndarray]:
+    """The gate as it multiplies the linear numerator (Sec. 3.2: g comes from a projection W_g; the paper names no
+    activation).  "none": g is used as given (already activated by the caller); "sigmoid": g holds the
+    pre-activation x W_g and the gate is its logistic function."""
+    if g is None:
+        return None
+    g = np.asarray(g, F64)
+    if gate_activation == "none":
+        return g
+    if gate_activation == "sigmoid":
+        return 1.0 / (1.0 + np.exp(-g))
+    raise ValueError(f"unknown gate activation {gate_activation!r}")
+
+
+def _prep(q, k, v, g, Wq, Wk, bq, bk, gate_activation="none"):
     q = np.asarray(q, F64)
     k = np.asarray(k, F64)
     v = np.asarray(v, F64)
-    g = None if g is None else np.asarray(g, F64)
-    return q, k, v, g
+    return q, k, v, gate_activate(g, gate_activation)
 
 
 def _result(N, d, rows):
@@ -270,11 +283,11 @@ def _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained=None):
 
 def still_definition(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
                      sel=None, score=None, rows: Optional[Tuple[int, int]] = None,
-                     max_retained: Optional[int] = None) -> Dict:
+                     max_retained: Optional[int] = None, gate_activation: str = "none") -> Dict:
     """Row t in chunk c sees, through exp: the local span (previous chunk and own chunk up to t)
     plus the selected tokens of chunks <= c-2; through phi_q.phi_k: every other token of
     chunks <= c-2.  One division merges them."""
-    q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk)
+    q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk, gate_activation)
     N, d = q.shape
     score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained)
     phi_q = np_map(q, Wq, bq)
@@ -313,12 +326,12 @@ def still_definition(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None
 
 def still_recurrent(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
                     sel=None, score=None, rows: Optional[Tuple[int, int]] = None,
-                    return_state: bool = False, max_retained: Optional[int] = None) -> Dict:
+                    return_state: bool = False, max_retained: Optional[int] = None, gate_activation: str = "none") -> Dict:
     """Step t (1-indexed as in the paper) is written t = (a+1)C + b with 1 <= b <= C.
     When b == 1 and a >= 1 the chunk a (tokens (a-1)C+1 .. aC) is routed: its top-lambda
     keys/values join the retained part of the cache, the others are added to (s, z).
     The cache also always holds the local span aC < i <= t."""
-    q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk)
+    q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk, gate_activation)
     N, d = q.shape
     score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained)
     dprime = 2 * np.asarray(Wq).shape[1]
@@ -367,11 +380,11 @@ def still_recurrent(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
 
 def still_chunkwise(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
                     sel=None, score=None, rows: Optional[Tuple[int, int]] = None,
-                     max_retained: Optional[int] = None) -> Dict:
+                     max_retained: Optional[int] = None, gate_activation: str = "none") -> Dict:
     """Chunk tensors; per-chunk states phi_k(k_LA)^T v_LA cumulated over chunks and delayed by
     two; chunk c attends with exp to the flattened selected keys of chunks <= c-2, to the whole
     previous chunk and causally to itself; a single division merges both branches."""
-    q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk)
+    q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk, gate_activation)
     N, d = q.shape
     score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained)
     T = -(-N // C)
@@ -453,7 +466,8 @@ def still_forward_units(inputs: Dict[str, np.ndarray], kv_map: np.ndarray, units
                         form: str = "chunkwise", sel: Optional[np.ndarray] = None,
                         rows: Optional[Tuple[int, int]] = None,
                         max_retained: Optional[int] = None,
-                        shared_selection: bool = False) -> Dict[Tuple[int, int], Dict]:
+                        shared_selection: bool = False,
+                        gate_activation: str = "none") -> Dict[Tuple[int, int], Dict]:
     """Run one form on the listed (b, hq) units of a batched problem.
 
     inputs: q [B,N,Hq,d], k,v [B,N,Hkv,d], Wq,Wk [Hq,d,d_f], optional g [B,N,Hq,d],
@@ -482,6 +496,6 @@ def still_forward_units(inputs: Dict[str, np.ndarray], kv_map: np.ndarray, units
             s_in = select_top_lambda(rank, C, lam, max_retained)
         out[(b, h)] = fn(inputs["q"][b, :, h], inputs["k"][b, :, kh], inputs["v"][b, :, kh], g,
                          inputs["Wq"][h], inputs["Wk"][h], C, W, lam, scale, eps, bq=bq, bk=bk,
-                         sel=s_in, rows=rows, max_retained=max_retained)
+                         sel=s_in, rows=rows, max_retained=max_retained, gate_activation=gate_activation)
         out[(b, h)]["rank_score"] = out[(b, h)]["score"] if rank is None else rank
     return out

@@ -105,6 +105,8 @@ still_status_t validate_params(const still_params_t* p, bool need_n) {
   if (need_n && p->N < 1) return fail(STILL_ERR_INVALID_ARG, "N must be >= 1 (got %d)", p->N);
   if (p->lambda < 0 || p->lambda > p->C) return fail(STILL_ERR_INVALID_ARG, "lambda %d outside [0, C=%d]", p->lambda, p->C);
   if (p->W < 1) return fail(STILL_ERR_INVALID_ARG, "W must be >= 1");
+  if (p->gate_activation != 0 && p->gate_activation != 1)
+    return fail(STILL_ERR_INVALID_ARG, "gate_activation %d unknown (0: none, 1: sigmoid)", p->gate_activation);
   if (!(p->eps > 0.f)) return fail(STILL_ERR_INVALID_ARG, "eps must be > 0");
   if (!(p->scale > 0.f)) return fail(STILL_ERR_INVALID_ARG, "scale must be > 0");
   if (p->Hq > still::kMaxHq) return fail(STILL_ERR_UNSUPPORTED, "Hq %d > %d", p->Hq, still::kMaxHq);
@@ -486,7 +488,7 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   sx.k_sb = p->k_sb; sx.k_st = p->k_st; sx.k_sh = p->k_sh;
   sx.vt = ws + L.vt; sx.kret = ws + L.kret; sx.vrett = ws + L.vrett;
   sx.wqt = ws + L.wqt; sx.bq = bq;
-  sx.g = g; sx.g_sb = p->g_sb; sx.g_st = p->g_st; sx.g_sh = p->g_sh;
+  sx.g = g; sx.g_sb = p->g_sb; sx.g_st = p->g_st; sx.g_sh = p->g_sh; sx.gate_act = p->gate_activation != 0;
   sx.snap = la.snap; sx.zsnap = la.zsnap; sx.nc = nc;
   sx.n_la_out = p->emit_terms ? reinterpret_cast<float*>(ws + L.n_la) : nullptr;
   sx.d_la_out = p->emit_terms ? reinterpret_cast<float*>(ws + L.d_la) : nullptr;
@@ -638,6 +640,7 @@ still_status_t decode_step(const still_params_t* p, void* state, int32_t t, cons
   a.cap = L.cap; a.R = L.R; a.nchunks = L.n_chunks; a.t = t; a.rcap = retained_budget(p);
   a.scale = p->scale; a.eps = p->eps;
   a.tpos = t_dev; a.max_tokens = p->max_tokens; a.shared = p->shared_selection != 0;
+  a.gate_act = p->gate_activation != 0;
   const int c = t / p->C;
   const int rows = still::retained_rows(c >= 1 ? c - 1 : 0, p->lambda, a.rcap) + (t - (c >= 1 ? c - 1 : 0) * p->C + 1);
   const int units = p->B * (p->shared_selection ? p->Hkv : p->Hq);   // workgroups per split

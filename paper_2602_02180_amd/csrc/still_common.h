@@ -143,6 +143,9 @@ __device__ __forceinline__ float to_f32(T x) { return static_cast<float>(x); }
 template <typename T>
 __device__ __forceinline__ T from_f32(float x) { return static_cast<T>(x); }
 
+// logistic function through the hardware exp2 / rcp
+__device__ __forceinline__ float fast_sigmoid(float x) { return fast_rcp(1.0f + fast_exp2(-x * kLog2e)); }
+
 __device__ __forceinline__ floatx16 zero16() {
   floatx16 z;
 #pragma unroll

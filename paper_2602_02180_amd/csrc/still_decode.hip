@@ -666,7 +666,10 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(DecArgs a) {
     float nla = 0.f;
 #pragma unroll
     for (int rp = 0; rp < RP; ++rp) nla += red[rp][tid];
-    if (a.g != nullptr) nla *= to_f32(static_cast<const T*>(a.g)[unit * D + tid]);
+    if (a.g != nullptr) {
+      const float gx = to_f32(static_cast<const T*>(a.g)[unit * D + tid]);
+      nla *= a.gate_act ? fast_sigmoid(gx) : gx;
+    }
     const float y = (fs * acc + fl * nla) / (fs * L + fl * dl);
     static_cast<T*>(a.out)[unit * D + tid] = from_f32<T>(y);
   }

@@ -140,6 +140,7 @@ struct SaArgs {
   const void* bq;      // nullable [Hq, df]
   const void* g;       // nullable gate [B, N, Hq, d]
   int64_t g_sb, g_st, g_sh;
+  int gate_act;        // 1: g is a pre-activation, the gate is its logistic function
   const void* snap;    // [B, Hq, nc][D][DP]: see LaArgs
   const float* zsnap;  // [B, Hq, nc][DP]
   float* n_la_out;     // nullable [B, Hq, N, d]: the gated linear numerator of every row (inspection)
@@ -173,6 +174,7 @@ struct DecArgs {
   HeadMap map;
   int B, Hq, Hkv, C, W, lam, cap, R, nchunks, t, nsplit, rcap;
   int shared;              // 1: the query heads of one kv head rank by their summed score (one list per group)
+  int gate_act;            // 1: g is a pre-activation, the gate is its logistic function
   const int32_t* tpos;     // nullable, device [B]: index of each sequence's new token (t is then ignored)
   int max_tokens;
   float scale, eps;

@@ -545,7 +545,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
               const T* gp = static_cast<const T*>(a.g) + (int64_t)b * a.g_sb + (int64_t)tq * a.g_st +
                             (int64_t)hq * a.g_sh + x0;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) gv[e] = to_f32(gp[e]);
+              for (int e = 0; e < 4; ++e) gv[e] = a.gate_act ? fast_sigmoid(to_f32(gp[e])) : to_f32(gp[e]);
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[dt][4 * i4 + e] *= in * gv[e];

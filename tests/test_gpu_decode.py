@@ -16,7 +16,7 @@ from tests import gpu_util as U
 pytestmark = pytest.mark.gpu
 
 
-def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False):
+def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False, gate_activation=0):
     """Prefill tokens [0, n_prefill) with state_out (or start from an empty state), then decode up to n_total."""
     import torch
 
@@ -26,7 +26,8 @@ def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False):
     B = w.B
     out = torch.full((B, n_total, w.Hq, w.d), float("nan"), dtype=full["q"].dtype, device=dev)
     base = dict(B=B, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype=w.dtype,
-                d_f=w.df, kv_head_of_q=kv_map, max_tokens=n_total, max_retained=w.max_retained, shared_selection=w.shared_selection)
+                d_f=w.df, kv_head_of_q=kv_map, max_tokens=n_total, max_retained=w.max_retained, shared_selection=w.shared_selection,
+                gate_activation=gate_activation)
     ps = S.make_params(N=1, **base)
     state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
     S.still_state_init(ps, state)
@@ -94,8 +95,10 @@ def run_decode_staggered(w, inp, n_total, offsets, tight_bound=True):
     return synth.from_torch(out), sel
 
 
-def check_decode(w, inp, n_prefill, n_total, with_gate=False, result=None):
-    got, sel_h = result if result is not None else run_decode(w, inp, n_prefill, n_total, with_gate=with_gate)
+def check_decode(w, inp, n_prefill, n_total, with_gate=False, result=None, gate_activation=0):
+    got, sel_h = result if result is not None else run_decode(w, inp, n_prefill, n_total, with_gate=with_gate,
+                                                              gate_activation=gate_activation)
+    act = "sigmoid" if gate_activation else "none"
     kv_map = synth.kv_head_map(w)
     sub = {k: (v[:, :n_total] if k in ("q", "k", "v", "g") else v) for k, v in inp.items() if k != "heavy"}
     if not with_gate:
@@ -117,7 +120,8 @@ def check_decode(w, inp, n_prefill, n_total, with_gate=False, result=None):
                 assert np.all(sel_h[b, h, c][:quota] >= 0) and np.all(sel_h[b, h, c][quota:] == -1), (b, h, c)
                 sel_full[c] = sel_h[b, h, c]
             ref = O.still_forward_units(sub, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                                        sel=sel_full[None, None].repeat(w.B, 0).repeat(w.Hq, 1))[(b, h)]
+                                        sel=sel_full[None, None].repeat(w.B, 0).repeat(w.Hq, 1),
+                                        gate_activation=act)[(b, h)]
             x = got[b, n_prefill:n_total, h].astype(np.float64)
             y = ref["out"][n_prefill:n_total]
             assert np.all(np.isfinite(x))
@@ -196,6 +200,15 @@ def test_decode_with_gate():
     w = wl("decg", dtype="f32", d=64, C=64, W=64, lam=8)
     inp = synth.make_inputs(w, seed=23, n_tokens=280, with_gate=True)
     check_decode(w, inp, 150, 280, with_gate=True)
+
+
+def test_decode_with_sigmoid_gate_from_preactivation():
+    """gate_activation = 1 through prefill, hand-over and decode steps: the gate arrives as a pre-activation."""
+    w = wl("decsg", dtype="f32", d=64, C=64, W=64, lam=8)
+    inp = synth.make_inputs(w, seed=29, n_tokens=280)
+    rng = np.random.default_rng(30)
+    inp["g"] = synth.round_to_dtype(2.0 * rng.standard_normal(inp["q"].shape), w.dtype)
+    check_decode(w, inp, 150, 280, with_gate=True, gate_activation=1)
 
 
 def test_decode_rejects_token_beyond_capacity():

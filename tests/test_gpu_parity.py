@@ -224,6 +224,24 @@ def test_gate_bias_and_custom_head_map():
     run_case(w, inp, kv_map=kv_map)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sigmoid_gate_from_preactivation(dtype):
+    """gate_activation = 1: g holds the pre-activation and the kernel applies the logistic function where it reads
+    the gate (prefill: the prologue of the sparse-attention kernel)."""
+    w = small("sgate", N=700, Hq=2, Hkv=1, dtype=dtype, d=128 if dtype == "bf16" else 64, C=64, W=64, lam=8)
+    inp = synth.make_inputs(w, seed=19)
+    rng = np.random.default_rng(20)
+    inp["g"] = synth.round_to_dtype(2.0 * rng.standard_normal(inp["q"].shape), w.dtype)
+    units = all_units(w)
+    hip = U.run_hip(w, inp, gate_activation=1)
+    ref = U.oracle_units(w, inp, units, sel=hip["sel"], gate_activation="sigmoid")
+    check_terms(w, hip, ref, units, "sigmoid gate")
+    check_outputs(w, hip, ref, units, "sigmoid gate")
+    # and it is not the identity: the same numbers taken as they stand give something else
+    raw = U.run_hip(w, inp, gate_activation=0)
+    assert np.max(np.abs(raw["out"].astype(np.float64) - hip["out"].astype(np.float64))) > 1e-3
+
+
 def test_heavy_hitter_keys_bf16():
     w = small("heavy", N=2048, Hq=2, Hkv=1, dtype="bf16", d=128, C=128, W=128, heavy_frac=0.01)
     run_case(w, synth.make_inputs(w, seed=11))

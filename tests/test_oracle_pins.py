@@ -203,6 +203,26 @@ def test_gate_multiplies_linear_numerator_only():
                                rtol=1e-10, atol=1e-14)
 
 
+@pytest.mark.parametrize("form", FORMS)
+def test_sigmoid_gate_literals(form):
+    """Gate given as a pre-activation (Sec. 3.2: the gate comes from a projection W_g; sigmoid is this build's
+    option, the paper names no activation): literal values of the logistic function, no formula retyped.
+    sigmoid(0) = 1/2 halves the linear numerator; +-40 are 1 and 0 to machine precision; ln 3 gives 3/4."""
+    q, k, v, g, Wq, Wk = rand_problem(23, 48, 8)
+    kw = dict(C=8, W=8, lam=2, scale=0.35, eps=EPS)
+    r0 = form(q, k, v, None, Wq, Wk, **kw)
+    for x, val in ((0.0, 0.5), (40.0, 1.0), (-40.0, 0.0), (np.log(3.0), 0.75), (-np.log(3.0), 0.25)):
+        r = form(q, k, v, np.full_like(g, x), Wq, Wk, gate_activation="sigmoid", **kw)
+        np.testing.assert_allclose(r["N_LA"], val * r0["N_LA"], rtol=1e-12, atol=1e-16)
+        np.testing.assert_array_equal(r["D_LA"], r0["D_LA"])
+    # without the option the same numbers are used as they stand
+    r = form(q, k, v, np.full_like(g, 0.5), Wq, Wk, **kw)
+    ra = form(q, k, v, np.zeros_like(g), Wq, Wk, gate_activation="sigmoid", **kw)
+    np.testing.assert_allclose(r["out"], ra["out"], rtol=1e-13)
+    with pytest.raises(ValueError):
+        form(q, k, v, g, Wq, Wk, gate_activation="tanh", **kw)
+
+
 # --------------------------------------------------------------------------- score
 def test_score_of_one_token_window_is_closed_value():
     q, k, *_ = rand_problem(10, 12, 8)
