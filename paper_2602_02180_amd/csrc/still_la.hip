@@ -105,6 +105,9 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 
   if (wave >= NCW) {
     // ------------------------------------------------------------------ producer wave v
+    // The producers are the critical path of a round (the consumers wait for them at the barrier): where both
+    // waves of a SIMD are ready, the producer goes first.
+    __builtin_amdgcn_s_setprio(3);
     const int v = wave - NCW;
     const T* __restrict__ kbase = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)kvh * a.k_sh;
     const T* __restrict__ wkf = static_cast<const T*>(a.wkf) + (int64_t)hq * DF * D;
