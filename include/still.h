@@ -113,9 +113,11 @@ typedef struct still_ws_layout {
   size_t vrett;    /* dtype   [B, Hq, d, cap]                    retained values, transposed               */
   size_t wqt;      /* dtype   [Hq, d_f, d]                       Wq transposed                             */
   size_t wkf;      /* dtype   [Hq, d_f * d]                      Wk transposed, in matrix-operand order    */
-  size_t seg;      /* float   [B, Hq, nseg, 2*d_f*(d+1)]         per-segment linear-attention states       */
-  size_t snap;     /* dtype   [B, Hq, ceil(N/C), d, 2*d_f]       S^T through chunk c-2, for the rows of chunk c */
-  size_t zsnap;    /* float   [B, Hq, ceil(N/C), 2*d_f]          z through chunk c-2                       */
+  size_t seg;      /* float   [B, Hq, nseg, 2*d_f*(d+1)]         per-segment totals of the linear-attention state */
+  size_t snap;     /* dtype   [B, Hq, ceil(N/C), d, 2*d_f]       S^T summed inside chunk c's segment, through chunk c-2 */
+  size_t zsnap;    /* float   [B, Hq, ceil(N/C), 2*d_f]          z likewise                                */
+  size_t pimg;     /* dtype   [B, Hq, nseg, d, 2*d_f]            S^T through the chunk before the segment (prefix) */
+  size_t zpre;     /* float   [B, Hq, nseg, 2*d_f]               z likewise                                */
   size_t kmask;    /* uint32  [B, Hq, N/C, C/32]                 the selection as one bit per token        */
   size_t n_la;     /* float   [B, Hq, N, d]                      gated linear-branch numerator N_LA (emit_terms) */
   size_t d_la;     /* float   [B, Hq, N]                         linear-branch normaliser D_LA (emit_terms) */

@@ -34,7 +34,7 @@ struct Profile {
 };
 thread_local Profile g_prof;
 const char* const kSlotNames[STILL_PROFILE_SLOTS] = {"transpose_v", "transpose_w", "score_select", "gather",
-                                                     "la_sums",     "la_prefix",   "la_states",    "sparse_attn_merge"};
+                                                     "keep_mask",   "la_states",   "la_prefix",    "sparse_attn_merge"};
 
 void prof_begin(int slot, hipStream_t stream) {
   if (!g_prof.on || (g_prof.last_only && slot != STILL_PROFILE_SLOTS - 1)) return;
@@ -202,6 +202,8 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   L->seg = take((size_t)B * Hq * nseg * (2 * df * (d + 1)) * 4);
   L->snap = take((size_t)B * Hq * nc * d * (2 * df) * es);
   L->zsnap = take((size_t)B * Hq * nc * (2 * df) * 4);
+  L->pimg = take((size_t)B * Hq * nseg * d * (2 * df) * es);
+  L->zpre = take((size_t)B * Hq * nseg * (2 * df) * 4);
   L->kmask = take((size_t)B * Hq * ncf * (p->C / 32) * 4);
   L->n_la = take(p->emit_terms ? (size_t)B * Hq * N * d * 4 : 0);
   L->d_la = take(p->emit_terms ? (size_t)B * Hq * N * 4 : 0);
@@ -446,7 +448,7 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   // everything below reads the transposed copies
   if ((e = join_side()) != hipSuccess) return hip_fail("side stream", e);
 
-  // NP-Map of the keys + scan of the linear-attention state: segment sums, prefix, per-chunk states
+  // NP-Map of the keys + scan of the linear-attention state: per-chunk sums inside every segment, prefix over segments
   still::LaArgs la{};
   la.k = k;
   la.k_sb = p->k_sb; la.k_st = p->k_st; la.k_sh = p->k_sh;
@@ -459,6 +461,8 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   la.seg = reinterpret_cast<float*>(ws + L.seg);
   la.snap = ws + L.snap;
   la.zsnap = reinterpret_cast<float*>(ws + L.zsnap);
+  la.pimg = ws + L.pimg;
+  la.zpre = reinterpret_cast<float*>(ws + L.zpre);
   still_state_layout_t SL{};
   unsigned char* stp = static_cast<unsigned char*>(state_out);
   if (state_out != nullptr) compute_state_layout(p, &SL);
@@ -468,16 +472,14 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
                          retained_budget(p)};
   if ((e = still::launch_keep_mask(km, B, stream)) != hipSuccess)
     return hip_fail("keep_mask", e);
-  if ((e = still::launch_la_sums(la, p->dtype, d, B, stream)) != hipSuccess)
-    return hip_fail("la_sums", e);
   prof_end(4, stream);
   prof_begin(5, stream);
-  if ((e = still::launch_la_prefix(la, d, B, stream)) != hipSuccess)
-    return hip_fail("la_prefix", e);
-  prof_end(5, stream);
-  prof_begin(6, stream);
   if ((e = still::launch_la_states(la, p->dtype, d, B, stream)) != hipSuccess)
     return hip_fail("la_states", e);
+  prof_end(5, stream);
+  prof_begin(6, stream);
+  if ((e = still::launch_la_prefix(la, p->dtype, d, B, stream)) != hipSuccess)
+    return hip_fail("la_prefix", e);
   prof_end(6, stream);
 
   prof_begin(7, stream);
@@ -490,6 +492,7 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   sx.wqt = ws + L.wqt; sx.bq = bq;
   sx.g = g; sx.g_sb = p->g_sb; sx.g_st = p->g_st; sx.g_sh = p->g_sh; sx.gate_act = p->gate_activation != 0;
   sx.snap = la.snap; sx.zsnap = la.zsnap; sx.nc = nc;
+  sx.pimg = la.pimg; sx.zpre = la.zpre; sx.seg_chunks = L.seg_chunks; sx.nseg = L.nseg;
   sx.n_la_out = p->emit_terms ? reinterpret_cast<float*>(ws + L.n_la) : nullptr;
   sx.d_la_out = p->emit_terms ? reinterpret_cast<float*>(ws + L.d_la) : nullptr;
   sx.out = out; sx.o_sb = p->o_sb; sx.o_st = p->o_st; sx.o_sh = p->o_sh;

@@ -193,6 +193,8 @@ __device__ __forceinline__ void head_major_block(int L, int Hq, int& hq, int& it
 // everything" (the instruction touches two address spaces), which drains the LDS read pipeline of the very
 // loops these copies are meant to run under.  The price: the compiler does not know about these copies, so the
 // caller must wait for them itself (s_waitcnt vmcnt(0), then a workgroup barrier) before the data is read.
+// The LDS base is uniform over the wave by contract; it is taken from the first lane because the constraint
+// needs a scalar register and a base selected at run time (one slot or another) may sit in a vector register.
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
@@ -202,14 +204,14 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 __device__ __forceinline__ void async_copy16(const void* gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
-               : "v"(gptr), "s"(lds_base)
+               : "v"(gptr), "s"(__builtin_amdgcn_readfirstlane(lds_base))
                : "memory", "m0");
 }
 
 __device__ __forceinline__ void async_copy4(const void* gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
                :
-               : "v"(gptr), "s"(lds_base)
+               : "v"(gptr), "s"(__builtin_amdgcn_readfirstlane(lds_base))
                : "memory", "m0");
 }
 

@@ -120,10 +120,12 @@ struct LaArgs {
   int N, Np, C, Hq, Hkv, nc, ncf;
   const int32_t* seq_len;   // nullable, device [B]
   int seg_chunks, nseg;
-  float* seg;          // [B, Hq, nseg, DP*(D+1)]: S (DP x D) then z (DP)
-  void* snap;          // [B, Hq, nc][D][DP] storage type: S^T through chunk c-2, for the rows of chunk c
-  float* zsnap;        // [B, Hq, nc][DP]: z through chunk c-2
-  float* s_final;      // nullable [B, Hq, DP*(D+1)]: fp32 state through chunk (last chunk - 2)
+  float* seg;          // [B, Hq, nseg][D*DP + DP]: every segment's total, S^T as [x][feature], then z
+  void* snap;          // [B, Hq, nc][D][DP] storage type: S^T summed over chunk c's own segment, through chunk c-2
+  float* zsnap;        // [B, Hq, nc][DP]: z likewise
+  void* pimg;          // [B, Hq, nseg][D][DP] storage type: S^T through the chunk before the segment (prefix)
+  float* zpre;         // [B, Hq, nseg][DP]: z likewise
+  float* s_final;      // nullable [B, Hq, DP*(D+1)] as S [feature][x] then z: fp32 state through chunk (last - 2)
 };
 
 // query rows per workgroup of the sparse-attention kernel (one wave per 32 rows)
@@ -143,6 +145,9 @@ struct SaArgs {
   int gate_act;        // 1: g is a pre-activation, the gate is its logistic function
   const void* snap;    // [B, Hq, nc][D][DP]: see LaArgs
   const float* zsnap;  // [B, Hq, nc][DP]
+  const void* pimg;    // [B, Hq, nseg][D][DP]
+  const float* zpre;   // [B, Hq, nseg][DP]
+  int seg_chunks, nseg;
   float* n_la_out;     // nullable [B, Hq, N, d]: the gated linear numerator of every row (inspection)
   float* d_la_out;     // nullable [B, Hq, N]
   void* out;
@@ -229,9 +234,8 @@ hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStre
 hipError_t launch_transpose_w(const TransposeWArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_gather(const GatherArgs& a, int dtype, int B, hipStream_t stream);
 hipError_t launch_keep_mask(const KeepMaskArgs& a, int B, hipStream_t stream);
-hipError_t launch_la_sums(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
-hipError_t launch_la_prefix(const LaArgs& a, int d, int B, hipStream_t stream);
 hipError_t launch_la_states(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
+hipError_t launch_la_prefix(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
 hipError_t launch_sa(const SaArgs& a, int dtype, int d, int B, hipStream_t stream);
 
 }  // namespace still

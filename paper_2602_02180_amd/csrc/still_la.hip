@@ -6,19 +6,18 @@
 // delayed by two chunks).  The other half of the branch, phi_q(q) s and phi_q(q) z for every row, is computed by
 // the sparse-attention kernel from the per-chunk states this file leaves in memory.
 //
-// What is produced: for every (batch, head) and every chunk c >= 0, the state through chunk c-2
-//   snap [chunk c] = S^T as [d][2 d_f] in the storage type (the operand layout of the product phi_q S),
-//   zsnap[chunk c] = z   as [2 d_f] float,
-// and, for the decode hand-over, the fp32 state through chunk (last chunk - 2).
-//
-// The scan over chunks is sequential per (batch, head); it is cut into segments so that one long sequence still
-// fills the chip, and run twice:
-//   pass 0 (MODE 0): one workgroup per (batch, head, segment) sums phi_k^T v and sum phi_k over its chunks;
-//   la_prefix      : exclusive prefix over the segments (elementwise, tiny);
-//   pass 1 (MODE 1): the same walk again, started from the prefix, writing the state after every chunk.
-// Segment s covers chunks [s*G-1, (s+1)*G-1), so its prefix is exactly the state through chunk s*G-2, the one
-// chunk s*G needs.  Walking twice costs a second NP-Map of the keys; in return every consumer reads ONE complete
-// state per chunk, and the fp32 running state is rounded to the storage type exactly once.
+// The scan over chunks is sequential per (batch, head); it is cut into segments of G chunks so that one long
+// sequence still fills the chip, and every segment is walked ONCE, starting from an empty state.  Segment s covers
+// chunks [s*G-1, (s+1)*G-1).  What is produced, for every (batch, head):
+//   snap [chunk c] = S^T_local as [d][2 d_f] in the storage type: the sum over the chunks s*G-1 .. c-2 of c's own
+//                    segment s = c / G (the operand layout of the product phi_q S),
+//   zsnap[chunk c] = z_local as [2 d_f] float,
+//   seg  [s]       = the segment's total, fp32, which la_prefix turns into the exclusive prefix over segments,
+//                    i.e. the state through chunk s*G-2: pimg[s] (storage type, same layout as snap) and zpre[s].
+// The state through chunk c-2, which the rows of chunk c need, is pimg[c / G] + snap[c]: the consumer (the
+// sparse-attention kernel) contracts phi_q with both.  The product is linear in the state, so nothing is lost, the
+// fp32 sums are rounded to the storage type once each, and the keys' NP-Map is computed once.  For the decode
+// hand-over the fp32 state through chunk (last chunk - 2) is written as local part here, prefix added by la_prefix.
 //
 // Workgroup plan (tokens are handled in rounds of RT = 128 or 64, a round never splits a 32-token tile):
 //   producer waves (RT/32): wave v owns tokens [32v, 32v+32) of the round and ALL features: f = W^T x on the
@@ -69,7 +68,7 @@ struct LaCfg {
 
 __device__ __forceinline__ int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
 
-template <typename T, int D, int C, int MODE>
+template <typename T, int D, int C>
 __device__ __forceinline__ void la_body(const LaArgs& a) {
   typedef Mma<T> M;
   typedef LaCfg<T, D, C> L;
@@ -89,7 +88,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
   const int N = seq_tokens(a.seq_len, b, a.N);   // this sequence's tokens (a right-padded batch has shorter ones)
   const int nc_b = (N + C - 1) / C, ncf_b = N / C;
   const int G = a.seg_chunks;
-  if (MODE == 1 && seg * G >= nc_b) return;      // the whole segment is padding (uniform over the workgroup)
+  if (seg * G >= nc_b) return;                   // the whole segment is padding (uniform over the workgroup)
 
   const int seg_tok0 = (seg * G - 1) * C;        // first token of the segment's first chunk (chunk -1 for segment 0)
   const int R = G * C / RT;                      // rounds; G * C is a multiple of RT by construction of G
@@ -265,17 +264,9 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
   const int col = 32 * wave + r;
   floatx16 S[PT];
   float z;                                       // feature row 64 wave + lane
-  if (MODE == 1 && seg > 0) {
 #pragma unroll
-    for (int ft = 0; ft < PT; ++ft)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) S[ft][i] = segp[(int64_t)(32 * ft + M::pos_of_reg(i, g)) * D + col];
-    z = segp[DP * D + 64 * wave + lane];
-  } else {
-#pragma unroll
-    for (int ft = 0; ft < PT; ++ft) S[ft] = zero16();
-    z = 0.f;
-  }
+  for (int ft = 0; ft < PT; ++ft) S[ft] = zero16();
+  z = 0.f;
 
   const T* __restrict__ vfr = static_cast<const T*>(a.vfr) + ((int64_t)b * a.Hkv + kvh) * (int64_t)D * a.Np;
   typedef typename M::frag VFrag[HS];            // V fragments of one part (B operand, k = tokens)
@@ -292,9 +283,9 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
     for (int s = 0; s < HS; ++s) vf[s] = M::load(vrow + s * 64 * M::KPL);
   };
 
-  // the state through chunk oc-2, for the rows of chunk oc
+  // the segment's running sums, for the rows of chunk oc (the chunks before the segment arrive as its prefix)
   auto emit = [&](int oc) __attribute__((always_inline)) {
-    if (MODE != 1 || oc >= nc_b) return;
+    if (oc >= nc_b) return;
     const int lane_now = fresh_lane_id(), rr = lane_now & 31, gg = lane_now >> 5;
     T* sp = static_cast<T*>(a.snap) + (unit * a.nc + oc) * (int64_t)(D * DP) + (int64_t)(32 * wave + rr) * DP;
 #pragma unroll
@@ -380,38 +371,57 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
       if (gp + 1 < NP) part_step(gp + 1, vb, va);
     }
   }
-  if (MODE == 0) {
+  // the segment's total, as [x][feature] like the snapshots (written once per workgroup)
+  {
+    const int lane_now = fresh_lane_id(), rr = lane_now & 31, gg = lane_now >> 5;
+    float* tp = segp + (int64_t)(32 * wave + rr) * DP;
 #pragma unroll
     for (int ft = 0; ft < PT; ++ft)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) segp[(int64_t)(32 * ft + M::pos_of_reg(i, g)) * D + col] = S[ft][i];
-    segp[DP * D + 64 * wave + lane] = z;
+      for (int i = 0; i < 16; ++i) tp[32 * ft + M::pos_of_reg(i, gg)] = S[ft][i];
+    segp[D * DP + 64 * wave + lane_now] = z;
   }
 }
 
 // (the body lives in a __device__ function behind a thin __global__ wrapper)
-template <typename T, int D, int C, int MODE>
+template <typename T, int D, int C>
 __global__ __launch_bounds__((LaCfg<T, D, C>::NCW + LaCfg<T, D, C>::NPW) * 64) void la_kernel(LaArgs a) {
-  la_body<T, D, C, MODE>(a);
+  la_body<T, D, C>(a);
 }
 
-// exclusive prefix over segments, in place: seg[s] <- sum_{s' < s} seg[s'] (slot nseg-1 is only written)
-__global__ __launch_bounds__(256) void la_prefix_kernel(float* seg, int nseg, int64_t elems) {
+// Exclusive prefix over the segments of one (batch, head), elementwise over the state as [x][feature] (+ z):
+// pimg[s] / zpre[s] = sum of the totals of the segments before s, i.e. the state through chunk s*G-2; the fp32
+// state of the decode hand-over (written by the scan as a local part, laid out [feature][x]) receives the prefix
+// of the segment of the sequence's last chunk.
+template <typename T>
+__global__ __launch_bounds__(256) void la_prefix_kernel(LaArgs a, int D) {
+  const int DP = 2 * D;
+  const int64_t elems = (int64_t)DP * (D + 1);
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= elems) return;
-  float* p = seg + (int64_t)blockIdx.y * nseg * elems + idx;
+  const int64_t unit = blockIdx.y;
+  const int b = (int)(unit / a.Hq);
+  const int N = seq_tokens(a.seq_len, b, a.N);
+  const int seg_last = ((N + a.C - 1) / a.C - 1) / a.seg_chunks;     // segment of the sequence's last chunk
+  const float* tot = a.seg + unit * a.nseg * elems + idx;
+  const bool is_z = idx >= (int64_t)D * DP;
   float run = 0.f;
-  for (int s = 0; s < nseg; ++s) {
-    const float cur = (s + 1 < nseg) ? p[(int64_t)s * elems] : 0.f;
-    p[(int64_t)s * elems] = run;
-    run += cur;
+  for (int s = 0; s < a.nseg; ++s) {
+    if (is_z) a.zpre[(unit * a.nseg + s) * DP + (idx - (int64_t)D * DP)] = run;
+    else static_cast<T*>(a.pimg)[(unit * a.nseg + s) * (int64_t)(D * DP) + idx] = from_f32<T>(run);
+    if (s == seg_last && a.s_final != nullptr) {
+      float* sf = a.s_final + unit * elems;
+      if (is_z) sf[idx] += run;                                       // z sits behind S in both layouts
+      else sf[(idx % DP) * D + idx / DP] += run;                      // [x][feature] -> [feature][x]
+    }
+    if (s <= seg_last && s + 1 < a.nseg) run += tot[(int64_t)s * elems];   // later segments were never walked
   }
 }
 
-template <typename T, int D, int C, int MODE>
+template <typename T, int D, int C>
 static hipError_t launch_la_t(const LaArgs& a, int B, int nblocks, hipStream_t stream) {
   typedef LaCfg<T, D, C> L;
-  auto kern = la_kernel<T, D, C, MODE>;
+  auto kern = la_kernel<T, D, C>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::smem_bytes);
   if (e != hipSuccess) return e;
@@ -420,35 +430,27 @@ static hipError_t launch_la_t(const LaArgs& a, int B, int nblocks, hipStream_t s
   return hipGetLastError();
 }
 
-template <int MODE>
-static hipError_t launch_la_mode(const LaArgs& a, int dtype, int d, int B, int nblocks, hipStream_t stream) {
+hipError_t launch_la_states(const LaArgs& a, int dtype, int d, int B, hipStream_t stream) {
+  const int nblocks = a.nseg;
   if (nblocks <= 0) return hipSuccess;
   if (dtype == 1) {
-    if (d == 64) return a.C == 64 ? launch_la_t<bf16, 64, 64, MODE>(a, B, nblocks, stream)
-                                  : launch_la_t<bf16, 64, 128, MODE>(a, B, nblocks, stream);
-    return a.C == 64 ? launch_la_t<bf16, 128, 64, MODE>(a, B, nblocks, stream)
-                     : launch_la_t<bf16, 128, 128, MODE>(a, B, nblocks, stream);
+    if (d == 64) return a.C == 64 ? launch_la_t<bf16, 64, 64>(a, B, nblocks, stream)
+                                  : launch_la_t<bf16, 64, 128>(a, B, nblocks, stream);
+    return a.C == 64 ? launch_la_t<bf16, 128, 64>(a, B, nblocks, stream)
+                     : launch_la_t<bf16, 128, 128>(a, B, nblocks, stream);
   }
-  if (d == 64) return a.C == 64 ? launch_la_t<float, 64, 64, MODE>(a, B, nblocks, stream)
-                                : launch_la_t<float, 64, 128, MODE>(a, B, nblocks, stream);
-  return a.C == 64 ? launch_la_t<float, 128, 64, MODE>(a, B, nblocks, stream)
-                   : launch_la_t<float, 128, 128, MODE>(a, B, nblocks, stream);
+  if (d == 64) return a.C == 64 ? launch_la_t<float, 64, 64>(a, B, nblocks, stream)
+                                : launch_la_t<float, 64, 128>(a, B, nblocks, stream);
+  return a.C == 64 ? launch_la_t<float, 128, 64>(a, B, nblocks, stream)
+                   : launch_la_t<float, 128, 128>(a, B, nblocks, stream);
 }
 
-hipError_t launch_la_sums(const LaArgs& a, int dtype, int d, int B, hipStream_t stream) {
-  return launch_la_mode<0>(a, dtype, d, B, a.nseg - 1, stream);   // the last segment's sum is never needed
-}
-
-hipError_t launch_la_prefix(const LaArgs& a, int d, int B, hipStream_t stream) {
-  if (a.nseg <= 1) return hipSuccess;
+hipError_t launch_la_prefix(const LaArgs& a, int dtype, int d, int B, hipStream_t stream) {
   const int64_t elems = (int64_t)2 * d * (d + 1);
   dim3 grid((unsigned)((elems + 255) / 256), B * a.Hq), block(256);
-  hipLaunchKernelGGL(la_prefix_kernel, grid, block, 0, stream, a.seg, a.nseg, elems);
+  if (dtype == 1) hipLaunchKernelGGL(la_prefix_kernel<bf16>, grid, block, 0, stream, a, d);
+  else hipLaunchKernelGGL(la_prefix_kernel<float>, grid, block, 0, stream, a, d);
   return hipGetLastError();
-}
-
-hipError_t launch_la_states(const LaArgs& a, int dtype, int d, int B, hipStream_t stream) {
-  return launch_la_mode<1>(a, dtype, d, B, a.nseg, stream);
 }
 
 }  // namespace still

@@ -341,8 +341,9 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
         for (int j = 0; j < Cf::K_INSTR; ++j)
           async_copy16(base + k_off_ret[j], lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
       };
-      auto request_s = [&](int cc, int jt, T* slot) {   // S^T[:, 64 jt .. +64) of chunk cc: like a V^T tile, row stride DP
-        const T* base = static_cast<const T*>(a.snap) + (unit * a.nc + cc) * (int64_t)(D * DP) + 64 * jt;
+      // columns [64 jt, +64) of a state image [D][DP]: like a V^T tile, row stride DP
+      auto request_t = [&](const T* img, int jt, T* slot) {
+        const T* base = img + 64 * jt;
         T* dst = slot + wave_s * 64 * Cf::EPV;
         const int lane_now = fresh_lane_id();
 #pragma unroll
@@ -352,16 +353,43 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
           async_copy16(base + (lrow * DP + col), lds_address(dst + Cf::NW * j * 64 * Cf::EPV));
         }
       };
-      auto slot_of = [&](int jt) -> T* {              // state tiles 0, 1 use the V slots, 2, 3 the K slots
-        return jt < 2 ? Vl + jt * Cf::V_ELEMS : Kl + (jt - 2) * Cf::K_ELEMS;
+      // The state through chunk cc-2 is the sum of two images: the running sums of cc's own segment (operand 0;
+      // empty for the first chunk of a segment) and the prefix of that segment (operand 1; empty in segment 0).
+      // The product is linear in the state: phi_q^T meets the tiles of both.  Work is dealt in PAIRS of NWT tiles
+      // (one half of the features of one operand of one chunk), positive halves first; pair p uses the V slots
+      // (p even) or the K slots (p odd), and pair p+1 travels while pair p is contracted.
+      const int Gs = a.seg_chunks;
+      const T* snap_u = static_cast<const T*>(a.snap) + unit * a.nc * (int64_t)(D * DP);
+      const T* pimg_u = static_cast<const T*>(a.pimg) + unit * a.nseg * (int64_t)(D * DP);
+      uint32_t codes = 0;      // 4 bits per pair: (chunk - la_lo) << 2 | half << 1 | operand
+      int np = 0;
+      for (int cc = la_lo; cc <= la_hi; ++cc)
+        for (int half = 0; half < 2; ++half)
+          for (int op = 0; op < 2; ++op)
+            if (op == 0 ? (cc % Gs) != 0 : (cc / Gs) >= 1) {
+              codes |= (uint32_t)(((cc - la_lo) << 2) | (half << 1) | op) << (4 * np);
+              ++np;
+            }
+      codes = __builtin_amdgcn_readfirstlane(codes);   // uniform by construction
+      np = __builtin_amdgcn_readfirstlane(np);
+      constexpr int MAXP = 8;                          // two chunks x two halves x two operands
+      static_assert(Cf::K_ELEMS == Cf::V_ELEMS, "the four slots are equal and contiguous: K, K, V, V");
+      auto slot_of = [&](int p, int w) -> T* { return Kl + (w + 2 * (1 - (p & 1))) * Cf::K_ELEMS; };
+      auto request_pair = [&](int p) __attribute__((always_inline)) {
+        const int code = (codes >> (4 * p)) & 7;
+        const int cc = la_lo + (code >> 2), half = (code >> 1) & 1;
+        const T* img = (code & 1) ? pimg_u + (int64_t)(cc / Gs) * (D * DP) : snap_u + (int64_t)cc * (D * DP);
+#pragma unroll
+        for (int w = 0; w < NWT; ++w) request_t(img, half * NWT + w, slot_of(p, w));
       };
-      // stage 1: W_q^T, z of the chunks, the first two state tiles of the first chunk
+      // stage 0: W_q^T into the K slots, the first pair into the V slots, z of the chunks
 #pragma unroll
       for (int wt = 0; wt < NWT; ++wt) request_w(wt, Kl + wt * Cf::K_ELEMS);
-      request_s(la_lo, 0, slot_of(0));
-      request_s(la_lo, 1, slot_of(1));
-      for (int i = tid; i < (la_hi - la_lo + 1) * DP; i += Cf::NW * 64)
-        zl[i] = a.zsnap[(unit * a.nc + la_lo) * DP + i];
+      request_pair(0);
+      for (int i = tid; i < (la_hi - la_lo + 1) * DP; i += Cf::NW * 64) {
+        const int cc = la_lo + i / DP, fz = i % DP;
+        zl[i] = a.zsnap[(unit * a.nc + cc) * DP + fz] + a.zpre[(unit * a.nseg + cc / Gs) * DP + fz];
+      }
 #pragma unroll
       for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(qf[s]));
       wait_async_copies();
@@ -377,11 +405,8 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
         for (int wt = 0; wt < NWT; ++wt) sa_qk<T, D>(Kl + wt * Cf::K_ELEMS, qf, f[wt], r, g);
       }
       lds_barrier();   // every wave has read W_q^T: the K slots are free
-      // the other two state tiles of the first chunk travel to the K slots under the feature map's vector work
-      if (NST > 2) {
-        request_s(la_lo, 2, slot_of(2));
-        request_s(la_lo, 3, slot_of(3));
-      }
+      // the second pair travels to the K slots under the feature map's vector work
+      if (np > 1) request_pair(1);
       if (mine) {
         if (a.bq != nullptr) {
           const T* bq = static_cast<const T*>(a.bq) + (int64_t)hq * DF;
@@ -494,44 +519,35 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
               if (idx + PDEPTH < NPV) af[idx % PDEPTH] = a_at(idx + PDEPTH);
               __builtin_amdgcn_sched_barrier(0);
             }
-            if (jt == NWT - 1) {       // the positive half is complete: (ip / in) A now, + B and * in later = ip A + in B
-              const float k1 = ip * sn_keep;
+          }
+        });
+      };
+      // The steps are laid out at compile time in the order of the codes (chunk, half, operand), so that the
+      // fragments a product reads are known statically; whether a step exists, and which slots its pair sits in
+      // (pairs alternate between the V and the K slots), is decided at run time, uniformly.
+      int pi = 0;                                        // pairs done so far
+      static_for<MAXP>([&](auto SS) __attribute__((always_inline)) {
+        constexpr int st = decltype(SS)::value;
+        constexpr int ci = st >> 2, half = (st >> 1) & 1, op = st & 1;
+        const int cc = la_lo + ci;
+        if (cc <= la_hi && (op == 0 ? (cc % Gs) != 0 : (cc / Gs) >= 1)) {
+          if (pi >= 1 && pi + 1 < np) request_pair(pi + 1);   // (pair 1 was requested above)
+          if (mine && cw == cc) {
+            if (half == 1 && op == (cc % Gs != 0 ? 0 : 1)) {  // first negative pair: the positive halves are complete;
+              const float k1 = ip * sn_keep;                  // (ip / in) A now, + B and * in later = ip A + in B
 #pragma unroll
               for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[dt][i] *= k1;
             }
-          }
-        });
-      };
-      for (int cc = la_lo; cc <= la_hi; ++cc) {
-        const bool now = mine && cw == cc;
-        if (cc > la_lo) {               // second chunk of the workgroup (all four slots are free)
-          request_s(cc, 0, slot_of(0));
-          request_s(cc, 1, slot_of(1));
-          if (NST > 2) {
-            request_s(cc, 2, slot_of(2));
-            request_s(cc, 3, slot_of(3));
+#pragma unroll
+            for (int w = 0; w < NWT; ++w) la_pv(half * NWT + w, slot_of(pi, w));
           }
           wait_async_copies();
-          lds_barrier();
+          lds_barrier();                  // pair pi+1 has arrived everywhere, the slots of pair pi may be refilled
+          ++pi;
         }
-        if (now) {
-          la_pv(0, slot_of(0));
-          la_pv(1, slot_of(1));
-        }
-        if (NST > 2) {
-          if (cc == la_lo) {            // the first chunk's tiles 2, 3 were requested above, under the vector work
-            wait_async_copies();
-            lds_barrier();
-          }
-          if (now) {
-            la_pv(2, slot_of(2));
-            la_pv(3, slot_of(3));
-          }
-        }
-        lds_barrier();                  // the slots may be refilled
-      }
+      });
       if (mine) {
         la_done = true;
         const int tq = t < N ? t : N - 1;

@@ -37,13 +37,14 @@ def test_workspace_layout_is_consistent():
     p = params()
     L = S.still_fwd_workspace_layout(p)
     assert S.still_fwd_workspace_bytes(p) == L.total
-    offs = [L.score, L.sel, L.vt, L.kret, L.vrett, L.wqt, L.wkf, L.seg, L.snap, L.zsnap, L.kmask, L.n_la, L.d_la, L.vfr, L.total]
+    offs = [L.score, L.sel, L.vt, L.kret, L.vrett, L.wqt, L.wkf, L.seg, L.snap, L.zsnap, L.pimg, L.zpre, L.kmask, L.n_la, L.d_la, L.vfr, L.total]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert L.n_pad % 128 == 0 and L.n_pad >= 1024
     assert L.cap % 64 == 0 and L.cap >= (1024 // 64) * 16
     assert L.nseg * L.seg_chunks >= 16
     assert L.snap - L.seg >= 1 * 4 * L.nseg * (2 * 64 * 65) * 4
     assert L.zsnap - L.snap >= 1 * 4 * 16 * 64 * 128 * 2           # one bf16 state per (head, chunk)
+    assert L.zpre - L.pimg >= 1 * 4 * L.nseg * 64 * 128 * 2        # and one per (head, segment)
     assert L.d_la - L.n_la <= 256                                   # the inspection regions are empty by default
     Lt = S.still_fwd_workspace_layout(params(emit_terms=1))
     assert Lt.d_la - Lt.n_la >= 1 * 4 * 1024 * 64 * 4 and Lt.total > L.total
