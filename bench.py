@@ -31,7 +31,7 @@ PEAK_HBM = 8.0e12
 # HBM bytes per launch of the dominant prefill kernel (sparse_attn_merge), measured with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE and scaled by the plain-copy calibration (two counter runs plus two --calibrate-copy runs; FETCH_SIZE
 # counts 2 KiB and WRITE_SIZE 1 KiB per unit on this machine).  Other configs: null.
-MEASURED_TRAFFIC = {"c4": 1.882e9}
+MEASURED_TRAFFIC = {"c4": 1.866e9}
 
 
 def sparse_branch_flops(w: synth.Workload, N: int) -> float:
