@@ -139,7 +139,7 @@ __global__ __launch_bounds__(128) void decode_score_kernel(DecArgs a) {
 
 // ---------------------------------------------------------------- routing of chunk cr = t/C - 2
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr_all) {
+__global__ __launch_bounds__(256, 2) void decode_route_kernel(DecArgs a, int cr_all) {
   constexpr int DF = D, DP = 2 * D;
   __shared__ float s_sc[128];
   __shared__ unsigned char s_flag[128];
@@ -203,152 +203,194 @@ __global__ __launch_bounds__(256) void decode_route_kernel(DecArgs a, int cr_all
       vret[(int64_t)row * D + x] = vring[(int64_t)slot * D + x];
     }
   }
-  // the others -> (S, z): thread f owns row f of S; thread tid also owns the slice part = tid / d_f of column
-  // tid % d_f of Wk (a whole column per thread would cost 128 more registers and halve the occupancy).  The tokens
-  // are taken TB at a time (in order): one set of barriers per batch instead of one per token.  Per batch:
-  //   (A) every thread projects the TB tokens onto its slice of its column; the slices are added in (B),
-  //   (B) wave w turns token w's d_f projections into its 2 d_f features (all of a token's features sit in one
-  //       wave, two per lane, so the statistics need wave reductions only),
-  //   (C) every thread adds the TB rank-1 terms to its row of S, token by token.
-  // The key/value rows of the next batch are loaded into registers before (A), so their latency hides behind
-  // the arithmetic of the current batch.
-  constexpr int TB = 4;
-  constexpr int XP = 256 / DF, XS = D / XP;          // slices per column, rows per slice
-  constexpr int NLD = TB * D / 256;                  // row elements per thread and batch
-  __shared__ __attribute__((aligned(16))) float xs[D][TB], vs[D][TB], fpart[XP][TB][DF], phi[DP][TB];
-  __shared__ int s_rest[128];
-  __shared__ int s_nrest;
-  if (tid < C && !chosen) {
-    int before = 0;
-    for (int jx = 0; jx < tid; ++jx) before += s_flag[jx];
-    s_rest[tid - before] = tid;
-  }
-  if (tid == 0) {
-    int n = 0;
-    for (int jx = 0; jx < C; ++jx) n += s_flag[jx] ? 0 : 1;
-    s_nrest = n;
-  }
-  const int fi = tid % DF, part = tid / DF;
-  float wcol[XS];
-  {
-    const T* wk = static_cast<const T*>(a.wk) + (int64_t)hq * D * DF + (int64_t)(part * XS) * DF + fi;
-#pragma unroll
-    for (int x = 0; x < XS; ++x) wcol[x] = to_f32(wk[(int64_t)x * DF]);
-  }
+  // The others -> (S, z), on the matrix core, in parts of PT tokens (PT = 128 two-byte or 64 four-byte tokens, at
+  // most the chunk).  LDS holds, per part, the feature image phi^T [2 d_f][PT] and V^T [d][PT] in the storage type
+  // (rows padded by 16 bytes), both read as 16-byte operand fragments; at d = 128 the image is built and
+  // contracted in two pieces (positive half, negative half) so that two workgroups fit a CU.  W_k^T [d_f][d] is
+  // staged into the same memory first (the image is written only after every wave has finished projecting).
+  //   projection  f^T = W_k^T x^T: wave w owns tokens [32w, 32w+32) of the chunk, one lane per token and all
+  //               features, so the token's statistics are per-lane reductions plus one exchange of lane groups;
+  //   features    the two exponential halves, normalised and rounded to the storage type (zero for the tokens the
+  //               softmax branch keeps), written to the image;
+  //   update      S += phi^T V: wave w owns rows [32w, 32w+32) of every piece of S for every column, loaded into
+  //               MFMA accumulators at the start of the kernel and stored at the end; z is the image's row sum.
+  typedef Mma<T> M;
+  constexpr int EPV = 16 / (int)sizeof(T);
+  constexpr int PTMAX = sizeof(T) == 2 ? 128 : 64;
+  constexpr int PADE = EPV;                                   // row padding, elements (16 bytes)
+  constexpr int WST = D + PADE;                               // W^T row stride
+  constexpr int FT = DF / 32, KS = D / M::KK, XT = D / 32;
+  constexpr int NH = D == 128 ? 2 : 1;                        // the image is built and contracted in NH pieces of HR rows
+  constexpr int HR = DP / NH;                                 //   (d = 128: the positive half, then the negative half)
+  static_assert(HR == 128, "a piece is one 32-row tile per wave");
+  extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
+  const int PT = C < PTMAX ? C : PTMAX, nparts = C / PT;
+  const int IST = PT + PADE;                                  // image and V^T row stride
+  T* wt = reinterpret_cast<T*>(dsm);
+  T* img = reinterpret_cast<T*>(dsm);
+  T* vtl = img + HR * (PTMAX + PADE);
   const int lane = tid & 63, wave = tid >> 6;
-  float bias[DF / 64];
-#pragma unroll
-  for (int h = 0; h < DF / 64; ++h)
-    bias[h] = a.bk != nullptr ? to_f32(static_cast<const T*>(a.bk)[(int64_t)hq * DF + lane + 64 * h]) : 0.f;
+  const int r = lane & 31, g = lane >> 5;
   float* Sg = a.S + unit * (int64_t)(DP * (D + 1));
-  float srow[D];
-  float zf = 0.f;
-  if (tid < DP) {
+
+  // W_k [d][d_f] row-major -> W_k^T in LDS
+  {
+    const T* wk = static_cast<const T*>(a.wk) + (int64_t)hq * D * DF;
+    for (int idx = tid; idx < D * DF / EPV; idx += 256) {
+      const int kk = idx % D, f0 = (idx / D) * EPV;             // consecutive lanes: consecutive LDS elements
+      const Vec16 w16 = *reinterpret_cast<const Vec16*>(wk + (int64_t)kk * DF + f0);
+      const T* we = reinterpret_cast<const T*>(&w16);
 #pragma unroll
-    for (int x = 0; x < D; ++x) srow[x] = Sg[(int64_t)tid * D + x];
-    zf = Sg[DP * D + tid];
+      for (int e = 0; e < EPV; ++e) wt[(f0 + e) * WST + kk] = we[e];
+    }
   }
   __syncthreads();
-  const int n_rest = s_nrest;
-  float xn[NLD], vn[NLD];                            // this thread's elements of the next batch's rows
-  auto fetch = [&](int i0) __attribute__((always_inline)) {
+
+  // projection and statistics of this wave's tokens
+  const int tok = 32 * wave + r;                               // token of the chunk owned by this lane
+  const bool has_tok = 32 * wave < C;                          // (wave-uniform)
+  floatx16 f[FT];
+  float a1 = 0.f, bp = 0.f, bn = 0.f, isp = 0.f, isn = 0.f;
+  typename M::frag xb[KS];
+  if (has_tok) {
+    const int slot = (cr * C + tok) % R;
+    const T* xp = kring + (int64_t)slot * D + g * M::KPL;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int idx = tid + 256 * i, tb = idx / D, x = idx % D;
-      xn[i] = 0.f;
-      vn[i] = 0.f;
-      if (i0 + tb < n_rest) {
-        const int slot = (cr * C + s_rest[i0 + tb]) % R;
-        xn[i] = to_f32(kring[(int64_t)slot * D + x]);
-        vn[i] = to_f32(vring[(int64_t)slot * D + x]);
-      }
-    }
+    for (int ks = 0; ks < KS; ++ks) xb[ks] = M::load(xp + ks * M::KK);
+  }
+  // S rows of this wave -> accumulators.  The first piece is issued after the token rows and before the products
+  // (loads complete in order, so the next wait that covers them is the one for the V rows, a projection later);
+  // the second piece follows when the projection's registers are free.
+  floatx16 acc[NH][XT];                                        // piece h: rows h HR + 32 wave + (0..31) of S
+  auto load_piece = [&](int h) __attribute__((always_inline)) {
+#pragma unroll
+    for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        acc[h][xt][i] = Sg[(int64_t)(h * HR + 32 * wave + c_row(i, g)) * D + 32 * xt + r];
   };
-  fetch(0);
-  for (int i0 = 0; i0 < n_rest; i0 += TB) {
-    const int nb = n_rest - i0 < TB ? n_rest - i0 : TB;
-    __syncthreads();                             // the previous batch's operands have been consumed
+  load_piece(0);
+  float zf[NH];
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int idx = tid + 256 * i, tb = idx / D, x = idx % D;
-      xs[x][tb] = xn[i];
-      vs[x][tb] = vn[i];
+  for (int h = 0; h < NH; ++h) zf[h] = tid < HR ? Sg[DP * D + h * HR + tid] : 0.f;
+
+  if (has_tok) {
+#pragma unroll
+    for (int ft = 0; ft < FT; ++ft) {
+      f[ft] = zero16();
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        f[ft] = M::mma(M::load(wt + (32 * ft + r) * WST + ks * M::KK + g * M::KPL), xb[ks], f[ft]);
     }
-    __syncthreads();
-    if (i0 + TB < n_rest) fetch(i0 + TB);
-    // (A)
-    {
-      float f[TB];
+    if (a.bk != nullptr) {
+      const T* bk = static_cast<const T*>(a.bk) + (int64_t)hq * DF;
 #pragma unroll
-      for (int tb = 0; tb < TB; ++tb) f[tb] = 0.f;
+      for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-      for (int x = 0; x < XS; ++x) {
-        const floatx4 x4 = *reinterpret_cast<const floatx4*>(&xs[part * XS + x][0]);
-#pragma unroll
-        for (int tb = 0; tb < TB; ++tb) f[tb] = fmaf(x4[tb], wcol[x], f[tb]);
-      }
-#pragma unroll
-      for (int tb = 0; tb < TB; ++tb) fpart[part][tb][fi] = f[tb];
+        for (int i = 0; i < 16; ++i) f[ft][i] += to_f32(bk[32 * ft + c_row(i, g)]);
     }
-    __syncthreads();
-    // (B) blockDim = 256 = TB waves
-    {
-      const int tb = wave;
-      float fv[DF / 64], nx2 = 0.f, nf2 = 0.f, fmx = -INFINITY, fmn = INFINITY;
+    float x4[4] = {0.f, 0.f, 0.f, 0.f}, q4[4] = {0.f, 0.f, 0.f, 0.f}, mx = -INFINITY, mn = INFINITY;
 #pragma unroll
-      for (int h = 0; h < DF / 64; ++h) {
-        float s = 0.f;
+    for (int ks = 0; ks < KS; ++ks) x4[ks & 3] = M::dot_into(xb[ks], xb[ks], x4[ks & 3]);
 #pragma unroll
-        for (int pp = 0; pp < XP; ++pp) s += fpart[pp][tb][lane + 64 * h];   // slices in ascending order
-        fv[h] = s + bias[h];
-        nf2 = fmaf(fv[h], fv[h], nf2);
-        fmx = fmaxf(fmx, fv[h]);
-        fmn = fminf(fmn, fv[h]);
+    for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        q4[i & 3] = fmaf(f[ft][i], f[ft][i], q4[i & 3]);
+        mx = fmaxf(mx, f[ft][i]);
+        mn = fminf(mn, f[ft][i]);
       }
+    const float nx2 = sum32((x4[0] + x4[1]) + (x4[2] + x4[3]));
+    const float nf2 = sum32((q4[0] + q4[1]) + (q4[2] + q4[3]));
+    mx = max32(mx);
+    mn = min32(mn);
+    const float ratio = nf2 > 0.f ? sqrtf(nx2 / nf2) : 0.f;
+    a1 = ratio * kLog2e;
+    bp = -mx * a1;
+    bn = mn * a1;
+    float sp = 0.f, sn = 0.f;
 #pragma unroll
-      for (int h = 0; h < D / 64; ++h) nx2 = fmaf(xs[lane + 64 * h][tb], xs[lane + 64 * h][tb], nx2);
-      nx2 = wave_sum(nx2);
-      nf2 = wave_sum(nf2);
-      fmx = wave_max(fmx);
-      fmn = -wave_max(-fmn);
-      const float ratio = nf2 > 0.f ? sqrtf(nx2 / nf2) : 0.f;
-      const float a1 = ratio * kLog2e;
-      float ep[DF / 64], en[DF / 64], sp = 0.f, sn = 0.f;
+    for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-      for (int h = 0; h < DF / 64; ++h) {
-        ep[h] = fast_exp2(fmaf(fv[h], a1, -fmx * a1));
-        en[h] = fast_exp2(fmaf(fv[h], -a1, fmn * a1));
-        sp += ep[h];
-        sn += en[h];
+      for (int i = 0; i < 16; ++i) {
+        sp += fast_exp2(fmaf(f[ft][i], a1, bp));
+        sn += fast_exp2(fmaf(f[ft][i], -a1, bn));
       }
-      sp = wave_sum(sp);
-      sn = wave_sum(sn);
-      const bool live = tb < nb;
+    isp = 1.0f / sum32(sp);
+    isn = 1.0f / sum32(sn);
+    if (s_flag[tok]) isp = 0.f, isn = 0.f;                     // kept by the softmax branch: contributes nothing
+  }
+
+  if (NH == 2) load_piece(NH - 1);   // (after the projection's registers are free; arrives under the first piece)
+  for (int part = 0; part < nparts; ++part) {
 #pragma unroll
-      for (int h = 0; h < DF / 64; ++h) {
-        phi[lane + 64 * h][tb] = live ? round_to<T>(ep[h] / sp) : 0.f;
-        phi[DF + lane + 64 * h][tb] = live ? round_to<T>(en[h] / sn) : 0.f;
+    for (int h = 0; h < NH; ++h) {
+      __syncthreads();                                         // W^T (or the previous piece) has been consumed
+      // features of the part's tokens -> image piece h
+      if (has_tok && tok / PT == part) {
+        const int tl = tok - part * PT;
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int fr = 32 * ft + c_row(i, g);
+            if (NH == 1 || h == 0) img[fr * IST + tl] = from_f32<T>(fast_exp2(fmaf(f[ft][i], a1, bp)) * isp);
+            if (NH == 1 || h == 1)
+              img[((NH == 1 ? DF : 0) + fr) * IST + tl] = from_f32<T>(fast_exp2(fmaf(f[ft][i], -a1, bn)) * isn);
+          }
       }
-    }
-    __syncthreads();
-    // (C)
-    if (tid < DP) {
-      const floatx4 pf = *reinterpret_cast<const floatx4*>(&phi[tid][0]);
+      // V rows of the part -> V^T (once per part)
+      if (h == 0) {
+        for (int idx = tid; idx < PT * D / EPV; idx += 256) {
+          const int tl = idx % PT, x0 = (idx / PT) * EPV;
+          const int slot = (cr * C + part * PT + tl) % R;
+          const Vec16 v16 = *reinterpret_cast<const Vec16*>(vring + (int64_t)slot * D + x0);
+          const T* ve = reinterpret_cast<const T*>(&v16);
 #pragma unroll
-      for (int tb = 0; tb < TB; ++tb) zf += pf[tb];
+          for (int e = 0; e < EPV; ++e) vtl[(x0 + e) * IST + tl] = ve[e];
+        }
+      }
+      __syncthreads();
+      // update of piece h
+      for (int ks = 0; ks < PT / M::KK; ++ks) {
+        typename M::frag bf[XT];
+        const typename M::frag af = M::load(img + (32 * wave + r) * IST + ks * M::KK + g * M::KPL);
 #pragma unroll
-      for (int x = 0; x < D; ++x) {
-        const floatx4 v4 = *reinterpret_cast<const floatx4*>(&vs[x][0]);
+        for (int xt = 0; xt < XT; ++xt) bf[xt] = M::load(vtl + (32 * xt + r) * IST + ks * M::KK + g * M::KPL);
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb) srow[x] = fmaf(pf[tb], v4[tb], srow[x]);
+        for (int xt = 0; xt < XT; ++xt) acc[h][xt] = M::mma(af, bf[xt], acc[h][xt]);
+      }
+      if (tid < HR) {
+        float zs = 0.f;
+        for (int tl = 0; tl < PT; tl += EPV) {
+          const Vec16 p16 = *reinterpret_cast<const Vec16*>(img + tid * IST + tl);
+          const T* pe = reinterpret_cast<const T*>(&p16);
+#pragma unroll
+          for (int e = 0; e < EPV; ++e) zs += to_f32(pe[e]);
+        }
+        zf[h] += zs;
       }
     }
   }
-  if (tid < DP) {
 #pragma unroll
-    for (int x = 0; x < D; ++x) Sg[(int64_t)tid * D + x] = srow[x];
-    Sg[DP * D + tid] = zf;
-  }
+  for (int h = 0; h < NH; ++h)
+#pragma unroll
+    for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        Sg[(int64_t)(h * HR + 32 * wave + c_row(i, g)) * D + 32 * xt + r] = acc[h][xt][i];
+#pragma unroll
+  for (int h = 0; h < NH; ++h)
+    if (tid < HR) Sg[DP * D + h * HR + tid] = zf[h];
+}
+
+// LDS of the routing kernel: one image piece (128 rows) + V^T of one part, or W_k^T (whichever is larger)
+template <typename T, int D>
+constexpr size_t decode_route_smem() {
+  constexpr int EPV = 16 / (int)sizeof(T), PTMAX = sizeof(T) == 2 ? 128 : 64;
+  constexpr size_t part = (size_t)(128 + D) * (PTMAX + EPV) * sizeof(T);
+  constexpr size_t w = (size_t)D * (D + EPV) * sizeof(T);
+  return part > w ? part : w;
 }
 
 // ---------------------------------------------------------------- attention over the salient cache (split)
@@ -735,7 +777,15 @@ hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hi
   STILL_DISPATCH(dtype, d, CALL_SCORE)
   if (route) {
     const int cr = a.t / a.C - 2;
-#define CALL_ROUTE(TT, DD) hipLaunchKernelGGL((decode_route_kernel<TT, DD>), dim3(a.Hq, a.B), dim3(256), 0, stream, a, cr);
+#define CALL_ROUTE(TT, DD)                                                                              \
+  {                                                                                                     \
+    auto kern = decode_route_kernel<TT, DD>;                                                            \
+    const size_t smem = decode_route_smem<TT, DD>();                                                    \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                             \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);          \
+    if (e != hipSuccess) return e;                                                                      \
+    hipLaunchKernelGGL(kern, dim3(a.Hq, a.B), dim3(256), smem, stream, a, cr);                          \
+  }
     STILL_DISPATCH(dtype, d, CALL_ROUTE)
   }
 #define CALL_ATT(TT, DD) hipLaunchKernelGGL((decode_attend_kernel<TT, DD>), dim3(a.nsplit, a.Hq, a.B), dim3(256), 0, stream, a);
