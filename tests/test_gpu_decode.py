@@ -23,6 +23,8 @@ def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False, gate_ac
     dev = "cuda"
     full = {k: synth.to_torch(inp[k], w.dtype, dev) for k in ("q", "k", "v", "Wq", "Wk")}
     g_full = synth.to_torch(inp["g"], w.dtype, dev) if with_gate else None
+    bq = synth.to_torch(inp["bq"], w.dtype, dev) if inp.get("bq") is not None else None
+    bk = synth.to_torch(inp["bk"], w.dtype, dev) if inp.get("bk") is not None else None
     B = w.B
     out = torch.full((B, n_total, w.Hq, w.d), float("nan"), dtype=full["q"].dtype, device=dev)
     base = dict(B=B, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype=w.dtype,
@@ -37,7 +39,7 @@ def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False, gate_ac
         o0 = torch.empty_like(q0)
         p0 = S.make_params(N=n_prefill, q=q0, k=k0, v=v0, out=o0, g=g0, **base)
         ws = torch.empty(S.still_fwd_workspace_bytes(p0), dtype=torch.uint8, device=dev)
-        S.still_hybrid_attn_fwd(p0, q0, k0, v0, g0, full["Wq"], None, full["Wk"], None, o0, state_out=state,
+        S.still_hybrid_attn_fwd(p0, q0, k0, v0, g0, full["Wq"], bq, full["Wk"], bk, o0, state_out=state,
                                 workspace=ws)
         out[:, :n_prefill] = o0
     for t in range(n_prefill, n_total):
@@ -46,7 +48,7 @@ def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False, gate_ac
         vt = full["v"][:, t].contiguous()
         gt = g_full[:, t].contiguous() if with_gate else None
         ot = torch.empty_like(qt)
-        S.still_hybrid_attn_decode_step(ps, state, t, qt, kt, vt, gt, full["Wq"], None, full["Wk"], None, ot)
+        S.still_hybrid_attn_decode_step(ps, state, t, qt, kt, vt, gt, full["Wq"], bq, full["Wk"], bk, ot)
         out[:, t] = ot
     torch.cuda.synchronize()
     L = S.still_state_layout(ps)
@@ -194,6 +196,21 @@ def _decode_with_retained_budget(kw, n_prefill, n_total):
     p = S.make_params(B=w.B, N=1, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
                       dtype=w.dtype, max_tokens=1 << 20, max_retained=w.max_retained, shared_selection=w.shared_selection)
     assert S.still_state_layout(p).cap <= (w.max_retained + 63) // 64 * 64 + 64
+
+
+@pytest.mark.parametrize("kw,n_prefill,n_total", [
+    (dict(dtype="f32", d=128, C=128, W=128, lam=8), 0, 420),      # routing update: two image pieces x two parts
+    (dict(dtype="f32", d=128, C=64, W=64, lam=8), 150, 300),
+    (dict(dtype="bf16", d=64, C=128, W=96, lam=12), 300, 560),
+])
+def test_decode_with_feature_map_biases(kw, n_prefill, n_total):
+    """The NP-Map's linear layers with biases (Sec. 3.2: f is a learnable layer), prefill hand-over and routing."""
+    w = wl("decbias", **kw)
+    inp = synth.make_inputs(w, seed=27, n_tokens=n_total)
+    rng = np.random.default_rng(5)
+    inp["bq"] = synth.round_to_dtype(rng.standard_normal((w.Hq, w.df)) * 0.1, w.dtype)
+    inp["bk"] = synth.round_to_dtype(rng.standard_normal((w.Hq, w.df)) * 0.1, w.dtype)
+    check_decode(w, inp, n_prefill, n_total)
 
 
 def test_decode_with_gate():
