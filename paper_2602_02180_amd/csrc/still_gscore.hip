@@ -64,21 +64,31 @@ __global__ __launch_bounds__(256) void global_score_kernel(GScoreArgs a) {
       *reinterpret_cast<Vec16*>(&Kl[row * LD + piece * EPV]) = stage[i];
     }
   };
-  // logits (log2 domain) of this lane's query against the 16 keys it owns in sub-tile `sub` of tile kt
-  auto logits = [&](int kt, int sub, float (&x)[16]) __attribute__((always_inline)) {
+  // raw logits of this lane's query against the 16 keys it owns in sub-tile `sub` of the staged tile
+  auto products = [&](int sub) __attribute__((always_inline)) {
     floatx16 acc = zero16();
     const T* krow = &Kl[(32 * sub + r) * LD + g * M::KPL];
 #pragma unroll
     for (int s = 0; s < KS; ++s) acc = M::mma(M::load(krow + s * M::KK), qf[s], acc);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int key = kt * BK + 32 * sub + c_row(i, g);
-      x[i] = key <= tq ? acc[i] * sc2 : -INFINITY;
-    }
+    return acc;
   };
 
-  float m = -INFINITY, z_all = 0.f, z_nd = 0.f, total = 0.f;
-  float inv_all = 0.f, inv_nd = 0.f;
+  // A sub-tile whose 32 keys all precede the wave's first query is FULL: every key is visible to every row and none
+  // is a diagonal key, so it needs neither masks nor the with/without-diagonal distinction.  All but the last one
+  // to three sub-tiles of a wave are full; their sums are kept apart from the edge sub-tiles':
+  //   z_all = z_full + z_edge_all,   z_nd = z_full + z_edge_nd,   e_diag summed on its own   (no cancellation).
+  // Pass 2 does not subtract two nearly equal logarithms (over a long prefix a_j and n_j differ by the factor
+  // 1 - a_diag with a_diag ~ 1e-4, which fp32 logarithms of a_j + eps and n_j + eps resolve to a few per cent
+  // only).  For a key other than the diagonal one, with e_j the exponential under the row maximum,
+  //   (a_j + eps) / (n_j + eps) = (z_nd / z_all) (e_j + eps z_all) / (e_j + eps z_nd)
+  //                             = (1 - a_diag) (1 + eps e_diag / (e_j + eps z_nd)),
+  // both factors of the form 1 + (small, exactly known): K = log(1 - a_diag) once per row (series when a_diag is
+  // small) and log(1 + eps e_diag / (e_j + c2)) per key, so that
+  //   sum_{j != t} a_j log(...) = (1 / z_all) sum_j e_j [K + log(1 + ced / (e_j + c2))],  c2 = eps z_nd, ced = eps e_diag.
+  // The diagonal key's term, a_diag [log(a_diag + eps) - log eps], is taken as it stands.
+  float m = -INFINITY, z_full = 0.f, z_all = 0.f, z_nd = 0.f, z_dg = 0.f, total = 0.f, tfull = 0.f;
+  float inv_all = 0.f, c2 = 0.f, ced = 0.f, K = 0.f;
+  const float log2_eps = fast_log2(a.eps);
   for (int pass = 0; pass < 2; ++pass) {
     fetch(0);
     for (int kt = 0; kt < n_kt; ++kt) {
@@ -89,35 +99,59 @@ __global__ __launch_bounds__(256) void global_score_kernel(GScoreArgs a) {
       if (!wave_on || kt * BK > wave_last) continue;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
-        if (kt * BK + 32 * sub > wave_last) continue;      // uniform over the wave
-        float x[16];
-        logits(kt, sub, x);
+        const int k0 = kt * BK + 32 * sub;
+        if (k0 > wave_last) continue;                      // uniform over the wave
+        const floatx16 acc = products(sub);
+        const bool full = k0 + 31 < q0;                    // uniform over the wave
         if (pass == 0) {
+          float x[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) x[i] = (full || k0 + c_row(i, g) <= tq) ? acc[i] * sc2 : -INFINITY;
           float mt = x[0];
 #pragma unroll
           for (int i = 1; i < 16; ++i) mt = fmaxf(mt, x[i]);
           const float m_new = fmaxf(m, mt);
           if (m_new != -INFINITY) {                        // else every key so far is masked for this lane
             const float resc = fast_exp2(m - m_new);       // 0 when m = -inf
+            z_full *= resc;
             z_all *= resc;
             z_nd *= resc;
+            z_dg *= resc;
+            if (full) {
+              float z4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const float e = fast_exp2(x[i] - m_new);
-              const bool diag = kt * BK + 32 * sub + c_row(i, g) == tq;
-              z_all += e;
-              z_nd += diag ? 0.f : e;
+              for (int i = 0; i < 16; ++i) z4[i & 3] += fast_exp2(x[i] - m_new);
+              z_full += (z4[0] + z4[1]) + (z4[2] + z4[3]);
+            } else {
+#pragma unroll
+              for (int i = 0; i < 16; ++i) {
+                const float e = fast_exp2(x[i] - m_new);
+                const bool diag = k0 + c_row(i, g) == tq;
+                z_all += e;
+                z_nd += diag ? 0.f : e;
+                z_dg += diag ? e : 0.f;
+              }
             }
             m = m_new;
           }
+        } else if (full) {
+          float t4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float e = fast_exp2(fmaf(acc[i], sc2, -m));   // m is the row maximum now
+            t4[i & 3] = fmaf(e, fast_log2(fmaf(ced, fast_rcp(e + c2), 1.0f)), t4[i & 3]);
+          }
+          tfull += (t4[0] + t4[1]) + (t4[2] + t4[3]);
         } else {
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            const float e = fast_exp2(x[i] - m);           // m is the row maximum now; masked keys give 0
-            const bool diag = kt * BK + 32 * sub + c_row(i, g) == tq;
+            const bool vis = k0 + c_row(i, g) <= tq;
+            const bool diag = k0 + c_row(i, g) == tq;
+            const float e = vis ? fast_exp2(fmaf(acc[i], sc2, -m)) : 0.f;
             const float ad = e * inv_all;
-            const float an = diag ? 0.f : e * inv_nd;
-            total = fmaf(ad, fast_log2(ad + a.eps) - fast_log2(an + a.eps), total);
+            const float lg = diag ? fast_log2(ad + a.eps) - log2_eps
+                                  : K + fast_log2(fmaf(ced, fast_rcp(e + c2), 1.0f));
+            total = fmaf(ad, vis ? lg : 0.f, total);       // (an invisible key has e = 0, and c2 may be 0 too)
           }
         }
       }
@@ -126,14 +160,21 @@ __global__ __launch_bounds__(256) void global_score_kernel(GScoreArgs a) {
       // combine the two lane groups of each query: common maximum, then the normalisers
       const float m_row = max32(m);
       const float w = m == -INFINITY ? 0.f : fast_exp2(m - m_row);
-      z_all = sum32(z_all * w);
-      z_nd = sum32(z_nd * w);
+      z_full = sum32(z_full * w);
+      z_all = z_full + sum32(z_all * w);
+      z_nd = z_full + sum32(z_nd * w);
+      z_dg = sum32(z_dg * w);
       m = m_row;
       inv_all = 1.0f / z_all;
-      inv_nd = z_nd > 0.f ? 1.0f / z_nd : 0.f;             // the first token has no other key: n = 0
+      c2 = a.eps * z_nd;
+      ced = a.eps * z_dg;
+      // K = log2(1 - a_diag); a row whose only key is the diagonal one has no other term (K unused, kept finite)
+      const float y = z_dg * inv_all;
+      K = z_nd > 0.f ? (y < 0.01f ? -y * (1.0f + y * (0.5f + y * (1.0f / 3.0f))) * kLog2e : fast_log2(z_nd * inv_all)) : 0.f;
     }
   }
-  total = sum32(total);
+  // the full sub-tiles' share (a row without other keys has none: z_full = 0)
+  total = sum32(total + inv_all * tfull) + inv_all * K * z_full;
   if (g == 0 && t < N) a.score[((int64_t)b * a.Hq + hq) * N + t] = total * kLn2;
 }
 

@@ -457,7 +457,7 @@ def test_profile_modes_report_kernel_times():
     dict(dtype="bf16", d=128, N=1500, Hq=4, Hkv=2, B=2, C=128, W=128),
     dict(dtype="bf16", d=64, N=129, Hq=2, Hkv=1),
     dict(dtype="f32", d=64, N=1, Hq=1, Hkv=1),
-    dict(dtype="f32", d=128, N=400, Hq=2, Hkv=1, C=128, W=128),     # a shape the prefill's linear branch restricts
+    dict(dtype="f32", d=128, N=400, Hq=2, Hkv=1, C=128, W=128),
 ], ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
 def test_global_score_and_selection_overlap(kw):
     """Score over the whole causal prefix against the oracle's two-softmax form, then the per-chunk overlap of the
@@ -474,13 +474,7 @@ def test_global_score_and_selection_overlap(kw):
     glob = torch.full((w.B, w.Hq, w.N), float("nan"), dtype=torch.float32, device=dev)
     S.still_global_score(p, q, k, glob)
     kv = synth.kv_head_map(w)
-    if not (w.dtype == "f32" and w.d == 128 and w.C == 128):
-        local = torch.from_numpy(U.run_hip(w, inp, want_terms=False)["score"]).to(dev)
-    else:                              # a shape only the side entry points take: local scores from the oracle
-        loc = np.stack([np.stack([O.self_saliency_scores(inp["q"][b, :, h].astype(np.float64),
-                                                         inp["k"][b, :, kv[h]].astype(np.float64), w.W, w.scale, w.eps)
-                                  for h in range(w.Hq)]) for b in range(w.B)])
-        local = torch.from_numpy(loc.astype(np.float32)).to(dev)
+    local = torch.from_numpy(U.run_hip(w, inp, want_terms=False)["score"]).to(dev)
     ncf = w.N // w.C
     ov = torch.full((w.B, w.Hq, max(ncf, 1)), -1, dtype=torch.int32, device=dev)
     S.still_selection_overlap(p, local, glob, ov)
@@ -504,6 +498,35 @@ def test_global_score_and_selection_overlap(kw):
             exact += int(clear.sum()); total += ncf
     print(f"[gscore {w.dtype} d={w.d} N={w.N}] global score max-abs err {worst:.3e}; chunks with clear gaps {exact}/{total}")
     assert worst <= 5e-5, worst      # the bar of the window-local score
+
+
+def test_global_score_over_a_long_prefix_keeps_relative_accuracy():
+    """Over thousands of keys a_j and n_j differ by the factor 1 - a_diag with a_diag ~ 1e-3 .. 1e-4, and the score
+    itself is of that size: an absolute bar says nothing there.  Every row's score must match the float64 oracle to
+    1e-3 of its own value plus 2e-8 (the kernel takes the logarithm of the ratio as log(1 - a_diag) + log(1 + small) rather
+    than as the difference of two fp32 logarithms, which resolves it to a few per cent only)."""
+    import torch
+    from oracle import still_oracle as O
+
+    w = small("gslong", dtype="bf16", d=128, N=6144, Hq=1, Hkv=1, C=128, W=128)
+    inp = synth.make_inputs(w, seed=33)
+    dev = "cuda"
+    q, k = synth.to_torch(inp["q"], w.dtype, dev), synth.to_torch(inp["k"], w.dtype, dev)
+    p = S.make_params(B=w.B, N=w.N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, q=q, k=k)
+    glob = torch.full((w.B, w.Hq, w.N), float("nan"), dtype=torch.float32, device=dev)
+    S.still_global_score(p, q, k, glob)
+    torch.cuda.synchronize()
+    got = glob.cpu().numpy()[0, 0].astype(np.float64)
+    ref = O.global_scores(inp["q"][0, :, 0].astype(np.float64), inp["k"][0, :, 0].astype(np.float64), w.scale, w.eps)
+    err = np.abs(got - ref)
+    tail = slice(1024, None)
+    bar = 1e-3 * np.abs(ref) + 2e-8                  # (a score can pass through zero: a small absolute floor)
+    frac = (err / bar)[tail]
+    print(f"[gscore long prefix] rows >= 1024: median |score| {np.median(np.abs(ref[tail])):.3e}, "
+          f"worst error / (1e-3 |ref| + 2e-8) = {frac.max():.3f}, max-abs error {err.max():.3e}")
+    assert err.max() <= 5e-5
+    assert frac.max() <= 1.0, frac.max()
 
 
 def test_128k_context_last_rows_and_selection():
