@@ -104,13 +104,16 @@ __global__ __launch_bounds__(256) void global_score_kernel(GScoreArgs a) {
         const floatx16 acc = products(sub);
         const bool full = k0 + 31 < q0;                    // uniform over the wave
         if (pass == 0) {
-          float x[16];
+          // running maximum and normalisers (raw logits: the positive scale commutes with the maximum)
+          float mraw = -INFINITY;
+          if (full) {
 #pragma unroll
-          for (int i = 0; i < 16; ++i) x[i] = (full || k0 + c_row(i, g) <= tq) ? acc[i] * sc2 : -INFINITY;
-          float mt = x[0];
+            for (int i = 0; i < 16; ++i) mraw = fmaxf(mraw, acc[i]);
+          } else {
 #pragma unroll
-          for (int i = 1; i < 16; ++i) mt = fmaxf(mt, x[i]);
-          const float m_new = fmaxf(m, mt);
+            for (int i = 0; i < 16; ++i) mraw = fmaxf(mraw, k0 + c_row(i, g) <= tq ? acc[i] : -INFINITY);
+          }
+          const float m_new = fmaxf(m, mraw * sc2);
           if (m_new != -INFINITY) {                        // else every key so far is masked for this lane
             const float resc = fast_exp2(m - m_new);       // 0 when m = -inf
             z_full *= resc;
@@ -120,16 +123,16 @@ __global__ __launch_bounds__(256) void global_score_kernel(GScoreArgs a) {
             if (full) {
               float z4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-              for (int i = 0; i < 16; ++i) z4[i & 3] += fast_exp2(x[i] - m_new);
+              for (int i = 0; i < 16; ++i) z4[i & 3] += fast_exp2(fmaf(acc[i], sc2, -m_new));
               z_full += (z4[0] + z4[1]) + (z4[2] + z4[3]);
             } else {
 #pragma unroll
               for (int i = 0; i < 16; ++i) {
-                const float e = fast_exp2(x[i] - m_new);
-                const bool diag = k0 + c_row(i, g) == tq;
+                const int key = k0 + c_row(i, g);
+                const float e = key <= tq ? fast_exp2(fmaf(acc[i], sc2, -m_new)) : 0.f;
                 z_all += e;
-                z_nd += diag ? 0.f : e;
-                z_dg += diag ? e : 0.f;
+                z_nd += key == tq ? 0.f : e;
+                z_dg += key == tq ? e : 0.f;
               }
             }
             m = m_new;
