@@ -160,6 +160,28 @@ def select_top_lambda(score: np.ndarray, C: int, lam: int, max_retained: Optiona
     return sel
 
 
+def retained_sets_evict(score: np.ndarray, sel: np.ndarray, max_retained: int):
+    """Budget policy "evict" (an invention: Sec. 4's long-context settings cap the cached tokens, the policy is not
+    stated).  Every routed chunk offers its Top-lambda tokens (`sel`, one row per full chunk, -1 = unused slot).
+    After routing step s the retained set is the union of the previous set and chunk s's offer, cut back to
+    max_retained members by removing the lowest score first (between equal scores the higher index goes first, so
+    the lower index is kept, as in the Top-lambda rule).  A removed token, whether it was retained earlier or has
+    just been offered, is handed to the linear-attention state AT THIS STEP.
+
+    Returns (retained, released): retained[s] = sorted token indices kept after step s, released[s] = sorted token
+    indices removed at step s."""
+    kept: list = []
+    retained, released = [], []
+    for s in range(sel.shape[0]):
+        kept = kept + [int(i) for i in sel[s] if i >= 0]
+        kept.sort(key=lambda i: (-score[i], i))            # best first
+        out = kept[max_retained:]
+        kept = kept[:max_retained]
+        retained.append(np.asarray(sorted(kept), np.int64))
+        released.append(np.asarray(sorted(out), np.int64))
+    return retained, released
+
+
 def global_scores(q: np.ndarray, k: np.ndarray, scale: float, eps: float) -> np.ndarray:
     """The score with the window set replaced by the whole causal prefix {0..t}: the "global" reference of the
     local-versus-global consistency study of Sec. 3.1.  Same two softmaxes, same formula."""
@@ -267,11 +289,11 @@ def _merge(res, t):
     res["out"][t] = (res["N_SA"][t] + f * res["N_LA"][t]) / (res["D_SA"][t] + f * res["D_LA"][t])
 
 
-def _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained=None):
+def _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained=None, budget_policy="stop"):
     if score is None:
         score = self_saliency_scores(q, k, W, scale, eps)
     if sel is None:
-        sel = select_top_lambda(score, C, lam, max_retained)
+        sel = select_top_lambda(score, C, lam, None if budget_policy == "evict" else max_retained)
     sel = np.asarray(sel, np.int64)
     sel = sel.reshape(q.shape[0] // C, sel.size // max(1, q.shape[0] // C))
     return score, sel
@@ -283,13 +305,18 @@ def _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained=None):
 
 def still_definition(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
                      sel=None, score=None, rows: Optional[Tuple[int, int]] = None,
-                     max_retained: Optional[int] = None, gate_activation: str = "none") -> Dict:
+                     max_retained: Optional[int] = None, gate_activation: str = "none",
+                     budget_policy: str = "stop", rank_score=None) -> Dict:
     """Row t in chunk c sees, through exp: the local span (previous chunk and own chunk up to t)
     plus the selected tokens of chunks <= c-2; through phi_q.phi_k: every other token of
-    chunks <= c-2.  One division merges them."""
+    chunks <= c-2.  One division merges them.  (budget_policy "evict": the selected tokens are those
+    retained after routing step c-2, see retained_sets_evict; rank_score overrides the score they are ranked by.)"""
     q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk, gate_activation)
     N, d = q.shape
-    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained)
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained, budget_policy)
+    evict = budget_policy == "evict" and max_retained is not None
+    if evict:
+        kept_after, _ = retained_sets_evict(score if rank_score is None else rank_score, sel, max_retained)
     phi_q = np_map(q, Wq, bq)
     phi_k = np_map(k, Wk, bk)
     rows = (0, N) if rows is None else rows
@@ -299,7 +326,11 @@ def still_definition(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None
         c = t // C
         local = list(range(max(0, (c - 1) * C), t + 1))
         ret, lin = [], []
-        for cc in range(0, c - 1):
+        if evict and c >= 2:
+            chosen = set(int(i) for i in kept_after[c - 2])
+            for i in range(0, (c - 1) * C):
+                (ret if i in chosen else lin).append(i)
+        for cc in range(0, c - 1 if not evict else 0):
             chosen = set(int(i) for i in sel[cc] if i >= 0)
             for i in range(cc * C, (cc + 1) * C):
                 (ret if i in chosen else lin).append(i)
@@ -326,14 +357,17 @@ def still_definition(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None
 
 def still_recurrent(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
                     sel=None, score=None, rows: Optional[Tuple[int, int]] = None,
-                    return_state: bool = False, max_retained: Optional[int] = None, gate_activation: str = "none") -> Dict:
+                    return_state: bool = False, max_retained: Optional[int] = None, gate_activation: str = "none",
+                    budget_policy: str = "stop", rank_score=None) -> Dict:
     """Step t (1-indexed as in the paper) is written t = (a+1)C + b with 1 <= b <= C.
     When b == 1 and a >= 1 the chunk a (tokens (a-1)C+1 .. aC) is routed: its top-lambda
     keys/values join the retained part of the cache, the others are added to (s, z).
     The cache also always holds the local span aC < i <= t."""
     q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk, gate_activation)
     N, d = q.shape
-    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained)
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained, budget_policy)
+    evict = budget_policy == "evict" and max_retained is not None
+    rk = score if rank_score is None else rank_score
     dprime = 2 * np.asarray(Wq).shape[1]
     s = np.zeros((dprime, v.shape[1]), F64)
     z = np.zeros(dprime, F64)
@@ -349,7 +383,15 @@ def still_recurrent(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
             chosen = [int(i) for i in sel[chunk0] if i >= 0]
             retained.extend(chosen)
             cs = set(chosen)
-            rest = np.asarray([i for i in range(chunk0 * C, (chunk0 + 1) * C) if i not in cs], np.int64)
+            rest = [i for i in range(chunk0 * C, (chunk0 + 1) * C) if i not in cs]
+            if evict:
+                # the cache is over its budget: the lowest scores leave it (between equal scores the higher index
+                # first) and join the chunk's unselected tokens on their way into the state
+                while len(retained) > max_retained:
+                    worst = min(retained, key=lambda i: (rk[i], -i))
+                    retained.remove(worst)
+                    rest.append(worst)
+            rest = np.asarray(sorted(rest), np.int64)
             if rest.size:
                 pk = np_map(k[rest], Wk, bk)
                 s = s + pk.T @ v[rest]
@@ -380,13 +422,17 @@ def still_recurrent(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
 
 def still_chunkwise(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
                     sel=None, score=None, rows: Optional[Tuple[int, int]] = None,
-                     max_retained: Optional[int] = None, gate_activation: str = "none") -> Dict:
+                     max_retained: Optional[int] = None, gate_activation: str = "none",
+                     budget_policy: str = "stop", rank_score=None) -> Dict:
     """Chunk tensors; per-chunk states phi_k(k_LA)^T v_LA cumulated over chunks and delayed by
     two; chunk c attends with exp to the flattened selected keys of chunks <= c-2, to the whole
-    previous chunk and causally to itself; a single division merges both branches."""
+    previous chunk and causally to itself; a single division merges both branches.
+    (budget_policy "evict": chunk c's selected keys are the set retained after routing step c-2, and a token
+    released at step s is part of chunk s's contribution to the state.)"""
     q, k, v, g = _prep(q, k, v, g, Wq, Wk, bq, bk, gate_activation)
     N, d = q.shape
-    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained)
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained, budget_policy)
+    evict = budget_policy == "evict" and max_retained is not None
     T = -(-N // C)
     ncf = N // C
     dprime = 2 * np.asarray(Wq).shape[1]
@@ -400,12 +446,16 @@ def still_chunkwise(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
     flat = np.concatenate(kept) if ncf else np.zeros(0, np.int64)
     k_sa_flat = k[flat]
     v_sa_flat = v[flat]
+    if evict:
+        kept_after, released = retained_sets_evict(score if rank_score is None else rank_score, sel, max_retained)
     ds = np.zeros((T, dprime, v.shape[1]), F64)
     dz = np.zeros((T, dprime), F64)
     for c in range(ncf):
         keep = np.ones(C, bool)
         keep[kept[c] - c * C] = False
         idx = np.nonzero(keep)[0] + c * C
+        if evict:
+            idx = np.concatenate([idx, released[c]])
         if idx.size:
             pk = np_map(k[idx], Wk, bk)
             ds[c] = pk.T @ v[idx]
@@ -420,6 +470,10 @@ def still_chunkwise(q, k, v, g, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None,
         n_vis = int(n_kept[min(max(0, c - 1), ncf)])     # selected keys of chunks 0..c-2
         blocks_k = [k_sa_flat[:n_vis]]
         blocks_v = [v_sa_flat[:n_vis]]
+        if evict:
+            alive = kept_after[min(c - 2, ncf - 1)] if c >= 2 and ncf else np.zeros(0, np.int64)
+            n_vis = alive.size
+            blocks_k, blocks_v = [k[alive]], [v[alive]]
         masks = [np.ones((t1 - t0, n_vis), bool)]
         if c >= 1:
             blocks_k.append(k[t0 - C:t0])
@@ -467,13 +521,16 @@ def still_forward_units(inputs: Dict[str, np.ndarray], kv_map: np.ndarray, units
                         rows: Optional[Tuple[int, int]] = None,
                         max_retained: Optional[int] = None,
                         shared_selection: bool = False,
-                        gate_activation: str = "none") -> Dict[Tuple[int, int], Dict]:
+                        gate_activation: str = "none", budget_policy: str = "stop",
+                        rank_scores: Optional[np.ndarray] = None) -> Dict[Tuple[int, int], Dict]:
     """Run one form on the listed (b, hq) units of a batched problem.
 
     inputs: q [B,N,Hq,d], k,v [B,N,Hkv,d], Wq,Wk [Hq,d,d_f], optional g [B,N,Hq,d],
     optional bq,bk [Hq,d_f].  sel (optional) [B,Hq,N//C,lam] overrides the selection.
     shared_selection: the heads that read one kv head rank by the sum of their scores and share one list.
     Every result carries "rank_score": the score its selection was ranked by (its own, or the group's sum).
+    budget_policy "evict" (with max_retained): see retained_sets_evict; rank_scores (optional) [B,Hq,N] overrides the
+    score the evictions are ranked by (tests pass the device's fp32 scores, so both sides decide in one precision).
     """
     fn = {"chunkwise": still_chunkwise, "recurrent": still_recurrent, "definition": still_definition}[form]
     out = {}
@@ -493,9 +550,14 @@ def still_forward_units(inputs: Dict[str, np.ndarray], kv_map: np.ndarray, units
         bk = inputs["bk"][h] if inputs.get("bk") is not None else None
         s_in = None if sel is None else sel[b, h]
         if s_in is None and rank is not None:
-            s_in = select_top_lambda(rank, C, lam, max_retained)
+            s_in = select_top_lambda(rank, C, lam, None if budget_policy == "evict" else max_retained)
+        extra = {}
+        if budget_policy == "evict":
+            if shared_selection:
+                raise ValueError("the evict policy is defined per query head")
+            extra = dict(budget_policy="evict", rank_score=None if rank_scores is None else rank_scores[b, h])
         out[(b, h)] = fn(inputs["q"][b, :, h], inputs["k"][b, :, kh], inputs["v"][b, :, kh], g,
                          inputs["Wq"][h], inputs["Wk"][h], C, W, lam, scale, eps, bq=bq, bk=bk,
-                         sel=s_in, rows=rows, max_retained=max_retained, gate_activation=gate_activation)
+                         sel=s_in, rows=rows, max_retained=max_retained, gate_activation=gate_activation, **extra)
         out[(b, h)]["rank_score"] = out[(b, h)]["score"] if rank is None else rank
     return out

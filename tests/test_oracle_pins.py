@@ -465,6 +465,111 @@ def test_budget_forms_agree():
     assert np.array_equal(rs[0]["sel"], rs[1]["sel"]) and np.array_equal(rs[0]["sel"], rs[2]["sel"])
 
 
+# --------------------------------------------------------------------------- budget policy "evict"
+def test_evict_policy_retained_sets_literals():
+    """Hand example, C = 4, lam = 2, budget 3.  Scores by token:
+         chunk 0: 5 1 4 0   -> offers tokens 0, 2
+         chunk 1: 9 8 0 0   -> offers 4, 5
+         chunk 2: 1 2 0 0   -> offers 8, 9
+         chunk 3: 5 5 5 0   -> offers 12, 13 (tie of three: the lower indices)
+    step 0: {0, 2}, nothing leaves.  step 1: {0:5, 2:4, 4:9, 5:8} -> 2 leaves.  step 2: 8 and 9 (scores 1, 2) are
+    below everything kept and leave at once.  step 3: {0:5, 4:9, 5:8, 12:5, 13:5}: two of the three 5s must go,
+    the higher indices first -> 13 and 12 leave, 0 stays."""
+    score = np.array([5, 1, 4, 0, 9, 8, 0, 0, 1, 2, 0, 0, 5, 5, 5, 0], float)
+    sel = O.select_top_lambda(score, 4, 2)
+    assert sel.tolist() == [[0, 2], [4, 5], [8, 9], [12, 13]]
+    kept, out = O.retained_sets_evict(score, sel, 3)
+    assert [x.tolist() for x in kept] == [[0, 2], [0, 4, 5], [0, 4, 5], [0, 4, 5]]
+    assert [x.tolist() for x in out] == [[], [2], [8, 9], [12, 13]]
+    kept1, out1 = O.retained_sets_evict(score, sel, 1)
+    assert [x.tolist() for x in kept1] == [[0], [4], [4], [4]]
+    assert [x.tolist() for x in out1] == [[2], [0, 5], [8, 9], [12, 13]]
+
+
+@pytest.mark.parametrize("form", FORMS)
+@pytest.mark.parametrize("N,C,lam,cap", [(40, 4, 2, 5), (41, 4, 3, 4), (36, 6, 6, 9), (33, 4, 2, 1)])
+def test_evict_policy_budget_never_exceeded_and_every_token_seen_once(form, N, C, lam, cap):
+    """One-hot values: row t of chunk c sees through exp the local span and the `cap` best-scored offers of chunks
+    <= c-2 (brute force over all offers made so far), every other routed token through phi, nothing twice."""
+    rng = np.random.default_rng(41)
+    q = rng.standard_normal((N, 4))
+    k = rng.standard_normal((N, 4))
+    Wq = rng.standard_normal((4, 3))
+    Wk = rng.standard_normal((4, 3))
+    r = form(q, k, np.eye(N), None, Wq, Wk, C=C, W=3, lam=lam, scale=0.5, eps=EPS, max_retained=cap,
+             budget_policy="evict")
+    sel, score = r["sel"], r["score"]
+    assert np.all(sel >= 0)                       # every chunk offers its full Top-lambda
+    for t in range(N):
+        c = t // C
+        sa, la = r["N_SA"][t] > 0, r["N_LA"][t] > 0
+        assert not np.any(sa & la)
+        assert np.all((sa | la)[: t + 1]) and not np.any((sa | la)[t + 1:])
+        lo = max(0, (c - 1) * C)
+        offers = [int(i) for cc in range(0, c - 1) for i in sel[cc]]
+        best = sorted(offers, key=lambda i: (-score[i], i))[:cap]
+        assert sa[:lo].sum() == len(best) <= cap
+        expect = np.zeros(N, bool)
+        expect[lo: t + 1] = True
+        expect[best] = True
+        assert np.array_equal(sa, expect)
+
+
+@pytest.mark.parametrize("form", FORMS)
+def test_evict_policy_special_cases(form):
+    q, k, v, g, Wq, Wk = rand_problem(42, 64, 8)
+    kw = dict(C=8, W=6, lam=3, scale=0.35, eps=EPS)
+    free = form(q, k, v, g, Wq, Wk, **kw)
+    # a budget nobody reaches is no budget
+    roomy = form(q, k, v, g, Wq, Wk, max_retained=3 * 8, budget_policy="evict", **kw)
+    np.testing.assert_array_equal(free["out"], roomy["out"])
+    # budget zero: every offer leaves at once = nothing is ever kept
+    none = form(q, k, v, g, Wq, Wk, C=8, W=6, lam=0, scale=0.35, eps=EPS)
+    zero = form(q, k, v, g, Wq, Wk, max_retained=0, budget_policy="evict", **kw)
+    np.testing.assert_allclose(zero["out"], none["out"], rtol=1e-12)
+    # scores that fall from chunk to chunk: a later offer never beats a kept token, so evicting the lowest score
+    # is the stop-adding policy (the offers that do not fit leave at once)
+    N = 64
+    falling = -np.arange(N, dtype=float)
+    stop = form(q, k, v, g, Wq, Wk, max_retained=7, score=falling, **kw)
+    evict = form(q, k, v, g, Wq, Wk, max_retained=7, score=falling, budget_policy="evict", **kw)
+    np.testing.assert_allclose(stop["out"], evict["out"], rtol=1e-12)
+    # scores that rise: the cache always holds the newest offers, i.e. a budget of whole offers is a sliding set
+    rising = np.arange(N, dtype=float)
+    ev = form(q, k, v, g, Wq, Wk, max_retained=6, score=rising, budget_policy="evict", **kw)
+    # the same operator without a budget, fed for every row the two newest offers: only checkable row by row, so
+    # compare one row of chunk 6 (sees offers of chunks 0..4, keeps those of chunks 3 and 4) against the definition
+    t = 6 * 8 + 5
+    keep = [int(i) for cc in (3, 4) for i in ev["sel"][cc]]
+    local = list(range(5 * 8, t + 1))
+    lin = [i for i in range(0, 5 * 8) if i not in keep]
+    sa = np.asarray(keep + local)
+    logit = 0.35 * (k[sa] @ q[t])
+    e = np.exp(logit - logit.max())
+    pq, pk = O.np_map(q, Wq), O.np_map(k, Wk)
+    wgt = pk[lin] @ pq[t] * np.exp(-logit.max())
+    y = (e @ v[sa] + (wgt @ v[lin]) * g[t]) / (e.sum() + wgt.sum())
+    np.testing.assert_allclose(ev["out"][t], y, rtol=1e-11)
+
+
+def test_evict_policy_forms_agree_and_rank_score_override():
+    q, k, v, g, Wq, Wk = rand_problem(43, 70, 8, df=6)
+    kw = dict(C=8, W=11, lam=3, scale=0.35, eps=EPS, max_retained=10, budget_policy="evict")
+    rs = [f(q, k, v, g, Wq, Wk, **kw) for f in FORMS]
+    for key in ("out", "M", "N_SA", "D_SA", "N_LA", "D_LA"):
+        np.testing.assert_allclose(rs[0][key], rs[1][key], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(rs[0][key], rs[2][key], rtol=1e-11, atol=1e-13)
+    stop = O.still_chunkwise(q, k, v, g, Wq, Wk, C=8, W=11, lam=3, scale=0.35, eps=EPS, max_retained=10)
+    assert np.abs(stop["out"] - rs[2]["out"]).max() > 1e-6          # the two policies differ on random scores
+    # ranking the evictions by another score changes who stays, not who is offered
+    other = np.random.default_rng(5).standard_normal(70)
+    alt = [f(q, k, v, g, Wq, Wk, rank_score=other, **kw) for f in FORMS]
+    assert np.array_equal(alt[0]["sel"], rs[0]["sel"])
+    assert np.abs(alt[0]["out"] - rs[0]["out"]).max() > 1e-6
+    np.testing.assert_allclose(alt[0]["out"], alt[1]["out"], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(alt[0]["out"], alt[2]["out"], rtol=1e-11, atol=1e-13)
+
+
 def test_budget_with_whole_chunks_kept_is_attention_sink_plus_window_plus_linear_rest():
     """lam = C and a budget of m chunks: the first m chunks stay under softmax for good, the local span
     slides, everything between goes through phi.  Written out directly with scipy's softmax weights and
