@@ -87,6 +87,15 @@ typedef struct still_params {
                                     1: g holds a pre-activation (x W_g of Sec. 3.2) and the kernels apply the
                                     logistic function 1 / (1 + exp(-g)) where they read it; the paper names no
                                     activation, this one is an option of this library.  Prefill and decode.   */
+  int32_t budget_policy;         /* what max_retained means once the budget is reached (both are inventions, see
+                                    max_retained).  0: stop adding, as described there.  1: evict the lowest
+                                    score: every routed chunk offers its lambda highest scores; the retained set
+                                    is then cut back to max_retained members by removing the lowest score first
+                                    (between equal scores the higher token index first), and a removed token,
+                                    retained earlier or just offered, enters the linear state (through the
+                                    NP-Map) at that routing step, so that every past token is still seen exactly
+                                    once.  sel lists then hold the chunk's offers.  Decode steps only (a state
+                                    from still_state_init); the prefill and shared_selection refuse it.        */
   int64_t q_sb, q_st, q_sh;      /* q   [B, N, Hq,  d]                                                     */
   int64_t k_sb, k_st, k_sh;      /* k   [B, N, Hkv, d]                                                     */
   int64_t v_sb, v_st, v_sh;      /* v   [B, N, Hkv, d]                                                     */
@@ -232,6 +241,8 @@ STILL_API const char* still_profile_kernel_name(int32_t i);
  *   ring dtype [B, Hkv, R, d] x 2     keys and values of the last R = 4*C tokens, slot = token % R
  *   sc   float [B, Hq, R]             Self-Saliency Score of the same tokens
  *   part float [B, Hq, 32, d+2]       split partials of the attention pass
+ *   rsc  float [B, Hq, cap]           budget_policy 1 only: Self-Saliency Score of every retained row
+ *   rtok int32 [B, Hq, cap]           budget_policy 1 only: its token index (retained rows are then in no order)
  * The number of tokens seen is NOT stored: the caller passes the index t of the new token to every step.
  * The buffer can be copied or saved with plain memcpy.  p->N is ignored by the state functions.
  */
@@ -239,7 +250,7 @@ STILL_API size_t still_state_bytes(const still_params_t* p);
 
 /* Byte offsets of the regions above inside a state buffer (for tests/tools). */
 typedef struct still_state_layout {
-  size_t S, kret, vret, sel, kring, vring, score, part, total;
+  size_t S, kret, vret, sel, kring, vring, score, part, ret_score, ret_tok, total;
   int32_t cap, R, n_chunks;
 } still_state_layout_t;
 STILL_API still_status_t still_state_layout(const still_params_t* p, still_state_layout_t* layout);

@@ -182,6 +182,18 @@ def retained_sets_evict(score: np.ndarray, sel: np.ndarray, max_retained: int):
     return retained, released
 
 
+def eviction_margins(score: np.ndarray, sel: np.ndarray, max_retained: int) -> np.ndarray:
+    """Test helper for the "evict" policy: per routing step, the lowest score that stays minus the highest score
+    that leaves (+inf when nothing leaves).  A comparison of two implementations is only meaningful at steps
+    whose margin exceeds their score tolerance."""
+    kept, out = retained_sets_evict(score, sel, max_retained)
+    m = np.full(len(kept), np.inf)
+    for s in range(len(kept)):
+        if out[s].size and kept[s].size:
+            m[s] = score[kept[s]].min() - score[out[s]].max()
+    return m
+
+
 def global_scores(q: np.ndarray, k: np.ndarray, scale: float, eps: float) -> np.ndarray:
     """The score with the window set replaced by the whole causal prefix {0..t}: the "global" reference of the
     local-versus-global consistency study of Sec. 3.1.  Same two softmaxes, same formula."""

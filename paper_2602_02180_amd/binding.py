@@ -25,7 +25,7 @@ class StillParams(ct.Structure):
         ("d_f", ct.c_int32), ("C", ct.c_int32), ("W", ct.c_int32), ("lam", ct.c_int32),
         ("scale", ct.c_float), ("eps", ct.c_float), ("dtype", ct.c_int32), ("max_tokens", ct.c_int32),
         ("max_retained", ct.c_int32), ("shared_selection", ct.c_int32), ("emit_terms", ct.c_int32),
-        ("gate_activation", ct.c_int32),
+        ("gate_activation", ct.c_int32), ("budget_policy", ct.c_int32),
         ("q_sb", ct.c_int64), ("q_st", ct.c_int64), ("q_sh", ct.c_int64),
         ("k_sb", ct.c_int64), ("k_st", ct.c_int64), ("k_sh", ct.c_int64),
         ("v_sb", ct.c_int64), ("v_st", ct.c_int64), ("v_sh", ct.c_int64),
@@ -44,7 +44,7 @@ class StillWsLayout(ct.Structure):
 
 class StillStateLayout(ct.Structure):
     _fields_ = [(n, ct.c_size_t) for n in
-                ("S", "kret", "vret", "sel", "kring", "vring", "score", "part", "total")] + \
+                ("S", "kret", "vret", "sel", "kring", "vring", "score", "part", "ret_score", "ret_tok", "total")] + \
                [(n, ct.c_int32) for n in ("cap", "R", "n_chunks")]
 
 
@@ -124,7 +124,7 @@ def _strides(t):
 
 def make_params(*, B, N, Hq, Hkv, d, C, W, lam, scale, eps, dtype, d_f=None, q=None, k=None, v=None, out=None,
                 g=None, kv_head_of_q=None, max_tokens=0, max_retained=0, shared_selection=0, seq_len=None,
-                emit_terms=0, gate_activation=0) -> StillParams:
+                emit_terms=0, gate_activation=0, budget_policy=0) -> StillParams:
     """Fill a still_params_t; strides are taken from the torch tensors ([B, N, H, d])."""
     p = StillParams()
     p.B, p.N, p.Hq, p.Hkv, p.d, p.d_f = B, N, Hq, Hkv, d, (d_f or d)
@@ -135,6 +135,7 @@ def make_params(*, B, N, Hq, Hkv, d, C, W, lam, scale, eps, dtype, d_f=None, q=N
     p.shared_selection = int(shared_selection)
     p.emit_terms = int(emit_terms)
     p.gate_activation = int(gate_activation)
+    p.budget_policy = int(budget_policy)
     if seq_len is not None:   # int32 device tensor [B]; kept alive by the params object
         assert seq_len.is_cuda and seq_len.is_contiguous() and seq_len.numel() == B and str(seq_len.dtype) == "torch.int32"
         p._seq_len_keepalive = seq_len

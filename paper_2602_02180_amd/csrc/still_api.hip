@@ -107,6 +107,16 @@ still_status_t validate_params(const still_params_t* p, bool need_n) {
   if (p->W < 1) return fail(STILL_ERR_INVALID_ARG, "W must be >= 1");
   if (p->gate_activation != 0 && p->gate_activation != 1)
     return fail(STILL_ERR_INVALID_ARG, "gate_activation %d unknown (0: none, 1: sigmoid)", p->gate_activation);
+  if (p->budget_policy != 0 && p->budget_policy != 1)
+    return fail(STILL_ERR_INVALID_ARG, "budget_policy %d unknown (0: stop adding, 1: evict the lowest score)",
+                p->budget_policy);
+  if (p->budget_policy == 1) {
+    if (p->max_retained < 1) return fail(STILL_ERR_INVALID_ARG, "budget_policy 1 needs max_retained >= 1");
+    if (p->shared_selection) return fail(STILL_ERR_UNSUPPORTED, "budget_policy 1 is defined per query head");
+    if (p->max_retained > still::kMaxEvictBudget)
+      return fail(STILL_ERR_UNSUPPORTED, "budget_policy 1: max_retained %d > %d", p->max_retained,
+                  still::kMaxEvictBudget);
+  }
   if (!(p->eps > 0.f)) return fail(STILL_ERR_INVALID_ARG, "eps must be > 0");
   if (!(p->scale > 0.f)) return fail(STILL_ERR_INVALID_ARG, "scale must be > 0");
   if (p->Hq > still::kMaxHq) return fail(STILL_ERR_UNSUPPORTED, "Hq %d > %d", p->Hq, still::kMaxHq);
@@ -244,6 +254,8 @@ void compute_state_layout(const still_params_t* p, still_state_layout_t* L) {
   L->vring = take((size_t)B * Hkv * R * d * es);
   L->score = take((size_t)B * Hq * R * 4);
   L->part = take((size_t)B * Hq * 32 * (d + 2) * 4);
+  L->ret_score = take(p->budget_policy == 1 ? (size_t)B * Hq * cap * 4 : 0);
+  L->ret_tok = take(p->budget_policy == 1 ? (size_t)B * Hq * cap * 4 : 0);
   L->total = off;
   L->cap = (int32_t)cap;
   L->R = (int32_t)R;
@@ -316,6 +328,8 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   if (st != STILL_OK) return st;
   st = validate_strides(p, g != nullptr);
   if (st != STILL_OK) return st;
+  if (p->budget_policy != 0)
+    return fail(STILL_ERR_UNSUPPORTED, "budget_policy 1 (evict the lowest score) is built for decode steps only");
   if (!q || !k || !v || !Wq || !Wk || !out || (!workspace && !static_ws))
     return fail(STILL_ERR_INVALID_ARG, "a required pointer (q, k, v, Wq, Wk, out, workspace) is NULL");
   const void* ptrs[] = {q, k, v, g, Wq, bq, Wk, bk, out, score_out, sel_idx, workspace};
@@ -644,6 +658,9 @@ still_status_t decode_step(const still_params_t* p, void* state, int32_t t, cons
   a.scale = p->scale; a.eps = p->eps;
   a.tpos = t_dev; a.max_tokens = p->max_tokens; a.shared = p->shared_selection != 0;
   a.gate_act = p->gate_activation != 0;
+  a.evict = p->budget_policy == 1;
+  a.ret_score = reinterpret_cast<float*>(sp + L.ret_score);
+  a.ret_tok = reinterpret_cast<int32_t*>(sp + L.ret_tok);
   const int c = t / p->C;
   const int rows = still::retained_rows(c >= 1 ? c - 1 : 0, p->lambda, a.rcap) + (t - (c >= 1 ? c - 1 : 0) * p->C + 1);
   const int units = p->B * (p->shared_selection ? p->Hkv : p->Hq);   // workgroups per split

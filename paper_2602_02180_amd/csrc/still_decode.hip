@@ -153,8 +153,17 @@ __global__ __launch_bounds__(256, 2) void decode_route_kernel(DecArgs a, int cr_
   }
   const int kvh = a.map.kv[hq];
   const int C = a.C, lam = a.lam, R = a.R;
-  const int quota = chunk_quota(cr, lam, a.rcap);   // what the budget on retained tokens leaves this chunk
+  const bool evict = a.evict != 0;                  // the budget is held by evicting the lowest score
+  // what the budget on retained tokens leaves this chunk (under eviction every chunk offers its lam best)
+  const int quota = evict ? lam : chunk_quota(cr, lam, a.rcap);
   const int64_t unit = (int64_t)b * a.Hq + hq;
+  extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
+  __shared__ int s_src[128];   // eviction: retained row whose old content a chunk slot carries into the state (-1: none)
+  __shared__ int s_dst[128];   // eviction: retained row the i-th offer of the chunk moves into (-1: it is not kept)
+  if (tid < 128) {
+    s_src[tid] = -1;
+    s_dst[tid] = -1;
+  }
   const T* kring = static_cast<const T*>(a.kring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)R * D;
   const T* vring = static_cast<const T*>(a.vring) + ((int64_t)b * a.Hkv + kvh) * (int64_t)R * D;
 
@@ -192,7 +201,7 @@ __global__ __launch_bounds__(256, 2) void decode_route_kernel(DecArgs a, int cr_
   if (tid >= quota && tid < lam) a.sel[(unit * a.nchunks + cr) * lam + tid] = -1;
   __syncthreads();
   // selected rows -> retained cache (rows cr*lam ..)
-  if (writes_retained(a.shared != 0, a.map, hq)) {
+  if (!evict && writes_retained(a.shared != 0, a.map, hq)) {
     const int64_t slice = retained_slice(a.shared != 0, b, hq, kvh, a.Hq, a.Hkv);
     T* kret = static_cast<T*>(a.kret) + (slice * a.cap + (int64_t)cr * lam) * D;
     T* vret = static_cast<T*>(a.vret) + (slice * a.cap + (int64_t)cr * lam) * D;
@@ -203,6 +212,89 @@ __global__ __launch_bounds__(256, 2) void decode_route_kernel(DecArgs a, int cr_
       vret[(int64_t)row * D + x] = vring[(int64_t)slot * D + x];
     }
   }
+  // Eviction (a budget policy of this library, not of the paper): the retained rows and the chunk's lam offers are
+  // ranked together, the `over` lowest scores leave (between equal scores the higher token index first).  An offer
+  // that leaves is simply not selected.  A retained row that leaves must enter the state at this step: the offer that
+  // takes over its row lends it its slot among the chunk's tokens (a kept token contributes nothing to the state,
+  // so its slot is free), and the update below reads that slot's key and value from the retained row instead of
+  // the ring.  The offers are copied into their rows only after the update has read the old contents.
+  float* rsc = a.ret_score + unit * a.cap;
+  int32_t* rtk = a.ret_tok + unit * a.cap;
+  if (evict) {
+    unsigned long long* keys = reinterpret_cast<unsigned long long*>(dsm);   // (the update's buffers, not yet in use)
+    __shared__ unsigned long long s_best[4];
+    __shared__ int s_besti[4], s_ev[128], evrow[128];
+    __shared__ unsigned char gone[128];
+    const int M = a.rcap;
+    const int n_old = cr * lam < M ? cr * lam : M;
+    const int total = n_old + quota;
+    const int over = total > M ? total - M : 0;
+    // ascending key order = ascending score, then descending token index
+    auto make_key = [](float sc, int tk) -> unsigned long long {
+      uint32_t u = __float_as_uint(sc);
+      u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+      return ((unsigned long long)u << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)tk);
+    };
+    __syncthreads();                                      // s_list is complete
+    for (int i = tid; i < total; i += 256) {
+      if (i < n_old) {
+        keys[i] = make_key(rsc[i], rtk[i]);
+      } else {
+        const int pos = s_list[i - n_old];
+        keys[i] = make_key(s_sc[pos], cr * C + pos);
+      }
+    }
+    __syncthreads();
+    for (int it = 0; it < over; ++it) {
+      unsigned long long best = ~0ull;
+      int bi = -1;
+      for (int i = tid; i < total; i += 256) {
+        const unsigned long long kk = keys[i];
+        if (kk < best) best = kk, bi = i;
+      }
+      for (int off = 32; off > 0; off >>= 1) {
+        const unsigned long long ob = __shfl_xor(best, off);
+        const int oi = __shfl_xor(bi, off);
+        if (ob < best) best = ob, bi = oi;
+      }
+      if ((tid & 63) == 0) s_best[tid >> 6] = best, s_besti[tid >> 6] = bi;
+      __syncthreads();
+      if (tid == 0) {
+        int w = 0;
+        for (int j = 1; j < 4; ++j)
+          if (s_best[j] < s_best[w]) w = j;
+        s_ev[it] = s_besti[w];
+        keys[s_besti[w]] = ~0ull;
+      }
+      __syncthreads();
+    }
+    if (tid == 0) {
+      // which retained rows leave, which offers leave at once; then a row for every offer that stays: the free
+      // rows first, then the rows that were just vacated
+      int nev = 0;
+      for (int i = 0; i < quota; ++i) gone[i] = 0;
+      for (int it = 0; it < over; ++it) {
+        const int idx = s_ev[it];
+        if (idx < n_old) evrow[nev++] = idx;
+        else gone[idx - n_old] = 1;
+      }
+      int free_row = n_old, e = 0;
+      for (int i = 0; i < quota; ++i) {
+        const int pos = s_list[i];
+        if (gone[i]) {
+          s_flag[pos] = 0;                                // joins the chunk's other tokens on their way to the state
+        } else {
+          const int row = free_row < M ? free_row++ : evrow[e++];
+          s_dst[i] = row;
+          if (row < n_old) s_src[pos] = row;              // this slot carries the row's old content into the state
+        }
+      }
+    }
+    __syncthreads();
+  }
+  const T* kret_u = static_cast<const T*>(a.kret) + unit * (int64_t)a.cap * D;   // (one slice per unit: not shared)
+  const T* vret_u = static_cast<const T*>(a.vret) + unit * (int64_t)a.cap * D;
+
   // The others -> (S, z), on the matrix core, in parts of PT tokens (PT = 128 two-byte or 64 four-byte tokens, at
   // most the chunk).  LDS holds, per part, the feature image phi^T [2 d_f][PT] and V^T [d][PT] in the storage type
   // (rows padded by 16 bytes), both read as 16-byte operand fragments; at d = 128 the image is built and
@@ -223,7 +315,6 @@ __global__ __launch_bounds__(256, 2) void decode_route_kernel(DecArgs a, int cr_
   constexpr int NH = D == 128 ? 2 : 1;                        // the image is built and contracted in NH pieces of HR rows
   constexpr int HR = DP / NH;                                 //   (d = 128: the positive half, then the negative half)
   static_assert(HR == 128, "a piece is one 32-row tile per wave");
-  extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
   const int PT = C < PTMAX ? C : PTMAX, nparts = C / PT;
   const int IST = PT + PADE;                                  // image and V^T row stride
   T* wt = reinterpret_cast<T*>(dsm);
@@ -253,8 +344,8 @@ __global__ __launch_bounds__(256, 2) void decode_route_kernel(DecArgs a, int cr_
   float a1 = 0.f, bp = 0.f, bn = 0.f, isp = 0.f, isn = 0.f;
   typename M::frag xb[KS];
   if (has_tok) {
-    const int slot = (cr * C + tok) % R;
-    const T* xp = kring + (int64_t)slot * D + g * M::KPL;
+    const int slot = (cr * C + tok) % R, src = s_src[tok];
+    const T* xp = (src >= 0 ? kret_u + (int64_t)src * D : kring + (int64_t)slot * D) + g * M::KPL;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) xb[ks] = M::load(xp + ks * M::KK);
   }
@@ -318,7 +409,7 @@ __global__ __launch_bounds__(256, 2) void decode_route_kernel(DecArgs a, int cr_
       }
     isp = 1.0f / sum32(sp);
     isn = 1.0f / sum32(sn);
-    if (s_flag[tok]) isp = 0.f, isn = 0.f;                     // kept by the softmax branch: contributes nothing
+    if (s_flag[tok] && s_src[tok] < 0) isp = 0.f, isn = 0.f;   // kept by the softmax branch: contributes nothing
   }
 
   if (NH == 2) load_piece(NH - 1);   // (after the projection's registers are free; arrives under the first piece)
@@ -343,8 +434,9 @@ __global__ __launch_bounds__(256, 2) void decode_route_kernel(DecArgs a, int cr_
       if (h == 0) {
         for (int idx = tid; idx < PT * D / EPV; idx += 256) {
           const int tl = idx % PT, x0 = (idx / PT) * EPV;
-          const int slot = (cr * C + part * PT + tl) % R;
-          const Vec16 v16 = *reinterpret_cast<const Vec16*>(vring + (int64_t)slot * D + x0);
+          const int slot = (cr * C + part * PT + tl) % R, src = s_src[part * PT + tl];
+          const Vec16 v16 = *reinterpret_cast<const Vec16*>(
+              (src >= 0 ? vret_u + (int64_t)src * D : vring + (int64_t)slot * D) + x0);
           const T* ve = reinterpret_cast<const T*>(&v16);
 #pragma unroll
           for (int e = 0; e < EPV; ++e) vtl[(x0 + e) * IST + tl] = ve[e];
@@ -382,6 +474,26 @@ __global__ __launch_bounds__(256, 2) void decode_route_kernel(DecArgs a, int cr_
 #pragma unroll
   for (int h = 0; h < NH; ++h)
     if (tid < HR) Sg[DP * D + h * HR + tid] = zf[h];
+  if (evict) {
+    // the offers that stay move into their rows, now that the old contents have been read (the last reads of the
+    // retained rows were the V rows of the last part, before the barrier that preceded its products)
+    T* kret_w = static_cast<T*>(a.kret) + unit * (int64_t)a.cap * D;
+    T* vret_w = static_cast<T*>(a.vret) + unit * (int64_t)a.cap * D;
+    for (int idx = tid; idx < quota * (D / EPV); idx += 256) {
+      const int i = idx / (D / EPV), x0 = (idx % (D / EPV)) * EPV;
+      const int row = s_dst[i];
+      if (row < 0) continue;
+      const int slot = (cr * C + s_list[i]) % R;
+      *reinterpret_cast<Vec16*>(kret_w + (int64_t)row * D + x0) =
+          *reinterpret_cast<const Vec16*>(kring + (int64_t)slot * D + x0);
+      *reinterpret_cast<Vec16*>(vret_w + (int64_t)row * D + x0) =
+          *reinterpret_cast<const Vec16*>(vring + (int64_t)slot * D + x0);
+    }
+    if (tid < quota && s_dst[tid] >= 0) {
+      rsc[s_dst[tid]] = s_sc[s_list[tid]];
+      rtk[s_dst[tid]] = cr * C + s_list[tid];
+    }
+  }
 }
 
 // LDS of the routing kernel: one image piece (128 rows) + V^T of one part, or W_k^T (whichever is larger)

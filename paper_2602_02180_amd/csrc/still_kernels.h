@@ -29,6 +29,7 @@ __host__ __device__ inline int retained_rows(int chunks, int lam, int rcap) {
   return r < rcap ? r : rcap;
 }
 constexpr int kNoBudget = 1 << 30;
+constexpr int kMaxEvictBudget = 8192;   // the routing step ranks the retained rows in LDS (8 bytes each)
 
 // Tokens of sequence b: N for every sequence, or, for a right-padded batch, the caller's per-sequence count
 // (device array, clamped to [1, N]).  Rows at and beyond it are padding: never read as keys or values by a real
@@ -180,6 +181,9 @@ struct DecArgs {
   int B, Hq, Hkv, C, W, lam, cap, R, nchunks, t, nsplit, rcap;
   int shared;              // 1: the query heads of one kv head rank by their summed score (one list per group)
   int gate_act;            // 1: g is a pre-activation, the gate is its logistic function
+  int evict;               // 1: the budget is held by evicting the lowest score (ret_score, ret_tok are then kept)
+  float* ret_score;        // [B, Hq, cap] score of every retained row
+  int32_t* ret_tok;        // [B, Hq, cap] its token index
   const int32_t* tpos;     // nullable, device [B]: index of each sequence's new token (t is then ignored)
   int max_tokens;
   float scale, eps;

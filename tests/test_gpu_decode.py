@@ -16,7 +16,7 @@ from tests import gpu_util as U
 pytestmark = pytest.mark.gpu
 
 
-def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False, gate_activation=0):
+def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False, gate_activation=0, budget_policy=0):
     """Prefill tokens [0, n_prefill) with state_out (or start from an empty state), then decode up to n_total."""
     import torch
 
@@ -29,7 +29,7 @@ def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False, gate_ac
     out = torch.full((B, n_total, w.Hq, w.d), float("nan"), dtype=full["q"].dtype, device=dev)
     base = dict(B=B, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype=w.dtype,
                 d_f=w.df, kv_head_of_q=kv_map, max_tokens=n_total, max_retained=w.max_retained, shared_selection=w.shared_selection,
-                gate_activation=gate_activation)
+                gate_activation=gate_activation, budget_policy=budget_policy)
     ps = S.make_params(N=1, **base)
     state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
     S.still_state_init(ps, state)
@@ -97,10 +97,13 @@ def run_decode_staggered(w, inp, n_total, offsets, tight_bound=True):
     return synth.from_torch(out), sel
 
 
-def check_decode(w, inp, n_prefill, n_total, with_gate=False, result=None, gate_activation=0):
+def check_decode(w, inp, n_prefill, n_total, with_gate=False, result=None, gate_activation=0, budget_policy=0):
     got, sel_h = result if result is not None else run_decode(w, inp, n_prefill, n_total, with_gate=with_gate,
-                                                              gate_activation=gate_activation)
+                                                              gate_activation=gate_activation,
+                                                              budget_policy=budget_policy)
     act = "sigmoid" if gate_activation else "none"
+    policy = "evict" if budget_policy else "stop"
+    offer_budget = None if budget_policy else U.budget(w)      # under eviction every chunk offers its full Top-lambda
     kv_map = synth.kv_head_map(w)
     sub = {k: (v[:, :n_total] if k in ("q", "k", "v", "g") else v) for k, v in inp.items() if k != "heavy"}
     if not with_gate:
@@ -109,21 +112,26 @@ def check_decode(w, inp, n_prefill, n_total, with_gate=False, result=None, gate_
     for b in range(w.B):
         for h in range(w.Hq):
             own = O.still_forward_units(sub, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                                        max_retained=U.budget(w), shared_selection=w.shared_selection)[(b, h)]
+                                        max_retained=U.budget(w), shared_selection=w.shared_selection,
+                                        budget_policy=policy)[(b, h)]
             n_routed = sel_h.shape[2]
             ncf = n_total // w.C
             sel_full = own["sel"].copy()
             # routed chunks: the HIP path's choice must be the oracle's wherever the gap is clear
-            gaps = O.selection_gaps(own["rank_score"], w.C, w.lam, U.budget(w))
+            gaps = O.selection_gaps(own["rank_score"], w.C, w.lam, offer_budget)
+            if budget_policy:      # the case must be well-posed: no eviction decided by less than the score tolerance
+                margins = O.eviction_margins(own["rank_score"], own["sel"], w.max_retained)[:n_routed]
+                assert margins.min() > 1e-5, f"ill-posed eviction case (margin {margins.min():.2e}): pick another seed"
             for c in range(n_routed):
                 if gaps[c] > 1e-5:
                     assert np.array_equal(sel_h[b, h, c], own["sel"][c]), (b, h, c)
-                quota = O.chunk_quota(c, w.lam, U.budget(w))
+                quota = O.chunk_quota(c, w.lam, offer_budget)
                 assert np.all(sel_h[b, h, c][:quota] >= 0) and np.all(sel_h[b, h, c][quota:] == -1), (b, h, c)
                 sel_full[c] = sel_h[b, h, c]
             ref = O.still_forward_units(sub, kv_map, [(b, h)], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
                                         sel=sel_full[None, None].repeat(w.B, 0).repeat(w.Hq, 1),
-                                        gate_activation=act)[(b, h)]
+                                        gate_activation=act, budget_policy=policy,
+                                        max_retained=U.budget(w) if budget_policy else None)[(b, h)]
             x = got[b, n_prefill:n_total, h].astype(np.float64)
             y = ref["out"][n_prefill:n_total]
             assert np.all(np.isfinite(x))
@@ -211,6 +219,20 @@ def test_decode_with_feature_map_biases(kw, n_prefill, n_total):
     inp["bq"] = synth.round_to_dtype(rng.standard_normal((w.Hq, w.df)) * 0.1, w.dtype)
     inp["bk"] = synth.round_to_dtype(rng.standard_normal((w.Hq, w.df)) * 0.1, w.dtype)
     check_decode(w, inp, n_prefill, n_total)
+
+
+@pytest.mark.parametrize("kw,n_total", [
+    (dict(dtype="f32", d=64, C=64, W=64, lam=16, max_retained=40), 700),          # fills at chunk 2, then evicts
+    (dict(dtype="f32", d=64, C=64, W=48, lam=16, max_retained=5), 400),           # budget below one chunk's offer
+    (dict(dtype="bf16", d=128, C=128, W=128, lam=16, max_retained=24, Hq=4, Hkv=2, B=2), 1300),
+    (dict(dtype="f32", d=128, C=64, W=64, lam=8, max_retained=16), 600),
+])
+def test_decode_with_eviction_policy(kw, n_total):
+    """Budget policy 1 (a variant of this library): the retained rows are the best-scored offers so far, a row that
+    leaves enters the state at that routing step; decode from an empty state against the oracle's same policy."""
+    w = wl("decev", **kw)
+    inp = synth.make_inputs(w, seed=29, n_tokens=n_total)
+    check_decode(w, inp, 0, n_total, budget_policy=1)
 
 
 def test_decode_with_gate():

@@ -481,6 +481,8 @@ def test_evict_policy_retained_sets_literals():
     kept, out = O.retained_sets_evict(score, sel, 3)
     assert [x.tolist() for x in kept] == [[0, 2], [0, 4, 5], [0, 4, 5], [0, 4, 5]]
     assert [x.tolist() for x in out] == [[], [2], [8, 9], [12, 13]]
+    # margins: step 1 keeps {5, 9, 8}, releases 4 -> 5 - 4 = 1; step 2: 5 - 2 = 3; step 3: a tie, margin 0
+    assert O.eviction_margins(score, sel, 3).tolist() == [np.inf, 1.0, 3.0, 0.0]
     kept1, out1 = O.retained_sets_evict(score, sel, 1)
     assert [x.tolist() for x in kept1] == [[0], [4], [4], [4]]
     assert [x.tolist() for x in out1] == [[2], [0, 5], [8, 9], [12, 13]]
