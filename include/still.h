@@ -94,8 +94,9 @@ typedef struct still_params {
                                     (between equal scores the higher token index first), and a removed token,
                                     retained earlier or just offered, enters the linear state (through the
                                     NP-Map) at that routing step, so that every past token is still seen exactly
-                                    once.  sel lists then hold the chunk's offers.  Decode steps only (a state
-                                    from still_state_init); the prefill and shared_selection refuse it.        */
+                                    once.  sel lists then hold the chunk's offers (cap of the workspace layout
+                                    counts all offers).  Prefill and decode; shared_selection, injected indices
+                                    (sel_idx_is_input) and the allocation-free entry point refuse it.          */
   int64_t q_sb, q_st, q_sh;      /* q   [B, N, Hq,  d]                                                     */
   int64_t k_sb, k_st, k_sh;      /* k   [B, N, Hkv, d]                                                     */
   int64_t v_sb, v_st, v_sh;      /* v   [B, N, Hkv, d]                                                     */
@@ -131,6 +132,11 @@ typedef struct still_ws_layout {
   size_t n_la;     /* float   [B, Hq, N, d]                      gated linear-branch numerator N_LA (emit_terms) */
   size_t d_la;     /* float   [B, Hq, N]                         linear-branch normaliser D_LA (emit_terms) */
   size_t vfr;      /* dtype   [B, Hkv, Npad * d]                 v in the operand order of the state update */
+  size_t ev_src;   /* int32   [B, Hq, N]          budget_policy 1: token whose key/value a position carries into the state */
+  size_t ev_alive; /* uint64  [B, Hq, ceil(N/C), cap/64]  budget_policy 1: per row chunk, which offers are retained */
+  size_t ev_fin;   /* budget_policy 1: the set retained after the last routed step: int32 tok [B,Hq,M], float score
+                      [B,Hq,M], int32 count [B,Hq]                                                           */
+  size_t ev_vfr;   /* dtype   [B, Hq, Npad * d]   budget_policy 1: v in operand order per query head, through ev_src */
   size_t total;    /* bytes needed                                                                         */
   int32_t n_pad;   /* Npad                                                                                 */
   int32_t cap;     /* retained-row capacity (multiple of 64)                                               */

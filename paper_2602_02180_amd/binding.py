@@ -38,7 +38,7 @@ class StillParams(ct.Structure):
 
 class StillWsLayout(ct.Structure):
     _fields_ = [(n, ct.c_size_t) for n in
-                ("score", "sel", "vt", "kret", "vrett", "wqt", "wkf", "seg", "snap", "zsnap", "pimg", "zpre", "kmask", "n_la", "d_la", "vfr", "total")] + \
+                ("score", "sel", "vt", "kret", "vrett", "wqt", "wkf", "seg", "snap", "zsnap", "pimg", "zpre", "kmask", "n_la", "d_la", "vfr", "ev_src", "ev_alive", "ev_fin", "ev_vfr", "total")] + \
                [(n, ct.c_int32) for n in ("n_pad", "cap", "nseg", "seg_chunks")]
 
 

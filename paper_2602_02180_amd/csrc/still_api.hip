@@ -188,7 +188,8 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   const int64_t B = p->B, N = p->N, Hq = p->Hq, Hkv = p->Hkv, d = p->d, df = p->d_f;
   const int64_t nc = (N + p->C - 1) / p->C, ncf = N / p->C;
   const int64_t npad = (N + 127) / 128 * 128;
-  const int64_t cap = ((int64_t)still::retained_rows((int)ncf, p->lambda, retained_budget(p)) + 63) / 64 * 64;
+  const bool evict = p->budget_policy == 1;   // then the retained rows of the workspace are ALL offers, under masks
+  const int64_t cap = ((int64_t)still::retained_rows((int)ncf, p->lambda, evict ? still::kNoBudget : retained_budget(p)) + 63) / 64 * 64;
   int64_t G = (nc * B * Hq + 255) / 256;   // one workgroup per CU at the size of the chip
   if (G < 2) G = 2;
   if (G > nc) G = nc;
@@ -218,6 +219,11 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   L->n_la = take(p->emit_terms ? (size_t)B * Hq * N * d * 4 : 0);
   L->d_la = take(p->emit_terms ? (size_t)B * Hq * N * 4 : 0);
   L->vfr = take((size_t)B * Hkv * d * npad * es);
+  const size_t M = evict ? (size_t)p->max_retained : 0;
+  L->ev_src = take(evict ? (size_t)B * Hq * N * 4 : 0);
+  L->ev_alive = take(evict ? (size_t)B * Hq * nc * (cap / 64) * 8 : 0);
+  L->ev_fin = take(evict ? (size_t)B * Hq * (2 * M + 1) * 4 : 0);
+  L->ev_vfr = take(evict ? (size_t)B * Hq * d * npad * es : 0);
   L->total = off;
   L->n_pad = (int32_t)npad;
   L->cap = (int32_t)cap;
@@ -328,8 +334,14 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   if (st != STILL_OK) return st;
   st = validate_strides(p, g != nullptr);
   if (st != STILL_OK) return st;
-  if (p->budget_policy != 0)
-    return fail(STILL_ERR_UNSUPPORTED, "budget_policy 1 (evict the lowest score) is built for decode steps only");
+  if (p->budget_policy != 0) {
+    if (sel_idx_is_input || static_ws)
+      return fail(STILL_ERR_UNSUPPORTED, "budget_policy 1 with injected indices or the built-in scratch array");
+    const int64_t offers = (int64_t)(p->N / p->C) * p->lambda;
+    if (offers > still::kMaxEvictOffers)
+      return fail(STILL_ERR_UNSUPPORTED, "budget_policy 1: %lld offers per head > %d", (long long)offers,
+                  still::kMaxEvictOffers);
+  }
   if (!q || !k || !v || !Wq || !Wk || !out || (!workspace && !static_ws))
     return fail(STILL_ERR_INVALID_ARG, "a required pointer (q, k, v, Wq, Wk, out, workspace) is NULL");
   const void* ptrs[] = {q, k, v, g, Wq, bq, Wk, bk, out, score_out, sel_idx, workspace};
@@ -403,7 +415,10 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
     return fail(STILL_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
   };
   prof_begin(0, s2);
-  still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, ws + L.vfr, N, L.n_pad, p->Hkv, d, C, p->seq_len};
+  const bool evict = p->budget_policy == 1;
+  const int budget = evict ? still::kNoBudget : retained_budget(p);   // under eviction every chunk offers its lam best
+  still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, evict ? nullptr : ws + L.vfr, N, L.n_pad, p->Hkv, d,
+                           C, p->seq_len};
   if ((e = still::launch_transpose_v(tv, p->dtype, B, s2)) != hipSuccess)
     return hip_fail("transpose_v", e);
   prof_end(0, s2);
@@ -422,7 +437,7 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   sa.q_sb = p->q_sb; sa.q_st = p->q_st; sa.q_sh = p->q_sh;
   sa.k_sb = p->k_sb; sa.k_st = p->k_st; sa.k_sh = p->k_sh;
   sa.map = map;
-  sa.N = N; sa.C = C; sa.W = p->W; sa.lam = p->lambda; sa.Hq = p->Hq; sa.ncf = ncf; sa.rcap = retained_budget(p);
+  sa.N = N; sa.C = C; sa.W = p->W; sa.lam = p->lambda; sa.Hq = p->Hq; sa.ncf = ncf; sa.rcap = budget;
   sa.scale = p->scale; sa.eps = p->eps;
   sa.score = score;
   const bool group_sel = p->shared_selection != 0;
@@ -451,9 +466,9 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   ga.v_sb = p->v_sb; ga.v_st = p->v_st; ga.v_sh = p->v_sh;
   ga.map = map;
   ga.sel = sel;
-  ga.nsel = have_sel ? still::retained_rows(ncf, p->lambda, retained_budget(p)) : 0;
+  ga.nsel = have_sel ? still::retained_rows(ncf, p->lambda, budget) : 0;
   ga.sel_stride = ncf * p->lambda;
-  ga.C = C; ga.lam = p->lambda; ga.rcap = retained_budget(p); ga.seq_len = p->seq_len;
+  ga.C = C; ga.lam = p->lambda; ga.rcap = budget; ga.seq_len = p->seq_len;
   ga.cap = L.cap; ga.Hq = p->Hq; ga.d = d; ga.N = N;
   ga.kret = ws + L.kret; ga.vrett = ws + L.vrett;
   if ((e = still::launch_gather(ga, p->dtype, B, stream)) != hipSuccess)
@@ -482,10 +497,33 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   if (state_out != nullptr) compute_state_layout(p, &SL);
   la.s_final = state_out != nullptr ? reinterpret_cast<float*>(stp + SL.S) : nullptr;
   prof_begin(4, stream);
-  still::KeepMaskArgs km{sel, reinterpret_cast<uint32_t*>(ws + L.kmask), p->Hq, ncf, C, have_sel ? p->lambda : 0,
-                         retained_budget(p)};
-  if ((e = still::launch_keep_mask(km, B, stream)) != hipSuccess)
-    return hip_fail("keep_mask", e);
+  const bool plan = evict && have_sel;
+  int32_t* fin_tok = reinterpret_cast<int32_t*>(ws + L.ev_fin);
+  float* fin_score = reinterpret_cast<float*>(ws + L.ev_fin) + (size_t)B * p->Hq * (plan ? p->max_retained : 0);
+  int32_t* fin_n = fin_tok + (size_t)2 * B * p->Hq * (plan ? p->max_retained : 0);
+  if (plan) {
+    // which offers are retained for which rows, and which token every position carries into the state scan
+    still::EvictPlanArgs ep{};
+    ep.score = score; ep.sel = sel;
+    ep.src = reinterpret_cast<int32_t*>(ws + L.ev_src); ep.alive = ws + L.ev_alive;
+    ep.fin_tok = fin_tok; ep.fin_score = fin_score; ep.fin_n = fin_n;
+    ep.seq_len = p->seq_len;
+    ep.N = N; ep.C = C; ep.lam = p->lambda; ep.M = p->max_retained; ep.Hq = p->Hq; ep.ncf_all = ncf; ep.nc_all = nc;
+    ep.AW = L.cap / 64;
+    if ((e = still::launch_evict_plan(ep, B, stream)) != hipSuccess) return hip_fail("evict_plan", e);
+    still::VfrGatherArgs vg{};
+    vg.v = v; vg.v_sb = p->v_sb; vg.v_st = p->v_st; vg.v_sh = p->v_sh;
+    vg.src = ep.src; vg.vfr = ws + L.ev_vfr; vg.map = map; vg.seq_len = p->seq_len;
+    vg.N = N; vg.Np = L.n_pad; vg.Hq = p->Hq; vg.d = d; vg.C = C;
+    if ((e = still::launch_vfr_gather(vg, p->dtype, B, stream)) != hipSuccess) return hip_fail("vfr_gather", e);
+    la.src = ep.src;
+    la.vfr = ws + L.ev_vfr;
+  } else {   // (also budget_policy 1 with lambda = 0 or without a full chunk: nothing is ever offered)
+    still::KeepMaskArgs km{sel, reinterpret_cast<uint32_t*>(ws + L.kmask), p->Hq, ncf, C, have_sel ? p->lambda : 0,
+                           retained_budget(p)};
+    if ((e = still::launch_keep_mask(km, B, stream)) != hipSuccess)
+      return hip_fail("keep_mask", e);
+  }
   prof_end(4, stream);
   prof_begin(5, stream);
   if ((e = still::launch_la_states(la, p->dtype, d, B, stream)) != hipSuccess)
@@ -512,7 +550,11 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   sx.out = out; sx.o_sb = p->o_sb; sx.o_st = p->o_st; sx.o_sh = p->o_sh;
   sx.map = map;
   sx.N = N; sx.Np = L.n_pad; sx.C = C; sx.lam = have_sel ? p->lambda : 0; sx.Hq = p->Hq; sx.Hkv = p->Hkv;
-  sx.rcap = retained_budget(p); sx.seq_len = p->seq_len;
+  sx.rcap = budget; sx.seq_len = p->seq_len;
+  if (plan) {
+    sx.alive = ws + L.ev_alive;
+    sx.AW = L.cap / 64;
+  }
   sx.cap = L.cap; sx.ntiles = (N + still::kSaRows - 1) / still::kSaRows; sx.B_ = B;
   sx.scale = p->scale;
   if ((e = still::launch_sa(sx, p->dtype, d, B, stream)) != hipSuccess)
@@ -531,11 +573,25 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
     sf.kring = stp + SL.kring; sf.vring = stp + SL.vring;
     sf.score_ring = reinterpret_cast<float*>(stp + SL.score);
     sf.N = N; sf.R = SL.R; sf.Hq = p->Hq; sf.Hkv = p->Hkv; sf.d = d; sf.lam = have_sel ? p->lambda : 0;
-    sf.cap = SL.cap; sf.ncf = ncf; sf.nchunks = SL.n_chunks; sf.rcap = retained_budget(p);
+    sf.cap = SL.cap; sf.ncf = ncf; sf.nchunks = SL.n_chunks; sf.rcap = budget;
     sf.shared = p->shared_selection != 0; sf.C = C; sf.seq_len = p->seq_len;
+    sf.lists_only = plan;      // under eviction the lists are the offers and the rows come from the plan's last set
     const int n_routed = nc >= 2 ? nc - 2 : 0;
     if ((e = still::launch_state_fill(sf, p->dtype, B, n_routed, stream)) != hipSuccess)
       return hip_fail("state_fill", e);
+    if (plan) {
+      still::StateFillEvictArgs fe{};
+      fe.k = k; fe.v = v;
+      fe.k_sb = p->k_sb; fe.k_st = p->k_st; fe.k_sh = p->k_sh;
+      fe.v_sb = p->v_sb; fe.v_st = p->v_st; fe.v_sh = p->v_sh;
+      fe.fin_tok = fin_tok; fe.fin_score = fin_score; fe.fin_n = fin_n;
+      fe.kret = stp + SL.kret; fe.vret = stp + SL.vret;
+      fe.ret_score = reinterpret_cast<float*>(stp + SL.ret_score);
+      fe.ret_tok = reinterpret_cast<int32_t*>(stp + SL.ret_tok);
+      fe.map = map; fe.M = p->max_retained; fe.cap = SL.cap; fe.Hq = p->Hq; fe.d = d;
+      if ((e = still::launch_state_fill_evict(fe, p->dtype, B, stream)) != hipSuccess)
+        return hip_fail("state_fill_evict", e);
+    }
   }
   g_err[0] = 0;
   return STILL_OK;

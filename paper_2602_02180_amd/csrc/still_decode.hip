@@ -863,7 +863,7 @@ __global__ void state_fill_retained_kernel(StateFillArgs a) {
   int tok = a.sel[(unit * a.ncf + cr) * a.lam + pos];
   const bool used = pos < chunk_quota(cr, a.lam, a.rcap);   // the budget on retained tokens leaves later slots empty
   if (threadIdx.x == 0) a.sel_state[(unit * a.nchunks + cr) * a.lam + pos] = used ? tok : -1;
-  if (!used || !writes_retained(a.shared != 0, a.map, hq)) return;
+  if (!used || a.lists_only || !writes_retained(a.shared != 0, a.map, hq)) return;
   if (tok < 0 || tok >= a.N) tok = 0;
   const T* k = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)tok * a.k_st + (int64_t)kvh * a.k_sh;
   const T* v = static_cast<const T*>(a.v) + (int64_t)b * a.v_sb + (int64_t)tok * a.v_st + (int64_t)kvh * a.v_sh;

@@ -127,7 +127,47 @@ struct LaArgs {
   void* pimg;          // [B, Hq, nseg][D][DP] storage type: S^T through the chunk before the segment (prefix)
   float* zpre;         // [B, Hq, nseg][DP]: z likewise
   float* s_final;      // nullable [B, Hq, DP*(D+1)] as S [feature][x] then z: fp32 state through chunk (last - 2)
+  const int32_t* src;  // evict policy only [B, Hq, N]: token carried by every position (-1: none); replaces kmask, and
+                       //   vfr is then per QUERY head ([B, Hq, Np * d], built through the same table)
 };
+
+// Budget policy "evict the lowest score" in the prefill (still_evict.hip)
+struct EvictPlanArgs {
+  const float* score;      // [B, Hq, N]
+  const int32_t* sel;      // [B, Hq, ncf_all, lam]: every chunk's offers (its lam highest scores)
+  int32_t* src;            // [B, Hq, N]: token whose key/value a position carries into the state scan (-1: none)
+  void* alive;             // [B, Hq, nc_all, AW] 64-bit words: bit j = offer j (routing order) is retained for the rows
+                           //   of that chunk
+  int32_t* fin_tok;        // nullable [B, Hq, M]: the set retained after the last routed step (decode hand-over)
+  float* fin_score;        // [B, Hq, M]
+  int32_t* fin_n;          // [B, Hq]
+  const int32_t* seq_len;  // nullable, device [B]
+  int N, C, lam, M, Hq, ncf_all, nc_all, AW;
+};
+struct VfrGatherArgs {
+  const void* v;
+  int64_t v_sb, v_st, v_sh;
+  const int32_t* src;      // [B, Hq, N]
+  void* vfr;               // [B, Hq, Np * d]
+  HeadMap map;
+  const int32_t* seq_len;
+  int N, Np, Hq, d, C;
+};
+struct StateFillEvictArgs {
+  const void* k;
+  const void* v;
+  int64_t k_sb, k_st, k_sh, v_sb, v_st, v_sh;
+  const int32_t* fin_tok;
+  const float* fin_score;
+  const int32_t* fin_n;
+  void* kret;
+  void* vret;
+  float* ret_score;
+  int32_t* ret_tok;
+  HeadMap map;
+  int M, cap, Hq, d;
+};
+constexpr int kMaxEvictOffers = 32768;   // offers per (sequence, head) the sparse kernel's LDS mask rows hold (x 2 chunks)
 
 // query rows per workgroup of the sparse-attention kernel (one wave per 32 rows)
 constexpr int kSaRows = 128;
@@ -157,6 +197,8 @@ struct SaArgs {
   int N, Np, C, lam, Hq, Hkv, cap, ntiles, B_, rcap, nc;
   const int32_t* seq_len;   // nullable, device [B]
   float scale;
+  const void* alive;   // evict policy only [B, Hq, nc, AW] 64-bit words: see EvictPlanArgs (the retained tiles are then
+  int AW;              //   all offers, each under its chunk's mask; AW = words per row = cap / 64)
 };
 
 struct DecArgs {
@@ -223,6 +265,7 @@ struct StateFillArgs {
   void* vring;
   float* score_ring;
   int N, R, Hq, Hkv, d, lam, cap, ncf, nchunks, rcap, shared, C;
+  int lists_only;           // 1: write the index lists of the routed chunks but no retained rows (evict policy)
   const int32_t* seq_len;   // nullable, device [B]
 };
 
@@ -241,5 +284,9 @@ hipError_t launch_keep_mask(const KeepMaskArgs& a, int B, hipStream_t stream);
 hipError_t launch_la_states(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
 hipError_t launch_la_prefix(const LaArgs& a, int dtype, int d, int B, hipStream_t stream);
 hipError_t launch_sa(const SaArgs& a, int dtype, int d, int B, hipStream_t stream);
+hipError_t launch_evict_plan(const EvictPlanArgs& a, int B, hipStream_t stream);
+hipError_t launch_vfr_gather(const VfrGatherArgs& a, int dtype, int B, hipStream_t stream);
+hipError_t launch_state_fill_evict(const StateFillEvictArgs& a, int dtype, int B, hipStream_t stream);
+size_t evict_plan_smem(int M, int lam, int AW);
 
 }  // namespace still

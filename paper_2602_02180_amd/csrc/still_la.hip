@@ -68,7 +68,9 @@ struct LaCfg {
 
 __device__ __forceinline__ int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
 
-template <typename T, int D, int C>
+// SUB: the budget policy that evicts (still_evict.hip): every token position carries the key and value of the token
+// a.src names (-1: nothing), and the operand-order copy of v is per query head.
+template <typename T, int D, int C, bool SUB>
 __device__ __forceinline__ void la_body(const LaArgs& a) {
   typedef Mma<T> M;
   typedef LaCfg<T, D, C> L;
@@ -114,10 +116,15 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 
     typename M::frag xb[KS];                     // the tile's token rows (B operand of f^T = W^T x^T)
     uint32_t kw;                                 // bit r: token r of the tile is kept by the softmax branch
+    int carried = 0;                             // (SUB) the token this lane's position carries, -1: none
     auto load_x = [&](int tokw) __attribute__((always_inline)) {
       int tok = tokw + r;
       tok = tok < N ? tok : N - 1;
       tok = tok < 0 ? 0 : tok;
+      if constexpr (SUB) {
+        carried = a.src[unit * a.N + tok];
+        tok = carried >= 0 ? carried : tok;
+      }
       const T* xp = kbase + (int64_t)tok * a.k_st + g * M::KPL;
 #pragma unroll
       for (int s = 0; s < KS; ++s) xb[s] = M::load(xp + s * M::KK);
@@ -127,7 +134,8 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
     auto load_keep = [&](int tokw) __attribute__((always_inline)) {
       const int cc = floor_div(tokw, C);
       const bool valid = cc >= 0 && cc < ncf_b;          // only full chunks are ever routed
-      kw = valid ? a.kmask[(unit * a.ncf + cc) * (C / 32) + (tokw - cc * C) / 32] : 0xffffffffu;
+      if constexpr (SUB) kw = valid ? 0u : 0xffffffffu;  // (which positions carry nothing comes with the rows)
+      else kw = valid ? a.kmask[(unit * a.ncf + cc) * (C / 32) + (tokw - cc * C) / 32] : 0xffffffffu;
     };
     const T* wsrc = L::W_LDS ? wl : wkf;
     // f^T (features x tokens) = W^T x^T, all features of the tile's 32 tokens, and ||x||^2.  The W^T fragments are
@@ -159,7 +167,7 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 #pragma unroll 1
     for (int it = 0; it < R; ++it) {
       const int tokw = seg_tok0 + it * RT + 32 * v;      // first token of this wave's tile
-      const bool live = ((kw >> r) & 1u) == 0u;
+      const bool live = ((kw >> r) & 1u) == 0u && (!SUB || carried >= 0);
       project();
       if (it + 1 < R) {               // the rows are dead now: request the next round's
         load_x(tokw + RT);
@@ -268,7 +276,8 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
   for (int ft = 0; ft < PT; ++ft) S[ft] = zero16();
   z = 0.f;
 
-  const T* __restrict__ vfr = static_cast<const T*>(a.vfr) + ((int64_t)b * a.Hkv + kvh) * (int64_t)D * a.Np;
+  const T* __restrict__ vfr = static_cast<const T*>(a.vfr) +
+                              (SUB ? (int64_t)b * a.Hq + hq : (int64_t)b * a.Hkv + kvh) * (int64_t)D * a.Np;
   typedef typename M::frag VFrag[HS];            // V fragments of one part (B operand, k = tokens)
   const int NP = R * NPART;                      // parts of the segment
   auto load_v = [&](int gp, VFrag& vf) __attribute__((always_inline)) {
@@ -384,9 +393,9 @@ __device__ __forceinline__ void la_body(const LaArgs& a) {
 }
 
 // (the body lives in a __device__ function behind a thin __global__ wrapper)
-template <typename T, int D, int C>
+template <typename T, int D, int C, bool SUB>
 __global__ __launch_bounds__((LaCfg<T, D, C>::NCW + LaCfg<T, D, C>::NPW) * 64) void la_kernel(LaArgs a) {
-  la_body<T, D, C>(a);
+  la_body<T, D, C, SUB>(a);
 }
 
 // Exclusive prefix over the segments of one (batch, head), elementwise over the state as [x][feature] (+ z):
@@ -421,7 +430,7 @@ __global__ __launch_bounds__(256) void la_prefix_kernel(LaArgs a, int D) {
 template <typename T, int D, int C>
 static hipError_t launch_la_t(const LaArgs& a, int B, int nblocks, hipStream_t stream) {
   typedef LaCfg<T, D, C> L;
-  auto kern = la_kernel<T, D, C>;
+  auto kern = a.src != nullptr ? la_kernel<T, D, C, true> : la_kernel<T, D, C, false>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::smem_bytes);
   if (e != hipSuccess) return e;

@@ -102,11 +102,12 @@ __device__ __forceinline__ void sa_qk(const T* __restrict__ Ks, const typename M
 }
 
 // MASK: 0 = every key of the tile is visible to every row of the wave, 1 = retained tile with a ragged end,
-//       2 = local tile (window start and causal limit)
+//       2 = local tile (window start and causal limit), 3 = retained tile under a bit mask (bit j = key j of the
+//       tile is retained for the wave's chunk: the budget policy that evicts, still_evict.hip)
 template <typename T, int D, int MASK>
 __device__ __forceinline__ void sa_softmax_pv(const T* __restrict__ Vs, floatx16 (&st)[2], floatx16 (&o)[D / 32],
                                               float& m_ref, float& lpart, int kb, int ret_w, int lo_w, int t,
-                                              float sc2, int r, int g) {
+                                              float sc2, int r, int g, unsigned long long bits = 0ull) {
   typedef Mma<T> M;
   typedef SaCfg<T, D> Cf;
   constexpr int DT = D / 32;
@@ -119,7 +120,9 @@ __device__ __forceinline__ void sa_softmax_pv(const T* __restrict__ Vs, floatx16
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int key = kb + 32 * mt + M::pos_of_reg(i, g);
-        const bool valid = MASK == 1 ? (key < ret_w) : (key >= lo_w && key <= t);
+        const uint32_t half = (uint32_t)(mt ? bits >> 32 : bits);
+        const bool valid = MASK == 3 ? ((half >> M::pos_of_reg(i, g)) & 1u) != 0u
+                                     : (MASK == 1 ? (key < ret_w) : (key >= lo_w && key <= t));
         st[mt][i] = valid ? st[mt][i] : -INFINITY;
       }
   }
@@ -163,7 +166,9 @@ __device__ __forceinline__ void sa_softmax_pv(const T* __restrict__ Vs, floatx16
 }
 
 // (a __device__ body behind a thin __global__ wrapper keeps the kernel's host-side launch stub simple)
-template <typename T, int D>
+// EV: the budget policy that evicts: the retained tiles are all offers in routing order, each under the bit mask of
+// the wave's chunk (a.alive), staged in LDS behind the tiles and the z vectors.
+template <typename T, int D, bool EV>
 __device__ __forceinline__ void sa_body(const SaArgs& a) {
   typedef Mma<T> M;
   typedef SaCfg<T, D> Cf;
@@ -210,6 +215,14 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   const int loc_lo = (c_first >= 1 ? c_first - 1 : 0) * C;
   const int n_ret_tiles = (ret_max + BN - 1) / BN;
   const int n_tiles = n_ret_tiles + (last_row + 1 - loc_lo + BN - 1) / BN;
+  unsigned long long* aliveL = reinterpret_cast<unsigned long long*>(smem + Cf::tile_bytes + 2 * (2 * D) * 4);
+  if constexpr (EV) {
+    // mask rows of the tile's chunks (at most two); every wave passes a barrier before the first retained tile
+    const unsigned long long* al = static_cast<const unsigned long long*>(a.alive) +
+                                   (((int64_t)b * a.Hq + hq) * a.nc + c_first) * (int64_t)a.AW;
+    for (int i = tid; i < (c_last - c_first + 1) * a.AW; i += Cf::NW * 64) aliveL[i] = al[i];
+  }
+  auto tile_bits = [&](int ti) -> unsigned long long { return aliveL[(cw - c_first) * a.AW + ti]; };
 
   const T* __restrict__ kloc = static_cast<const T*>(a.k) + (int64_t)b * a.k_sb + (int64_t)kvh * a.k_sh;
   const T* __restrict__ vtl = static_cast<const T*>(a.vt) + ((int64_t)b * a.Hkv + kvh) * (int64_t)D * a.Np;
@@ -297,6 +310,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
     if (!wave_active) return -1;
     const int kb = tile_kb(ti);
     if (ti < n_ret_tiles) {
+      if constexpr (EV) return (kb < ret_w && tile_bits(ti) != 0ull) ? 3 : -1;
       if (kb + BN <= ret_w) return 0;
       return kb < ret_w ? 1 : -1;
     }
@@ -619,6 +633,8 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       sa_softmax_pv<T, D, 1>(Vs, st_cur, o, m_ref, lpart, kb, ret_w, lo_w, t, sc2, r, g);
     else if (mode == 2)
       sa_softmax_pv<T, D, 2>(Vs, st_cur, o, m_ref, lpart, kb, ret_w, lo_w, t, sc2, r, g);
+    else if (EV && mode == 3)
+      sa_softmax_pv<T, D, 3>(Vs, st_cur, o, m_ref, lpart, kb, ret_w, lo_w, t, sc2, r, g, tile_bits(ti));
     wait_async_copies();
     lds_barrier();
   };
@@ -652,7 +668,7 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   int ti = 0;
   {
     // last even ti (exclusive) such that tiles ti+1 (fully visible) and ti+2, ti+3 (retained) qualify
-    int n_steady = wave_active ? ret_w / BN - 1 : 0;             // ti + 1 < ret_w / BN  for both steps of a trip
+    int n_steady = (wave_active && !EV) ? ret_w / BN - 1 : 0;    // ti + 1 < ret_w / BN  for both steps of a trip
     if (n_steady > n_ret_tiles - 3) n_steady = n_ret_tiles - 3;  // ti + 3 < n_ret_tiles
     n_steady = __builtin_amdgcn_readfirstlane(n_steady);
     for (; ti < n_steady; ti += 2) {
@@ -714,20 +730,22 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
   }
 }
 
-template <typename T, int D>
+template <typename T, int D, bool EV>
 __global__ __launch_bounds__(kSaRows * 2, kSaRows == 128 ? 2 : 1) void sa_kernel(SaArgs a) {
-  sa_body<T, D>(a);
+  sa_body<T, D, EV>(a);
 }
 
 template <typename T, int D>
 static hipError_t launch_sa_t(const SaArgs& a, int B, hipStream_t stream) {
   typedef SaCfg<T, D> Cf;
-  auto kern = sa_kernel<T, D>;
+  const bool ev = a.alive != nullptr;
+  auto kern = ev ? sa_kernel<T, D, true> : sa_kernel<T, D, false>;
+  const size_t smem = Cf::smem_bytes + (ev ? (size_t)2 * a.AW * 8 : 0);   // + the mask rows of two chunks
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cf::smem_bytes);
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
   dim3 grid((unsigned)(a.ntiles * a.Hq * B)), block(64 * Cf::NW);
-  hipLaunchKernelGGL(kern, grid, block, Cf::smem_bytes, stream, a);
+  hipLaunchKernelGGL(kern, grid, block, smem, stream, a);
   return hipGetLastError();
 }
 

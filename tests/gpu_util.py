@@ -13,7 +13,8 @@ from paper_2602_02180_amd import synth
 
 
 def run_hip(w: synth.Workload, inp: Dict[str, np.ndarray], sel_in: Optional[np.ndarray] = None,
-            kv_map: Optional[np.ndarray] = None, want_terms: bool = True, gate_activation: int = 0) -> Dict[str, np.ndarray]:
+            kv_map: Optional[np.ndarray] = None, want_terms: bool = True, gate_activation: int = 0,
+            budget_policy: int = 0) -> Dict[str, np.ndarray]:
     """One still_hybrid_attn_fwd call; returns out, score, sel and (want_terms: the call is made with the
     emit_terms inspection hook, and the linear-branch terms are read from the workspace) N_LA, D_LA."""
     import torch
@@ -32,7 +33,7 @@ def run_hip(w: synth.Workload, inp: Dict[str, np.ndarray], sel_in: Optional[np.n
     p = S.make_params(B=B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
                       dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, g=g, kv_head_of_q=kv_map,
                       max_retained=w.max_retained, shared_selection=w.shared_selection, emit_terms=want_terms,
-                      gate_activation=gate_activation)
+                      gate_activation=gate_activation, budget_policy=budget_policy)
     ncf = N // w.C
     score = torch.full((B, w.Hq, N), float("nan"), dtype=torch.float32, device=dev)
     sel = torch.full((B, w.Hq, max(ncf, 1), max(w.lam, 1)), -1, dtype=torch.int32, device=dev)
@@ -56,11 +57,13 @@ def run_hip(w: synth.Workload, inp: Dict[str, np.ndarray], sel_in: Optional[np.n
 
 
 def oracle_units(w: synth.Workload, inp, units: Iterable[Tuple[int, int]], sel: Optional[np.ndarray] = None,
-                 kv_map: Optional[np.ndarray] = None, rows=None, N: Optional[int] = None, gate_activation: str = "none"):
+                 kv_map: Optional[np.ndarray] = None, rows=None, N: Optional[int] = None, gate_activation: str = "none",
+                 budget_policy: str = "stop", rank_scores: Optional[np.ndarray] = None):
     kv_map = synth.kv_head_map(w) if kv_map is None else kv_map
     return O.still_forward_units(inp, kv_map, list(units), C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
                                  form="chunkwise", sel=sel, rows=rows, max_retained=budget(w),
-                                 shared_selection=w.shared_selection, gate_activation=gate_activation)
+                                 shared_selection=w.shared_selection, gate_activation=gate_activation,
+                                 budget_policy=budget_policy, rank_scores=rank_scores)
 
 
 def budget(w: synth.Workload) -> Optional[int]:

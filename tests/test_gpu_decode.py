@@ -235,6 +235,19 @@ def test_decode_with_eviction_policy(kw, n_total):
     check_decode(w, inp, 0, n_total, budget_policy=1)
 
 
+@pytest.mark.parametrize("kw,n_prefill,n_total", [
+    (dict(dtype="f32", d=64, C=64, W=64, lam=16, max_retained=40), 300, 700),     # the budget is full at the hand-over
+    (dict(dtype="f32", d=64, C=64, W=64, lam=16, max_retained=40), 130, 500),     # fills during decode
+    (dict(dtype="bf16", d=128, C=128, W=128, lam=16, max_retained=24, Hq=4, Hkv=2), 700, 1200),
+])
+def test_decode_continues_prefill_with_eviction_policy(kw, n_prefill, n_total):
+    """The prefill exports the set retained after its last routed step, with scores and token indices; the decode
+    steps go on evicting from it."""
+    w = wl("decev2", **kw)
+    inp = synth.make_inputs(w, seed=30, n_tokens=n_total)
+    check_decode(w, inp, n_prefill, n_total, budget_policy=1)
+
+
 def test_decode_with_gate():
     w = wl("decg", dtype="f32", d=64, C=64, W=64, lam=8)
     inp = synth.make_inputs(w, seed=23, n_tokens=280, with_gate=True)

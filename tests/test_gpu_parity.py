@@ -169,6 +169,36 @@ def test_retained_budget(kw):
 
 
 # variant: the query heads of one kv head rank by their summed score and share one list
+@pytest.mark.parametrize("kw", [
+    dict(N=640, lam=16, max_retained=40),                                  # fp32 d=64 C=64: fills at chunk 2, then evicts
+    dict(N=500, lam=16, max_retained=5, W=48),                             # budget below one chunk's offer, ragged end
+    dict(dtype="bf16", d=128, C=128, W=128, N=1536, lam=16, max_retained=24, Hq=4, Hkv=2, B=2),
+    dict(d=128, C=64, W=64, N=700, lam=8, max_retained=16),
+    dict(dtype="bf16", d=64, C=64, N=2048, lam=16, max_retained=96, Hq=4, Hkv=1),   # several scan segments
+], ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
+def test_eviction_policy_prefill(kw):
+    """Budget policy 1 (a variant of this library): rows of chunk c see the best-scored offers of chunks <= c-2, a
+    token that leaves enters the state at the step it leaves.  The evictions are ranked by the device's own fp32
+    scores on both sides (one precision decides); scores and offers are checked against the oracle's as usual."""
+    w = small("evict", **kw)
+    inp = synth.make_inputs(w, seed=37)
+    units = all_units(w)
+    hip = U.run_hip(w, inp, budget_policy=1)
+    ref_own = U.oracle_units(w, inp, units, budget_policy="evict")
+    for (b, h) in units:
+        assert float(np.max(np.abs(hip["score"][b, h] - ref_own[(b, h)]["score"]))) <= 5e-5
+        n, clear, bad, tie = U.selection_report(ref_own[(b, h)]["rank_score"], ref_own[(b, h)]["sel"], hip["sel"][b, h],
+                                                w.C, w.lam)
+        assert bad == 0 and np.all(hip["sel"][b, h] >= 0)
+    ref = U.oracle_units(w, inp, units, sel=hip["sel"], budget_policy="evict", rank_scores=hip["score"].astype(np.float64))
+    check_terms(w, hip, ref, units, "evict")
+    check_outputs(w, hip, ref, units, "evict")
+    # and the policy is not a no-op here: the stop-adding operator gives other rows
+    stop = U.oracle_units(w, inp, units[:1])
+    b, h = units[0]
+    assert np.abs(stop[(b, h)]["out"] - ref[(b, h)]["out"]).max() > 1e-4
+
+
 @pytest.mark.parametrize("kw,kv_map", [
     (dict(dtype="f32", d=64, C=64, W=64, N=700, Hq=4, Hkv=2), None),
     (dict(dtype="f32", d=64, C=128, W=100, N=900, Hq=6, Hkv=2, lam=20, max_retained=50), [0, 1, 0, 1, 1, 0]),

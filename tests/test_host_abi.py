@@ -37,7 +37,7 @@ def test_workspace_layout_is_consistent():
     p = params()
     L = S.still_fwd_workspace_layout(p)
     assert S.still_fwd_workspace_bytes(p) == L.total
-    offs = [L.score, L.sel, L.vt, L.kret, L.vrett, L.wqt, L.wkf, L.seg, L.snap, L.zsnap, L.pimg, L.zpre, L.kmask, L.n_la, L.d_la, L.vfr, L.total]
+    offs = [L.score, L.sel, L.vt, L.kret, L.vrett, L.wqt, L.wkf, L.seg, L.snap, L.zsnap, L.pimg, L.zpre, L.kmask, L.n_la, L.d_la, L.vfr, L.ev_src, L.ev_alive, L.ev_fin, L.ev_vfr, L.total]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert L.n_pad % 128 == 0 and L.n_pad >= 1024
     assert L.cap % 64 == 0 and L.cap >= (1024 // 64) * 16
