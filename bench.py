@@ -92,7 +92,7 @@ def _oracle_unit(unit):
     t0 = time.perf_counter()
     O.still_forward_units(inp, synth.kv_head_map(w), [unit], C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
                           max_retained=w.max_retained if w.max_retained > 0 else None,
-                          shared_selection=w.shared_selection)
+                          shared_selection=w.shared_selection, budget_policy="evict" if w.budget_policy else "stop")
     return time.perf_counter() - t0
 
 
@@ -140,6 +140,7 @@ def cpu_baseline(w: synth.Workload, inp, budget_s: float = 15.0):
 
 def budget_tag(w: synth.Workload) -> str:
     return (f" max_retained={w.max_retained}" if w.max_retained > 0 else "") + \
+        (" budget_policy=evict" if w.budget_policy else "") + \
         (" shared_selection" if w.shared_selection else "")
 
 
@@ -234,7 +235,8 @@ def decode_record(args, steps: int, with_cpu: bool):
     import torch
     from paper_2602_02180_amd import binding as S
 
-    w = synth.workload("c5", max_retained=args.max_retained, shared_selection=args.shared_selection)
+    w = synth.workload("c5", max_retained=args.max_retained, shared_selection=args.shared_selection,
+                       budget_policy=int(args.evict))
     dev = "cuda"
     gen = torch.Generator(device=dev)
     gen.manual_seed(w.seed)
@@ -250,7 +252,8 @@ def decode_record(args, steps: int, with_cpu: bool):
     Wq = (torch.randn(Hq, d, d, generator=gen, device=dev) / d ** 0.5).to(bf)
     Wk = (torch.randn(Hq, d, d, generator=gen, device=dev) / d ** 0.5).to(bf)
     base = dict(B=B, Hq=Hq, Hkv=Hkv, d=d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps, dtype="bf16",
-                max_tokens=max_tokens, max_retained=w.max_retained, shared_selection=w.shared_selection)
+                max_tokens=max_tokens, max_retained=w.max_retained, shared_selection=w.shared_selection,
+                budget_policy=w.budget_policy)
     ps = S.make_params(N=1, **base)
     L = S.still_state_layout(ps)
     state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
@@ -357,7 +360,8 @@ def decode_cpu_baseline(w, ctx, toks, Wq, Wk, warmup, n_steps, budget_s: float =
         v = np.concatenate([ctx["v"][:, h // G], vd]).astype(np.float64)
         O.still_chunkwise(q, k, v, None, Wq[h].float().cpu().numpy().astype(np.float64),
                           Wk[h].float().cpu().numpy().astype(np.float64), w.C, w.W, w.lam, w.scale, w.eps,
-                          rows=(w.N, w.N + n_dec), max_retained=w.max_retained if w.max_retained > 0 else None)
+                          rows=(w.N, w.N + n_dec), max_retained=w.max_retained if w.max_retained > 0 else None,
+                          budget_policy="evict" if w.budget_policy else "stop")
         units_done += 1
         if time.perf_counter() - t0 > budget_s:
             break
@@ -381,6 +385,9 @@ def main() -> int:
     ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--max-retained", type=int, default=0,
                     help="budget on the retained tokens per (sequence, head); 0 (default) = none, the headline workload")
+    ap.add_argument("--evict", action="store_true",
+                    help="with --max-retained: hold the budget by evicting the lowest score (budget policy 1) instead "
+                         "of not adding (side figures only)")
     ap.add_argument("--shared-selection", action="store_true",
                     help="variant: the query heads of one kv head rank by their summed score and share one retained "
                          "set (not the paper's method; side figures only)")
@@ -408,7 +415,8 @@ def main() -> int:
     prefill_run = not (args.calibrate_copy or args.global_score or args.config == "c5")
     w = inp = cpu_rec = None
     if prefill_run:
-        w = synth.workload(args.config, max_retained=args.max_retained, shared_selection=args.shared_selection)
+        w = synth.workload(args.config, max_retained=args.max_retained, shared_selection=args.shared_selection,
+                           budget_policy=int(args.evict))
         inp = synth.make_inputs(w)
         # The oracle leg forks worker processes, so it runs before this process initialises the GPU (a forked copy
         # of an initialised HIP runtime is not something to rely on); it is outside every timed GPU region anyway.
@@ -443,7 +451,7 @@ def main() -> int:
     N = w.N
     p = S.make_params(B=w.B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
                       dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, max_retained=w.max_retained,
-                      shared_selection=w.shared_selection)
+                      shared_selection=w.shared_selection, budget_policy=w.budget_policy)
     ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 

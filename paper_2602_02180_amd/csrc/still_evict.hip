@@ -30,22 +30,32 @@ __device__ __forceinline__ int evict_key_token(unsigned long long key) {
   return (int)(0xFFFFFFFFu - (uint32_t)(key & 0xFFFFFFFFull));
 }
 
-// One workgroup of 256 threads per (sequence, query head), walking the routing steps in order.
-// LDS (dynamic): keys[M + lam] (8 bytes), slot[M + lam] (4 bytes: index of the offer in routing order), then the
-// words of one alive row.
+// One workgroup of 256 threads per (sequence, query head), walking the routing steps in order.  The retained set is
+// kept SORTED by key (ascending: the first entries are the first to leave) in one of two LDS buffers.  Per step:
+//   the lam offers are sorted among themselves (rank counting);
+//   the `over` smallest keys of the union are found by merging the two sorted heads (one thread, at most lam picks):
+//   they are the first e_old retained entries and the first e_new offers;
+//   the survivors of both lists are merged into the other buffer, every entry computing its own place (its index
+//   in its list plus a binary search in the other);
+//   the offers that stay lend their positions to the retained tokens that leave (src), the mask row of chunk s+2 is
+//   built from the entries' offer indices.
+// The barriers inside the loop order LDS traffic only (the kernel never reads back what it writes to global memory),
+// so the offers of the next step, fetched a step ahead, and the stores of this step stay in flight across them.
+// LDS (dynamic): 2 x keys[M + lam] (8 bytes), 2 x slot[M + lam] (4 bytes), the words of one mask row.
 __global__ __launch_bounds__(256) void evict_plan_kernel(EvictPlanArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
-  const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int64_t unit = (int64_t)b * a.Hq + hq;
   const int N = seq_tokens(a.seq_len, b, a.N);
-  const int C = a.C, lam = a.lam, M = a.M;
+  const int C = a.C, lam = a.lam, M = a.M, cap = M + lam;
   const int ncf = N / C, nc = (N + C - 1) / C;
   const int n_exp = nc >= 2 ? nc - 2 : 0;                 // routing steps a decode hand-over has seen
-  unsigned long long* keys = reinterpret_cast<unsigned long long*>(dsm);
-  int* slot = reinterpret_cast<int*>(dsm + (size_t)(M + lam) * 8);
-  uint32_t* words = reinterpret_cast<uint32_t*>(dsm + (size_t)(M + lam) * 12);   // 2 * AW 32-bit words
-  __shared__ unsigned long long s_best[4];
-  __shared__ int s_besti[4], s_ev[128], s_host[128], s_n;
+  unsigned long long* kbuf[2] = {reinterpret_cast<unsigned long long*>(dsm),
+                                 reinterpret_cast<unsigned long long*>(dsm) + cap};
+  int* sbuf[2] = {reinterpret_cast<int*>(dsm + (size_t)cap * 16), reinterpret_cast<int*>(dsm + (size_t)cap * 16) + cap};
+  uint32_t* words = reinterpret_cast<uint32_t*>(dsm + (size_t)cap * 24);   // 2 * AW 32-bit words
+  __shared__ unsigned long long s_new[128], s_raw[128];
+  __shared__ int s_newslot[128], s_eold;
 
   const float* score = a.score + unit * a.N;
   const int32_t* sel = a.sel + unit * (int64_t)a.ncf_all * lam;
@@ -55,93 +65,101 @@ __global__ __launch_bounds__(256) void evict_plan_kernel(EvictPlanArgs a) {
   for (int t = tid; t < a.N; t += 256) src[t] = t;        // every position carries its own token unless told otherwise
   for (int i = tid; i < 2 * (2 * a.AW); i += 256)         // rows of chunks 0 and 1 see no retained token
     if (i / (2 * a.AW) < a.nc_all) alive[i] = 0u;
-  if (tid == 0) {
-    s_n = 0;
-    a.fin_n[unit] = 0;
-  }
+  if (tid == 0) a.fin_n[unit] = 0;
+  int n = 0, cur = 0;                                     // retained entries (in kbuf[cur]); uniform over the workgroup
+  // the offers of the next step are fetched a step ahead (two dependent global loads: index, then score)
+  unsigned long long next_key = 0ull;
+  auto fetch_offer = [&](int s) {
+    if (tid < lam && s < ncf) {
+      const int tok = sel[(int64_t)s * lam + tid];
+      next_key = evict_key(score[tok], tok);
+    }
+  };
+  fetch_offer(0);
   __syncthreads();
 
   for (int s = 0; s < ncf; ++s) {
-    const int n_old = s_n;
-    // the chunk's offers join the set
+    const unsigned long long* kold = kbuf[cur];
+    const int* sold = sbuf[cur];
+    unsigned long long* knew = kbuf[cur ^ 1];
+    int* snew = sbuf[cur ^ 1];
+    // the chunk's offers, sorted among themselves
+    if (tid < lam) s_raw[tid] = next_key;
+    if (tid == 0) s_eold = 0;
+    lds_barrier();
+    fetch_offer(s + 1);
     if (tid < lam) {
-      const int tok = sel[(int64_t)s * lam + tid];
-      keys[n_old + tid] = evict_key(score[tok], tok);
-      slot[n_old + tid] = s * lam + tid;
-      src[tok] = -1;                                       // kept: carries nothing (revised below)
+      const unsigned long long mine = s_raw[tid];
+      int rank = 0;
+      for (int j = 0; j < lam; ++j) rank += s_raw[j] < mine ? 1 : 0;   // keys are distinct (distinct tokens)
+      s_new[rank] = mine;
+      s_newslot[rank] = s * lam + tid;
     }
-    __syncthreads();
-    const int total = n_old + lam;
-    const int over = total > M ? total - M : 0;
-    for (int it = 0; it < over; ++it) {
-      unsigned long long best = ~0ull;
-      int bi = -1;
-      for (int i = tid; i < total; i += 256) {
-        const unsigned long long kk = keys[i];
-        if (kk < best) best = kk, bi = i;
-      }
-      for (int off = 32; off > 0; off >>= 1) {
-        const unsigned long long ob = __shfl_xor(best, off);
-        const int oi = __shfl_xor(bi, off);
-        if (ob < best) best = ob, bi = oi;
-      }
-      if (lane == 0) s_best[wave] = best, s_besti[wave] = bi;
-      __syncthreads();
-      if (tid == 0) {
-        int w = 0;
-        for (int j = 1; j < 4; ++j)
-          if (s_best[j] < s_best[w]) w = j;
-        s_ev[it] = s_besti[w];
-        s_host[it] = evict_key_token(s_best[w]);           // the token that leaves
-        keys[s_besti[w]] = ~0ull;
-      }
-      __syncthreads();
+    lds_barrier();
+    // The `over` smallest keys of the union are among the first `over` entries of either sorted list.  Retained
+    // entry i (< over) leaves iff fewer than `over` keys of the union are smaller: its own index plus the offers
+    // below it.  The leavers of a sorted list are a prefix, so counting them gives e_old; the rest are offers.
+    const int over = n + lam > M ? n + lam - M : 0;
+    if (tid < over && tid < n) {
+      const unsigned long long key = kold[tid];
+      int below = tid;
+      const int jmax = over < lam ? over : lam;
+      for (int j = 0; j < jmax; ++j) below += s_new[j] < key ? 1 : 0;
+      if (below < over) atomicAdd(&s_eold, 1);
     }
-    if (tid == 0) {
-      // An offer that leaves at once is an ordinary unselected token of its chunk.  A retained token that leaves is
-      // carried by the position of an offer that stays (in ascending order of both).
-      int nh = 0;                                          // leavers that were retained before this step
-      for (int it = 0; it < over; ++it) {
-        if (s_ev[it] >= n_old) src[s_host[it]] = s_host[it];
-        else s_host[nh++] = s_host[it];
+    lds_barrier();
+    const int e_old = s_eold, e_new = over - e_old;
+    const int n_old_s = n - e_old, n_new_s = lam - e_new;   // survivors of both lists
+    // merge the survivors into the other buffer
+    for (int i = tid; i < n_old_s; i += 256) {
+      const unsigned long long key = kold[e_old + i];
+      int lo = 0, hi = n_new_s;                            // offers that stay and are smaller
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (s_new[e_new + mid] < key) lo = mid + 1;
+        else hi = mid;
       }
-      int h = 0;
-      for (int i = 0; i < lam && h < nh; ++i)
-        if (keys[n_old + i] != ~0ull) src[evict_key_token(keys[n_old + i])] = s_host[h++];
-      // close the gaps: the last valid entries move into the vacated places (vacated indices in descending order)
-      for (int x = 1; x < over; ++x) {                     // insertion sort, at most lam entries
-        const int v = s_ev[x];
-        int y = x - 1;
-        while (y >= 0 && s_ev[y] < v) s_ev[y + 1] = s_ev[y], --y;
-        s_ev[y + 1] = v;
-      }
-      int last = total - 1;
-      for (int x = 0; x < over; ++x) {
-        const int idx = s_ev[x];
-        if (idx != last) keys[idx] = keys[last], slot[idx] = slot[last];
-        --last;
-      }
-      s_n = total - over;
+      knew[i + lo] = key;
+      snew[i + lo] = sold[e_old + i];
     }
-    __syncthreads();
-    const int n_now = s_n;
+    if (tid < n_new_s) {
+      const unsigned long long key = s_new[e_new + tid];
+      int lo = 0, hi = n_old_s;                            // retained entries that stay and are smaller
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (kold[e_old + mid] < key) lo = mid + 1;
+        else hi = mid;
+      }
+      knew[tid + lo] = key;
+      snew[tid + lo] = s_newslot[e_new + tid];
+    }
+    // what every offer's position carries into the state: an offer that leaves at once is an ordinary unselected
+    // token; an offer that stays carries nothing, or the retained token that leaves in its favour
+    if (tid < lam) {
+      const int tok = evict_key_token(s_new[tid]);
+      int carries = tok;
+      if (tid >= e_new) carries = (tid - e_new < e_old) ? evict_key_token(kold[tid - e_new]) : -1;
+      src[tok] = carries;
+    }
+    n = n_old_s + n_new_s;
+    cur ^= 1;
     // the set the rows of chunk s+2 see, as one bit per offer in routing order
+    for (int i = tid; i < 2 * a.AW; i += 256) words[i] = 0u;
+    lds_barrier();
     if (s + 2 < nc) {
-      for (int i = tid; i < 2 * a.AW; i += 256) words[i] = 0u;
-      __syncthreads();
-      for (int i = tid; i < n_now; i += 256) atomicOr(&words[slot[i] >> 5], 1u << (slot[i] & 31));
-      __syncthreads();
+      for (int i = tid; i < n; i += 256) atomicOr(&words[snew[i] >> 5], 1u << (snew[i] & 31));
+      lds_barrier();
       for (int i = tid; i < 2 * a.AW; i += 256) alive[(int64_t)(s + 2) * (2 * a.AW) + i] = words[i];
     }
     if (s == n_exp - 1 && a.fin_tok != nullptr) {
-      for (int i = tid; i < n_now; i += 256) {
-        const int tok = evict_key_token(keys[i]);
+      for (int i = tid; i < n; i += 256) {
+        const int tok = evict_key_token(knew[i]);
         a.fin_tok[unit * M + i] = tok;
         a.fin_score[unit * M + i] = score[tok];
       }
-      if (tid == 0) a.fin_n[unit] = n_now;
+      if (tid == 0) a.fin_n[unit] = n;
     }
-    __syncthreads();
+    lds_barrier();
   }
 }
 
@@ -217,7 +235,7 @@ __global__ __launch_bounds__(64) void state_fill_evict_kernel(StateFillEvictArgs
   }
 }
 
-size_t evict_plan_smem(int M, int lam, int AW) { return (size_t)(M + lam) * 12 + (size_t)2 * AW * 4 + 16; }
+size_t evict_plan_smem(int M, int lam, int AW) { return (size_t)(M + lam) * 24 + (size_t)2 * AW * 4 + 16; }
 
 hipError_t launch_evict_plan(const EvictPlanArgs& a, int B, hipStream_t stream) {
   const size_t smem = evict_plan_smem(a.M, a.lam, a.AW);

@@ -29,7 +29,7 @@ __host__ __device__ inline int retained_rows(int chunks, int lam, int rcap) {
   return r < rcap ? r : rcap;
 }
 constexpr int kNoBudget = 1 << 30;
-constexpr int kMaxEvictBudget = 8192;   // the routing step ranks the retained rows in LDS (8 bytes each)
+constexpr int kMaxEvictBudget = 4096;   // the plan and the routing step hold the retained set in LDS
 
 // Tokens of sequence b: N for every sequence, or, for a right-padded batch, the caller's per-sequence count
 // (device array, clamped to [1, N]).  Rows at and beyond it are padding: never read as keys or values by a real

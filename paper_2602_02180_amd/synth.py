@@ -39,6 +39,7 @@ class Workload:
     eps: float = 1e-6
     decode_steps: int = 0
     max_retained: int = 0     # budget on the retained tokens per (sequence, head); 0 => none
+    budget_policy: int = 0    # with a budget: 0 = stop adding, 1 = evict the lowest score
     shared_selection: bool = False   # variant: the heads of one kv head rank by their summed score
 
     @property
