@@ -30,7 +30,7 @@ __device__ __forceinline__ int evict_key_token(unsigned long long key) {
   return (int)(0xFFFFFFFFu - (uint32_t)(key & 0xFFFFFFFFull));
 }
 
-// One workgroup of 256 threads per (sequence, query head), walking the routing steps in order.  The retained set is
+// One workgroup per (sequence, query head), walking the routing steps in order.  The retained set is
 // kept SORTED by key (ascending: the first entries are the first to leave) in one of two LDS buffers.  Per step:
 //   the lam offers are sorted among themselves (rank counting);
 //   the `over` smallest keys of the union are found by merging the two sorted heads (one thread, at most lam picks):
@@ -42,7 +42,9 @@ __device__ __forceinline__ int evict_key_token(unsigned long long key) {
 // The barriers inside the loop order LDS traffic only (the kernel never reads back what it writes to global memory),
 // so the offers of the next step, fetched a step ahead, and the stores of this step stay in flight across them.
 // LDS (dynamic): 2 x keys[M + lam] (8 bytes), 2 x slot[M + lam] (4 bytes), the words of one mask row.
-__global__ __launch_bounds__(256) void evict_plan_kernel(EvictPlanArgs a) {
+// (threads per workgroup: with one entry per thread the dependent LDS reads of a step overlap)
+constexpr int kPlanThreads = 1024;
+__global__ __launch_bounds__(kPlanThreads) void evict_plan_kernel(EvictPlanArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char dsm[];
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int64_t unit = (int64_t)b * a.Hq + hq;
@@ -62,8 +64,8 @@ __global__ __launch_bounds__(256) void evict_plan_kernel(EvictPlanArgs a) {
   int32_t* src = a.src + unit * a.N;
   uint32_t* alive = reinterpret_cast<uint32_t*>(a.alive) + unit * (int64_t)a.nc_all * (2 * a.AW);
 
-  for (int t = tid; t < a.N; t += 256) src[t] = t;        // every position carries its own token unless told otherwise
-  for (int i = tid; i < 2 * (2 * a.AW); i += 256)         // rows of chunks 0 and 1 see no retained token
+  for (int t = tid; t < a.N; t += kPlanThreads) src[t] = t;        // every position carries its own token unless told otherwise
+  for (int i = tid; i < 2 * (2 * a.AW); i += kPlanThreads)         // rows of chunks 0 and 1 see no retained token
     if (i / (2 * a.AW) < a.nc_all) alive[i] = 0u;
   if (tid == 0) a.fin_n[unit] = 0;
   int n = 0, cur = 0;                                     // retained entries (in kbuf[cur]); uniform over the workgroup
@@ -111,7 +113,7 @@ __global__ __launch_bounds__(256) void evict_plan_kernel(EvictPlanArgs a) {
     const int e_old = s_eold, e_new = over - e_old;
     const int n_old_s = n - e_old, n_new_s = lam - e_new;   // survivors of both lists
     // merge the survivors into the other buffer
-    for (int i = tid; i < n_old_s; i += 256) {
+    for (int i = tid; i < n_old_s; i += kPlanThreads) {
       const unsigned long long key = kold[e_old + i];
       int lo = 0, hi = n_new_s;                            // offers that stay and are smaller
       while (lo < hi) {
@@ -144,15 +146,15 @@ __global__ __launch_bounds__(256) void evict_plan_kernel(EvictPlanArgs a) {
     n = n_old_s + n_new_s;
     cur ^= 1;
     // the set the rows of chunk s+2 see, as one bit per offer in routing order
-    for (int i = tid; i < 2 * a.AW; i += 256) words[i] = 0u;
+    for (int i = tid; i < 2 * a.AW; i += kPlanThreads) words[i] = 0u;
     lds_barrier();
     if (s + 2 < nc) {
-      for (int i = tid; i < n; i += 256) atomicOr(&words[snew[i] >> 5], 1u << (snew[i] & 31));
+      for (int i = tid; i < n; i += kPlanThreads) atomicOr(&words[snew[i] >> 5], 1u << (snew[i] & 31));
       lds_barrier();
-      for (int i = tid; i < 2 * a.AW; i += 256) alive[(int64_t)(s + 2) * (2 * a.AW) + i] = words[i];
+      for (int i = tid; i < 2 * a.AW; i += kPlanThreads) alive[(int64_t)(s + 2) * (2 * a.AW) + i] = words[i];
     }
     if (s == n_exp - 1 && a.fin_tok != nullptr) {
-      for (int i = tid; i < n; i += 256) {
+      for (int i = tid; i < n; i += kPlanThreads) {
         const int tok = evict_key_token(knew[i]);
         a.fin_tok[unit * M + i] = tok;
         a.fin_score[unit * M + i] = score[tok];
@@ -242,7 +244,7 @@ hipError_t launch_evict_plan(const EvictPlanArgs& a, int B, hipStream_t stream) 
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(evict_plan_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(evict_plan_kernel, dim3(a.Hq, B), dim3(256), smem, stream, a);
+  hipLaunchKernelGGL(evict_plan_kernel, dim3(a.Hq, B), dim3(kPlanThreads), smem, stream, a);
   return hipGetLastError();
 }
 
