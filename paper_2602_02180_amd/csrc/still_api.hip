@@ -272,7 +272,7 @@ void compute_state_layout(const still_params_t* p, still_state_layout_t* L) {
 
 extern "C" {
 
-int32_t still_version(void) { return 200; }
+int32_t still_version(void) { return 300;   // 0.3.0: budget_policy in the params, two regions more in both layouts }
 
 const char* still_last_error(void) { return g_err; }
 
