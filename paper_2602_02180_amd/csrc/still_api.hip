@@ -272,7 +272,8 @@ void compute_state_layout(const still_params_t* p, still_state_layout_t* L) {
 
 extern "C" {
 
-int32_t still_version(void) { return 300;   // 0.3.0: budget_policy in the params, two regions more in both layouts }
+// 0.3.0: budget_policy in the params, more regions in both layouts
+int32_t still_version(void) { return 300; }
 
 const char* still_last_error(void) { return g_err; }
 
