@@ -237,7 +237,8 @@ def test_full_length_config4_shape_with_budget_held_by_eviction_fp32():
     setting (896 retained tokens) held by evicting the lowest score, in fp32 (four query heads on one kv head) so that
     the plan over all steps, the masks over 4096 offers and the redirected state scan are held to the fp32 bar on
     every row of a unit.  (In bf16 the same run is within the bf16 bar on most sampled units; rows that two heavy
-    keys with far-apart values share can miss it by the rounding of the weights themselves.)"""
+    keys with far-apart values share can miss it by the rounding of the weights themselves: a kernel that hands the
+    weights to the matrix core in bf16 is off by up to 2^-9 max_j |v_j - y| whatever else it does.)"""
     w = synth.workload("c4", max_retained=896, dtype="f32", Hq=4, Hkv=1)
     inp = synth.make_inputs(w)
     units = [(0, 1)]
