@@ -64,6 +64,24 @@ def test_retained_budget_bounds_the_retained_rows_of_workspace_and_state():
     assert s_tight.kret < s_tight.vret and s_tight.vret - s_tight.kret == 1 * 4 * s_tight.cap * 64 * 2
 
 
+def test_eviction_policy_layouts():
+    """Budget policy 1: the workspace holds ALL offers (the sparse kernel walks them under masks) plus the plan's
+    regions; the decode state holds max_retained rows plus their scores and token indices."""
+    stop = S.still_fwd_workspace_layout(params(N=8192, max_retained=100))
+    ev = S.still_fwd_workspace_layout(params(N=8192, max_retained=100, budget_policy=1))
+    assert stop.cap == 128 and ev.cap == (8192 // 64) * 16
+    assert stop.ev_alive - stop.ev_src <= 256 and stop.total - stop.ev_vfr <= 256      # empty without the policy
+    assert ev.ev_alive - ev.ev_src >= 1 * 4 * 8192 * 4
+    assert ev.ev_fin - ev.ev_alive >= 1 * 4 * (8192 // 64) * (ev.cap // 64) * 8
+    assert ev.ev_vfr - ev.ev_fin >= 1 * 4 * (2 * 100 + 1) * 4
+    assert ev.total - ev.ev_vfr >= 1 * 4 * 64 * ev.n_pad * 2
+    s_stop = S.still_state_layout(params(N=1, max_tokens=1 << 20, max_retained=896))
+    s_ev = S.still_state_layout(params(N=1, max_tokens=1 << 20, max_retained=896, budget_policy=1))
+    assert s_ev.cap == s_stop.cap == 896 + 64
+    assert s_stop.ret_tok - s_stop.ret_score <= 256
+    assert s_ev.ret_tok - s_ev.ret_score >= 1 * 4 * s_ev.cap * 4 and s_ev.total - s_ev.ret_tok >= 1 * 4 * s_ev.cap * 4
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(d=96), S.STILL_ERR_UNSUPPORTED),
     (dict(C=32), S.STILL_ERR_UNSUPPORTED),
@@ -75,6 +93,10 @@ def test_retained_budget_bounds_the_retained_rows_of_workspace_and_state():
     (dict(Hq=5), S.STILL_ERR_INVALID_ARG),
     (dict(eps=0.0), S.STILL_ERR_INVALID_ARG),
     (dict(kv_head_of_q=[0, 1, 2, 0]), S.STILL_ERR_INVALID_ARG),
+    (dict(budget_policy=2, max_retained=64), S.STILL_ERR_INVALID_ARG),
+    (dict(budget_policy=1), S.STILL_ERR_INVALID_ARG),                       # eviction needs a budget to hold
+    (dict(budget_policy=1, max_retained=64, shared_selection=1), S.STILL_ERR_UNSUPPORTED),
+    (dict(budget_policy=1, max_retained=5000), S.STILL_ERR_UNSUPPORTED),    # the retained set is ranked in LDS
 ])
 def test_bad_params_are_rejected_on_the_host(kw, code):
     p = params(**kw)
