@@ -51,7 +51,7 @@ typedef enum { STILL_F32 = 0, STILL_BF16 = 1 } still_dtype_t;
  * number lambda, small constant eps; plus what the paper leaves implicit: batch, GQA head map, the
  * score window W of the window-set equation, and the logit scale).
  *
- * Supported by the kernels (both dtypes): d in {64,128}; d_f == d; C in {64,128}; 1 <= W <= 128; 0 <= lambda <= C;
+ * Supported by the kernels (both dtypes): d in {64,128}; d_f == d; C in {64,128}; 1 <= W <= min(256, 4 C); 0 <= lambda <= C;
  * Hq <= 128; Hq % Hkv == 0 when kv_head_of_q is NULL.  N >= 1 need not be a multiple of C: the trailing
  * partial chunk is never ranked.  Anything else returns STILL_ERR_UNSUPPORTED.
  *

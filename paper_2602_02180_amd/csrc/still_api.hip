@@ -130,7 +130,8 @@ still_status_t validate_params(const still_params_t* p, bool need_n) {
   if (p->d != 64 && p->d != 128) return fail(STILL_ERR_UNSUPPORTED, "d = %d (supported: 64, 128)", p->d);
   if (p->d_f != p->d) return fail(STILL_ERR_UNSUPPORTED, "d_f = %d (supported: d_f == d)", p->d_f);
   if (p->C != 64 && p->C != 128) return fail(STILL_ERR_UNSUPPORTED, "C = %d (supported: 64, 128)", p->C);
-  if (p->W > 128) return fail(STILL_ERR_UNSUPPORTED, "W = %d (supported: 1..128)", p->W);
+  if (p->W > 256 || p->W > 4 * p->C)   // nine band tiles at most; a decode state keeps the last 4 C tokens
+    return fail(STILL_ERR_UNSUPPORTED, "W = %d (supported: 1..min(256, 4 C))", p->W);
   if (need_n && (int64_t)p->N > (int64_t)1 << 24) return fail(STILL_ERR_UNSUPPORTED, "N = %d too large", p->N);
   return STILL_OK;
 }

@@ -88,9 +88,9 @@ __device__ __forceinline__ void decode_append(const DecArgs& a, int h, int b, in
 // Workgroups 0 .. Hq-1 of a sequence score the new token for one query head each; workgroups Hq .. Hq+Hkv-1 copy
 // the new key/value rows of one kv head into the ring.  The two do not depend on each other within the step: the
 // score reads the new key from the caller's k_t, and the ring slot being overwritten (token t - R) lies outside
-// every window (W <= 128 < R).
+// every window (W <= R).  One thread per window key: 128 threads, or 256 for a window of more than 128 keys.
 template <typename T, int D>
-__global__ __launch_bounds__(128) void decode_score_kernel(DecArgs a) {
+__global__ __launch_bounds__(256) void decode_score_kernel(DecArgs a) {
   __shared__ float sh[16];
   const int b = blockIdx.y;
   const int t = step_index(a, b);
@@ -122,18 +122,19 @@ __global__ __launch_bounds__(128) void decode_score_kernel(DecArgs a) {
   }
   const float x2 = valid ? dot * (a.scale * kLog2e) : -INFINITY;
   float s0 = 0.f, s1 = 0.f, mx = x2, mn = 0.f;
-  block_reduce4(s0, s1, mx, mn, sh, 2);
+  const int nwaves = blockDim.x >> 6;
+  block_reduce4(s0, s1, mx, mn, sh, nwaves);
   const float e = valid ? fast_exp2(x2 - mx) : 0.f;
   float d_all = e, d_no = j == 0 ? 0.f : e;
   float c0 = 0.f, c1 = 0.f;
-  block_reduce4(d_all, d_no, c0, c1, sh, 2);
+  block_reduce4(d_all, d_no, c0, c1, sh, nwaves);
   const float inv_all = 1.0f / d_all;
   const float inv_no = d_no > 0.f ? 1.0f / d_no : 0.f;
   const float ad = e * inv_all;
   const float an = j == 0 ? 0.f : e * inv_no;
   float term = valid ? ad * (fast_log2(ad + a.eps) - fast_log2(an + a.eps)) : 0.f;
   float z0 = 0.f, z1 = 0.f, z2 = 0.f;
-  block_reduce4(term, z0, z1, z2, sh, 2);
+  block_reduce4(term, z0, z1, z2, sh, nwaves);
   if (threadIdx.x == 0) a.score[((int64_t)b * a.Hq + hq) * a.R + t % a.R] = term * kLn2;
 }
 
@@ -885,7 +886,7 @@ __global__ void state_fill_retained_kernel(StateFillArgs a) {
   }
 
 hipError_t launch_decode_step(const DecArgs& a, int dtype, int d, bool route, hipStream_t stream) {
-#define CALL_SCORE(TT, DD) hipLaunchKernelGGL((decode_score_kernel<TT, DD>), dim3(a.Hq + a.Hkv, a.B), dim3(128), 0, stream, a);
+#define CALL_SCORE(TT, DD) hipLaunchKernelGGL((decode_score_kernel<TT, DD>), dim3(a.Hq + a.Hkv, a.B), dim3(a.W > 128 ? 256 : 128), 0, stream, a);
   STILL_DISPATCH(dtype, d, CALL_SCORE)
   if (route) {
     const int cr = a.t / a.C - 2;

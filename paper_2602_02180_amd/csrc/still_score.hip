@@ -16,7 +16,7 @@
 namespace still {
 
 template <typename T, int D, int NT>
-__global__ __launch_bounds__(256, 3) void score_select_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(256, NT > 5 ? 2 : 3) void score_select_kernel(ScoreArgs a) {
   typedef Mma<T> M;
   constexpr int KS = D / M::KK;
   const T* __restrict__ q = static_cast<const T*>(a.q);
@@ -260,8 +260,10 @@ static hipError_t launch_score_t(const ScoreArgs& a, int B, int nc, hipStream_t 
   dim3 grid(nc * a.Hq, 1, B), block((a.C / 32) * 64);
   if (a.W <= 64)   // the band must be at least 32 keys longer than the window less one: W <= 32 (NT - 1)
     hipLaunchKernelGGL((score_select_kernel<T, D, 3>), grid, block, 0, stream, a);
-  else
+  else if (a.W <= 128)
     hipLaunchKernelGGL((score_select_kernel<T, D, 5>), grid, block, 0, stream, a);
+  else             // up to 256 keys: nine band tiles (two workgroups per CU: 144 accumulator registers)
+    hipLaunchKernelGGL((score_select_kernel<T, D, 9>), grid, block, 0, stream, a);
   return hipGetLastError();
 }
 

@@ -248,6 +248,17 @@ def test_decode_continues_prefill_with_eviction_policy(kw, n_prefill, n_total):
     check_decode(w, inp, n_prefill, n_total, budget_policy=1)
 
 
+@pytest.mark.parametrize("kw,n_prefill,n_total", [
+    (dict(dtype="f32", d=64, C=64, W=200), 0, 420),             # 256 threads score the new token
+    (dict(dtype="f32", d=64, C=64, W=256, lam=8), 300, 600),    # the window spans the whole ring
+    (dict(dtype="bf16", d=128, C=128, W=160, Hq=4, Hkv=2), 500, 900),
+])
+def test_decode_with_wide_score_windows(kw, n_prefill, n_total):
+    w = wl("decwide", **kw)
+    inp = synth.make_inputs(w, seed=31, n_tokens=n_total)
+    check_decode(w, inp, n_prefill, n_total)
+
+
 def test_decode_with_gate():
     w = wl("decg", dtype="f32", d=64, C=64, W=64, lam=8)
     inp = synth.make_inputs(w, seed=23, n_tokens=280, with_gate=True)

@@ -148,6 +148,7 @@ def test_c1_fp32_full():
     dict(dtype="bf16", d=64, C=64, W=64, N=1333, lam=40, Hq=2, Hkv=2),
 ], ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
 def test_small_shapes(kw):
+    """(shapes listed above; see also test_wide_score_windows)"""
     w = small("small", **kw)
     run_case(w, synth.make_inputs(w, seed=1234))
 
@@ -254,6 +255,19 @@ def test_full_length_config4_shape_with_budget_held_by_eviction_fp32():
     check_terms(w, hip, ref, units, "evict-32k")
     check_outputs(w, hip, ref, units, "evict-32k")
     assert np.all(np.isfinite(hip["out"]))
+
+
+@pytest.mark.parametrize("kw", [
+    dict(N=700, W=129),                                     # fp32 d=64 C=64: nine band tiles
+    dict(N=900, W=256, C=64, lam=8),                        # the widest window: four chunks
+    dict(N=1000, W=200, C=128, d=128, lam=16),
+    dict(dtype="bf16", N=1200, W=255, C=128, d=128, Hq=4, Hkv=2, lam=16),
+], ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
+def test_wide_score_windows(kw):
+    """Score windows of more than 128 keys (Sec. 3.1 leaves the window length free): the band of the score kernel
+    grows to nine tiles."""
+    w = small("wide", **kw)
+    run_case(w, synth.make_inputs(w, seed=39))
 
 
 @pytest.mark.parametrize("lam", [0, 1, 64])

@@ -85,7 +85,7 @@ def test_eviction_policy_layouts():
 @pytest.mark.parametrize("kw,code", [
     (dict(d=96), S.STILL_ERR_UNSUPPORTED),
     (dict(C=32), S.STILL_ERR_UNSUPPORTED),
-    (dict(W=129), S.STILL_ERR_UNSUPPORTED),
+    (dict(W=257, C=128), S.STILL_ERR_UNSUPPORTED),
     (dict(d_f=32), S.STILL_ERR_UNSUPPORTED),
     (dict(lam=65), S.STILL_ERR_INVALID_ARG),
     (dict(lam=-1), S.STILL_ERR_INVALID_ARG),
@@ -144,7 +144,7 @@ def test_state_export_with_injected_indices_needs_scores_and_is_rejected_before_
 
 
 def test_side_entry_points_validate_only_what_they_read():
-    """The global score and the overlap count do not touch the linear branch: its restrictions (d_f == d, W <= 128,
+    """The global score and the overlap count do not touch the linear branch: its restrictions (d_f == d, W <= 256,
     no fp32 with d = C = 128) must not be applied to them.  Null pointers make the calls stop right after the
     parameter checks, with the pointer message."""
     lib = S.lib()
