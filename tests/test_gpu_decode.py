@@ -58,7 +58,7 @@ def run_decode(w, inp, n_prefill, n_total, kv_map=None, with_gate=False, gate_ac
     return synth.from_torch(out), sel
 
 
-def run_decode_staggered(w, inp, n_total, offsets, tight_bound=True):
+def run_decode_staggered(w, inp, n_total, offsets, tight_bound=True, budget_policy=0):
     """Sequence b joins at step offsets[b] with an empty state and then appends one token per step through
     still_hybrid_attn_decode_step_at; before joining and after its last token it sits the step out (-1)."""
     import torch
@@ -68,7 +68,8 @@ def run_decode_staggered(w, inp, n_total, offsets, tight_bound=True):
     B = w.B
     out = torch.full((B, n_total, w.Hq, w.d), float("nan"), dtype=full["q"].dtype, device=dev)
     ps = S.make_params(B=B, N=1, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
-                       dtype=w.dtype, d_f=w.df, max_tokens=n_total, max_retained=w.max_retained, shared_selection=w.shared_selection)
+                       dtype=w.dtype, d_f=w.df, max_tokens=n_total, max_retained=w.max_retained, shared_selection=w.shared_selection,
+                       budget_policy=budget_policy)
     state = torch.empty(S.still_state_bytes(ps), dtype=torch.uint8, device=dev)
     S.still_state_init(ps, state)
     ar = torch.arange(B, device=dev)
@@ -333,6 +334,15 @@ def test_decode_sequences_at_their_own_positions(kw, n_total, offsets, tight):
     w = wl("decat", **kw)
     inp = synth.make_inputs(w, seed=24, n_tokens=n_total)
     check_decode(w, inp, 0, n_total, result=run_decode_staggered(w, inp, n_total, offsets, tight_bound=tight))
+
+
+def test_decode_sequences_at_their_own_positions_with_eviction_policy():
+    """The same with the budget held by eviction: every sequence evicts at its own routing steps."""
+    w = wl("decatev", dtype="f32", d=64, C=64, W=64, B=3, lam=16, max_retained=24)
+    n_total, offsets = 420, [64, 0, 1]
+    inp = synth.make_inputs(w, seed=32, n_tokens=n_total)
+    check_decode(w, inp, 0, n_total, budget_policy=1,
+                 result=run_decode_staggered(w, inp, n_total, offsets, tight_bound=False, budget_policy=1))
 
 
 def test_decode_step_at_replays_from_a_hip_graph():
