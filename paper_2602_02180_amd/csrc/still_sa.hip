@@ -661,14 +661,21 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
       });
     };
     sa_qk<T, D>(Kl + ((ti + 1) & 1) * Cf::K_ELEMS, qf, st_next, r, g, issue);
-    sa_softmax_pv<T, D, 0>(Vl + (ti & 1) * Cf::V_ELEMS, st_cur, o, m_ref, lpart, ti * BN, ret_w, lo_w, t, sc2, r, g);
+    if constexpr (EV) {   // every offer of the tile exists for this wave; which of them are retained is in the mask
+      const unsigned long long bits = tile_bits(ti);
+      if (bits != 0ull)
+        sa_softmax_pv<T, D, 3>(Vl + (ti & 1) * Cf::V_ELEMS, st_cur, o, m_ref, lpart, ti * BN, ret_w, lo_w, t, sc2, r, g,
+                               bits);
+    } else {
+      sa_softmax_pv<T, D, 0>(Vl + (ti & 1) * Cf::V_ELEMS, st_cur, o, m_ref, lpart, ti * BN, ret_w, lo_w, t, sc2, r, g);
+    }
     wait_async_copies();
     lds_barrier();
   };
   int ti = 0;
   {
     // last even ti (exclusive) such that tiles ti+1 (fully visible) and ti+2, ti+3 (retained) qualify
-    int n_steady = (wave_active && !EV) ? ret_w / BN - 1 : 0;    // ti + 1 < ret_w / BN  for both steps of a trip
+    int n_steady = wave_active ? ret_w / BN - 1 : 0;             // ti + 1 < ret_w / BN  for both steps of a trip
     if (n_steady > n_ret_tiles - 3) n_steady = n_ret_tiles - 3;  // ti + 3 < n_ret_tiles
     n_steady = __builtin_amdgcn_readfirstlane(n_steady);
     for (; ti < n_steady; ti += 2) {
