@@ -88,7 +88,8 @@ __global__ __launch_bounds__(kPlanThreads) void evict_plan_kernel(EvictPlanArgs 
     // the chunk's offers, sorted among themselves
     if (tid < lam) s_raw[tid] = next_key;
     if (tid == 0) s_eold = 0;
-    lds_barrier();
+    lds_barrier();                        // (also: every thread has finished the previous step's mask row)
+    for (int i = tid; i < 2 * a.AW; i += kPlanThreads) words[i] = 0u;
     fetch_offer(s + 1);
     if (tid < lam) {
       const unsigned long long mine = s_raw[tid];
@@ -146,7 +147,6 @@ __global__ __launch_bounds__(kPlanThreads) void evict_plan_kernel(EvictPlanArgs 
     n = n_old_s + n_new_s;
     cur ^= 1;
     // the set the rows of chunk s+2 see, as one bit per offer in routing order
-    for (int i = tid; i < 2 * a.AW; i += kPlanThreads) words[i] = 0u;
     lds_barrier();
     if (s + 2 < nc) {
       for (int i = tid; i < n; i += kPlanThreads) atomicOr(&words[snew[i] >> 5], 1u << (snew[i] & 31));
@@ -161,7 +161,6 @@ __global__ __launch_bounds__(kPlanThreads) void evict_plan_kernel(EvictPlanArgs 
       }
       if (tid == 0) a.fin_n[unit] = n;
     }
-    lds_barrier();
   }
 }
 
