@@ -1,7 +1,8 @@
 /*
- * libstill - forward hot path of STILL's intra-layer hybrid attention on AMD MI355X (gfx950).
+ * libstill - hot path of STILL's intra-layer hybrid attention on AMD MI355X (gfx950).
  *
- * One Transformer layer's attention operator from "STILL" (arXiv 2602.02180), forward only:
+ * One Transformer layer's attention operator from "STILL" (arXiv 2602.02180), forward (prefill and decode) and the
+ * backward pass of the prefill:
  *   - Self-Saliency Score over a causal sliding window            (Sec. 3.1, score equation)
  *   - delayed, chunk-granular Top-lambda routing                   (Sec. 3.3, delayed-selection eq.)
  *   - softmax attention over the salient cache (local span + retained tokens)
@@ -137,6 +138,8 @@ typedef struct still_ws_layout {
   size_t ev_fin;   /* budget_policy 1: the set retained after the last routed step: int32 tok [B,Hq,M], float score
                       [B,Hq,M], int32 count [B,Hq]                                                           */
   size_t ev_vfr;   /* dtype   [B, Hq, Npad * d]   budget_policy 1: v in operand order per query head, through ev_src */
+  size_t lse;      /* float   [B, Hq, N]          ln(D_SA + D_LA) of every row: the log of the shared normaliser of the
+                      output equation, written by every prefill call; still_hybrid_attn_bwd reads it           */
   size_t total;    /* bytes needed                                                                         */
   int32_t n_pad;   /* Npad                                                                                 */
   int32_t cap;     /* retained-row capacity (multiple of 64)                                               */
@@ -177,7 +180,7 @@ STILL_API still_status_t still_fwd_workspace_layout(const still_params_t* p, sti
  *                  on return it holds the tokens 0..N-1, so the next decode step is t = N.  Its previous
  *                  contents are overwritten (no still_state_init needed)
  *   workspace      device scratch of at least still_fwd_workspace_bytes(p) bytes; contents undefined
- *                  afterwards
+ *                  afterwards, except the regions the layout documents as results (score, sel, lse)
  *   stream         hipStream_t (as void*)
  *
  * Ties in the Top-lambda step go to the lower token index.  NaN inputs give undefined routing.
@@ -326,6 +329,62 @@ STILL_API still_status_t still_global_score(const still_params_t* p, const void*
                                             void* stream);
 STILL_API still_status_t still_selection_overlap(const still_params_t* p, const float* score_a, const float* score_b,
                                                  int32_t* overlap, void* stream);
+
+/*
+ * Backward pass of the prefill.  The paper trains the operator (Sec. 4.1: attention transfer for the feature maps
+ * and the gate, then low-rank adaptation of the projections) without printing its gradients; what is differentiated
+ * here is the output equation of Sec. 3.3, y = (N_SA + g N_LA) / (D_SA + D_LA), through the softmax branch's
+ * exponentials, the linear branch's phi_q . phi_k weights and the NP-Map of Sec. 3.2, for the index lists the forward
+ * pass chose: the Top-lambda selection is a discrete decision and passes no gradient, and the Self-Saliency Score
+ * only feeds that decision.
+ *
+ *   q, k, v, g, Wq, bq, Wk, bk   as given to still_hybrid_attn_fwd (same `p`, same strides)
+ *   out            device, dtype: the forward pass's result
+ *   dout           device, dtype, strided like out: gradient of the loss w.r.t. out
+ *   lse            device float [B, Hq, N]: region `lse` of the forward call's workspace (ln of the shared normaliser)
+ *   sel_idx        device int32 [B, Hq, N/C, lambda]: the forward call's index lists (its sel_idx, or region `sel`
+ *                  of its workspace); may be NULL when lambda = 0 or N < C.  Entries outside their chunk are ignored
+ *   dq, dk, dv     device, dtype, strided like q, k, v: gradients (dk, dv summed over the query heads of a kv head)
+ *   dg             device, dtype, strided like g; given exactly when g is.  With gate_activation = 1 it is the
+ *                  gradient w.r.t. the pre-activation
+ *   dWq, dWk       device FLOAT [Hq, d, d_f]; dbq, dbk device FLOAT [Hq, d_f], given exactly when bq, bk are.
+ *                  Parameter gradients are sums over every token of the batch and are returned in fp32
+ *   workspace      device scratch of at least still_bwd_workspace_bytes(p) bytes
+ *
+ * Covers budget_policy 0 (with or without max_retained), both selection modes, both gate modes; d = 64 or 128 in
+ * bf16, d = 64 in fp32; not right-padded batches (seq_len must be NULL).  dk, dv and the parameter gradients are
+ * accumulated with floating-point atomic adds: results are reproducible to rounding, not bit for bit.
+ * Validation on the host before any launch, as everywhere.
+ */
+typedef struct still_bwd_ws_layout {
+  size_t fwd;      /* a forward workspace (still_ws_layout_t offsets apply from here): the states are rebuilt   */
+  size_t e_row;    /* float [B, Hq, N]        E_t = exp(-lse_t)                                               */
+  size_t delta;    /* float [B, Hq, N]        dout_t . out_t                                                  */
+  size_t ed;       /* float [B, Hq, N]        E_t * delta_t                                                   */
+  size_t a;        /* dtype [B, Hq, N, d]     E_t (gate_t * dout_t)                                           */
+  size_t phi_q;    /* dtype [B, Hq, N, 2*d_f] feature map of the queries                                      */
+  size_t phi_k;    /* dtype [B, Hq, N, 2*d_f] feature map of the keys, zero for the selected tokens           */
+  size_t uq, uk;   /* float [B, Hq, N, d_f]   rescaled pre-activations u of Sec. 3.2                          */
+  size_t stq, stk; /* float [B, Hq, N, 2]     |x|, |f(x)|                                                     */
+  size_t nraw;     /* float [B, Hq, N, d]     phi_q S (the ungated linear numerator)                          */
+  size_t gq;       /* float [B, Hq, N, 2*d_f] S A_t                                                           */
+  size_t dphi_k;   /* float [B, Hq, N, 2*d_f] dS v_j                                                          */
+  size_t ds;       /* float [B, Hq, ceil(N/C), 2*d_f, d]  gradient of the state the rows of chunk c+2 and later read */
+  size_t dz;       /* float [B, Hq, ceil(N/C), 2*d_f]     likewise for z                                       */
+  size_t dfq, dfk; /* dtype [B, Hq, N, d_f]   gradient of f(x)                                                */
+  size_t dq32;     /* float [B, Hq, N, d]                                                                     */
+  size_t dk32, dv32; /* float [B, Hkv, N, d]                                                                  */
+  size_t total;
+} still_bwd_ws_layout_t;
+STILL_API size_t still_bwd_workspace_bytes(const still_params_t* p);
+STILL_API still_status_t still_bwd_workspace_layout(const still_params_t* p, still_bwd_ws_layout_t* layout);
+STILL_API still_status_t still_hybrid_attn_bwd(const still_params_t* p,
+                                     const void* q, const void* k, const void* v, const void* g,
+                                     const void* Wq, const void* bq, const void* Wk, const void* bk,
+                                     const void* out, const void* dout, const float* lse, const int32_t* sel_idx,
+                                     void* dq, void* dk, void* dv, void* dg,
+                                     float* dWq, float* dbq, float* dWk, float* dbk,
+                                     void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

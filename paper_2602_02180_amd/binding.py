@@ -38,7 +38,7 @@ class StillParams(ct.Structure):
 
 class StillWsLayout(ct.Structure):
     _fields_ = [(n, ct.c_size_t) for n in
-                ("score", "sel", "vt", "kret", "vrett", "wqt", "wkf", "seg", "snap", "zsnap", "pimg", "zpre", "kmask", "n_la", "d_la", "vfr", "ev_src", "ev_alive", "ev_fin", "ev_vfr", "total")] + \
+                ("score", "sel", "vt", "kret", "vrett", "wqt", "wkf", "seg", "snap", "zsnap", "pimg", "zpre", "kmask", "n_la", "d_la", "vfr", "ev_src", "ev_alive", "ev_fin", "ev_vfr", "lse", "total")] + \
                [(n, ct.c_int32) for n in ("n_pad", "cap", "nseg", "seg_chunks")]
 
 
@@ -46,6 +46,12 @@ class StillStateLayout(ct.Structure):
     _fields_ = [(n, ct.c_size_t) for n in
                 ("S", "kret", "vret", "sel", "kring", "vring", "score", "part", "ret_score", "ret_tok", "total")] + \
                [(n, ct.c_int32) for n in ("cap", "R", "n_chunks")]
+
+
+class StillBwdWsLayout(ct.Structure):
+    _fields_ = [(n, ct.c_size_t) for n in
+                ("fwd", "e_row", "delta", "ed", "a", "phi_q", "phi_k", "uq", "uk", "stq", "stk", "nraw", "gq",
+                 "dphi_k", "ds", "dz", "dfq", "dfk", "dq32", "dk32", "dv32", "total")]
 
 
 class StillError(RuntimeError):
@@ -96,6 +102,12 @@ def lib() -> ct.CDLL:
         L.still_global_score.argtypes = [pp, vp, vp, vp, vp]
         L.still_selection_overlap.restype = ct.c_int
         L.still_selection_overlap.argtypes = [pp, vp, vp, vp, vp]
+        L.still_bwd_workspace_bytes.restype = ct.c_size_t
+        L.still_bwd_workspace_bytes.argtypes = [pp]
+        L.still_bwd_workspace_layout.restype = ct.c_int
+        L.still_bwd_workspace_layout.argtypes = [pp, ct.POINTER(StillBwdWsLayout)]
+        L.still_hybrid_attn_bwd.restype = ct.c_int
+        L.still_hybrid_attn_bwd.argtypes = [pp] + [vp] * 20 + [vp, ct.c_size_t, vp]
         L.still_profile_enable.restype = None
         L.still_profile_enable.argtypes = [ct.c_int32]
         L.still_profile_read.restype = ct.c_int
@@ -205,6 +217,33 @@ def still_hybrid_attn_fwd_static(p: StillParams, q, k, v, g, Wq, bq, Wk, bk, out
     _check(lib().still_hybrid_attn_fwd_static(
         ct.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(out),
         _ptr(score_out), _ptr(sel_idx), 1 if sel_idx_is_input else 0, _ptr(state_out), stream.cuda_stream))
+
+
+def still_bwd_workspace_bytes(p: StillParams) -> int:
+    n = lib().still_bwd_workspace_bytes(ct.byref(p))
+    if n == 0:
+        raise StillError(STILL_ERR_INVALID_ARG, still_last_error())
+    return n
+
+
+def still_bwd_workspace_layout(p: StillParams) -> StillBwdWsLayout:
+    L = StillBwdWsLayout()
+    _check(lib().still_bwd_workspace_layout(ct.byref(p), ct.byref(L)))
+    return L
+
+
+def still_hybrid_attn_bwd(p: StillParams, q, k, v, g, Wq, bq, Wk, bk, out, dout, lse, sel_idx, dq, dk, dv, dg,
+                          dWq, dbq, dWk, dbk, workspace, stream=None) -> None:
+    """Enqueue the backward pass of the prefill on `stream` (default: torch's current stream)."""
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(lib().still_hybrid_attn_bwd(
+        ct.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(out),
+        _ptr(dout), _ptr(lse), _ptr(sel_idx), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _ptr(dWq), _ptr(dbq),
+        _ptr(dWk), _ptr(dbk), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), stream.cuda_stream))
 
 
 def still_state_bytes(p: StillParams) -> int:

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libstill.so")
 SOURCES = ["still_api.hip", "still_score.hip", "still_prep.hip", "still_la.hip", "still_sa.hip",
-           "still_decode.hip", "still_gscore.hip", "still_evict.hip"]  # files not yet present are skipped
+           "still_decode.hip", "still_gscore.hip", "still_evict.hip", "still_bwd.hip"]  # files not yet present are skipped
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -225,6 +225,7 @@ void compute_layout(const still_params_t* p, still_ws_layout_t* L) {
   L->ev_alive = take(evict ? (size_t)B * Hq * nc * (cap / 64) * 8 : 0);
   L->ev_fin = take(evict ? (size_t)B * Hq * (2 * M + 1) * 4 : 0);
   L->ev_vfr = take(evict ? (size_t)B * Hq * d * npad * es : 0);
+  L->lse = take((size_t)B * Hq * N * 4);
   L->total = off;
   L->n_pad = (int32_t)npad;
   L->cap = (int32_t)cap;
@@ -549,6 +550,7 @@ still_status_t fwd_impl(const still_params_t* p, const void* q, const void* k, c
   sx.pimg = la.pimg; sx.zpre = la.zpre; sx.seg_chunks = L.seg_chunks; sx.nseg = L.nseg;
   sx.n_la_out = p->emit_terms ? reinterpret_cast<float*>(ws + L.n_la) : nullptr;
   sx.d_la_out = p->emit_terms ? reinterpret_cast<float*>(ws + L.d_la) : nullptr;
+  sx.lse = reinterpret_cast<float*>(ws + L.lse);
   sx.out = out; sx.o_sb = p->o_sb; sx.o_st = p->o_st; sx.o_sh = p->o_sh;
   sx.map = map;
   sx.N = N; sx.Np = L.n_pad; sx.C = C; sx.lam = have_sel ? p->lambda : 0; sx.Hq = p->Hq; sx.Hkv = p->Hkv;
@@ -794,6 +796,310 @@ still_status_t still_selection_overlap(const still_params_t* p, const float* sco
   if (e != hipSuccess) return fail(STILL_ERR_HIP, "selection_overlap: %s", hipGetErrorString(e));
   g_err[0] = 0;
   return STILL_OK;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------------------------------
+// Backward pass of the prefill (the routing held fixed)
+// ---------------------------------------------------------------------------------------------------------
+namespace {
+
+still_status_t validate_bwd_params(const still_params_t* p) {
+  still_status_t st = validate_params(p, true);
+  if (st != STILL_OK) return st;
+  if (p->budget_policy != 0) return fail(STILL_ERR_UNSUPPORTED, "the backward pass does not cover budget_policy 1");
+  if (p->seq_len != nullptr) return fail(STILL_ERR_UNSUPPORTED, "the backward pass does not cover right-padded batches");
+  if (p->dtype == STILL_F32 && p->d != 64)
+    return fail(STILL_ERR_UNSUPPORTED, "the backward pass in fp32 is built for d = 64 only");
+  return STILL_OK;
+}
+
+void compute_bwd_layout(const still_params_t* p, still_bwd_ws_layout_t* L) {
+  still_ws_layout_t F;
+  compute_layout(p, &F);
+  const size_t es = esize(p->dtype);
+  const size_t U = (size_t)p->B * p->Hq, N = p->N, d = p->d, df = p->d_f, DP = 2 * df;
+  const size_t nc = (N + p->C - 1) / p->C, rows = U * N, kvrows = (size_t)p->B * p->Hkv * N;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + (bytes ? bytes : 16), 256);
+    return o;
+  };
+  L->fwd = take(F.total);
+  L->e_row = take(rows * 4);
+  L->delta = take(rows * 4);
+  L->ed = take(rows * 4);
+  L->a = take(rows * d * es);
+  L->phi_q = take(rows * DP * es);
+  L->phi_k = take(rows * DP * es);
+  L->uq = take(rows * df * 4);
+  L->uk = take(rows * df * 4);
+  L->stq = take(rows * 2 * 4);
+  L->stk = take(rows * 2 * 4);
+  L->nraw = take(rows * d * 4);
+  L->gq = take(rows * DP * 4);
+  L->dphi_k = take(rows * DP * 4);
+  L->ds = take(U * nc * DP * d * 4);
+  L->dz = take(U * nc * DP * 4);
+  L->dfq = take(rows * df * es);
+  L->dfk = take(rows * df * es);
+  L->dq32 = take(rows * d * 4);
+  L->dk32 = take(kvrows * d * 4);
+  L->dv32 = take(kvrows * d * 4);
+  L->total = off;
+}
+
+still::GemmOperand operand(const void* base, int64_t s_b, int64_t s_h, int64_t s_c, int64_t s_r, int64_t s_k,
+                           int kv = 0, int f32 = 0, int c_div = 1) {
+  still::GemmOperand o;
+  o.base = base; o.s_b = s_b; o.s_h = s_h; o.s_c = s_c; o.s_r = s_r; o.s_k = s_k;
+  o.kv = kv; o.c_div = c_div; o.f32 = f32;
+  return o;
+}
+
+still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, const void* v, const void* g,
+                        const void* Wq, const void* bq, const void* Wk, const void* bk, const void* out,
+                        const void* dout, const float* lse, const int32_t* sel_idx, void* dq, void* dk, void* dv,
+                        void* dg, float* dWq, float* dbq, float* dWk, float* dbk, void* workspace,
+                        size_t workspace_bytes, void* stream_v) {
+  still_status_t st = validate_bwd_params(p);
+  if (st != STILL_OK) return st;
+  st = validate_strides(p, g != nullptr);
+  if (st != STILL_OK) return st;
+  if (!q || !k || !v || !Wq || !Wk || !out || !dout || !lse || !dq || !dk || !dv || !dWq || !dWk || !workspace)
+    return fail(STILL_ERR_INVALID_ARG,
+                "a required pointer (q, k, v, Wq, Wk, out, dout, lse, dq, dk, dv, dWq, dWk, workspace) is NULL");
+  if ((g != nullptr) != (dg != nullptr)) return fail(STILL_ERR_INVALID_ARG, "dg must be given exactly when g is");
+  if ((bq != nullptr) != (dbq != nullptr) || (bk != nullptr) != (dbk != nullptr))
+    return fail(STILL_ERR_INVALID_ARG, "dbq / dbk must be given exactly when bq / bk are");
+  const int B = p->B, N = p->N, d = p->d, C = p->C, F = p->d_f, DP = 2 * F, Hq = p->Hq, Hkv = p->Hkv;
+  const int nc = (N + C - 1) / C, ncf = N / C, U = B * Hq;
+  const bool have_sel = p->lambda > 0 && ncf > 0;
+  if (have_sel && sel_idx == nullptr)
+    return fail(STILL_ERR_INVALID_ARG, "sel_idx (the forward pass's index lists) is NULL");
+  const void* ptrs[] = {q, k, v, g, Wq, bq, Wk, bk, out, dout, lse, sel_idx, dq, dk, dv, dg, dWq, dbq, dWk, dbk, workspace};
+  for (const void* x : ptrs)
+    if (x != nullptr && !aligned16(x)) return fail(STILL_ERR_INVALID_ARG, "pointer %p is not 16-byte aligned", x);
+  still_bwd_ws_layout_t BL;
+  compute_bwd_layout(p, &BL);
+  if (workspace_bytes < BL.total)
+    return fail(STILL_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, BL.total);
+  still_ws_layout_t L;
+  compute_layout(p, &L);
+
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  unsigned char* bws = static_cast<unsigned char*>(workspace);
+  unsigned char* ws = bws + BL.fwd;
+  still::HeadMap map;
+  fill_map(p, &map);
+  const int dt = p->dtype;
+  const int budget = retained_budget(p);
+  hipError_t e;
+  auto hip_fail = [&](const char* what, hipError_t err) -> still_status_t {
+    return fail(STILL_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
+  };
+  auto f32p = [&](size_t off) { return reinterpret_cast<float*>(bws + off); };
+  const int64_t rows = (int64_t)U * N, kvrows = (int64_t)B * Hkv * N;
+
+  // ---- outputs and accumulators that are added into
+  if ((e = still::launch_fill_f32(f32p(BL.dk32), kvrows * d, 0.f, stream)) != hipSuccess ||
+      (e = still::launch_fill_f32(f32p(BL.dv32), kvrows * d, 0.f, stream)) != hipSuccess ||
+      (e = still::launch_fill_f32(dWq, (int64_t)Hq * d * F, 0.f, stream)) != hipSuccess ||
+      (e = still::launch_fill_f32(dWk, (int64_t)Hq * d * F, 0.f, stream)) != hipSuccess ||
+      (dbq && (e = still::launch_fill_f32(dbq, (int64_t)Hq * F, 0.f, stream)) != hipSuccess) ||
+      (dbk && (e = still::launch_fill_f32(dbk, (int64_t)Hq * F, 0.f, stream)) != hipSuccess))
+    return hip_fail("fill", e);
+
+  // ---- the forward pass's linear-attention states, rebuilt from the index lists (same kernels as the prefill)
+  still::TransposeVArgs tv{v, p->v_sb, p->v_st, p->v_sh, ws + L.vt, ws + L.vfr, N, L.n_pad, Hkv, d, C, nullptr};
+  if ((e = still::launch_transpose_v(tv, dt, B, stream)) != hipSuccess) return hip_fail("transpose_v", e);
+  still::TransposeWArgs twk{Wk, ws + L.wkf, Hq, d, F, 1};
+  if ((e = still::launch_transpose_w(twk, dt, stream)) != hipSuccess) return hip_fail("transpose_w", e);
+  still::KeepMaskArgs km{sel_idx, reinterpret_cast<uint32_t*>(ws + L.kmask), Hq, ncf, C, have_sel ? p->lambda : 0,
+                         budget};
+  if ((e = still::launch_keep_mask(km, B, stream)) != hipSuccess) return hip_fail("keep_mask", e);
+  still::LaArgs la{};
+  la.k = k;
+  la.k_sb = p->k_sb; la.k_st = p->k_st; la.k_sh = p->k_sh;
+  la.vfr = ws + L.vfr; la.wkf = ws + L.wkf; la.bk = bk;
+  la.kmask = reinterpret_cast<const uint32_t*>(ws + L.kmask);
+  la.map = map;
+  la.N = N; la.Np = L.n_pad; la.C = C; la.Hq = Hq; la.Hkv = Hkv;
+  la.nc = nc; la.ncf = ncf; la.seq_len = nullptr;
+  la.seg_chunks = L.seg_chunks; la.nseg = L.nseg;
+  la.seg = reinterpret_cast<float*>(ws + L.seg);
+  la.snap = ws + L.snap;
+  la.zsnap = reinterpret_cast<float*>(ws + L.zsnap);
+  la.pimg = ws + L.pimg;
+  la.zpre = reinterpret_cast<float*>(ws + L.zpre);
+  la.s_final = nullptr;
+  if ((e = still::launch_la_states(la, dt, d, B, stream)) != hipSuccess) return hip_fail("la_states", e);
+  if ((e = still::launch_la_prefix(la, dt, d, B, stream)) != hipSuccess) return hip_fail("la_prefix", e);
+
+  // ---- per-row scalars and A_t = E_t (gate_t * dy_t)
+  still::BwdRowArgs ra{};
+  ra.out = out; ra.dout = dout; ra.o_sb = p->o_sb; ra.o_st = p->o_st; ra.o_sh = p->o_sh;
+  ra.g = g; ra.g_sb = p->g_sb; ra.g_st = p->g_st; ra.g_sh = p->g_sh; ra.gate_act = p->gate_activation != 0;
+  ra.lse = lse; ra.e_row = f32p(BL.e_row); ra.delta = f32p(BL.delta); ra.ed = f32p(BL.ed);
+  ra.A = bws + BL.a; ra.nraw = f32p(BL.nraw); ra.dg = dg;
+  ra.U = U; ra.N = N; ra.Hq = Hq; ra.d = d;
+  if ((e = still::launch_bwd_row_prep(ra, dt, stream)) != hipSuccess) return hip_fail("bwd_row_prep", e);
+
+  // ---- softmax branch: dq (owned rows), dk / dv (atomic adds per key tile)
+  still::BwdSaArgs sa{};
+  sa.q = q; sa.k = k; sa.v = v; sa.dout = dout;
+  sa.q_sb = p->q_sb; sa.q_st = p->q_st; sa.q_sh = p->q_sh;
+  sa.k_sb = p->k_sb; sa.k_st = p->k_st; sa.k_sh = p->k_sh;
+  sa.v_sb = p->v_sb; sa.v_st = p->v_st; sa.v_sh = p->v_sh;
+  sa.o_sb = p->o_sb; sa.o_st = p->o_st; sa.o_sh = p->o_sh;
+  sa.sel = sel_idx; sa.lse = lse; sa.delta = ra.delta;
+  sa.dq32 = f32p(BL.dq32); sa.dk32 = f32p(BL.dk32); sa.dv32 = f32p(BL.dv32);
+  sa.map = map;
+  sa.N = N; sa.C = C; sa.lam = have_sel ? p->lambda : 0; sa.rcap = budget; sa.Hq = Hq; sa.Hkv = Hkv; sa.nc = nc;
+  sa.sel_stride = ncf * p->lambda;
+  sa.n_row_tiles = (N + 63) / 64;
+  sa.n_ret_tiles = (still::retained_rows(nc >= 2 ? nc - 2 : 0, sa.lam, budget) + 63) / 64;
+  sa.scale = p->scale;
+  if ((e = still::launch_bwd_sa(sa, dt, d, U, stream)) != hipSuccess) return hip_fail("bwd_sparse_attention", e);
+
+  // ---- NP-Map of q and k again: f = x W on the matrix core, then phi, u and the norms per token
+  still::GemmArgs gm{};
+  gm.Hq = Hq; gm.map = map;
+  auto product = [&](const still::GemmOperand& A_, const still::GemmOperand& B_, float* Cp, int64_t c_b, int64_t c_h,
+                     int64_t c_c, int64_t c_r, int c_kv, int M_, int Nn_, int K_, int m_total, int k_total, int mode,
+                     int n_c) -> hipError_t {
+    gm.A = A_; gm.B = B_; gm.C = Cp; gm.c_b = c_b; gm.c_h = c_h; gm.c_c = c_c; gm.c_r = c_r; gm.c_kv = c_kv;
+    gm.M = M_; gm.Nn = Nn_; gm.K = K_; gm.m_total = m_total; gm.k_total = k_total; gm.mode = mode;
+    return still::launch_bgemm(gm, dt, U, n_c, stream);
+  };
+  const int64_t NF = (int64_t)N * F, NDP = (int64_t)N * DP, ND = (int64_t)N * d;
+  const still::GemmOperand q_rows = operand(q, p->q_sb, p->q_sh, (int64_t)C * p->q_st, p->q_st, 1);
+  const still::GemmOperand k_rows = operand(k, p->k_sb, p->k_sh, (int64_t)C * p->k_st, p->k_st, 1, 1);
+  const still::GemmOperand v_rows = operand(v, p->v_sb, p->v_sh, (int64_t)C * p->v_st, p->v_st, 1, 1);
+  const still::GemmOperand wq_fx = operand(Wq, 0, (int64_t)d * F, 0, 1, F);   // (n = feature, k = x)
+  const still::GemmOperand wk_fx = operand(Wk, 0, (int64_t)d * F, 0, 1, F);
+  const still::GemmOperand wq_xf = operand(Wq, 0, (int64_t)d * F, 0, F, 1);   // (n = x, k = feature)
+  const still::GemmOperand wk_xf = operand(Wk, 0, (int64_t)d * F, 0, F, 1);
+  if ((e = product(q_rows, wq_fx, f32p(BL.uq), Hq * NF, NF, (int64_t)C * F, F, 0, C, F, d, N, 0, 0, nc)) != hipSuccess ||
+      (e = product(k_rows, wk_fx, f32p(BL.uk), Hq * NF, NF, (int64_t)C * F, F, 0, C, F, d, N, 0, 0, nc)) != hipSuccess)
+    return hip_fail("bwd f = x W", e);
+  still::BwdNpArgs nq{};
+  nq.x = q; nq.x_sb = p->q_sb; nq.x_st = p->q_st; nq.x_sh = p->q_sh; nq.x_kv = 0;
+  nq.bias = bq; nq.u = f32p(BL.uq); nq.st = f32p(BL.stq); nq.phi = bws + BL.phi_q; nq.kmask = nullptr;
+  nq.dphi = f32p(BL.gq); nq.coef = ra.ed; nq.z1 = la.zsnap; nq.z2 = la.zpre;
+  nq.df = bws + BL.dfq; nq.dx32 = f32p(BL.dq32);
+  nq.map = map; nq.U = U; nq.N = N; nq.Hq = Hq; nq.Hkv = Hkv; nq.d = d; nq.F = F; nq.C = C; nq.nc = nc; nq.ncf = ncf;
+  nq.nseg = L.nseg; nq.seg_chunks = L.seg_chunks;
+  still::BwdNpArgs nk = nq;
+  nk.x = k; nk.x_sb = p->k_sb; nk.x_st = p->k_st; nk.x_sh = p->k_sh; nk.x_kv = 1;
+  nk.bias = bk; nk.u = f32p(BL.uk); nk.st = f32p(BL.stk); nk.phi = bws + BL.phi_k; nk.kmask = la.kmask;
+  nk.dphi = f32p(BL.dphi_k); nk.coef = nullptr; nk.z1 = f32p(BL.dz); nk.z2 = nullptr;
+  nk.df = bws + BL.dfk; nk.dx32 = f32p(BL.dk32);
+  if ((e = still::launch_bwd_np(nq, dt, false, stream)) != hipSuccess ||
+      (e = still::launch_bwd_np(nk, dt, false, stream)) != hipSuccess)
+    return hip_fail("bwd_np_fwd", e);
+
+  // ---- query side of the linear branch: phi_q S (for dg) and S A (for dphi_q), against both state images
+  const still::GemmOperand phiq_rows = operand(bws + BL.phi_q, Hq * NDP, NDP, (int64_t)C * DP, DP, 1);
+  const still::GemmOperand a_rows = operand(bws + BL.a, Hq * ND, ND, (int64_t)C * d, d, 1);
+  const int64_t img = (int64_t)d * DP;
+  const still::GemmOperand snap_xf = operand(la.snap, Hq * nc * img, nc * img, img, DP, 1);        // (n = x, k = f)
+  const still::GemmOperand pimg_xf = operand(la.pimg, Hq * L.nseg * img, L.nseg * img, img, DP, 1, 0, 0, L.seg_chunks);
+  const still::GemmOperand snap_fx = operand(la.snap, Hq * nc * img, nc * img, img, 1, DP);        // (n = f, k = x)
+  const still::GemmOperand pimg_fx = operand(la.pimg, Hq * L.nseg * img, L.nseg * img, img, 1, DP, 0, 0, L.seg_chunks);
+  if ((e = product(phiq_rows, snap_xf, f32p(BL.nraw), Hq * ND, ND, (int64_t)C * d, d, 0, C, d, DP, N, 0, 0, nc)) != hipSuccess ||
+      (e = product(phiq_rows, pimg_xf, f32p(BL.nraw), Hq * ND, ND, (int64_t)C * d, d, 0, C, d, DP, N, 0, 1, nc)) != hipSuccess ||
+      (e = product(a_rows, snap_fx, f32p(BL.gq), Hq * NDP, NDP, (int64_t)C * DP, DP, 0, C, DP, d, N, 0, 0, nc)) != hipSuccess ||
+      (e = product(a_rows, pimg_fx, f32p(BL.gq), Hq * NDP, NDP, (int64_t)C * DP, DP, 0, C, DP, d, N, 0, 1, nc)) != hipSuccess)
+    return hip_fail("bwd query-side products", e);
+  if (g != nullptr && (e = still::launch_bwd_dg(ra, dt, stream)) != hipSuccess) return hip_fail("bwd_dg", e);
+
+  // ---- gradient of the states: per-chunk contributions, then the sum over the chunks two and more ahead
+  const still::GemmOperand phiq_ft = operand(bws + BL.phi_q, Hq * NDP, NDP, (int64_t)C * DP, 1, DP);   // (m = f, k = token)
+  const still::GemmOperand a_xt = operand(bws + BL.a, Hq * ND, ND, (int64_t)C * d, 1, d);              // (n = x, k = token)
+  const int64_t simg = (int64_t)DP * d;
+  if ((e = product(phiq_ft, a_xt, f32p(BL.ds), Hq * nc * simg, nc * simg, simg, d, 0, DP, d, C, 0, N, 0, nc)) != hipSuccess)
+    return hip_fail("bwd state contributions", e);
+  still::BwdColsumArgs cz{bws + BL.phi_q, ra.ed, f32p(BL.dz), N, C, nc, DP, Hq, 0};
+  if ((e = still::launch_bwd_colsum(cz, dt, U, stream)) != hipSuccess) return hip_fail("bwd_colsum", e);
+  if ((e = still::launch_bwd_revcumsum(f32p(BL.ds), U, nc, simg, stream)) != hipSuccess ||
+      (e = still::launch_bwd_revcumsum(f32p(BL.dz), U, nc, DP, stream)) != hipSuccess)
+    return hip_fail("bwd_revcumsum", e);
+
+  // ---- key side: dphi_k = v dS^T (- dz, in the NP-Map kernel), dv += phi_k dS
+  const still::GemmOperand ds_fx = operand(f32p(BL.ds), Hq * nc * simg, nc * simg, simg, d, 1, 0, 1);   // (n = f, k = x)
+  const still::GemmOperand ds_xf = operand(f32p(BL.ds), Hq * nc * simg, nc * simg, simg, 1, d, 0, 1);   // (n = x, k = f)
+  const still::GemmOperand phik_rows = operand(bws + BL.phi_k, Hq * NDP, NDP, (int64_t)C * DP, DP, 1);
+  if ((e = product(v_rows, ds_fx, f32p(BL.dphi_k), Hq * NDP, NDP, (int64_t)C * DP, DP, 0, C, DP, d, N, 0, 0, nc)) != hipSuccess ||
+      (e = product(phik_rows, ds_xf, f32p(BL.dv32), Hkv * ND, ND, (int64_t)C * d, d, 1, C, d, DP, N, 0, 2, nc)) != hipSuccess)
+    return hip_fail("bwd key-side products", e);
+
+  // ---- NP-Map backwards (df, and the |x| path of dx), then dx += df W^T and dW += x^T df
+  if ((e = still::launch_bwd_np(nq, dt, true, stream)) != hipSuccess ||
+      (e = still::launch_bwd_np(nk, dt, true, stream)) != hipSuccess)
+    return hip_fail("bwd_np_bwd", e);
+  const still::GemmOperand dfq_rows = operand(bws + BL.dfq, Hq * NF, NF, (int64_t)C * F, F, 1);
+  const still::GemmOperand dfk_rows = operand(bws + BL.dfk, Hq * NF, NF, (int64_t)C * F, F, 1);
+  if ((e = product(dfq_rows, wq_xf, f32p(BL.dq32), Hq * ND, ND, (int64_t)C * d, d, 0, C, d, F, N, 0, 1, nc)) != hipSuccess ||
+      (e = product(dfk_rows, wk_xf, f32p(BL.dk32), Hkv * ND, ND, (int64_t)C * d, d, 1, C, d, F, N, 0, 2, nc)) != hipSuccess)
+    return hip_fail("bwd dx += df W^T", e);
+  const int KS = 256, nsplit = (N + KS - 1) / KS;   // tokens per split of the sum over tokens
+  const still::GemmOperand q_xt = operand(q, p->q_sb, p->q_sh, (int64_t)KS * p->q_st, 1, p->q_st);       // (m = x, k = token)
+  const still::GemmOperand k_xt = operand(k, p->k_sb, p->k_sh, (int64_t)KS * p->k_st, 1, p->k_st, 1);
+  const still::GemmOperand dfq_ft = operand(bws + BL.dfq, Hq * NF, NF, (int64_t)KS * F, 1, F);           // (n = f, k = token)
+  const still::GemmOperand dfk_ft = operand(bws + BL.dfk, Hq * NF, NF, (int64_t)KS * F, 1, F);
+  if ((e = product(q_xt, dfq_ft, dWq, 0, (int64_t)d * F, 0, F, 0, d, F, KS, 0, N, 2, nsplit)) != hipSuccess ||
+      (e = product(k_xt, dfk_ft, dWk, 0, (int64_t)d * F, 0, F, 0, d, F, KS, 0, N, 2, nsplit)) != hipSuccess)
+    return hip_fail("bwd dW += x^T df", e);
+  if (dbq != nullptr) {
+    still::BwdColsumArgs cb{bws + BL.dfq, nullptr, dbq, N, C, nc, F, Hq, 1};
+    if ((e = still::launch_bwd_colsum(cb, dt, U, stream)) != hipSuccess) return hip_fail("bwd db", e);
+  }
+  if (dbk != nullptr) {
+    still::BwdColsumArgs cb{bws + BL.dfk, nullptr, dbk, N, C, nc, F, Hq, 1};
+    if ((e = still::launch_bwd_colsum(cb, dt, U, stream)) != hipSuccess) return hip_fail("bwd db", e);
+  }
+
+  // ---- fp32 sums -> the caller's tensors
+  still::BwdFinishArgs fq{f32p(BL.dq32), dq, p->q_sb, p->q_st, p->q_sh, B, Hq, N, d};
+  still::BwdFinishArgs fk{f32p(BL.dk32), dk, p->k_sb, p->k_st, p->k_sh, B, Hkv, N, d};
+  still::BwdFinishArgs fv{f32p(BL.dv32), dv, p->v_sb, p->v_st, p->v_sh, B, Hkv, N, d};
+  if ((e = still::launch_bwd_finish(fq, dt, stream)) != hipSuccess ||
+      (e = still::launch_bwd_finish(fk, dt, stream)) != hipSuccess ||
+      (e = still::launch_bwd_finish(fv, dt, stream)) != hipSuccess)
+    return hip_fail("bwd_finish", e);
+  g_err[0] = 0;
+  return STILL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t still_bwd_workspace_bytes(const still_params_t* p) {
+  if (validate_bwd_params(p) != STILL_OK) return 0;
+  still_bwd_ws_layout_t L;
+  compute_bwd_layout(p, &L);
+  return L.total;
+}
+
+still_status_t still_bwd_workspace_layout(const still_params_t* p, still_bwd_ws_layout_t* layout) {
+  if (layout == nullptr) return fail(STILL_ERR_INVALID_ARG, "layout is NULL");
+  still_status_t st = validate_bwd_params(p);
+  if (st != STILL_OK) return st;
+  compute_bwd_layout(p, layout);
+  return STILL_OK;
+}
+
+still_status_t still_hybrid_attn_bwd(const still_params_t* p, const void* q, const void* k, const void* v,
+                                     const void* g, const void* Wq, const void* bq, const void* Wk, const void* bk,
+                                     const void* out, const void* dout, const float* lse, const int32_t* sel_idx,
+                                     void* dq, void* dk, void* dv, void* dg, float* dWq, float* dbq, float* dWk,
+                                     float* dbk, void* workspace, size_t workspace_bytes, void* stream) {
+  return bwd_impl(p, q, k, v, g, Wq, bq, Wk, bk, out, dout, lse, sel_idx, dq, dk, dv, dg, dWq, dbq, dWk, dbk,
+                  workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

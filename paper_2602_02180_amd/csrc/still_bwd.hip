@@ -1,0 +1,747 @@
+// Backward pass of the prefill operator, the routing held fixed (gfx950).
+//
+// What is differentiated is the output equation of Sec. 3.3, y = (N_SA + g N_LA) / (D_SA + D_LA), for the index
+// lists the forward pass chose: the Top-lambda selection is a discrete decision and passes no gradient, and the
+// Self-Saliency Score of Sec. 3.1 only feeds that decision.  With L_t = ln(D_SA + D_LA) (kept by the forward pass),
+// delta_t = dy_t . y_t and E_t = exp(-L_t):
+//   softmax branch, key j visible to row t through exp:   P_tj = exp(scale q_t.k_j - L_t)
+//        dv_j += P_tj dy_t          dl_tj = P_tj (dy_t . v_j - delta_t)
+//        dq_t += scale dl_tj k_j    dk_j += scale dl_tj q_t
+//   linear branch, S = sum phi_k(k_j)^T v_j and z = sum phi_k(k_j) over the un-selected tokens of chunks <= c-2:
+//        A_t = E_t (g_t * dy_t)                     (per channel)
+//        dphi_q(t) = S A_t - E_t delta_t z          dg_t = E_t dy_t * (phi_q(t) S)
+//        dS(c) = sum over the rows of chunks >= c+2 of phi_q(t)^T A_t,   dz(c) likewise of phi_q(t) E_t delta_t
+//        dphi_k(j) = dS(c_j) v_j - dz(c_j)          dv_j += dS(c_j)^T phi_k(j)
+//   and the NP-Map of Sec. 3.2 (f = x W + b, u = f |x| / |f|, phi = [softmax(u), softmax(-u)]) backwards:
+//        du = phi+ (dphi+ - <phi+, dphi+>) - phi- (dphi- - <phi-, dphi->)
+//        df = (|x| / |f|) (du - fh <fh, du>),  fh = f / |f|;   dx = df W^T + <fh, du> x / |x|;   dW = x^T df
+//
+// This first version keeps every step a separate, simple kernel: the sparse branch as two tile kernels (one that
+// owns query rows and produces dq, one that owns key tiles and produces dk, dv), the linear branch as a sequence of
+// batched products on one generic 64 x 64 MFMA tile kernel with element-wise kernels between them, intermediates in
+// the workspace.  All sums are fp32; operands of the matrix core are in the storage type.
+#include "still_kernels.h"
+
+namespace still {
+
+namespace {
+
+template <typename T>
+__device__ __forceinline__ float ld_as_f32(const void* base, int64_t off, int is_f32) {
+  return is_f32 ? static_cast<const float*>(base)[off] : to_f32<T>(static_cast<const T*>(base)[off]);
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Generic batched product on the matrix core: C[m][n] (=, +=, atomic +=) sum_k A(m, k) B(n, k), one 64 x 64 tile
+// of one batch item per workgroup (four waves, one 32 x 32 block each), both operands through LDS in the storage
+// type with the contraction index contiguous.  Operands are addressed through explicit strides, so a transposed
+// or fp32 operand costs nothing but element-wise loads.
+// ---------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void bgemm_kernel(GemmArgs a) {
+  typedef Mma<T> M;
+  constexpr int BK = 32;
+  constexpr int LDK = BK + (sizeof(T) == 2 ? 8 : 4);
+  __shared__ __attribute__((aligned(16))) T As[64 * LDK];
+  __shared__ __attribute__((aligned(16))) T Bs[64 * LDK];
+  const int unit = blockIdx.z, c = blockIdx.y;
+  const int ntn = a.Nn / 64;
+  const int mt = blockIdx.x / ntn, nt = blockIdx.x % ntn;
+  const int b = unit / a.Hq, h = unit % a.Hq, kvh = a.map.kv[h];
+  int m_valid = a.M, k_valid = a.K;
+  if (a.m_total > 0) m_valid = min(a.M, a.m_total - c * a.M);
+  if (a.k_total > 0) k_valid = min(a.K, a.k_total - c * a.K);
+  if (m_valid <= mt * 64 || k_valid <= 0) return;   // uniform over the workgroup
+  const int64_t a_off = b * a.A.s_b + (a.A.kv ? kvh : h) * a.A.s_h + (int64_t)(c / a.A.c_div) * a.A.s_c;
+  const int64_t b_off = b * a.B.s_b + (a.B.kv ? kvh : h) * a.B.s_h + (int64_t)(c / a.B.c_div) * a.B.s_c;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, g = lane >> 5;
+  const int wr = wave >> 1, wc = wave & 1;
+  floatx16 acc = zero16();
+  for (int k0 = 0; k0 < k_valid; k0 += BK) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int idx = tid + 256 * j;
+      {
+        int row, kk;
+        if (a.A.s_k == 1) { row = idx / BK; kk = idx % BK; } else { row = idx % 64; kk = idx / 64; }
+        const int mg = mt * 64 + row, kg = k0 + kk;
+        float x = 0.f;
+        if (mg < m_valid && kg < k_valid) x = ld_as_f32<T>(a.A.base, a_off + mg * a.A.s_r + kg * a.A.s_k, a.A.f32);
+        As[row * LDK + kk] = from_f32<T>(x);
+      }
+      {
+        int row, kk;
+        if (a.B.s_k == 1) { row = idx / BK; kk = idx % BK; } else { row = idx % 64; kk = idx / 64; }
+        const int ng = nt * 64 + row, kg = k0 + kk;
+        float x = 0.f;
+        if (kg < k_valid) x = ld_as_f32<T>(a.B.base, b_off + ng * a.B.s_r + kg * a.B.s_k, a.B.f32);
+        Bs[row * LDK + kk] = from_f32<T>(x);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < BK / M::KK; ++s) {
+      const typename M::frag af = M::load(As + (32 * wr + l31) * LDK + s * M::KK + g * M::KPL);
+      const typename M::frag bf = M::load(Bs + (32 * wc + l31) * LDK + s * M::KK + g * M::KPL);
+      acc = M::mma(af, bf, acc);
+    }
+    __syncthreads();
+  }
+  float* cp = a.C + b * a.c_b + (a.c_kv ? kvh : h) * a.c_h + (int64_t)c * a.c_c;
+  const int n = nt * 64 + 32 * wc + l31;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int m = mt * 64 + 32 * wr + c_row(i, g);
+    if (m < m_valid) {
+      float* dst = cp + (int64_t)m * a.c_r + n;
+      if (a.mode == 0) *dst = acc[i];
+      else if (a.mode == 1) *dst += acc[i];
+      else atomicAdd(dst, acc[i]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Element-wise kernels (one wave per token row unless said otherwise)
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_f32_kernel(float* p, int64_t n, float x) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = x;
+}
+
+// delta_t = dy_t . y_t, E_t = exp(-L_t), A_t = E_t (gate_t * dy_t)
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_row_prep_kernel(BwdRowArgs a) {
+  const int64_t row = blockIdx.x * 4ll + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= (int64_t)a.U * a.N) return;
+  const int unit = (int)(row / a.N), t = (int)(row % a.N);
+  const int b = unit / a.Hq, h = unit % a.Hq;
+  const T* y = static_cast<const T*>(a.out) + b * a.o_sb + (int64_t)t * a.o_st + h * a.o_sh;
+  const T* dy = static_cast<const T*>(a.dout) + b * a.o_sb + (int64_t)t * a.o_st + h * a.o_sh;
+  const T* gp = a.g ? static_cast<const T*>(a.g) + b * a.g_sb + (int64_t)t * a.g_st + h * a.g_sh : nullptr;
+  const float E = __expf(-a.lse[row]);
+  float dot = 0.f;
+  for (int x = lane; x < a.d; x += 64) {
+    const float dyx = to_f32<T>(dy[x]);
+    dot += dyx * to_f32<T>(y[x]);
+    float gate = 1.f;
+    if (gp) {
+      gate = to_f32<T>(gp[x]);
+      if (a.gate_act) gate = 1.f / (1.f + __expf(-gate));
+    }
+    static_cast<T*>(a.A)[row * a.d + x] = from_f32<T>(E * gate * dyx);
+  }
+  dot = wave_sum(dot);
+  if (lane == 0) {
+    a.e_row[row] = E;
+    a.delta[row] = dot;
+    a.ed[row] = E * dot;
+  }
+}
+
+// NP-Map forward from f = x W (bias added here): phi (storage type; zero for tokens the softmax branch keeps),
+// u over f in place, and (|x|, |f|).
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_np_fwd_kernel(BwdNpArgs a) {
+  const int64_t row = blockIdx.x * 4ll + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= (int64_t)a.U * a.N) return;
+  const int unit = (int)(row / a.N), t = (int)(row % a.N);
+  const int b = unit / a.Hq, h = unit % a.Hq;
+  const int hx = a.x_kv ? a.map.kv[h] : h;
+  const T* x = static_cast<const T*>(a.x) + b * a.x_sb + (int64_t)t * a.x_st + hx * a.x_sh;
+  const int F = a.F;
+  float* f = a.u + row * F;
+  const T* bias = a.bias ? static_cast<const T*>(a.bias) + h * F : nullptr;
+  float nx2 = 0.f;
+  for (int i = lane; i < a.d; i += 64) {
+    const float xv = to_f32<T>(x[i]);
+    nx2 += xv * xv;
+  }
+  float fv[2], nf2 = 0.f;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int i = lane + 64 * j;
+    fv[j] = 0.f;
+    if (i < F) {
+      fv[j] = f[i] + (bias ? to_f32<T>(bias[i]) : 0.f);
+      nf2 += fv[j] * fv[j];
+    }
+  }
+  nx2 = wave_sum(nx2);
+  nf2 = wave_sum(nf2);
+  const float nx = sqrtf(nx2), nf = sqrtf(nf2);
+  const float ratio = nf2 > 0.f ? nx / nf : 0.f;
+  float mp = -INFINITY, mn = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+    if (lane + 64 * j < F) {
+      fv[j] *= ratio;
+      mp = fmaxf(mp, fv[j]);
+      mn = fmaxf(mn, -fv[j]);
+    }
+  mp = wave_max(mp);
+  mn = wave_max(mn);
+  float ep[2], en[2], sp = 0.f, sn = 0.f;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    ep[j] = en[j] = 0.f;
+    if (lane + 64 * j < F) {
+      ep[j] = __expf(fv[j] - mp);
+      en[j] = __expf(-fv[j] - mn);
+      sp += ep[j];
+      sn += en[j];
+    }
+  }
+  sp = wave_sum(sp);
+  sn = wave_sum(sn);
+  bool kept = false;
+  if (a.kmask != nullptr && t < a.ncf * a.C) {
+    const int c = t / a.C, w = t % a.C;
+    kept = (a.kmask[((int64_t)unit * a.ncf + c) * (a.C / 32) + w / 32] >> (w & 31)) & 1u;
+  }
+  const float ip = kept ? 0.f : 1.f / sp, in = kept ? 0.f : 1.f / sn;
+  T* phi = static_cast<T*>(a.phi) + row * 2 * F;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int i = lane + 64 * j;
+    if (i < F) {
+      phi[i] = from_f32<T>(ep[j] * ip);
+      phi[F + i] = from_f32<T>(en[j] * in);
+      f[i] = fv[j];
+    }
+  }
+  if (lane == 0) {
+    a.st[2 * row] = nx;
+    a.st[2 * row + 1] = nf;
+  }
+}
+
+// NP-Map backward for one token: dphi (minus coef * z) -> df in the storage type, and the |x| path of dx added to the
+// fp32 gradient of x (plain add where the row is owned, atomic where query heads share a kv head).
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_np_bwd_kernel(BwdNpArgs a) {
+  const int64_t row = blockIdx.x * 4ll + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= (int64_t)a.U * a.N) return;
+  const int unit = (int)(row / a.N), t = (int)(row % a.N);
+  const int b = unit / a.Hq, h = unit % a.Hq;
+  const int hx = a.x_kv ? a.map.kv[h] : h;
+  const int F = a.F, c = t / a.C;
+  T* df = static_cast<T*>(a.df) + row * F;
+  bool kept = false;
+  if (a.kmask != nullptr && t < a.ncf * a.C) {
+    const int w = t % a.C;
+    kept = (a.kmask[((int64_t)unit * a.ncf + c) * (a.C / 32) + w / 32] >> (w & 31)) & 1u;
+  }
+  const float nx = a.st[2 * row], nf = a.st[2 * row + 1];
+  if (kept || !(nx > 0.f) || !(nf > 0.f)) {   // uniform over the wave
+    for (int i = lane; i < F; i += 64) df[i] = from_f32<T>(0.f);
+    return;
+  }
+  const float* u = a.u + row * F;
+  const float* dphi = a.dphi + row * 2 * F;
+  const float coef = a.coef ? a.coef[row] : 1.f;
+  const float* z1 = a.z1 + ((int64_t)unit * a.nc + c) * 2 * F;
+  const float* z2 = a.z2 ? a.z2 + ((int64_t)unit * a.nseg + c / a.seg_chunks) * 2 * F : nullptr;
+  float uv[2], mp = -INFINITY, mn = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+    if (lane + 64 * j < F) {
+      uv[j] = u[lane + 64 * j];
+      mp = fmaxf(mp, uv[j]);
+      mn = fmaxf(mn, -uv[j]);
+    }
+  mp = wave_max(mp);
+  mn = wave_max(mn);
+  float ep[2], en[2], dp[2], dn[2], sp = 0.f, sn = 0.f;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int i = lane + 64 * j;
+    ep[j] = en[j] = dp[j] = dn[j] = 0.f;
+    if (i < F) {
+      ep[j] = __expf(uv[j] - mp);
+      en[j] = __expf(-uv[j] - mn);
+      sp += ep[j];
+      sn += en[j];
+      dp[j] = dphi[i] - coef * (z1[i] + (z2 ? z2[i] : 0.f));
+      dn[j] = dphi[F + i] - coef * (z1[F + i] + (z2 ? z2[F + i] : 0.f));
+    }
+  }
+  sp = wave_sum(sp);
+  sn = wave_sum(sn);
+  float ap = 0.f, an = 0.f;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    ep[j] /= sp;
+    en[j] /= sn;
+    ap += ep[j] * dp[j];
+    an += en[j] * dn[j];
+  }
+  ap = wave_sum(ap);
+  an = wave_sum(an);
+  float du[2], dnx = 0.f;
+  const float inx = 1.f / nx;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    du[j] = ep[j] * (dp[j] - ap) - en[j] * (dn[j] - an);
+    if (lane + 64 * j < F) dnx += uv[j] * inx * du[j];
+  }
+  dnx = wave_sum(dnx);
+  const float ratio = nx / nf;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int i = lane + 64 * j;
+    if (i < F) df[i] = from_f32<T>(ratio * (du[j] - uv[j] * inx * dnx));
+  }
+  const T* x = static_cast<const T*>(a.x) + b * a.x_sb + (int64_t)t * a.x_st + hx * a.x_sh;
+  const int64_t xrow = a.x_kv ? ((int64_t)b * a.Hkv + hx) * a.N + t : row;
+  float* dx = a.dx32 + xrow * a.d;
+  for (int i = lane; i < a.d; i += 64) {
+    const float add = dnx * inx * to_f32<T>(x[i]);
+    if (a.x_kv) atomicAdd(dx + i, add);
+    else dx[i] += add;
+  }
+}
+
+// out[f] (per (unit, chunk), or added atomically per head) = sum over the chunk's tokens of X[t][f] * w[t]
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_colsum_kernel(BwdColsumArgs a) {
+  const int c = blockIdx.x, unit = blockIdx.y;
+  const int h = unit % a.Hq;
+  const int t0 = c * a.C, t1 = min(a.N, t0 + a.C);
+  const T* X = static_cast<const T*>(a.X) + ((int64_t)unit * a.N) * a.L;
+  for (int f = threadIdx.x; f < a.L; f += 256) {
+    float s = 0.f;
+    for (int t = t0; t < t1; ++t) s += to_f32<T>(X[(int64_t)t * a.L + f]) * (a.w ? a.w[(int64_t)unit * a.N + t] : 1.f);
+    if (a.per_head) atomicAdd(a.out + (int64_t)h * a.L + f, s);
+    else a.out[((int64_t)unit * a.nc + c) * a.L + f] = s;
+  }
+}
+
+// X[unit][c][l] <- sum over c' >= c + 2 of X[unit][c'][l]  (the rows of chunk c' see the state through chunk c'-2)
+__global__ __launch_bounds__(256) void bwd_revcumsum_kernel(float* X, int nc, int64_t L) {
+  const int64_t l = blockIdx.x * 256ll + threadIdx.x;
+  if (l >= L) return;
+  float* p = X + (int64_t)blockIdx.y * nc * L + l;
+  float s1 = 0.f, s2 = 0.f;
+  for (int c = nc - 1; c >= 0; --c) {
+    const float v = p[(int64_t)c * L];
+    p[(int64_t)c * L] = s2;
+    s2 = s1;
+    s1 += v;
+  }
+}
+
+// dg = E_t dy_t * (phi_q S)_t  (times the logistic function's slope when the gate is activated here)
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_dg_kernel(BwdRowArgs a) {
+  const int64_t n = (int64_t)a.U * a.N * a.d;
+  for (int64_t i = blockIdx.x * 256ll + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t row = i / a.d;
+    const int x = (int)(i % a.d);
+    const int unit = (int)(row / a.N), t = (int)(row % a.N);
+    const int b = unit / a.Hq, h = unit % a.Hq;
+    const float dyx = to_f32<T>(static_cast<const T*>(a.dout)[b * a.o_sb + (int64_t)t * a.o_st + h * a.o_sh + x]);
+    float r = a.e_row[row] * dyx * a.nraw[i];
+    const int64_t go = b * a.g_sb + (int64_t)t * a.g_st + h * a.g_sh + x;
+    if (a.gate_act) {
+      const float s = 1.f / (1.f + __expf(-to_f32<T>(static_cast<const T*>(a.g)[go])));
+      r *= s * (1.f - s);
+    }
+    static_cast<T*>(a.dg)[go] = from_f32<T>(r);
+  }
+}
+
+// fp32 gradient rows -> the caller's strided tensors in the storage type
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_finish_kernel(BwdFinishArgs a) {
+  const int64_t n = (int64_t)a.B * a.H * a.N * a.d;
+  for (int64_t i = blockIdx.x * 256ll + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int x = (int)(i % a.d);
+    const int64_t row = i / a.d;
+    const int t = (int)(row % a.N);
+    const int bh = (int)(row / a.N);
+    const int b = bh / a.H, h = bh % a.H;
+    static_cast<T*>(a.dst)[b * a.s_b + (int64_t)t * a.s_t + h * a.s_h + x] = from_f32<T>(a.src[i]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Sparse (softmax) branch.  Tiles of 64 query rows x 64 keys, four waves, one 32 x 32 block of logits each.
+// A key tile is either 64 consecutive entries of the head's retained list (routing order, gathered by token index)
+// or 64 consecutive tokens of the local span.  Row t of chunk c sees retained entry e when e < n_vis(c) =
+// min((c-1) lambda, budget), and local token j when (c-1) C <= j <= t.
+// ---------------------------------------------------------------------------------------------------------
+template <typename T, int D>
+struct BwdTile {
+  static constexpr int PAD = sizeof(T) == 2 ? 8 : 4;
+  static constexpr int LD = D + PAD;        // row stride of a [64][D] tile
+  static constexpr int LT = 64 + PAD;       // row stride of a [D][64] or [64][64] tile
+  static constexpr int EPV = 16 / sizeof(T);
+};
+
+// rows [r0, r0+64) of a strided tensor -> LDS [64][LD] (zero beyond n_rows), optionally also transposed [D][LT]
+template <typename T, int D, bool TR>
+__device__ __forceinline__ void load_rows(T* dst, T* dstT, const T* base, int64_t stride, const int* toks, int r0,
+                                          int n_rows, int tid) {
+  typedef BwdTile<T, D> Cf;
+  constexpr int VPR = D / Cf::EPV;   // 16-byte vectors per row
+  for (int idx = tid; idx < 64 * VPR; idx += 256) {
+    const int row = idx % 64, xv = idx / 64;
+    int tok = toks ? toks[row] : r0 + row;
+    const bool ok = tok >= 0 && tok < n_rows;
+    Vec16 v{{0u, 0u, 0u, 0u}};
+    if (ok) v = *reinterpret_cast<const Vec16*>(base + (int64_t)tok * stride + xv * Cf::EPV);
+    *reinterpret_cast<Vec16*>(dst + row * Cf::LD + xv * Cf::EPV) = v;
+    if (TR) {
+      const T* e = reinterpret_cast<const T*>(&v);
+#pragma unroll
+      for (int j = 0; j < Cf::EPV; ++j) dstT[(xv * Cf::EPV + j) * Cf::LT + row] = e[j];
+    }
+  }
+}
+
+// one wave's 32 x 32 block of X Y^T, X rows [32 xr ..], Y rows [32 yr ..] of [64][LD] tiles
+template <typename T, int D>
+__device__ __forceinline__ floatx16 block_xyT(const T* X, const T* Y, int xr, int yr, int l31, int g) {
+  typedef Mma<T> M;
+  typedef BwdTile<T, D> Cf;
+  floatx16 acc = zero16();
+#pragma unroll
+  for (int s = 0; s < D / M::KK; ++s)
+    acc = M::mma(M::load(X + (32 * xr + l31) * Cf::LD + s * M::KK + g * M::KPL),
+                 M::load(Y + (32 * yr + l31) * Cf::LD + s * M::KK + g * M::KPL), acc);
+  return acc;
+}
+
+// acc += sum over 64 contraction entries of X[32 xr + m][k] Y[32 yr + n][k], both [..][LT] tiles
+template <typename T, int D>
+__device__ __forceinline__ void block_acc64(floatx16& acc, const T* X, const T* Y, int xr, int yr, int l31, int g) {
+  typedef Mma<T> M;
+  typedef BwdTile<T, D> Cf;
+#pragma unroll
+  for (int s = 0; s < 64 / M::KK; ++s)
+    acc = M::mma(M::load(X + (32 * xr + l31) * Cf::LT + s * M::KK + g * M::KPL),
+                 M::load(Y + (32 * yr + l31) * Cf::LT + s * M::KK + g * M::KPL), acc);
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_sa_dq_kernel(BwdSaArgs a) {
+  typedef BwdTile<T, D> Cf;
+  constexpr int DX = D / 64;   // 32-column blocks of dq per wave
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T* Qs = reinterpret_cast<T*>(smem);
+  T* dOs = Qs + 64 * Cf::LD;
+  T* Ks = dOs + 64 * Cf::LD;
+  T* Vs = Ks + 64 * Cf::LD;
+  T* KTs = Vs + 64 * Cf::LD;            // [D][LT]
+  T* dSs = KTs + D * Cf::LT;            // [64][LT]
+  float* Ls = reinterpret_cast<float*>(dSs + 64 * Cf::LT);
+  float* dls = Ls + 64;
+  int* toks = reinterpret_cast<int*>(dls + 64);
+
+  const int unit = blockIdx.y, rt = a.n_row_tiles - 1 - blockIdx.x;   // long rows first
+  const int b = unit / a.Hq, h = unit % a.Hq, kvh = a.map.kv[h];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, g = lane >> 5, wr = wave >> 1, wc = wave & 1;
+  const int N = a.N, C = a.C, r0 = rt * 64;
+  const int c = r0 / C;
+  const int n_vis = retained_rows(c >= 1 ? c - 1 : 0, a.lam, a.rcap);
+  const int lo = (c >= 1 ? c - 1 : 0) * C;
+  const int last = min(N - 1, r0 + 63);
+  const int n_ret_tiles = (n_vis + 63) / 64, n_tiles = n_ret_tiles + (last + 1 - lo + 63) / 64;
+
+  const T* qb = static_cast<const T*>(a.q) + b * a.q_sb + h * a.q_sh;
+  const T* dob = static_cast<const T*>(a.dout) + b * a.o_sb + h * a.o_sh;
+  const T* kb = static_cast<const T*>(a.k) + b * a.k_sb + kvh * a.k_sh;
+  const T* vb = static_cast<const T*>(a.v) + b * a.v_sb + kvh * a.v_sh;
+  const int32_t* sel = a.sel + (int64_t)unit * a.sel_stride;
+  load_rows<T, D, false>(Qs, nullptr, qb, a.q_st, nullptr, r0, N, tid);
+  load_rows<T, D, false>(dOs, nullptr, dob, a.o_st, nullptr, r0, N, tid);
+  if (tid < 64) {
+    const int t = r0 + tid;
+    Ls[tid] = t < N ? a.lse[(int64_t)unit * N + t] * kLog2e : 0.f;
+    dls[tid] = t < N ? a.delta[(int64_t)unit * N + t] : 0.f;
+  }
+  floatx16 dq[DX];
+#pragma unroll
+  for (int j = 0; j < DX; ++j) dq[j] = zero16();
+  const float sc2 = a.scale * kLog2e;
+
+  for (int ti = 0; ti < n_tiles; ++ti) {
+    const bool ret = ti < n_ret_tiles;
+    const int k0 = ret ? ti * 64 : lo + (ti - n_ret_tiles) * 64;
+    __syncthreads();   // the previous tile's products are done; also orders the loads above
+    if (tid < 64) {
+      int tok;
+      if (ret) {
+        const int e = k0 + tid;
+        tok = e < n_vis ? sel[e] : -1;
+        if (tok < 0 || tok >= N || tok / C != e / a.lam) tok = -1;   // lists are never trusted for addressing
+      } else {
+        tok = k0 + tid < N ? k0 + tid : -1;
+      }
+      toks[tid] = tok;
+    }
+    __syncthreads();
+    load_rows<T, D, true>(Ks, KTs, kb, a.k_st, toks, 0, N, tid);
+    load_rows<T, D, false>(Vs, nullptr, vb, a.v_st, toks, 0, N, tid);
+    __syncthreads();
+    floatx16 s = block_xyT<T, D>(Qs, Ks, wr, wc, l31, g);
+    floatx16 dp = block_xyT<T, D>(dOs, Vs, wr, wc, l31, g);
+    const int kcol = 32 * wc + l31;
+    const int tok = toks[kcol];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int r = 32 * wr + c_row(i, g);
+      const int t = r0 + r;
+      const bool vis = tok >= 0 && t < N && (ret || (tok >= lo && tok <= t));
+      const float p = vis ? fast_exp2(fmaf(s[i], sc2, -Ls[r])) : 0.f;
+      dSs[r * Cf::LT + kcol] = from_f32<T>(p * (dp[i] - dls[r]) * a.scale);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < DX; ++j) block_acc64<T, D>(dq[j], dSs, KTs, wr, wc * DX + j, l31, g);
+  }
+  float* out = a.dq32 + ((int64_t)unit * N) * D;
+#pragma unroll
+  for (int j = 0; j < DX; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int t = r0 + 32 * wr + c_row(i, g);
+      if (t < N) out[(int64_t)t * D + 32 * (wc * DX + j) + l31] = dq[j][i];
+    }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
+  typedef BwdTile<T, D> Cf;
+  constexpr int DX = D / 64;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T* Qs = reinterpret_cast<T*>(smem);
+  T* dOs = Qs + 64 * Cf::LD;
+  T* Ks = dOs + 64 * Cf::LD;
+  T* Vs = Ks + 64 * Cf::LD;
+  T* QTs = Vs + 64 * Cf::LD;            // [D][LT]
+  T* dOTs = QTs + D * Cf::LT;           // [D][LT]
+  T* PTs = dOTs + D * Cf::LT;           // [64 keys][LT rows]
+  T* dSTs = PTs + 64 * Cf::LT;
+  float* Ls = reinterpret_cast<float*>(dSTs + 64 * Cf::LT);
+  float* dls = Ls + 64;
+  int* toks = reinterpret_cast<int*>(dls + 64);
+
+  const int unit = blockIdx.y, ti = blockIdx.x;   // retained tiles (the long ones) come first
+  const int b = unit / a.Hq, h = unit % a.Hq, kvh = a.map.kv[h];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, g = lane >> 5, wr = wave >> 1, wc = wave & 1;
+  const int N = a.N, C = a.C;
+  const bool ret = ti < a.n_ret_tiles;
+  const int k0 = ret ? ti * 64 : (ti - a.n_ret_tiles) * 64;
+  int row_lo, row_hi;   // rows that may see a key of this tile: [row_lo, row_hi)
+  if (ret) {
+    if (a.lam <= 0 || k0 >= retained_rows(a.nc >= 2 ? a.nc - 2 : 0, a.lam, a.rcap)) return;
+    row_lo = (k0 / a.lam + 2) * C;
+    row_hi = N;
+  } else {
+    row_lo = k0;
+    row_hi = min(N, (k0 / C + 2) * C);
+  }
+  if (row_lo >= row_hi) return;
+  const T* qb = static_cast<const T*>(a.q) + b * a.q_sb + h * a.q_sh;
+  const T* dob = static_cast<const T*>(a.dout) + b * a.o_sb + h * a.o_sh;
+  const T* kb = static_cast<const T*>(a.k) + b * a.k_sb + kvh * a.k_sh;
+  const T* vb = static_cast<const T*>(a.v) + b * a.v_sb + kvh * a.v_sh;
+  const int32_t* sel = a.sel + (int64_t)unit * a.sel_stride;
+  if (tid < 64) {
+    int tok;
+    if (ret) {
+      const int e = k0 + tid;
+      tok = e < a.sel_stride ? sel[e] : -1;
+      if (tok < 0 || tok >= N || tok / C != e / a.lam) tok = -1;
+    } else {
+      tok = k0 + tid < N ? k0 + tid : -1;
+    }
+    toks[tid] = tok;
+  }
+  __syncthreads();
+  load_rows<T, D, false>(Ks, nullptr, kb, a.k_st, toks, 0, N, tid);
+  load_rows<T, D, false>(Vs, nullptr, vb, a.v_st, toks, 0, N, tid);
+  floatx16 dk[DX], dv[DX];
+#pragma unroll
+  for (int j = 0; j < DX; ++j) dk[j] = dv[j] = zero16();
+  const float sc2 = a.scale * kLog2e;
+  const int kcol = 32 * wc + l31;
+
+  for (int r0 = row_lo / 64 * 64; r0 < row_hi; r0 += 64) {
+    __syncthreads();
+    load_rows<T, D, true>(Qs, QTs, qb, a.q_st, nullptr, r0, N, tid);
+    load_rows<T, D, true>(dOs, dOTs, dob, a.o_st, nullptr, r0, N, tid);
+    if (tid < 64) {
+      const int t = r0 + tid;
+      Ls[tid] = t < N ? a.lse[(int64_t)unit * N + t] * kLog2e : 0.f;
+      dls[tid] = t < N ? a.delta[(int64_t)unit * N + t] : 0.f;
+    }
+    __syncthreads();
+    floatx16 s = block_xyT<T, D>(Qs, Ks, wr, wc, l31, g);
+    floatx16 dp = block_xyT<T, D>(dOs, Vs, wr, wc, l31, g);
+    const int tok = toks[kcol];
+    const int e = k0 + kcol;
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      float pv[4], dsv[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i = 4 * i4 + j;
+        const int r = 32 * wr + c_row(i, g);
+        const int t = r0 + r;
+        const int c = t / C;
+        bool vis = tok >= 0 && t < N;
+        if (ret) vis = vis && e < retained_rows(c >= 1 ? c - 1 : 0, a.lam, a.rcap);
+        else vis = vis && tok <= t && tok >= (c >= 1 ? c - 1 : 0) * C;
+        const float p = vis ? fast_exp2(fmaf(s[i], sc2, -Ls[r])) : 0.f;
+        pv[j] = p;
+        dsv[j] = p * (dp[i] - dls[r]) * a.scale;
+      }
+      const int rbase = 32 * wr + c_row(4 * i4, g);   // four consecutive rows
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        PTs[kcol * Cf::LT + rbase + j] = from_f32<T>(pv[j]);
+        dSTs[kcol * Cf::LT + rbase + j] = from_f32<T>(dsv[j]);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < DX; ++j) {
+      block_acc64<T, D>(dv[j], PTs, dOTs, wr, wc * DX + j, l31, g);    // dV[key][x] += P^T dO
+      block_acc64<T, D>(dk[j], dSTs, QTs, wr, wc * DX + j, l31, g);    // dK[key][x] += dS^T Q
+    }
+  }
+  float* dkb = a.dk32 + ((int64_t)b * a.Hkv + kvh) * N * D;
+  float* dvb = a.dv32 + ((int64_t)b * a.Hkv + kvh) * N * D;
+#pragma unroll
+  for (int j = 0; j < DX; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int tok = toks[32 * wr + c_row(i, g)];
+      if (tok >= 0) {
+        const int x = 32 * (wc * DX + j) + l31;
+        atomicAdd(dkb + (int64_t)tok * D + x, dk[j][i]);
+        atomicAdd(dvb + (int64_t)tok * D + x, dv[j][i]);
+      }
+    }
+}
+
+template <typename T, int D>
+size_t sa_dq_smem() {
+  typedef BwdTile<T, D> Cf;
+  return (size_t)(4 * 64 * Cf::LD + D * Cf::LT + 64 * Cf::LT) * sizeof(T) + 64 * 4 * 3;
+}
+template <typename T, int D>
+size_t sa_dkv_smem() {
+  typedef BwdTile<T, D> Cf;
+  return (size_t)(4 * 64 * Cf::LD + 2 * D * Cf::LT + 2 * 64 * Cf::LT) * sizeof(T) + 64 * 4 * 3;
+}
+
+template <typename T, int D>
+hipError_t launch_sa_t(const BwdSaArgs& a, int U, hipStream_t s) {
+  static bool attr_done = false;
+  const size_t s1 = sa_dq_smem<T, D>(), s2 = sa_dkv_smem<T, D>();
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_sa_dq_kernel<T, D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)s1);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_sa_dkv_kernel<T, D>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)s2);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((bwd_sa_dq_kernel<T, D>), dim3(a.n_row_tiles, U), dim3(256), s1, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((bwd_sa_dkv_kernel<T, D>), dim3(a.n_ret_tiles + a.n_row_tiles, U), dim3(256), s2, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_bgemm(const GemmArgs& a, int dtype, int U, int n_c, hipStream_t s) {
+  const dim3 grid((a.Nn / 64) * ((a.M + 63) / 64), n_c, U);
+  if (dtype == 1) hipLaunchKernelGGL((bgemm_kernel<bf16>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((bgemm_kernel<float>), grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_f32(float* p, int64_t n, float x, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+  hipLaunchKernelGGL(fill_f32_kernel, dim3(blocks), dim3(256), 0, s, p, n, x);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_row_prep(const BwdRowArgs& a, int dtype, hipStream_t s) {
+  const int blocks = (int)(((int64_t)a.U * a.N + 3) / 4);
+  if (dtype == 1) hipLaunchKernelGGL((bwd_row_prep_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((bwd_row_prep_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_dg(const BwdRowArgs& a, int dtype, hipStream_t s) {
+  const int64_t n = (int64_t)a.U * a.N * a.d;
+  const int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+  if (dtype == 1) hipLaunchKernelGGL((bwd_dg_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((bwd_dg_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_np(const BwdNpArgs& a, int dtype, bool backward, hipStream_t s) {
+  const int blocks = (int)(((int64_t)a.U * a.N + 3) / 4);
+  if (dtype == 1) {
+    if (backward) hipLaunchKernelGGL((bwd_np_bwd_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((bwd_np_fwd_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
+  } else {
+    if (backward) hipLaunchKernelGGL((bwd_np_bwd_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((bwd_np_fwd_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_colsum(const BwdColsumArgs& a, int dtype, int U, hipStream_t s) {
+  const dim3 grid(a.nc, U);
+  if (dtype == 1) hipLaunchKernelGGL((bwd_colsum_kernel<bf16>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((bwd_colsum_kernel<float>), grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_revcumsum(float* X, int U, int nc, int64_t L, hipStream_t s) {
+  hipLaunchKernelGGL(bwd_revcumsum_kernel, dim3((unsigned)((L + 255) / 256), U), dim3(256), 0, s, X, nc, L);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_finish(const BwdFinishArgs& a, int dtype, hipStream_t s) {
+  const int64_t n = (int64_t)a.B * a.H * a.N * a.d;
+  const int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+  if (dtype == 1) hipLaunchKernelGGL((bwd_finish_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((bwd_finish_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_sa(const BwdSaArgs& a, int dtype, int d, int U, hipStream_t s) {
+  if (dtype == 1) return d == 128 ? launch_sa_t<bf16, 128>(a, U, s) : launch_sa_t<bf16, 64>(a, U, s);
+  if (d == 64) return launch_sa_t<float, 64>(a, U, s);
+  return hipErrorInvalidValue;   // fp32 at d = 128 does not fit the tiles in LDS (refused by the host checks)
+}
+
+}  // namespace still

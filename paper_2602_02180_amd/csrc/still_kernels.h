@@ -191,6 +191,7 @@ struct SaArgs {
   int seg_chunks, nseg;
   float* n_la_out;     // nullable [B, Hq, N, d]: the gated linear numerator of every row (inspection)
   float* d_la_out;     // nullable [B, Hq, N]
+  float* lse;          // nullable [B, Hq, N]: ln(D_SA + D_LA) of every row
   void* out;
   int64_t o_sb, o_st, o_sh;
   HeadMap map;
@@ -288,5 +289,96 @@ hipError_t launch_evict_plan(const EvictPlanArgs& a, int B, hipStream_t stream);
 hipError_t launch_vfr_gather(const VfrGatherArgs& a, int dtype, int B, hipStream_t stream);
 hipError_t launch_state_fill_evict(const StateFillEvictArgs& a, int dtype, int B, hipStream_t stream);
 size_t evict_plan_smem(int M, int lam, int AW);
+
+// ---- backward pass (still_bwd.hip) ----
+// One operand of the generic batched product: element (row, k) of batch item (b, head, c) sits at
+// base[b*s_b + head*s_h + (c / c_div)*s_c + row*s_r + k*s_k]; head is the query head or, with kv = 1, its kv head.
+struct GemmOperand {
+  const void* base;
+  int64_t s_b, s_h, s_c, s_r, s_k;
+  int kv, c_div, f32;      // f32 = 1: the elements are float whatever the storage type
+};
+struct GemmArgs {
+  GemmOperand A, B;        // C[m][n] = sum_k A(m, k) B(n, k)
+  float* C;                // element (m, n) of item (b, head, c) at C[b*c_b + head*c_h + c*c_c + m*c_r + n]
+  int64_t c_b, c_h, c_c, c_r;
+  int c_kv;
+  int M, Nn, K;            // per item; Nn a multiple of 64
+  int m_total, k_total;    // > 0: item c holds only min(M, m_total - c*M) rows / min(K, k_total - c*K) contraction entries
+  int Hq;
+  HeadMap map;
+  int mode;                // 0: store, 1: add, 2: atomic add
+};
+struct BwdRowArgs {
+  const void* out;         // y of the forward pass, strided like dout
+  const void* dout;
+  int64_t o_sb, o_st, o_sh;
+  const void* g;           // nullable gate
+  int64_t g_sb, g_st, g_sh;
+  int gate_act;
+  const float* lse;        // [U, N]
+  float* e_row;            // [U, N]: E_t = exp(-L_t)
+  float* delta;            // [U, N]: dy_t . y_t
+  float* ed;               // [U, N]: E_t delta_t
+  void* A;                 // [U, N, d] storage type: E_t (gate_t * dy_t)
+  const float* nraw;       // [U, N, d]: phi_q S (dg kernel)
+  void* dg;                // strided like g (dg kernel)
+  int U, N, Hq, d;
+};
+struct BwdNpArgs {
+  const void* x;           // q or k
+  int64_t x_sb, x_st, x_sh;
+  int x_kv;                // 1: x is read (and its gradient accumulated) at the kv head of the query head
+  const void* bias;        // nullable [Hq, F]
+  float* u;                // [U, N, F]: f = x W on entry of the forward kernel, u afterwards
+  float* st;               // [U, N, 2]: |x|, |f|
+  void* phi;               // [U, N, 2F] storage type (forward kernel)
+  const uint32_t* kmask;   // nullable [B, Hq, ncf, C/32]: tokens the softmax branch keeps have phi = 0, df = 0
+  const float* dphi;       // [U, N, 2F] (backward kernel)
+  const float* coef;       // nullable [U, N]: dphi -= coef * (z1 + z2)
+  const float* z1;         // [U, nc, 2F]
+  const float* z2;         // nullable [U, nseg, 2F], indexed by chunk / seg_chunks
+  void* df;                // [U, N, F] storage type
+  float* dx32;             // [U, N, d], or [B, Hkv, N, d] with x_kv (atomic adds)
+  HeadMap map;
+  int U, N, Hq, Hkv, d, F, C, nc, ncf, nseg, seg_chunks;
+};
+struct BwdColsumArgs {
+  const void* X;           // [U, N, L] storage type
+  const float* w;          // nullable [U, N]
+  float* out;              // [U, nc, L], or (per_head) [Hq, L] added atomically
+  int N, C, nc, L, Hq, per_head;
+};
+struct BwdFinishArgs {
+  const float* src;        // [B, H, N, d]
+  void* dst;               // strided, storage type
+  int64_t s_b, s_t, s_h;
+  int B, H, N, d;
+};
+struct BwdSaArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  const void* dout;
+  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh, v_sb, v_st, v_sh, o_sb, o_st, o_sh;
+  const int32_t* sel;      // [U, sel_stride]: retained entry e is token sel[e] (chunk e / lam)
+  const float* lse;        // [U, N]
+  const float* delta;      // [U, N]
+  float* dq32;             // [U, N, d]
+  float* dk32;             // [B, Hkv, N, d], zeroed by the caller
+  float* dv32;
+  HeadMap map;
+  int N, C, lam, rcap, Hq, Hkv, nc, sel_stride, n_row_tiles, n_ret_tiles;
+  float scale;
+};
+hipError_t launch_bgemm(const GemmArgs& a, int dtype, int U, int n_c, hipStream_t stream);
+hipError_t launch_fill_f32(float* p, int64_t n, float x, hipStream_t stream);
+hipError_t launch_bwd_row_prep(const BwdRowArgs& a, int dtype, hipStream_t stream);
+hipError_t launch_bwd_dg(const BwdRowArgs& a, int dtype, hipStream_t stream);
+hipError_t launch_bwd_np(const BwdNpArgs& a, int dtype, bool backward, hipStream_t stream);
+hipError_t launch_bwd_colsum(const BwdColsumArgs& a, int dtype, int U, hipStream_t stream);
+hipError_t launch_bwd_revcumsum(float* X, int U, int nc, int64_t L, hipStream_t stream);
+hipError_t launch_bwd_finish(const BwdFinishArgs& a, int dtype, hipStream_t stream);
+hipError_t launch_bwd_sa(const BwdSaArgs& a, int dtype, int d, int U, hipStream_t stream);
 
 }  // namespace still

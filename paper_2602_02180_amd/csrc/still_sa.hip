@@ -700,7 +700,11 @@ __device__ __forceinline__ void sa_body(const SaArgs& a) {
     static_assert(Cf::NW * 32 * ROWB_O <= (int)Cf::tile_bytes, "epilogue staging fits the tile slots");
     unsigned char* reg = smem + wave_s * (32 * ROWB_O);
     const int lane_now = fresh_lane_id();
-    const float inv = 1.0f / sum32(lpart);
+    const float lsum = sum32(lpart);
+    const float inv = 1.0f / lsum;
+    // log of the shared normaliser D_SA + D_LA with the common factor undone (what a backward pass starts from)
+    if (a.lse != nullptr && t < N && g == 0)
+      a.lse[(int64_t)unit * a.N + t] = (m_ref + fast_log2(lsum)) * 0.6931471805599453f;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll

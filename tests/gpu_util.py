@@ -184,3 +184,65 @@ def assert_bf16_bar(x: np.ndarray, ref: np.ndarray, what: str = "") -> Dict[str,
     print(f"[bf16 {what}] {bf16_report_text(r)}")
     assert r["bar_fraction"] <= 1.0, (what, r)
     return r
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# backward pass
+# ---------------------------------------------------------------------------------------------------------------
+def run_hip_backward(w: synth.Workload, inp: Dict[str, np.ndarray], dy: np.ndarray,
+                     kv_map: Optional[np.ndarray] = None, gate_activation: int = 0,
+                     want_intermediates: bool = False) -> Dict[str, np.ndarray]:
+    """still_hybrid_attn_fwd followed by still_hybrid_attn_bwd with the forward call's index lists and log
+    normalisers.  Returns the forward's out / sel / lse and every gradient as float arrays."""
+    import torch
+
+    dev = "cuda"
+    up = lambda name: synth.to_torch(inp[name], w.dtype, dev) if inp.get(name) is not None else None
+    q, k, v, Wq, Wk, g, bq, bk = (up(n) for n in ("q", "k", "v", "Wq", "Wk", "g", "bq", "bk"))
+    dout = synth.to_torch(dy, w.dtype, dev)
+    B, N = q.shape[0], q.shape[1]
+    out = torch.full_like(q, float("nan"))
+    p = S.make_params(B=B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, g=g, kv_head_of_q=kv_map,
+                      max_retained=w.max_retained, shared_selection=w.shared_selection,
+                      gate_activation=gate_activation)
+    ncf = N // w.C
+    sel = torch.full((B, w.Hq, max(ncf, 1), max(w.lam, 1)), -1, dtype=torch.int32, device=dev)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    S.still_hybrid_attn_fwd(p, q, k, v, g, Wq, bq, Wk, bk, out, sel_idx=sel, workspace=ws)
+    L = S.still_fwd_workspace_layout(p)
+    lse = ws[L.lse:L.lse + B * w.Hq * N * 4].view(torch.float32).reshape(B, w.Hq, N).clone()
+    dq, dk, dv = (torch.full_like(t, float("nan")) for t in (q, k, v))
+    dg = torch.full_like(g, float("nan")) if g is not None else None
+    f32 = dict(dtype=torch.float32, device=dev)
+    dWq, dWk = torch.full((w.Hq, w.d, w.df), float("nan"), **f32), torch.full((w.Hq, w.d, w.df), float("nan"), **f32)
+    dbq = torch.full((w.Hq, w.df), float("nan"), **f32) if bq is not None else None
+    dbk = torch.full((w.Hq, w.df), float("nan"), **f32) if bk is not None else None
+    bws = torch.empty(S.still_bwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    S.still_hybrid_attn_bwd(p, q, k, v, g, Wq, bq, Wk, bk, out, dout, lse, sel if w.lam > 0 and ncf > 0 else None,
+                            dq, dk, dv, dg, dWq, dbq, dWk, dbk, bws)
+    torch.cuda.synchronize()
+    res = {"out": synth.from_torch(out), "lse": lse.cpu().numpy(),
+           "sel": sel.cpu().numpy()[:, :, :ncf, :w.lam].astype(np.int64),
+           "dq": synth.from_torch(dq), "dk": synth.from_torch(dk), "dv": synth.from_torch(dv),
+           "dg": synth.from_torch(dg) if dg is not None else None,
+           "dWq": dWq.cpu().numpy(), "dWk": dWk.cpu().numpy(),
+           "dbq": dbq.cpu().numpy() if dbq is not None else None,
+           "dbk": dbk.cpu().numpy() if dbk is not None else None}
+    if want_intermediates:
+        BL = S.still_bwd_workspace_layout(p)
+        U_, DP = B * w.Hq, 2 * w.df
+        nc = (N + w.C - 1) // w.C
+
+        def f32_region(off, shape):
+            n = int(np.prod(shape)) * 4
+            return bws[off:off + n].view(torch.float32).reshape(*shape).cpu().numpy()
+
+        res["nraw"] = f32_region(BL.nraw, (B, w.Hq, N, w.d))
+        res["gq"] = f32_region(BL.gq, (B, w.Hq, N, DP))
+        res["ds"] = f32_region(BL.ds, (B, w.Hq, nc, DP, w.d))
+        res["dz"] = f32_region(BL.dz, (B, w.Hq, nc, DP))
+        res["dphi_k"] = f32_region(BL.dphi_k, (B, w.Hq, N, DP))
+        res["uq"] = f32_region(BL.uq, (B, w.Hq, N, w.df))
+        res["dq32"] = f32_region(BL.dq32, (B, w.Hq, N, w.d))
+    return res

@@ -1,0 +1,131 @@
+"""GPU parity of the backward pass (still_hybrid_attn_bwd through the C ABI) against the float64 backward oracle on
+the same seeded, dtype-rounded inputs, with the index lists the HIP forward pass chose.
+
+Bars: every gradient tensor within 1e-4 of its largest magnitude on fp32 (measured ~1e-6; (the chain is longer than the forward's:
+recomputed weights, two contractions per branch, the NP-Map backwards), within 1e-2 of it on bf16 (measured 2-5e-3; operands of the
+matrix core and the stored results are rounded to 8 bits of mantissa); the log normaliser the forward pass leaves for
+the backward pass within 1e-5 (fp32) / 2e-2 (bf16) absolute.  dk, dv are compared after the oracle's per-head parts
+are added up over the query heads of a kv head, parameter gradients after adding up the batch."""
+import numpy as np
+import pytest
+
+from oracle import still_backward as OB
+from paper_2602_02180_amd import binding as S
+from paper_2602_02180_amd import synth
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+BAR = {"f32": 1e-4, "bf16": 1e-2}
+
+
+def small(name, **kw):
+    base = dict(B=1, N=512, Hq=2, Hkv=1, d=64, C=64, W=64, lam=16, dtype="f32")
+    base.update(kw)
+    return synth.Workload(name, **base)
+
+
+def make_dy(w, inp, seed):
+    rng = np.random.default_rng(seed)
+    return synth.round_to_dtype(rng.standard_normal(inp["q"].shape).astype(np.float32), w.dtype)
+
+
+def oracle_grads(w, inp, dy, sel, kv_map, gate_activation="none"):
+    B, N = inp["q"].shape[:2]
+    units = [(b, h) for b in range(B) for h in range(w.Hq)]
+    ref = OB.still_backward_units(inp, dy.astype(np.float64), kv_map, units, w.C, w.W, w.lam, w.scale, w.eps,
+                                  sel, max_retained=U.budget(w), gate_activation=gate_activation)
+    g = {"dq": np.zeros(inp["q"].shape), "dk": np.zeros(inp["k"].shape), "dv": np.zeros(inp["v"].shape),
+         "dWq": np.zeros(inp["Wq"].shape), "dWk": np.zeros(inp["Wk"].shape),
+         "lse": np.zeros((B, w.Hq, N)),
+         "dg": np.zeros(inp["q"].shape) if inp.get("g") is not None else None,
+         "dbq": np.zeros((w.Hq, w.df)) if inp.get("bq") is not None else None,
+         "dbk": np.zeros((w.Hq, w.df)) if inp.get("bk") is not None else None}
+    for (b, h) in units:
+        r = ref[(b, h)]
+        kh = int(kv_map[h])
+        g["dq"][b, :, h] = r["dq"]
+        g["dk"][b, :, kh] += r["dk"]
+        g["dv"][b, :, kh] += r["dv"]
+        g["dWq"][h] += r["dWq"]
+        g["dWk"][h] += r["dWk"]
+        g["lse"][b, h] = r["lse"]
+        for name in ("dg",):
+            if g[name] is not None:
+                g[name][b, :, h] = r[name]
+        for name in ("dbq", "dbk"):
+            if g[name] is not None:
+                g[name][h] += r[name]
+    return g
+
+
+def check_backward(w, inp, seed, kv_map=None, gate_activation=0):
+    kv = synth.kv_head_map(w) if kv_map is None else kv_map
+    dy = make_dy(w, inp, seed)
+    hip = U.run_hip_backward(w, inp, dy, kv_map=kv_map, gate_activation=gate_activation)
+    ref = oracle_grads(w, inp, dy, hip["sel"], kv, "sigmoid" if gate_activation else "none")
+    lse_err = float(np.max(np.abs(hip["lse"] - ref["lse"])))
+    print(f"[{w.name}] lse max-abs err {lse_err:.3e}")
+    assert lse_err <= (1e-5 * max(1.0, float(np.max(np.abs(ref["lse"])))) if w.dtype == "f32" else 2e-2)
+    worst = {}
+    for name in ("dq", "dk", "dv", "dg", "dWq", "dWk", "dbq", "dbk"):
+        if ref[name] is None:
+            assert hip[name] is None
+            continue
+        x = hip[name].astype(np.float64)
+        assert np.all(np.isfinite(x)), name
+        scale = float(np.max(np.abs(ref[name])))
+        err = float(np.max(np.abs(x - ref[name])))
+        worst[name] = err / max(scale, 1e-30) if scale > 0 else err
+        print(f"[{w.name}] {name}: max |ref| {scale:.3e}  max-abs err {err:.3e}  ratio {worst[name]:.3e}")
+    for name, r in worst.items():
+        assert r <= BAR[w.dtype], (name, r)
+    return hip, ref
+
+
+def with_bias(w, inp, seed):
+    rng = np.random.default_rng(seed)
+    inp["bq"] = synth.round_to_dtype(rng.standard_normal((w.Hq, w.df)) * 0.1, w.dtype)
+    inp["bk"] = synth.round_to_dtype(rng.standard_normal((w.Hq, w.df)) * 0.1, w.dtype)
+    return inp
+
+
+def test_backward_fp32_gate_bias_gqa_ragged_tail():
+    w = small("bwd", N=600, Hq=4, Hkv=2, lam=8, B=2)
+    inp = with_bias(w, synth.make_inputs(w, seed=31, with_gate=True), 32)
+    hip, ref = check_backward(w, inp, 33)
+    # both branches are live: no gradient is identically zero
+    for name in ("dq", "dk", "dv", "dg", "dWq", "dWk", "dbq", "dbk"):
+        assert np.max(np.abs(ref[name])) > 1e-4, name
+
+
+@pytest.mark.parametrize("kw", [
+    dict(N=512, lam=16, max_retained=40),                 # the budget runs out in chunk 2
+    dict(N=384, lam=0),                                   # nothing retained: local span + linear state only
+    dict(N=320, lam=64),                                  # everything retained: no linear branch at all
+    dict(N=50),                                           # shorter than one chunk
+    dict(N=1024, C=128, W=128, lam=16, Hq=2, Hkv=2),      # the wide chunk
+    dict(N=2304, lam=4, Hq=1),                            # many chunks: several segments of the state scan
+], ids=["budget", "lam0", "all-kept", "short", "C128", "segments"])
+def test_backward_fp32_cases(kw):
+    w = small("bwd-" + "-".join(f"{k}{v}" for k, v in kw.items()), **kw)
+    check_backward(w, synth.make_inputs(w, seed=41, with_gate=True), 42)
+
+
+def test_backward_fp32_sigmoid_gate_and_custom_head_map():
+    w = small("bwd-sg", N=448, Hq=4, Hkv=2, lam=8)
+    inp = synth.make_inputs(w, seed=51)
+    rng = np.random.default_rng(52)
+    inp["g"] = synth.round_to_dtype(2.0 * rng.standard_normal(inp["q"].shape), w.dtype)
+    check_backward(w, inp, 53, kv_map=np.array([1, 0, 0, 1], np.int32), gate_activation=1)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(d=128, C=128, W=128, N=1024, Hq=4, Hkv=2),
+    dict(d=64, C=64, W=64, N=1100, Hq=4, Hkv=1, B=2),
+    dict(d=128, C=64, W=128, N=900, Hq=2, Hkv=1, max_retained=96),
+], ids=["d128-C128", "d64-ragged", "d128-budget"])
+def test_backward_bf16(kw):
+    w = small("bwd16-" + "-".join(f"{k}{v}" for k, v in kw.items()), dtype="bf16", **kw)
+    inp = with_bias(w, synth.make_inputs(w, seed=61, with_gate=True), 62)
+    check_backward(w, inp, 63)

@@ -20,7 +20,8 @@ def test_library_exports_every_declared_symbol():
     names = declared_symbols()
     assert {"still_hybrid_attn_fwd", "still_hybrid_attn_decode_step", "still_fwd_workspace_bytes",
             "still_state_bytes", "still_state_init", "still_last_error", "still_version",
-            "still_hybrid_attn_decode_step_at", "still_hybrid_attn_fwd_static"} <= set(names)
+            "still_hybrid_attn_decode_step_at", "still_hybrid_attn_fwd_static", "still_hybrid_attn_bwd",
+            "still_bwd_workspace_bytes", "still_bwd_workspace_layout"} <= set(names)
     lib = S.lib()
     for n in names:
         assert hasattr(lib, n), n
@@ -37,7 +38,7 @@ def test_workspace_layout_is_consistent():
     p = params()
     L = S.still_fwd_workspace_layout(p)
     assert S.still_fwd_workspace_bytes(p) == L.total
-    offs = [L.score, L.sel, L.vt, L.kret, L.vrett, L.wqt, L.wkf, L.seg, L.snap, L.zsnap, L.pimg, L.zpre, L.kmask, L.n_la, L.d_la, L.vfr, L.ev_src, L.ev_alive, L.ev_fin, L.ev_vfr, L.total]
+    offs = [L.score, L.sel, L.vt, L.kret, L.vrett, L.wqt, L.wkf, L.seg, L.snap, L.zsnap, L.pimg, L.zpre, L.kmask, L.n_la, L.d_la, L.vfr, L.ev_src, L.ev_alive, L.ev_fin, L.ev_vfr, L.lse, L.total]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert L.n_pad % 128 == 0 and L.n_pad >= 1024
     assert L.cap % 64 == 0 and L.cap >= (1024 // 64) * 16
@@ -70,11 +71,11 @@ def test_eviction_policy_layouts():
     stop = S.still_fwd_workspace_layout(params(N=8192, max_retained=100))
     ev = S.still_fwd_workspace_layout(params(N=8192, max_retained=100, budget_policy=1))
     assert stop.cap == 128 and ev.cap == (8192 // 64) * 16
-    assert stop.ev_alive - stop.ev_src <= 256 and stop.total - stop.ev_vfr <= 256      # empty without the policy
+    assert stop.ev_alive - stop.ev_src <= 256 and stop.lse - stop.ev_vfr <= 256      # empty without the policy
     assert ev.ev_alive - ev.ev_src >= 1 * 4 * 8192 * 4
     assert ev.ev_fin - ev.ev_alive >= 1 * 4 * (8192 // 64) * (ev.cap // 64) * 8
     assert ev.ev_vfr - ev.ev_fin >= 1 * 4 * (2 * 100 + 1) * 4
-    assert ev.total - ev.ev_vfr >= 1 * 4 * 64 * ev.n_pad * 2
+    assert ev.lse - ev.ev_vfr >= 1 * 4 * 64 * ev.n_pad * 2 and ev.total - ev.lse >= 1 * 4 * 8192 * 4
     s_stop = S.still_state_layout(params(N=1, max_tokens=1 << 20, max_retained=896))
     s_ev = S.still_state_layout(params(N=1, max_tokens=1 << 20, max_retained=896, budget_policy=1))
     assert s_ev.cap == s_stop.cap == 896 + 64
@@ -104,6 +105,34 @@ def test_bad_params_are_rejected_on_the_host(kw, code):
         S.still_fwd_workspace_layout(p)
     assert e.value.code == code
     assert S.still_last_error() != ""
+
+
+def test_backward_entry_point_validates_on_the_host():
+    """The backward pass covers budget_policy 0 without padding; fp32 only at d = 64; its workspace holds a forward
+    workspace plus its own regions; null pointers are refused before any launch."""
+    for kw in (dict(dtype="f32", d=128, C=128), dict(max_retained=64, budget_policy=1)):
+        with pytest.raises(S.StillError) as e:
+            S.still_bwd_workspace_layout(params(**kw))
+        assert e.value.code == S.STILL_ERR_UNSUPPORTED
+    p = params()
+    BL = S.still_bwd_workspace_layout(p)
+    assert S.still_bwd_workspace_bytes(p) == BL.total
+    names = [n for n, _ in S.StillBwdWsLayout._fields_]
+    offs = [getattr(BL, n) for n in names]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    assert BL.e_row - BL.fwd >= S.still_fwd_workspace_bytes(p)
+    assert BL.dz - BL.ds >= 1 * 4 * 16 * 128 * 64 * 4 and BL.total - BL.dv32 >= 1 * 2 * 1024 * 64 * 4
+    p.q_st = p.k_st = p.v_st = p.o_st = 64
+    null, fake = ctypes.c_void_p(None), ctypes.c_void_p(0x1000)
+    rc = S.lib().still_hybrid_attn_bwd(ctypes.byref(p), fake, fake, fake, null, fake, null, fake, null, fake, fake,
+                                        null, fake, fake, fake, fake, null, fake, null, fake, null, fake, 1 << 40, null)
+    assert rc == S.STILL_ERR_INVALID_ARG and "pointer" in S.still_last_error()
+    rc = S.lib().still_hybrid_attn_bwd(ctypes.byref(p), fake, fake, fake, null, fake, null, fake, null, fake, fake,
+                                        fake, fake, fake, fake, fake, null, fake, null, fake, null, fake, 16, null)
+    assert rc == S.STILL_ERR_WORKSPACE_TOO_SMALL
+    rc = S.lib().still_hybrid_attn_bwd(ctypes.byref(p), fake, fake, fake, fake, fake, null, fake, null, fake, fake,
+                                        fake, fake, fake, fake, fake, null, fake, null, fake, null, fake, 1 << 40, null)
+    assert rc == S.STILL_ERR_INVALID_ARG and "dg" in S.still_last_error()
 
 
 def test_fwd_rejects_null_and_misaligned_pointers_without_launching():
