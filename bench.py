@@ -223,6 +223,95 @@ def global_score_bench(args) -> int:
     return 0
 
 
+def backward_flops(w: synth.Workload, N: int) -> float:
+    """Algorithmic flops of one backward call.  Softmax branch: five products per visible (row, key) pair (logits and
+    dy.v again, then dv, dk, dq), 2 d flops each.  Linear branch, per token and head: on the query side f = x W, phi_q S,
+    S A, phi_q^T A, df W^T and x^T df; on the key side f = x W, the state update again, dS v, dS^T phi_k, df W^T and
+    x^T df: 36 d d_f flops together."""
+    return 2.5 * sparse_branch_flops(w, N) + 36.0 * w.d * w.df * N * w.B * w.Hq
+
+
+def backward_bench(args) -> int:
+    """Side figure: one training step of the operator, still_hybrid_attn_fwd + still_hybrid_attn_bwd, on the
+    training shape (config c6: sequences of 1024 tokens, Sec. 4.1) or on the chosen config."""
+    import torch
+    from paper_2602_02180_amd import binding as S
+
+    w = synth.workload(args.config if args.config in ("c2", "c3", "c4", "c6") else "c6")
+    inp = synth.make_inputs(w, with_gate=True)
+    dev = "cuda"
+    q, k, v, g = (synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v", "g"))
+    Wq, Wk = synth.to_torch(inp["Wq"], w.dtype, dev), synth.to_torch(inp["Wk"], w.dtype, dev)
+    rng = np.random.default_rng(w.seed + 1000)
+    dout = synth.to_torch(synth.round_to_dtype(rng.standard_normal(inp["q"].shape, dtype=np.float32), w.dtype), w.dtype, dev)
+    N = w.N
+    out = torch.empty_like(q)
+    p = S.make_params(B=w.B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, d_f=w.df, q=q, k=k, v=v, out=out, g=g)
+    sel = torch.full((w.B, w.Hq, N // w.C, w.lam), -1, dtype=torch.int32, device=dev)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    L = S.still_fwd_workspace_layout(p)
+    lse = ws[L.lse:L.lse + w.B * w.Hq * N * 4].view(torch.float32)
+    dq, dk, dv, dg = (torch.empty_like(t) for t in (q, k, v, g))
+    dWq = torch.empty(w.Hq, w.d, w.df, dtype=torch.float32, device=dev)
+    dWk = torch.empty_like(dWq)
+    bws = torch.empty(S.still_bwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+
+    def fwd():
+        S.still_hybrid_attn_fwd(p, q, k, v, g, Wq, None, Wk, None, out, sel_idx=sel, workspace=ws)
+
+    def bwd():
+        S.still_hybrid_attn_bwd(p, q, k, v, g, Wq, None, Wk, None, out, dout, lse, sel, dq, dk, dv, dg, dWq, None,
+                                dWk, None, bws)
+
+    steps = args.steps if args.steps else 10
+    for _ in range(max(1, min(args.warmup, 3))):
+        fwd()
+        bwd()
+    torch.cuda.synchronize()
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    f_ms = b_ms = 0.0
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        e[0].record()
+        fwd()
+        e[1].record()
+        bwd()
+        e[2].record()
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    # the last step's split (events are reused: only the last recording survives), the mean from the wall clock
+    f_ms, b_ms = e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])
+    flops = backward_flops(w, N)
+    rec = {
+        "metric": f"hybrid-attn fwd+bwd tokens/s ({w.name} shape)", "value": w.B * N * steps / el, "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": max(1, min(args.warmup, 3)), "ms_per_step": el / steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"forward + backward, {w.name}: B={w.B} N={N} Hq={w.Hq} Hkv={w.Hkv} d={w.d} C={w.C} "
+                               f"W={w.W} lambda={w.lam}, gate given",
+                   "fwd_ms": f_ms, "bwd_ms": b_ms, "bwd_workspace_gb": bws.numel() / 1e9},
+        "roofline": {"bound": "mfma", "kernel": "still_hybrid_attn_bwd (whole call)",
+                     "achieved": flops / (b_ms * 1e-3) / 1e12, "peak": PEAK_MFMA[w.dtype] / 1e12, "unit": "TFLOP/s",
+                     "frac": flops / (b_ms * 1e-3) / PEAK_MFMA[w.dtype], "traffic": None,
+                     "algorithmic_flops_per_call": flops, "avg_launch_ms": b_ms},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import still_backward as OB
+        sel_h = sel.cpu().numpy().astype(np.int64)
+        n_s = min(N, 1024)
+        t0 = time.perf_counter()
+        OB.still_backward_definition(inp["q"][0, :n_s, 0], inp["k"][0, :n_s, 0], inp["v"][0, :n_s, 0],
+                                     inp["g"][0, :n_s, 0], inp["Wq"][0], inp["Wk"][0], w.C, w.W, w.lam, w.scale, w.eps,
+                                     np.asarray(synth.from_torch(dout[0, :n_s, 0]), np.float64),
+                                     sel=sel_h[0, 0, :n_s // w.C])
+        el_c = time.perf_counter() - t0
+        rec["cpu_baseline"] = {"value": n_s / el_c / w.Hq * (n_s / N), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                               "sample": f"backward oracle on rows 0..{n_s - 1} of one (batch, head) unit, {el_c:.1f} s; "
+                                         f"scaled to {w.Hq} heads (and quadratically to {N} rows)"}
+    print(json.dumps(rec))
+    return 0
+
+
 def decode_bench(args) -> int:
     print(json.dumps(decode_record(args, args.steps if args.steps else 0, with_cpu=not args.no_cpu_baseline)))
     return 0
@@ -382,7 +471,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (default: 20 prefill calls, 128 decode steps)")
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c6"])
+    ap.add_argument("--backward", action="store_true",
+                    help="side figure: forward + backward of the operator (default shape: c6, the training shape)")
     ap.add_argument("--max-retained", type=int, default=0,
                     help="budget on the retained tokens per (sequence, head); 0 (default) = none, the headline workload")
     ap.add_argument("--evict", action="store_true",
@@ -438,6 +529,10 @@ def main() -> int:
         print(json.dumps({"calibrate_copy_bytes": 1 << 30, "launches": 4}))
         return 0
 
+    if args.backward:
+        if args.config == "c4" and "--config" not in sys.argv:
+            args.config = "c6"
+        return backward_bench(args)
     if args.global_score:
         return global_score_bench(args)
     if args.config == "c5":

@@ -52,7 +52,7 @@ class Workload:
 
     @property
     def seed(self) -> int:
-        return BASE_SEED + {"c1": 1, "c2": 2, "c3": 3, "c4": 4, "c5": 5}.get(self.name, 99)
+        return BASE_SEED + {"c1": 1, "c2": 2, "c3": 3, "c4": 4, "c5": 5, "c6": 6}.get(self.name, 99)
 
 
 CONFIGS: Dict[str, Workload] = {
@@ -68,6 +68,8 @@ CONFIGS: Dict[str, Workload] = {
     # decode at the 8B shape: 64 sequences with a 32K prefilled context each
     "c5": Workload("c5", B=64, N=32768, Hq=32, Hkv=8, d=128, C=128, W=128, lam=16, dtype="bf16",
                    heavy_frac=0.01, decode_steps=128),
+    # training shape: the paper trains on sequences of 1024 tokens (Sec. 4.1); 8B-shaped layer, 16 sequences
+    "c6": Workload("c6", B=16, N=1024, Hq=32, Hkv=8, d=128, C=64, W=128, lam=16, dtype="bf16"),
 }
 
 

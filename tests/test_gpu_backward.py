@@ -1,11 +1,11 @@
 """GPU parity of the backward pass (still_hybrid_attn_bwd through the C ABI) against the float64 backward oracle on
 the same seeded, dtype-rounded inputs, with the index lists the HIP forward pass chose.
 
-Bars: every gradient tensor within 1e-4 of its largest magnitude on fp32 (measured ~1e-6; (the chain is longer than the forward's:
-recomputed weights, two contractions per branch, the NP-Map backwards), within 1e-2 of it on bf16 (measured 2-5e-3; operands of the
-matrix core and the stored results are rounded to 8 bits of mantissa); the log normaliser the forward pass leaves for
-the backward pass within 1e-5 (fp32) / 2e-2 (bf16) absolute.  dk, dv are compared after the oracle's per-head parts
-are added up over the query heads of a kv head, parameter gradients after adding up the batch."""
+Bars: every gradient tensor within 1e-4 of its largest magnitude on fp32 (measured ~1e-6), within 1e-2 of it on
+bf16 (measured 2-5e-3: the operands of the matrix core and the stored results carry 8 bits of mantissa, the sums are
+fp32); the log normaliser that the forward pass leaves for the backward pass within 1e-5 relative (fp32) / 2e-2
+absolute (bf16).  dk, dv are compared after the oracle's per-head parts are added up over the query heads of a kv
+head, parameter gradients after adding up the batch."""
 import numpy as np
 import pytest
 
