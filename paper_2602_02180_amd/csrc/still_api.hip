@@ -969,8 +969,9 @@ still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, c
   gm.Hq = Hq; gm.map = map;
   auto product = [&](const still::GemmOperand& A_, const still::GemmOperand& B_, float* Cp, int64_t c_b, int64_t c_h,
                      int64_t c_c, int64_t c_r, int c_kv, int M_, int Nn_, int K_, int m_total, int k_total, int mode,
-                     int n_c) -> hipError_t {
-    gm.A = A_; gm.B = B_; gm.C = Cp; gm.c_b = c_b; gm.c_h = c_h; gm.c_c = c_c; gm.c_r = c_r; gm.c_kv = c_kv;
+                     int n_c, const still::GemmOperand* B2_ = nullptr) -> hipError_t {
+    gm.A = A_; gm.B = B_; gm.C = Cp;
+    gm.B2 = B2_ != nullptr ? *B2_ : still::GemmOperand{}; gm.c_b = c_b; gm.c_h = c_h; gm.c_c = c_c; gm.c_r = c_r; gm.c_kv = c_kv;
     gm.M = M_; gm.Nn = Nn_; gm.K = K_; gm.m_total = m_total; gm.k_total = k_total; gm.mode = mode;
     return still::launch_bgemm(gm, dt, U, n_c, stream);
   };
@@ -1009,10 +1010,8 @@ still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, c
   const still::GemmOperand pimg_xf = operand(la.pimg, Hq * L.nseg * img, L.nseg * img, img, DP, 1, 0, 0, L.seg_chunks);
   const still::GemmOperand snap_fx = operand(la.snap, Hq * nc * img, nc * img, img, 1, DP);        // (n = f, k = x)
   const still::GemmOperand pimg_fx = operand(la.pimg, Hq * L.nseg * img, L.nseg * img, img, 1, DP, 0, 0, L.seg_chunks);
-  if ((e = product(phiq_rows, snap_xf, f32p(BL.nraw), Hq * ND, ND, (int64_t)C * d, d, 0, C, d, DP, N, 0, 0, nc)) != hipSuccess ||
-      (e = product(phiq_rows, pimg_xf, f32p(BL.nraw), Hq * ND, ND, (int64_t)C * d, d, 0, C, d, DP, N, 0, 1, nc)) != hipSuccess ||
-      (e = product(a_rows, snap_fx, f32p(BL.gq), Hq * NDP, NDP, (int64_t)C * DP, DP, 0, C, DP, d, N, 0, 0, nc)) != hipSuccess ||
-      (e = product(a_rows, pimg_fx, f32p(BL.gq), Hq * NDP, NDP, (int64_t)C * DP, DP, 0, C, DP, d, N, 0, 1, nc)) != hipSuccess)
+  if ((e = product(phiq_rows, snap_xf, f32p(BL.nraw), Hq * ND, ND, (int64_t)C * d, d, 0, C, d, DP, N, 0, 0, nc, &pimg_xf)) != hipSuccess ||
+      (e = product(a_rows, snap_fx, f32p(BL.gq), Hq * NDP, NDP, (int64_t)C * DP, DP, 0, C, DP, d, N, 0, 0, nc, &pimg_fx)) != hipSuccess)
     return hip_fail("bwd query-side products", e);
   if (g != nullptr && (e = still::launch_bwd_dg(ra, dt, stream)) != hipSuccess) return hip_fail("bwd_dg", e);
 

@@ -26,11 +26,6 @@ namespace still {
 
 namespace {
 
-template <typename T>
-__device__ __forceinline__ float ld_as_f32(const void* base, int64_t off, int is_f32) {
-  return is_f32 ? static_cast<const float*>(base)[off] : to_f32<T>(static_cast<const T*>(base)[off]);
-}
-
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
@@ -43,72 +38,123 @@ __device__ __forceinline__ float wave_max(float x) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Generic batched product on the matrix core: C[m][n] (=, +=, atomic +=) sum_k A(m, k) B(n, k), one 64 x 64 tile
-// of one batch item per workgroup (four waves, one 32 x 32 block each), both operands through LDS in the storage
-// type with the contraction index contiguous.  Operands are addressed through explicit strides, so a transposed
-// or fp32 operand costs nothing but element-wise loads.
+// Generic batched product on the matrix core: C[m][n] (=, +=, atomic +=) sum_k A(m, k) B(n, k) [+ sum_k A(m, k)
+// B2(n, k)], one 64 x BN tile of one batch item per workgroup (four waves as 2 x 2, each 32 x BN/2), both operands
+// through LDS in the storage type with the contraction index contiguous, 64 contraction entries per barrier pair.
+// Operands are addressed through explicit strides.  Every global access is a 16-byte (32-byte for fp32 data) vector
+// along the operand's contiguous index: for an operand whose contraction index is contiguous the vector goes to LDS
+// as it is; for one whose row index is contiguous (a transposed view) its eight elements go to eight LDS rows, the
+// lanes of a wave then covering consecutive k so that neither side meets bank conflicts.
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
+__device__ __forceinline__ void load8(float (&x)[8], const void* base, int64_t off, int is_f32) {
+  if (is_f32) {
+    const floatx4 a = *reinterpret_cast<const floatx4*>(static_cast<const float*>(base) + off);
+    const floatx4 b = *reinterpret_cast<const floatx4*>(static_cast<const float*>(base) + off + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
+  } else if constexpr (sizeof(T) == 2) {
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(static_cast<const T*>(base) + off);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = static_cast<float>(v[e]);
+  } else {
+    const floatx4 a = *reinterpret_cast<const floatx4*>(static_cast<const float*>(base) + off);
+    const floatx4 b = *reinterpret_cast<const floatx4*>(static_cast<const float*>(base) + off + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
+  }
+}
+
+// ROWS x 64 tile of one operand into LDS [ROWS][LDK]; rows at and beyond row_valid and contraction entries at and
+// beyond k_valid read as zero
+template <typename T, int ROWS, int LDK>
+__device__ __forceinline__ void load_operand(T* dst, const GemmOperand& o, int64_t off, int row0, int row_valid, int k0,
+                                             int k_valid, int tid) {
+  constexpr int NV = ROWS * 64 / 8 / 256;   // vectors per thread
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int idx = tid + 256 * j;
+    float x[8];
+    if (o.s_k == 1) {        // contraction index contiguous: vector along k
+      const int row = idx / 8, kv = (idx % 8) * 8;
+      const bool ok = row0 + row < row_valid && k0 + kv < k_valid;
+      if (ok) load8<T>(x, o.base, off + (int64_t)(row0 + row) * o.s_r + (k0 + kv), o.f32);
+      T* d = dst + row * LDK + kv;
+      if constexpr (sizeof(T) == 2) {
+        bf16x8 v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = static_cast<bf16>(ok ? x[e] : 0.f);
+        *reinterpret_cast<bf16x8*>(d) = v;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) d[e] = ok ? x[e] : 0.f;
+      }
+    } else {                 // row index contiguous: vector along rows, lanes along k
+      const int kk = idx % 64, rv = (idx / 64) * 8;
+      const bool ok = k0 + kk < k_valid && row0 + rv < row_valid;
+      if (ok) load8<T>(x, o.base, off + (int64_t)(row0 + rv) + (int64_t)(k0 + kk) * o.s_k, o.f32);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dst[(rv + e) * LDK + kk] = from_f32<T>(ok ? x[e] : 0.f);
+    }
+  }
+}
+
+template <typename T, int BN>
 __global__ __launch_bounds__(256) void bgemm_kernel(GemmArgs a) {
   typedef Mma<T> M;
-  constexpr int BK = 32;
+  constexpr int BK = 64, NT = BN / 64;
   constexpr int LDK = BK + (sizeof(T) == 2 ? 8 : 4);
   __shared__ __attribute__((aligned(16))) T As[64 * LDK];
-  __shared__ __attribute__((aligned(16))) T Bs[64 * LDK];
+  __shared__ __attribute__((aligned(16))) T Bs[BN * LDK];
   const int unit = blockIdx.z, c = blockIdx.y;
-  const int ntn = a.Nn / 64;
+  const int ntn = a.Nn / BN;
   const int mt = blockIdx.x / ntn, nt = blockIdx.x % ntn;
   const int b = unit / a.Hq, h = unit % a.Hq, kvh = a.map.kv[h];
   int m_valid = a.M, k_valid = a.K;
   if (a.m_total > 0) m_valid = min(a.M, a.m_total - c * a.M);
   if (a.k_total > 0) k_valid = min(a.K, a.k_total - c * a.K);
   if (m_valid <= mt * 64 || k_valid <= 0) return;   // uniform over the workgroup
-  const int64_t a_off = b * a.A.s_b + (a.A.kv ? kvh : h) * a.A.s_h + (int64_t)(c / a.A.c_div) * a.A.s_c;
-  const int64_t b_off = b * a.B.s_b + (a.B.kv ? kvh : h) * a.B.s_h + (int64_t)(c / a.B.c_div) * a.B.s_c;
+  auto item_off = [&](const GemmOperand& o) {
+    return b * o.s_b + (o.kv ? kvh : h) * o.s_h + (int64_t)(c / o.c_div) * o.s_c;
+  };
+  const int64_t a_off = item_off(a.A);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, g = lane >> 5;
   const int wr = wave >> 1, wc = wave & 1;
-  floatx16 acc = zero16();
-  for (int k0 = 0; k0 < k_valid; k0 += BK) {
+  floatx16 acc[NT];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int idx = tid + 256 * j;
-      {
-        int row, kk;
-        if (a.A.s_k == 1) { row = idx / BK; kk = idx % BK; } else { row = idx % 64; kk = idx / 64; }
-        const int mg = mt * 64 + row, kg = k0 + kk;
-        float x = 0.f;
-        if (mg < m_valid && kg < k_valid) x = ld_as_f32<T>(a.A.base, a_off + mg * a.A.s_r + kg * a.A.s_k, a.A.f32);
-        As[row * LDK + kk] = from_f32<T>(x);
-      }
-      {
-        int row, kk;
-        if (a.B.s_k == 1) { row = idx / BK; kk = idx % BK; } else { row = idx % 64; kk = idx / 64; }
-        const int ng = nt * 64 + row, kg = k0 + kk;
-        float x = 0.f;
-        if (kg < k_valid) x = ld_as_f32<T>(a.B.base, b_off + ng * a.B.s_r + kg * a.B.s_k, a.B.f32);
-        Bs[row * LDK + kk] = from_f32<T>(x);
-      }
-    }
-    __syncthreads();
+  for (int j = 0; j < NT; ++j) acc[j] = zero16();
+  const int n_b = a.B2.base != nullptr ? 2 : 1;
+  for (int pass = 0; pass < n_b; ++pass) {
+    const GemmOperand& ob = pass == 0 ? a.B : a.B2;
+    const int64_t b_off = item_off(ob);
+    for (int k0 = 0; k0 < k_valid; k0 += BK) {
+      load_operand<T, 64, LDK>(As, a.A, a_off, mt * 64, m_valid, k0, k_valid, tid);
+      load_operand<T, BN, LDK>(Bs, ob, b_off, nt * BN, a.Nn, k0, k_valid, tid);
+      __syncthreads();
 #pragma unroll
-    for (int s = 0; s < BK / M::KK; ++s) {
-      const typename M::frag af = M::load(As + (32 * wr + l31) * LDK + s * M::KK + g * M::KPL);
-      const typename M::frag bf = M::load(Bs + (32 * wc + l31) * LDK + s * M::KK + g * M::KPL);
-      acc = M::mma(af, bf, acc);
+      for (int s = 0; s < BK / M::KK; ++s) {
+        const typename M::frag af = M::load(As + (32 * wr + l31) * LDK + s * M::KK + g * M::KPL);
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          acc[j] = M::mma(af, M::load(Bs + (32 * (wc * NT + j) + l31) * LDK + s * M::KK + g * M::KPL), acc[j]);
+      }
+      __syncthreads();
     }
-    __syncthreads();
   }
   float* cp = a.C + b * a.c_b + (a.c_kv ? kvh : h) * a.c_h + (int64_t)c * a.c_c;
-  const int n = nt * 64 + 32 * wc + l31;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int m = mt * 64 + 32 * wr + c_row(i, g);
-    if (m < m_valid) {
-      float* dst = cp + (int64_t)m * a.c_r + n;
-      if (a.mode == 0) *dst = acc[i];
-      else if (a.mode == 1) *dst += acc[i];
-      else atomicAdd(dst, acc[i]);
+  for (int j = 0; j < NT; ++j) {
+    const int n = nt * BN + 32 * (wc * NT + j) + l31;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m = mt * 64 + 32 * wr + c_row(i, g);
+      if (m < m_valid) {
+        float* dst = cp + (int64_t)m * a.c_r + n;
+        if (a.mode == 0) *dst = acc[j][i];
+        else if (a.mode == 1) *dst += acc[j][i];
+        else atomicAdd(dst, acc[j][i]);
+      }
     }
   }
 }
@@ -678,9 +724,15 @@ hipError_t launch_sa_t(const BwdSaArgs& a, int U, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_bgemm(const GemmArgs& a, int dtype, int U, int n_c, hipStream_t s) {
-  const dim3 grid((a.Nn / 64) * ((a.M + 63) / 64), n_c, U);
-  if (dtype == 1) hipLaunchKernelGGL((bgemm_kernel<bf16>), grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((bgemm_kernel<float>), grid, dim3(256), 0, s, a);
+  const int bn = a.Nn % 128 == 0 ? 128 : 64;
+  const dim3 grid((a.Nn / bn) * ((a.M + 63) / 64), n_c, U);
+  if (dtype == 1) {
+    if (bn == 128) hipLaunchKernelGGL((bgemm_kernel<bf16, 128>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((bgemm_kernel<bf16, 64>), grid, dim3(256), 0, s, a);
+  } else {
+    if (bn == 128) hipLaunchKernelGGL((bgemm_kernel<float, 128>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((bgemm_kernel<float, 64>), grid, dim3(256), 0, s, a);
+  }
   return hipGetLastError();
 }
 

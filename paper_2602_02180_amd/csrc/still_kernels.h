@@ -300,10 +300,11 @@ struct GemmOperand {
 };
 struct GemmArgs {
   GemmOperand A, B;        // C[m][n] = sum_k A(m, k) B(n, k)
+  GemmOperand B2;          // base != nullptr: ... + sum_k A(m, k) B2(n, k), the same A against a second operand
   float* C;                // element (m, n) of item (b, head, c) at C[b*c_b + head*c_h + c*c_c + m*c_r + n]
   int64_t c_b, c_h, c_c, c_r;
   int c_kv;
-  int M, Nn, K;            // per item; Nn a multiple of 64
+  int M, Nn, K;            // per item; Nn and K multiples of 64 (a K cut short by k_total reads as zeros)
   int m_total, k_total;    // > 0: item c holds only min(M, m_total - c*M) rows / min(K, k_total - c*K) contraction entries
   int Hq;
   HeadMap map;
