@@ -374,6 +374,8 @@ typedef struct still_bwd_ws_layout {
   size_t dfq, dfk; /* dtype [B, Hq, N, d_f]   gradient of f(x)                                                */
   size_t dq32;     /* float [B, Hq, N, d]                                                                     */
   size_t dk32, dv32; /* float [B, Hkv, N, d]                                                                  */
+  size_t qt, dot;  /* dtype [B, Hq, d, Npad]  q and dout transposed, zero padded                              */
+  size_t kt;       /* dtype [B, Hkv, d, Npad] k transposed                                                    */
   size_t total;
 } still_bwd_ws_layout_t;
 STILL_API size_t still_bwd_workspace_bytes(const still_params_t* p);

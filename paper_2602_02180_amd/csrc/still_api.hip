@@ -848,6 +848,9 @@ void compute_bwd_layout(const still_params_t* p, still_bwd_ws_layout_t* L) {
   L->dq32 = take(rows * d * 4);
   L->dk32 = take(kvrows * d * 4);
   L->dv32 = take(kvrows * d * 4);
+  L->qt = take(U * d * (size_t)F.n_pad * es);
+  L->dot = take(U * d * (size_t)F.n_pad * es);
+  L->kt = take((size_t)p->B * p->Hkv * d * (size_t)F.n_pad * es);
   L->total = off;
 }
 
@@ -947,8 +950,31 @@ still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, c
   ra.U = U; ra.N = N; ra.Hq = Hq; ra.d = d;
   if ((e = still::launch_bwd_row_prep(ra, dt, stream)) != hipSuccess) return hip_fail("bwd_row_prep", e);
 
-  // ---- softmax branch: dq (owned rows), dk / dv (atomic adds per key tile)
+  // ---- softmax branch: dq (owned rows), dk / dv (atomic adds per key tile).  Its products over rows and keys read
+  // transposed copies: q^T, dout^T, k^T of the sequence, and the retained keys both ways (the prefill's gather
+  // kernel with k in the place of v too).
+  still::TransposeVArgs tq{q, p->q_sb, p->q_st, p->q_sh, bws + BL.qt, nullptr, N, L.n_pad, Hq, d, C, nullptr};
+  still::TransposeVArgs td{dout, p->o_sb, p->o_st, p->o_sh, bws + BL.dot, nullptr, N, L.n_pad, Hq, d, C, nullptr};
+  still::TransposeVArgs tk{k, p->k_sb, p->k_st, p->k_sh, bws + BL.kt, nullptr, N, L.n_pad, Hkv, d, C, nullptr};
+  if ((e = still::launch_transpose_v(tq, dt, B, stream)) != hipSuccess ||
+      (e = still::launch_transpose_v(td, dt, B, stream)) != hipSuccess ||
+      (e = still::launch_transpose_v(tk, dt, B, stream)) != hipSuccess)
+    return hip_fail("bwd transposes", e);
+  still::GatherArgs ga{};
+  ga.k = k; ga.v = k;
+  ga.k_sb = p->k_sb; ga.k_st = p->k_st; ga.k_sh = p->k_sh;
+  ga.v_sb = p->k_sb; ga.v_st = p->k_st; ga.v_sh = p->k_sh;
+  ga.map = map;
+  ga.sel = sel_idx;
+  ga.nsel = have_sel ? still::retained_rows(ncf, p->lambda, budget) : 0;
+  ga.sel_stride = ncf * p->lambda;
+  ga.C = C; ga.lam = p->lambda; ga.rcap = budget; ga.seq_len = nullptr;
+  ga.cap = L.cap; ga.Hq = Hq; ga.d = d; ga.N = N;
+  ga.kret = ws + L.kret; ga.vrett = ws + L.vrett;
+  if ((e = still::launch_gather(ga, dt, B, stream)) != hipSuccess) return hip_fail("bwd gather", e);
   still::BwdSaArgs sa{};
+  sa.qt = bws + BL.qt; sa.dot = bws + BL.dot; sa.kt = bws + BL.kt; sa.kret = ws + L.kret; sa.krett = ws + L.vrett;
+  sa.Np = L.n_pad; sa.cap = L.cap;
   sa.q = q; sa.k = k; sa.v = v; sa.dout = dout;
   sa.q_sb = p->q_sb; sa.q_st = p->q_st; sa.q_sh = p->q_sh;
   sa.k_sb = p->k_sb; sa.k_st = p->k_st; sa.k_sh = p->k_sh;

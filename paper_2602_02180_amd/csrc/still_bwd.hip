@@ -427,77 +427,39 @@ __global__ __launch_bounds__(256) void bwd_finish_kernel(BwdFinishArgs a) {
 
 // ---------------------------------------------------------------------------------------------------------
 // Sparse (softmax) branch.  Tiles of 64 query rows x 64 keys, four waves, one 32 x 32 block of logits each.
-// A key tile is either 64 consecutive entries of the head's retained list (routing order, gathered by token index)
-// or 64 consecutive tokens of the local span.  Row t of chunk c sees retained entry e when e < n_vis(c) =
-// min((c-1) lambda, budget), and local token j when (c-1) C <= j <= t.
+// A key tile is either 64 consecutive entries of the head's retained list (routing order) or 64 consecutive tokens of
+// the local span.  Row t of chunk c sees retained entry e when e < n_vis(c) = min((c-1) lambda, budget), and local
+// token j when (c-1) C <= j <= t.
+// Every matrix operand is read from global memory directly in fragment form (a lane's 8 consecutive contraction
+// entries are 16 contiguous bytes): rows of q, k, v, dout for the products that contract over the head dimension,
+// and transposed copies (q^T, dout^T, k^T of the local span, k^T of the retained rows, all [d][tokens], zero padded)
+// for those that contract over rows or keys.  LDS only carries P and dS from the accumulator layout of one product
+// to the operand layout of the next.
 // ---------------------------------------------------------------------------------------------------------
-template <typename T, int D>
+template <typename T>
 struct BwdTile {
   static constexpr int PAD = sizeof(T) == 2 ? 8 : 4;
-  static constexpr int LD = D + PAD;        // row stride of a [64][D] tile
-  static constexpr int LT = 64 + PAD;       // row stride of a [D][64] or [64][64] tile
-  static constexpr int EPV = 16 / sizeof(T);
+  static constexpr int LT = 64 + PAD;       // row stride of a [64][64] tile
 };
 
-// rows [r0, r0+64) of a strided tensor -> LDS [64][LD] (zero beyond n_rows), optionally also transposed [D][LT]
-template <typename T, int D, bool TR>
-__device__ __forceinline__ void load_rows(T* dst, T* dstT, const T* base, int64_t stride, const int* toks, int r0,
-                                          int n_rows, int tid) {
-  typedef BwdTile<T, D> Cf;
-  constexpr int VPR = D / Cf::EPV;   // 16-byte vectors per row
-  for (int idx = tid; idx < 64 * VPR; idx += 256) {
-    const int row = idx % 64, xv = idx / 64;
-    int tok = toks ? toks[row] : r0 + row;
-    const bool ok = tok >= 0 && tok < n_rows;
-    Vec16 v{{0u, 0u, 0u, 0u}};
-    if (ok) v = *reinterpret_cast<const Vec16*>(base + (int64_t)tok * stride + xv * Cf::EPV);
-    *reinterpret_cast<Vec16*>(dst + row * Cf::LD + xv * Cf::EPV) = v;
-    if (TR) {
-      const T* e = reinterpret_cast<const T*>(&v);
-#pragma unroll
-      for (int j = 0; j < Cf::EPV; ++j) dstT[(xv * Cf::EPV + j) * Cf::LT + row] = e[j];
-    }
-  }
-}
-
-// one wave's 32 x 32 block of X Y^T, X rows [32 xr ..], Y rows [32 yr ..] of [64][LD] tiles
-template <typename T, int D>
-__device__ __forceinline__ floatx16 block_xyT(const T* X, const T* Y, int xr, int yr, int l31, int g) {
+// acc += sum over 64 contraction entries of X[m][k] Y[n][k]: X an LDS tile [..][LT] (rows xr0 + m), Y rows in global
+// memory (row n of the block at yrow, contraction entries contiguous)
+template <typename T>
+__device__ __forceinline__ void acc64_lds_global(floatx16& acc, const T* X, int xr0, const T* yrow, int l31, int g) {
   typedef Mma<T> M;
-  typedef BwdTile<T, D> Cf;
-  floatx16 acc = zero16();
-#pragma unroll
-  for (int s = 0; s < D / M::KK; ++s)
-    acc = M::mma(M::load(X + (32 * xr + l31) * Cf::LD + s * M::KK + g * M::KPL),
-                 M::load(Y + (32 * yr + l31) * Cf::LD + s * M::KK + g * M::KPL), acc);
-  return acc;
-}
-
-// acc += sum over 64 contraction entries of X[32 xr + m][k] Y[32 yr + n][k], both [..][LT] tiles
-template <typename T, int D>
-__device__ __forceinline__ void block_acc64(floatx16& acc, const T* X, const T* Y, int xr, int yr, int l31, int g) {
-  typedef Mma<T> M;
-  typedef BwdTile<T, D> Cf;
 #pragma unroll
   for (int s = 0; s < 64 / M::KK; ++s)
-    acc = M::mma(M::load(X + (32 * xr + l31) * Cf::LT + s * M::KK + g * M::KPL),
-                 M::load(Y + (32 * yr + l31) * Cf::LT + s * M::KK + g * M::KPL), acc);
+    acc = M::mma(M::load(X + (xr0 + l31) * BwdTile<T>::LT + s * M::KK + g * M::KPL),
+                 M::load(yrow + s * M::KK + g * M::KPL), acc);
 }
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void bwd_sa_dq_kernel(BwdSaArgs a) {
-  typedef BwdTile<T, D> Cf;
-  constexpr int DX = D / 64;   // 32-column blocks of dq per wave
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  T* Qs = reinterpret_cast<T*>(smem);
-  T* dOs = Qs + 64 * Cf::LD;
-  T* Ks = dOs + 64 * Cf::LD;
-  T* Vs = Ks + 64 * Cf::LD;
-  T* KTs = Vs + 64 * Cf::LD;            // [D][LT]
-  T* dSs = KTs + D * Cf::LT;            // [64][LT]
-  float* Ls = reinterpret_cast<float*>(dSs + 64 * Cf::LT);
-  float* dls = Ls + 64;
-  int* toks = reinterpret_cast<int*>(dls + 64);
+  typedef Mma<T> M;
+  constexpr int LT = BwdTile<T>::LT, KS = D / M::KK, DX = D / 64;
+  __shared__ __attribute__((aligned(16))) T dSs[64 * LT];
+  __shared__ float Ls[64], dls[64];
+  __shared__ int toks[64];
 
   const int unit = blockIdx.y, rt = a.n_row_tiles - 1 - blockIdx.x;   // long rows first
   const int b = unit / a.Hq, h = unit % a.Hq, kvh = a.map.kv[h];
@@ -510,27 +472,39 @@ __global__ __launch_bounds__(256) void bwd_sa_dq_kernel(BwdSaArgs a) {
   const int last = min(N - 1, r0 + 63);
   const int n_ret_tiles = (n_vis + 63) / 64, n_tiles = n_ret_tiles + (last + 1 - lo + 63) / 64;
 
-  const T* qb = static_cast<const T*>(a.q) + b * a.q_sb + h * a.q_sh;
-  const T* dob = static_cast<const T*>(a.dout) + b * a.o_sb + h * a.o_sh;
   const T* kb = static_cast<const T*>(a.k) + b * a.k_sb + kvh * a.k_sh;
   const T* vb = static_cast<const T*>(a.v) + b * a.v_sb + kvh * a.v_sh;
+  const T* kret = static_cast<const T*>(a.kret) + (int64_t)unit * a.cap * D;
+  const T* krett = static_cast<const T*>(a.krett) + (int64_t)unit * D * a.cap;
+  const T* kt = static_cast<const T*>(a.kt) + ((int64_t)b * a.Hkv + kvh) * D * a.Np;
   const int32_t* sel = a.sel + (int64_t)unit * a.sel_stride;
-  load_rows<T, D, false>(Qs, nullptr, qb, a.q_st, nullptr, r0, N, tid);
-  load_rows<T, D, false>(dOs, nullptr, dob, a.o_st, nullptr, r0, N, tid);
   if (tid < 64) {
     const int t = r0 + tid;
     Ls[tid] = t < N ? a.lse[(int64_t)unit * N + t] * kLog2e : 0.f;
     dls[tid] = t < N ? a.delta[(int64_t)unit * N + t] : 0.f;
   }
+  // this wave's 32 query rows as A operands, for the whole kernel
+  typename M::frag qf[KS], dof[KS];
+  {
+    const int t = min(r0 + 32 * wr + l31, N - 1);
+    const T* qp = static_cast<const T*>(a.q) + b * a.q_sb + (int64_t)t * a.q_st + h * a.q_sh + g * M::KPL;
+    const T* dp = static_cast<const T*>(a.dout) + b * a.o_sb + (int64_t)t * a.o_st + h * a.o_sh + g * M::KPL;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      qf[s] = M::load(qp + s * M::KK);
+      dof[s] = M::load(dp + s * M::KK);
+    }
+  }
   floatx16 dq[DX];
 #pragma unroll
   for (int j = 0; j < DX; ++j) dq[j] = zero16();
   const float sc2 = a.scale * kLog2e;
+  const int kcol = 32 * wc + l31;
 
   for (int ti = 0; ti < n_tiles; ++ti) {
     const bool ret = ti < n_ret_tiles;
     const int k0 = ret ? ti * 64 : lo + (ti - n_ret_tiles) * 64;
-    __syncthreads();   // the previous tile's products are done; also orders the loads above
+    __syncthreads();   // the previous tile's products have read dSs and toks (first trip: Ls, dls are written)
     if (tid < 64) {
       int tok;
       if (ret) {
@@ -543,24 +517,30 @@ __global__ __launch_bounds__(256) void bwd_sa_dq_kernel(BwdSaArgs a) {
       toks[tid] = tok;
     }
     __syncthreads();
-    load_rows<T, D, true>(Ks, KTs, kb, a.k_st, toks, 0, N, tid);
-    load_rows<T, D, false>(Vs, nullptr, vb, a.v_st, toks, 0, N, tid);
-    __syncthreads();
-    floatx16 s = block_xyT<T, D>(Qs, Ks, wr, wc, l31, g);
-    floatx16 dp = block_xyT<T, D>(dOs, Vs, wr, wc, l31, g);
-    const int kcol = 32 * wc + l31;
     const int tok = toks[kcol];
+    const int tokc = tok < 0 ? 0 : tok;
+    const T* krow = (ret ? kret + (int64_t)(k0 + kcol) * D : kb + (int64_t)tokc * a.k_st) + g * M::KPL;
+    const T* vrow = vb + (int64_t)tokc * a.v_st + g * M::KPL;
+    floatx16 s = zero16(), dp = zero16();
+#pragma unroll
+    for (int st = 0; st < KS; ++st) {
+      s = M::mma(qf[st], M::load(krow + st * M::KK), s);
+      dp = M::mma(dof[st], M::load(vrow + st * M::KK), dp);
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int r = 32 * wr + c_row(i, g);
       const int t = r0 + r;
       const bool vis = tok >= 0 && t < N && (ret || (tok >= lo && tok <= t));
       const float p = vis ? fast_exp2(fmaf(s[i], sc2, -Ls[r])) : 0.f;
-      dSs[r * Cf::LT + kcol] = from_f32<T>(p * (dp[i] - dls[r]) * a.scale);
+      dSs[r * LT + kcol] = from_f32<T>(p * (dp[i] - dls[r]) * a.scale);
     }
     __syncthreads();
+    const T* ktile = ret ? krett + k0 : kt + k0;
+    const int64_t kstride = ret ? a.cap : a.Np;
 #pragma unroll
-    for (int j = 0; j < DX; ++j) block_acc64<T, D>(dq[j], dSs, KTs, wr, wc * DX + j, l31, g);
+    for (int j = 0; j < DX; ++j)
+      acc64_lds_global<T>(dq[j], dSs, 32 * wr, ktile + (int64_t)(32 * (wc * DX + j) + l31) * kstride, l31, g);
   }
   float* out = a.dq32 + ((int64_t)unit * N) * D;
 #pragma unroll
@@ -574,20 +554,12 @@ __global__ __launch_bounds__(256) void bwd_sa_dq_kernel(BwdSaArgs a) {
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
-  typedef BwdTile<T, D> Cf;
-  constexpr int DX = D / 64;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  T* Qs = reinterpret_cast<T*>(smem);
-  T* dOs = Qs + 64 * Cf::LD;
-  T* Ks = dOs + 64 * Cf::LD;
-  T* Vs = Ks + 64 * Cf::LD;
-  T* QTs = Vs + 64 * Cf::LD;            // [D][LT]
-  T* dOTs = QTs + D * Cf::LT;           // [D][LT]
-  T* PTs = dOTs + D * Cf::LT;           // [64 keys][LT rows]
-  T* dSTs = PTs + 64 * Cf::LT;
-  float* Ls = reinterpret_cast<float*>(dSTs + 64 * Cf::LT);
-  float* dls = Ls + 64;
-  int* toks = reinterpret_cast<int*>(dls + 64);
+  typedef Mma<T> M;
+  constexpr int LT = BwdTile<T>::LT, KS = D / M::KK, DX = D / 64;
+  __shared__ __attribute__((aligned(16))) T PTs[64 * LT];     // [key][row]
+  __shared__ __attribute__((aligned(16))) T dSTs[64 * LT];
+  __shared__ float Ls[64], dls[64];
+  __shared__ int toks[64];
 
   const int unit = blockIdx.y, ti = blockIdx.x;   // retained tiles (the long ones) come first
   const int b = unit / a.Hq, h = unit % a.Hq, kvh = a.map.kv[h];
@@ -610,6 +582,8 @@ __global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
   const T* dob = static_cast<const T*>(a.dout) + b * a.o_sb + h * a.o_sh;
   const T* kb = static_cast<const T*>(a.k) + b * a.k_sb + kvh * a.k_sh;
   const T* vb = static_cast<const T*>(a.v) + b * a.v_sb + kvh * a.v_sh;
+  const T* qt = static_cast<const T*>(a.qt) + (int64_t)unit * D * a.Np;
+  const T* dot = static_cast<const T*>(a.dot) + (int64_t)unit * D * a.Np;
   const int32_t* sel = a.sel + (int64_t)unit * a.sel_stride;
   if (tid < 64) {
     int tok;
@@ -623,56 +597,68 @@ __global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
     toks[tid] = tok;
   }
   __syncthreads();
-  load_rows<T, D, false>(Ks, nullptr, kb, a.k_st, toks, 0, N, tid);
-  load_rows<T, D, false>(Vs, nullptr, vb, a.v_st, toks, 0, N, tid);
+  const int kcol = 32 * wc + l31;
+  const int tok = toks[kcol];
+  // this wave's 32 keys as B operands of the logits and of dy.v, for the whole kernel
+  typename M::frag kf[KS], vf[KS];
+  {
+    const int tokc = tok < 0 ? 0 : tok;
+    const T* kp = kb + (int64_t)tokc * a.k_st + g * M::KPL;
+    const T* vp = vb + (int64_t)tokc * a.v_st + g * M::KPL;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      kf[s] = M::load(kp + s * M::KK);
+      vf[s] = M::load(vp + s * M::KK);
+    }
+  }
   floatx16 dk[DX], dv[DX];
 #pragma unroll
   for (int j = 0; j < DX; ++j) dk[j] = dv[j] = zero16();
   const float sc2 = a.scale * kLog2e;
-  const int kcol = 32 * wc + l31;
+  const int e = k0 + kcol;
 
   for (int r0 = row_lo / 64 * 64; r0 < row_hi; r0 += 64) {
-    __syncthreads();
-    load_rows<T, D, true>(Qs, QTs, qb, a.q_st, nullptr, r0, N, tid);
-    load_rows<T, D, true>(dOs, dOTs, dob, a.o_st, nullptr, r0, N, tid);
+    __syncthreads();   // the previous trip's products have read PTs, dSTs, Ls, dls
     if (tid < 64) {
       const int t = r0 + tid;
       Ls[tid] = t < N ? a.lse[(int64_t)unit * N + t] * kLog2e : 0.f;
       dls[tid] = t < N ? a.delta[(int64_t)unit * N + t] : 0.f;
     }
-    __syncthreads();
-    floatx16 s = block_xyT<T, D>(Qs, Ks, wr, wc, l31, g);
-    floatx16 dp = block_xyT<T, D>(dOs, Vs, wr, wc, l31, g);
-    const int tok = toks[kcol];
-    const int e = k0 + kcol;
+    floatx16 s = zero16(), dp = zero16();
+    {
+      const int t = min(r0 + 32 * wr + l31, N - 1);
+      const T* qp = qb + (int64_t)t * a.q_st + g * M::KPL;
+      const T* dp_ = dob + (int64_t)t * a.o_st + g * M::KPL;
+#pragma unroll
+      for (int st = 0; st < KS; ++st) {
+        s = M::mma(M::load(qp + st * M::KK), kf[st], s);
+        dp = M::mma(M::load(dp_ + st * M::KK), vf[st], dp);
+      }
+    }
+    __syncthreads();   // Ls, dls visible
 #pragma unroll
     for (int i4 = 0; i4 < 4; ++i4) {
-      float pv[4], dsv[4];
+      const int rbase = 32 * wr + c_row(4 * i4, g);   // four consecutive rows
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int i = 4 * i4 + j;
-        const int r = 32 * wr + c_row(i, g);
+        const int r = rbase + j;
         const int t = r0 + r;
         const int c = t / C;
         bool vis = tok >= 0 && t < N;
         if (ret) vis = vis && e < retained_rows(c >= 1 ? c - 1 : 0, a.lam, a.rcap);
         else vis = vis && tok <= t && tok >= (c >= 1 ? c - 1 : 0) * C;
         const float p = vis ? fast_exp2(fmaf(s[i], sc2, -Ls[r])) : 0.f;
-        pv[j] = p;
-        dsv[j] = p * (dp[i] - dls[r]) * a.scale;
-      }
-      const int rbase = 32 * wr + c_row(4 * i4, g);   // four consecutive rows
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        PTs[kcol * Cf::LT + rbase + j] = from_f32<T>(pv[j]);
-        dSTs[kcol * Cf::LT + rbase + j] = from_f32<T>(dsv[j]);
+        PTs[kcol * LT + r] = from_f32<T>(p);
+        dSTs[kcol * LT + r] = from_f32<T>(p * (dp[i] - dls[r]) * a.scale);
       }
     }
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < DX; ++j) {
-      block_acc64<T, D>(dv[j], PTs, dOTs, wr, wc * DX + j, l31, g);    // dV[key][x] += P^T dO
-      block_acc64<T, D>(dk[j], dSTs, QTs, wr, wc * DX + j, l31, g);    // dK[key][x] += dS^T Q
+      const int64_t xrow = (int64_t)(32 * (wc * DX + j) + l31) * a.Np + r0;
+      acc64_lds_global<T>(dv[j], PTs, 32 * wr, dot + xrow, l31, g);    // dV[key][x] += P^T dO
+      acc64_lds_global<T>(dk[j], dSTs, 32 * wr, qt + xrow, l31, g);    // dK[key][x] += dS^T Q
     }
   }
   float* dkb = a.dk32 + ((int64_t)b * a.Hkv + kvh) * N * D;
@@ -681,43 +667,21 @@ __global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
   for (int j = 0; j < DX; ++j)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int tok = toks[32 * wr + c_row(i, g)];
-      if (tok >= 0) {
+      const int tk = toks[32 * wr + c_row(i, g)];
+      if (tk >= 0) {
         const int x = 32 * (wc * DX + j) + l31;
-        atomicAdd(dkb + (int64_t)tok * D + x, dk[j][i]);
-        atomicAdd(dvb + (int64_t)tok * D + x, dv[j][i]);
+        atomicAdd(dkb + (int64_t)tk * D + x, dk[j][i]);
+        atomicAdd(dvb + (int64_t)tk * D + x, dv[j][i]);
       }
     }
 }
 
 template <typename T, int D>
-size_t sa_dq_smem() {
-  typedef BwdTile<T, D> Cf;
-  return (size_t)(4 * 64 * Cf::LD + D * Cf::LT + 64 * Cf::LT) * sizeof(T) + 64 * 4 * 3;
-}
-template <typename T, int D>
-size_t sa_dkv_smem() {
-  typedef BwdTile<T, D> Cf;
-  return (size_t)(4 * 64 * Cf::LD + 2 * D * Cf::LT + 2 * 64 * Cf::LT) * sizeof(T) + 64 * 4 * 3;
-}
-
-template <typename T, int D>
 hipError_t launch_sa_t(const BwdSaArgs& a, int U, hipStream_t s) {
-  static bool attr_done = false;
-  const size_t s1 = sa_dq_smem<T, D>(), s2 = sa_dkv_smem<T, D>();
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_sa_dq_kernel<T, D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)s1);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_sa_dkv_kernel<T, D>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)s2);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
-  hipLaunchKernelGGL((bwd_sa_dq_kernel<T, D>), dim3(a.n_row_tiles, U), dim3(256), s1, s, a);
+  hipLaunchKernelGGL((bwd_sa_dq_kernel<T, D>), dim3(a.n_row_tiles, U), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((bwd_sa_dkv_kernel<T, D>), dim3(a.n_ret_tiles + a.n_row_tiles, U), dim3(256), s2, s, a);
+  hipLaunchKernelGGL((bwd_sa_dkv_kernel<T, D>), dim3(a.n_ret_tiles + a.n_row_tiles, U), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -362,6 +362,11 @@ struct BwdSaArgs {
   const void* v;
   const void* dout;
   int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh, v_sb, v_st, v_sh, o_sb, o_st, o_sh;
+  const void* qt;          // [U, d, Np]: q transposed, zero padded
+  const void* dot;         // [U, d, Np]: dout transposed
+  const void* kt;          // [B, Hkv, d, Np]: k transposed
+  const void* kret;        // [U, cap, d]: retained keys in routing order, zero rows where no token is retained
+  const void* krett;       // [U, d, cap]: the same, transposed
   const int32_t* sel;      // [U, sel_stride]: retained entry e is token sel[e] (chunk e / lam)
   const float* lse;        // [U, N]
   const float* delta;      // [U, N]
@@ -369,7 +374,7 @@ struct BwdSaArgs {
   float* dk32;             // [B, Hkv, N, d], zeroed by the caller
   float* dv32;
   HeadMap map;
-  int N, C, lam, rcap, Hq, Hkv, nc, sel_stride, n_row_tiles, n_ret_tiles;
+  int N, Np, cap, C, lam, rcap, Hq, Hkv, nc, sel_stride, n_row_tiles, n_ret_tiles;
   float scale;
 };
 hipError_t launch_bgemm(const GemmArgs& a, int dtype, int U, int n_c, hipStream_t stream);
