@@ -374,6 +374,7 @@ typedef struct still_bwd_ws_layout {
   size_t dfq, dfk; /* dtype [B, Hq, N, d_f]   gradient of f(x)                                                */
   size_t dq32;     /* float [B, Hq, N, d]                                                                     */
   size_t dk32, dv32; /* float [B, Hkv, N, d]                                                                  */
+  size_t cxq, cxk; /* float [B, Hq, N]        coefficient of x in its own gradient (the norm |x| of Sec. 3.2)   */
   size_t qt, dot;  /* dtype [B, Hq, d, Npad]  q and dout transposed, zero padded                              */
   size_t kt;       /* dtype [B, Hkv, d, Npad] k transposed                                                    */
   size_t total;

@@ -848,6 +848,8 @@ void compute_bwd_layout(const still_params_t* p, still_bwd_ws_layout_t* L) {
   L->dq32 = take(rows * d * 4);
   L->dk32 = take(kvrows * d * 4);
   L->dv32 = take(kvrows * d * 4);
+  L->cxq = take(rows * 4);
+  L->cxk = take(rows * 4);
   L->qt = take(U * d * (size_t)F.n_pad * es);
   L->dot = take(U * d * (size_t)F.n_pad * es);
   L->kt = take((size_t)p->B * p->Hkv * d * (size_t)F.n_pad * es);
@@ -904,12 +906,9 @@ still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, c
     return fail(STILL_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
   };
   auto f32p = [&](size_t off) { return reinterpret_cast<float*>(bws + off); };
-  const int64_t rows = (int64_t)U * N, kvrows = (int64_t)B * Hkv * N;
 
   // ---- outputs and accumulators that are added into
-  if ((e = still::launch_fill_f32(f32p(BL.dk32), kvrows * d, 0.f, stream)) != hipSuccess ||
-      (e = still::launch_fill_f32(f32p(BL.dv32), kvrows * d, 0.f, stream)) != hipSuccess ||
-      (e = still::launch_fill_f32(dWq, (int64_t)Hq * d * F, 0.f, stream)) != hipSuccess ||
+  if ((e = still::launch_fill_f32(dWq, (int64_t)Hq * d * F, 0.f, stream)) != hipSuccess ||
       (e = still::launch_fill_f32(dWk, (int64_t)Hq * d * F, 0.f, stream)) != hipSuccess ||
       (dbq && (e = still::launch_fill_f32(dbq, (int64_t)Hq * F, 0.f, stream)) != hipSuccess) ||
       (dbk && (e = still::launch_fill_f32(dbk, (int64_t)Hq * F, 0.f, stream)) != hipSuccess))
@@ -988,7 +987,7 @@ still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, c
   sa.n_row_tiles = (N + 63) / 64;
   sa.n_ret_tiles = (still::retained_rows(nc >= 2 ? nc - 2 : 0, sa.lam, budget) + 63) / 64;
   sa.scale = p->scale;
-  if ((e = still::launch_bwd_sa(sa, dt, d, U, stream)) != hipSuccess) return hip_fail("bwd_sparse_attention", e);
+  if ((e = still::launch_bwd_sa(sa, dt, d, B, stream)) != hipSuccess) return hip_fail("bwd_sparse_attention", e);
 
   // ---- NP-Map of q and k again: f = x W on the matrix core, then phi, u and the norms per token
   still::GemmArgs gm{};
@@ -1016,14 +1015,14 @@ still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, c
   nq.x = q; nq.x_sb = p->q_sb; nq.x_st = p->q_st; nq.x_sh = p->q_sh; nq.x_kv = 0;
   nq.bias = bq; nq.u = f32p(BL.uq); nq.st = f32p(BL.stq); nq.phi = bws + BL.phi_q; nq.kmask = nullptr;
   nq.dphi = f32p(BL.gq); nq.coef = ra.ed; nq.z1 = la.zsnap; nq.z2 = la.zpre;
-  nq.df = bws + BL.dfq; nq.dx32 = f32p(BL.dq32);
+  nq.df = bws + BL.dfq; nq.cx = f32p(BL.cxq);
   nq.map = map; nq.U = U; nq.N = N; nq.Hq = Hq; nq.Hkv = Hkv; nq.d = d; nq.F = F; nq.C = C; nq.nc = nc; nq.ncf = ncf;
   nq.nseg = L.nseg; nq.seg_chunks = L.seg_chunks;
   still::BwdNpArgs nk = nq;
   nk.x = k; nk.x_sb = p->k_sb; nk.x_st = p->k_st; nk.x_sh = p->k_sh; nk.x_kv = 1;
   nk.bias = bk; nk.u = f32p(BL.uk); nk.st = f32p(BL.stk); nk.phi = bws + BL.phi_k; nk.kmask = la.kmask;
   nk.dphi = f32p(BL.dphi_k); nk.coef = nullptr; nk.z1 = f32p(BL.dz); nk.z2 = nullptr;
-  nk.df = bws + BL.dfk; nk.dx32 = f32p(BL.dk32);
+  nk.df = bws + BL.dfk; nk.cx = f32p(BL.cxk);
   if ((e = still::launch_bwd_np(nq, dt, false, stream)) != hipSuccess ||
       (e = still::launch_bwd_np(nk, dt, false, stream)) != hipSuccess)
     return hip_fail("bwd_np_fwd", e);
@@ -1088,9 +1087,9 @@ still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, c
   }
 
   // ---- fp32 sums -> the caller's tensors
-  still::BwdFinishArgs fq{f32p(BL.dq32), dq, p->q_sb, p->q_st, p->q_sh, B, Hq, N, d};
-  still::BwdFinishArgs fk{f32p(BL.dk32), dk, p->k_sb, p->k_st, p->k_sh, B, Hkv, N, d};
-  still::BwdFinishArgs fv{f32p(BL.dv32), dv, p->v_sb, p->v_st, p->v_sh, B, Hkv, N, d};
+  still::BwdFinishArgs fq{f32p(BL.dq32), dq, q, p->q_sb, p->q_st, p->q_sh, f32p(BL.cxq), 0, map, B, Hq, Hq, N, d};
+  still::BwdFinishArgs fk{f32p(BL.dk32), dk, k, p->k_sb, p->k_st, p->k_sh, f32p(BL.cxk), 1, map, B, Hkv, Hq, N, d};
+  still::BwdFinishArgs fv{f32p(BL.dv32), dv, v, p->v_sb, p->v_st, p->v_sh, nullptr, 0, map, B, Hkv, Hq, N, d};
   if ((e = still::launch_bwd_finish(fq, dt, stream)) != hipSuccess ||
       (e = still::launch_bwd_finish(fk, dt, stream)) != hipSuccess ||
       (e = still::launch_bwd_finish(fv, dt, stream)) != hipSuccess)

@@ -160,206 +160,246 @@ __global__ __launch_bounds__(256) void bgemm_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Element-wise kernels (one wave per token row unless said otherwise)
+// Element-wise kernels
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void fill_f32_kernel(float* p, int64_t n, float x) {
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = x;
 }
 
+// The row-wise kernels below give every token row to d/8 lanes (d = d_f here), 8 contiguous elements per lane, so
+// that every access is a 16-byte (storage type) or 32-byte (fp32) vector and a row reduction is 3 or 4 exchanges
+// inside the group.  A wave holds 64 / (d/8) rows, a workgroup four waves.
+template <typename T>
+__device__ __forceinline__ void load8_t(float (&x)[8], const T* p) {
+  load8<T>(x, p, 0, 0);
+}
+template <typename T>
+__device__ __forceinline__ void store8_t(T* p, const float (&x)[8]) {
+  if constexpr (sizeof(T) == 2) {
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = static_cast<bf16>(x[e]);
+    *reinterpret_cast<bf16x8*>(p) = v;
+  } else {
+    floatx4 a, b;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { a[e] = x[e]; b[e] = x[4 + e]; }
+    *reinterpret_cast<floatx4*>(p) = a;
+    *reinterpret_cast<floatx4*>(p + 4) = b;
+  }
+}
+__device__ __forceinline__ void load8_f32(float (&x)[8], const float* p) { load8<float>(x, p, 0, 1); }
+__device__ __forceinline__ void store8_f32(float* p, const float (&x)[8]) { store8_t<float>(p, x); }
+__device__ __forceinline__ float group_sum(float x, int lpr) {
+  for (int o = lpr >> 1; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+__device__ __forceinline__ float group_max(float x, int lpr) {
+  for (int o = lpr >> 1; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+// row handled by this lane, and its first element; false when the row is past the end (whole groups drop out)
+__device__ __forceinline__ bool row_of_lane(int64_t n_rows, int width, int64_t& row, int& e0, int& lpr) {
+  lpr = width / 8;
+  const int tid = threadIdx.x;
+  row = (int64_t)blockIdx.x * (256 / lpr) + tid / lpr;
+  e0 = (tid % lpr) * 8;
+  return row < n_rows;
+}
+
 // delta_t = dy_t . y_t, E_t = exp(-L_t), A_t = E_t (gate_t * dy_t)
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_row_prep_kernel(BwdRowArgs a) {
-  const int64_t row = blockIdx.x * 4ll + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  if (row >= (int64_t)a.U * a.N) return;
-  const int unit = (int)(row / a.N), t = (int)(row % a.N);
+  int64_t row;
+  int e0, lpr;
+  const bool live = row_of_lane((int64_t)a.U * a.N, a.d, row, e0, lpr);
+  const int64_t rowc = live ? row : 0;
+  const int unit = (int)(rowc / a.N), t = (int)(rowc % a.N);
   const int b = unit / a.Hq, h = unit % a.Hq;
-  const T* y = static_cast<const T*>(a.out) + b * a.o_sb + (int64_t)t * a.o_st + h * a.o_sh;
-  const T* dy = static_cast<const T*>(a.dout) + b * a.o_sb + (int64_t)t * a.o_st + h * a.o_sh;
-  const T* gp = a.g ? static_cast<const T*>(a.g) + b * a.g_sb + (int64_t)t * a.g_st + h * a.g_sh : nullptr;
-  const float E = __expf(-a.lse[row]);
-  float dot = 0.f;
-  for (int x = lane; x < a.d; x += 64) {
-    const float dyx = to_f32<T>(dy[x]);
-    dot += dyx * to_f32<T>(y[x]);
-    float gate = 1.f;
-    if (gp) {
-      gate = to_f32<T>(gp[x]);
-      if (a.gate_act) gate = 1.f / (1.f + __expf(-gate));
+  const int64_t oo = b * a.o_sb + (int64_t)t * a.o_st + h * a.o_sh + e0;
+  float y[8], dy[8], gate[8];
+  load8_t<T>(y, static_cast<const T*>(a.out) + oo);
+  load8_t<T>(dy, static_cast<const T*>(a.dout) + oo);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) gate[e] = 1.f;
+  if (a.g) {
+    load8_t<T>(gate, static_cast<const T*>(a.g) + b * a.g_sb + (int64_t)t * a.g_st + h * a.g_sh + e0);
+    if (a.gate_act) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) gate[e] = 1.f / (1.f + __expf(-gate[e]));
     }
-    static_cast<T*>(a.A)[row * a.d + x] = from_f32<T>(E * gate * dyx);
   }
-  dot = wave_sum(dot);
-  if (lane == 0) {
+  const float E = __expf(-a.lse[rowc]);
+  float dot = 0.f, av[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    dot += dy[e] * y[e];
+    av[e] = E * gate[e] * dy[e];
+  }
+  dot = group_sum(dot, lpr);
+  if (!live) return;
+  store8_t<T>(static_cast<T*>(a.A) + row * a.d + e0, av);
+  if (e0 == 0) {
     a.e_row[row] = E;
     a.delta[row] = dot;
     a.ed[row] = E * dot;
   }
 }
 
+__device__ __forceinline__ bool token_kept(const BwdNpArgs& a, int unit, int t) {
+  if (a.kmask == nullptr || t >= a.ncf * a.C) return false;
+  const int c = t / a.C, w = t % a.C;
+  return (a.kmask[((int64_t)unit * a.ncf + c) * (a.C / 32) + w / 32] >> (w & 31)) & 1u;
+}
+
 // NP-Map forward from f = x W (bias added here): phi (storage type; zero for tokens the softmax branch keeps),
 // u over f in place, and (|x|, |f|).
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_np_fwd_kernel(BwdNpArgs a) {
-  const int64_t row = blockIdx.x * 4ll + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  if (row >= (int64_t)a.U * a.N) return;
-  const int unit = (int)(row / a.N), t = (int)(row % a.N);
+  int64_t row;
+  int e0, lpr;
+  const bool live = row_of_lane((int64_t)a.U * a.N, a.F, row, e0, lpr);
+  const int64_t rowc = live ? row : 0;
+  const int unit = (int)(rowc / a.N), t = (int)(rowc % a.N);
   const int b = unit / a.Hq, h = unit % a.Hq;
   const int hx = a.x_kv ? a.map.kv[h] : h;
-  const T* x = static_cast<const T*>(a.x) + b * a.x_sb + (int64_t)t * a.x_st + hx * a.x_sh;
   const int F = a.F;
-  float* f = a.u + row * F;
-  const T* bias = a.bias ? static_cast<const T*>(a.bias) + h * F : nullptr;
-  float nx2 = 0.f;
-  for (int i = lane; i < a.d; i += 64) {
-    const float xv = to_f32<T>(x[i]);
-    nx2 += xv * xv;
-  }
-  float fv[2], nf2 = 0.f;
+  float xv[8], fv[8];
+  load8_t<T>(xv, static_cast<const T*>(a.x) + b * a.x_sb + (int64_t)t * a.x_st + hx * a.x_sh + e0);
+  load8_f32(fv, a.u + rowc * F + e0);
+  if (a.bias) {
+    float bv[8];
+    load8_t<T>(bv, static_cast<const T*>(a.bias) + h * F + e0);
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int i = lane + 64 * j;
-    fv[j] = 0.f;
-    if (i < F) {
-      fv[j] = f[i] + (bias ? to_f32<T>(bias[i]) : 0.f);
-      nf2 += fv[j] * fv[j];
-    }
+    for (int e = 0; e < 8; ++e) fv[e] += bv[e];
   }
-  nx2 = wave_sum(nx2);
-  nf2 = wave_sum(nf2);
+  float nx2 = 0.f, nf2 = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    nx2 += xv[e] * xv[e];
+    nf2 += fv[e] * fv[e];
+  }
+  nx2 = group_sum(nx2, lpr);
+  nf2 = group_sum(nf2, lpr);
   const float nx = sqrtf(nx2), nf = sqrtf(nf2);
   const float ratio = nf2 > 0.f ? nx / nf : 0.f;
   float mp = -INFINITY, mn = -INFINITY;
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
-    if (lane + 64 * j < F) {
-      fv[j] *= ratio;
-      mp = fmaxf(mp, fv[j]);
-      mn = fmaxf(mn, -fv[j]);
-    }
-  mp = wave_max(mp);
-  mn = wave_max(mn);
-  float ep[2], en[2], sp = 0.f, sn = 0.f;
+  for (int e = 0; e < 8; ++e) {
+    fv[e] *= ratio;
+    mp = fmaxf(mp, fv[e]);
+    mn = fmaxf(mn, -fv[e]);
+  }
+  mp = group_max(mp, lpr);
+  mn = group_max(mn, lpr);
+  float ep[8], en[8], sp = 0.f, sn = 0.f;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    ep[j] = en[j] = 0.f;
-    if (lane + 64 * j < F) {
-      ep[j] = __expf(fv[j] - mp);
-      en[j] = __expf(-fv[j] - mn);
-      sp += ep[j];
-      sn += en[j];
-    }
+  for (int e = 0; e < 8; ++e) {
+    ep[e] = __expf(fv[e] - mp);
+    en[e] = __expf(-fv[e] - mn);
+    sp += ep[e];
+    sn += en[e];
   }
-  sp = wave_sum(sp);
-  sn = wave_sum(sn);
-  bool kept = false;
-  if (a.kmask != nullptr && t < a.ncf * a.C) {
-    const int c = t / a.C, w = t % a.C;
-    kept = (a.kmask[((int64_t)unit * a.ncf + c) * (a.C / 32) + w / 32] >> (w & 31)) & 1u;
-  }
+  sp = group_sum(sp, lpr);
+  sn = group_sum(sn, lpr);
+  if (!live) return;
+  const bool kept = token_kept(a, unit, t);
   const float ip = kept ? 0.f : 1.f / sp, in = kept ? 0.f : 1.f / sn;
-  T* phi = static_cast<T*>(a.phi) + row * 2 * F;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int i = lane + 64 * j;
-    if (i < F) {
-      phi[i] = from_f32<T>(ep[j] * ip);
-      phi[F + i] = from_f32<T>(en[j] * in);
-      f[i] = fv[j];
-    }
+  for (int e = 0; e < 8; ++e) {
+    ep[e] *= ip;
+    en[e] *= in;
   }
-  if (lane == 0) {
+  T* phi = static_cast<T*>(a.phi) + row * 2 * F;
+  store8_t<T>(phi + e0, ep);
+  store8_t<T>(phi + F + e0, en);
+  store8_f32(a.u + row * F + e0, fv);
+  if (e0 == 0) {
     a.st[2 * row] = nx;
     a.st[2 * row + 1] = nf;
   }
 }
 
-// NP-Map backward for one token: dphi (minus coef * z) -> df in the storage type, and the |x| path of dx added to the
-// fp32 gradient of x (plain add where the row is owned, atomic where query heads share a kv head).
+// NP-Map backward for one token: dphi (minus coef * z) -> df in the storage type, and the coefficient of the |x| path
+// of dx (dx = df W^T + <fh, du> x / |x|).
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_np_bwd_kernel(BwdNpArgs a) {
-  const int64_t row = blockIdx.x * 4ll + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  if (row >= (int64_t)a.U * a.N) return;
-  const int unit = (int)(row / a.N), t = (int)(row % a.N);
+  int64_t row;
+  int e0, lpr;
+  const bool live = row_of_lane((int64_t)a.U * a.N, a.F, row, e0, lpr);
+  const int64_t rowc = live ? row : 0;
+  const int unit = (int)(rowc / a.N), t = (int)(rowc % a.N);
   const int b = unit / a.Hq, h = unit % a.Hq;
   const int hx = a.x_kv ? a.map.kv[h] : h;
   const int F = a.F, c = t / a.C;
-  T* df = static_cast<T*>(a.df) + row * F;
-  bool kept = false;
-  if (a.kmask != nullptr && t < a.ncf * a.C) {
-    const int w = t % a.C;
-    kept = (a.kmask[((int64_t)unit * a.ncf + c) * (a.C / 32) + w / 32] >> (w & 31)) & 1u;
-  }
-  const float nx = a.st[2 * row], nf = a.st[2 * row + 1];
-  if (kept || !(nx > 0.f) || !(nf > 0.f)) {   // uniform over the wave
-    for (int i = lane; i < F; i += 64) df[i] = from_f32<T>(0.f);
-    return;
-  }
-  const float* u = a.u + row * F;
-  const float* dphi = a.dphi + row * 2 * F;
-  const float coef = a.coef ? a.coef[row] : 1.f;
-  const float* z1 = a.z1 + ((int64_t)unit * a.nc + c) * 2 * F;
-  const float* z2 = a.z2 ? a.z2 + ((int64_t)unit * a.nseg + c / a.seg_chunks) * 2 * F : nullptr;
-  float uv[2], mp = -INFINITY, mn = -INFINITY;
+  const float nx = a.st[2 * rowc], nf = a.st[2 * rowc + 1];
+  const bool dead = token_kept(a, unit, t) || !(nx > 0.f) || !(nf > 0.f);   // uniform over the row's lanes
+  const float coef = a.coef ? a.coef[rowc] : 1.f;
+  const float* z1 = a.z1 + ((int64_t)unit * a.nc + c) * 2 * F + e0;
+  float uv[8], dp[8], dn[8], zz[8];
+  load8_f32(uv, a.u + rowc * F + e0);
+  load8_f32(dp, a.dphi + rowc * 2 * F + e0);
+  load8_f32(dn, a.dphi + rowc * 2 * F + F + e0);
+  load8_f32(zz, z1);
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
-    if (lane + 64 * j < F) {
-      uv[j] = u[lane + 64 * j];
-      mp = fmaxf(mp, uv[j]);
-      mn = fmaxf(mn, -uv[j]);
-    }
-  mp = wave_max(mp);
-  mn = wave_max(mn);
-  float ep[2], en[2], dp[2], dn[2], sp = 0.f, sn = 0.f;
+  for (int e = 0; e < 8; ++e) dp[e] -= coef * zz[e];
+  load8_f32(zz, z1 + F);
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int i = lane + 64 * j;
-    ep[j] = en[j] = dp[j] = dn[j] = 0.f;
-    if (i < F) {
-      ep[j] = __expf(uv[j] - mp);
-      en[j] = __expf(-uv[j] - mn);
-      sp += ep[j];
-      sn += en[j];
-      dp[j] = dphi[i] - coef * (z1[i] + (z2 ? z2[i] : 0.f));
-      dn[j] = dphi[F + i] - coef * (z1[F + i] + (z2 ? z2[F + i] : 0.f));
-    }
+  for (int e = 0; e < 8; ++e) dn[e] -= coef * zz[e];
+  if (a.z2) {
+    const float* z2 = a.z2 + ((int64_t)unit * a.nseg + c / a.seg_chunks) * 2 * F + e0;
+    load8_f32(zz, z2);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dp[e] -= coef * zz[e];
+    load8_f32(zz, z2 + F);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dn[e] -= coef * zz[e];
   }
-  sp = wave_sum(sp);
-  sn = wave_sum(sn);
+  float mp = -INFINITY, mn = -INFINITY;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    mp = fmaxf(mp, uv[e]);
+    mn = fmaxf(mn, -uv[e]);
+  }
+  mp = group_max(mp, lpr);
+  mn = group_max(mn, lpr);
+  float ep[8], en[8], sp = 0.f, sn = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    ep[e] = __expf(uv[e] - mp);
+    en[e] = __expf(-uv[e] - mn);
+    sp += ep[e];
+    sn += en[e];
+  }
+  sp = 1.f / group_sum(sp, lpr);
+  sn = 1.f / group_sum(sn, lpr);
   float ap = 0.f, an = 0.f;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    ep[j] /= sp;
-    en[j] /= sn;
-    ap += ep[j] * dp[j];
-    an += en[j] * dn[j];
+  for (int e = 0; e < 8; ++e) {
+    ep[e] *= sp;
+    en[e] *= sn;
+    ap += ep[e] * dp[e];
+    an += en[e] * dn[e];
   }
-  ap = wave_sum(ap);
-  an = wave_sum(an);
-  float du[2], dnx = 0.f;
-  const float inx = 1.f / nx;
+  ap = group_sum(ap, lpr);
+  an = group_sum(an, lpr);
+  const float inx = nx > 0.f ? 1.f / nx : 0.f;
+  float du[8], dnx = 0.f;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    du[j] = ep[j] * (dp[j] - ap) - en[j] * (dn[j] - an);
-    if (lane + 64 * j < F) dnx += uv[j] * inx * du[j];
+  for (int e = 0; e < 8; ++e) {
+    du[e] = ep[e] * (dp[e] - ap) - en[e] * (dn[e] - an);
+    dnx += uv[e] * inx * du[e];
   }
-  dnx = wave_sum(dnx);
-  const float ratio = nx / nf;
+  dnx = group_sum(dnx, lpr);
+  if (!live) return;
+  const float ratio = dead ? 0.f : nx / nf;
+  float dfv[8];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int i = lane + 64 * j;
-    if (i < F) df[i] = from_f32<T>(ratio * (du[j] - uv[j] * inx * dnx));
-  }
-  const T* x = static_cast<const T*>(a.x) + b * a.x_sb + (int64_t)t * a.x_st + hx * a.x_sh;
-  const int64_t xrow = a.x_kv ? ((int64_t)b * a.Hkv + hx) * a.N + t : row;
-  float* dx = a.dx32 + xrow * a.d;
-  for (int i = lane; i < a.d; i += 64) {
-    const float add = dnx * inx * to_f32<T>(x[i]);
-    if (a.x_kv) atomicAdd(dx + i, add);
-    else dx[i] += add;
-  }
+  for (int e = 0; e < 8; ++e) dfv[e] = dead ? 0.f : ratio * (du[e] - uv[e] * inx * dnx);
+  store8_t<T>(static_cast<T*>(a.df) + row * F + e0, dfv);
+  // the |x| path of dx is a multiple of x itself: the finishing kernel adds coefficient * x (for keys, the sum of the
+  // coefficients of the query heads that share the kv head)
+  if (e0 == 0) a.cx[row] = dead ? 0.f : dnx * inx;
 }
 
 // out[f] (per (unit, chunk), or added atomically per head) = sum over the chunk's tokens of X[t][f] * w[t]
@@ -394,35 +434,56 @@ __global__ __launch_bounds__(256) void bwd_revcumsum_kernel(float* X, int nc, in
 // dg = E_t dy_t * (phi_q S)_t  (times the logistic function's slope when the gate is activated here)
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_dg_kernel(BwdRowArgs a) {
-  const int64_t n = (int64_t)a.U * a.N * a.d;
-  for (int64_t i = blockIdx.x * 256ll + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const int64_t row = i / a.d;
-    const int x = (int)(i % a.d);
-    const int unit = (int)(row / a.N), t = (int)(row % a.N);
-    const int b = unit / a.Hq, h = unit % a.Hq;
-    const float dyx = to_f32<T>(static_cast<const T*>(a.dout)[b * a.o_sb + (int64_t)t * a.o_st + h * a.o_sh + x]);
-    float r = a.e_row[row] * dyx * a.nraw[i];
-    const int64_t go = b * a.g_sb + (int64_t)t * a.g_st + h * a.g_sh + x;
-    if (a.gate_act) {
-      const float s = 1.f / (1.f + __expf(-to_f32<T>(static_cast<const T*>(a.g)[go])));
-      r *= s * (1.f - s);
+  int64_t row;
+  int e0, lpr;
+  if (!row_of_lane((int64_t)a.U * a.N, a.d, row, e0, lpr)) return;
+  const int unit = (int)(row / a.N), t = (int)(row % a.N);
+  const int b = unit / a.Hq, h = unit % a.Hq;
+  float dy[8], nr[8], r[8];
+  load8_t<T>(dy, static_cast<const T*>(a.dout) + b * a.o_sb + (int64_t)t * a.o_st + h * a.o_sh + e0);
+  load8_f32(nr, a.nraw + row * a.d + e0);
+  const float E = a.e_row[row];
+  const int64_t go = b * a.g_sb + (int64_t)t * a.g_st + h * a.g_sh + e0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = E * dy[e] * nr[e];
+  if (a.gate_act) {
+    float gv[8];
+    load8_t<T>(gv, static_cast<const T*>(a.g) + go);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float sg = 1.f / (1.f + __expf(-gv[e]));
+      r[e] *= sg * (1.f - sg);
     }
-    static_cast<T*>(a.dg)[go] = from_f32<T>(r);
   }
+  store8_t<T>(static_cast<T*>(a.dg) + go, r);
 }
 
-// fp32 gradient rows -> the caller's strided tensors in the storage type
+// fp32 gradient rows (+ coefficient * x for the |x| path of the NP-Map, summed over the query heads that read the
+// row's head) -> the caller's strided tensors in the storage type
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_finish_kernel(BwdFinishArgs a) {
-  const int64_t n = (int64_t)a.B * a.H * a.N * a.d;
-  for (int64_t i = blockIdx.x * 256ll + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const int x = (int)(i % a.d);
-    const int64_t row = i / a.d;
-    const int t = (int)(row % a.N);
-    const int bh = (int)(row / a.N);
-    const int b = bh / a.H, h = bh % a.H;
-    static_cast<T*>(a.dst)[b * a.s_b + (int64_t)t * a.s_t + h * a.s_h + x] = from_f32<T>(a.src[i]);
+  int64_t row;
+  int e0, lpr;
+  if (!row_of_lane((int64_t)a.B * a.H * a.N, a.d, row, e0, lpr)) return;
+  const int t = (int)(row % a.N);
+  const int bh = (int)(row / a.N);
+  const int b = bh / a.H, h = bh % a.H;
+  float x[8];
+  load8_f32(x, a.src + row * a.d + e0);
+  if (a.cx != nullptr) {
+    float coef = 0.f;
+    if (a.per_kv) {
+      for (int hq = 0; hq < a.Hq; ++hq)
+        if (a.map.kv[hq] == h) coef += a.cx[((int64_t)b * a.Hq + hq) * a.N + t];
+    } else {
+      coef = a.cx[row];
+    }
+    float xv[8];
+    load8_t<T>(xv, static_cast<const T*>(a.x) + b * a.s_b + (int64_t)t * a.s_t + h * a.s_h + e0);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] += coef * xv[e];
   }
+  store8_t<T>(static_cast<T*>(a.dst) + b * a.s_b + (int64_t)t * a.s_t + h * a.s_h + e0, x);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -552,7 +613,11 @@ __global__ __launch_bounds__(256) void bwd_sa_dq_kernel(BwdSaArgs a) {
     }
 }
 
-template <typename T, int D>
+// LOCAL: one workgroup per (batch, kv head, tile of 64 tokens); it walks the query heads that read this kv head one
+// after the other, so the sums over the group stay in its accumulators and every row of the fp32 gradients is written
+// once, with plain stores (no zero fill is needed before, and the atomic adds of every other step come after).
+// !LOCAL: one workgroup per (batch, query head, tile of 64 retained entries), added atomically at the entries' tokens.
+template <typename T, int D, bool LOCAL>
 __global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
   typedef Mma<T> M;
   constexpr int LT = BwdTile<T>::LT, KS = D / M::KK, DX = D / 64;
@@ -561,15 +626,24 @@ __global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
   __shared__ float Ls[64], dls[64];
   __shared__ int toks[64];
 
-  const int unit = blockIdx.y, ti = blockIdx.x;   // retained tiles (the long ones) come first
-  const int b = unit / a.Hq, h = unit % a.Hq, kvh = a.map.kv[h];
+  const int ti = blockIdx.x;
+  int b, kvh, h_lo, h_hi;
+  if (LOCAL) {
+    b = blockIdx.y / a.Hkv;
+    kvh = blockIdx.y % a.Hkv;
+    h_lo = 0;
+    h_hi = a.Hq - 1;
+  } else {
+    b = blockIdx.y / a.Hq;
+    h_lo = h_hi = blockIdx.y % a.Hq;
+    kvh = a.map.kv[h_lo];
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, g = lane >> 5, wr = wave >> 1, wc = wave & 1;
   const int N = a.N, C = a.C;
-  const bool ret = ti < a.n_ret_tiles;
-  const int k0 = ret ? ti * 64 : (ti - a.n_ret_tiles) * 64;
+  const int k0 = ti * 64;
   int row_lo, row_hi;   // rows that may see a key of this tile: [row_lo, row_hi)
-  if (ret) {
+  if (!LOCAL) {
     if (a.lam <= 0 || k0 >= retained_rows(a.nc >= 2 ? a.nc - 2 : 0, a.lam, a.rcap)) return;
     row_lo = (k0 / a.lam + 2) * C;
     row_hi = N;
@@ -578,19 +652,14 @@ __global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
     row_hi = min(N, (k0 / C + 2) * C);
   }
   if (row_lo >= row_hi) return;
-  const T* qb = static_cast<const T*>(a.q) + b * a.q_sb + h * a.q_sh;
-  const T* dob = static_cast<const T*>(a.dout) + b * a.o_sb + h * a.o_sh;
   const T* kb = static_cast<const T*>(a.k) + b * a.k_sb + kvh * a.k_sh;
   const T* vb = static_cast<const T*>(a.v) + b * a.v_sb + kvh * a.v_sh;
-  const T* qt = static_cast<const T*>(a.qt) + (int64_t)unit * D * a.Np;
-  const T* dot = static_cast<const T*>(a.dot) + (int64_t)unit * D * a.Np;
-  const int32_t* sel = a.sel + (int64_t)unit * a.sel_stride;
   if (tid < 64) {
     int tok;
-    if (ret) {
+    if (!LOCAL) {
       const int e = k0 + tid;
-      tok = e < a.sel_stride ? sel[e] : -1;
-      if (tok < 0 || tok >= N || tok / C != e / a.lam) tok = -1;
+      tok = e < a.sel_stride ? a.sel[((int64_t)b * a.Hq + h_lo) * a.sel_stride + e] : -1;
+      if (tok < 0 || tok >= N || tok / C != e / a.lam) tok = -1;   // lists are never trusted for addressing
     } else {
       tok = k0 + tid < N ? k0 + tid : -1;
     }
@@ -617,48 +686,56 @@ __global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
   const float sc2 = a.scale * kLog2e;
   const int e = k0 + kcol;
 
-  for (int r0 = row_lo / 64 * 64; r0 < row_hi; r0 += 64) {
-    __syncthreads();   // the previous trip's products have read PTs, dSTs, Ls, dls
-    if (tid < 64) {
-      const int t = r0 + tid;
-      Ls[tid] = t < N ? a.lse[(int64_t)unit * N + t] * kLog2e : 0.f;
-      dls[tid] = t < N ? a.delta[(int64_t)unit * N + t] : 0.f;
-    }
-    floatx16 s = zero16(), dp = zero16();
-    {
-      const int t = min(r0 + 32 * wr + l31, N - 1);
-      const T* qp = qb + (int64_t)t * a.q_st + g * M::KPL;
-      const T* dp_ = dob + (int64_t)t * a.o_st + g * M::KPL;
-#pragma unroll
-      for (int st = 0; st < KS; ++st) {
-        s = M::mma(M::load(qp + st * M::KK), kf[st], s);
-        dp = M::mma(M::load(dp_ + st * M::KK), vf[st], dp);
+  for (int h = h_lo; h <= h_hi; ++h) {
+    if (LOCAL && a.map.kv[h] != kvh) continue;   // uniform
+    const int unit = b * a.Hq + h;
+    const T* qb = static_cast<const T*>(a.q) + b * a.q_sb + h * a.q_sh;
+    const T* dob = static_cast<const T*>(a.dout) + b * a.o_sb + h * a.o_sh;
+    const T* qt = static_cast<const T*>(a.qt) + (int64_t)unit * D * a.Np;
+    const T* dot = static_cast<const T*>(a.dot) + (int64_t)unit * D * a.Np;
+    for (int r0 = row_lo / 64 * 64; r0 < row_hi; r0 += 64) {
+      __syncthreads();   // the previous trip's products have read PTs, dSTs, Ls, dls
+      if (tid < 64) {
+        const int t = r0 + tid;
+        Ls[tid] = t < N ? a.lse[(int64_t)unit * N + t] * kLog2e : 0.f;
+        dls[tid] = t < N ? a.delta[(int64_t)unit * N + t] : 0.f;
       }
-    }
-    __syncthreads();   // Ls, dls visible
+      floatx16 s = zero16(), dp = zero16();
+      {
+        const int t = min(r0 + 32 * wr + l31, N - 1);
+        const T* qp = qb + (int64_t)t * a.q_st + g * M::KPL;
+        const T* dp_ = dob + (int64_t)t * a.o_st + g * M::KPL;
 #pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      const int rbase = 32 * wr + c_row(4 * i4, g);   // four consecutive rows
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int i = 4 * i4 + j;
-        const int r = rbase + j;
-        const int t = r0 + r;
-        const int c = t / C;
-        bool vis = tok >= 0 && t < N;
-        if (ret) vis = vis && e < retained_rows(c >= 1 ? c - 1 : 0, a.lam, a.rcap);
-        else vis = vis && tok <= t && tok >= (c >= 1 ? c - 1 : 0) * C;
-        const float p = vis ? fast_exp2(fmaf(s[i], sc2, -Ls[r])) : 0.f;
-        PTs[kcol * LT + r] = from_f32<T>(p);
-        dSTs[kcol * LT + r] = from_f32<T>(p * (dp[i] - dls[r]) * a.scale);
+        for (int st = 0; st < KS; ++st) {
+          s = M::mma(M::load(qp + st * M::KK), kf[st], s);
+          dp = M::mma(M::load(dp_ + st * M::KK), vf[st], dp);
+        }
       }
-    }
-    __syncthreads();
+      __syncthreads();   // Ls, dls visible
 #pragma unroll
-    for (int j = 0; j < DX; ++j) {
-      const int64_t xrow = (int64_t)(32 * (wc * DX + j) + l31) * a.Np + r0;
-      acc64_lds_global<T>(dv[j], PTs, 32 * wr, dot + xrow, l31, g);    // dV[key][x] += P^T dO
-      acc64_lds_global<T>(dk[j], dSTs, 32 * wr, qt + xrow, l31, g);    // dK[key][x] += dS^T Q
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int rbase = 32 * wr + c_row(4 * i4, g);   // four consecutive rows
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int i = 4 * i4 + j;
+          const int r = rbase + j;
+          const int t = r0 + r;
+          const int c = t / C;
+          bool vis = tok >= 0 && t < N;
+          if (!LOCAL) vis = vis && e < retained_rows(c >= 1 ? c - 1 : 0, a.lam, a.rcap);
+          else vis = vis && tok <= t && tok >= (c >= 1 ? c - 1 : 0) * C;
+          const float p = vis ? fast_exp2(fmaf(s[i], sc2, -Ls[r])) : 0.f;
+          PTs[kcol * LT + r] = from_f32<T>(p);
+          dSTs[kcol * LT + r] = from_f32<T>(p * (dp[i] - dls[r]) * a.scale);
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < DX; ++j) {
+        const int64_t xrow = (int64_t)(32 * (wc * DX + j) + l31) * a.Np + r0;
+        acc64_lds_global<T>(dv[j], PTs, 32 * wr, dot + xrow, l31, g);    // dV[key][x] += P^T dO
+        acc64_lds_global<T>(dk[j], dSTs, 32 * wr, qt + xrow, l31, g);    // dK[key][x] += dS^T Q
+      }
     }
   }
   float* dkb = a.dk32 + ((int64_t)b * a.Hkv + kvh) * N * D;
@@ -670,18 +747,27 @@ __global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
       const int tk = toks[32 * wr + c_row(i, g)];
       if (tk >= 0) {
         const int x = 32 * (wc * DX + j) + l31;
-        atomicAdd(dkb + (int64_t)tk * D + x, dk[j][i]);
-        atomicAdd(dvb + (int64_t)tk * D + x, dv[j][i]);
+        if (LOCAL) {
+          dkb[(int64_t)tk * D + x] = dk[j][i];
+          dvb[(int64_t)tk * D + x] = dv[j][i];
+        } else {
+          atomicAdd(dkb + (int64_t)tk * D + x, dk[j][i]);
+          atomicAdd(dvb + (int64_t)tk * D + x, dv[j][i]);
+        }
       }
     }
 }
 
 template <typename T, int D>
-hipError_t launch_sa_t(const BwdSaArgs& a, int U, hipStream_t s) {
-  hipLaunchKernelGGL((bwd_sa_dq_kernel<T, D>), dim3(a.n_row_tiles, U), dim3(256), 0, s, a);
+hipError_t launch_sa_t(const BwdSaArgs& a, int B, hipStream_t s) {
+  hipLaunchKernelGGL((bwd_sa_dq_kernel<T, D>), dim3(a.n_row_tiles, B * a.Hq), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((bwd_sa_dkv_kernel<T, D>), dim3(a.n_ret_tiles + a.n_row_tiles, U), dim3(256), 0, s, a);
+  // the local tiles first: they store, everything after them adds
+  hipLaunchKernelGGL((bwd_sa_dkv_kernel<T, D, true>), dim3(a.n_row_tiles, B * a.Hkv), dim3(256), 0, s, a);
+  e = hipGetLastError();
+  if (e != hipSuccess || a.n_ret_tiles == 0) return e;
+  hipLaunchKernelGGL((bwd_sa_dkv_kernel<T, D, false>), dim3(a.n_ret_tiles, B * a.Hq), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
@@ -708,22 +794,24 @@ hipError_t launch_fill_f32(float* p, int64_t n, float x, hipStream_t s) {
 }
 
 hipError_t launch_bwd_row_prep(const BwdRowArgs& a, int dtype, hipStream_t s) {
-  const int blocks = (int)(((int64_t)a.U * a.N + 3) / 4);
+  const int rpb = 256 / (a.d / 8);   // rows per workgroup
+  const int blocks = (int)(((int64_t)a.U * a.N + rpb - 1) / rpb);
   if (dtype == 1) hipLaunchKernelGGL((bwd_row_prep_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
   else hipLaunchKernelGGL((bwd_row_prep_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd_dg(const BwdRowArgs& a, int dtype, hipStream_t s) {
-  const int64_t n = (int64_t)a.U * a.N * a.d;
-  const int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+  const int rpb = 256 / (a.d / 8);
+  const int blocks = (int)(((int64_t)a.U * a.N + rpb - 1) / rpb);
   if (dtype == 1) hipLaunchKernelGGL((bwd_dg_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
   else hipLaunchKernelGGL((bwd_dg_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd_np(const BwdNpArgs& a, int dtype, bool backward, hipStream_t s) {
-  const int blocks = (int)(((int64_t)a.U * a.N + 3) / 4);
+  const int rpb = 256 / (a.F / 8);
+  const int blocks = (int)(((int64_t)a.U * a.N + rpb - 1) / rpb);
   if (dtype == 1) {
     if (backward) hipLaunchKernelGGL((bwd_np_bwd_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
     else hipLaunchKernelGGL((bwd_np_fwd_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
@@ -747,16 +835,16 @@ hipError_t launch_bwd_revcumsum(float* X, int U, int nc, int64_t L, hipStream_t 
 }
 
 hipError_t launch_bwd_finish(const BwdFinishArgs& a, int dtype, hipStream_t s) {
-  const int64_t n = (int64_t)a.B * a.H * a.N * a.d;
-  const int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+  const int rpb = 256 / (a.d / 8);
+  const int blocks = (int)(((int64_t)a.B * a.H * a.N + rpb - 1) / rpb);
   if (dtype == 1) hipLaunchKernelGGL((bwd_finish_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
   else hipLaunchKernelGGL((bwd_finish_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
-hipError_t launch_bwd_sa(const BwdSaArgs& a, int dtype, int d, int U, hipStream_t s) {
-  if (dtype == 1) return d == 128 ? launch_sa_t<bf16, 128>(a, U, s) : launch_sa_t<bf16, 64>(a, U, s);
-  if (d == 64) return launch_sa_t<float, 64>(a, U, s);
+hipError_t launch_bwd_sa(const BwdSaArgs& a, int dtype, int d, int B, hipStream_t s) {
+  if (dtype == 1) return d == 128 ? launch_sa_t<bf16, 128>(a, B, s) : launch_sa_t<bf16, 64>(a, B, s);
+  if (d == 64) return launch_sa_t<float, 64>(a, B, s);
   return hipErrorInvalidValue;   // fp32 at d = 128 does not fit the tiles in LDS (refused by the host checks)
 }
 

@@ -340,7 +340,7 @@ struct BwdNpArgs {
   const float* z1;         // [U, nc, 2F]
   const float* z2;         // nullable [U, nseg, 2F], indexed by chunk / seg_chunks
   void* df;                // [U, N, F] storage type
-  float* dx32;             // [U, N, d], or [B, Hkv, N, d] with x_kv (atomic adds)
+  float* cx;               // [U, N]: coefficient of x in dx (the |x| path), 0 for tokens without a gradient
   HeadMap map;
   int U, N, Hq, Hkv, d, F, C, nc, ncf, nseg, seg_chunks;
 };
@@ -353,8 +353,12 @@ struct BwdColsumArgs {
 struct BwdFinishArgs {
   const float* src;        // [B, H, N, d]
   void* dst;               // strided, storage type
+  const void* x;           // the tensor the gradient belongs to (same strides as dst); read when cx is given
   int64_t s_b, s_t, s_h;
-  int B, H, N, d;
+  const float* cx;         // nullable [B, Hq, N]: dst += coefficient * x
+  int per_kv;              // 1: H counts kv heads, the coefficients of the query heads of a kv head are added up
+  HeadMap map;
+  int B, H, Hq, N, d;
 };
 struct BwdSaArgs {
   const void* q;
@@ -371,7 +375,7 @@ struct BwdSaArgs {
   const float* lse;        // [U, N]
   const float* delta;      // [U, N]
   float* dq32;             // [U, N, d]
-  float* dk32;             // [B, Hkv, N, d], zeroed by the caller
+  float* dk32;             // [B, Hkv, N, d]: stored by the local key tiles, added to by the retained ones
   float* dv32;
   HeadMap map;
   int N, Np, cap, C, lam, rcap, Hq, Hkv, nc, sel_stride, n_row_tiles, n_ret_tiles;
@@ -385,6 +389,6 @@ hipError_t launch_bwd_np(const BwdNpArgs& a, int dtype, bool backward, hipStream
 hipError_t launch_bwd_colsum(const BwdColsumArgs& a, int dtype, int U, hipStream_t stream);
 hipError_t launch_bwd_revcumsum(float* X, int U, int nc, int64_t L, hipStream_t stream);
 hipError_t launch_bwd_finish(const BwdFinishArgs& a, int dtype, hipStream_t stream);
-hipError_t launch_bwd_sa(const BwdSaArgs& a, int dtype, int d, int U, hipStream_t stream);
+hipError_t launch_bwd_sa(const BwdSaArgs& a, int dtype, int d, int B, hipStream_t stream);
 
 }  // namespace still
