@@ -377,7 +377,11 @@ typedef struct still_bwd_ws_layout {
   size_t cxq, cxk; /* float [B, Hq, N]        coefficient of x in its own gradient (the norm |x| of Sec. 3.2)   */
   size_t qt, dot;  /* dtype [B, Hq, d, Npad]  q and dout transposed, zero padded                              */
   size_t kt;       /* dtype [B, Hkv, d, Npad] k transposed                                                    */
+  size_t kret;     /* dtype [B, Hq, cap, d]   retained keys in routing order                                  */
+  size_t krett;    /* dtype [B, Hq, d, cap]   the same, transposed                                            */
   size_t total;
+  int32_t n_pad_t; /* Npad of the three transposed copies above (64 more than the forward workspace's)         */
+  int32_t cap_t;   /* cap of the two retained-key copies (likewise)                                           */
 } still_bwd_ws_layout_t;
 STILL_API size_t still_bwd_workspace_bytes(const still_params_t* p);
 STILL_API still_status_t still_bwd_workspace_layout(const still_params_t* p, still_bwd_ws_layout_t* layout);

@@ -51,7 +51,8 @@ class StillStateLayout(ct.Structure):
 class StillBwdWsLayout(ct.Structure):
     _fields_ = [(n, ct.c_size_t) for n in
                 ("fwd", "e_row", "delta", "ed", "a", "phi_q", "phi_k", "uq", "uk", "stq", "stk", "nraw", "gq",
-                 "dphi_k", "ds", "dz", "dfq", "dfk", "dq32", "dk32", "dv32", "cxq", "cxk", "qt", "dot", "kt", "total")]
+                 "dphi_k", "ds", "dz", "dfq", "dfk", "dq32", "dk32", "dv32", "cxq", "cxk", "qt", "dot", "kt", "kret", "krett", "total")] + \
+               [(n, ct.c_int32) for n in ("n_pad_t", "cap_t")]
 
 
 class StillError(RuntimeError):

@@ -850,9 +850,16 @@ void compute_bwd_layout(const still_params_t* p, still_bwd_ws_layout_t* L) {
   L->dv32 = take(kvrows * d * 4);
   L->cxq = take(rows * 4);
   L->cxk = take(rows * 4);
-  L->qt = take(U * d * (size_t)F.n_pad * es);
-  L->dot = take(U * d * (size_t)F.n_pad * es);
-  L->kt = take((size_t)p->B * p->Hkv * d * (size_t)F.n_pad * es);
+  // transposed copies with a row stride that is no power of two: their readers fetch 16 bytes from each of 32 rows
+  // at once, and rows a power of two apart would all fall into one memory channel
+  const size_t npt = (size_t)F.n_pad + 64, capt = (size_t)F.cap + 64;
+  L->qt = take(U * d * npt * es);
+  L->dot = take(U * d * npt * es);
+  L->kt = take((size_t)p->B * p->Hkv * d * npt * es);
+  L->kret = take(F.cap ? U * capt * d * es : 0);
+  L->krett = take(F.cap ? U * capt * d * es : 0);
+  L->n_pad_t = (int32_t)npt;
+  L->cap_t = (int32_t)(F.cap ? capt : 0);
   L->total = off;
 }
 
@@ -952,9 +959,9 @@ still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, c
   // ---- softmax branch: dq (owned rows), dk / dv (atomic adds per key tile).  Its products over rows and keys read
   // transposed copies: q^T, dout^T, k^T of the sequence, and the retained keys both ways (the prefill's gather
   // kernel with k in the place of v too).
-  still::TransposeVArgs tq{q, p->q_sb, p->q_st, p->q_sh, bws + BL.qt, nullptr, N, L.n_pad, Hq, d, C, nullptr};
-  still::TransposeVArgs td{dout, p->o_sb, p->o_st, p->o_sh, bws + BL.dot, nullptr, N, L.n_pad, Hq, d, C, nullptr};
-  still::TransposeVArgs tk{k, p->k_sb, p->k_st, p->k_sh, bws + BL.kt, nullptr, N, L.n_pad, Hkv, d, C, nullptr};
+  still::TransposeVArgs tq{q, p->q_sb, p->q_st, p->q_sh, bws + BL.qt, nullptr, N, BL.n_pad_t, Hq, d, C, nullptr};
+  still::TransposeVArgs td{dout, p->o_sb, p->o_st, p->o_sh, bws + BL.dot, nullptr, N, BL.n_pad_t, Hq, d, C, nullptr};
+  still::TransposeVArgs tk{k, p->k_sb, p->k_st, p->k_sh, bws + BL.kt, nullptr, N, BL.n_pad_t, Hkv, d, C, nullptr};
   if ((e = still::launch_transpose_v(tq, dt, B, stream)) != hipSuccess ||
       (e = still::launch_transpose_v(td, dt, B, stream)) != hipSuccess ||
       (e = still::launch_transpose_v(tk, dt, B, stream)) != hipSuccess)
@@ -968,12 +975,12 @@ still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, c
   ga.nsel = have_sel ? still::retained_rows(ncf, p->lambda, budget) : 0;
   ga.sel_stride = ncf * p->lambda;
   ga.C = C; ga.lam = p->lambda; ga.rcap = budget; ga.seq_len = nullptr;
-  ga.cap = L.cap; ga.Hq = Hq; ga.d = d; ga.N = N;
-  ga.kret = ws + L.kret; ga.vrett = ws + L.vrett;
+  ga.cap = BL.cap_t; ga.Hq = Hq; ga.d = d; ga.N = N;
+  ga.kret = bws + BL.kret; ga.vrett = bws + BL.krett;
   if ((e = still::launch_gather(ga, dt, B, stream)) != hipSuccess) return hip_fail("bwd gather", e);
   still::BwdSaArgs sa{};
-  sa.qt = bws + BL.qt; sa.dot = bws + BL.dot; sa.kt = bws + BL.kt; sa.kret = ws + L.kret; sa.krett = ws + L.vrett;
-  sa.Np = L.n_pad; sa.cap = L.cap;
+  sa.qt = bws + BL.qt; sa.dot = bws + BL.dot; sa.kt = bws + BL.kt; sa.kret = bws + BL.kret; sa.krett = bws + BL.krett;
+  sa.Np = BL.n_pad_t; sa.cap = BL.cap_t;
   sa.q = q; sa.k = k; sa.v = v; sa.dout = dout;
   sa.q_sb = p->q_sb; sa.q_st = p->q_st; sa.q_sh = p->q_sh;
   sa.k_sb = p->k_sb; sa.k_st = p->k_st; sa.k_sh = p->k_sh;

@@ -129,3 +129,34 @@ def test_backward_bf16(kw):
     w = small("bwd16-" + "-".join(f"{k}{v}" for k, v in kw.items()), dtype="bf16", **kw)
     inp = with_bias(w, synth.make_inputs(w, seed=61, with_gate=True), 62)
     check_backward(w, inp, 63)
+
+
+def test_backward_at_the_training_shape_sampled_units():
+    """Config c6 (the shape bench.py --backward times: 16 sequences of 1024 tokens, 32 query heads over 8 kv heads,
+    d = 128, bf16), in the launch configuration the benchmark uses.  The oracle covers what it can reach in seconds:
+    dq and dg of the four query heads of kv head 2 in sequence 5, dk and dv of that kv head (the sum over exactly
+    those four heads), and dWq, dWk, of query head 9 (sums over all 16 sequences)."""
+    w = synth.workload("c6")
+    inp = synth.make_inputs(w, with_gate=True)
+    dy = make_dy(w, inp, 71)
+    hip = U.run_hip_backward(w, inp, dy)
+    kv = synth.kv_head_map(w)
+    b, kh = 5, 2
+    heads = [h for h in range(w.Hq) if kv[h] == kh]
+    units = [(b, h) for h in heads] + [(bb, 9) for bb in range(w.B)]
+    ref = OB.still_backward_units(inp, dy.astype(np.float64), kv, units, w.C, w.W, w.lam, w.scale, w.eps, hip["sel"])
+    bar = BAR[w.dtype]
+
+    def check(name, x, y):
+        scale = float(np.max(np.abs(y)))
+        err = float(np.max(np.abs(x.astype(np.float64) - y)))
+        print(f"[c6] {name}: max |ref| {scale:.3e}  max-abs err {err:.3e}  ratio {err / scale:.3e}")
+        assert np.all(np.isfinite(x)) and err <= bar * scale, (name, err, scale)
+
+    for h in heads:
+        check(f"dq head {h}", hip["dq"][b, :, h], ref[(b, h)]["dq"])
+        check(f"dg head {h}", hip["dg"][b, :, h], ref[(b, h)]["dg"])
+    check("dk", hip["dk"][b, :, kh], sum(ref[(b, h)]["dk"] for h in heads))
+    check("dv", hip["dv"][b, :, kh], sum(ref[(b, h)]["dv"] for h in heads))
+    check("dWq head 9", hip["dWq"][9], sum(ref[(bb, 9)]["dWq"] for bb in range(w.B)))
+    check("dWk head 9", hip["dWk"][9], sum(ref[(bb, 9)]["dWk"] for bb in range(w.B)))
