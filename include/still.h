@@ -369,7 +369,7 @@ typedef struct still_bwd_ws_layout {
   size_t nraw;     /* float [B, Hq, N, d]     phi_q S (the ungated linear numerator)                          */
   size_t gq;       /* float [B, Hq, N, 2*d_f] S A_t                                                           */
   size_t dphi_k;   /* float [B, Hq, N, 2*d_f] dS v_j                                                          */
-  size_t ds;       /* float [B, Hq, ceil(N/C), 2*d_f, d]  gradient of the state the rows of chunk c+2 and later read */
+  size_t ds;       /* dtype [B, Hq, ceil(N/C), 2*d_f, d]  gradient of the state the rows of chunk c+2 and later read */
   size_t dz;       /* float [B, Hq, ceil(N/C), 2*d_f]     likewise for z                                       */
   size_t dfq, dfk; /* dtype [B, Hq, N, d_f]   gradient of f(x)                                                */
   size_t dq32;     /* float [B, Hq, N, d]                                                                     */

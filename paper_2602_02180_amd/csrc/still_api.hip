@@ -841,7 +841,7 @@ void compute_bwd_layout(const still_params_t* p, still_bwd_ws_layout_t* L) {
   L->nraw = take(rows * d * 4);
   L->gq = take(rows * DP * 4);
   L->dphi_k = take(rows * DP * 4);
-  L->ds = take(U * nc * DP * d * 4);
+  L->ds = take(U * nc * DP * d * es);
   L->dz = take(U * nc * DP * 4);
   L->dfq = take(rows * df * es);
   L->dfk = take(rows * df * es);
@@ -1047,21 +1047,24 @@ still_status_t bwd_impl(const still_params_t* p, const void* q, const void* k, c
     return hip_fail("bwd query-side products", e);
   if (g != nullptr && (e = still::launch_bwd_dg(ra, dt, stream)) != hipSuccess) return hip_fail("bwd_dg", e);
 
-  // ---- gradient of the states: per-chunk contributions, then the sum over the chunks two and more ahead
+  // ---- gradient of the states: the per-chunk contributions phi_q^T A summed over the chunks two and more ahead
   const still::GemmOperand phiq_ft = operand(bws + BL.phi_q, Hq * NDP, NDP, (int64_t)C * DP, 1, DP);   // (m = f, k = token)
   const still::GemmOperand a_xt = operand(bws + BL.a, Hq * ND, ND, (int64_t)C * d, 1, d);              // (n = x, k = token)
   const int64_t simg = (int64_t)DP * d;
-  if ((e = product(phiq_ft, a_xt, f32p(BL.ds), Hq * nc * simg, nc * simg, simg, d, 0, DP, d, C, 0, N, 0, nc)) != hipSuccess)
-    return hip_fail("bwd state contributions", e);
+  gm.A = phiq_ft; gm.B = a_xt; gm.B2 = still::GemmOperand{};
+  gm.C = f32p(BL.ds);   // written in the storage type by the scan
+  gm.c_b = Hq * nc * simg; gm.c_h = nc * simg; gm.c_c = simg; gm.c_r = d; gm.c_kv = 0;
+  gm.M = DP; gm.Nn = d; gm.K = C; gm.m_total = 0; gm.k_total = N; gm.mode = 0;
+  if ((e = still::launch_bgemm_revscan(gm, dt, U, nc, stream)) != hipSuccess)
+    return hip_fail("bwd state gradient", e);
   still::BwdColsumArgs cz{bws + BL.phi_q, ra.ed, f32p(BL.dz), N, C, nc, DP, Hq, 0};
   if ((e = still::launch_bwd_colsum(cz, dt, U, stream)) != hipSuccess) return hip_fail("bwd_colsum", e);
-  if ((e = still::launch_bwd_revcumsum(f32p(BL.ds), U, nc, simg, stream)) != hipSuccess ||
-      (e = still::launch_bwd_revcumsum(f32p(BL.dz), U, nc, DP, stream)) != hipSuccess)
+  if ((e = still::launch_bwd_revcumsum(f32p(BL.dz), U, nc, DP, stream)) != hipSuccess)
     return hip_fail("bwd_revcumsum", e);
 
   // ---- key side: dphi_k = v dS^T (- dz, in the NP-Map kernel), dv += phi_k dS
-  const still::GemmOperand ds_fx = operand(f32p(BL.ds), Hq * nc * simg, nc * simg, simg, d, 1, 0, 1);   // (n = f, k = x)
-  const still::GemmOperand ds_xf = operand(f32p(BL.ds), Hq * nc * simg, nc * simg, simg, 1, d, 0, 1);   // (n = x, k = f)
+  const still::GemmOperand ds_fx = operand(bws + BL.ds, Hq * nc * simg, nc * simg, simg, d, 1);   // (n = f, k = x)
+  const still::GemmOperand ds_xf = operand(bws + BL.ds, Hq * nc * simg, nc * simg, simg, 1, d);   // (n = x, k = f)
   const still::GemmOperand phik_rows = operand(bws + BL.phi_k, Hq * NDP, NDP, (int64_t)C * DP, DP, 1);
   if ((e = product(v_rows, ds_fx, f32p(BL.dphi_k), Hq * NDP, NDP, (int64_t)C * DP, DP, 0, C, DP, d, N, 0, 0, nc)) != hipSuccess ||
       (e = product(phik_rows, ds_xf, f32p(BL.dv32), Hkv * ND, ND, (int64_t)C * d, d, 1, C, d, DP, N, 0, 2, nc)) != hipSuccess)

@@ -159,6 +159,62 @@ __global__ __launch_bounds__(256) void bgemm_kernel(GemmArgs a) {
   }
 }
 
+// The state gradient as a running sum: dS(c) = sum over c' >= c + 2 of A(c')^T-products.  One workgroup owns a 64 x BN
+// tile of the state for one (batch, head) and walks the chunks from the last one down, keeping the sum in its
+// accumulators: after adding the contribution of chunk c' the accumulators ARE dS(c' - 2), which is stored in the
+// storage type (it is only ever a matrix-core operand again).  The two last chunks' dS is zero.  Operands as in
+// bgemm_kernel (item index = chunk, contraction over the chunk's tokens, cut short in a ragged last chunk).
+template <typename T, int BN>
+__global__ __launch_bounds__(256) void bgemm_revscan_kernel(GemmArgs a, int n_c) {
+  typedef Mma<T> M;
+  constexpr int BK = 64, NT = BN / 64;
+  constexpr int LDK = BK + (sizeof(T) == 2 ? 8 : 4);
+  __shared__ __attribute__((aligned(16))) T As[64 * LDK];
+  __shared__ __attribute__((aligned(16))) T Bs[BN * LDK];
+  const int unit = blockIdx.z;
+  const int ntn = a.Nn / BN;
+  const int mt = blockIdx.x / ntn, nt = blockIdx.x % ntn;
+  const int b = unit / a.Hq, h = unit % a.Hq, kvh = a.map.kv[h];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, g = lane >> 5;
+  const int wr = wave >> 1, wc = wave & 1;
+  floatx16 acc[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) acc[j] = zero16();
+  T* cbase = reinterpret_cast<T*>(a.C) + b * a.c_b + (a.c_kv ? kvh : h) * a.c_h;
+  auto store = [&](int c) {
+    T* cp = cbase + (int64_t)c * a.c_c;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int n = nt * BN + 32 * (wc * NT + j) + l31;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) cp[(int64_t)(mt * 64 + 32 * wr + c_row(i, g)) * a.c_r + n] = from_f32<T>(acc[j][i]);
+    }
+  };
+  if (n_c >= 1) store(n_c - 1);
+  if (n_c >= 2) store(n_c - 2);
+  for (int c = n_c - 1; c >= 2; --c) {
+    int k_valid = a.K;
+    if (a.k_total > 0) k_valid = min(a.K, a.k_total - c * a.K);
+    const int64_t a_off = b * a.A.s_b + (a.A.kv ? kvh : h) * a.A.s_h + (int64_t)c * a.A.s_c;
+    const int64_t b_off = b * a.B.s_b + (a.B.kv ? kvh : h) * a.B.s_h + (int64_t)c * a.B.s_c;
+    for (int k0 = 0; k0 < k_valid; k0 += BK) {
+      load_operand<T, 64, LDK>(As, a.A, a_off, mt * 64, a.M, k0, k_valid, tid);
+      load_operand<T, BN, LDK>(Bs, a.B, b_off, nt * BN, a.Nn, k0, k_valid, tid);
+      __syncthreads();
+#pragma unroll
+      for (int s = 0; s < BK / M::KK; ++s) {
+        const typename M::frag af = M::load(As + (32 * wr + l31) * LDK + s * M::KK + g * M::KPL);
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          acc[j] = M::mma(af, M::load(Bs + (32 * (wc * NT + j) + l31) * LDK + s * M::KK + g * M::KPL), acc[j]);
+      }
+      __syncthreads();
+    }
+    store(c - 2);
+  }
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // Element-wise kernels
 // ---------------------------------------------------------------------------------------------------------
@@ -782,6 +838,19 @@ hipError_t launch_bgemm(const GemmArgs& a, int dtype, int U, int n_c, hipStream_
   } else {
     if (bn == 128) hipLaunchKernelGGL((bgemm_kernel<float, 128>), grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL((bgemm_kernel<float, 64>), grid, dim3(256), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_bgemm_revscan(const GemmArgs& a, int dtype, int U, int n_c, hipStream_t s) {
+  const int bn = a.Nn % 128 == 0 ? 128 : 64;
+  const dim3 grid((a.Nn / bn) * (a.M / 64), 1, U);
+  if (dtype == 1) {
+    if (bn == 128) hipLaunchKernelGGL((bgemm_revscan_kernel<bf16, 128>), grid, dim3(256), 0, s, a, n_c);
+    else hipLaunchKernelGGL((bgemm_revscan_kernel<bf16, 64>), grid, dim3(256), 0, s, a, n_c);
+  } else {
+    if (bn == 128) hipLaunchKernelGGL((bgemm_revscan_kernel<float, 128>), grid, dim3(256), 0, s, a, n_c);
+    else hipLaunchKernelGGL((bgemm_revscan_kernel<float, 64>), grid, dim3(256), 0, s, a, n_c);
   }
   return hipGetLastError();
 }

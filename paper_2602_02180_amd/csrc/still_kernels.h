@@ -382,6 +382,9 @@ struct BwdSaArgs {
   float scale;
 };
 hipError_t launch_bgemm(const GemmArgs& a, int dtype, int U, int n_c, hipStream_t stream);
+// the same product summed over the items c' >= c + 2 for every item c, written in the storage type (C is then a T*;
+// M a multiple of 64, m_total unused)
+hipError_t launch_bgemm_revscan(const GemmArgs& a, int dtype, int U, int n_c, hipStream_t stream);
 hipError_t launch_fill_f32(float* p, int64_t n, float x, hipStream_t stream);
 hipError_t launch_bwd_row_prep(const BwdRowArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_bwd_dg(const BwdRowArgs& a, int dtype, hipStream_t stream);

@@ -240,7 +240,6 @@ def run_hip_backward(w: synth.Workload, inp: Dict[str, np.ndarray], dy: np.ndarr
 
         res["nraw"] = f32_region(BL.nraw, (B, w.Hq, N, w.d))
         res["gq"] = f32_region(BL.gq, (B, w.Hq, N, DP))
-        res["ds"] = f32_region(BL.ds, (B, w.Hq, nc, DP, w.d))
         res["dz"] = f32_region(BL.dz, (B, w.Hq, nc, DP))
         res["dphi_k"] = f32_region(BL.dphi_k, (B, w.Hq, N, DP))
         res["uq"] = f32_region(BL.uq, (B, w.Hq, N, w.df))

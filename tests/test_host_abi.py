@@ -121,7 +121,7 @@ def test_backward_entry_point_validates_on_the_host():
     offs = [getattr(BL, n) for n in names]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert BL.e_row - BL.fwd >= S.still_fwd_workspace_bytes(p)
-    assert BL.dz - BL.ds >= 1 * 4 * 16 * 128 * 64 * 4 and BL.total - BL.dv32 >= 1 * 2 * 1024 * 64 * 4
+    assert BL.dz - BL.ds >= 1 * 4 * 16 * 128 * 64 * 2 and BL.total - BL.dv32 >= 1 * 2 * 1024 * 64 * 4
     p.q_st = p.k_st = p.v_st = p.o_st = 64
     null, fake = ctypes.c_void_p(None), ctypes.c_void_p(0x1000)
     rc = S.lib().still_hybrid_attn_bwd(ctypes.byref(p), fake, fake, fake, null, fake, null, fake, null, fake, fake,
