@@ -160,3 +160,50 @@ def test_backward_at_the_training_shape_sampled_units():
     check("dv", hip["dv"][b, :, kh], sum(ref[(b, h)]["dv"] for h in heads))
     check("dWq head 9", hip["dWq"][9], sum(ref[(bb, 9)]["dWq"] for bb in range(w.B)))
     check("dWk head 9", hip["dWk"][9], sum(ref[(bb, 9)]["dWk"] for bb in range(w.B)))
+
+
+def test_backward_with_group_shared_selection_bf16():
+    """The selection variant only changes WHICH tokens are kept (one list per kv head); the backward pass takes the
+    lists as they are."""
+    w = small("bwd-shared", dtype="bf16", d=64, N=768, Hq=4, Hkv=2, lam=8, shared_selection=True)
+    inp = synth.make_inputs(w, seed=81, with_gate=True)
+    hip, _ = check_backward(w, inp, 82)
+    assert np.array_equal(hip["sel"][:, 0], hip["sel"][:, 1]) and np.array_equal(hip["sel"][:, 2], hip["sel"][:, 3])
+
+
+def test_backward_twice_on_a_user_stream_gives_the_same_gradients():
+    """Nothing in the workspace has to start at zero and nothing survives a call: a second call into the same
+    (dirty) workspace on a non-default stream reproduces the first to rounding (dk, dv and the parameter gradients
+    are summed with atomic adds, so not bit for bit)."""
+    import torch
+
+    w = small("bwd-twice", N=700, Hq=4, Hkv=2, lam=8)
+    inp = synth.make_inputs(w, seed=91, with_gate=True)
+    dy = make_dy(w, inp, 92)
+    dev = "cuda"
+    q, k, v, g, Wq, Wk = (synth.to_torch(inp[n], w.dtype, dev) for n in ("q", "k", "v", "g", "Wq", "Wk"))
+    dout = synth.to_torch(dy, w.dtype, dev)
+    out = torch.empty_like(q)
+    p = S.make_params(B=w.B, N=w.N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, q=q, k=k, v=v, out=out, g=g)
+    sel = torch.zeros(w.B, w.Hq, w.N // w.C, w.lam, dtype=torch.int32, device=dev)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    bws = torch.empty(S.still_bwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    L = S.still_fwd_workspace_layout(p)
+    lse = ws[L.lse:L.lse + w.B * w.Hq * w.N * 4].view(torch.float32)
+    stream = torch.cuda.Stream()
+    results = []
+    with torch.cuda.stream(stream):
+        S.still_hybrid_attn_fwd(p, q, k, v, g, Wq, None, Wk, None, out, sel_idx=sel, workspace=ws, stream=stream)
+        for _ in range(2):
+            grads = [torch.full_like(t, float("nan")) for t in (q, k, v, g)]
+            dWq = torch.full((w.Hq, w.d, w.d), float("nan"), dtype=torch.float32, device=dev)
+            dWk = torch.full_like(dWq, float("nan"))
+            S.still_hybrid_attn_bwd(p, q, k, v, g, Wq, None, Wk, None, out, dout, lse, sel, grads[0], grads[1], grads[2],
+                                    grads[3], dWq, None, dWk, None, bws, stream=stream)
+            results.append([t.clone() for t in grads + [dWq, dWk]])
+    stream.synchronize()
+    for a_, b_ in zip(*results):
+        a_, b_ = a_.float(), b_.float()
+        assert torch.isfinite(a_).all() and torch.isfinite(b_).all()
+        assert float((a_ - b_).abs().max()) <= 1e-5 * float(a_.abs().max())
