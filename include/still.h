@@ -393,6 +393,19 @@ STILL_API still_status_t still_hybrid_attn_bwd(const still_params_t* p,
                                      float* dWq, float* dbq, float* dWk, float* dbk,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Rotary position embedding of q and k, in place: a pre-pass for callers whose q and k are not rotated yet (the
+ * paper converts Llama-family layers, which rotate q and k before attention; nothing in the method depends on it, and
+ * every other entry point takes q and k as they are).  Channel pair (i, i + d/2) of the token at position pos turns
+ * by the angle pos * base^(-2 i / d) (the half-split pairing of those checkpoints); pos = pos0[b] + t for token t of
+ * sequence b (pos0: device int32 [B], or NULL for zeros), so a decode step rotates its one new token with N = 1 and
+ * pos0 = the token's index.  q: device, dtype, [B, N, Hq, d]; k: [B, N, Hkv, d]; either may be NULL.  Read from `p`:
+ * B, N, Hq, Hkv, d (even), dtype, the q and k strides.  Angles, sines and cosines are computed in double (an fp32
+ * angle of thousands of radians is only good to 1e-4), the rotation in fp32.
+ */
+STILL_API still_status_t still_rope_apply(const still_params_t* p, void* q, void* k, const int32_t* pos0, float base,
+                                          void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -259,6 +259,22 @@ def np_map_u(x: np.ndarray, Wm: np.ndarray, b: Optional[np.ndarray] = None) -> n
 
 
 # ----------------------------------------------------------------------------
+# Rotary position embedding of q and k (the layer applies it before the operator; not part of the paper's method)
+# ----------------------------------------------------------------------------
+
+def rope_rotate(x: np.ndarray, positions: np.ndarray, base: float = 10000.0) -> np.ndarray:
+    """Rotate rows of x [N, d] (d even) by their positions: channel pair (i, i + d/2) of row t turns by the angle
+    positions[t] * base**(-2 i / d), the half-split pairing of the Llama family that the paper converts."""
+    x = np.asarray(x, F64)
+    N, d = x.shape
+    half = d // 2
+    theta = base ** (-2.0 * np.arange(half) / d)
+    ang = np.asarray(positions, F64)[:, None] * theta[None, :]
+    z = (x[:, :half] + 1j * x[:, half:]) * np.exp(1j * ang)
+    return np.concatenate([z.real, z.imag], axis=1)
+
+
+# ----------------------------------------------------------------------------
 # shared result container
 # ----------------------------------------------------------------------------
 

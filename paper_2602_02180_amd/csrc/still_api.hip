@@ -2,6 +2,7 @@
 // See include/still.h for the contract of every entry point.
 #include "../../include/still.h"
 
+#include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -1124,6 +1125,29 @@ still_status_t still_bwd_workspace_layout(const still_params_t* p, still_bwd_ws_
   still_status_t st = validate_bwd_params(p);
   if (st != STILL_OK) return st;
   compute_bwd_layout(p, layout);
+  return STILL_OK;
+}
+
+still_status_t still_rope_apply(const still_params_t* p, void* q, void* k, const int32_t* pos0, float base,
+                                void* stream_v) {
+  if (p == nullptr) return fail(STILL_ERR_INVALID_ARG, "params is NULL");
+  if (p->dtype != STILL_F32 && p->dtype != STILL_BF16) return fail(STILL_ERR_INVALID_ARG, "dtype %d unknown", p->dtype);
+  if (p->B < 1 || p->N < 1 || p->Hq < 1 || p->Hkv < 1) return fail(STILL_ERR_INVALID_ARG, "B, N, Hq, Hkv must be >= 1");
+  if (p->d < 2 || p->d % 2 != 0) return fail(STILL_ERR_INVALID_ARG, "d = %d must be even", p->d);
+  if (!(base > 1.f)) return fail(STILL_ERR_INVALID_ARG, "base must be > 1");
+  if (q == nullptr && k == nullptr) return fail(STILL_ERR_INVALID_ARG, "both q and k are NULL");
+  if (pos0 != nullptr && (reinterpret_cast<uintptr_t>(pos0) & 3) != 0)
+    return fail(STILL_ERR_INVALID_ARG, "pos0 is not 4-byte aligned");
+  const int64_t str[] = {p->q_sb, p->q_st, p->q_sh, p->k_sb, p->k_st, p->k_sh};
+  for (int64_t x : str)
+    if (x < 0) return fail(STILL_ERR_INVALID_ARG, "negative stride");
+  if ((q != nullptr && p->q_st < p->d) || (k != nullptr && p->k_st < p->d))
+    return fail(STILL_ERR_INVALID_ARG, "token stride smaller than d");
+  still::RopeArgs a{q, k, p->q_sb, p->q_st, p->q_sh, p->k_sb, p->k_st, p->k_sh, pos0, log2((double)base),
+                    p->B, p->N, p->Hq, p->Hkv, p->d};
+  hipError_t e = still::launch_rope(a, p->dtype, static_cast<hipStream_t>(stream_v));
+  if (e != hipSuccess) return fail(STILL_ERR_HIP, "rope_apply: %s", hipGetErrorString(e));
+  g_err[0] = 0;
   return STILL_OK;
 }
 

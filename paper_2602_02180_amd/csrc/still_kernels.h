@@ -381,6 +381,15 @@ struct BwdSaArgs {
   int N, Np, cap, C, lam, rcap, Hq, Hkv, nc, sel_stride, n_row_tiles, n_ret_tiles;
   float scale;
 };
+struct RopeArgs {
+  void* q;                 // nullable [B, N, Hq, d], rotated in place
+  void* k;                 // nullable [B, N, Hkv, d]
+  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
+  const int32_t* pos0;     // nullable, device [B]: position of each sequence's token 0
+  double log2_base;
+  int B, N, Hq, Hkv, d;
+};
+hipError_t launch_rope(const RopeArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_bgemm(const GemmArgs& a, int dtype, int U, int n_c, hipStream_t stream);
 // the same product summed over the items c' >= c + 2 for every item c, written in the storage type (C is then a T*;
 // M a multiple of 64, m_total unused)

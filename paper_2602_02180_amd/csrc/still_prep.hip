@@ -188,6 +188,46 @@ hipError_t launch_keep_mask(const KeepMaskArgs& a, int B, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// Rotary position embedding of q and k in place (the layer applies it before the operator; a pre-pass here, not
+// fused into the tile loads: every key tile is re-read once per row tile and per score window, so rotating on load
+// would repeat the rotation many times to save one element-wise pass).  One thread per (token, channel pair
+// (i, i + d/2)): the angle position * base^(-2 i / d) and its sine and cosine are computed once and applied to that
+// pair of every query head and every kv head of the token.
+template <typename E>
+__global__ __launch_bounds__(256) void rope_kernel(RopeArgs a) {
+  const int half = a.d / 2;
+  const int64_t idx = blockIdx.x * 256ll + threadIdx.x;
+  const int64_t tok_idx = idx / half;
+  const int i = (int)(idx % half);
+  if (tok_idx >= (int64_t)a.B * a.N) return;
+  const int b = (int)(tok_idx / a.N), t = (int)(tok_idx % a.N);
+  const double pos = (double)((a.pos0 ? a.pos0[b] : 0) + t);
+  // base^(-2 i / d) = exp2(-(2 i / d) log2(base)).  The angle reaches thousands of radians, where an fp32 product
+  // is only good to ~1e-4 rad: angle, sine and cosine are taken in double (one pair per token and channel pair, a
+  // small share of this memory-bound pass), the rotation itself in fp32.
+  const double theta = exp2(-(2.0 * (double)i / (double)a.d) * (double)a.log2_base);
+  double snd, csd;
+  sincos(pos * theta, &snd, &csd);
+  const float sn = (float)snd, cs = (float)csd;
+  auto turn = [&](E* row) {
+    const float x0 = to_f32<E>(row[i]), x1 = to_f32<E>(row[i + half]);
+    row[i] = from_f32<E>(x0 * cs - x1 * sn);
+    row[i + half] = from_f32<E>(x0 * sn + x1 * cs);
+  };
+  if (a.q != nullptr)
+    for (int h = 0; h < a.Hq; ++h) turn(static_cast<E*>(a.q) + b * a.q_sb + (int64_t)t * a.q_st + h * a.q_sh);
+  if (a.k != nullptr)
+    for (int h = 0; h < a.Hkv; ++h) turn(static_cast<E*>(a.k) + b * a.k_sb + (int64_t)t * a.k_st + h * a.k_sh);
+}
+
+hipError_t launch_rope(const RopeArgs& a, int dtype, hipStream_t stream) {
+  const int64_t n = (int64_t)a.B * a.N * (a.d / 2);
+  const dim3 grid((unsigned)((n + 255) / 256));
+  if (dtype == 1) hipLaunchKernelGGL(rope_kernel<bf16>, grid, dim3(256), 0, stream, a);
+  else hipLaunchKernelGGL(rope_kernel<float>, grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_transpose_v(const TransposeVArgs& a, int dtype, int B, hipStream_t stream) {
   dim3 grid(a.Np / 64, a.Hkv * (a.d / 64), B), block(256);
   if (dtype == 1)

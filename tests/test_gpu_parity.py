@@ -627,3 +627,37 @@ def test_128k_context_last_rows_and_selection():
     x = o[0, rows[0]:rows[1], unit[1]].astype(np.float64)
     y = ref["out"][rows[0]:rows[1]]
     U.assert_bf16_bar(x, y, "128k last rows")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rope_pre_pass_matches_the_oracle_and_composes_with_the_prefill(dtype):
+    """still_rope_apply rotates q and k in place (per-sequence start positions, GQA, strided tensors); the rotated
+    tensors then go through the prefill like any other input."""
+    import torch
+
+    w = small("rope", N=300, Hq=4, Hkv=2, B=2, dtype=dtype, d=128 if dtype == "bf16" else 64, lam=8)
+    inp = synth.make_inputs(w, seed=23)
+    dev = "cuda"
+    q, k = synth.to_torch(inp["q"], w.dtype, dev), synth.to_torch(inp["k"], w.dtype, dev)
+    pos0 = torch.tensor([0, 4000], dtype=torch.int32, device=dev)
+    p = S.make_params(B=w.B, N=w.N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, q=q, k=k, v=k, out=q)
+    S.still_rope_apply(p, q, k, pos0, base=10000.0)
+    torch.cuda.synchronize()
+    gq, gk = synth.from_torch(q).astype(np.float64), synth.from_torch(k).astype(np.float64)
+    from oracle import still_oracle as O
+    tol = 2e-5 if dtype == "f32" else 2.0 ** -8      # relative to the row's largest magnitude: one rounding on bf16
+    for b in range(w.B):
+        pos = np.arange(w.N) + int(pos0[b])
+        for name, got, H in (("q", gq, w.Hq), ("k", gk, w.Hkv)):
+            for h in range(H):
+                ref = O.rope_rotate(inp[name][b, :, h], pos)
+                err = np.max(np.abs(got[b, :, h] - ref)) / np.max(np.abs(ref))
+                assert err <= tol, (name, b, h, err)
+    # position 0 of sequence 0 is untouched, everything else moved
+    assert np.array_equal(gq[0, 0], inp["q"][0, 0].astype(np.float64))
+    assert np.max(np.abs(gq[1] - inp["q"][1])) > 0.1
+    # the rotated tensors are ordinary inputs of the prefill
+    inp2 = dict(inp)
+    inp2["q"], inp2["k"] = synth.from_torch(q), synth.from_torch(k)
+    run_case(w, inp2)

@@ -135,6 +135,18 @@ def test_backward_entry_point_validates_on_the_host():
     assert rc == S.STILL_ERR_INVALID_ARG and "dg" in S.still_last_error()
 
 
+def test_rope_entry_point_validates_on_the_host():
+    lib = S.lib()
+    null, fake = ctypes.c_void_p(None), ctypes.c_void_p(0x1000)
+    p = params()
+    p.q_st = p.k_st = 64
+    assert lib.still_rope_apply(ctypes.byref(p), null, null, null, ctypes.c_float(10000.0), null) == S.STILL_ERR_INVALID_ARG
+    assert lib.still_rope_apply(ctypes.byref(p), fake, fake, null, ctypes.c_float(1.0), null) == S.STILL_ERR_INVALID_ARG
+    assert "base" in S.still_last_error()
+    p.q_st = 32
+    assert lib.still_rope_apply(ctypes.byref(p), fake, null, null, ctypes.c_float(10000.0), null) == S.STILL_ERR_INVALID_ARG
+
+
 def test_fwd_rejects_null_and_misaligned_pointers_without_launching():
     p = params()
     lib = S.lib()

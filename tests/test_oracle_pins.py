@@ -679,3 +679,24 @@ def test_selection_overlap_counts_common_tokens():
         tb = set(np.argsort(-b[8 * c:8 * c + 8], kind="stable")[:4].tolist())
         assert got[c] == len(ta & tb)
     assert O.selection_overlap(a[:37], b[:37], C=8, lam=4).shape == (4,)        # the partial chunk is not ranked
+
+
+def test_rope_rotation_literals_norms_and_relative_positions():
+    """The rotary embedding helper: a pair turned by a quarter turn, position 0 is the identity, norms are kept, and
+    the product of a rotated query and a rotated key depends on their positions only through the difference."""
+    # d = 2: one pair, theta = 1: position pi/2 turns (1, 0) into (0, 1)
+    got = O.rope_rotate(np.array([[1.0, 0.0]]), np.array([np.pi / 2]), base=10000.0)
+    assert np.allclose(got, [[0.0, 1.0]], atol=1e-15)
+    # d = 4, base 100: pair (0, 2) turns by pos, pair (1, 3) by pos / 10
+    x = np.array([[1.0, 2.0, 0.0, 0.0]])
+    got = O.rope_rotate(x, np.array([3.0]), base=100.0)
+    assert np.allclose(got, [[np.cos(3.0), 2 * np.cos(0.3), np.sin(3.0), 2 * np.sin(0.3)]], atol=1e-15)
+    rng = np.random.default_rng(5)
+    q, k = rng.normal(size=(7, 8)), rng.normal(size=(7, 8))
+    assert np.array_equal(O.rope_rotate(q, np.zeros(7)), q)
+    pos = np.array([0, 1, 2, 5, 9, 100, 4000])
+    assert np.allclose(np.linalg.norm(O.rope_rotate(q, pos), axis=1), np.linalg.norm(q, axis=1), rtol=1e-13)
+    a = O.rope_rotate(q[:1], np.array([12.0])) @ O.rope_rotate(k[:1], np.array([5.0])).T
+    b = O.rope_rotate(q[:1], np.array([1007.0])) @ O.rope_rotate(k[:1], np.array([1000.0])).T
+    assert np.allclose(a, b, rtol=1e-10)
+    assert not np.allclose(a, q[:1] @ k[:1].T)
