@@ -16,26 +16,15 @@
 //        du = phi+ (dphi+ - <phi+, dphi+>) - phi- (dphi- - <phi-, dphi->)
 //        df = (|x| / |f|) (du - fh <fh, du>),  fh = f / |f|;   dx = df W^T + <fh, du> x / |x|;   dW = x^T df
 //
-// This first version keeps every step a separate, simple kernel: the sparse branch as two tile kernels (one that
-// owns query rows and produces dq, one that owns key tiles and produces dk, dv), the linear branch as a sequence of
-// batched products on one generic 64 x 64 MFMA tile kernel with element-wise kernels between them, intermediates in
-// the workspace.  All sums are fp32; operands of the matrix core are in the storage type.
+// This first version keeps every step a separate, simple kernel: the sparse branch as tile kernels (one that owns
+// query rows and produces dq, one that owns key tiles and produces dk, dv), the linear branch as a sequence of
+// batched products on one generic MFMA tile kernel with row-wise kernels between them, intermediates in the
+// workspace.  All sums are fp32; operands of the matrix core are in the storage type.
 #include "still_kernels.h"
 
 namespace still {
 
 namespace {
-
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
-  return x;
-}
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
-  return x;
-}
 
 // ---------------------------------------------------------------------------------------------------------
 // Generic batched product on the matrix core: C[m][n] (=, +=, atomic +=) sum_k A(m, k) B(n, k) [+ sum_k A(m, k)
@@ -385,8 +374,6 @@ __global__ __launch_bounds__(256) void bwd_np_bwd_kernel(BwdNpArgs a) {
   const bool live = row_of_lane((int64_t)a.U * a.N, a.F, row, e0, lpr);
   const int64_t rowc = live ? row : 0;
   const int unit = (int)(rowc / a.N), t = (int)(rowc % a.N);
-  const int b = unit / a.Hq, h = unit % a.Hq;
-  const int hx = a.x_kv ? a.map.kv[h] : h;
   const int F = a.F, c = t / a.C;
   const float nx = a.st[2 * rowc], nf = a.st[2 * rowc + 1];
   const bool dead = token_kept(a, unit, t) || !(nx > 0.f) || !(nf > 0.f);   // uniform over the row's lanes
