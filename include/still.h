@@ -394,6 +394,21 @@ STILL_API still_status_t still_hybrid_attn_bwd(const still_params_t* p,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Attention map of the operator, for inspection and for the first training stage of Sec. 4.1 (which compares it
+ * with the teacher's softmax map): map_out[b, hq, t, j] = weight of v_j in row t under the shared normaliser of the
+ * Sec. 3.3 output equation: exp(scale q_t.k_j - lse_t) for the keys the softmax branch sees (local span, retained
+ * tokens), phi_q(q_t).phi_k(k_j) exp(-lse_t) for the tokens that went to the linear state, 0 for j > t.  Every row
+ * sums to one; with a gate of ones out = map v (the per-channel gate scales the linear part of the numerator only
+ * and is not part of a scalar map).  map_out: device FLOAT [B, Hq, N, N] (quadratic in N: meant for training-length
+ * sequences); lse, sel_idx as for still_hybrid_attn_bwd; workspace: at least still_bwd_workspace_bytes(p) bytes.
+ * Same coverage and validation as the backward pass.
+ */
+STILL_API still_status_t still_attention_map(const still_params_t* p, const void* q, const void* k,
+                                   const void* Wq, const void* bq, const void* Wk, const void* bk,
+                                   const float* lse, const int32_t* sel_idx, float* map_out,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Rotary position embedding of q and k, in place: a pre-pass for callers whose q and k are not rotated yet (the
  * paper converts Llama-family layers, which rotate q and k before attention; nothing in the method depends on it, and
  * every other entry point takes q and k as they are).  Channel pair (i, i + d/2) of the token at position pos turns

@@ -15,7 +15,9 @@ Score only feeds that decision.  Every derivative below is the chain rule on tha
 branch's exponentials, on the linear branch's phi_q . phi_k weights, and on the NP-Map of Sec. 3.2.
 
 Pins (tests/test_oracle_backward.py): central finite differences of still_definition for every input, the
-textbook causal-softmax gradient when every token is kept, plain linear attention when none is.
+textbook causal-softmax gradient when every token is kept, the NP-Map's Jacobian and invariances.
+attention_map (the weights under the shared normaliser, what the first training stage compares with the teacher's
+map) is pinned by A v = y, unit row sums, scipy's softmax when every token is kept and one written-out entry.
 """
 from __future__ import annotations
 
@@ -146,3 +148,30 @@ def still_backward_units(inputs: Dict[str, np.ndarray], dy: np.ndarray, kv_map: 
             C, W, lam, scale, eps, dy[b, :, h], bq=bq, bk=bk, sel=sel[b, h], max_retained=max_retained,
             gate_activation=gate_activation)
     return out
+
+
+def attention_map(q, k, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None, sel=None, score=None,
+                  max_retained: Optional[int] = None) -> np.ndarray:
+    """The operator's attention map for ONE (batch, query-head) problem: A[t, j] = weight of v_j in row t under the
+    shared normaliser of the Sec. 3.3 output equation: exp(scale q_t.k_j) / (D_SA + D_LA) for the keys the softmax
+    branch sees (local span and retained tokens), phi_q(q_t).phi_k(k_j) / (D_SA + D_LA) for the tokens that went to
+    the linear state, 0 for the future.  Every row sums to one; with a gate of ones, y = A v.  (This is the map the
+    paper's first training stage compares with the teacher's softmax map, Sec. 4.1; the per-channel gate scales the
+    linear part of the numerator only and is not part of a scalar map.)"""
+    q = np.asarray(q, F64)
+    k = np.asarray(k, F64)
+    N = q.shape[0]
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained, "stop")
+    phi_q = np_map(q, Wq, bq)
+    phi_k = np_map(k, Wk, bk)
+    A = np.zeros((N, N), F64)
+    for t in range(N):
+        c = t // C
+        for j in range(max(0, (c - 1) * C), t + 1):
+            A[t, j] = np.exp(scale * np.dot(q[t], k[j]))
+        for cc in range(0, c - 1):
+            chosen = set(int(i) for i in sel[cc] if i >= 0)
+            for j in range(cc * C, (cc + 1) * C):
+                A[t, j] = np.exp(scale * np.dot(q[t], k[j])) if j in chosen else np.dot(phi_q[t], phi_k[j])
+        A[t] /= A[t].sum()
+    return A

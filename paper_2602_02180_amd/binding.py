@@ -109,6 +109,8 @@ def lib() -> ct.CDLL:
         L.still_bwd_workspace_layout.argtypes = [pp, ct.POINTER(StillBwdWsLayout)]
         L.still_hybrid_attn_bwd.restype = ct.c_int
         L.still_hybrid_attn_bwd.argtypes = [pp] + [vp] * 20 + [vp, ct.c_size_t, vp]
+        L.still_attention_map.restype = ct.c_int
+        L.still_attention_map.argtypes = [pp] + [vp] * 9 + [vp, ct.c_size_t, vp]
         L.still_rope_apply.restype = ct.c_int
         L.still_rope_apply.argtypes = [pp, vp, vp, vp, ct.c_float, vp]
         L.still_profile_enable.restype = None
@@ -247,6 +249,17 @@ def still_hybrid_attn_bwd(p: StillParams, q, k, v, g, Wq, bq, Wk, bk, out, dout,
         _ptr(dout), _ptr(lse), _ptr(sel_idx), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _ptr(dWq), _ptr(dbq),
         _ptr(dWk), _ptr(dbk), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), stream.cuda_stream))
+
+
+def still_attention_map(p: StillParams, q, k, Wq, bq, Wk, bk, lse, sel_idx, map_out, workspace, stream=None) -> None:
+    """The operator's attention map [B, Hq, N, N] (float32) for the forward call that produced lse and sel_idx."""
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(lib().still_attention_map(
+        ct.byref(p), _ptr(q), _ptr(k), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(lse), _ptr(sel_idx), _ptr(map_out),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), stream.cuda_stream))
 
 
 def still_rope_apply(p: StillParams, q, k, pos0=None, base: float = 10000.0, stream=None) -> None:

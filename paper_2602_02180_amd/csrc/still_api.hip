@@ -1128,6 +1128,80 @@ still_status_t still_bwd_workspace_layout(const still_params_t* p, still_bwd_ws_
   return STILL_OK;
 }
 
+still_status_t still_attention_map(const still_params_t* p, const void* q, const void* k, const void* Wq,
+                                   const void* bq, const void* Wk, const void* bk, const float* lse,
+                                   const int32_t* sel_idx, float* map_out, void* workspace, size_t workspace_bytes,
+                                   void* stream_v) {
+  still_status_t st = validate_bwd_params(p);
+  if (st != STILL_OK) return st;
+  st = validate_strides(p, false);
+  if (st != STILL_OK) return st;
+  if (!q || !k || !Wq || !Wk || !lse || !map_out || !workspace)
+    return fail(STILL_ERR_INVALID_ARG, "a required pointer (q, k, Wq, Wk, lse, map_out, workspace) is NULL");
+  const int B = p->B, N = p->N, d = p->d, C = p->C, F = p->d_f, Hq = p->Hq;
+  const int nc = (N + C - 1) / C, ncf = N / C, U = B * Hq;
+  const bool have_sel = p->lambda > 0 && ncf > 0;
+  if (have_sel && sel_idx == nullptr) return fail(STILL_ERR_INVALID_ARG, "sel_idx (the forward pass's index lists) is NULL");
+  const void* ptrs[] = {q, k, Wq, bq, Wk, bk, lse, sel_idx, map_out, workspace};
+  for (const void* x : ptrs)
+    if (x != nullptr && !aligned16(x)) return fail(STILL_ERR_INVALID_ARG, "pointer %p is not 16-byte aligned", x);
+  still_bwd_ws_layout_t BL;
+  compute_bwd_layout(p, &BL);
+  if (workspace_bytes < BL.total)
+    return fail(STILL_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, BL.total);
+  still_ws_layout_t L;
+  compute_layout(p, &L);
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  unsigned char* bws = static_cast<unsigned char*>(workspace);
+  unsigned char* ws = bws + BL.fwd;
+  still::HeadMap map;
+  fill_map(p, &map);
+  const int dt = p->dtype;
+  hipError_t e;
+  auto hip_fail = [&](const char* what, hipError_t err) -> still_status_t {
+    return fail(STILL_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
+  };
+  auto f32p = [&](size_t off) { return reinterpret_cast<float*>(bws + off); };
+  still::KeepMaskArgs km{sel_idx, reinterpret_cast<uint32_t*>(ws + L.kmask), Hq, ncf, C, have_sel ? p->lambda : 0,
+                         retained_budget(p)};
+  if ((e = still::launch_keep_mask(km, B, stream)) != hipSuccess) return hip_fail("keep_mask", e);
+  // the feature maps of q and k: f = x W on the matrix core, then phi per token (phi_k zero for selected tokens)
+  still::GemmArgs gm{};
+  gm.Hq = Hq; gm.map = map;
+  const int64_t NF = (int64_t)N * F;
+  auto fxw = [&](const void* x, int64_t sb, int64_t st_, int64_t sh, int kv, const void* Wm, float* dst) -> hipError_t {
+    gm.A = operand(x, sb, sh, (int64_t)C * st_, st_, 1, kv);
+    gm.B = operand(Wm, 0, (int64_t)d * F, 0, 1, F);
+    gm.B2 = still::GemmOperand{};
+    gm.C = dst; gm.c_b = Hq * NF; gm.c_h = NF; gm.c_c = (int64_t)C * F; gm.c_r = F; gm.c_kv = 0;
+    gm.M = C; gm.Nn = F; gm.K = d; gm.m_total = N; gm.k_total = 0; gm.mode = 0;
+    return still::launch_bgemm(gm, dt, U, nc, stream);
+  };
+  if ((e = fxw(q, p->q_sb, p->q_st, p->q_sh, 0, Wq, f32p(BL.uq))) != hipSuccess ||
+      (e = fxw(k, p->k_sb, p->k_st, p->k_sh, 1, Wk, f32p(BL.uk))) != hipSuccess)
+    return hip_fail("attention_map f = x W", e);
+  still::BwdNpArgs nq{};
+  nq.x = q; nq.x_sb = p->q_sb; nq.x_st = p->q_st; nq.x_sh = p->q_sh; nq.x_kv = 0;
+  nq.bias = bq; nq.u = f32p(BL.uq); nq.st = f32p(BL.stq); nq.phi = bws + BL.phi_q; nq.kmask = nullptr;
+  nq.map = map; nq.U = U; nq.N = N; nq.Hq = Hq; nq.Hkv = p->Hkv; nq.d = d; nq.F = F; nq.C = C; nq.nc = nc; nq.ncf = ncf;
+  nq.nseg = L.nseg; nq.seg_chunks = L.seg_chunks;
+  still::BwdNpArgs nk = nq;
+  nk.x = k; nk.x_sb = p->k_sb; nk.x_st = p->k_st; nk.x_sh = p->k_sh; nk.x_kv = 1;
+  nk.bias = bk; nk.u = f32p(BL.uk); nk.st = f32p(BL.stk); nk.phi = bws + BL.phi_k;
+  nk.kmask = reinterpret_cast<const uint32_t*>(ws + L.kmask);
+  if ((e = still::launch_bwd_np(nq, dt, false, stream)) != hipSuccess ||
+      (e = still::launch_bwd_np(nk, dt, false, stream)) != hipSuccess)
+    return hip_fail("attention_map phi", e);
+  still::AttnMapArgs am{};
+  am.q = q; am.k = k;
+  am.q_sb = p->q_sb; am.q_st = p->q_st; am.q_sh = p->q_sh; am.k_sb = p->k_sb; am.k_st = p->k_st; am.k_sh = p->k_sh;
+  am.phi_q = bws + BL.phi_q; am.phi_k = bws + BL.phi_k; am.kmask = nk.kmask; am.lse = lse; am.map_out = map_out;
+  am.map = map; am.N = N; am.C = C; am.Hq = Hq; am.ncf = ncf; am.scale = p->scale;
+  if ((e = still::launch_attn_map(am, dt, d, U, stream)) != hipSuccess) return hip_fail("attention_map", e);
+  g_err[0] = 0;
+  return STILL_OK;
+}
+
 still_status_t still_rope_apply(const still_params_t* p, void* q, void* k, const int32_t* pos0, float base,
                                 void* stream_v) {
   if (p == nullptr) return fail(STILL_ERR_INVALID_ARG, "params is NULL");

@@ -801,6 +801,60 @@ __global__ __launch_bounds__(256) void bwd_sa_dkv_kernel(BwdSaArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Attention map of the operator: A[t][j] = weight of v_j in row t under the shared normaliser (what the first
+// training stage of Sec. 4.1 compares with the teacher's softmax map).  One workgroup per (64 rows, 64 keys) at or
+// below the diagonal: the logits q.k and the linear weights phi_q.phi_k of the tile on the matrix core (operands in
+// fragment form straight from global memory), then per element the branch that owns the pair: the exponential for
+// the local span and for selected tokens of chunks <= c-2, E_t phi_q.phi_k for the other tokens of those chunks
+// (phi_k is stored as zero for selected tokens), zero above the diagonal.  Tiles above the diagonal are zero-filled.
+// ---------------------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void attn_map_kernel(AttnMapArgs a) {
+  typedef Mma<T> M;
+  constexpr int KS = D / M::KK, KP = 2 * D / M::KK;
+  const int unit = blockIdx.z, rt = blockIdx.y, kt = blockIdx.x;
+  const int b = unit / a.Hq, h = unit % a.Hq, kvh = a.map.kv[h];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, g = lane >> 5, wr = wave >> 1, wc = wave & 1;
+  const int N = a.N, C = a.C, r0 = rt * 64, k0 = kt * 64;
+  float* out = a.map_out + (int64_t)unit * N * N;
+  const int j = k0 + 32 * wc + l31;              // this lane's key
+  floatx16 s = zero16(), w = zero16();
+  const bool live = kt <= rt;                    // uniform
+  if (live) {
+    const int tr = min(r0 + 32 * wr + l31, N - 1), jc = min(j, N - 1);
+    const T* qp = static_cast<const T*>(a.q) + b * a.q_sb + (int64_t)tr * a.q_st + h * a.q_sh + g * M::KPL;
+    const T* kp = static_cast<const T*>(a.k) + b * a.k_sb + (int64_t)jc * a.k_st + kvh * a.k_sh + g * M::KPL;
+#pragma unroll
+    for (int st = 0; st < KS; ++st) s = M::mma(M::load(qp + st * M::KK), M::load(kp + st * M::KK), s);
+    const T* pq = static_cast<const T*>(a.phi_q) + ((int64_t)unit * N + tr) * (2 * D) + g * M::KPL;
+    const T* pk = static_cast<const T*>(a.phi_k) + ((int64_t)unit * N + jc) * (2 * D) + g * M::KPL;
+#pragma unroll
+    for (int st = 0; st < KP; ++st) w = M::mma(M::load(pq + st * M::KK), M::load(pk + st * M::KK), w);
+  }
+  bool kept = false;
+  const int cj = j / C;
+  if (live && j < N && cj < a.ncf) {
+    const int wi = j % C;
+    kept = (a.kmask[((int64_t)unit * a.ncf + cj) * (C / 32) + wi / 32] >> (wi & 31)) & 1u;
+  }
+  const float sc2 = a.scale * kLog2e;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int t = r0 + 32 * wr + c_row(i, g);
+    if (t >= N || j >= N) continue;
+    float val = 0.f;
+    if (live && j <= t) {
+      const int c = t / C;
+      const float L = a.lse[(int64_t)unit * N + t];
+      if (cj >= c - 1 || kept) val = fast_exp2(fmaf(s[i], sc2, -L * kLog2e));
+      else val = __expf(-L) * w[i];
+    }
+    out[(int64_t)t * N + j] = val;
+  }
+}
+
 template <typename T, int D>
 hipError_t launch_sa_t(const BwdSaArgs& a, int B, hipStream_t s) {
   hipLaunchKernelGGL((bwd_sa_dq_kernel<T, D>), dim3(a.n_row_tiles, B * a.Hq), dim3(256), 0, s, a);
@@ -895,6 +949,19 @@ hipError_t launch_bwd_finish(const BwdFinishArgs& a, int dtype, hipStream_t s) {
   const int blocks = (int)(((int64_t)a.B * a.H * a.N + rpb - 1) / rpb);
   if (dtype == 1) hipLaunchKernelGGL((bwd_finish_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
   else hipLaunchKernelGGL((bwd_finish_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_map(const AttnMapArgs& a, int dtype, int d, int U, hipStream_t s) {
+  const int nt = (a.N + 63) / 64;
+  const dim3 grid(nt, nt, U);
+  if (dtype == 1) {
+    if (d == 128) hipLaunchKernelGGL((attn_map_kernel<bf16, 128>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((attn_map_kernel<bf16, 64>), grid, dim3(256), 0, s, a);
+  } else {
+    if (d == 128) hipLaunchKernelGGL((attn_map_kernel<float, 128>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((attn_map_kernel<float, 64>), grid, dim3(256), 0, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -402,5 +402,19 @@ hipError_t launch_bwd_colsum(const BwdColsumArgs& a, int dtype, int U, hipStream
 hipError_t launch_bwd_revcumsum(float* X, int U, int nc, int64_t L, hipStream_t stream);
 hipError_t launch_bwd_finish(const BwdFinishArgs& a, int dtype, hipStream_t stream);
 hipError_t launch_bwd_sa(const BwdSaArgs& a, int dtype, int d, int B, hipStream_t stream);
+struct AttnMapArgs {
+  const void* q;
+  const void* k;
+  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
+  const void* phi_q;       // [U, N, 2d] storage type
+  const void* phi_k;       // [U, N, 2d], zero rows' worth for selected tokens
+  const uint32_t* kmask;   // [U, ncf, C/32]: bit = token selected (within its chunk's quota)
+  const float* lse;        // [U, N]
+  float* map_out;          // [U, N, N]
+  HeadMap map;
+  int N, C, Hq, ncf;
+  float scale;
+};
+hipError_t launch_attn_map(const AttnMapArgs& a, int dtype, int d, int U, hipStream_t stream);
 
 }  // namespace still

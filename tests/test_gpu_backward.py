@@ -207,3 +207,53 @@ def test_backward_twice_on_a_user_stream_gives_the_same_gradients():
         a_, b_ = a_.float(), b_.float()
         assert torch.isfinite(a_).all() and torch.isfinite(b_).all()
         assert float((a_ - b_).abs().max()) <= 1e-5 * float(a_.abs().max())
+
+
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f32", N=600, Hq=4, Hkv=2, lam=8, B=2),
+    dict(dtype="f32", N=512, lam=16, max_retained=40),
+    dict(dtype="bf16", d=128, C=128, W=128, N=1024, Hq=4, Hkv=2),
+], ids=["f32-gqa-ragged", "f32-budget", "bf16-d128"])
+def test_attention_map_against_the_oracle(kw):
+    """still_attention_map for the forward call's lists and normalisers: element-wise against the oracle's map
+    (weights are at most one: absolute bars 2e-6 on fp32, 4e-3 on bf16, whose logits and features carry 8 bits),
+    rows sum to one, nothing above the diagonal, and map x v reproduces the forward output (no gate)."""
+    import torch
+
+    w = small("map-" + "-".join(f"{k}{v}" for k, v in kw.items()), **kw)
+    inp = with_bias(w, synth.make_inputs(w, seed=101), 102)
+    dev = "cuda"
+    up = lambda n: synth.to_torch(inp[n], w.dtype, dev)
+    q, k, v, Wq, Wk, bq, bk = (up(n) for n in ("q", "k", "v", "Wq", "Wk", "bq", "bk"))
+    B, N = q.shape[:2]
+    out = torch.empty_like(q)
+    p = S.make_params(B=B, N=N, Hq=w.Hq, Hkv=w.Hkv, d=w.d, C=w.C, W=w.W, lam=w.lam, scale=w.scale, eps=w.eps,
+                      dtype=w.dtype, q=q, k=k, v=v, out=out, max_retained=w.max_retained)
+    sel = torch.full((B, w.Hq, N // w.C, w.lam), -1, dtype=torch.int32, device=dev)
+    ws = torch.empty(S.still_fwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    S.still_hybrid_attn_fwd(p, q, k, v, None, Wq, bq, Wk, bk, out, sel_idx=sel, workspace=ws)
+    L = S.still_fwd_workspace_layout(p)
+    lse = ws[L.lse:L.lse + B * w.Hq * N * 4].view(torch.float32)
+    amap = torch.full((B, w.Hq, N, N), float("nan"), dtype=torch.float32, device=dev)
+    bws = torch.empty(S.still_bwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    S.still_attention_map(p, q, k, Wq, bq, Wk, bk, lse, sel, amap, bws)
+    torch.cuda.synchronize()
+    A = amap.cpu().numpy().astype(np.float64)
+    sel_h = sel.cpu().numpy().astype(np.int64)
+    y = synth.from_torch(out).astype(np.float64)
+    kv = synth.kv_head_map(w)
+    bar = 2e-6 if w.dtype == "f32" else 4e-3
+    assert np.all(np.isfinite(A)) and np.all(np.triu(A, 1) == 0.0)
+    worst = 0.0
+    for b in range(B):
+        for h in range(w.Hq):
+            ref = OB.attention_map(inp["q"][b, :, h], inp["k"][b, :, kv[h]], inp["Wq"][h], inp["Wk"][h], w.C, w.W, w.lam,
+                                   w.scale, w.eps, bq=inp["bq"][h], bk=inp["bk"][h], sel=sel_h[b, h],
+                                   max_retained=U.budget(w))
+            worst = max(worst, float(np.max(np.abs(A[b, h] - ref))))
+            assert np.max(np.abs(A[b, h].sum(axis=1) - 1.0)) <= (1e-5 if w.dtype == "f32" else 1e-2)
+            yv = A[b, h] @ inp["v"][b, :, kv[h]].astype(np.float64)
+            if w.dtype == "f32":
+                assert U.rel_err(yv, y[b, :, h]) <= 1e-4
+    print(f"[{w.name}] attention map: max-abs err {worst:.3e}")
+    assert worst <= bar, worst

@@ -123,3 +123,28 @@ def test_units_driver_adds_nothing_of_its_own():
     one = OB.still_backward_definition(inputs["q"][0, :, 1], inputs["k"][0, :, 0], inputs["v"][0, :, 0], None,
                                        inputs["Wq"][1], inputs["Wk"][1], C, 3, 1, 0.5, 1e-6, dy[0, :, 1], sel=sel[0, 1])
     assert np.array_equal(res[(0, 1)]["dk"], one["dk"]) and res[(0, 1)]["dg"] is None
+
+
+def test_attention_map_rows_sum_to_one_reproduce_the_output_and_reduce_to_softmax():
+    """A v equals the forward definition's output when the gate is one; every row sums to one and sees no future
+    token; with every token kept the map is the causal softmax map (scipy's softmax, row by row); a token that went
+    to the linear state carries the phi_q . phi_k weight, written out for one entry."""
+    from scipy.special import softmax
+
+    C, W, lam, scale, eps = 4, 3, 1, 0.6, 1e-6
+    p, _ = tiny(21, N=22, gate=False)
+    fwd = O.still_definition(p["q"], p["k"], p["v"], None, p["Wq"], p["Wk"], C, W, lam, scale, eps, bq=p["bq"], bk=p["bk"])
+    A = OB.attention_map(p["q"], p["k"], p["Wq"], p["Wk"], C, W, lam, scale, eps, bq=p["bq"], bk=p["bk"], sel=fwd["sel"])
+    assert np.allclose(A.sum(axis=1), 1.0, rtol=1e-13) and np.all(np.triu(A, 1) == 0.0) and np.all(A >= 0.0)
+    assert np.allclose(A @ p["v"], fwd["out"], rtol=1e-11, atol=1e-13)
+    # row 21 (chunk 5): token 2 of chunk 0 is un-selected unless the list says otherwise
+    t = 21
+    j = next(i for i in range(0, 4) if i not in set(fwd["sel"][0]))
+    den = np.exp(fwd["M"][t]) * fwd["D_SA"][t] + fwd["D_LA"][t]
+    w = O.np_map(p["q"][t], p["Wq"], p["bq"])[0] @ O.np_map(p["k"][j], p["Wk"], p["bk"])[0]
+    assert np.isclose(A[t, j], w / den, rtol=1e-12)
+    # everything kept: the causal softmax map
+    sel_all = np.arange(20).reshape(5, 4)
+    A2 = OB.attention_map(p["q"], p["k"], p["Wq"], p["Wk"], C, W, C, scale, eps, sel=sel_all)
+    for t in range(22):
+        assert np.allclose(A2[t, :t + 1], softmax(scale * p["k"][:t + 1] @ p["q"][t]), rtol=1e-12)
