@@ -409,6 +409,23 @@ STILL_API still_status_t still_attention_map(const still_params_t* p, const void
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Backward of the attention map w.r.t. the feature-map parameters: given dmap = d loss / d map (device FLOAT
+ * [B, Hq, N, N]; entries above the diagonal are ignored) and the map itself (as written by still_attention_map for the
+ * same inputs), returns dWq, dWk (device FLOAT [Hq, d, d_f]) and dbq, dbk (device FLOAT [Hq, d_f], given exactly when
+ * bq, bk are), with q, k and the routing held fixed: what the first training stage of Sec. 4.1 updates (q and k come
+ * from the frozen teacher there).  map_tj = a_tj / s_t with s_t the row's sum, so da_tj = (dmap_tj - <dmap_t, map_t>)
+ * / s_t, and only the pairs owned by the linear branch depend on the parameters, through phi_q(q_t) . phi_k(k_j).
+ * workspace: at least still_attention_map_bwd_workspace_bytes(p) bytes (a backward workspace plus one [B, Hq, N, N]
+ * matrix in the storage type).  Same coverage and validation as the backward pass; sums with atomic adds.
+ */
+STILL_API size_t still_attention_map_bwd_workspace_bytes(const still_params_t* p);
+STILL_API still_status_t still_attention_map_bwd(const still_params_t* p, const void* q, const void* k,
+                                   const void* Wq, const void* bq, const void* Wk, const void* bk,
+                                   const float* lse, const int32_t* sel_idx, const float* map, const float* dmap,
+                                   float* dWq, float* dbq, float* dWk, float* dbk,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Rotary position embedding of q and k, in place: a pre-pass for callers whose q and k are not rotated yet (the
  * paper converts Llama-family layers, which rotate q and k before attention; nothing in the method depends on it, and
  * every other entry point takes q and k as they are).  Channel pair (i, i + d/2) of the token at position pos turns

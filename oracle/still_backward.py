@@ -17,7 +17,8 @@ branch's exponentials, on the linear branch's phi_q . phi_k weights, and on the 
 Pins (tests/test_oracle_backward.py): central finite differences of still_definition for every input, the
 textbook causal-softmax gradient when every token is kept, the NP-Map's Jacobian and invariances.
 attention_map (the weights under the shared normaliser, what the first training stage compares with the teacher's
-map) is pinned by A v = y, unit row sums, scipy's softmax when every token is kept and one written-out entry.
+map) is pinned by A v = y, unit row sums, scipy's softmax when every token is kept and one written-out entry;
+attention_map_backward (its gradient w.r.t. the feature-map parameters) by central differences of attention_map.
 """
 from __future__ import annotations
 
@@ -175,3 +176,44 @@ def attention_map(q, k, Wq, Wk, C, W, lam, scale, eps, bq=None, bk=None, sel=Non
                 A[t, j] = np.exp(scale * np.dot(q[t], k[j])) if j in chosen else np.dot(phi_q[t], phi_k[j])
         A[t] /= A[t].sum()
     return A
+
+
+def attention_map_backward(q, k, Wq, Wk, C, W, lam, scale, eps, dA, bq=None, bk=None, sel=None, score=None,
+                           max_retained: Optional[int] = None) -> Dict[str, np.ndarray]:
+    """Gradient of sum(dA * A) (A = attention_map) w.r.t. the feature-map parameters W_q, W_k, b_q, b_k, with q, k
+    and the routing held fixed: what the first training stage of Sec. 4.1 updates (q and k come from the frozen
+    teacher there).  A_tj = a_tj / s_t with s_t the row's sum, so da_tj = (dA_tj - <dA_t, A_t>) / s_t; only the
+    pairs owned by the linear branch depend on the parameters, through a_tj = phi_q(q_t) . phi_k(k_j)."""
+    q = np.asarray(q, F64)
+    k = np.asarray(k, F64)
+    dA = np.asarray(dA, F64)
+    N = q.shape[0]
+    score, sel = _scores_and_sel(q, k, C, W, lam, scale, eps, sel, score, max_retained, "stop")
+    phi_q = np_map(q, Wq, bq)
+    phi_k = np_map(k, Wk, bk)
+    dphi_q = np.zeros_like(phi_q)
+    dphi_k = np.zeros_like(phi_k)
+    for t in range(N):
+        c = t // C
+        a = np.zeros(N, F64)
+        lin = []
+        for j in range(max(0, (c - 1) * C), t + 1):
+            a[j] = np.exp(scale * np.dot(q[t], k[j]))
+        for cc in range(0, c - 1):
+            chosen = set(int(i) for i in sel[cc] if i >= 0)
+            for j in range(cc * C, (cc + 1) * C):
+                if j in chosen:
+                    a[j] = np.exp(scale * np.dot(q[t], k[j]))
+                else:
+                    a[j] = np.dot(phi_q[t], phi_k[j])
+                    lin.append(j)
+        if not lin:
+            continue
+        s = a.sum()
+        da = (dA[t] - np.dot(dA[t], a / s)) / s
+        li = np.asarray(lin, np.int64)
+        dphi_q[t] += da[li] @ phi_k[li]
+        dphi_k[li] += np.outer(da[li], phi_q[t])
+    _, dWq, dbq_ = np_map_backward(q, Wq, bq, dphi_q)
+    _, dWk, dbk_ = np_map_backward(k, Wk, bk, dphi_k)
+    return {"dWq": dWq, "dWk": dWk, "dbq": dbq_ if bq is not None else None, "dbk": dbk_ if bk is not None else None}

@@ -111,6 +111,10 @@ def lib() -> ct.CDLL:
         L.still_hybrid_attn_bwd.argtypes = [pp] + [vp] * 20 + [vp, ct.c_size_t, vp]
         L.still_attention_map.restype = ct.c_int
         L.still_attention_map.argtypes = [pp] + [vp] * 9 + [vp, ct.c_size_t, vp]
+        L.still_attention_map_bwd_workspace_bytes.restype = ct.c_size_t
+        L.still_attention_map_bwd_workspace_bytes.argtypes = [pp]
+        L.still_attention_map_bwd.restype = ct.c_int
+        L.still_attention_map_bwd.argtypes = [pp] + [vp] * 14 + [vp, ct.c_size_t, vp]
         L.still_rope_apply.restype = ct.c_int
         L.still_rope_apply.argtypes = [pp, vp, vp, vp, ct.c_float, vp]
         L.still_profile_enable.restype = None
@@ -260,6 +264,26 @@ def still_attention_map(p: StillParams, q, k, Wq, bq, Wk, bk, lse, sel_idx, map_
     _check(lib().still_attention_map(
         ct.byref(p), _ptr(q), _ptr(k), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(lse), _ptr(sel_idx), _ptr(map_out),
         _ptr(workspace), workspace.numel() * workspace.element_size(), stream.cuda_stream))
+
+
+def still_attention_map_bwd_workspace_bytes(p: StillParams) -> int:
+    n = lib().still_attention_map_bwd_workspace_bytes(ct.byref(p))
+    if n == 0:
+        raise StillError(STILL_ERR_INVALID_ARG, still_last_error())
+    return n
+
+
+def still_attention_map_bwd(p: StillParams, q, k, Wq, bq, Wk, bk, lse, sel_idx, amap, dmap, dWq, dbq, dWk, dbk,
+                            workspace, stream=None) -> None:
+    """Gradient of a loss on the attention map w.r.t. the feature-map parameters (float32 outputs)."""
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    _check(lib().still_attention_map_bwd(
+        ct.byref(p), _ptr(q), _ptr(k), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(lse), _ptr(sel_idx), _ptr(amap),
+        _ptr(dmap), _ptr(dWq), _ptr(dbq), _ptr(dWk), _ptr(dbk), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), stream.cuda_stream))
 
 
 def still_rope_apply(p: StillParams, q, k, pos0=None, base: float = 10000.0, stream=None) -> None:

@@ -1128,35 +1128,22 @@ still_status_t still_bwd_workspace_layout(const still_params_t* p, still_bwd_ws_
   return STILL_OK;
 }
 
-still_status_t still_attention_map(const still_params_t* p, const void* q, const void* k, const void* Wq,
-                                   const void* bq, const void* Wk, const void* bk, const float* lse,
-                                   const int32_t* sel_idx, float* map_out, void* workspace, size_t workspace_bytes,
-                                   void* stream_v) {
-  still_status_t st = validate_bwd_params(p);
-  if (st != STILL_OK) return st;
-  st = validate_strides(p, false);
-  if (st != STILL_OK) return st;
-  if (!q || !k || !Wq || !Wk || !lse || !map_out || !workspace)
-    return fail(STILL_ERR_INVALID_ARG, "a required pointer (q, k, Wq, Wk, lse, map_out, workspace) is NULL");
+}  // extern "C"
+
+namespace {
+
+// keep mask and the feature maps of q and k (phi_k zero for selected tokens), u and the norms, into a backward
+// workspace: the common first part of the attention map and of its backward pass
+still_status_t prepare_feature_maps(const still_params_t* p, const void* q, const void* k, const void* Wq,
+                                    const void* bq, const void* Wk, const void* bk, const int32_t* sel_idx,
+                                    unsigned char* bws, const still_bwd_ws_layout_t& BL, const still_ws_layout_t& L,
+                                    const still::HeadMap& map, hipStream_t stream, still::BwdNpArgs* nq_out,
+                                    still::BwdNpArgs* nk_out) {
   const int B = p->B, N = p->N, d = p->d, C = p->C, F = p->d_f, Hq = p->Hq;
   const int nc = (N + C - 1) / C, ncf = N / C, U = B * Hq;
   const bool have_sel = p->lambda > 0 && ncf > 0;
-  if (have_sel && sel_idx == nullptr) return fail(STILL_ERR_INVALID_ARG, "sel_idx (the forward pass's index lists) is NULL");
-  const void* ptrs[] = {q, k, Wq, bq, Wk, bk, lse, sel_idx, map_out, workspace};
-  for (const void* x : ptrs)
-    if (x != nullptr && !aligned16(x)) return fail(STILL_ERR_INVALID_ARG, "pointer %p is not 16-byte aligned", x);
-  still_bwd_ws_layout_t BL;
-  compute_bwd_layout(p, &BL);
-  if (workspace_bytes < BL.total)
-    return fail(STILL_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, BL.total);
-  still_ws_layout_t L;
-  compute_layout(p, &L);
-  hipStream_t stream = static_cast<hipStream_t>(stream_v);
-  unsigned char* bws = static_cast<unsigned char*>(workspace);
-  unsigned char* ws = bws + BL.fwd;
-  still::HeadMap map;
-  fill_map(p, &map);
   const int dt = p->dtype;
+  unsigned char* ws = bws + BL.fwd;
   hipError_t e;
   auto hip_fail = [&](const char* what, hipError_t err) -> still_status_t {
     return fail(STILL_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
@@ -1165,7 +1152,6 @@ still_status_t still_attention_map(const still_params_t* p, const void* q, const
   still::KeepMaskArgs km{sel_idx, reinterpret_cast<uint32_t*>(ws + L.kmask), Hq, ncf, C, have_sel ? p->lambda : 0,
                          retained_budget(p)};
   if ((e = still::launch_keep_mask(km, B, stream)) != hipSuccess) return hip_fail("keep_mask", e);
-  // the feature maps of q and k: f = x W on the matrix core, then phi per token (phi_k zero for selected tokens)
   still::GemmArgs gm{};
   gm.Hq = Hq; gm.map = map;
   const int64_t NF = (int64_t)N * F;
@@ -1179,7 +1165,7 @@ still_status_t still_attention_map(const still_params_t* p, const void* q, const
   };
   if ((e = fxw(q, p->q_sb, p->q_st, p->q_sh, 0, Wq, f32p(BL.uq))) != hipSuccess ||
       (e = fxw(k, p->k_sb, p->k_st, p->k_sh, 1, Wk, f32p(BL.uk))) != hipSuccess)
-    return hip_fail("attention_map f = x W", e);
+    return hip_fail("f = x W", e);
   still::BwdNpArgs nq{};
   nq.x = q; nq.x_sb = p->q_sb; nq.x_st = p->q_st; nq.x_sh = p->q_sh; nq.x_kv = 0;
   nq.bias = bq; nq.u = f32p(BL.uq); nq.st = f32p(BL.stq); nq.phi = bws + BL.phi_q; nq.kmask = nullptr;
@@ -1191,13 +1177,166 @@ still_status_t still_attention_map(const still_params_t* p, const void* q, const
   nk.kmask = reinterpret_cast<const uint32_t*>(ws + L.kmask);
   if ((e = still::launch_bwd_np(nq, dt, false, stream)) != hipSuccess ||
       (e = still::launch_bwd_np(nk, dt, false, stream)) != hipSuccess)
-    return hip_fail("attention_map phi", e);
+    return hip_fail("feature maps", e);
+  *nq_out = nq;
+  *nk_out = nk;
+  return STILL_OK;
+}
+
+size_t map_bwd_extra(const still_params_t* p, size_t* rowdot_off, size_t* dw_off, int* np8) {
+  still_bwd_ws_layout_t BL;
+  compute_bwd_layout(p, &BL);
+  const size_t U = (size_t)p->B * p->Hq, N = p->N, n8 = (N + 7) / 8 * 8;
+  *rowdot_off = BL.total;
+  *dw_off = align_up(*rowdot_off + U * N * 4, 256);
+  *np8 = (int)n8;
+  return align_up(*dw_off + U * N * n8 * esize(p->dtype), 256);
+}
+
+}  // namespace
+
+extern "C" {
+
+still_status_t still_attention_map(const still_params_t* p, const void* q, const void* k, const void* Wq,
+                                   const void* bq, const void* Wk, const void* bk, const float* lse,
+                                   const int32_t* sel_idx, float* map_out, void* workspace, size_t workspace_bytes,
+                                   void* stream_v) {
+  still_status_t st = validate_bwd_params(p);
+  if (st != STILL_OK) return st;
+  st = validate_strides(p, false);
+  if (st != STILL_OK) return st;
+  if (!q || !k || !Wq || !Wk || !lse || !map_out || !workspace)
+    return fail(STILL_ERR_INVALID_ARG, "a required pointer (q, k, Wq, Wk, lse, map_out, workspace) is NULL");
+  const int ncf = p->N / p->C, U = p->B * p->Hq;
+  if (p->lambda > 0 && ncf > 0 && sel_idx == nullptr)
+    return fail(STILL_ERR_INVALID_ARG, "sel_idx (the forward pass's index lists) is NULL");
+  const void* ptrs[] = {q, k, Wq, bq, Wk, bk, lse, sel_idx, map_out, workspace};
+  for (const void* x : ptrs)
+    if (x != nullptr && !aligned16(x)) return fail(STILL_ERR_INVALID_ARG, "pointer %p is not 16-byte aligned", x);
+  still_bwd_ws_layout_t BL;
+  compute_bwd_layout(p, &BL);
+  if (workspace_bytes < BL.total)
+    return fail(STILL_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, BL.total);
+  still_ws_layout_t L;
+  compute_layout(p, &L);
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  unsigned char* bws = static_cast<unsigned char*>(workspace);
+  still::HeadMap map;
+  fill_map(p, &map);
+  still::BwdNpArgs nq, nk;
+  st = prepare_feature_maps(p, q, k, Wq, bq, Wk, bk, sel_idx, bws, BL, L, map, stream, &nq, &nk);
+  if (st != STILL_OK) return st;
   still::AttnMapArgs am{};
   am.q = q; am.k = k;
   am.q_sb = p->q_sb; am.q_st = p->q_st; am.q_sh = p->q_sh; am.k_sb = p->k_sb; am.k_st = p->k_st; am.k_sh = p->k_sh;
   am.phi_q = bws + BL.phi_q; am.phi_k = bws + BL.phi_k; am.kmask = nk.kmask; am.lse = lse; am.map_out = map_out;
-  am.map = map; am.N = N; am.C = C; am.Hq = Hq; am.ncf = ncf; am.scale = p->scale;
-  if ((e = still::launch_attn_map(am, dt, d, U, stream)) != hipSuccess) return hip_fail("attention_map", e);
+  am.map = map; am.N = p->N; am.C = p->C; am.Hq = p->Hq; am.ncf = ncf; am.scale = p->scale;
+  const hipError_t e = still::launch_attn_map(am, p->dtype, p->d, U, stream);
+  if (e != hipSuccess) return fail(STILL_ERR_HIP, "attention_map: %s", hipGetErrorString(e));
+  g_err[0] = 0;
+  return STILL_OK;
+}
+
+size_t still_attention_map_bwd_workspace_bytes(const still_params_t* p) {
+  if (validate_bwd_params(p) != STILL_OK) return 0;
+  size_t r, w;
+  int n8;
+  return map_bwd_extra(p, &r, &w, &n8);
+}
+
+still_status_t still_attention_map_bwd(const still_params_t* p, const void* q, const void* k, const void* Wq,
+                                       const void* bq, const void* Wk, const void* bk, const float* lse,
+                                       const int32_t* sel_idx, const float* map, const float* dmap, float* dWq,
+                                       float* dbq, float* dWk, float* dbk, void* workspace, size_t workspace_bytes,
+                                       void* stream_v) {
+  still_status_t st = validate_bwd_params(p);
+  if (st != STILL_OK) return st;
+  st = validate_strides(p, false);
+  if (st != STILL_OK) return st;
+  if (!q || !k || !Wq || !Wk || !lse || !map || !dmap || !dWq || !dWk || !workspace)
+    return fail(STILL_ERR_INVALID_ARG,
+                "a required pointer (q, k, Wq, Wk, lse, map, dmap, dWq, dWk, workspace) is NULL");
+  if ((bq != nullptr) != (dbq != nullptr) || (bk != nullptr) != (dbk != nullptr))
+    return fail(STILL_ERR_INVALID_ARG, "dbq / dbk must be given exactly when bq / bk are");
+  const int B = p->B, N = p->N, d = p->d, C = p->C, F = p->d_f, DP = 2 * F, Hq = p->Hq;
+  const int nc = (N + C - 1) / C, ncf = N / C, U = B * Hq;
+  if (p->lambda > 0 && ncf > 0 && sel_idx == nullptr)
+    return fail(STILL_ERR_INVALID_ARG, "sel_idx (the forward pass's index lists) is NULL");
+  const void* ptrs[] = {q, k, Wq, bq, Wk, bk, lse, sel_idx, map, dmap, dWq, dbq, dWk, dbk, workspace};
+  for (const void* x : ptrs)
+    if (x != nullptr && !aligned16(x)) return fail(STILL_ERR_INVALID_ARG, "pointer %p is not 16-byte aligned", x);
+  size_t rowdot_off, dw_off;
+  int np8;
+  const size_t need = map_bwd_extra(p, &rowdot_off, &dw_off, &np8);
+  if (workspace_bytes < need)
+    return fail(STILL_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  still_bwd_ws_layout_t BL;
+  compute_bwd_layout(p, &BL);
+  still_ws_layout_t L;
+  compute_layout(p, &L);
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  unsigned char* bws = static_cast<unsigned char*>(workspace);
+  still::HeadMap hmap;
+  fill_map(p, &hmap);
+  const int dt = p->dtype;
+  hipError_t e;
+  auto hip_fail = [&](const char* what, hipError_t err) -> still_status_t {
+    return fail(STILL_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
+  };
+  auto f32p = [&](size_t off) { return reinterpret_cast<float*>(bws + off); };
+  if ((e = still::launch_fill_f32(dWq, (int64_t)Hq * d * F, 0.f, stream)) != hipSuccess ||
+      (e = still::launch_fill_f32(dWk, (int64_t)Hq * d * F, 0.f, stream)) != hipSuccess ||
+      (dbq && (e = still::launch_fill_f32(dbq, (int64_t)Hq * F, 0.f, stream)) != hipSuccess) ||
+      (dbk && (e = still::launch_fill_f32(dbk, (int64_t)Hq * F, 0.f, stream)) != hipSuccess))
+    return hip_fail("fill", e);
+  still::BwdNpArgs nq, nk;
+  st = prepare_feature_maps(p, q, k, Wq, bq, Wk, bk, sel_idx, bws, BL, L, hmap, stream, &nq, &nk);
+  if (st != STILL_OK) return st;
+  // dw: the gradient of the linear branch's weights, zero on every other pair
+  still::MapDwArgs md{dmap, lse, nk.kmask, f32p(rowdot_off), bws + dw_off, N, np8, C, ncf};
+  if ((e = still::launch_map_dw(md, map, dt, U, stream)) != hipSuccess) return hip_fail("map_dw", e);
+  // dphi_q = dw phi_k, dphi_k = dw^T phi_q (one item per (batch, head), all rows)
+  still::GemmArgs gm{};
+  gm.Hq = Hq; gm.map = hmap;
+  const int64_t NDP = (int64_t)N * DP, NN8 = (int64_t)N * np8, NF = (int64_t)N * F;
+  auto run = [&](const still::GemmOperand& A_, const still::GemmOperand& B_, float* Cp, int64_t c_b, int64_t c_h,
+                 int64_t c_c, int64_t c_r, int M_, int Nn_, int K_, int k_total, int mode, int n_c) -> hipError_t {
+    gm.A = A_; gm.B = B_; gm.B2 = still::GemmOperand{}; gm.C = Cp;
+    gm.c_b = c_b; gm.c_h = c_h; gm.c_c = c_c; gm.c_r = c_r; gm.c_kv = 0;
+    gm.M = M_; gm.Nn = Nn_; gm.K = K_; gm.m_total = 0; gm.k_total = k_total; gm.mode = mode;
+    return still::launch_bgemm(gm, dt, U, n_c, stream);
+  };
+  const still::GemmOperand dw_tj = operand(bws + dw_off, Hq * NN8, NN8, 0, np8, 1);      // (m = t, k = j)
+  const still::GemmOperand dw_jt = operand(bws + dw_off, Hq * NN8, NN8, 0, 1, np8);      // (m = j, k = t)
+  const still::GemmOperand phik_fj = operand(bws + BL.phi_k, Hq * NDP, NDP, 0, 1, DP);   // (n = f, k = j)
+  const still::GemmOperand phiq_ft = operand(bws + BL.phi_q, Hq * NDP, NDP, 0, 1, DP);   // (n = f, k = t)
+  if ((e = run(dw_tj, phik_fj, f32p(BL.gq), Hq * NDP, NDP, 0, DP, N, DP, N, 0, 0, 1)) != hipSuccess ||
+      (e = run(dw_jt, phiq_ft, f32p(BL.dphi_k), Hq * NDP, NDP, 0, DP, N, DP, N, 0, 0, 1)) != hipSuccess)
+    return hip_fail("map backward products", e);
+  // NP-Map backwards, then dW += x^T df and the bias gradients
+  nq.dphi = f32p(BL.gq); nq.coef = nullptr; nq.z1 = nullptr; nq.z2 = nullptr;
+  nq.df = bws + BL.dfq; nq.cx = f32p(BL.cxq);
+  nk.dphi = f32p(BL.dphi_k); nk.coef = nullptr; nk.z1 = nullptr; nk.z2 = nullptr;
+  nk.df = bws + BL.dfk; nk.cx = f32p(BL.cxk);
+  if ((e = still::launch_bwd_np(nq, dt, true, stream)) != hipSuccess ||
+      (e = still::launch_bwd_np(nk, dt, true, stream)) != hipSuccess)
+    return hip_fail("bwd_np_bwd", e);
+  const int KS = 256, nsplit = (N + KS - 1) / KS;
+  const still::GemmOperand q_xt = operand(q, p->q_sb, p->q_sh, (int64_t)KS * p->q_st, 1, p->q_st);
+  const still::GemmOperand k_xt = operand(k, p->k_sb, p->k_sh, (int64_t)KS * p->k_st, 1, p->k_st, 1);
+  const still::GemmOperand dfq_ft = operand(bws + BL.dfq, Hq * NF, NF, (int64_t)KS * F, 1, F);
+  const still::GemmOperand dfk_ft = operand(bws + BL.dfk, Hq * NF, NF, (int64_t)KS * F, 1, F);
+  if ((e = run(q_xt, dfq_ft, dWq, 0, (int64_t)d * F, 0, F, d, F, KS, N, 2, nsplit)) != hipSuccess ||
+      (e = run(k_xt, dfk_ft, dWk, 0, (int64_t)d * F, 0, F, d, F, KS, N, 2, nsplit)) != hipSuccess)
+    return hip_fail("dW += x^T df", e);
+  if (dbq != nullptr) {
+    still::BwdColsumArgs cb{bws + BL.dfq, nullptr, dbq, N, C, nc, F, Hq, 1};
+    if ((e = still::launch_bwd_colsum(cb, dt, U, stream)) != hipSuccess) return hip_fail("db", e);
+  }
+  if (dbk != nullptr) {
+    still::BwdColsumArgs cb{bws + BL.dfk, nullptr, dbk, N, C, nc, F, Hq, 1};
+    if ((e = still::launch_bwd_colsum(cb, dt, U, stream)) != hipSuccess) return hip_fail("db", e);
+  }
   g_err[0] = 0;
   return STILL_OK;
 }

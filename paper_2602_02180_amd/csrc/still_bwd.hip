@@ -378,17 +378,19 @@ __global__ __launch_bounds__(256) void bwd_np_bwd_kernel(BwdNpArgs a) {
   const float nx = a.st[2 * rowc], nf = a.st[2 * rowc + 1];
   const bool dead = token_kept(a, unit, t) || !(nx > 0.f) || !(nf > 0.f);   // uniform over the row's lanes
   const float coef = a.coef ? a.coef[rowc] : 1.f;
-  const float* z1 = a.z1 + ((int64_t)unit * a.nc + c) * 2 * F + e0;
   float uv[8], dp[8], dn[8], zz[8];
   load8_f32(uv, a.u + rowc * F + e0);
   load8_f32(dp, a.dphi + rowc * 2 * F + e0);
   load8_f32(dn, a.dphi + rowc * 2 * F + F + e0);
-  load8_f32(zz, z1);
+  if (a.z1) {
+    const float* z1 = a.z1 + ((int64_t)unit * a.nc + c) * 2 * F + e0;
+    load8_f32(zz, z1);
 #pragma unroll
-  for (int e = 0; e < 8; ++e) dp[e] -= coef * zz[e];
-  load8_f32(zz, z1 + F);
+    for (int e = 0; e < 8; ++e) dp[e] -= coef * zz[e];
+    load8_f32(zz, z1 + F);
 #pragma unroll
-  for (int e = 0; e < 8; ++e) dn[e] -= coef * zz[e];
+    for (int e = 0; e < 8; ++e) dn[e] -= coef * zz[e];
+  }
   if (a.z2) {
     const float* z2 = a.z2 + ((int64_t)unit * a.nseg + c / a.seg_chunks) * 2 * F + e0;
     load8_f32(zz, z2);
@@ -855,6 +857,38 @@ __global__ __launch_bounds__(256) void attn_map_kernel(AttnMapArgs a) {
   }
 }
 
+// Backward of the attention map w.r.t. the linear branch's weights: rowdot_t = <dA_t, A_t>, then
+// dw_tj = (dA_tj - rowdot_t) exp(-L_t) on the pairs the linear branch owns (token j of a chunk <= c-2 that was not
+// selected), zero elsewhere, in the storage type with rows padded to a multiple of 8 (an operand of the matrix core).
+__global__ __launch_bounds__(256) void map_rowdot_kernel(const float* A, const float* dA, float* rowdot, int64_t rows, int N) {
+  const int64_t row = blockIdx.x * 4ll + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const float* a = A + row * N;
+  const float* d = dA + row * N;
+  float s = 0.f;
+  for (int j = lane; j < N; j += 64) s += a[j] * d[j];
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (lane == 0) rowdot[row] = s;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void map_dw_kernel(MapDwArgs a) {
+  const int unit = blockIdx.z, t = blockIdx.y;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= a.Np8) return;
+  const int c = t / a.C, cj = j / a.C;
+  float val = 0.f;
+  if (j < a.N && cj <= c - 2) {   // (chunks <= c-2 are full chunks)
+    const int wi = j % a.C;
+    const bool kept = (a.kmask[((int64_t)unit * a.ncf + cj) * (a.C / 32) + wi / 32] >> (wi & 31)) & 1u;
+    const int64_t row = (int64_t)unit * a.N + t;
+    if (!kept) val = (a.dA[row * a.N + j] - a.rowdot[row]) * __expf(-a.lse[row]);
+  }
+  static_cast<T*>(a.dw)[((int64_t)unit * a.N + t) * a.Np8 + j] = from_f32<T>(val);
+}
+
 template <typename T, int D>
 hipError_t launch_sa_t(const BwdSaArgs& a, int B, hipStream_t s) {
   hipLaunchKernelGGL((bwd_sa_dq_kernel<T, D>), dim3(a.n_row_tiles, B * a.Hq), dim3(256), 0, s, a);
@@ -949,6 +983,17 @@ hipError_t launch_bwd_finish(const BwdFinishArgs& a, int dtype, hipStream_t s) {
   const int blocks = (int)(((int64_t)a.B * a.H * a.N + rpb - 1) / rpb);
   if (dtype == 1) hipLaunchKernelGGL((bwd_finish_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
   else hipLaunchKernelGGL((bwd_finish_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_map_dw(const MapDwArgs& a, const float* A, int dtype, int U, hipStream_t s) {
+  const int64_t rows = (int64_t)U * a.N;
+  hipLaunchKernelGGL(map_rowdot_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, A, a.dA, a.rowdot, rows, a.N);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const dim3 grid((a.Np8 + 255) / 256, a.N, U);
+  if (dtype == 1) hipLaunchKernelGGL((map_dw_kernel<bf16>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((map_dw_kernel<float>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -337,7 +337,7 @@ struct BwdNpArgs {
   const uint32_t* kmask;   // nullable [B, Hq, ncf, C/32]: tokens the softmax branch keeps have phi = 0, df = 0
   const float* dphi;       // [U, N, 2F] (backward kernel)
   const float* coef;       // nullable [U, N]: dphi -= coef * (z1 + z2)
-  const float* z1;         // [U, nc, 2F]
+  const float* z1;         // nullable [U, nc, 2F]
   const float* z2;         // nullable [U, nseg, 2F], indexed by chunk / seg_chunks
   void* df;                // [U, N, F] storage type
   float* cx;               // [U, N]: coefficient of x in dx (the |x| path), 0 for tokens without a gradient
@@ -415,6 +415,15 @@ struct AttnMapArgs {
   int N, C, Hq, ncf;
   float scale;
 };
+struct MapDwArgs {
+  const float* dA;         // [U, N, N]
+  const float* lse;        // [U, N]
+  const uint32_t* kmask;   // [U, ncf, C/32]
+  float* rowdot;           // [U, N]
+  void* dw;                // [U, N, Np8] storage type
+  int N, Np8, C, ncf;
+};
+hipError_t launch_map_dw(const MapDwArgs& a, const float* A, int dtype, int U, hipStream_t stream);
 hipError_t launch_attn_map(const AttnMapArgs& a, int dtype, int d, int U, hipStream_t stream);
 
 }  // namespace still

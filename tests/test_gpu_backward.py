@@ -257,3 +257,28 @@ def test_attention_map_against_the_oracle(kw):
                 assert U.rel_err(yv, y[b, :, h]) <= 1e-4
     print(f"[{w.name}] attention map: max-abs err {worst:.3e}")
     assert worst <= bar, worst
+    # and its backward pass to the feature-map parameters, for a random dmap
+    rng = np.random.default_rng(103)
+    dA = np.tril(rng.standard_normal((B, w.Hq, N, N)).astype(np.float32))
+    dmap = torch.from_numpy(dA).to(dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    dWq, dWk = torch.full((w.Hq, w.d, w.df), float("nan"), **f32), torch.full((w.Hq, w.d, w.df), float("nan"), **f32)
+    dbq, dbk = torch.full((w.Hq, w.df), float("nan"), **f32), torch.full((w.Hq, w.df), float("nan"), **f32)
+    mws = torch.empty(S.still_attention_map_bwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    S.still_attention_map_bwd(p, q, k, Wq, bq, Wk, bk, lse, sel, amap, dmap, dWq, dbq, dWk, dbk, mws)
+    torch.cuda.synchronize()
+    ref = {n: np.zeros(s_) for n, s_ in (("dWq", (w.Hq, w.d, w.df)), ("dWk", (w.Hq, w.d, w.df)), ("dbq", (w.Hq, w.df)),
+                                         ("dbk", (w.Hq, w.df)))}
+    for b in range(B):
+        for h in range(w.Hq):
+            r = OB.attention_map_backward(inp["q"][b, :, h], inp["k"][b, :, kv[h]], inp["Wq"][h], inp["Wk"][h], w.C, w.W,
+                                          w.lam, w.scale, w.eps, dA[b, h].astype(np.float64), bq=inp["bq"][h],
+                                          bk=inp["bk"][h], sel=sel_h[b, h], max_retained=U.budget(w))
+            for n in ref:
+                ref[n][h] += r[n]
+    for n, t in (("dWq", dWq), ("dWk", dWk), ("dbq", dbq), ("dbk", dbk)):
+        x = t.cpu().numpy().astype(np.float64)
+        scale_ = float(np.max(np.abs(ref[n])))
+        err = float(np.max(np.abs(x - ref[n])))
+        print(f"[{w.name}] map backward {n}: max |ref| {scale_:.3e}  max-abs err {err:.3e}  ratio {err / scale_:.3e}")
+        assert np.all(np.isfinite(x)) and err <= BAR[w.dtype] * scale_, (n, err, scale_)

@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
             "still_state_bytes", "still_state_init", "still_last_error", "still_version",
             "still_hybrid_attn_decode_step_at", "still_hybrid_attn_fwd_static", "still_hybrid_attn_bwd",
             "still_bwd_workspace_bytes", "still_bwd_workspace_layout", "still_attention_map",
-            "still_rope_apply"} <= set(names)
+            "still_attention_map_bwd", "still_attention_map_bwd_workspace_bytes", "still_rope_apply"} <= set(names)
     lib = S.lib()
     for n in names:
         assert hasattr(lib, n), n

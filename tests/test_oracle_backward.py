@@ -148,3 +148,38 @@ def test_attention_map_rows_sum_to_one_reproduce_the_output_and_reduce_to_softma
     A2 = OB.attention_map(p["q"], p["k"], p["Wq"], p["Wk"], C, W, C, scale, eps, sel=sel_all)
     for t in range(22):
         assert np.allclose(A2[t, :t + 1], softmax(scale * p["k"][:t + 1] @ p["q"][t]), rtol=1e-12)
+
+
+@pytest.mark.parametrize("lam,max_retained", [(1, None), (2, 3)])
+def test_attention_map_backward_matches_central_differences(lam, max_retained):
+    C, W, scale, eps = 4, 3, 0.6, 1e-6
+    p, _ = tiny(31 + lam, N=20, gate=False)
+    rng = np.random.default_rng(32)
+    dA = np.tril(rng.normal(size=(20, 20)))
+    fwd = O.still_definition(p["q"], p["k"], p["v"], None, p["Wq"], p["Wk"], C, W, lam, scale, eps, bq=p["bq"], bk=p["bk"],
+                             max_retained=max_retained)
+    sel = fwd["sel"]
+
+    def loss():
+        A = OB.attention_map(p["q"], p["k"], p["Wq"], p["Wk"], C, W, lam, scale, eps, bq=p["bq"], bk=p["bk"], sel=sel,
+                             max_retained=max_retained)
+        return float(np.sum(A * dA))
+
+    got = OB.attention_map_backward(p["q"], p["k"], p["Wq"], p["Wk"], C, W, lam, scale, eps, dA, bq=p["bq"], bk=p["bk"],
+                                    sel=sel, max_retained=max_retained)
+    h = 1e-5
+    for name, key in (("Wq", "dWq"), ("Wk", "dWk"), ("bq", "dbq"), ("bk", "dbk")):
+        base = p[name]
+        fd = np.zeros_like(base)
+        it = np.nditer(base, flags=["multi_index"])
+        for _ in it:
+            i = it.multi_index
+            old = base[i]
+            base[i] = old + h
+            up = loss()
+            base[i] = old - h
+            dn = loss()
+            base[i] = old
+            fd[i] = (up - dn) / (2 * h)
+        assert np.max(np.abs(fd)) > 1e-6, name
+        assert np.max(np.abs(fd - got[key])) <= 1e-6 * max(1.0, np.max(np.abs(fd))), name
