@@ -276,7 +276,7 @@ void compute_state_layout(const still_params_t* p, still_state_layout_t* L) {
 extern "C" {
 
 // 0.3.0: budget_policy in the params, more regions in both layouts
-int32_t still_version(void) { return 300; }
+int32_t still_version(void) { return 400; }   // 0.4.0: backward pass, attention map, rotary pre-pass
 
 const char* still_last_error(void) { return g_err; }
 
