@@ -124,7 +124,8 @@ def test_backward_fp32_sigmoid_gate_and_custom_head_map():
     dict(d=128, C=128, W=128, N=1024, Hq=4, Hkv=2),
     dict(d=64, C=64, W=64, N=1100, Hq=4, Hkv=1, B=2),
     dict(d=128, C=64, W=128, N=900, Hq=2, Hkv=1, max_retained=96),
-], ids=["d128-C128", "d64-ragged", "d128-budget"])
+    dict(d=64, C=128, W=256, N=1500, Hq=3, Hkv=1, B=3, lam=32, max_retained=70),
+], ids=["d128-C128", "d64-ragged", "d128-budget", "d64-C128-budget-wide-window"])
 def test_backward_bf16(kw):
     w = small("bwd16-" + "-".join(f"{k}{v}" for k, v in kw.items()), dtype="bf16", **kw)
     inp = with_bias(w, synth.make_inputs(w, seed=61, with_gate=True), 62)
@@ -213,7 +214,9 @@ def test_backward_twice_on_a_user_stream_gives_the_same_gradients():
     dict(dtype="f32", N=600, Hq=4, Hkv=2, lam=8, B=2),
     dict(dtype="f32", N=512, lam=16, max_retained=40),
     dict(dtype="bf16", d=128, C=128, W=128, N=1024, Hq=4, Hkv=2),
-], ids=["f32-gqa-ragged", "f32-budget", "bf16-d128"])
+    dict(dtype="f32", N=50),                               # shorter than a chunk: no linear branch, 56-column rows
+    dict(dtype="bf16", d=64, N=330, lam=4, Hq=3, Hkv=3, B=3),
+], ids=["f32-gqa-ragged", "f32-budget", "bf16-d128", "f32-short", "bf16-odd-sizes"])
 def test_attention_map_against_the_oracle(kw):
     """still_attention_map for the forward call's lists and normalisers: element-wise against the oracle's map
     (weights are at most one: absolute bars 2e-6 on fp32, 4e-3 on bf16, whose logits and features carry 8 bits),
@@ -280,5 +283,5 @@ def test_attention_map_against_the_oracle(kw):
         x = t.cpu().numpy().astype(np.float64)
         scale_ = float(np.max(np.abs(ref[n])))
         err = float(np.max(np.abs(x - ref[n])))
-        print(f"[{w.name}] map backward {n}: max |ref| {scale_:.3e}  max-abs err {err:.3e}  ratio {err / scale_:.3e}")
-        assert np.all(np.isfinite(x)) and err <= BAR[w.dtype] * scale_, (n, err, scale_)
+        print(f"[{w.name}] map backward {n}: max |ref| {scale_:.3e}  max-abs err {err:.3e}")
+        assert np.all(np.isfinite(x)) and err <= BAR[w.dtype] * max(scale_, 1e-30), (n, err, scale_)
