@@ -282,6 +282,26 @@ def backward_bench(args) -> int:
     el = time.perf_counter() - t0
     # the last step's split (events are reused: only the last recording survives), the mean from the wall clock
     f_ms, b_ms = e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])
+    # the attention map and its backward pass (the first training stage's pair), where the N x N maps fit comfortably
+    map_ms = map_bwd_ms = None
+    if N <= 2048:
+        amap = torch.empty(w.B, w.Hq, N, N, dtype=torch.float32, device=dev)
+        dmap = torch.randn(w.B, w.Hq, N, N, dtype=torch.float32, device=dev).tril_()
+        mws = torch.empty(S.still_attention_map_bwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+        dbq = dbk = None
+        for _ in range(2):
+            S.still_attention_map(p, q, k, Wq, None, Wk, None, lse, sel, amap, mws)
+            S.still_attention_map_bwd(p, q, k, Wq, None, Wk, None, lse, sel, amap, dmap, dWq, dbq, dWk, dbk, mws)
+        torch.cuda.synchronize()
+        m = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        m[0].record()
+        S.still_attention_map(p, q, k, Wq, None, Wk, None, lse, sel, amap, mws)
+        m[1].record()
+        S.still_attention_map_bwd(p, q, k, Wq, None, Wk, None, lse, sel, amap, dmap, dWq, dbq, dWk, dbk, mws)
+        m[2].record()
+        torch.cuda.synchronize()
+        map_ms, map_bwd_ms = m[0].elapsed_time(m[1]), m[1].elapsed_time(m[2])
+        del amap, dmap, mws
     flops = backward_flops(w, N)
     rec = {
         "metric": f"hybrid-attn fwd+bwd tokens/s ({w.name} shape)", "value": w.B * N * steps / el, "unit": "tokens/s",
@@ -289,7 +309,8 @@ def backward_bench(args) -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"forward + backward, {w.name}: B={w.B} N={N} Hq={w.Hq} Hkv={w.Hkv} d={w.d} C={w.C} "
                                f"W={w.W} lambda={w.lam}, gate given",
-                   "fwd_ms": f_ms, "bwd_ms": b_ms, "bwd_workspace_gb": bws.numel() / 1e9},
+                   "fwd_ms": f_ms, "bwd_ms": b_ms, "bwd_workspace_gb": bws.numel() / 1e9,
+                   "attention_map_ms": map_ms, "attention_map_bwd_ms": map_bwd_ms},
         "roofline": {"bound": "mfma", "kernel": "still_hybrid_attn_bwd (whole call)",
                      "achieved": flops / (b_ms * 1e-3) / 1e12, "peak": PEAK_MFMA[w.dtype] / 1e12, "unit": "TFLOP/s",
                      "frac": flops / (b_ms * 1e-3) / PEAK_MFMA[w.dtype], "traffic": None,
